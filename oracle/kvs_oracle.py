@@ -1,0 +1,235 @@
+"""Plain fp64 CPU oracle of the KVSlimmer KV-cache merge step.
+
+TEST INFRASTRUCTURE ONLY.  Nothing on the product path may import this module;
+it exists so that the GPU library can be checked against an independent, slow
+and obviously correct statement of what the step computes.  Only `tests/`,
+`__graft_entry__.smoke()` and the `cpu_baseline` leg of `bench.py` use it.  It
+shares no code with the HIP path and never rounds below fp64.
+
+The method is a heuristic closed form, not a faster route to an independently
+defined exact result, so the oracle is the algorithm itself, one step after the
+other in the paper's notation, for one *unit* (one layer, one sequence, one KV
+head):
+
+  O1-O3  attention of every query row of the window over all cached Keys
+         (Sec. 4.1, Eq. "attn_def_vec": e_i = q k_i^T / sqrt(d_k), alpha = softmax(e)),
+         averaged over the R = G*W rows into one distribution alpha_bar.
+  O4     o_bar = sum_t alpha_bar[t] V[t]            (same equation, with alpha_bar).
+  O5-O6  adjacent pairs with the smallest accumulated attention mass are the
+         merge candidates (App. C, paragraph (i)); edge score
+         sigma[m] = alpha_bar[m] + alpha_bar[m+1]; the r = n - budget eligible edges
+         with the smallest score are merged "in parallel", restoring the length
+         to the budget in one step (Sec. 3.1, last paragraph).  The first n_sink
+         tokens are always preserved (Sec. 5, implementation details).
+  O7     consecutive selected edges chain into one output slot.
+  O8     the forward-only vectors of Sec. 4.2 (Eqs. "c11_def"-"c12_def"):
+         c_tt = alpha_t (1 - 2 alpha_t)(v_t - o),  c_{t,t+1} = -alpha_t alpha_{t+1}(v_t + v_{t+1} - 2o);
+         A_t = ||c_tt||_2, C_t = ||c_{t,t+1}||_2.
+  O9     merged Key: Eq. "kstar_final" for a pair,
+         k* = [(A_m - C_m) k_m + (A_{m+1} - C_m) k_{m+1}] / (A_m - 2 C_m + A_{m+1});
+         for a run of L > 2 tokens the same weight form (Eq. "kstar_weight_final_rewrite":
+         w_a = sum_b g_ab / sum_ab g_ab) with the surrogate g_tt -> A_t,
+         g_{t,t+1} -> -C_t of Eq. "cos_sign_relation_supp1" and only the diagonal and
+         adjacent blocks kept.  Merged Value: the sum (Sec. 3.1, v* = v_m + v_{m+1}),
+         with the slot's cardinality returned beside it.
+
+Readings of points the paper leaves open (many query rows, ranking score, runs
+longer than two, a non-positive denominator) are this module's and are listed
+in the repository's design notes.
+
+Parity pins (tests/test_oracle_pins.py): score / O8 / O9 are pinned by finite
+differences of textbook attention, by brute-force minimisation of the
+second-order objective, by the dense pseudo-inverse solution of Eq.
+"optimal_k_cn", by identical-Key and lossless-Value special cases; select is
+pinned by a brute-force sort and slot invariants.  The *choice* of the readings
+P-1 (mean over query rows), P-2 (edge score) and P-3/P-4 (runs) is not fixed by
+the paper: parity unpinned for those choices themselves.
+"""
+
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------- O1-O4
+def attention_rows(Q: np.ndarray, K: np.ndarray, scale: Optional[float] = None) -> np.ndarray:
+    """alpha[q, t] of Eq. "attn_def_vec" for every row q of Q [R, D] over K [n, D]."""
+    Q = np.asarray(Q, dtype=F64).reshape(-1, K.shape[-1])
+    K = np.asarray(K, dtype=F64)
+    if scale is None:
+        scale = 1.0 / np.sqrt(K.shape[1])
+    e = scale * (Q @ K.T)                                   # O1
+    e = e - e.max(axis=1, keepdims=True)
+    p = np.exp(e)
+    return p / p.sum(axis=1, keepdims=True)                 # O2
+
+
+def score(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
+          scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """alpha_bar[n] (mean of the rows' attention) and o_bar[D] = sum_t alpha_bar[t] V[t]."""
+    alpha = attention_rows(Q, K, scale)
+    alpha_bar = alpha.mean(axis=0)                          # O3
+    o_bar = alpha_bar @ np.asarray(V, dtype=F64)            # O4
+    return alpha_bar, o_bar
+
+
+# --------------------------------------------------------------------------- O5-O7
+def eligible_edges(n: int, n_sink: int, n_recent: int) -> Tuple[int, int]:
+    """Edge m joins tokens m and m+1.  Eligible: n_sink <= m <= n - 2 - n_recent (inclusive)."""
+    return n_sink, n - 2 - n_recent
+
+
+def edge_scores(alpha_bar: np.ndarray, n_sink: int, n_recent: int, sigma_dtype=F64):
+    n = alpha_bar.shape[0]
+    lo, hi = eligible_edges(n, n_sink, n_recent)
+    if hi < lo:
+        return lo, hi, np.zeros(0, dtype=sigma_dtype)
+    a = np.asarray(alpha_bar).astype(sigma_dtype)
+    return lo, hi, a[lo:hi + 1] + a[lo + 1:hi + 2]          # O5, added in sigma_dtype
+
+
+def select(alpha_bar: np.ndarray, budget: int, n_sink: int = 32, n_recent: int = 0,
+           sigma_dtype=F64) -> Tuple[np.ndarray, np.ndarray]:
+    """mask[n] (mask[m] = 1: token m+1 joins token m's slot) and slot[n].
+
+    `sigma_dtype` is the precision in which the edge score is added and compared:
+    fp64 for the oracle proper; float32 when a kernel that takes fp32 alpha_bar and
+    decides in fp32 is checked in isolation (both sides then decide in the same precision).
+    """
+    n = alpha_bar.shape[0]
+    mask = np.zeros(n, dtype=np.uint8)
+    r = n - budget
+    if r > 0:
+        lo, hi, sigma = edge_scores(alpha_bar, n_sink, n_recent, sigma_dtype)
+        if r > sigma.shape[0]:
+            raise ValueError("budget below n_sink + 1 + n_recent: not enough eligible edges")
+        order = np.argsort(sigma, kind="stable")            # ties -> smaller m      (O6)
+        mask[lo + order[:r]] = 1
+    starts = np.ones(n, dtype=np.int64)
+    starts[1:] = 1 - mask[:-1].astype(np.int64)             # t starts a slot iff mask[t-1] = 0
+    slot = (np.cumsum(starts) - 1).astype(np.int32)         # O7
+    return mask, slot
+
+
+def boundary_gap(alpha_bar: np.ndarray, budget: int, n_sink: int = 32, n_recent: int = 0) -> float:
+    """Relative gap (sigma_(r+1) - sigma_(r)) / sigma_(r+1) at the budget boundary (inf if none)."""
+    n = alpha_bar.shape[0]
+    r = n - budget
+    _, _, sigma = edge_scores(alpha_bar, n_sink, n_recent)
+    if r <= 0 or r >= sigma.shape[0]:
+        return float("inf")
+    s = np.sort(sigma)
+    return float((s[r] - s[r - 1]) / s[r])
+
+
+# --------------------------------------------------------------------------- O8-O9
+def token_and_edge_norms(alpha_bar: np.ndarray, V: np.ndarray, o_bar: np.ndarray):
+    """A_t = ||c_tt||_2 for every token and C_t = ||c_{t,t+1}||_2 for every edge (Eqs. c11_def-c12_def)."""
+    a = np.asarray(alpha_bar, dtype=F64)
+    resid = np.asarray(V, dtype=F64) - np.asarray(o_bar, dtype=F64)[None, :]      # r_t = v_t - o
+    A = np.linalg.norm((a * (1.0 - 2.0 * a))[:, None] * resid, axis=1)
+    C = np.linalg.norm(-(a[:-1] * a[1:])[:, None] * (resid[:-1] + resid[1:]), axis=1)
+    return A, C
+
+
+@dataclass
+class MergeResult:
+    K_out: np.ndarray        # [n_out, D] fp64
+    V_out: np.ndarray        # [n_out, D] fp64
+    counts: np.ndarray       # [n_out] int32
+    U: np.ndarray            # [n_out] denominator of the Key weights (A_t for singletons)
+    A_sum: np.ndarray        # [n_out] sum of A_t over the slot
+    fallback: np.ndarray     # [n_out] bool: arithmetic-mean fallback taken
+
+
+def merge_compact(K: np.ndarray, V: np.ndarray, alpha_bar: np.ndarray, o_bar: np.ndarray,
+                  mask: np.ndarray, slot: np.ndarray) -> MergeResult:
+    K = np.asarray(K, dtype=F64)
+    V = np.asarray(V, dtype=F64)
+    n, D = K.shape
+    A, C = token_and_edge_norms(alpha_bar, V, o_bar)
+    n_out = int(slot[-1]) + 1 if n else 0
+    K_out = np.zeros((n_out, D), dtype=F64)
+    V_out = np.zeros((n_out, V.shape[1]), dtype=F64)
+    counts = np.zeros(n_out, dtype=np.int32)
+    U_all = np.zeros(n_out, dtype=F64)
+    A_sum = np.zeros(n_out, dtype=F64)
+    fallback = np.zeros(n_out, dtype=bool)
+    t = 0
+    for S in range(n_out):
+        t0 = t
+        while t < n - 1 and mask[t]:
+            t += 1
+        t1 = t                                              # slot S = tokens t0..t1 inclusive
+        t += 1
+        assert slot[t0] == S and slot[t1] == S
+        counts[S] = t1 - t0 + 1
+        V_out[S] = V[t0:t1 + 1].sum(axis=0)
+        A_sum[S] = A[t0:t1 + 1].sum()
+        if t1 == t0:
+            K_out[S] = K[t0]
+            U_all[S] = A[t0]
+            continue
+        u = A[t0:t1 + 1].copy()
+        u[:-1] -= C[t0:t1]                                  # coupling with the next token
+        u[1:] -= C[t0:t1]                                   # coupling with the previous token
+        U = u.sum()
+        U_all[S] = U
+        if np.isfinite(U) and U > 0.0:
+            K_out[S] = (u[:, None] * K[t0:t1 + 1]).sum(axis=0) / U
+        else:
+            fallback[S] = True
+            K_out[S] = K[t0:t1 + 1].mean(axis=0)
+    assert t == n
+    return MergeResult(K_out, V_out, counts, U_all, A_sum, fallback)
+
+
+def conditioning(res: MergeResult) -> float:
+    """min over merged slots of U / sum_t A_t (1 for an input without merged slots)."""
+    multi = res.counts > 1
+    if not multi.any():
+        return 1.0
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = res.U[multi] / res.A_sum[multi]
+    ratio = np.where(np.isfinite(ratio), ratio, -np.inf)
+    return float(ratio.min())
+
+
+# --------------------------------------------------------------------------- whole step
+@dataclass
+class StepResult:
+    alpha_bar: np.ndarray
+    o_bar: np.ndarray
+    mask: np.ndarray
+    slot: np.ndarray
+    merged: MergeResult
+
+
+def step(Q: np.ndarray, K: np.ndarray, V: np.ndarray, budget: int, n_sink: int = 32,
+         n_recent: int = 0, scale: Optional[float] = None) -> StepResult:
+    alpha_bar, o_bar = score(Q, K, V, scale)
+    mask, slot = select(alpha_bar, budget, n_sink, n_recent)
+    merged = merge_compact(K, V, alpha_bar, o_bar, mask, slot)
+    return StepResult(alpha_bar, o_bar, mask, slot, merged)
+
+
+# --------------------------------------------------------------------------- consumer of the merged cache
+def merged_attention(q: np.ndarray, K_out: np.ndarray, V_out: np.ndarray, counts: np.ndarray,
+                     scale: Optional[float] = None) -> np.ndarray:
+    """Attention of one query over a merged cache whose Values are sums.
+
+    A slot (k', V', c) stands for c tokens that all carry the Key k' (the "(k, k)"
+    replacement of Sec. 3.1) and whose Values add up to V':
+    o = sum_S exp(e_S) V'_S / sum_S c_S exp(e_S).
+    """
+    q = np.asarray(q, dtype=F64)
+    if scale is None:
+        scale = 1.0 / np.sqrt(q.shape[-1])
+    e = scale * (np.asarray(K_out, dtype=F64) @ q)
+    w = np.exp(e - e.max())
+    return (w @ np.asarray(V_out, dtype=F64)) / (w @ np.asarray(counts, dtype=F64))

@@ -1,0 +1,441 @@
+"""Pins of the fp64 oracle against what the paper and the mathematics fix.
+
+None of these tests re-types the oracle's formulas: the reference side is either
+textbook softmax attention differentiated numerically, a dense linear-algebra
+solution of the paper's Newton system, a brute-force minimiser, a brute-force
+sort, or an invariant.
+"""
+
+import itertools
+
+import numpy as np
+import pytest
+from scipy.optimize import minimize_scalar
+
+from oracle import kvs_oracle as O
+
+
+def softmax_attention(q, K, V):
+    """Textbook attention of one query (Sec. 4.1, Eq. attn_def_vec), written independently."""
+    e = K @ q / np.sqrt(q.shape[0])
+    w = np.exp(e - e.max())
+    a = w / w.sum()
+    return a, a @ V
+
+
+def tiny_head(seed, n=6, d=4, dv=None, spread=1.0):
+    rng = np.random.default_rng(seed)
+    dv = dv or d
+    return (rng.standard_normal(d), spread * rng.standard_normal((n, d)), rng.standard_normal((n, dv)))
+
+
+# --------------------------------------------------------------------------------------------
+# O1-O4
+def test_score_single_row_is_textbook_attention():
+    q, K, V = tiny_head(0, n=9, d=5)
+    a, o = softmax_attention(q, K, V)
+    ab, ob = O.score(q[None, :], K, V)
+    np.testing.assert_allclose(ab, a, rtol=1e-14)
+    np.testing.assert_allclose(ob, o, rtol=1e-13, atol=1e-15)
+
+
+def test_score_is_mean_over_rows_and_normalised():
+    rng = np.random.default_rng(1)
+    Q = rng.standard_normal((3, 4, 8))            # [G, W, D]
+    K = rng.standard_normal((50, 8)) * 3.0
+    V = rng.standard_normal((50, 8))
+    ab, ob = O.score(Q, K, V)
+    rows = [softmax_attention(q, K, V) for q in Q.reshape(-1, 8)]
+    np.testing.assert_allclose(ab, np.mean([r[0] for r in rows], axis=0), rtol=1e-13)
+    np.testing.assert_allclose(ob, np.mean([r[1] for r in rows], axis=0), rtol=1e-12, atol=1e-15)
+    assert abs(ab.sum() - 1.0) < 1e-14
+
+
+def test_score_shift_invariance_and_large_logits():
+    # softmax must be computed stably: logits around +-4000 overflow a naive exp.
+    rng = np.random.default_rng(2)
+    K = rng.standard_normal((20, 4)) * 100.0
+    Q = rng.standard_normal((2, 4)) * 100.0
+    V = rng.standard_normal((20, 4))
+    ab, _ = O.score(Q, K, V)
+    assert np.isfinite(ab).all() and abs(ab.sum() - 1) < 1e-12
+    # adding a vector to every Key shifts each row's logits by a constant: alpha unchanged
+    ab2, _ = O.score(Q, K + 0.01 * rng.standard_normal(4)[None, :], V)
+    np.testing.assert_allclose(ab2, ab, rtol=1e-9, atol=1e-300)
+
+
+# --------------------------------------------------------------------------------------------
+# O8: the forward-only vectors are the derivatives of s_i = alpha_i (v_i - o) w.r.t. the logits
+def s_of_logits(e, V):
+    w = np.exp(e - e.max())
+    a = w / w.sum()
+    o = a @ V
+    return a[:, None] * (V - o[None, :])
+
+
+def fd_ds_de(q, K, V, h=1e-5):
+    """J[i, j, :] = d s_i / d e_j by central differences on the logits."""
+    e0 = K @ q / np.sqrt(q.shape[0])
+    n = K.shape[0]
+    J = np.zeros((n, n, V.shape[1]))
+    for j in range(n):
+        ep, em = e0.copy(), e0.copy()
+        ep[j] += h
+        em[j] -= h
+        J[:, j, :] = (s_of_logits(ep, V) - s_of_logits(em, V)) / (2 * h)
+    return J
+
+
+@pytest.mark.parametrize("seed", [3, 4, 5])
+def test_norms_match_finite_difference_of_s(seed):
+    q, K, V = tiny_head(seed, n=6, d=4, dv=5, spread=1.5)
+    J = fd_ds_de(q, K, V)
+    ab, ob = O.score(q[None, :], K, V)
+    A, C = O.token_and_edge_norms(ab, V, ob)
+    np.testing.assert_allclose(A, [np.linalg.norm(J[i, i]) for i in range(6)], rtol=1e-7)
+    np.testing.assert_allclose(C, [np.linalg.norm(J[i, i + 1]) for i in range(5)], rtol=1e-7)
+    # the coupling is symmetric (h^{m+1,m} = h^{m,m+1}, Sec. 4.1)
+    np.testing.assert_allclose(J[1, 2], J[2, 1], atol=1e-9)
+
+
+def test_hessian_blocks_are_rank_one_with_forward_only_scalars():
+    """Central-difference Hessian of f(K) = E^T o(K) w.r.t. (k_i, k_j) equals
+    (1/d_k)(E^T ds_i/de_j) q q^T (Eq. hessian_rank1), with the same vectors whose norms the oracle uses."""
+    q, K, V = tiny_head(7, n=5, d=3, dv=4)
+    rng = np.random.default_rng(70)
+    E = rng.standard_normal(4)
+    d = 3
+
+    def f(Kx):
+        return E @ softmax_attention(q, Kx, V)[1]
+
+    h = 1e-4
+    J = fd_ds_de(q, K, V)
+
+    def hess_block(i, j):
+        H = np.zeros((d, d))
+        for a in range(d):
+            for b in range(d):
+                acc = 0.0
+                for sa, sb in itertools.product((1, -1), (1, -1)):
+                    Kx = K.copy()
+                    Kx[i, a] += sa * h
+                    Kx[j, b] += sb * h
+                    acc += sa * sb * f(Kx)
+                H[a, b] = acc / (4 * h * h)
+        return H
+
+    for (i, j) in [(1, 1), (1, 2), (2, 1), (0, 3)]:
+        want = (E @ J[i, j]) / d * np.outer(q, q)
+        np.testing.assert_allclose(hess_block(i, j), want, atol=2e-6)
+
+
+def test_softmax_second_derivative_signs():
+    """App. C: the off-diagonal second derivatives of softmax are negative; the diagonal of ds_i/de_i
+    keeps the direction of (v_i - o) while alpha_i < 1/2 and flips it above (the oracle takes the norm,
+    so its A_t must stay correct on both sides: covered by test_norms_match_finite_difference_of_s)."""
+    q, K, V = tiny_head(8, n=7, d=4)
+    a, o = softmax_attention(q, K, V)
+    assert a.max() > 0.5 > np.sort(a)[-2]     # this head has one dominant token: both signs occur
+    J = fd_ds_de(q, K, V)
+    for i in range(7):
+        cos = J[i, i] @ (V[i] - o) / (np.linalg.norm(J[i, i]) * np.linalg.norm(V[i] - o))
+        assert abs(cos - np.sign(1 - 2 * a[i])) < 1e-8
+    for i in range(6):
+        rsum = (V[i] - o) + (V[i + 1] - o)
+        cos = J[i, i + 1] @ rsum / (np.linalg.norm(J[i, i + 1]) * np.linalg.norm(rsum))
+        assert cos < -1 + 1e-8
+
+
+# --------------------------------------------------------------------------------------------
+# O9 for a pair: dense Newton system of Eq. optimal_k_cn, then the surrogate
+def test_pair_weight_form_equals_dense_pseudo_inverse_along_q():
+    q, K, V = tiny_head(9, n=6, d=4, dv=4)
+    rng = np.random.default_rng(90)
+    E = rng.standard_normal(4)
+    J = fd_ds_de(q, K, V)
+    m = 2
+    g11, g12, g22 = E @ J[m, m], E @ J[m, m + 1], E @ J[m + 1, m + 1]
+    qq = np.outer(q, q) / 4.0
+    h11, h12, h22 = g11 * qq, g12 * qq, g22 * qq
+    k_dense = np.linalg.pinv(h11 + 2 * h12 + h22) @ (h11 @ K[m] + h12 @ (K[m] + K[m + 1]) + h22 @ K[m + 1])
+    wm = (g11 + g12) / (g11 + 2 * g12 + g22)
+    k_weight = wm * K[m] + (1 - wm) * K[m + 1]
+    # the two expressions differ only by a vector orthogonal to q (Eqs. kstar_proj_form vs kstar_weight_final_rewrite)
+    assert abs(q @ k_dense - q @ k_weight) < 1e-8 * max(1.0, abs(q @ k_weight))
+
+
+def run_oracle_on_mask(q, K, V, mask):
+    ab, ob = O.score(q[None, :], K, V)
+    mask = np.asarray(mask, dtype=np.uint8)
+    starts = np.ones(len(mask), dtype=int)
+    starts[1:] = 1 - mask[:-1]
+    slot = (np.cumsum(starts) - 1).astype(np.int32)
+    return ab, ob, O.merge_compact(K, V, ab, ob, mask, slot)
+
+
+def surrogate_objective_minimiser(q, K, J, t0, t1):
+    """Brute-force minimiser (over x = q.k) of the second-order objective
+       sum_ab g_ab (q.(k - k_a)) (q.(k - k_b)),  a, b in the run,
+    with the gradient-free surrogate g_aa = ||ds_a/de_a||, g_{a,a+1} = -||ds_a/de_{a+1}|| and all other
+    blocks dropped.  The norms come from finite differences, not from the oracle."""
+    idx = list(range(t0, t1 + 1))
+    L = len(idx)
+    g = np.zeros((L, L))
+    for a in range(L):
+        g[a, a] = np.linalg.norm(J[idx[a], idx[a]])
+        if a + 1 < L:
+            g[a, a + 1] = g[a + 1, a] = -np.linalg.norm(J[idx[a], idx[a + 1]])
+    x = K[idx] @ q
+
+    def obj(z):
+        dz = z - x
+        return dz @ g @ dz
+
+    lo, hi = x.min() - 5 * (np.ptp(x) + 1), x.max() + 5 * (np.ptp(x) + 1)
+    grid = np.linspace(lo, hi, 20001)
+    z0 = grid[np.argmin([obj(z) for z in grid])]
+    step = grid[1] - grid[0]
+    res = minimize_scalar(obj, bracket=(z0 - step, z0, z0 + step), tol=1e-14)
+    return res.x, g
+
+
+@pytest.mark.parametrize("seed,L", [(10, 2), (11, 2), (12, 3), (13, 4), (16, 3), (17, 4)])
+def test_merged_key_minimises_second_order_objective(seed, L):
+    n = 8
+    q, K, V = tiny_head(seed, n=n, d=4, dv=6, spread=1.2)
+    t0 = 2
+    t1 = t0 + L - 1
+    mask = np.zeros(n, dtype=np.uint8)
+    mask[t0:t1] = 1
+    ab, ob, res = run_oracle_on_mask(q, K, V, mask)
+    J = fd_ds_de(q, K, V)
+    xstar, g = surrogate_objective_minimiser(q, K, J, t0, t1)
+    assert g.sum() > 0            # convex along q
+    S = t0                        # tokens before t0 are singletons
+    assert res.counts[S] == L
+    got = q @ res.K_out[S]
+    assert abs(got - xstar) < 2e-6 * max(1.0, abs(xstar))
+    # random perturbations of the merged Key never lower the objective
+    rng = np.random.default_rng(seed)
+    x = K[t0:t1 + 1] @ q
+    base = (got - x) @ g @ (got - x)
+    for _ in range(50):
+        z = q @ (res.K_out[S] + 0.1 * rng.standard_normal(4))
+        assert (z - x) @ g @ (z - x) >= base - 1e-12
+
+
+def test_pair_rule_is_the_printed_closed_form():
+    """|S| = 2 evaluated through the finite-difference norms reproduces Eq. kstar_final term by term."""
+    q, K, V = tiny_head(15, n=7, d=4, dv=5)
+    J = fd_ds_de(q, K, V)
+    m = 3
+    mask = np.zeros(7, dtype=np.uint8)
+    mask[m] = 1
+    _, _, res = run_oracle_on_mask(q, K, V, mask)
+    n11, n22, n12 = (np.linalg.norm(J[m, m]), np.linalg.norm(J[m + 1, m + 1]), np.linalg.norm(J[m, m + 1]))
+    want = ((n11 - n12) * K[m] + (n22 - n12) * K[m + 1]) / (n11 - 2 * n12 + n22)
+    np.testing.assert_allclose(res.K_out[m], want, rtol=1e-6, atol=1e-9)
+    # the coupling term is visible at this size: dropping it moves the Key measurably
+    no_coupling = (n11 * K[m] + n22 * K[m + 1]) / (n11 + n22)
+    assert np.linalg.norm(no_coupling - want) > 1e-3 * np.linalg.norm(want)
+
+
+def test_identical_keys_merge_to_themselves():
+    q, K, V = tiny_head(16, n=10, d=4)
+    K[3:7] = K[3]
+    mask = np.zeros(10, dtype=np.uint8)
+    mask[3:6] = 1          # run 3..6
+    mask[7] = 1            # pair 7, 8 with distinct Keys
+    _, _, res = run_oracle_on_mask(q, K, V, mask)
+    np.testing.assert_allclose(res.K_out[3], K[3], rtol=1e-13)
+    assert res.counts.tolist() == [1, 1, 1, 4, 2, 1]
+
+
+def test_lossless_values_when_merged_keys_identical():
+    """Sum-merged Values with cardinality normalisation reproduce full attention exactly when
+    the Keys of every run coincide (Sec. 3.1: replacing (k_m, k_{m+1}) by (k, k))."""
+    rng = np.random.default_rng(17)
+    n, d = 12, 4
+    K = rng.standard_normal((n, d))
+    V = rng.standard_normal((n, d))
+    K[2:5] = K[2]
+    K[8:10] = K[8]
+    mask = np.zeros(n, dtype=np.uint8)
+    mask[2:4] = 1
+    mask[8] = 1
+    q = rng.standard_normal(d)
+    _, _, res = run_oracle_on_mask(q, K, V, mask)
+    for _ in range(5):
+        qn = rng.standard_normal(d)
+        want = softmax_attention(qn, K, V)[1]
+        got = O.merged_attention(qn, res.K_out, res.V_out, res.counts)
+        np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
+
+
+def test_fallback_mean_when_denominator_vanishes():
+    # all Values equal => every residual v_t - o is zero => A = C = 0 => U = 0 => arithmetic mean
+    rng = np.random.default_rng(18)
+    K = rng.standard_normal((6, 4))
+    V = np.ones((6, 4))
+    q = rng.standard_normal(4)
+    mask = np.array([0, 1, 1, 0, 0, 0], dtype=np.uint8)
+    _, _, res = run_oracle_on_mask(q, K, V, mask)
+    assert res.fallback[1] and not res.fallback[0]
+    np.testing.assert_allclose(res.K_out[1], K[1:4].mean(axis=0), rtol=1e-14)
+
+
+def test_fallback_mean_when_surrogate_is_not_convex():
+    # a token at alpha = 1/2 has A = 0: the run's denominator goes negative, the quadratic has no minimiser
+    q, K, V = tiny_head(14, n=8, d=4, dv=6, spread=1.2)
+    mask = np.zeros(8, dtype=np.uint8)
+    mask[2:4] = 1
+    ab, _, res = run_oracle_on_mask(q, K, V, mask)
+    assert abs(ab[3] - 0.5) < 1e-2 and res.U[2] < 0 and res.fallback[2]
+    np.testing.assert_allclose(res.K_out[2], K[2:5].mean(axis=0), rtol=1e-14)
+
+
+# --------------------------------------------------------------------------------------------
+# O5-O7
+def brute_force_select(alpha, budget, s, nr):
+    n = len(alpha)
+    r = n - budget
+    edges = [(alpha[m] + alpha[m + 1], m) for m in range(s, n - 1 - nr)]
+    edges.sort()
+    chosen = {m for _, m in edges[:max(r, 0)]}
+    mask = np.array([1 if m in chosen else 0 for m in range(n)], dtype=np.uint8)
+    slot, cur = [], -1
+    for t in range(n):
+        if t == 0 or not mask[t - 1]:
+            cur += 1
+        slot.append(cur)
+    return mask, np.array(slot, dtype=np.int32)
+
+
+@pytest.mark.parametrize("n,budget,s,nr,seed", [
+    (40, 20, 4, 0, 0), (40, 5, 4, 0, 1), (64, 33, 32, 0, 2), (50, 25, 3, 7, 3), (33, 33, 2, 0, 4),
+    (33, 40, 2, 0, 5), (200, 50, 32, 0, 6), (10, 3, 0, 0, 7), (10, 1, 0, 0, 8)])
+def test_select_matches_brute_force(n, budget, s, nr, seed):
+    rng = np.random.default_rng(seed)
+    alpha = rng.dirichlet(np.ones(n) * 0.3)
+    mask, slot = O.select(alpha, budget, s, nr)
+    bm, bs = brute_force_select(alpha, budget, s, nr)
+    assert (mask == bm).all() and (slot == bs).all()
+    assert slot[-1] + 1 == max(min(budget, n), n - max(n - budget, 0))
+    assert mask[-1] == 0 and (mask[:s] == 0).all()
+    if nr:
+        assert (mask[n - 1 - nr:] == 0).all()
+
+
+def test_select_ties_go_to_lower_index():
+    alpha = np.full(16, 1 / 16)
+    mask, slot = O.select(alpha, 12, 2, 0)
+    assert mask.tolist() == [0, 0, 1, 1, 1, 1] + [0] * 10
+    # float32 decision: ties created by rounding also resolve to the lower index
+    a64 = np.array([0.1, 0.2, 0.1 - 1e-9, 0.25, 0.1, 0.3], dtype=np.float64)
+    m64, _ = O.select(a64, 5, 0, 0)
+    m32, _ = O.select(a64.astype(np.float32), 5, 0, 0, sigma_dtype=np.float32)
+    assert m64.tolist() == [0, 1, 0, 0, 0, 0]     # exact sums: edge 1 is strictly smallest
+    assert m32.tolist() == [1, 0, 0, 0, 0, 0]     # edges 0 and 1 are equal in fp32: the lower index wins
+
+
+def test_select_many_ties_large_n():
+    rng = np.random.default_rng(30)
+    n = 5000
+    alpha = rng.integers(1, 6, size=n).astype(np.float64)       # only 9 distinct edge scores
+    alpha /= alpha.sum()
+    for budget in (600, 2500, 4900):
+        mask, slot = O.select(alpha, budget, 32, 0)
+        bm, bs = brute_force_select(alpha, budget, 32, 0)
+        assert (mask == bm).all() and (slot == bs).all()
+
+
+def test_select_rejects_impossible_budget():
+    with pytest.raises(ValueError):
+        O.select(np.full(10, 0.1), 3, 4, 0)
+
+
+# --------------------------------------------------------------------------------------------
+# whole step: invariants and order-freedom (Sec. 3.1: the pairs are merged in parallel)
+@pytest.mark.parametrize("seed,n,budget,R", [(20, 96, 48, 3), (21, 300, 64, 8), (22, 128, 127, 1)])
+def test_step_invariants(seed, n, budget, R):
+    rng = np.random.default_rng(seed)
+    d = 8
+    K = np.cumsum(rng.standard_normal((n, d)), axis=0) * 0.3
+    V = rng.standard_normal((n, d))
+    Q = rng.standard_normal((R, d))
+    s = 4
+    r = O.step(Q, K, V, budget, s, 0)
+    m = r.merged
+    assert abs(r.alpha_bar.sum() - 1) < 1e-13
+    assert m.K_out.shape == (budget, d) and m.counts.sum() == n
+    np.testing.assert_allclose(m.V_out.sum(axis=0), V.sum(axis=0), rtol=1e-12, atol=1e-12)
+    inc = np.diff(r.slot)
+    assert set(np.unique(inc)) <= {0, 1} and r.slot[0] == 0
+    assert (m.counts[:s] == 1).all()
+    single = np.flatnonzero(m.counts == 1)
+    first_token = np.searchsorted(r.slot, np.arange(budget))
+    assert (m.K_out[single] == K[first_token[single]]).all()       # bit-identical copies
+    assert (m.V_out[single] == V[first_token[single]]).all()
+    # every merged Key is an affine combination of its run with weights summing to one:
+    # it reproduces any affine functional of the Keys when all run members agree on it
+    assert not m.fallback.any()
+
+
+def test_partition_is_independent_of_edge_processing_order():
+    rng = np.random.default_rng(23)
+    n, d, budget = 80, 4, 30
+    K = rng.standard_normal((n, d))
+    V = rng.standard_normal((n, d))
+    Q = rng.standard_normal((2, d))
+    r = O.step(Q, K, V, budget, 2, 0)
+    edges = np.flatnonzero(r.mask)
+    for trial in range(5):
+        parent = list(range(n))
+
+        def find(x):
+            while parent[x] != x:
+                parent[x] = parent[parent[x]]
+                x = parent[x]
+            return x
+
+        for m in rng.permutation(edges):
+            a, b = find(int(m)), find(int(m) + 1)
+            parent[max(a, b)] = min(a, b)
+        roots = np.array([find(t) for t in range(n)])
+        _, relabel = np.unique(roots, return_inverse=True)
+        assert (relabel == r.slot).all()
+
+
+def test_isolated_pairs_equal_sequential_pair_merges_in_any_order():
+    """When no two selected edges touch, the step is exactly the paper's pair merge applied to
+    each pair with the ORIGINAL alpha and o, whatever the order."""
+    rng = np.random.default_rng(24)
+    n, d = 20, 4
+    q, K, V = rng.standard_normal(d), rng.standard_normal((n, d)), rng.standard_normal((n, d))
+    mask = np.zeros(n, dtype=np.uint8)
+    mask[[2, 5, 9, 14]] = 1
+    ab, ob, res = run_oracle_on_mask(q, K, V, mask)
+    J = fd_ds_de(q, K, V)
+    merged = {}
+    for m in rng.permutation([2, 5, 9, 14]):
+        n11, n22, n12 = (np.linalg.norm(J[m, m]), np.linalg.norm(J[m + 1, m + 1]), np.linalg.norm(J[m, m + 1]))
+        merged[int(m)] = ((n11 - n12) * K[m] + (n22 - n12) * K[m + 1]) / (n11 - 2 * n12 + n22)
+    slot_of = {2: 2, 5: 4, 9: 7, 14: 11}
+    for m, S in slot_of.items():
+        np.testing.assert_allclose(res.K_out[S], merged[m], rtol=1e-6, atol=1e-9)
+        np.testing.assert_allclose(res.V_out[S], V[m] + V[m + 1], rtol=1e-14)
+
+
+def test_pair_denominator_positive_when_mass_below_half():
+    """With alpha_m + alpha_{m+1} < 1/2 the pair denominator A_m - 2 C_m + A_{m+1} is positive
+    (triangle inequality), so Eq. kstar_final never divides by a non-positive number there."""
+    rng = np.random.default_rng(25)
+    for _ in range(200):
+        n = 6
+        q, K, V = rng.standard_normal(4), rng.standard_normal((n, 4)) * 2, rng.standard_normal((n, 4))
+        ab, ob = O.score(q[None, :], K, V)
+        A, C = O.token_and_edge_norms(ab, V, ob)
+        for m in range(n - 1):
+            if ab[m] + ab[m + 1] < 0.5:
+                assert A[m] - 2 * C[m] + A[m + 1] > 0
