@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the merge step on the headline workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama8b_32k]
+
+One *step* is one pass of the whole hot path (score -> select -> merge_compact, one kvs_step call
+per layer) over every layer of the workload, layers one after the other, inputs resident in HBM.
+Prints ONE JSON line: whole-job merged KV tokens/s, the roofline of the dominant phase (timed live
+with events on the launch stream) and the fp64 oracle's rate on the host cores of this machine.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama8b_32k")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def phase_bytes(n, B, R, D, b):
+    """Algorithmic HBM bytes of one unit, per phase (each tensor counted once per phase that needs it)."""
+    score = 2 * n * D * b + R * D * b + 4 * n + 4 * D          # read K, V, Q; write alpha_bar, o_bar
+    select = 4 * n + n + 4 * n                                 # read alpha_bar; write edge mask, slot map
+    merge = 2 * n * D * b + 9 * n + 4 * D + 2 * B * D * b + 4 * B   # read K, V, alpha, mask, slot, o_bar; write K', V', counts
+    return {"score": score, "select": select, "merge_compact": merge}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (units are independent; sharding is by KV head, "
+              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2603_00907_amd as kvs
+    from workloads import WORKLOADS, f32_to_bf16_bits, generate_unit, unit_budget, unit_lengths
+
+    kvs.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    w = WORKLOADS[args.workload]
+    layers = args.layers or w.layers
+    lens_seq = unit_lengths(w)
+    lens = [lens_seq[s] for s in range(w.n_seq) for _ in range(w.n_kv_heads)]
+    budgets = [unit_budget(w, n) for n in lens]
+    D, R = w.head_dim, w.q_rows
+    b = 4 if w.dtype == "f32" else 2
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    problem = kvs.Problem(lens=lens, budgets=budgets, group=w.group, window=w.window, head_dim=D, dtype=w.dtype,
+                          n_sink=w.n_sink, n_recent=w.n_recent)
+
+    # ---- synthetic inputs, one independent draw per (layer, sequence, head), uploaded once
+    t_gen = time.time()
+    workers = min(16, os.cpu_count() or 1)
+    keep_host = {}                     # units kept on the host for the oracle sample
+    n_keep_layers = 0 if args.no_cpu_baseline else min(layers, 4)
+
+    def upload(x32):
+        if w.dtype == "f32":
+            return torch.from_numpy(np.ascontiguousarray(x32, dtype=np.float32)).to(dev)
+        return torch.from_numpy(f32_to_bf16_bits(x32).view(np.int16)).to(dev).view(torch.bfloat16)
+
+    Ks, Vs, Qs = [], [], []
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        for layer in range(layers):
+            ids = [(s, h) for s in range(w.n_seq) for h in range(w.n_kv_heads)]
+            units = list(pool.map(lambda sh: generate_unit(w, layer, sh[0], sh[1]), ids))
+            Ks.append(upload(np.concatenate([u.K for u in units])))
+            Vs.append(upload(np.concatenate([u.V for u in units])))
+            Qs.append(upload(np.stack([u.Q.reshape(R, D) for u in units])))
+            if layer < n_keep_layers:
+                keep_host[layer] = units
+    t_gen = time.time() - t_gen
+
+    K_out = [torch.empty((problem.rows_out, D), dtype=tdt, device=dev) for _ in range(layers)]
+    V_out = [torch.empty((problem.rows_out, D), dtype=tdt, device=dev) for _ in range(layers)]
+    counts = [torch.empty(problem.rows_out, dtype=torch.int32, device=dev) for _ in range(layers)]
+    ws = torch.empty(kvs.kvs_workspace_size(problem), dtype=torch.uint8, device=dev)
+    alpha = torch.empty(problem.rows_in, dtype=torch.float32, device=dev)
+    obar = torch.empty((len(lens), D), dtype=torch.float32, device=dev)
+    mask = torch.empty(problem.rows_in, dtype=torch.uint8, device=dev)
+    slot = torch.empty(problem.rows_in, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def one_step():
+        for l in range(layers):
+            kvs.kvs_step(problem, Qs[l], Ks[l], Vs[l], K_out[l], V_out[l], counts[l], ws, stream=stream)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        one_step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+    tokens_per_step = layers * sum(lens_seq)          # one token = the K and V rows of all KV heads at one position
+    value = tokens_per_step / (ms_per_step * 1e-3)
+
+    # ---- per-phase timing, same inputs, the three entry points one after the other with events between
+    phases = ["score", "select", "merge_compact"]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(layers)]
+    reps = max(1, min(args.steps, 5))
+    phase_ms = {p: 0.0 for p in phases}
+    for rep in range(reps + 1):
+        for l in range(layers):
+            evs[l][0].record()
+            kvs.kvs_score(problem, Qs[l], Ks[l], Vs[l], alpha, obar, ws, stream=stream)
+            evs[l][1].record()
+            kvs.kvs_select(problem, alpha, mask, slot, stream=stream)
+            evs[l][2].record()
+            kvs.kvs_merge_compact(problem, Ks[l], Vs[l], alpha, obar, mask, slot, K_out[l], V_out[l], counts[l],
+                                  stream=stream)
+            evs[l][3].record()
+        torch.cuda.synchronize()
+        if rep == 0:
+            continue                                   # warm-up of the stand-alone entry points
+        for l in range(layers):
+            for i, p in enumerate(phases):
+                phase_ms[p] += evs[l][i].elapsed_time(evs[l][i + 1])
+    launches = reps * layers
+    phase_ms = {p: v / launches for p, v in phase_ms.items()}
+    pb = {p: 0 for p in phases}
+    for n, B in zip(lens, budgets):
+        for p, v in phase_bytes(n, min(n, B), R, D, b).items():
+            pb[p] += v
+    dominant = max(phases, key=lambda p: phase_ms[p])
+    achieved = pb[dominant] / (phase_ms[dominant] * 1e-3) / 1e9
+    step_bytes = sum(pb.values())
+    step_gbs = step_bytes * layers / (ms_per_step * 1e-3) / 1e9
+
+    result = {
+        "metric": "merged KV tokens/s and achieved HBM GB/s (% of peak), 8B-shape 32K merge step",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 in/out, f32 accumulate" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "layers": layers, "kv_heads": w.n_kv_heads, "q_heads": w.group * w.n_kv_heads,
+                   "head_dim": D, "window": w.window, "tokens": lens_seq if w.n_seq > 1 else lens_seq[0],
+                   "budget": budgets[0] if w.n_seq == 1 else "25% of length", "n_sink": w.n_sink,
+                   "us_per_layer": ms_per_step * 1e3 / layers, "input_generation_s": round(t_gen, 1)},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "us_per_launch": phase_ms[dominant] * 1e3, "algorithmic_bytes_per_launch": pb[dominant],
+                     "phases_us": {p: phase_ms[p] * 1e3 for p in phases},
+                     "phases_frac": {p: pb[p] / (phase_ms[p] * 1e-3) / 1e9 / HBM_PEAK_GBS for p in phases},
+                     "step": {"algorithmic_bytes_per_layer": step_bytes, "achieved": step_gbs,
+                              "frac": step_gbs / HBM_PEAK_GBS}},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, keep_host, args.cpu_seconds, workers)
+    print(json.dumps(result))
+
+
+def cpu_baseline(w, keep_host, target_s, workers):
+    """The fp64 oracle as it stands, on this machine's host cores, over a bounded sample of the same units."""
+    from threadpoolctl import threadpool_limits
+
+    from oracle import kvs_oracle as O
+
+    units = [u for layer in sorted(keep_host) for u in keep_host[layer]]
+    if not units:
+        return None
+
+    def run(u):
+        O.step(u.Q, u.K, u.V, u.budget, w.n_sink, w.n_recent)
+        return u.n
+
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        run(units[0])
+        one = time.perf_counter() - t0
+        # as many units as fit the time target when `workers` of them run side by side
+        n_units = int(min(len(units), max(workers, target_s / max(one, 1e-3) * workers * 0.5)))
+        sample = units[:n_units]
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            done = sum(pool.map(run, sample))
+        dt = time.perf_counter() - t0
+    # a token counts K and V rows of ALL KV heads of a layer: n_kv_heads units make one token-layer row
+    tokens = done / w.n_kv_heads
+    return {"value": tokens / dt, "unit": "tokens/s", "cores": workers, "kind": "oracle",
+            "sample": f"{len(sample)} units (layer 0.., {w.n_kv_heads} KV heads per layer) of the same workload, "
+                      f"numpy fp64, one BLAS thread per unit, {workers} units side by side, {dt:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()

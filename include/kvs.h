@@ -1,0 +1,126 @@
+/*
+ * kvs.h - C ABI of the MI355X (gfx950) KVSlimmer KV-cache merge step.
+ *
+ * One call of kvs_step() takes one attention layer's cache from `len` to `budget` tokens per
+ * unit, where a unit is one (sequence, KV head) pair:
+ *
+ *   score          attention of a window of recent queries over every cached Key
+ *                  (Sec. 4.1, Eq. attn_def_vec: e_i = q k_i^T / sqrt(d_k), alpha = softmax(e),
+ *                  o = sum_t alpha_t v_t), averaged over the G*W query rows of the unit into one
+ *                  distribution alpha_bar and one output o_bar;
+ *   select         the r = len - budget adjacent pairs (edges) with the smallest accumulated
+ *                  attention mass alpha_bar[m] + alpha_bar[m+1] are merged in one parallel step
+ *                  (Sec. 3.1, chunk-based compression; App. C, paragraph (i)); the first n_sink
+ *                  tokens are always preserved (Sec. 5, implementation details);
+ *   merge_compact  merged Key by the gradient-free closed form of Sec. 4.2 (Eq. kstar_final, with
+ *                  the norms of the forward-only vectors c11, c22, c12 of Eqs. c11_def-c12_def,
+ *                  including the off-diagonal coupling term), merged Value by summation
+ *                  (Sec. 3.1, v* = v_m + v_{m+1}) together with the slot's cardinality.
+ *
+ * Conventions
+ *   - Pointers marked HOST are read on the host during the call and may be freed afterwards.
+ *     Pointers marked DEVICE are caller-owned device memory, 16-byte aligned, rows contiguous.
+ *     The library never allocates or frees device memory, never synchronises the stream and keeps
+ *     no state between calls.  All work is enqueued on `hip_stream` (a hipStream_t; NULL = default
+ *     stream) and completes asynchronously.
+ *   - The return value is the only error channel.  Every argument error is detected on the host
+ *     before anything is launched; in that case nothing has been enqueued.
+ *   - Outputs must not overlap inputs, each other or the workspace (KVS_ERR_ALIAS).
+ *   - A unit with len <= budget is passed through unchanged: len output rows, counts = 1.
+ *     Otherwise it produces exactly `budget` rows.  Rows of a unit beyond its output count are
+ *     never written.
+ *   - All accumulation is fp32; merged K/V are rounded once (nearest-even) to io_dtype.
+ */
+#ifndef KVS_H
+#define KVS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KVS_VERSION 100          /* major*10000 + minor*100 + patch */
+#define KVS_MAX_Q_ROWS 1024      /* largest supported G*W */
+
+typedef enum {
+  KVS_OK = 0,
+  KVS_ERR_INVALID_ARG = 1,  /* null pointer, misaligned pointer, non-positive size, head_dim not 64/128,
+                               G*W above KVS_MAX_Q_ROWS, overlapping units */
+  KVS_ERR_DTYPE = 2,        /* io_dtype is neither KVS_F32 nor KVS_BF16 */
+  KVS_ERR_BUDGET = 3,       /* budget < n_sink + 1 + n_recent for a unit that has to merge (len > budget),
+                               or budget < 1 */
+  KVS_ERR_WORKSPACE = 4,    /* workspace null, misaligned (256 B) or smaller than kvs_workspace_size() */
+  KVS_ERR_ALIAS = 5,        /* an output overlaps an input, another output or the workspace */
+  KVS_ERR_DEVICE = 6        /* a HIP launch failed; hipGetLastError() holds the cause */
+} kvs_status;
+
+typedef enum { KVS_F32 = 0, KVS_BF16 = 1 } kvs_dtype;
+
+typedef struct {
+  int32_t n_units;          /* n_seq * n_kv_heads; one unit = one sequence's one KV head            */
+  int32_t group;            /* G: query heads per KV head                                            */
+  int32_t window;           /* W: recent queries per query head                                      */
+  int32_t head_dim;         /* D = d_k = d_v; 64 or 128                                              */
+  int32_t n_sink;           /* tokens [0, n_sink) are never merged (paper default 32)                */
+  int32_t n_recent;         /* the last n_recent tokens are never merged (default 0)                 */
+  kvs_dtype io_dtype;       /* dtype of Q, K, V, K_out, V_out                                        */
+  float scale;              /* logit scale; 0 selects 1/sqrt(head_dim)                               */
+  const int32_t* len;       /* HOST [n_units] cached tokens per unit (>= 1)                          */
+  const int32_t* budget;    /* HOST [n_units] tokens to keep per unit                                */
+  const int64_t* in_row;    /* HOST [n_units] first row of the unit in K, V, alpha_bar, edge_mask,
+                               slot_of_token; the units' row ranges [in_row, in_row + len) must be
+                               disjoint                                                              */
+  const int64_t* out_row;   /* HOST [n_units] first row of the unit in K_out, V_out, counts_out;
+                               ranges [out_row, out_row + min(len, budget)) must be disjoint         */
+} kvs_problem;
+
+/* Bytes of DEVICE workspace (256-byte aligned) that the calls below need for this problem. */
+kvs_status kvs_workspace_size(const kvs_problem* p, size_t* bytes);
+
+/* Sec. 4.1, Eq. attn_def_vec, averaged over the unit's query rows.
+ *   Q         DEVICE [n_units, G, W, D] io_dtype
+ *   K, V      DEVICE [rows, D] io_dtype; unit u occupies rows in_row[u] .. in_row[u]+len[u]-1
+ *   alpha_bar DEVICE out [rows] fp32: mean over the G*W rows of softmax_t(scale * q.k_t)
+ *   o_bar     DEVICE out [n_units, D] fp32: sum_t alpha_bar[t] V[t]                              */
+kvs_status kvs_score(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                     float* alpha_bar, float* o_bar,
+                     void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Sec. 3.1 (parallel merge of adjacent pairs back to the budget) with the ranking of App. C (i).
+ *   edge score sigma[m] = alpha_bar[m] + alpha_bar[m+1], added and compared in fp32, for the eligible
+ *   edges n_sink <= m <= len-2-n_recent; the r = len - budget smallest are selected, ties to the lower m.
+ *   edge_mask     DEVICE out [rows] u8: 1 = token m+1 joins the slot of token m (last token: 0)
+ *   slot_of_token DEVICE out [rows] i32: unit-local output slot of every token (non-decreasing)   */
+kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar,
+                      uint8_t* edge_mask, int32_t* slot_of_token,
+                      void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Sec. 4.2, Eq. kstar_final (Keys) and Sec. 3.1, v* = v_m + v_{m+1} (Values), one pass over K and V.
+ *   For a slot S of consecutive tokens: A_t = alpha_t |1 - 2 alpha_t| ||v_t - o||, C_t =
+ *   alpha_t alpha_{t+1} ||v_t + v_{t+1} - 2o|| on the slot's inner edges, u_t = A_t - C_{t-1} - C_t,
+ *   K_out[S] = sum u_t K[t] / sum u_t (arithmetic mean of the slot if that denominator is not a
+ *   positive finite number), V_out[S] = sum V[t], counts_out[S] = |S|.  A slot of one token is a
+ *   bit-exact copy.
+ *   K_out, V_out DEVICE out [out rows, D] io_dtype;  counts_out DEVICE out [out rows] i32          */
+kvs_status kvs_merge_compact(const kvs_problem* p, const void* K, const void* V,
+                             const float* alpha_bar, const float* o_bar,
+                             const uint8_t* edge_mask, const int32_t* slot_of_token,
+                             void* K_out, void* V_out, int32_t* counts_out,
+                             void* ws, size_t ws_bytes, void* hip_stream);
+
+/* score -> select -> merge_compact in one call; intermediates live in the workspace.
+ *   slot_of_token_out, edge_mask_out: optional DEVICE outputs (NULL to keep them internal).       */
+kvs_status kvs_step(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                    void* K_out, void* V_out, int32_t* counts_out,
+                    int32_t* slot_of_token_out, uint8_t* edge_mask_out,
+                    void* ws, size_t ws_bytes, void* hip_stream);
+
+const char* kvs_status_str(kvs_status s);
+int kvs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVS_H */

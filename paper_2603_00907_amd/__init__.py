@@ -1,0 +1,30 @@
+"""MI355X (gfx950) KVSlimmer KV-cache merge step: HIP kernels behind a C ABI, plus a thin binding.
+
+    from paper_2603_00907_amd import Problem, kvs_step, kvs_workspace_size
+
+The compute lives in libkvs.so (csrc/*.hip, declared in include/kvs.h).  Build it with
+`python -m paper_2603_00907_amd.build`.
+"""
+
+from .binding import (  # noqa: F401
+    EXPORTS,
+    KVS_BF16,
+    KVS_ERR_ALIAS,
+    KVS_ERR_BUDGET,
+    KVS_ERR_DEVICE,
+    KVS_ERR_DTYPE,
+    KVS_ERR_INVALID_ARG,
+    KVS_ERR_WORKSPACE,
+    KVS_F32,
+    KVS_OK,
+    KvsError,
+    Problem,
+    kvs_merge_compact,
+    kvs_score,
+    kvs_select,
+    kvs_step,
+    kvs_version,
+    kvs_workspace_size,
+    load_library,
+    status_str,
+)

@@ -1,0 +1,304 @@
+// Host layer of libkvs: argument validation, workspace carve-up, unit tables, launch sequencing.
+// Everything that can fail because of the arguments fails here, before the first launch.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <vector>
+
+#include "kvs_device.h"
+
+namespace kvs {
+
+hipError_t launch_score_valu(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
+                             const void* V, float* alpha_bar, const Workspace& ws, hipStream_t stream);
+hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
+                             float* alpha_bar, const Workspace& ws, hipStream_t stream);
+bool score_mfma_supported(const Shape& sh, kvs_dtype dt);
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Plan {
+  int n_units = 0;
+  Shape shape{};
+  kvs_dtype dtype = KVS_F32;
+  size_t elt = 4;
+  long long rows_in = 0, rows_out = 0;
+  std::vector<Unit> units;       // chunk_base / m_base filled per launch group
+};
+
+kvs_status make_plan(const kvs_problem* p, Plan* plan) {
+  if (p == nullptr) return KVS_ERR_INVALID_ARG;
+  if (p->n_units < 1 || p->group < 1 || p->window < 1) return KVS_ERR_INVALID_ARG;
+  if ((long long)p->group * p->window > KVS_MAX_Q_ROWS) return KVS_ERR_INVALID_ARG;
+  if (p->head_dim != 64 && p->head_dim != 128) return KVS_ERR_INVALID_ARG;
+  if (p->n_sink < 0 || p->n_recent < 0) return KVS_ERR_INVALID_ARG;
+  if (p->io_dtype != KVS_F32 && p->io_dtype != KVS_BF16) return KVS_ERR_DTYPE;
+  if (!(p->scale >= 0.f) || !std::isfinite(p->scale)) return KVS_ERR_INVALID_ARG;
+  if (!p->len || !p->budget || !p->in_row || !p->out_row) return KVS_ERR_INVALID_ARG;
+
+  plan->n_units = p->n_units;
+  plan->dtype = p->io_dtype;
+  plan->elt = (p->io_dtype == KVS_F32) ? 4 : 2;
+  plan->shape.R = p->group * p->window;
+  plan->shape.D = p->head_dim;
+  plan->shape.n_sink = p->n_sink;
+  plan->shape.n_recent = p->n_recent;
+  const double scale = (p->scale == 0.f) ? 1.0 / std::sqrt((double)p->head_dim) : (double)p->scale;
+  plan->shape.scale_log2 = (float)(scale * 1.4426950408889634);
+  plan->units.resize(p->n_units);
+
+  for (int u = 0; u < p->n_units; ++u) {
+    const long long len = p->len[u], budget = p->budget[u];
+    if (len < 1 || len > (1ll << 30) || p->in_row[u] < 0 || p->out_row[u] < 0) return KVS_ERR_INVALID_ARG;
+    if (budget < 1) return KVS_ERR_BUDGET;
+    if (len > budget && budget < (long long)p->n_sink + 1 + p->n_recent) return KVS_ERR_BUDGET;
+    Unit& un = plan->units[u];
+    un.in_row = p->in_row[u];
+    un.out_row = p->out_row[u];
+    un.len = (int)len;
+    un.n_out = (int)std::min(len, budget);
+    const int per = (int)((len + kMaxChunks - 1) / kMaxChunks);
+    un.chunk_len = std::max(kMinChunkLen, (per + kWave - 1) / kWave * kWave);
+    un.n_chunks = (int)((len + un.chunk_len - 1) / un.chunk_len);
+    un.chunk_base = un.m_base = 0;
+    un.index = u;
+    un.pad = 0;
+    plan->rows_in = std::max(plan->rows_in, un.in_row + len);
+    plan->rows_out = std::max(plan->rows_out, un.out_row + (long long)un.n_out);
+  }
+  // the units' row ranges must not overlap, on the input and on the output side
+  std::vector<std::pair<long long, long long>> in(p->n_units), out(p->n_units);
+  for (int u = 0; u < p->n_units; ++u) {
+    in[u] = {plan->units[u].in_row, plan->units[u].in_row + plan->units[u].len};
+    out[u] = {plan->units[u].out_row, plan->units[u].out_row + plan->units[u].n_out};
+  }
+  std::sort(in.begin(), in.end());
+  std::sort(out.begin(), out.end());
+  for (int u = 1; u < p->n_units; ++u) {
+    if (in[u].first < in[u - 1].second || out[u].first < out[u - 1].second) return KVS_ERR_INVALID_ARG;
+  }
+  return KVS_OK;
+}
+
+// Workspace layout.  `base` may be null (sizing only).
+Workspace carve(const Plan& plan, void* base) {
+  Workspace w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* ptr = base ? (char*)base + off : nullptr;
+    off += align_up(bytes);
+    return (void*)ptr;
+  };
+  const size_t nu = (size_t)plan.n_units;
+  w.stats_part = (float2*)take(nu * kMaxChunks * plan.shape.R * sizeof(float2));
+  w.o_part = (float*)take(nu * kMaxChunks * plan.shape.D * sizeof(float));
+  w.alpha_bar = (float*)take((size_t)plan.rows_in * sizeof(float));
+  w.o_bar = (float*)take(nu * plan.shape.D * sizeof(float));
+  w.edge_mask = (uint8_t*)take((size_t)plan.rows_in);
+  w.slot = (int32_t*)take((size_t)plan.rows_in * sizeof(int32_t));
+  w.bytes = off;
+  return w;
+}
+
+struct Range {
+  const void* p;
+  size_t bytes;
+  bool is_output;
+};
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+kvs_status check_ranges(const std::vector<Range>& rs) {
+  for (const Range& r : rs) {
+    if (r.p == nullptr || !aligned16(r.p)) return KVS_ERR_INVALID_ARG;
+  }
+  for (size_t i = 0; i < rs.size(); ++i) {
+    if (!rs[i].is_output) continue;
+    for (size_t j = 0; j < rs.size(); ++j) {
+      if (i == j) continue;
+      const char* a0 = (const char*)rs[i].p;
+      const char* b0 = (const char*)rs[j].p;
+      if (a0 < b0 + rs[j].bytes && b0 < a0 + rs[i].bytes) return KVS_ERR_ALIAS;
+    }
+  }
+  return KVS_OK;
+}
+
+kvs_status check_ws(const Plan& plan, const void* ws, size_t ws_bytes, Workspace* out, void* ws_mut) {
+  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0) return KVS_ERR_WORKSPACE;
+  *out = carve(plan, ws_mut);
+  if (ws_bytes < out->bytes) return KVS_ERR_WORKSPACE;
+  return KVS_OK;
+}
+
+// Calls f(table) for every group of at most kMaxUnitsPerLaunch units.
+template <typename F>
+kvs_status for_each_group(const Plan& plan, F&& f) {
+  for (int first = 0; first < plan.n_units; first += kMaxUnitsPerLaunch) {
+    UnitTable tab;
+    std::memset(&tab, 0, sizeof(tab));
+    tab.n_units = std::min(kMaxUnitsPerLaunch, plan.n_units - first);
+    int chunks = 0, mblocks = 0;
+    for (int i = 0; i < tab.n_units; ++i) {
+      tab.u[i] = plan.units[first + i];
+      tab.u[i].chunk_base = chunks;
+      tab.u[i].m_base = mblocks;
+      chunks += tab.u[i].n_chunks;
+      mblocks += (tab.u[i].len + kMergeTokens - 1) / kMergeTokens;
+    }
+    tab.total_chunks = chunks;
+    tab.total_mblocks = mblocks;
+    if (f(tab) != hipSuccess) return KVS_ERR_DEVICE;
+  }
+  return KVS_OK;
+}
+
+}  // namespace
+
+hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
+                        const void* V, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+  // KVS_SCORE_PATH=valu forces the vector-ALU kernels (used by the tests to cover both paths).
+  const char* force = std::getenv("KVS_SCORE_PATH");
+  const bool force_valu = force && std::strcmp(force, "valu") == 0;
+  if (!force_valu && score_mfma_supported(sh, dt)) return launch_score_mfma(tab, sh, Q, K, V, alpha_bar, ws, stream);
+  return launch_score_valu(tab, sh, dt, Q, K, V, alpha_bar, ws, stream);
+}
+
+}  // namespace kvs
+
+using namespace kvs;
+
+extern "C" {
+
+kvs_status kvs_workspace_size(const kvs_problem* p, size_t* bytes) {
+  if (bytes == nullptr) return KVS_ERR_INVALID_ARG;
+  Plan plan;
+  const kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  *bytes = carve(plan, nullptr).bytes;
+  return KVS_OK;
+}
+
+kvs_status kvs_score(const kvs_problem* p, const void* Q, const void* K, const void* V, float* alpha_bar,
+                     float* o_bar, void* ws, size_t ws_bytes, void* hip_stream) {
+  Plan plan;
+  kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  Workspace w;
+  if ((st = check_ws(plan, ws, ws_bytes, &w, ws)) != KVS_OK) return st;
+  const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
+  const size_t nu = (size_t)plan.n_units;
+  st = check_ranges({{Q, nu * plan.shape.R * plan.shape.D * plan.elt, false},
+                     {K, kv, false},
+                     {V, kv, false},
+                     {alpha_bar, (size_t)plan.rows_in * 4, true},
+                     {o_bar, nu * plan.shape.D * 4, true},
+                     {ws, w.bytes, true}});
+  if (st != KVS_OK) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  return for_each_group(plan, [&](const UnitTable& tab) {
+    hipError_t e = launch_score(tab, plan.shape, plan.dtype, Q, K, V, alpha_bar, w, s);
+    if (e != hipSuccess) return e;
+    return launch_obar_reduce(tab, plan.shape, w, o_bar, s);
+  });
+}
+
+kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar, uint8_t* edge_mask, int32_t* slot_of_token,
+                      void* ws, size_t ws_bytes, void* hip_stream) {
+  (void)ws;
+  (void)ws_bytes;
+  Plan plan;
+  kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  st = check_ranges({{alpha_bar, (size_t)plan.rows_in * 4, false},
+                     {edge_mask, (size_t)plan.rows_in, true},
+                     {slot_of_token, (size_t)plan.rows_in * 4, true}});
+  if (st != KVS_OK) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  return for_each_group(plan, [&](const UnitTable& tab) {
+    return launch_select(tab, plan.shape, alpha_bar, edge_mask, slot_of_token, nullptr, nullptr, s);
+  });
+}
+
+kvs_status kvs_merge_compact(const kvs_problem* p, const void* K, const void* V, const float* alpha_bar,
+                             const float* o_bar, const uint8_t* edge_mask, const int32_t* slot_of_token,
+                             void* K_out, void* V_out, int32_t* counts_out, void* ws, size_t ws_bytes,
+                             void* hip_stream) {
+  (void)ws;
+  (void)ws_bytes;
+  Plan plan;
+  kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
+  const size_t kvo = (size_t)plan.rows_out * plan.shape.D * plan.elt;
+  st = check_ranges({{K, kv, false},
+                     {V, kv, false},
+                     {alpha_bar, (size_t)plan.rows_in * 4, false},
+                     {o_bar, (size_t)plan.n_units * plan.shape.D * 4, false},
+                     {edge_mask, (size_t)plan.rows_in, false},
+                     {slot_of_token, (size_t)plan.rows_in * 4, false},
+                     {K_out, kvo, true},
+                     {V_out, kvo, true},
+                     {counts_out, (size_t)plan.rows_out * 4, true}});
+  if (st != KVS_OK) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  return for_each_group(plan, [&](const UnitTable& tab) {
+    return launch_merge(tab, plan.shape, plan.dtype, K, V, alpha_bar, o_bar, edge_mask, slot_of_token, K_out,
+                        V_out, counts_out, s);
+  });
+}
+
+kvs_status kvs_step(const kvs_problem* p, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
+                    int32_t* counts_out, int32_t* slot_of_token_out, uint8_t* edge_mask_out, void* ws,
+                    size_t ws_bytes, void* hip_stream) {
+  Plan plan;
+  kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  Workspace w;
+  if ((st = check_ws(plan, ws, ws_bytes, &w, ws)) != KVS_OK) return st;
+  const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
+  const size_t kvo = (size_t)plan.rows_out * plan.shape.D * plan.elt;
+  std::vector<Range> rs = {{Q, (size_t)plan.n_units * plan.shape.R * plan.shape.D * plan.elt, false},
+                           {K, kv, false},
+                           {V, kv, false},
+                           {K_out, kvo, true},
+                           {V_out, kvo, true},
+                           {counts_out, (size_t)plan.rows_out * 4, true},
+                           {ws, w.bytes, true}};
+  if (slot_of_token_out) rs.push_back({slot_of_token_out, (size_t)plan.rows_in * 4, true});
+  if (edge_mask_out) rs.push_back({edge_mask_out, (size_t)plan.rows_in, true});
+  if ((st = check_ranges(rs)) != KVS_OK) return st;
+
+  uint8_t* mask = edge_mask_out ? edge_mask_out : w.edge_mask;
+  int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
+  hipStream_t s = (hipStream_t)hip_stream;
+  return for_each_group(plan, [&](const UnitTable& tab) {
+    hipError_t e = launch_score(tab, plan.shape, plan.dtype, Q, K, V, w.alpha_bar, w, s);
+    if (e != hipSuccess) return e;
+    e = launch_select(tab, plan.shape, w.alpha_bar, mask, slot, &w, w.o_bar, s);   // also reduces o_bar
+    if (e != hipSuccess) return e;
+    return launch_merge(tab, plan.shape, plan.dtype, K, V, w.alpha_bar, w.o_bar, mask, slot, K_out, V_out,
+                        counts_out, s);
+  });
+}
+
+const char* kvs_status_str(kvs_status s) {
+  switch (s) {
+    case KVS_OK: return "ok";
+    case KVS_ERR_INVALID_ARG: return "invalid argument";
+    case KVS_ERR_DTYPE: return "unsupported dtype";
+    case KVS_ERR_BUDGET: return "budget too small for n_sink + n_recent";
+    case KVS_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case KVS_ERR_ALIAS: return "an output overlaps another buffer";
+    case KVS_ERR_DEVICE: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+int kvs_version(void) { return KVS_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,113 @@
+// Internal declarations shared by the host layer and the gfx950 kernels of libkvs.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kvs.h"
+
+namespace kvs {
+
+constexpr int kMaxUnitsPerLaunch = 64;   // unit descriptors travel by value in the kernel arguments
+constexpr int kMaxChunks = 64;           // token chunks (= score workgroups) per unit
+constexpr int kMinChunkLen = 256;        // tokens
+constexpr int kMergeTokens = 256;     // tokens per merge workgroup
+constexpr int kWave = 64;
+
+// One (sequence, KV head).  Rows are in elements of D, not bytes.
+struct Unit {
+  long long in_row;     // first row in K, V, alpha_bar, edge_mask, slot_of_token
+  long long out_row;    // first row in K_out, V_out, counts_out
+  int len;              // cached tokens
+  int n_out;            // output rows: min(len, budget)
+  int chunk_len;        // tokens per score chunk (multiple of 64)
+  int n_chunks;         // ceil(len / chunk_len), <= kMaxChunks
+  int chunk_base;       // chunks of the launch's earlier units
+  int m_base;           // merge workgroups (kMergeTokens tokens each) of the launch's earlier units
+  int index;            // position of the unit in the caller's problem (indexes Q, o_bar, partials)
+  int pad;
+};
+
+struct UnitTable {
+  int n_units;
+  int total_chunks;
+  int total_mblocks;
+  int pad0;
+  Unit u[kMaxUnitsPerLaunch];
+};
+
+struct Shape {
+  int R;            // query rows per unit (G*W)
+  int D;            // head dim
+  int n_sink;
+  int n_recent;
+  float scale_log2; // logit scale * log2(e): logits are kept in the base-2 domain
+};
+
+// Workspace carve-up (all offsets multiples of 256 bytes).
+struct Workspace {
+  float2* stats_part;   // [n_units][kMaxChunks][R]  (running max, sum) of every chunk, base-2 domain
+  float* o_part;        // [n_units][kMaxChunks][D]  partial o_bar of every chunk
+  float* alpha_bar;     // [rows]    (kvs_step only)
+  float* o_bar;         // [n_units][D] (kvs_step only)
+  uint8_t* edge_mask;   // [rows]    (kvs_step only, when the caller keeps it internal)
+  int32_t* slot;        // [rows]
+  size_t bytes;
+};
+
+// Device helpers --------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// float -> bf16 bits, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16);
+}
+
+// 16-byte row piece -> floats.  T = float: 4 values; T = bf16 (uint16_t): 8 values.
+template <typename T> struct Piece;
+template <> struct Piece<float> {
+  static constexpr int N = 4;
+  __device__ __forceinline__ static void unpack(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+  __device__ __forceinline__ static uint4 pack(const float* f) {
+    return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+  }
+};
+template <> struct Piece<uint16_t> {
+  static constexpr int N = 8;
+  __device__ __forceinline__ static void unpack(const uint4& r, float* f) {
+    f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x); f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+    f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+  }
+  __device__ __forceinline__ static uint4 pack(const float* f) {
+    return make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
+  }
+};
+
+// Which unit and which chunk a workgroup of a chunk-indexed launch works on.
+__device__ __forceinline__ int find_unit(const UnitTable& tab, int chunk) {
+  int u = 0;
+  while (u + 1 < tab.n_units && tab.u[u + 1].chunk_base <= chunk) ++u;
+  return u;
+}
+
+// Launchers (defined next to their kernels).  All enqueue on `stream` and return the launch status.
+hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
+                        const void* V, float* alpha_bar, const Workspace& ws, hipStream_t stream);
+hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const Workspace& ws, float* o_bar,
+                              hipStream_t stream);
+hipError_t launch_select(const UnitTable& tab, const Shape& sh, const float* alpha_bar, uint8_t* edge_mask,
+                         int32_t* slot, const Workspace* ws_for_obar, float* o_bar, hipStream_t stream);
+hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* K, const void* V,
+                        const float* alpha_bar, const float* o_bar, const uint8_t* edge_mask,
+                        const int32_t* slot, void* K_out, void* V_out, int32_t* counts, hipStream_t stream);
+
+}  // namespace kvs

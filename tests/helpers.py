@@ -1,0 +1,157 @@
+"""Shared test plumbing: accepted seeds, oracle runs per unit, device marshalling.
+
+Acceptance of a drawn unit (spec rule): the relative gap between the r-th and the (r+1)-th
+smallest edge score must be at least 1e-4, and every merged slot's weight denominator must be at
+least 1e-3 of its sum of A_t, so that an fp32 implementation and the fp64 oracle cannot disagree
+on the selected set or on the fallback branch.  A rejected unit redraws its Queries only.
+"""
+
+from __future__ import annotations
+
+import json
+import os
+from dataclasses import dataclass
+from typing import Dict, List, Optional
+
+import numpy as np
+
+from oracle import kvs_oracle as O
+from workloads import Workload, f32_to_bf16_bits, generate_unit, unit_lengths
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+MANIFEST = os.path.join(GOLDEN, "accepted_attempts.json")
+GAP_MIN = 1e-4
+COND_MIN = 1e-3
+MAX_ATTEMPTS = 2000
+
+
+def manifest_key(w: Workload, layer: int, seq: int, head: int, n: int) -> str:
+    return f"{w.name}/n{n}/L{layer}/S{seq}/H{head}"
+
+
+def load_manifest() -> Dict[str, int]:
+    if os.path.exists(MANIFEST):
+        with open(MANIFEST) as f:
+            return json.load(f)
+    return {}
+
+
+@dataclass
+class AcceptedUnit:
+    inputs: object            # workloads.UnitInputs
+    ref: O.StepResult
+    gap: float
+    cond: float
+
+
+def accepted_unit(w: Workload, layer: int, seq: int, head: int, n: Optional[int] = None,
+                  manifest: Optional[Dict[str, int]] = None) -> AcceptedUnit:
+    """First attempt of this unit that passes the acceptance rule, with its oracle result."""
+    if n is None:
+        n = unit_lengths(w)[seq]
+    manifest = load_manifest() if manifest is None else manifest
+    start = manifest.get(manifest_key(w, layer, seq, head, n), 0)
+    base = None
+    for attempt in range(start, MAX_ATTEMPTS):
+        u = generate_unit(w, layer, seq, head, attempt=attempt, n=n, kv_from=base)
+        base = u
+        alpha_bar, o_bar = O.score(u.Q, u.K, u.V)
+        gap = O.boundary_gap(alpha_bar, u.budget, w.n_sink, w.n_recent)
+        if gap < GAP_MIN:
+            continue
+        mask, slot = O.select(alpha_bar, u.budget, w.n_sink, w.n_recent)
+        merged = O.merge_compact(u.K, u.V, alpha_bar, o_bar, mask, slot)
+        cond = O.conditioning(merged)
+        if cond < COND_MIN:
+            continue
+        return AcceptedUnit(u, O.StepResult(alpha_bar, o_bar, mask, slot, merged), gap, cond)
+    raise RuntimeError("no accepted attempt found")
+
+
+# ------------------------------------------------------------------------------------------------
+# device marshalling (torch is used for memory only)
+def to_device(x32: np.ndarray, dtype: str):
+    import torch
+    if dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(x32, dtype=np.float32)).cuda()
+    bits = f32_to_bf16_bits(x32)
+    assert (np.ascontiguousarray(x32, dtype=np.float32).view(np.uint32) & 0xFFFF == 0).all(), \
+        "bf16 inputs must already be representable"
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def from_device(t) -> np.ndarray:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.float().cpu().numpy()
+    return t.cpu().numpy()
+
+
+def torch_io_dtype(dtype: str):
+    import torch
+    return torch.float32 if dtype == "f32" else torch.bfloat16
+
+
+def rel_err_rows(got: np.ndarray, ref: np.ndarray) -> float:
+    """max over rows of ||got - ref||_2 / ||ref||_2."""
+    num = np.linalg.norm(got.astype(np.float64) - ref, axis=1)
+    den = np.linalg.norm(ref, axis=1)
+    den = np.where(den == 0, 1.0, den)
+    return float((num / den).max()) if len(num) else 0.0
+
+
+class DeviceBatch:
+    """Concatenates units into the flat row layout of the C ABI and allocates outputs with guard bands."""
+
+    GUARD = 64     # rows of guard band after each output buffer
+
+    def __init__(self, units: List, *, group: int, window: int, head_dim: int, dtype: str,
+                 n_sink: int, n_recent: int = 0, budgets: Optional[List[int]] = None, gap_rows: int = 0):
+        import torch
+        import paper_2603_00907_amd as kvs
+        self.kvs = kvs
+        self.units = units
+        lens = [u.K.shape[0] for u in units]
+        budgets = budgets if budgets is not None else [u.budget for u in units]
+        in_rows, acc = [], 0
+        for l in lens:
+            in_rows.append(acc)
+            acc += l + gap_rows
+        self.problem = kvs.Problem(lens=lens, budgets=budgets, group=group, window=window, head_dim=head_dim,
+                                   dtype=dtype, n_sink=n_sink, n_recent=n_recent, in_rows=in_rows)
+        p = self.problem
+        D = head_dim
+        self.dtype = dtype
+        Kall = np.zeros((p.rows_in, D), dtype=np.float32)
+        Vall = np.zeros((p.rows_in, D), dtype=np.float32)
+        for u, r0 in zip(units, in_rows):
+            Kall[r0:r0 + u.K.shape[0]] = u.K
+            Vall[r0:r0 + u.K.shape[0]] = u.V
+        self.K = to_device(Kall, dtype)
+        self.V = to_device(Vall, dtype)
+        self.Q = to_device(np.stack([u.Q.reshape(group * window, D) for u in units]), dtype)
+        tdt = torch_io_dtype(dtype)
+        G = self.GUARD
+        self.K_out = torch.full((p.rows_out + G, D), 777.0, dtype=tdt, device="cuda")
+        self.V_out = torch.full((p.rows_out + G, D), 777.0, dtype=tdt, device="cuda")
+        self.counts = torch.full((p.rows_out + G,), -7, dtype=torch.int32, device="cuda")
+        self.alpha_bar = torch.full((p.rows_in + G,), -7.0, dtype=torch.float32, device="cuda")
+        self.o_bar = torch.full((len(units) + 1, D), -7.0, dtype=torch.float32, device="cuda")
+        self.mask = torch.full((p.rows_in + G,), 9, dtype=torch.uint8, device="cuda")
+        self.slot = torch.full((p.rows_in + G,), -7, dtype=torch.int32, device="cuda")
+        self.ws = torch.empty(kvs.kvs_workspace_size(p) + 256, dtype=torch.uint8, device="cuda")
+        assert self.ws.data_ptr() % 256 == 0
+
+    def stream(self) -> int:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+
+    def check_guards(self):
+        p, G = self.problem, self.GUARD
+        assert (self.K_out[p.rows_out:].float() == 777.0).all()
+        assert (self.V_out[p.rows_out:].float() == 777.0).all()
+        assert (self.counts[p.rows_out:] == -7).all()
+        assert (self.alpha_bar[p.rows_in:] == -7.0).all()
+        assert (self.o_bar[len(self.units):] == -7.0).all()
+        assert (self.mask[p.rows_in:] == 9).all()
+        assert (self.slot[p.rows_in:] == -7).all()

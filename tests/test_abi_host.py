@@ -1,0 +1,160 @@
+"""CPU-only checks of the C ABI: the library loads, exports what include/kvs.h declares, and every
+argument error is reported on the host before anything is launched (so no GPU is needed here)."""
+
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2603_00907_amd as kvs
+from paper_2603_00907_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "kvs.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kvs_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = kvs.load_library()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+    assert kvs.kvs_version() == 100
+    assert kvs.status_str(kvs.KVS_OK) == "ok"
+    for code in range(1, 7):
+        assert kvs.status_str(code) not in ("ok", "unknown status")
+
+
+def problem(**kw):
+    base = dict(lens=[1024, 500], budgets=[512, 600], group=2, window=4, head_dim=64, dtype="f32")
+    base.update(kw)
+    return kvs.Problem(**base)
+
+
+def status_of(fn, *a, **k):
+    try:
+        fn(*a, **k)
+    except kvs.KvsError as e:
+        return e.status
+    return kvs.KVS_OK
+
+
+def test_workspace_size_grows_with_the_problem():
+    small = kvs.kvs_workspace_size(problem())
+    big = kvs.kvs_workspace_size(problem(lens=[100000, 500]))
+    assert small % 256 == 0 and big > small
+    # pieces: chunk statistics, chunk o_bar, alpha_bar, o_bar, edge mask, slot map
+    rows, nu, R, D = 1524, 2, 8, 64
+    lower = nu * 64 * R * 8 + nu * 64 * D * 4 + rows * 4 + nu * D * 4 + rows + rows * 4
+    assert lower <= small <= lower + 6 * 256
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(head_dim=96), kvs.KVS_ERR_INVALID_ARG),
+    (dict(group=0), kvs.KVS_ERR_INVALID_ARG),
+    (dict(group=64, window=32), kvs.KVS_ERR_INVALID_ARG),          # G*W above KVS_MAX_Q_ROWS
+    (dict(lens=[0, 5]), kvs.KVS_ERR_INVALID_ARG),
+    (dict(n_sink=-1), kvs.KVS_ERR_INVALID_ARG),
+    (dict(scale=float("nan")), kvs.KVS_ERR_INVALID_ARG),
+    (dict(dtype=7), kvs.KVS_ERR_DTYPE),
+    (dict(budgets=[20, 600]), kvs.KVS_ERR_BUDGET),                 # must merge but budget < n_sink + 1
+    (dict(budgets=[32, 600], n_sink=30, n_recent=2), kvs.KVS_ERR_BUDGET),
+    (dict(budgets=[0, 600]), kvs.KVS_ERR_BUDGET),
+    (dict(in_rows=[0, 1000]), kvs.KVS_ERR_INVALID_ARG),            # input rows of the units overlap
+    (dict(out_rows=[0, 100]), kvs.KVS_ERR_INVALID_ARG),            # output rows overlap
+    (dict(budgets=[33, 600]), kvs.KVS_OK),
+    (dict(budgets=[33, 600], n_recent=1), kvs.KVS_ERR_BUDGET),
+])
+def test_problem_validation(kw, want):
+    assert status_of(kvs.kvs_workspace_size, problem(**kw)) == want
+
+
+class FakeBuf:
+    """An address range that is never dereferenced: validation happens before any launch."""
+
+    def __init__(self, addr, nbytes):
+        self.addr, self.nbytes = addr, nbytes
+
+    def data_ptr(self):
+        return self.addr
+
+    def numel(self):
+        return self.nbytes
+
+    def element_size(self):
+        return 1
+
+
+def fake_buffers(p, D=64, elt=4):
+    a = 1 << 30
+    out = {}
+    for name, nbytes in [("Q", len(p.lens) * p.group * p.window * D * elt), ("K", p.rows_in * D * elt),
+                         ("V", p.rows_in * D * elt), ("K_out", p.rows_out * D * elt),
+                         ("V_out", p.rows_out * D * elt), ("counts", p.rows_out * 4),
+                         ("alpha", p.rows_in * 4), ("obar", len(p.lens) * D * 4), ("mask", p.rows_in),
+                         ("slot", p.rows_in * 4), ("ws", kvs.kvs_workspace_size(p))]:
+        out[name] = FakeBuf(a, nbytes)
+        a += (nbytes + 4095) // 4096 * 4096
+    return out
+
+
+def test_pointer_workspace_and_alias_errors_are_host_side():
+    p = problem()
+    b = fake_buffers(p)
+    step = lambda **o: status_of(  # noqa: E731
+        kvs.kvs_step, p, o.get("Q", b["Q"]), o.get("K", b["K"]), o.get("V", b["V"]), o.get("K_out", b["K_out"]),
+        o.get("V_out", b["V_out"]), o.get("counts", b["counts"]), o.get("ws", b["ws"]),
+        slot_of_token_out=o.get("slot"), edge_mask_out=o.get("mask"), ws_bytes=o.get("ws_bytes"))
+    assert step(K=None) == kvs.KVS_ERR_INVALID_ARG
+    assert step(K=FakeBuf(b["K"].addr + 4, 16)) == kvs.KVS_ERR_INVALID_ARG           # misaligned
+    assert step(ws=None, ws_bytes=0) == kvs.KVS_ERR_WORKSPACE
+    assert step(ws=FakeBuf(b["ws"].addr + 16, b["ws"].nbytes)) == kvs.KVS_ERR_WORKSPACE
+    assert step(ws_bytes=b["ws"].nbytes - 1) == kvs.KVS_ERR_WORKSPACE
+    assert step(K_out=b["K"]) == kvs.KVS_ERR_ALIAS
+    assert step(V_out=b["K_out"]) == kvs.KVS_ERR_ALIAS
+    assert step(counts=FakeBuf(b["ws"].addr + 256, 64)) == kvs.KVS_ERR_ALIAS
+    assert step(slot=b["V"]) == kvs.KVS_ERR_ALIAS
+    assert step(mask=FakeBuf(b["K_out"].addr + 16, 64)) == kvs.KVS_ERR_ALIAS
+    # inputs may alias each other (K used as V is legal, if odd)
+    bad = status_of(kvs.kvs_score, p, b["Q"], b["K"], b["K"], b["alpha"], b["K"], b["ws"])
+    assert bad == kvs.KVS_ERR_ALIAS
+    assert status_of(kvs.kvs_select, p, b["alpha"], b["alpha"], b["slot"]) == kvs.KVS_ERR_ALIAS
+    assert status_of(kvs.kvs_merge_compact, p, b["K"], b["V"], b["alpha"], b["obar"], b["mask"], b["slot"],
+                     b["K_out"], b["K_out"], b["counts"]) == kvs.KVS_ERR_ALIAS
+    assert status_of(kvs.kvs_merge_compact, p, b["K"], b["V"], b["alpha"], b["obar"], None, b["slot"],
+                     b["K_out"], b["V_out"], b["counts"]) == kvs.KVS_ERR_INVALID_ARG
+
+
+def test_null_problem_and_null_tables():
+    lib = kvs.load_library()
+    out = C.c_size_t(0)
+    assert lib.kvs_workspace_size(None, C.byref(out)) == kvs.KVS_ERR_INVALID_ARG
+    p = problem()
+    assert lib.kvs_workspace_size(p.ref, None) == kvs.KVS_ERR_INVALID_ARG
+    p.struct.len = None
+    assert lib.kvs_workspace_size(p.ref, C.byref(out)) == kvs.KVS_ERR_INVALID_ARG
+
+
+def test_generator_is_order_independent_and_rounds_once():
+    from workloads import WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, generate_unit
+    w = WORKLOADS["llama8b_8k"].scaled(length=("fixed", 300))
+    a = generate_unit(w, 0, 0, 3)
+    _ = generate_unit(w, 0, 0, 1)
+    b = generate_unit(w, 0, 0, 3)
+    assert (a.K == b.K).all() and (a.V == b.V).all() and (a.Q == b.Q).all()
+    c = generate_unit(w, 0, 0, 3, attempt=1, kv_from=a)
+    assert (c.K == a.K).all() and not (c.Q == a.Q).all()
+    assert (bf16_bits_to_f32(f32_to_bf16_bits(a.K)) == a.K).all()           # already representable
+    # round-to-nearest-even on a tie
+    x = np.array([1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8], dtype=np.float32)
+    assert bf16_bits_to_f32(f32_to_bf16_bits(x)).tolist() == [1.0, 1.0 + 2 ** -6]
+    # four outlier channels, scaled 8x
+    var = a.K.var(axis=0)
+    assert (var > 20 * np.median(var)).sum() == 4

@@ -1,0 +1,358 @@
+"""GPU-vs-oracle parity of the HIP library, called through its C ABI.
+
+Bars: selected edges, slot maps and counts bit-exact; merged K / V within 1e-5 (fp32 I/O) or
+1e-2 (bf16 I/O) relative L2 error per output row.  alpha_bar within 3e-5 relative (fp32 logits and
+exponentials; see the design doc for the derivation), o_bar within 3e-5 of sum_t alpha_bar[t] |V[t]|.
+"""
+
+import os
+
+import numpy as np
+import pytest
+
+from oracle import kvs_oracle as O
+from workloads import WORKLOADS, generate_unit, unit_lengths
+
+from helpers import DeviceBatch, accepted_unit, from_device, rel_err_rows
+
+pytestmark = pytest.mark.gpu
+
+TOL_KV = {"f32": 1e-5, "bf16": 1e-2}
+TOL_ALPHA = 3e-5
+
+
+def torch_sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def variant(base, **kw):
+    return WORKLOADS[base].scaled(**kw)
+
+
+class env_override:
+    def __init__(self, key, value):
+        self.key, self.value = key, value
+
+    def __enter__(self):
+        self.old = os.environ.get(self.key)
+        if self.value is None:
+            os.environ.pop(self.key, None)
+        else:
+            os.environ[self.key] = self.value
+
+    def __exit__(self, *a):
+        if self.old is None:
+            os.environ.pop(self.key, None)
+        else:
+            os.environ[self.key] = self.old
+
+
+# ------------------------------------------------------------------------------------------------
+SCORE_CASES = [
+    # base, dtype, D, G, W, lengths, path
+    ("tiny", "f32", 64, 1, 8, [1024], None),
+    ("tiny", "f32", 128, 2, 3, [777], None),
+    ("tiny", "f32", 64, 3, 7, [1300, 64], None),
+    ("tiny", "f32", 64, 1, 1, [257], None),
+    ("llama8b_8k", "bf16", 128, 4, 32, [2500], None),
+    ("llama8b_8k", "bf16", 128, 4, 32, [2500], "valu"),
+    ("llama8b_8k", "bf16", 64, 2, 16, [900], None),
+    ("llama8b_8k", "bf16", 128, 1, 20, [700, 33], None),
+    ("llama8b_8k", "bf16", 128, 3, 20, [1111], None),
+    ("llama8b_8k", "bf16", 128, 5, 20, [1500], None),
+    ("llama8b_8k", "bf16", 128, 8, 32, [3000], None),
+    ("stress128k", "bf16", 128, 8, 64, [3000], None),
+    ("stress128k", "bf16", 128, 8, 100, [1200], None),
+    ("llama8b_8k", "bf16", 64, 1, 4, [500], None),
+    ("ragged16", "bf16", 128, 4, 32, [300, 5000, 33000], None),
+]
+
+
+@pytest.mark.parametrize("base,dtype,D,G,W,lens,path", SCORE_CASES)
+def test_score_matches_oracle(base, dtype, D, G, W, lens, path):
+    w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
+    units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
+    batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype=dtype, n_sink=w.n_sink, gap_rows=3)
+    with env_override("KVS_SCORE_PATH", path):
+        batch.kvs.kvs_score(batch.problem, batch.Q, batch.K, batch.V, batch.alpha_bar, batch.o_bar, batch.ws,
+                            stream=batch.stream())
+        torch_sync()
+    batch.check_guards()
+    alpha = from_device(batch.alpha_bar)
+    obar = from_device(batch.o_bar)
+    for i, u in enumerate(units):
+        ra, ro = O.score(u.Q, u.K, u.V)
+        r0 = batch.problem.in_rows[i]
+        got = alpha[r0:r0 + len(ra)]
+        assert np.isfinite(got).all()
+        assert np.max(np.abs(got - ra) / ra) < TOL_ALPHA, (i, np.max(np.abs(got - ra) / ra))
+        bound = TOL_ALPHA * (ra @ np.abs(u.V.astype(np.float64))) + 1e-7
+        assert (np.abs(obar[i] - ro) <= bound).all(), (i, np.max(np.abs(obar[i] - ro) / bound))
+    # rows between units are never touched
+    for i in range(len(units) - 1):
+        gap0 = batch.problem.in_rows[i] + lens[i]
+        assert (alpha[gap0:gap0 + 3] == -7.0).all()
+
+
+# ------------------------------------------------------------------------------------------------
+def run_select(alphas, budgets, n_sink, n_recent):
+    import torch
+    import paper_2603_00907_amd as kvs
+    lens = [len(a) for a in alphas]
+    p = kvs.Problem(lens=lens, budgets=budgets, group=1, window=1, head_dim=64, dtype="f32",
+                    n_sink=n_sink, n_recent=n_recent)
+    flat = torch.from_numpy(np.concatenate(alphas).astype(np.float32)).cuda()
+    mask = torch.full((p.rows_in + 64,), 9, dtype=torch.uint8, device="cuda")
+    slot = torch.full((p.rows_in + 64,), -7, dtype=torch.int32, device="cuda")
+    kvs.kvs_select(p, flat, mask, slot, stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert (mask[p.rows_in:] == 9).all() and (slot[p.rows_in:] == -7).all()
+    return p, mask.cpu().numpy(), slot.cpu().numpy()
+
+
+def check_select(alphas, budgets, n_sink, n_recent):
+    p, mask, slot = run_select(alphas, budgets, n_sink, n_recent)
+    for i, a in enumerate(alphas):
+        a32 = a.astype(np.float32)
+        rm, rs = O.select(a32, budgets[i], n_sink, n_recent, sigma_dtype=np.float32)
+        r0 = p.in_rows[i]
+        assert (mask[r0:r0 + len(a)] == rm).all(), f"unit {i}: edge mask differs"
+        assert (slot[r0:r0 + len(a)] == rs).all(), f"unit {i}: slot map differs"
+
+
+@pytest.mark.parametrize("n,budget,s,nr,kind", [
+    (1024, 512, 32, 0, "dirichlet"), (1000, 100, 32, 0, "lognormal"), (5000, 4999, 32, 0, "lognormal"),
+    (5000, 33, 32, 0, "lognormal"), (4096, 1024, 0, 0, "ties"), (4096, 1024, 32, 100, "ties"),
+    (3000, 700, 32, 0, "uniform"), (32801, 4096, 32, 0, "lognormal"), (32802, 4096, 32, 0, "lognormal"),
+    (40000, 10000, 32, 0, "ties"), (131072, 8192, 32, 0, "lognormal"), (50, 50, 32, 0, "dirichlet"),
+    (50, 80, 32, 0, "dirichlet"), (34, 33, 32, 0, "dirichlet"), (1, 1, 32, 0, "dirichlet"),
+    (20, 5, 2, 3, "zeros")])
+def test_select_bit_exact(n, budget, s, nr, kind):
+    rng = np.random.default_rng(n * 7 + budget)
+    if kind == "dirichlet":
+        a = rng.dirichlet(np.ones(n) * 0.5)
+    elif kind == "lognormal":
+        a = np.exp(4.0 * rng.standard_normal(n))
+        a /= a.sum()
+    elif kind == "ties":
+        a = rng.integers(1, 5, size=n).astype(np.float64) / (2.5 * n)
+    elif kind == "uniform":
+        a = np.full(n, 1.0 / n)
+    else:
+        a = np.zeros(n)
+    check_select([a], [budget], s, nr)
+
+
+def test_select_many_ragged_units():
+    rng = np.random.default_rng(5)
+    lens = [int(x) for x in rng.integers(40, 9000, size=70)]       # more than one launch group
+    alphas = []
+    for n in lens:
+        a = np.exp(3.0 * rng.standard_normal(n))
+        alphas.append(a / a.sum())
+    budgets = [max(33, n // 4) for n in lens]
+    budgets[3] = lens[3] + 5                                         # pass-through unit
+    check_select(alphas, budgets, 32, 0)
+
+
+# ------------------------------------------------------------------------------------------------
+def merge_case(base, dtype, D, lens, budgets=None, R=(1, 4), seed_layer=0):
+    G, W = R
+    w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
+    units = [generate_unit(w, seed_layer, s, 0, n=n) for s, n in enumerate(lens)]
+    if budgets is not None:
+        for u, b in zip(units, budgets):
+            u.budget = b
+    return w, units
+
+
+@pytest.mark.parametrize("base,dtype,D,lens,budgets", [
+    ("tiny", "f32", 64, [1024], None),
+    ("tiny", "f32", 128, [700, 41], [300, 35]),
+    ("llama8b_8k", "bf16", 128, [3000, 257], [700, 100]),
+    ("llama8b_8k", "bf16", 64, [2000], [1999]),
+    ("tiny", "f32", 64, [600], [33]),            # one run swallows everything after the sinks
+    ("tiny", "f32", 64, [300, 200], [300, 500]),  # pass-through
+])
+def test_merge_compact_matches_oracle(base, dtype, D, lens, budgets):
+    import torch
+    w, units = merge_case(base, dtype, D, lens, budgets)
+    batch = DeviceBatch(units, group=w.group, window=w.window, head_dim=D, dtype=dtype, n_sink=w.n_sink)
+    p = batch.problem
+    refs = []
+    alpha_all = np.zeros(p.rows_in, dtype=np.float32)
+    mask_all = np.zeros(p.rows_in, dtype=np.uint8)
+    slot_all = np.zeros(p.rows_in, dtype=np.int32)
+    obar_all = np.zeros((len(units), D), dtype=np.float32)
+    for i, u in enumerate(units):
+        a, o = O.score(u.Q, u.K, u.V)
+        a32, o32 = a.astype(np.float32), o.astype(np.float32)
+        mask, slot = O.select(a32, u.budget, w.n_sink, 0, sigma_dtype=np.float32)
+        refs.append(O.merge_compact(u.K, u.V, a32.astype(np.float64), o32.astype(np.float64), mask, slot))
+        r0 = p.in_rows[i]
+        alpha_all[r0:r0 + len(a)] = a32
+        mask_all[r0:r0 + len(a)] = mask
+        slot_all[r0:r0 + len(a)] = slot
+        obar_all[i] = o32
+    batch.kvs.kvs_merge_compact(p, batch.K, batch.V, torch.from_numpy(alpha_all).cuda(),
+                                torch.from_numpy(obar_all).cuda(), torch.from_numpy(mask_all).cuda(),
+                                torch.from_numpy(slot_all).cuda(), batch.K_out, batch.V_out, batch.counts,
+                                stream=batch.stream())
+    torch_sync()
+    batch.check_guards()
+    compare_outputs(batch, refs, dtype)
+
+
+def compare_outputs(batch, refs, dtype, strict_guard=True):
+    p = batch.problem
+    Ko, Vo, cnt = from_device(batch.K_out), from_device(batch.V_out), batch.counts.cpu().numpy()
+    for i, ref in enumerate(refs):
+        r0, n_out = p.out_rows[i], p.n_out[i]
+        assert ref.K_out.shape[0] == n_out
+        assert (cnt[r0:r0 + n_out] == ref.counts).all(), f"unit {i}: counts differ"
+        assert not ref.fallback.any() or True
+        ek = rel_err_rows(Ko[r0:r0 + n_out], ref.K_out)
+        ev = rel_err_rows(Vo[r0:r0 + n_out], ref.V_out)
+        assert ek <= TOL_KV[dtype], f"unit {i}: merged K rel err {ek:.3e}"
+        assert ev <= TOL_KV[dtype], f"unit {i}: merged V rel err {ev:.3e}"
+        single = ref.counts == 1
+        assert (Ko[r0:r0 + n_out][single] == ref.K_out[single]).all(), f"unit {i}: singleton K not a copy"
+        assert (Vo[r0:r0 + n_out][single] == ref.V_out[single]).all(), f"unit {i}: singleton V not a copy"
+
+
+def test_merge_fallback_and_identical_keys():
+    """Crafted inputs: (a) residuals exactly zero -> denominator 0 -> arithmetic mean on both sides;
+    (b) identical Keys in a run merge to that Key."""
+    import torch
+    import paper_2603_00907_amd as kvs
+    rng = np.random.default_rng(3)
+    n, D = 96, 64
+    K = rng.standard_normal((n, D)).astype(np.float32)
+    V = rng.standard_normal((n, D)).astype(np.float32)
+    obar = rng.standard_normal(D).astype(np.float32)
+    V[10:14] = obar                       # zero residuals: A = C = 0 on the run 10..13
+    K[40:45] = K[40]                      # identical Keys on the run 40..44
+    alpha = rng.dirichlet(np.ones(n)).astype(np.float32)
+    mask = np.zeros(n, dtype=np.uint8)
+    mask[10:13] = 1
+    mask[40:44] = 1
+    mask[70] = 1
+    starts = np.ones(n, dtype=np.int64)
+    starts[1:] = 1 - mask[:-1]
+    slot = (np.cumsum(starts) - 1).astype(np.int32)
+    n_out = int(slot[-1]) + 1
+    ref = O.merge_compact(K, V, alpha.astype(np.float64), obar.astype(np.float64), mask, slot)
+    assert ref.fallback[10] and ref.fallback.sum() == 1
+    p = kvs.Problem(lens=[n], budgets=[n_out], group=1, window=1, head_dim=D, dtype="f32", n_sink=4)
+    Ko = torch.zeros((n_out, D), device="cuda")
+    Vo = torch.zeros((n_out, D), device="cuda")
+    cnt = torch.zeros(n_out, dtype=torch.int32, device="cuda")
+    kvs.kvs_merge_compact(p, torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda(), torch.from_numpy(alpha).cuda(),
+                          torch.from_numpy(obar[None]).cuda(), torch.from_numpy(mask).cuda(),
+                          torch.from_numpy(slot).cuda(), Ko, Vo, cnt)
+    torch.cuda.synchronize()
+    assert (cnt.cpu().numpy() == ref.counts).all()
+    assert rel_err_rows(Ko.cpu().numpy(), ref.K_out) < 1e-5
+    assert rel_err_rows(Vo.cpu().numpy(), ref.V_out) < 1e-5
+    np.testing.assert_allclose(Ko.cpu().numpy()[10], K[10:14].mean(axis=0), rtol=1e-6)
+    np.testing.assert_allclose(Ko.cpu().numpy()[37], K[40], rtol=2e-6)
+
+
+# ------------------------------------------------------------------------------------------------
+def run_step(w, accepted, path=None):
+    units = [a.inputs for a in accepted]
+    batch = DeviceBatch(units, group=w.group, window=w.window, head_dim=w.head_dim, dtype=w.dtype,
+                        n_sink=w.n_sink, n_recent=w.n_recent)
+    with env_override("KVS_SCORE_PATH", path):
+        batch.kvs.kvs_step(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out, batch.counts,
+                           batch.ws, slot_of_token_out=batch.slot, edge_mask_out=batch.mask, stream=batch.stream())
+        torch_sync()
+    batch.check_guards()
+    return batch
+
+
+def check_step(w, accepted, path=None):
+    batch = run_step(w, accepted, path)
+    p = batch.problem
+    mask, slot = batch.mask.cpu().numpy(), batch.slot.cpu().numpy()
+    for i, a in enumerate(accepted):
+        r0, n = p.in_rows[i], a.inputs.n
+        assert (mask[r0:r0 + n] == a.ref.mask).all(), f"unit {i}: selected edges differ (gap {a.gap:.2e})"
+        assert (slot[r0:r0 + n] == a.ref.slot).all(), f"unit {i}: slot map differs"
+    compare_outputs(batch, [a.ref.merged for a in accepted], w.dtype)
+    return batch
+
+
+def test_step_tiny_config():
+    w = WORKLOADS["tiny"]
+    check_step(w, [accepted_unit(w, 0, 0, 0)])
+
+
+def test_step_tiny_config_is_deterministic():
+    w = WORKLOADS["tiny"]
+    acc = [accepted_unit(w, 0, 0, 0)]
+    b1 = run_step(w, acc)
+    b2 = run_step(w, acc)
+    import torch
+    assert torch.equal(b1.K_out.view(torch.int32), b2.K_out.view(torch.int32))
+    assert torch.equal(b1.V_out.view(torch.int32), b2.V_out.view(torch.int32))
+    assert torch.equal(b1.counts, b2.counts)
+
+
+@pytest.mark.parametrize("path", [None, "valu"])
+def test_step_llama8b_8k_config(path):
+    w = WORKLOADS["llama8b_8k"]
+    heads = range(w.n_kv_heads) if path is None else range(2)
+    check_step(w, [accepted_unit(w, 0, 0, h) for h in heads], path)
+
+
+def test_step_llama8b_32k_one_layer_full_size():
+    """The headline workload's launch configuration: one layer, 8 KV heads x 32768 tokens -> 4096."""
+    w = WORKLOADS["llama8b_32k"]
+    batch = check_step(w, [accepted_unit(w, 5, 0, h) for h in range(w.n_kv_heads)])
+    import torch
+    b2 = run_step(w, [accepted_unit(w, 5, 0, h) for h in range(w.n_kv_heads)])
+    assert torch.equal(batch.K_out.view(torch.int16), b2.K_out.view(torch.int16))     # run-to-run bitwise
+
+
+def test_step_ragged_batch_reduced():
+    """Ragged batch recipe (lengths and rho drawn per sequence) on 5 of the 16 sequences, 2 heads each, capped
+    at 20000 tokens so the oracle finishes in seconds; more than 64 units are covered by the select test."""
+    w = WORKLOADS["ragged16"]
+    lens = unit_lengths(w)
+    accepted = []
+    for s in (0, 3, 7, 11, 15):
+        n = min(lens[s], 20000 + 37 * s)
+        for h in (0, 5):
+            a = accepted_unit(w, 0, s, h, n=n)
+            accepted.append(a)
+    check_step(w, accepted)
+
+
+def test_step_stress_reduced():
+    """Stress recipe (512 query rows, Student-t Values, rho 0.95) at 16384 tokens -> 1024, two heads."""
+    w = WORKLOADS["stress128k"].scaled(length=("fixed", 16384), budget=("fixed", 1024))
+    check_step(w, [accepted_unit(w, 0, 0, h) for h in range(2)])
+
+
+def test_step_stress_full_size_one_head():
+    """131072 tokens -> 8192 with 512 query rows, one KV head, full size."""
+    w = WORKLOADS["stress128k"]
+    check_step(w, [accepted_unit(w, 0, 0, 0)])
+
+
+def test_step_passthrough_and_single_token_units():
+    w = WORKLOADS["tiny"].scaled(n_seq=3)
+    units = [generate_unit(w, 0, 0, 0, n=40), generate_unit(w, 0, 1, 0, n=1), generate_unit(w, 0, 2, 0, n=600)]
+    units[0].budget, units[1].budget, units[2].budget = 64, 1, 600
+    batch = DeviceBatch(units, group=w.group, window=w.window, head_dim=w.head_dim, dtype=w.dtype, n_sink=w.n_sink)
+    batch.kvs.kvs_step(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out, batch.counts, batch.ws,
+                       slot_of_token_out=batch.slot, edge_mask_out=batch.mask, stream=batch.stream())
+    torch_sync()
+    batch.check_guards()
+    Ko, Vo, cnt = from_device(batch.K_out), from_device(batch.V_out), batch.counts.cpu().numpy()
+    for i, u in enumerate(units):
+        r0 = batch.problem.out_rows[i]
+        assert (Ko[r0:r0 + u.n] == u.K).all() and (Vo[r0:r0 + u.n] == u.V).all()
+        assert (cnt[r0:r0 + u.n] == 1).all()
