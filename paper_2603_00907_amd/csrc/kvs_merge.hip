@@ -88,9 +88,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 
     if (run == 0 && mask_t == 0) {
       const int s = sl[t];
-      Ko[(size_t)s * LPR] = kraw;
-      Vo[(size_t)s * LPR] = vraw;
-      if (piece == 0) cnt[s] = 1;
+      if ((unsigned)s < (unsigned)un.n_out) {      // a slot map from outside the library is not trusted
+        Ko[(size_t)s * LPR] = kraw;
+        Vo[(size_t)s * LPR] = vraw;
+        if (piece == 0) cnt[s] = 1;
+      }
     } else {
       float kf[EPL], vf[EPL], rr[EPL];
       Piece<T>::unpack(kraw, kf);
@@ -151,9 +153,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 #pragma unroll
           for (int i = 0; i < EPL; ++i) outk[i] *= inv;
         }
-        Ko[(size_t)out_slot * LPR] = Piece<T>::pack(outk);
-        Vo[(size_t)out_slot * LPR] = Piece<T>::pack(accV);
-        if (piece == 0) cnt[out_slot] = run;
+        if ((unsigned)out_slot < (unsigned)un.n_out) {
+          Ko[(size_t)out_slot * LPR] = Piece<T>::pack(outk);
+          Vo[(size_t)out_slot * LPR] = Piece<T>::pack(accV);
+          if (piece == 0) cnt[out_slot] = run;
+        }
         run = 0;
       } else {
         aprev = alpha_t;

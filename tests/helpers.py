@@ -132,8 +132,8 @@ class DeviceBatch:
         self.Q = to_device(np.stack([u.Q.reshape(group * window, D) for u in units]), dtype)
         tdt = torch_io_dtype(dtype)
         G = self.GUARD
-        self.K_out = torch.full((p.rows_out + G, D), 777.0, dtype=tdt, device="cuda")
-        self.V_out = torch.full((p.rows_out + G, D), 777.0, dtype=tdt, device="cuda")
+        self.K_out = torch.full((p.rows_out + G, D), 512.0, dtype=tdt, device="cuda")
+        self.V_out = torch.full((p.rows_out + G, D), 512.0, dtype=tdt, device="cuda")
         self.counts = torch.full((p.rows_out + G,), -7, dtype=torch.int32, device="cuda")
         self.alpha_bar = torch.full((p.rows_in + G,), -7.0, dtype=torch.float32, device="cuda")
         self.o_bar = torch.full((len(units) + 1, D), -7.0, dtype=torch.float32, device="cuda")
@@ -148,8 +148,8 @@ class DeviceBatch:
 
     def check_guards(self):
         p, G = self.problem, self.GUARD
-        assert (self.K_out[p.rows_out:].float() == 777.0).all()
-        assert (self.V_out[p.rows_out:].float() == 777.0).all()
+        assert (self.K_out[p.rows_out:].float() == 512.0).all()
+        assert (self.V_out[p.rows_out:].float() == 512.0).all()
         assert (self.counts[p.rows_out:] == -7).all()
         assert (self.alpha_bar[p.rows_in:] == -7.0).all()
         assert (self.o_bar[len(self.units):] == -7.0).all()

@@ -127,7 +127,7 @@ def check_select(alphas, budgets, n_sink, n_recent):
     (3000, 700, 32, 0, "uniform"), (32801, 4096, 32, 0, "lognormal"), (32802, 4096, 32, 0, "lognormal"),
     (40000, 10000, 32, 0, "ties"), (131072, 8192, 32, 0, "lognormal"), (50, 50, 32, 0, "dirichlet"),
     (50, 80, 32, 0, "dirichlet"), (34, 33, 32, 0, "dirichlet"), (1, 1, 32, 0, "dirichlet"),
-    (20, 5, 2, 3, "zeros")])
+    (20, 6, 2, 3, "zeros")])
 def test_select_bit_exact(n, budget, s, nr, kind):
     rng = np.random.default_rng(n * 7 + budget)
     if kind == "dirichlet":
