@@ -34,9 +34,10 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(report: bool = False) -> str:
+def build(report: bool = False, defines=(), out: str = LIB) -> str:
     cmd = [hipcc()] + FLAGS + (["-Rpass-analysis=kernel-resource-usage"] if report else [])
-    cmd += ["-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    cmd += ["-D" + d for d in defines]
+    cmd += ["-o", out] + [os.path.join(CSRC, s) for s in SOURCES]
     proc = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in proc.stderr.splitlines() if noise not in l)
@@ -46,7 +47,7 @@ def build(report: bool = False) -> str:
         print(_summarise(err))
     elif err.strip() and "warning" in err:
         sys.stderr.write(err + "\n")
-    return LIB
+    return out
 
 
 def _summarise(text: str) -> str:

@@ -11,8 +11,8 @@
 namespace kvs {
 
 hipError_t launch_score_valu(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
-                             const void* V, float* alpha_bar, const Workspace& ws, hipStream_t stream);
-hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
+                             float* alpha_bar, const Workspace& ws, hipStream_t stream);
+hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
                              float* alpha_bar, const Workspace& ws, hipStream_t stream);
 bool score_mfma_supported(const Shape& sh, kvs_dtype dt);
 
@@ -66,7 +66,7 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
     un.n_chunks = (int)((len + un.chunk_len - 1) / un.chunk_len);
     un.chunk_base = un.m_base = 0;
     un.index = u;
-    un.pad = 0;
+    un.o_base = 0;
     plan->rows_in = std::max(plan->rows_in, un.in_row + len);
     plan->rows_out = std::max(plan->rows_out, un.out_row + (long long)un.n_out);
   }
@@ -142,16 +142,19 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
     UnitTable tab;
     std::memset(&tab, 0, sizeof(tab));
     tab.n_units = std::min(kMaxUnitsPerLaunch, plan.n_units - first);
-    int chunks = 0, mblocks = 0;
+    int chunks = 0, mblocks = 0, ochunks = 0;
     for (int i = 0; i < tab.n_units; ++i) {
       tab.u[i] = plan.units[first + i];
       tab.u[i].chunk_base = chunks;
       tab.u[i].m_base = mblocks;
+      tab.u[i].o_base = ochunks;
+      ochunks += obar_chunks(tab.u[i].len);
       chunks += tab.u[i].n_chunks;
       mblocks += (tab.u[i].len + kMergeTokens - 1) / kMergeTokens;
     }
     tab.total_chunks = chunks;
     tab.total_mblocks = mblocks;
+    tab.total_ochunks = ochunks;
     if (f(tab) != hipSuccess) return KVS_ERR_DEVICE;
   }
   return KVS_OK;
@@ -160,12 +163,12 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
 }  // namespace
 
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
-                        const void* V, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+                        float* alpha_bar, const Workspace& ws, hipStream_t stream) {
   // KVS_SCORE_PATH=valu forces the vector-ALU kernels (used by the tests to cover both paths).
   const char* force = std::getenv("KVS_SCORE_PATH");
   const bool force_valu = force && std::strcmp(force, "valu") == 0;
-  if (!force_valu && score_mfma_supported(sh, dt)) return launch_score_mfma(tab, sh, Q, K, V, alpha_bar, ws, stream);
-  return launch_score_valu(tab, sh, dt, Q, K, V, alpha_bar, ws, stream);
+  if (!force_valu && score_mfma_supported(sh, dt)) return launch_score_mfma(tab, sh, Q, K, alpha_bar, ws, stream);
+  return launch_score_valu(tab, sh, dt, Q, K, alpha_bar, ws, stream);
 }
 
 }  // namespace kvs
@@ -201,9 +204,11 @@ kvs_status kvs_score(const kvs_problem* p, const void* Q, const void* K, const v
   if (st != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab) {
-    hipError_t e = launch_score(tab, plan.shape, plan.dtype, Q, K, V, alpha_bar, w, s);
+    hipError_t e = launch_score(tab, plan.shape, plan.dtype, Q, K, alpha_bar, w, s);
     if (e != hipSuccess) return e;
-    return launch_obar_reduce(tab, plan.shape, w, o_bar, s);
+    e = launch_select_obar(tab, plan.shape, plan.dtype, false, alpha_bar, nullptr, nullptr, V, w.o_part, s);
+    if (e != hipSuccess) return e;
+    return launch_obar_reduce(tab, plan.shape, w.o_part, o_bar, s);
   });
 }
 
@@ -220,7 +225,8 @@ kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar, uint8_t* edg
   if (st != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab) {
-    return launch_select(tab, plan.shape, alpha_bar, edge_mask, slot_of_token, nullptr, nullptr, s);
+    return launch_select_obar(tab, plan.shape, plan.dtype, true, alpha_bar, edge_mask, slot_of_token, nullptr,
+                              nullptr, s);
   });
 }
 
@@ -247,8 +253,8 @@ kvs_status kvs_merge_compact(const kvs_problem* p, const void* K, const void* V,
   if (st != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab) {
-    return launch_merge(tab, plan.shape, plan.dtype, K, V, alpha_bar, o_bar, edge_mask, slot_of_token, K_out,
-                        V_out, counts_out, s);
+    return launch_merge(tab, plan.shape, plan.dtype, K, V, alpha_bar, o_bar, nullptr, edge_mask, slot_of_token,
+                        K_out, V_out, counts_out, s);
   });
 }
 
@@ -277,12 +283,12 @@ kvs_status kvs_step(const kvs_problem* p, const void* Q, const void* K, const vo
   int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab) {
-    hipError_t e = launch_score(tab, plan.shape, plan.dtype, Q, K, V, w.alpha_bar, w, s);
+    hipError_t e = launch_score(tab, plan.shape, plan.dtype, Q, K, w.alpha_bar, w, s);
     if (e != hipSuccess) return e;
-    e = launch_select(tab, plan.shape, w.alpha_bar, mask, slot, &w, w.o_bar, s);   // also reduces o_bar
+    e = launch_select_obar(tab, plan.shape, plan.dtype, true, w.alpha_bar, mask, slot, V, w.o_part, s);
     if (e != hipSuccess) return e;
-    return launch_merge(tab, plan.shape, plan.dtype, K, V, w.alpha_bar, w.o_bar, mask, slot, K_out, V_out,
-                        counts_out, s);
+    return launch_merge(tab, plan.shape, plan.dtype, K, V, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,
+                        V_out, counts_out, s);
   });
 }
 

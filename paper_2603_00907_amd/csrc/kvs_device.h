@@ -11,7 +11,11 @@ namespace kvs {
 constexpr int kMaxUnitsPerLaunch = 64;   // unit descriptors travel by value in the kernel arguments
 constexpr int kMaxChunks = 64;           // token chunks (= score workgroups) per unit
 constexpr int kMinChunkLen = 256;        // tokens
-constexpr int kMergeTokens = 256;     // tokens per merge workgroup
+constexpr int kObarMinChunk = 1024;      // tokens per workgroup of the o_bar pass (at most kMaxChunks per unit)
+#ifndef KVS_MERGE_TOKENS
+#define KVS_MERGE_TOKENS 256
+#endif
+constexpr int kMergeTokens = KVS_MERGE_TOKENS;   // tokens per merge workgroup
 constexpr int kWave = 64;
 
 // One (sequence, KV head).  Rows are in elements of D, not bytes.
@@ -25,14 +29,25 @@ struct Unit {
   int chunk_base;       // chunks of the launch's earlier units
   int m_base;           // merge workgroups (kMergeTokens tokens each) of the launch's earlier units
   int index;            // position of the unit in the caller's problem (indexes Q, o_bar, partials)
-  int pad;
+  int o_base;           // o_bar-pass workgroups of the launch's earlier units
 };
+
+// Chunking of the o_bar pass over V: a function of the unit's length only.
+__host__ __device__ inline int obar_chunk_len(int len) {
+  const int per = (len + kMaxChunks - 1) / kMaxChunks;
+  const int rounded = (per + kWave - 1) / kWave * kWave;
+  return rounded > kObarMinChunk ? rounded : kObarMinChunk;
+}
+__host__ __device__ inline int obar_chunks(int len) {
+  const int cl = obar_chunk_len(len);
+  return (len + cl - 1) / cl;
+}
 
 struct UnitTable {
   int n_units;
   int total_chunks;
   int total_mblocks;
-  int pad0;
+  int total_ochunks;
   Unit u[kMaxUnitsPerLaunch];
 };
 
@@ -47,7 +62,7 @@ struct Shape {
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
   float2* stats_part;   // [n_units][kMaxChunks][R]  (running max, sum) of every chunk, base-2 domain
-  float* o_part;        // [n_units][kMaxChunks][D]  partial o_bar of every chunk
+  float* o_part;        // [n_units][kMaxChunks][D]  partial o_bar of every chunk of the o_bar pass
   float* alpha_bar;     // [rows]    (kvs_step only)
   float* o_bar;         // [n_units][D] (kvs_step only)
   uint8_t* edge_mask;   // [rows]    (kvs_step only, when the caller keeps it internal)
@@ -81,6 +96,15 @@ template <> struct Piece<float> {
     return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
   }
 };
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// two floats -> packed bf16 pair with the hardware converter (v_cvt_pk_bf16_f32, round to nearest even)
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
+  const f32x2_t f = {lo, hi};
+  const bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+  return *reinterpret_cast<const uint32_t*>(&b);
+}
+
 template <> struct Piece<uint16_t> {
   static constexpr int N = 8;
   __device__ __forceinline__ static void unpack(const uint4& r, float* f) {
@@ -88,9 +112,23 @@ template <> struct Piece<uint16_t> {
     f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z); f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
   }
   __device__ __forceinline__ static uint4 pack(const float* f) {
-    return make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
+    return make_uint4(cvt_pk_bf16(f[0], f[1]), cvt_pk_bf16(f[2], f[3]), cvt_pk_bf16(f[4], f[5]), cvt_pk_bf16(f[6], f[7]));
   }
 };
+
+// Sum over the LPR (8, 16 or 32) adjacent lanes that share a row; every lane gets the total.
+// gfx950 has no xor-by-4/8 DPP pattern, but once the four lanes of a quad agree, mirroring a
+// half-row and then a row swaps exactly the partners a butterfly would.
+template <int LPR>
+__device__ __forceinline__ float row_group_sum(float x) {
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));  // row_half_mirror
+  if (LPR >= 16)
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));  // row_mirror
+  if (LPR >= 32) x += __shfl_xor(x, 16, kWave);
+  return x;
+}
 
 // Which unit and which chunk a workgroup of a chunk-indexed launch works on.
 __device__ __forceinline__ int find_unit(const UnitTable& tab, int chunk) {
@@ -100,14 +138,20 @@ __device__ __forceinline__ int find_unit(const UnitTable& tab, int chunk) {
 }
 
 // Launchers (defined next to their kernels).  All enqueue on `stream` and return the launch status.
+// Both score sweeps: chunk statistics, then alpha_bar.
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
-                        const void* V, float* alpha_bar, const Workspace& ws, hipStream_t stream);
-hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const Workspace& ws, float* o_bar,
+                        float* alpha_bar, const Workspace& ws, hipStream_t stream);
+// One launch, two kinds of workgroups: the first `with_select ? n_units : 0` select the edges of one unit
+// each, the others stream one chunk of V each into o_part (skipped when V is null).
+hipError_t launch_select_obar(const UnitTable& tab, const Shape& sh, kvs_dtype dt, bool with_select,
+                              const float* alpha_bar, uint8_t* edge_mask, int32_t* slot, const void* V,
+                              float* o_part, hipStream_t stream);
+// o_bar[u] = sum of the unit's o_part chunks, in chunk order (only when o_bar itself is an output).
+hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float* o_part, float* o_bar,
                               hipStream_t stream);
-hipError_t launch_select(const UnitTable& tab, const Shape& sh, const float* alpha_bar, uint8_t* edge_mask,
-                         int32_t* slot, const Workspace* ws_for_obar, float* o_bar, hipStream_t stream);
+// Exactly one of o_bar (final values) and o_part (chunk sums, added up by every workgroup) is non-null.
 hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* K, const void* V,
-                        const float* alpha_bar, const float* o_bar, const uint8_t* edge_mask,
+                        const float* alpha_bar, const float* o_bar, const float* o_part, const uint8_t* edge_mask,
                         const int32_t* slot, void* K_out, void* V_out, int32_t* counts, hipStream_t stream);
 
 }  // namespace kvs

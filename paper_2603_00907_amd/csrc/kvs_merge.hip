@@ -11,47 +11,90 @@
 //   V_out[S] = sum V[t]                            (Sec. 3.1), counts[S] = t1 - t0 + 1
 // A slot of one token is copied bit for bit.
 //
-// Layout: a row is read by LPR = row_bytes / 16 adjacent lanes (16 bytes each); such a lane group
-// walks a contiguous range of kMergeTokens / groups tokens in order, carrying the open slot's
-// accumulators in registers.  A group starts at the first slot that begins inside its range and
-// runs past the range's end until that last slot is closed, so every slot is summed by exactly
-// one group, in token order: the result does not depend on the launch geometry and needs neither
-// atomics nor a carry between workgroups.  The next token's rows are requested before the current
-// token is processed.
+// Work split.  A workgroup is responsible for the slots that BEGIN in its nominal range of
+// kMergeTokens tokens: its real range [A, B) runs from the first slot start at or after the
+// nominal begin to the first slot start at or after the nominal end, so it owns whole slots and
+// never talks to another workgroup.  [A, B) is cut evenly over the workgroup's lane groups (a
+// lane group = the LPR adjacent lanes that read one row, 16 bytes each).  A group walks its
+// tokens in order with the open slot's accumulators in registers; slots that lie inside the group
+// are written directly, the pieces of a slot that crosses group borders (head / through / tail
+// fragments) go to LDS and are added up, in group order, by the group in which the slot begins.
+// Long runs are therefore summed by many groups in parallel and the result depends only on the
+// edge mask and the launch geometry, never on timing (no atomics).
+// Rows are requested kPrefetch tokens ahead of their use.
 #include "kvs_device.h"
 
 namespace kvs {
 namespace {
 
 constexpr int kThreads = 256;
+#ifndef KVS_MERGE_PREFETCH
+#define KVS_MERGE_PREFETCH 4
+#endif
+constexpr int kPrefetch = KVS_MERGE_PREFETCH;
 
 template <int LPR>
 __device__ __forceinline__ float group_sum(float x) {
+#ifdef KVS_MERGE_NO_DPP
 #pragma unroll
   for (int off = LPR / 2; off >= 1; off >>= 1) x += __shfl_xor(x, off, kWave);
   return x;
+#else
+  return row_group_sum<LPR>(x);
+#endif
+}
+
+// First token t >= from that starts a slot (t == 0 or mask[t-1] == 0); n if there is none.
+// Called by the whole workgroup; sm is 1 + kThreads / kWave ints of scratch.
+__device__ __forceinline__ int first_slot_start(const uint8_t* __restrict__ mk, int from, int n, int* sm) {
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  for (int base = from;; base += kThreads) {
+    const int t = base + tid;
+    const bool start = (t >= n) || (t == 0) || (mk[t - 1] == 0);
+    const uint64_t bal = __ballot(start);
+    if (lane == 0) sm[wave] = bal ? base + wave * kWave + (__ffsll((long long)bal) - 1) : 0x7fffffff;
+    __syncthreads();
+    int best = 0x7fffffff;
+#pragma unroll
+    for (int w = 0; w < kThreads / kWave; ++w) best = min(best, sm[w]);
+    __syncthreads();
+    if (best != 0x7fffffff) return min(best, n);
+  }
 }
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void merge_kernel(
     const UnitTable tab, const Shape sh, const T* __restrict__ K, const T* __restrict__ V,
-    const float* __restrict__ alpha_bar, const float* __restrict__ o_bar, const uint8_t* __restrict__ edge_mask,
-    const int32_t* __restrict__ slot, T* __restrict__ K_out, T* __restrict__ V_out, int32_t* __restrict__ counts) {
+    const float* __restrict__ alpha_bar, const float* __restrict__ o_bar, const float* __restrict__ o_part,
+    const uint8_t* __restrict__ edge_mask, const int32_t* __restrict__ slot, T* __restrict__ K_out,
+    T* __restrict__ V_out, int32_t* __restrict__ counts) {
   constexpr int EPL = Piece<T>::N;
   constexpr int LPR = D / EPL;
   constexpr int GROUPS = kThreads / LPR;
-  constexpr int TPG = kMergeTokens / GROUPS;
+  constexpr int FRAG = 2 * D + 4;           // accK[D], accV[D], U, count, first token, pad
 
-  // which unit: merge workgroups are numbered by m_base
+  __shared__ float sm_frag[GROUPS][2][FRAG];   // [g][0]: head fragment, [g][1]: tail / through fragment
+  __shared__ int sm_flag[GROUPS];              // bit 0: head fragment ends here, 1: through, 2: tail starts here
+  __shared__ int sm_tail_slot[GROUPS];
+  __shared__ int sm_scan[1 + kThreads / kWave];
+  __shared__ float sm_obar[2][D];
+
   int ui = 0;
   while (ui + 1 < tab.n_units && tab.u[ui + 1].m_base <= (int)blockIdx.x) ++ui;
   const Unit un = tab.u[ui];
   const int n = un.len;
   const int tid = threadIdx.x;
   const int group = tid / LPR, piece = tid % LPR;
-  const int a = ((int)blockIdx.x - un.m_base) * kMergeTokens + group * TPG;   // nominal range [a, b)
-  const int b = min(n, a + TPG);
-  if (a >= n) return;
+  const uint8_t* mk = edge_mask + un.in_row;
+
+  const int nom_a = ((int)blockIdx.x - un.m_base) * kMergeTokens;
+  const int nom_b = min(n, nom_a + kMergeTokens);
+  const int A = first_slot_start(mk, nom_a, n, sm_scan);
+  const int B = (nom_b >= n) ? n : first_slot_start(mk, nom_b, n, sm_scan);
+  if (A >= B) return;                          // the whole nominal range lies inside a slot owned earlier
+#if defined(KVS_MERGE_DEBUG_STOP) && KVS_MERGE_DEBUG_STOP == 1
+  return;
+#endif
 
   const uint4* Kp = reinterpret_cast<const uint4*>(K + (size_t)un.in_row * D) + piece;
   const uint4* Vp = reinterpret_cast<const uint4*>(V + (size_t)un.in_row * D) + piece;
@@ -59,117 +102,225 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   uint4* Vo = reinterpret_cast<uint4*>(V_out + (size_t)un.out_row * D) + piece;
   int32_t* cnt = counts + un.out_row;
   const float* al = alpha_bar + un.in_row;
-  const uint8_t* mk = edge_mask + un.in_row;
   const int32_t* sl = slot + un.in_row;
 
   float o[EPL];
+  if (o_bar != nullptr) {
 #pragma unroll
-  for (int i = 0; i < EPL; ++i) o[i] = o_bar[(size_t)un.index * D + piece * EPL + i];
-
-  // first slot that begins inside [a, b)
-  int t = a;
-  while (t < b && t > 0 && mk[t - 1]) ++t;
-  if (t >= b) return;
-
-  float accK[EPL], accV[EPL], kprev[EPL], rprev[EPL];
-  float U = 0.f, pend = 0.f, aprev = 0.f;
-  int run = 0, out_slot = 0;
-
-  uint4 kraw = Kp[(size_t)t * LPR], vraw = Vp[(size_t)t * LPR];
-  float alpha_t = al[t];
-  int mask_t = mk[t];
-
-  while (true) {
-    // request the next token before working on this one (clamped: the last request is discarded)
-    const int tn = min(t + 1, n - 1);
-    const uint4 kraw_n = Kp[(size_t)tn * LPR], vraw_n = Vp[(size_t)tn * LPR];
-    const float alpha_n = al[tn];
-    const int mask_n = mk[tn];
-
-    if (run == 0 && mask_t == 0) {
-      const int s = sl[t];
-      if ((unsigned)s < (unsigned)un.n_out) {      // a slot map from outside the library is not trusted
-        Ko[(size_t)s * LPR] = kraw;
-        Vo[(size_t)s * LPR] = vraw;
-        if (piece == 0) cnt[s] = 1;
-      }
-    } else {
-      float kf[EPL], vf[EPL], rr[EPL];
-      Piece<T>::unpack(kraw, kf);
-      Piece<T>::unpack(vraw, vf);
-      float ss = 0.f, sc = 0.f;
+    for (int i = 0; i < EPL; ++i) o[i] = o_bar[(size_t)un.index * D + piece * EPL + i];
+  } else {
+    // o_bar = sum of the chunk sums of the o_bar pass, in a fixed order: every workgroup gets the same bits
+    const int nc = obar_chunks(un.len);
+    const int half_nc = (nc + 1) / 2;
+    for (int i = tid; i < 2 * D; i += kThreads) {
+      const int d = i % D, h = i / D;
+      float s = 0.f;
+      for (int c = h * half_nc; c < min(nc, (h + 1) * half_nc); ++c)
+        s += o_part[((size_t)un.index * kMaxChunks + c) * D + d];
+      sm_obar[h][d] = s;
+    }
+    __syncthreads();
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        rr[i] = vf[i] - o[i];
-        ss = fmaf(rr[i], rr[i], ss);
+    for (int i = 0; i < EPL; ++i) o[i] = sm_obar[0][piece * EPL + i] + sm_obar[1][piece * EPL + i];
+  }
+
+  // One finished slot -> global memory (all lanes of the group call it together).  `raw_*` are the
+  // untouched rows of the slot's last token: a slot of one token is copied bit for bit.
+  auto finish = [&](int out_slot, const float* accK, const float* accV, float U, int count, int first_tok,
+                    const uint4& raw_k, const uint4& raw_v) {
+    float outk[EPL];
+    if (U > 0.f && U < INFINITY) {
+      const float inv = __builtin_amdgcn_rcpf(U);
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) outk[i] = accK[i] * inv;
+    } else {                                   // no usable weights: arithmetic mean of the run
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) outk[i] = 0.f;
+      for (int j = first_tok; j < first_tok + count; ++j) {
+        float kj[EPL];
+        Piece<T>::unpack(Kp[(size_t)j * LPR], kj);
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) outk[i] += kj[i];
       }
-      if (run > 0) {
+      const float inv = 1.f / (float)count;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) outk[i] *= inv;
+    }
+    uint4 ok = Piece<T>::pack(outk), ov = Piece<T>::pack(accV);
+    if (count == 1) { ok = raw_k; ov = raw_v; }
+    if ((unsigned)out_slot < (unsigned)un.n_out) {   // a slot map from outside the library is not trusted
+      Ko[(size_t)out_slot * LPR] = ok;
+      Vo[(size_t)out_slot * LPR] = ov;
+      if (piece == 0) cnt[out_slot] = count;
+    }
+  };
+  auto store_frag = [&](float* f, const float* accK, const float* accV, float U, int count, int first_tok) {
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      f[piece * EPL + i] = accK[i];
+      f[D + piece * EPL + i] = accV[i];
+    }
+    if (piece == 0) {
+      f[2 * D] = U;
+      f[2 * D + 1] = __int_as_float(count);
+      f[2 * D + 2] = __int_as_float(first_tok);
+    }
+  };
+
+  const int per = (B - A + GROUPS - 1) / GROUPS;
+  const int ga = A + group * per;
+  const int gb = min(B, ga + per);
+  int flags = 0, tail_slot = 0;
+
+  if (ga < gb) {
+    const bool head_open = (ga > A) && (mk[ga - 1] != 0);
+    const bool tail_open = (gb < n) && (mk[gb - 1] != 0);  // for a consistent mask gb < B then
+
+    // rows needed besides the group's own: V[ga-1] for C_{ga-1}, V[gb] for C_{gb-1}
+    uint4 v_before = make_uint4(0, 0, 0, 0), v_after = make_uint4(0, 0, 0, 0);
+    float a_before = 0.f, a_after = 0.f;
+    if (head_open) { v_before = Vp[(size_t)(ga - 1) * LPR]; a_before = al[ga - 1]; }
+    if (tail_open) { v_after = Vp[(size_t)gb * LPR]; a_after = al[gb]; }
+    // slots are numbered consecutively: only the first one is looked up
+    int out_slot = sl[ga];
+
+    uint4 rk[kPrefetch], rv[kPrefetch];
+    float ra[kPrefetch];
+    int rm[kPrefetch];
+#pragma unroll
+    for (int j = 0; j < kPrefetch; ++j) {
+      const int tt = min(ga + j, gb - 1);
+      rk[j] = Kp[(size_t)tt * LPR];
+      rv[j] = Vp[(size_t)tt * LPR];
+      ra[j] = al[tt];
+      rm[j] = mk[tt];
+    }
+
+    // state of the open slot; between slots the accumulators are zero
+    float accK[EPL], accV[EPL], kprev[EPL], rprev[EPL];
+    float U = 0.f, pend = 0.f, aprev = a_before;
+    int count = 0, first_tok = ga;
+    bool cont = head_open;          // the current token continues a slot
+    bool is_head = head_open;       // the open slot began before this group
+    bool own_prev = false;          // the previous token belongs to this group
+    {
+      float vf[EPL];
+      Piece<T>::unpack(v_before, vf);
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) { rprev[i] = vf[i] - o[i]; accK[i] = 0.f; accV[i] = 0.f; kprev[i] = 0.f; }
+    }
+
+    for (int t0 = ga; t0 < gb; t0 += kPrefetch) {
+#pragma unroll
+      for (int j = 0; j < kPrefetch; ++j) {
+        const int t = t0 + j;
+        if (t >= gb) break;
+        const uint4 kraw = rk[j], vraw = rv[j];
+        const float alpha_t = ra[j];
+        const int mask_t = rm[j];
+        {
+          const int tt = min(t + kPrefetch, gb - 1);
+          rk[j] = Kp[(size_t)tt * LPR];
+          rv[j] = Vp[(size_t)tt * LPR];
+          ra[j] = al[tt];
+          rm[j] = mk[tt];
+        }
+        // the same straight-line code for every token: lane groups of a wavefront stay converged
+        float kf[EPL], vf[EPL], rr[EPL];
+        Piece<T>::unpack(kraw, kf);
+        Piece<T>::unpack(vraw, vf);
+        float ss = 0.f, sc = 0.f;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
+          rr[i] = vf[i] - o[i];
+          ss = fmaf(rr[i], rr[i], ss);
           const float p = rprev[i] + rr[i];
           sc = fmaf(p, p, sc);
         }
-      }
-      ss = group_sum<LPR>(ss);
-      sc = group_sum<LPR>(sc);
-      const float A = alpha_t * fabsf(1.f - 2.f * alpha_t) * sqrtf(ss);
-      if (run == 0) {
-        out_slot = sl[t];
-        U = 0.f;
-        pend = A;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) { accK[i] = 0.f; accV[i] = vf[i]; }
-      } else {
-        const float C = aprev * alpha_t * sqrtf(sc);
-        const float u_prev = pend - C;
-        U += u_prev;
-        pend = A - C;
+        ss = group_sum<LPR>(ss);
+        sc = group_sum<LPR>(sc);
+        const float Anorm = alpha_t * fabsf(1.f - 2.f * alpha_t) * __builtin_amdgcn_sqrtf(ss);
+        const float C = cont ? aprev * alpha_t * __builtin_amdgcn_sqrtf(sc) : 0.f;
+        const float w_prev = (cont && own_prev) ? pend - C : 0.f;   // completed weight of token t-1
+        first_tok = cont ? first_tok : t;
+        U += w_prev;
+        pend = Anorm - C;
+        ++count;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
-          accK[i] = fmaf(u_prev, kprev[i], accK[i]);
+          accK[i] = fmaf(w_prev, kprev[i], accK[i]);
           accV[i] += vf[i];
+          kprev[i] = kf[i];
+          rprev[i] = rr[i];
         }
-      }
-      ++run;
-      if (mask_t == 0) {               // the slot ends here
-        U += pend;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) accK[i] = fmaf(pend, kf[i], accK[i]);
-        float outk[EPL];
-        if (U > 0.f && U < INFINITY) {
-          const float inv = 1.f / U;
-#pragma unroll
-          for (int i = 0; i < EPL; ++i) outk[i] = accK[i] * inv;
-        } else {                       // no usable weights: arithmetic mean of the run
-#pragma unroll
-          for (int i = 0; i < EPL; ++i) outk[i] = 0.f;
-          for (int j = t - run + 1; j <= t; ++j) {
-            float kj[EPL];
-            Piece<T>::unpack(Kp[(size_t)j * LPR], kj);
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) outk[i] += kj[i];
-          }
-          const float inv = 1.f / (float)run;
-#pragma unroll
-          for (int i = 0; i < EPL; ++i) outk[i] *= inv;
-        }
-        if ((unsigned)out_slot < (unsigned)un.n_out) {
-          Ko[(size_t)out_slot * LPR] = Piece<T>::pack(outk);
-          Vo[(size_t)out_slot * LPR] = Piece<T>::pack(accV);
-          if (piece == 0) cnt[out_slot] = run;
-        }
-        run = 0;
-      } else {
         aprev = alpha_t;
+        own_prev = true;
+        cont = (mask_t != 0);
+        if (!cont) {                               // the slot ends at t
+          U += pend;
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) { kprev[i] = kf[i]; rprev[i] = rr[i]; }
+          for (int i = 0; i < EPL; ++i) accK[i] = fmaf(pend, kf[i], accK[i]);
+          if (is_head) {
+            store_frag(sm_frag[group][0], accK, accV, U, count, first_tok);
+            flags |= 1;
+            is_head = false;
+          } else {
+            finish(out_slot, accK, accV, U, count, first_tok, kraw, vraw);
+          }
+          ++out_slot;
+          U = 0.f;
+          count = 0;
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) { accK[i] = 0.f; accV[i] = 0.f; }
+        }
       }
     }
+    if (cont) {                                    // the last token's weight still lacks C_{gb-1}
+      float vf[EPL];
+      Piece<T>::unpack(v_after, vf);
+      float sc = 0.f;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        const float p = rprev[i] + (vf[i] - o[i]);
+        sc = fmaf(p, p, sc);
+      }
+      sc = group_sum<LPR>(sc);
+      const float u_prev = pend - aprev * a_after * __builtin_amdgcn_sqrtf(sc);
+      U += u_prev;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) accK[i] = fmaf(u_prev, kprev[i], accK[i]);
+      store_frag(sm_frag[group][1], accK, accV, U, count, first_tok);
+      if (is_head) {
+        flags |= 2;                                // the whole group lies inside one slot
+      } else {
+        flags |= 4;                                // the slot began in this group
+        tail_slot = out_slot;
+      }
+    }
+  }
+  if (piece == 0) { sm_flag[group] = flags; sm_tail_slot[group] = tail_slot; }
+  __syncthreads();
 
-    const bool slot_closed = (mask_t == 0);
-    ++t;
-    if (t >= n || (t >= b && slot_closed)) break;
-    kraw = kraw_n; vraw = vraw_n; alpha_t = alpha_n; mask_t = mask_n;
+  if (flags & 4) {
+    // this group owns a slot that continues in later groups: add their fragments in group order
+    float accK[EPL], accV[EPL];
+    const float* f = sm_frag[group][1];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) { accK[i] = f[piece * EPL + i]; accV[i] = f[D + piece * EPL + i]; }
+    float U = f[2 * D];
+    int count = __float_as_int(f[2 * D + 1]);
+    const int first_tok = __float_as_int(f[2 * D + 2]);
+    for (int g = group + 1; g < GROUPS; ++g) {
+      const int fl = sm_flag[g];
+      const float* h = sm_frag[g][(fl & 2) ? 1 : 0];
+      if (!(fl & 3)) break;                        // cannot happen for a consistent mask
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) { accK[i] += h[piece * EPL + i]; accV[i] += h[D + piece * EPL + i]; }
+      U += h[2 * D];
+      count += __float_as_int(h[2 * D + 1]);
+      if (fl & 1) break;                           // the slot ended in group g
+    }
+    finish(tail_slot, accK, accV, U, count, first_tok, make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0));
   }
 }
 
@@ -177,25 +328,26 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 
 template <typename T, int D>
 static hipError_t launch_merge_t(const UnitTable& tab, const Shape& sh, const void* K, const void* V,
-                                 const float* alpha_bar, const float* o_bar, const uint8_t* edge_mask,
-                                 const int32_t* slot, void* K_out, void* V_out, int32_t* counts,
-                                 hipStream_t stream) {
+                                 const float* alpha_bar, const float* o_bar, const float* o_part,
+                                 const uint8_t* edge_mask, const int32_t* slot, void* K_out, void* V_out,
+                                 int32_t* counts, hipStream_t stream) {
   hipLaunchKernelGGL((merge_kernel<T, D>), dim3(tab.total_mblocks), dim3(kThreads), 0, stream, tab, sh,
-                     (const T*)K, (const T*)V, alpha_bar, o_bar, edge_mask, slot, (T*)K_out, (T*)V_out, counts);
+                     (const T*)K, (const T*)V, alpha_bar, o_bar, o_part, edge_mask, slot, (T*)K_out, (T*)V_out,
+                     counts);
   return hipGetLastError();
 }
 
 hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* K, const void* V,
-                        const float* alpha_bar, const float* o_bar, const uint8_t* edge_mask,
+                        const float* alpha_bar, const float* o_bar, const float* o_part, const uint8_t* edge_mask,
                         const int32_t* slot, void* K_out, void* V_out, int32_t* counts, hipStream_t stream) {
   if (dt == KVS_F32) {
     return sh.D == 64
-               ? launch_merge_t<float, 64>(tab, sh, K, V, alpha_bar, o_bar, edge_mask, slot, K_out, V_out, counts, stream)
-               : launch_merge_t<float, 128>(tab, sh, K, V, alpha_bar, o_bar, edge_mask, slot, K_out, V_out, counts, stream);
+               ? launch_merge_t<float, 64>(tab, sh, K, V, alpha_bar, o_bar, o_part, edge_mask, slot, K_out, V_out, counts, stream)
+               : launch_merge_t<float, 128>(tab, sh, K, V, alpha_bar, o_bar, o_part, edge_mask, slot, K_out, V_out, counts, stream);
   }
   return sh.D == 64
-             ? launch_merge_t<uint16_t, 64>(tab, sh, K, V, alpha_bar, o_bar, edge_mask, slot, K_out, V_out, counts, stream)
-             : launch_merge_t<uint16_t, 128>(tab, sh, K, V, alpha_bar, o_bar, edge_mask, slot, K_out, V_out, counts, stream);
+             ? launch_merge_t<uint16_t, 64>(tab, sh, K, V, alpha_bar, o_bar, o_part, edge_mask, slot, K_out, V_out, counts, stream)
+             : launch_merge_t<uint16_t, 128>(tab, sh, K, V, alpha_bar, o_bar, o_part, edge_mask, slot, K_out, V_out, counts, stream);
 }
 
 }  // namespace kvs

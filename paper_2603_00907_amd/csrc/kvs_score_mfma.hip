@@ -1,20 +1,27 @@
 // Score kernels, MFMA path: bf16 inputs, query windows of at least 16 rows.
 //
-// Same two sweeps as the vector-ALU path (Sec. 4.1, Eq. attn_def_vec: logits, softmax over all
-// cached Keys, here averaged over the unit's query rows): sweep 0 leaves per-chunk softmax
-// statistics, sweep 1 recomputes the logits, writes alpha_bar and the chunk's share of o_bar.
+// Two sweeps over K (Sec. 4.1, Eq. attn_def_vec: logits, softmax over all cached Keys, here
+// averaged over the unit's query rows): sweep 0 leaves per-chunk softmax statistics (running
+// maximum and sum of exponentials, base-2 domain), sweep 1 recomputes the logits, normalises them
+// with the unit-wide statistics and writes alpha_bar.  (o_bar is accumulated by a separate
+// streaming pass over V, see kvs_select.hip.)
 //
 // The logit tile is computed transposed, S^T[token, query] = K_tile * Q^T, with
 // v_mfma_f32_32x32x16_bf16: the A operand is a 32-token tile of K, the B operand a block of
 // 32 query rows.  The Q block of a wavefront (32*NT rows, NT <= 4) stays in registers for the whole
-// sweep; K streams from HBM in coalesced 16-byte loads (16 lanes per 256-byte row), is staged in a
-// wavefront-private, padded LDS region and read back in the operand layout.  In the accumulator
-// a lane holds ONE query column and 16 token rows, so the running softmax statistics are
-// lane-private (NT pairs per lane) and need no cross-lane traffic inside the loop; the sum over
-// queries of sweep 1 is a 16-value reduce-scatter over 32 lanes (16 shuffles per tile).
+// sweep.  K streams from HBM straight into LDS (global_load_lds_dwordx4: 16 lanes fetch one
+// 256-byte row, every instruction four whole rows) into a wavefront-private 8 KB tile; the 16-byte
+// pieces of a row are stored XOR-swizzled by the row number so that the operand reads
+// (ds_read_b128, 32 rows at the same piece) spread over all banks.  Once the operands of a tile
+// sit in registers the same LDS tile is refilled with the wavefront's next tile, which flies while
+// the MFMAs and the softmax arithmetic of the current tile run; wavefronts never wait for each
+// other inside the sweep.  In the accumulator a lane holds ONE query column and 16 token rows, so
+// the running softmax statistics are lane-private (NT pairs per lane); the sum over queries of
+// sweep 1 is a 16-value reduce-scatter over 32 lanes (16 shuffles per tile).
 //
-// A workgroup has four wavefronts: WQ of them split the query rows (32*NT each), 4 / WQ split the
-// chunk's 32-token tiles.  More than 128 * WQ query rows are handled in passes.
+// A workgroup has four wavefronts.  Up to 128 query rows every wavefront holds all of them (WQ = 1)
+// and the four split the chunk's tiles.  Above that, WQ of them split the query rows of a pass
+// and share tiles; then alpha_bar is combined through LDS with a workgroup barrier per tile.
 #include "kvs_device.h"
 
 namespace kvs {
@@ -29,25 +36,26 @@ constexpr int kTile = 32;                 // tokens per MFMA tile
 
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+#define KVS_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define KVS_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
 template <int D, int NT, int WQ, int PHASE>
-__global__ __launch_bounds__(kThreads) void score_mfma_kernel(
+__global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
-    const uint16_t* __restrict__ V, float* __restrict__ alpha_bar, float2* __restrict__ stats_part,
-    float* __restrict__ o_part) {
+    float* __restrict__ alpha_bar, float2* __restrict__ stats_part) {
   constexpr int WT = kWaves / WQ;           // wavefronts that split the tiles
   constexpr int KS = D / 16;                // MFMA k-steps per tile
-  constexpr int LPR = D / 8;                // lanes per row when staging (16 bytes each)
-  constexpr int RPI = kWave / LPR;          // rows per staging load instruction
-  constexpr int NLD = kTile / RPI;          // staging loads per tile
-  constexpr int STRIDE = D * 2 + 16;        // padded LDS row, bytes
+  constexpr int LPR = D / 8;                // 16-byte pieces (= lanes) per row
+  constexpr int RPI = kWave / LPR;          // rows per load instruction
+  constexpr int NLD = kTile / RPI;          // load instructions per tile
+  constexpr int ROWB = D * 2;               // bytes per row
   constexpr int QROWS = 32 * NT;            // query rows per wavefront
   constexpr int PASS_ROWS = QROWS * WQ;
 
-  __shared__ __attribute__((aligned(16))) unsigned char sm_k[kWaves][kTile * STRIDE];
+  __shared__ __attribute__((aligned(1024))) unsigned char sm_k[kWaves][kTile * ROWB];
   __shared__ float sm_c[KVS_MAX_Q_ROWS];
   __shared__ float2 sm_stats[kWaves][QROWS];
   __shared__ float sm_alpha[kWaves][kTile];
-  __shared__ float sm_o[kWaves][D];
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -64,10 +72,22 @@ __global__ __launch_bounds__(kThreads) void score_mfma_kernel(
   const size_t part_base = (size_t)un.index * kMaxChunks;
 
   const uint4* Kg = reinterpret_cast<const uint4*>(K + (size_t)un.in_row * D);
-  const uint4* Vg = reinterpret_cast<const uint4*>(V + (size_t)un.in_row * D);
   const uint16_t* Qu = Q + (size_t)un.index * R * D;
   unsigned char* my_k = sm_k[wave];
-  const int st_row = lane / LPR, st_piece = lane % LPR;
+  // staging: lane -> (row within the instruction's block of RPI rows, LDS slot); the piece fetched
+  // into slot s of row r is s ^ (r % LPR)
+  const int st_row = lane / LPR, st_slot = lane % LPR;
+
+  auto issue_tile = [&](int j) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int row = st_row + i * RPI;
+      const int t = max(t0, min(t0 + j * kTile + row, t1 - 1));
+      const int piece = st_slot ^ (row % LPR);
+      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(Kg + (size_t)t * LPR + piece), KVS_LDS_PTR(my_k + i * 1024),
+                                       16, 0, 0);
+    }
+  };
 
   if (PHASE == 1) {
     for (int q = tid; q < R; q += kThreads) {
@@ -83,13 +103,10 @@ __global__ __launch_bounds__(kThreads) void score_mfma_kernel(
     __syncthreads();
   }
 
-  float o_acc[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) o_acc[i] = 0.f;
-
   for (int qp = 0; qp < R; qp += PASS_ROWS) {
     const bool first_pass = (qp == 0);
-    const bool last_pass = (qp + PASS_ROWS >= R);
+
+    issue_tile(wt);                           // flies while the Q block is fetched
 
     // this wavefront's block of query rows, kept in registers as MFMA B operands
     bf16x8 bq[NT][KS];
@@ -111,44 +128,23 @@ __global__ __launch_bounds__(kThreads) void score_mfma_kernel(
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) { m_run[nt] = -INFINITY; l_run[nt] = 0.f; }
 
-    // stage the first tile
-    uint4 kreg[NLD];
-    {
-      const int j = wt;
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const int t = min(t0 + j * kTile + st_row + i * RPI, t1 - 1);
-        kreg[i] = Kg[(size_t)t * LPR + st_piece];
-      }
-    }
-
     for (int it = 0; it < iters; ++it) {
       const int j = it * WT + wt;                   // tile index inside the chunk
       const int tile_t0 = t0 + j * kTile;
       const int nvalid = min(kTile, t1 - tile_t0);  // <= 0: this wavefront has no tile in this round
 
-      // registers -> LDS (operand staging), then request the next tile and this tile's V rows
+      // wait for the tile, pull its operands into registers, hand the LDS tile to the next load
+      __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
+      asm volatile("" ::: "memory");
+      bf16x8 a[KS];
 #pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        *reinterpret_cast<uint4*>(my_k + (st_row + i * RPI) * STRIDE + st_piece * 16) = kreg[i];
+      for (int kk = 0; kk < KS; ++kk) {
+        const int slot = (2 * kk + half) ^ (col % LPR);
+        a[kk] = *reinterpret_cast<const bf16x8*>(my_k + col * ROWB + slot * 16);
       }
-      __syncthreads();
-      {
-        const int jn = j + WT;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          const int t = max(t0, min(t0 + jn * kTile + st_row + i * RPI, t1 - 1));
-          kreg[i] = Kg[(size_t)t * LPR + st_piece];
-        }
-      }
-      uint4 vreg[NLD];
-      if (PHASE == 1 && last_pass && wq == 0) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          const int t = max(t0, min(tile_t0 + st_row + i * RPI, t1 - 1));
-          vreg[i] = Vg[(size_t)t * LPR + st_piece];
-        }
-      }
+      __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0): operands have left LDS
+      asm volatile("" ::: "memory");
+      if (it + 1 < iters) issue_tile(j + WT);
 
       // S^T tile = K_tile (32 x D) * Q_block^T (D x 32*NT)
       f32x16 acc[NT];
@@ -159,10 +155,9 @@ __global__ __launch_bounds__(kThreads) void score_mfma_kernel(
       }
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(my_k + col * STRIDE + (kk * 16 + 8 * half) * 2);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[nt][kk], acc[nt], 0, 0, 0);
+          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bq[nt][kk], acc[nt], 0, 0, 0);
         }
       }
       // accumulator element v of a lane: token row 8*(v/4) + 4*half + v%4, query column `col`
@@ -231,35 +226,28 @@ __global__ __launch_bounds__(kThreads) void score_mfma_kernel(
         p[0] += __shfl_xor(p[0], 1, kWave);
         const int v = (lane >> 1) & 15;
         const int row = 8 * (v / 4) + 4 * half + (v % 4);
-        if ((lane & 1) == 0) sm_alpha[wave][row] = p[0];
-        __syncthreads();
-        if (wq == 0) {
-          // rows of this tile: sum over the WQ wavefronts that share it, then over earlier passes
-          float a_tok = 0.f;
-          if (lane < kTile) {
+        float a_tok = p[0];
+        if (WQ > 1) {
+          // the WQ wavefronts that share this tile add their query blocks up through LDS
+          if ((lane & 1) == 0) sm_alpha[wave][row] = a_tok;
+          __syncthreads();
+          if (wq == 0 && lane < kTile) {
+            a_tok = 0.f;
 #pragma unroll
             for (int w = 0; w < WQ; ++w) a_tok += sm_alpha[wave + w][lane];
             if (lane < nvalid) {
               float* dst = alpha_bar + un.in_row + tile_t0 + lane;
               if (!first_pass) a_tok += *dst;
               *dst = a_tok;
-            } else {
-              a_tok = 0.f;
             }
           }
-          if (last_pass) {
-#pragma unroll
-            for (int i = 0; i < NLD; ++i) {
-              const float a_row = __shfl(a_tok, st_row + i * RPI, kWave);
-              float vf[8];
-              Piece<uint16_t>::unpack(vreg[i], vf);
-#pragma unroll
-              for (int e = 0; e < 8; ++e) o_acc[e] = fmaf(a_row, vf[e], o_acc[e]);
-            }
-          }
+          __syncthreads();
+        } else if ((lane & 1) == 0 && row < nvalid) {
+          float* dst = alpha_bar + un.in_row + tile_t0 + row;
+          if (!first_pass) a_tok += *dst;
+          *dst = a_tok;
         }
       }
-      __syncthreads();   // the LDS staging region and sm_alpha are rewritten in the next round
     }
 
     if (PHASE == 0) {
@@ -294,59 +282,40 @@ __global__ __launch_bounds__(kThreads) void score_mfma_kernel(
       __syncthreads();
     }
   }
-
-  if (PHASE == 1) {
-    // chunk share of o_bar: lanes with the same 16-byte piece, then the wavefronts
-#pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o_acc[e] += __shfl_xor(o_acc[e], off, kWave);
-    }
-    if (st_row == 0) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) sm_o[wave][st_piece * 8 + e] = o_acc[e];
-    }
-    __syncthreads();
-    for (int d = tid; d < D; d += kThreads) {
-      float s = 0.f;
-      for (int w = 0; w < kWaves; ++w) s += sm_o[w][d];
-      o_part[(part_base + chunk) * D + d] = s;
-    }
-  }
 }
 
 template <int D, int NT, int WQ>
-hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
-                    float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
+                    const Workspace& ws, hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
   hipLaunchKernelGGL((score_mfma_kernel<D, NT, WQ, 0>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, (const uint16_t*)V, alpha_bar, ws.stats_part, ws.o_part);
+                     (const uint16_t*)K, alpha_bar, ws.stats_part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((score_mfma_kernel<D, NT, WQ, 1>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, (const uint16_t*)V, alpha_bar, ws.stats_part, ws.o_part);
+                     (const uint16_t*)K, alpha_bar, ws.stats_part);
   return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
-                    float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
+                    const Workspace& ws, hipStream_t stream) {
   const int R = sh.R;
-  if (R <= 32) return launch_t<D, 1, 1>(tab, sh, Q, K, V, alpha_bar, ws, stream);
-  if (R <= 64) return launch_t<D, 2, 1>(tab, sh, Q, K, V, alpha_bar, ws, stream);
-  if (R <= 128) return launch_t<D, 4, 1>(tab, sh, Q, K, V, alpha_bar, ws, stream);
-  if (R <= 256) return launch_t<D, 4, 2>(tab, sh, Q, K, V, alpha_bar, ws, stream);
-  return launch_t<D, 4, 4>(tab, sh, Q, K, V, alpha_bar, ws, stream);
+  if (R <= 32) return launch_t<D, 1, 1>(tab, sh, Q, K, alpha_bar, ws, stream);
+  if (R <= 64) return launch_t<D, 2, 1>(tab, sh, Q, K, alpha_bar, ws, stream);
+  if (R <= 128) return launch_t<D, 4, 1>(tab, sh, Q, K, alpha_bar, ws, stream);
+  if (R <= 256) return launch_t<D, 4, 2>(tab, sh, Q, K, alpha_bar, ws, stream);
+  return launch_t<D, 4, 4>(tab, sh, Q, K, alpha_bar, ws, stream);
 }
 
 }  // namespace
 
 bool score_mfma_supported(const Shape& sh, kvs_dtype dt) { return dt == KVS_BF16 && sh.R >= 16; }
 
-hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
-                             float* alpha_bar, const Workspace& ws, hipStream_t stream) {
-  return sh.D == 64 ? launch_d<64>(tab, sh, Q, K, V, alpha_bar, ws, stream)
-                    : launch_d<128>(tab, sh, Q, K, V, alpha_bar, ws, stream);
+hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
+                             const Workspace& ws, hipStream_t stream) {
+  return sh.D == 64 ? launch_d<64>(tab, sh, Q, K, alpha_bar, ws, stream)
+                    : launch_d<128>(tab, sh, Q, K, alpha_bar, ws, stream);
 }
 
 }  // namespace kvs

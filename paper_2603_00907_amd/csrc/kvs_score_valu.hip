@@ -2,14 +2,14 @@
 //
 // Computes, per unit, the attention of every query row over all cached Keys (Sec. 4.1, Eq.
 // attn_def_vec) in two sweeps over K: sweep 0 leaves the softmax statistics (running maximum and
-// sum of exponentials) of every token chunk; sweep 1 recomputes the logits, normalises them with
-// the unit-wide statistics, averages over the query rows into alpha_bar and accumulates the
-// chunk's share of o_bar = sum_t alpha_bar[t] V[t].
+// sum of exponentials, base-2 domain) of every token chunk; sweep 1 recomputes the logits,
+// normalises them with the unit-wide statistics and averages over the query rows into alpha_bar.
+// (o_bar is accumulated by a separate streaming pass over V, see kvs_select.hip.)
 //
-// Layout: a row of K or V is read by LPR = row_bytes / 16 adjacent lanes, 16 bytes each, so one
+// Layout: a row of K is read by LPR = row_bytes / 16 adjacent lanes, 16 bytes each, so one
 // wavefront load instruction fetches 64 / LPR whole rows.  Dot products are reduced across the
-// LPR lanes with xor shuffles.  This is the path for query windows below 16 rows and for fp32
-// inputs; the bf16 MFMA path lives in kvs_score_mfma.hip.
+// LPR lanes with DPP adds.  This is the path for query windows below 16 rows and for fp32 inputs;
+// the bf16 MFMA path lives in kvs_score_mfma.hip.
 #include "kvs_device.h"
 
 namespace kvs {
@@ -18,18 +18,10 @@ namespace {
 constexpr int kQB = 8;          // query rows held in registers at a time
 constexpr int kThreads = 256;
 
-template <int LPR>
-__device__ __forceinline__ float group_sum(float x) {
-#pragma unroll
-  for (int off = LPR / 2; off >= 1; off >>= 1) x += __shfl_xor(x, off, kWave);
-  return x;
-}
-
 template <typename T, int D, int PHASE>
 __global__ __launch_bounds__(kThreads) void score_valu_kernel(
     const UnitTable tab, const Shape sh, const T* __restrict__ Q, const T* __restrict__ K,
-    const T* __restrict__ V, float* __restrict__ alpha_bar, float2* __restrict__ stats_part,
-    float* __restrict__ o_part) {
+    float* __restrict__ alpha_bar, float2* __restrict__ stats_part) {
   constexpr int EPL = Piece<T>::N;          // elements per lane
   constexpr int LPR = D / EPL;              // lanes per row
   constexpr int RPW = kWave / LPR;          // rows per wavefront load
@@ -37,7 +29,6 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
 
   __shared__ float2 sm_stats[(kThreads / kWave) * RPW][kQB];
   __shared__ float sm_c[KVS_MAX_Q_ROWS];
-  __shared__ float sm_o[kThreads / kWave][D];
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -50,7 +41,6 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
   const size_t part_base = ((size_t)un.index * kMaxChunks);
 
   const uint4* Kp = reinterpret_cast<const uint4*>(K + (size_t)un.in_row * D) + piece;
-  const uint4* Vp = reinterpret_cast<const uint4*>(V + (size_t)un.in_row * D) + piece;
   const uint4* Qp = reinterpret_cast<const uint4*>(Q + (size_t)un.index * R * D) + piece;
 
   if (PHASE == 1) {
@@ -67,10 +57,6 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
     }
     __syncthreads();
   }
-
-  float o_acc[EPL];
-#pragma unroll
-  for (int i = 0; i < EPL; ++i) o_acc[i] = 0.f;
 
   for (int qb = 0; qb < R; qb += kQB) {
     float qf[kQB][EPL];
@@ -90,7 +76,6 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
     float m[kQB], l[kQB];
 #pragma unroll
     for (int j = 0; j < kQB; ++j) { m[j] = -INFINITY; l[j] = 0.f; }
-    const bool last_qb = (qb + kQB >= R);
 
     for (int t = t0 + wave * RPW + grp; t < t1; t += RPB) {
       float kf[EPL];
@@ -101,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
         float d = 0.f;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) d = fmaf(qf[j][i], kf[i], d);
-        const float s = group_sum<LPR>(d) * sh.scale_log2;
+        const float s = row_group_sum<LPR>(d) * sh.scale_log2;
         if (PHASE == 0) {
           if (s > m[j]) {
             l[j] = l[j] * __builtin_amdgcn_exp2f(m[j] - s) + 1.f;
@@ -113,20 +98,10 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
           a += __builtin_amdgcn_exp2f(s - cq[j]);
         }
       }
-      if (PHASE == 1) {
+      if (PHASE == 1 && piece == 0) {
         // the lane that owns the row keeps its running sum over the blocks of query rows
-        float acc = a;
-        if (piece == 0) {
-          if (qb != 0) acc += alpha_bar[un.in_row + t];
-          alpha_bar[un.in_row + t] = acc;
-        }
-        if (last_qb) {
-          acc = __shfl(acc, grp * LPR, kWave);
-          float vf[EPL];
-          Piece<T>::unpack(Vp[(size_t)t * LPR], vf);
-#pragma unroll
-          for (int i = 0; i < EPL; ++i) o_acc[i] = fmaf(acc, vf[i], o_acc[i]);
-        }
+        if (qb != 0) a += alpha_bar[un.in_row + t];
+        alpha_bar[un.in_row + t] = a;
       }
     }
 
@@ -149,68 +124,31 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
       __syncthreads();
     }
   }
-
-  if (PHASE == 1) {
-    // chunk share of o_bar: lanes holding the same piece of the row, then the four wavefronts
-#pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1) {
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) o_acc[i] += __shfl_xor(o_acc[i], off, kWave);
-    }
-    if (grp == 0) {
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) sm_o[wave][piece * EPL + i] = o_acc[i];
-    }
-    __syncthreads();
-    for (int d = tid; d < D; d += kThreads) {
-      float s = 0.f;
-      for (int w = 0; w < kThreads / kWave; ++w) s += sm_o[w][d];
-      o_part[(part_base + chunk) * D + d] = s;
-    }
-  }
 }
 
 }  // namespace
 
 template <typename T, int D>
 static hipError_t launch_score_valu_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                                      const void* V, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+                                      float* alpha_bar, const Workspace& ws, hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
   hipLaunchKernelGGL((score_valu_kernel<T, D, 0>), grid, block, 0, stream, tab, sh, (const T*)Q, (const T*)K,
-                     (const T*)V, alpha_bar, ws.stats_part, ws.o_part);
+                     alpha_bar, ws.stats_part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((score_valu_kernel<T, D, 1>), grid, block, 0, stream, tab, sh, (const T*)Q, (const T*)K,
-                     (const T*)V, alpha_bar, ws.stats_part, ws.o_part);
+                     alpha_bar, ws.stats_part);
   return hipGetLastError();
 }
 
 hipError_t launch_score_valu(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
-                             const void* V, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+                             float* alpha_bar, const Workspace& ws, hipStream_t stream) {
   if (dt == KVS_F32) {
-    return sh.D == 64 ? launch_score_valu_t<float, 64>(tab, sh, Q, K, V, alpha_bar, ws, stream)
-                      : launch_score_valu_t<float, 128>(tab, sh, Q, K, V, alpha_bar, ws, stream);
+    return sh.D == 64 ? launch_score_valu_t<float, 64>(tab, sh, Q, K, alpha_bar, ws, stream)
+                      : launch_score_valu_t<float, 128>(tab, sh, Q, K, alpha_bar, ws, stream);
   }
-  return sh.D == 64 ? launch_score_valu_t<uint16_t, 64>(tab, sh, Q, K, V, alpha_bar, ws, stream)
-                    : launch_score_valu_t<uint16_t, 128>(tab, sh, Q, K, V, alpha_bar, ws, stream);
-}
-
-// ---------------------------------------------------------------------------------------------
-// o_bar[u][d] = sum over the unit's chunks of the partial sums, in chunk order.
-__global__ void obar_reduce_kernel(const UnitTable tab, const Shape sh, const float* __restrict__ o_part,
-                                   float* __restrict__ o_bar) {
-  const Unit un = tab.u[blockIdx.x];
-  for (int d = threadIdx.x; d < sh.D; d += blockDim.x) {
-    float s = 0.f;
-    for (int c = 0; c < un.n_chunks; ++c) s += o_part[((size_t)un.index * kMaxChunks + c) * sh.D + d];
-    o_bar[(size_t)un.index * sh.D + d] = s;
-  }
-}
-
-hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const Workspace& ws, float* o_bar,
-                              hipStream_t stream) {
-  hipLaunchKernelGGL(obar_reduce_kernel, dim3(tab.n_units), dim3(128), 0, stream, tab, sh, ws.o_part, o_bar);
-  return hipGetLastError();
+  return sh.D == 64 ? launch_score_valu_t<uint16_t, 64>(tab, sh, Q, K, alpha_bar, ws, stream)
+                    : launch_score_valu_t<uint16_t, 128>(tab, sh, Q, K, alpha_bar, ws, stream);
 }
 
 }  // namespace kvs

@@ -1,18 +1,25 @@
-// Select kernel: which adjacent pairs merge, and the slot of every token.
+// Select kernel (which adjacent pairs merge, and the slot of every token) and the o_bar pass,
+// in ONE launch: both need nothing but alpha_bar, so the few select workgroups (one per unit,
+// latency-bound) run beside the many streaming workgroups that read V once for
+// o_bar = sum_t alpha_bar[t] V[t] (Sec. 4.1, Eq. attn_def_vec, with the window's mean distribution).
 //
-// Per unit: edge score sigma[m] = alpha_bar[m] + alpha_bar[m+1] for the eligible edges
+// Select, per unit: edge score sigma[m] = alpha_bar[m] + alpha_bar[m+1] for the eligible edges
 // n_sink <= m <= len-2-n_recent (App. C, paragraph (i): pairs with small accumulated attention
 // mass; Sec. 5: the first tokens are always preserved); the r = len - budget smallest scores are
 // selected in one parallel step (Sec. 3.1), ties going to the lower index; consecutive selected
-// edges chain into one output slot.
+// edges chain into one output slot.  One workgroup of 1024 threads per unit.  Scores are
+// non-negative floats, so their bit patterns order like unsigned integers: an MSB-first radix
+// select (11 + 11 + 10 bits, LDS histograms) finds the r-th smallest key T and how many keys equal
+// to T are still wanted; a final pass in index order takes every key below T and the first `want`
+// keys equal to T, and turns the selection into the slot map with wavefront ballots and a scan
+// over the 16 wavefronts.  Keys of units up to kLdsKeys edges are kept in LDS between the passes;
+// longer units recompute them from alpha_bar (L2-resident).
 //
-// One workgroup of 1024 threads per unit.  Scores are non-negative floats, so their bit patterns
-// order like unsigned integers: an MSB-first radix select (11 + 11 + 10 bits, LDS histograms)
-// finds the r-th smallest key T and how many keys equal to T are still wanted; a final pass in
-// index order takes every key below T and the first `want` keys equal to T, and turns the
-// selection into the slot map with wavefront ballots and a scan over the 16 wavefronts.  Keys of
-// units up to kLdsKeys edges are kept in LDS between the passes; longer units recompute them from
-// alpha_bar (L2-resident).
+// o_bar pass, per chunk of a unit: rows of V are read by LPR adjacent lanes (16 bytes each), scaled
+// by alpha_bar[t] and summed per lane, then over the workgroup; the chunk's sum goes to the
+// workspace; whoever needs o_bar (every merge workgroup, or a tiny reduce kernel when o_bar itself
+// is an output) adds the chunks up in chunk order, so the result does not depend on timing and no
+// device-wide fence is needed (one costs a whole L2 write-back on this chip).
 #include "kvs_device.h"
 
 namespace kvs {
@@ -31,30 +38,22 @@ __device__ __forceinline__ int lanes_below(uint64_t ballot, int lane) {
   return __popcll(ballot & ((1ull << lane) - 1ull));
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_kernel(
-    const UnitTable tab, const Shape sh, const float* __restrict__ alpha_bar, uint8_t* __restrict__ edge_mask,
-    int32_t* __restrict__ slot, const float* __restrict__ o_part, float* __restrict__ o_bar) {
-  __shared__ uint32_t sm_keys[kLdsKeys];
-  __shared__ int sm_hist[kBins];
-  __shared__ int sm_wave[kSelWaves];
-  __shared__ int sm_pick[2];           // digit, keys below it
-  __shared__ int sm_lt[kSelWaves], sm_eq[kSelWaves];
+struct SelectSmem {
+  uint32_t keys[kLdsKeys];
+  int hist[kBins];
+  int wave[kSelWaves];
+  int pick[2];           // digit, keys below it
+  int lt[kSelWaves], eq[kSelWaves];
+};
 
-  const Unit un = tab.u[blockIdx.x];
+__device__ void select_unit(const Unit& un, const Shape& sh, const float* __restrict__ alpha_bar,
+                            uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, SelectSmem& sm) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int n = un.len;
   const int r = n - un.n_out;
   const float* a = alpha_bar + un.in_row;
   uint8_t* mk = edge_mask + un.in_row;
   int32_t* sl = slot + un.in_row;
-
-  if (o_part != nullptr) {             // fused: o_bar = sum of the chunks' partial sums, in chunk order
-    for (int d = tid; d < sh.D; d += kSelThreads) {
-      float s = 0.f;
-      for (int c = 0; c < un.n_chunks; ++c) s += o_part[((size_t)un.index * kMaxChunks + c) * sh.D + d];
-      o_bar[(size_t)un.index * sh.D + d] = s;
-    }
-  }
 
   const int lo = sh.n_sink;
   const int hi = n - 2 - sh.n_recent;
@@ -65,7 +64,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   }
   const bool cached = (E <= kLdsKeys);
   if (cached) {
-    for (int i = tid; i < E; i += kSelThreads) sm_keys[i] = edge_key(a, lo + i);
+    for (int i = tid; i < E; i += kSelThreads) sm.keys[i] = edge_key(a, lo + i);
   }
   __syncthreads();
 
@@ -78,32 +77,32 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   for (int pass = 0; pass < 3; ++pass) {
     const int shift = shifts[pass];
     const int bins = 1 << widths[pass];
-    for (int b = tid; b < kBins; b += kSelThreads) sm_hist[b] = 0;
+    for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
     __syncthreads();
     for (int i = tid; i < E; i += kSelThreads) {
-      const uint32_t k = cached ? sm_keys[i] : edge_key(a, lo + i);
-      if ((k & pmask) == prefix) atomicAdd(&sm_hist[(k >> shift) & (bins - 1)], 1);
+      const uint32_t k = cached ? sm.keys[i] : edge_key(a, lo + i);
+      if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
     }
     __syncthreads();
     // exclusive scan over the bins, two bins per thread
-    const int h0 = sm_hist[2 * tid], h1 = sm_hist[2 * tid + 1];
+    const int h0 = sm.hist[2 * tid], h1 = sm.hist[2 * tid + 1];
     int incl = h0 + h1;
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
       const int v = __shfl_up(incl, off, kWave);
       if (lane >= off) incl += v;
     }
-    if (lane == kWave - 1) sm_wave[wave] = incl;
+    if (lane == kWave - 1) sm.wave[wave] = incl;
     __syncthreads();
     int base = 0;
-    for (int w = 0; w < wave; ++w) base += sm_wave[w];
+    for (int w = 0; w < wave; ++w) base += sm.wave[w];
     const int excl = base + incl - (h0 + h1);
-    if (want > excl && want <= excl + h0) { sm_pick[0] = 2 * tid; sm_pick[1] = excl; }
-    else if (want > excl + h0 && want <= excl + h0 + h1) { sm_pick[0] = 2 * tid + 1; sm_pick[1] = excl + h0; }
+    if (want > excl && want <= excl + h0) { sm.pick[0] = 2 * tid; sm.pick[1] = excl; }
+    else if (want > excl + h0 && want <= excl + h0 + h1) { sm.pick[0] = 2 * tid + 1; sm.pick[1] = excl + h0; }
     __syncthreads();
-    prefix |= (uint32_t)sm_pick[0] << shift;
+    prefix |= (uint32_t)sm.pick[0] << shift;
     pmask |= (uint32_t)(bins - 1) << shift;
-    want -= sm_pick[1];
+    want -= sm.pick[1];
     __syncthreads();
   }
   const uint32_t T = prefix;           // `want` keys equal to T are taken, the lowest indices first
@@ -114,21 +113,21 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   int n_lt = 0, n_eq = 0;
   for (int i = e0 + lane; i < e1 + lane; i += kWave) {     // whole wavefront iterates together
     uint32_t k = 0xffffffffu;
-    if (i < e1) k = cached ? sm_keys[i] : edge_key(a, lo + i);
+    if (i < e1) k = cached ? sm.keys[i] : edge_key(a, lo + i);
     n_lt += __popcll(__ballot(k < T));
     n_eq += __popcll(__ballot(k == T && i < e1));
   }
-  if (lane == 0) { sm_lt[wave] = n_lt; sm_eq[wave] = n_eq; }
+  if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
   __syncthreads();
   int eq_before = 0, sel_before = 0;
   for (int w = 0; w < wave; ++w) {
-    const int take = min(max(want - eq_before, 0), sm_eq[w]);
-    sel_before += sm_lt[w] + take;
-    eq_before += sm_eq[w];
+    const int take = min(max(want - eq_before, 0), sm.eq[w]);
+    sel_before += sm.lt[w] + take;
+    eq_before += sm.eq[w];
   }
   for (int i = e0 + lane; i < e1 + lane; i += kWave) {
     uint32_t k = 0xffffffffu;
-    if (i < e1) k = cached ? sm_keys[i] : edge_key(a, lo + i);
+    if (i < e1) k = cached ? sm.keys[i] : edge_key(a, lo + i);
     const bool is_eq = (k == T) && (i < e1);
     const uint64_t beq = __ballot(is_eq);
     const bool sel = (k < T) || (is_eq && (eq_before + lanes_below(beq, lane) < want));
@@ -146,12 +145,117 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(
   for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
 }
 
+template <typename T, int D>
+__device__ void obar_chunk(const Unit& un, int chunk, const T* __restrict__ V, const float* __restrict__ alpha_bar,
+                           float* __restrict__ o_part, float (*sm_o)[128]) {
+  constexpr int EPL = Piece<T>::N;
+  constexpr int LPR = D / EPL;
+  constexpr int RPW = kWave / LPR;
+  constexpr int RPB = RPW * kSelWaves;
+  constexpr int UNROLL = 4;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int grp = lane / LPR, piece = lane % LPR;
+  const int clen = obar_chunk_len(un.len);
+  const int t0 = chunk * clen;
+  const int t1 = min(un.len, t0 + clen);
+  const uint4* Vp = reinterpret_cast<const uint4*>(V + (size_t)un.in_row * D) + piece;
+  const float* al = alpha_bar + un.in_row;
+
+  float acc[EPL];
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+  for (int tb = t0 + wave * RPW + grp; tb < t1; tb += RPB * UNROLL) {
+    uint4 raw[UNROLL];
+    float a[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int t = tb + u * RPB;
+      const int tc = min(t, t1 - 1);
+      raw[u] = Vp[(size_t)tc * LPR];
+      a[u] = (t < t1) ? al[tc] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      float vf[EPL];
+      Piece<T>::unpack(raw[u], vf);
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) acc[i] = fmaf(a[u], vf[i], acc[i]);
+    }
+  }
+  // lanes that hold the same piece of the row, then the wavefronts, in a fixed order
+#pragma unroll
+  for (int off = LPR; off < kWave; off <<= 1) {
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] += __shfl_xor(acc[i], off, kWave);
+  }
+  if (grp == 0) {
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) sm_o[wave][piece * EPL + i] = acc[i];
+  }
+  __syncthreads();
+  if (tid < D) {
+    float s = 0.f;
+    for (int w = 0; w < kSelWaves; ++w) s += sm_o[w][tid];
+    o_part[((size_t)un.index * kMaxChunks + chunk) * D + tid] = s;
+  }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
+    const UnitTable tab, const Shape sh, const int n_select, const float* __restrict__ alpha_bar,
+    uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, const T* __restrict__ V,
+    float* __restrict__ o_part) {
+  __shared__ SelectSmem sm;
+  __shared__ float sm_o[kSelWaves][128];
+  const int b = blockIdx.x;
+  if (b < n_select) {
+    select_unit(tab.u[b], sh, alpha_bar, edge_mask, slot, sm);
+  } else {
+    const int c = b - n_select;
+    int ui = 0;
+    while (ui + 1 < tab.n_units && tab.u[ui + 1].o_base <= c) ++ui;
+    obar_chunk<T, D>(tab.u[ui], c - tab.u[ui].o_base, V, alpha_bar, o_part, sm_o);
+  }
+}
+
+__global__ void obar_reduce_kernel(const UnitTable tab, const Shape sh, const float* __restrict__ o_part,
+                                   float* __restrict__ o_bar) {
+  const Unit un = tab.u[blockIdx.x];
+  const int nc = obar_chunks(un.len);
+  for (int d = threadIdx.x; d < sh.D; d += blockDim.x) {
+    float s = 0.f;
+    for (int c = 0; c < nc; ++c) s += o_part[((size_t)un.index * kMaxChunks + c) * sh.D + d];
+    o_bar[(size_t)un.index * sh.D + d] = s;
+  }
+}
+
+template <typename T, int D>
+hipError_t launch_t(const UnitTable& tab, const Shape& sh, bool with_select, const float* alpha_bar,
+                    uint8_t* edge_mask, int32_t* slot, const void* V, float* o_part, hipStream_t stream) {
+  const int n_select = with_select ? tab.n_units : 0;
+  const int n_obar = V ? tab.total_ochunks : 0;
+  if (n_select + n_obar == 0) return hipSuccess;
+  hipLaunchKernelGGL((select_obar_kernel<T, D>), dim3(n_select + n_obar), dim3(kSelThreads), 0, stream, tab, sh,
+                     n_select, alpha_bar, edge_mask, slot, (const T*)V, o_part);
+  return hipGetLastError();
+}
+
 }  // namespace
 
-hipError_t launch_select(const UnitTable& tab, const Shape& sh, const float* alpha_bar, uint8_t* edge_mask,
-                         int32_t* slot, const Workspace* ws_for_obar, float* o_bar, hipStream_t stream) {
-  hipLaunchKernelGGL(select_kernel, dim3(tab.n_units), dim3(kSelThreads), 0, stream, tab, sh, alpha_bar,
-                     edge_mask, slot, ws_for_obar ? ws_for_obar->o_part : nullptr, o_bar);
+hipError_t launch_select_obar(const UnitTable& tab, const Shape& sh, kvs_dtype dt, bool with_select,
+                              const float* alpha_bar, uint8_t* edge_mask, int32_t* slot, const void* V,
+                              float* o_part, hipStream_t stream) {
+  if (dt == KVS_F32) {
+    return sh.D == 64 ? launch_t<float, 64>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, o_part, stream)
+                      : launch_t<float, 128>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, o_part, stream);
+  }
+  return sh.D == 64 ? launch_t<uint16_t, 64>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, o_part, stream)
+                    : launch_t<uint16_t, 128>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, o_part, stream);
+}
+
+hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float* o_part, float* o_bar,
+                              hipStream_t stream) {
+  hipLaunchKernelGGL(obar_reduce_kernel, dim3(tab.n_units), dim3(128), 0, stream, tab, sh, o_part, o_bar);
   return hipGetLastError();
 }
 

@@ -259,6 +259,34 @@ def test_merge_fallback_and_identical_keys():
     np.testing.assert_allclose(Ko.cpu().numpy()[37], K[40], rtol=2e-6)
 
 
+def test_merge_bf16_output_rounds_to_nearest_even():
+    """Sums that fall exactly between two bf16 values go to the even one (one rounding, at the store)."""
+    import torch
+    import paper_2603_00907_amd as kvs
+    n, D = 8, 64
+    rng = np.random.default_rng(11)
+    K = rng.integers(-3, 4, size=(n, D)).astype(np.float32)
+    V = rng.integers(-3, 4, size=(n, D)).astype(np.float32)
+    V[2], V[3] = 1.0, 2.0 ** -8              # 1.00390625: tie between 1.0 (even) and 1.0078125
+    V[5], V[6] = 1.0078125, 2.0 ** -8        # 1.01171875: tie between 1.0078125 (odd) and 1.015625
+    mask = np.array([0, 0, 1, 0, 0, 1, 0, 0], dtype=np.uint8)
+    slot = np.array([0, 1, 2, 2, 3, 4, 4, 5], dtype=np.int32)
+    alpha = np.full(n, 1.0 / n, dtype=np.float32)
+    obar = np.zeros((1, D), dtype=np.float32)
+    p = kvs.Problem(lens=[n], budgets=[6], group=1, window=1, head_dim=D, dtype="bf16", n_sink=0)
+    dev = lambda x: torch.from_numpy(x).cuda()  # noqa: E731
+    Ko = torch.zeros((6, D), dtype=torch.bfloat16, device="cuda")
+    Vo = torch.zeros((6, D), dtype=torch.bfloat16, device="cuda")
+    cnt = torch.zeros(6, dtype=torch.int32, device="cuda")
+    kvs.kvs_merge_compact(p, dev(K).bfloat16(), dev(V).bfloat16(), dev(alpha), dev(obar), dev(mask), dev(slot),
+                          Ko, Vo, cnt)
+    torch.cuda.synchronize()
+    Vg = Vo.float().cpu().numpy()
+    assert (Vg[2] == 1.0).all() and (Vg[4] == 1.015625).all()
+    assert cnt.cpu().numpy().tolist() == [1, 1, 2, 1, 2, 1]
+    assert (Vg[0] == V[0]).all() and (Ko.float().cpu().numpy()[3] == K[4]).all()
+
+
 # ------------------------------------------------------------------------------------------------
 def run_step(w, accepted, path=None):
     units = [a.inputs for a in accepted]
