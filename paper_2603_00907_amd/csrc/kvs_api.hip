@@ -14,7 +14,7 @@ hipError_t launch_score_valu(const UnitTable& tab, const Shape& sh, kvs_dtype dt
                              float* alpha_bar, const Workspace& ws, hipStream_t stream);
 hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
                              float* alpha_bar, const Workspace& ws, hipStream_t stream);
-bool score_mfma_supported(const Shape& sh, kvs_dtype dt);
+bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt);
 
 namespace {
 
@@ -167,7 +167,7 @@ hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, con
   // KVS_SCORE_PATH=valu forces the vector-ALU kernels (used by the tests to cover both paths).
   const char* force = std::getenv("KVS_SCORE_PATH");
   const bool force_valu = force && std::strcmp(force, "valu") == 0;
-  if (!force_valu && score_mfma_supported(sh, dt)) return launch_score_mfma(tab, sh, Q, K, alpha_bar, ws, stream);
+  if (!force_valu && score_mfma_supported(tab, sh, dt)) return launch_score_mfma(tab, sh, Q, K, alpha_bar, ws, stream);
   return launch_score_valu(tab, sh, dt, Q, K, alpha_bar, ws, stream);
 }
 

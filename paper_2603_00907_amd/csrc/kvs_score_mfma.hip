@@ -56,6 +56,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   __shared__ float sm_c[KVS_MAX_Q_ROWS];
   __shared__ float2 sm_stats[kWaves][QROWS];
   __shared__ float sm_alpha[kWaves][kTile];
+  __shared__ float2 sm_pair[2][128];
+  // the Q block of a pass, staged once per workgroup when all wavefronts share it (WQ == 1)
+  __shared__ __attribute__((aligned(1024))) unsigned char sm_q[WQ == 1 ? QROWS * ROWB : 16];
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -78,30 +81,28 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   // into slot s of row r is s ^ (r % LPR)
   const int st_row = lane / LPR, st_slot = lane % LPR;
 
+  // byte offset of this lane's piece inside a full tile, for each of the NLD load instructions
+  int ld_off[NLD];
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    const int row = st_row + i * RPI;
+    ld_off[i] = row * ROWB + (st_slot ^ (row % LPR)) * 16;
+  }
+  // A tile always holds 32 whole rows of the chunk: the ragged last tile is moved back so that it ends
+  // at the chunk's end, and the rows it shares with the tile before it are masked out (`shift` of
+  // them).  Every unit has at least 32 tokens on this path, so the moved tile stays inside the unit.
   auto issue_tile = [&](int j) {
+    const int tile_t0 = t0 + j * kTile;
+    if (tile_t0 >= t1) return;                // no such tile
+    const int base_t = min(tile_t0, t1 - kTile);
+    const unsigned char* base = reinterpret_cast<const unsigned char*>(Kg) + (size_t)base_t * ROWB;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const int row = st_row + i * RPI;
-      const int t = max(t0, min(t0 + j * kTile + row, t1 - 1));
-      const int piece = st_slot ^ (row % LPR);
-      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(Kg + (size_t)t * LPR + piece), KVS_LDS_PTR(my_k + i * 1024),
-                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]), KVS_LDS_PTR(my_k + i * 1024), 16, 0, 0);
     }
   };
 
-  if (PHASE == 1) {
-    for (int q = tid; q < R; q += kThreads) {
-      float M = -INFINITY;
-      for (int c = 0; c < un.n_chunks; ++c) M = fmaxf(M, stats_part[(part_base + c) * R + q].x);
-      float Z = 0.f;
-      for (int c = 0; c < un.n_chunks; ++c) {
-        const float2 s = stats_part[(part_base + c) * R + q];
-        Z += s.y * ex2(s.x - M);
-      }
-      sm_c[q] = M + log2f(Z * (float)R);
-    }
-    __syncthreads();
-  }
+  if (PHASE == 1) finalize_stats(stats_part, part_base, un.n_chunks, R, sm_c, sm_pair);
 
   for (int qp = 0; qp < R; qp += PASS_ROWS) {
     const bool first_pass = (qp == 0);
@@ -111,16 +112,44 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     // this wavefront's block of query rows, kept in registers as MFMA B operands
     bf16x8 bq[NT][KS];
     float cq[NT];
+    if (WQ == 1) {
+      // one coalesced, swizzled copy of the block in LDS per workgroup (every wavefront fetches a
+      // quarter), then operand reads from LDS: 4x less L2 traffic than per-wavefront row gathers
+      constexpr int QLD = QROWS / RPI / kWaves;       // load instructions per wavefront
+      const uint4* Qg = reinterpret_cast<const uint4*>(Qu);
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int qrow = qp + wq * QROWS + nt * 32 + col;
-      const bool ok = qrow < R;
-      cq[nt] = (PHASE == 1 && ok) ? sm_c[qrow] : INFINITY;
+      for (int i = 0; i < QLD; ++i) {
+        const int row = (wave * QLD + i) * RPI + st_row;
+        const int qrow = min(qp + row, R - 1);        // rows past R repeat the last row (never used)
+        const int piece = st_slot ^ (row % LPR);
+        __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(Qg + (size_t)qrow * LPR + piece),
+                                         KVS_LDS_PTR(sm_q + (wave * QLD + i) * 1024), 16, 0, 0);
+      }
+      __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0)
+      __syncthreads();
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) {
-        uint4 raw = make_uint4(0, 0, 0, 0);
-        if (ok) raw = *reinterpret_cast<const uint4*>(Qu + (size_t)qrow * D + kk * 16 + 8 * half);
-        bq[nt][kk] = *reinterpret_cast<bf16x8*>(&raw);
+      for (int nt = 0; nt < NT; ++nt) {
+        const int row = nt * 32 + col;
+        cq[nt] = (PHASE == 1 && qp + row < R) ? sm_c[qp + row] : INFINITY;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+          const int slot = (2 * kk + half) ^ (row % LPR);
+          bq[nt][kk] = *reinterpret_cast<const bf16x8*>(sm_q + row * ROWB + slot * 16);
+        }
+      }
+      __syncthreads();                                // sm_q is refilled by the next pass
+    } else {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int qrow = qp + wq * QROWS + nt * 32 + col;
+        const bool ok = qrow < R;
+        cq[nt] = (PHASE == 1 && ok) ? sm_c[qrow] : INFINITY;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+          uint4 raw = make_uint4(0, 0, 0, 0);
+          if (ok) raw = *reinterpret_cast<const uint4*>(Qu + (size_t)qrow * D + kk * 16 + 8 * half);
+          bq[nt][kk] = *reinterpret_cast<bf16x8*>(&raw);
+        }
       }
     }
 
@@ -131,41 +160,61 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     for (int it = 0; it < iters; ++it) {
       const int j = it * WT + wt;                   // tile index inside the chunk
       const int tile_t0 = t0 + j * kTile;
-      const int nvalid = min(kTile, t1 - tile_t0);  // <= 0: this wavefront has no tile in this round
+      const int base_t = min(tile_t0, t1 - kTile);  // first token of the (possibly moved back) tile
+      const int shift = (tile_t0 >= t1) ? kTile : tile_t0 - base_t;   // leading rows that are not ours
+      if (WQ == 1 && shift == kTile) break;         // this wavefront has run out of tiles
 
-      // wait for the tile, pull its operands into registers, hand the LDS tile to the next load
+      // wait for the tile; first half of the k-steps: operands to registers, MFMAs
       __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
       asm volatile("" ::: "memory");
-      bf16x8 a[KS];
-#pragma unroll
-      for (int kk = 0; kk < KS; ++kk) {
-        const int slot = (2 * kk + half) ^ (col % LPR);
-        a[kk] = *reinterpret_cast<const bf16x8*>(my_k + col * ROWB + slot * 16);
-      }
-      __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0): operands have left LDS
-      asm volatile("" ::: "memory");
-      if (it + 1 < iters) issue_tile(j + WT);
-
-      // S^T tile = K_tile (32 x D) * Q_block^T (D x 32*NT)
+      constexpr int KH = KS / 2;
       f32x16 acc[NT];
+      {
+        bf16x8 a[KH];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) {
+        for (int kk = 0; kk < KH; ++kk) {
+          const int slot = (2 * kk + half) ^ (col % LPR);
+          a[kk] = *reinterpret_cast<const bf16x8*>(my_k + col * ROWB + slot * 16);
+        }
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[nt][v] = 0.f;
+        for (int kk = 0; kk < KH; ++kk) {
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            if (kk == 0) {
+              const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+              acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bq[nt][kk], zero, 0, 0, 0);
+            } else {
+              acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bq[nt][kk], acc[nt], 0, 0, 0);
+            }
+          }
+        }
       }
+      // second half; once its operands have left LDS the tile buffer goes to the next load
+      asm volatile("" ::: "memory");
+      {
+        bf16x8 a[KH];
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) {
+        for (int kk = 0; kk < KH; ++kk) {
+          const int slot = (2 * (kk + KH) + half) ^ (col % LPR);
+          a[kk] = *reinterpret_cast<const bf16x8*>(my_k + col * ROWB + slot * 16);
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0)
+        asm volatile("" ::: "memory");
+        if (it + 1 < iters) issue_tile(j + WT);
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bq[nt][kk], acc[nt], 0, 0, 0);
+        for (int kk = 0; kk < KH; ++kk) {
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bq[nt][kk + KH], acc[nt], 0, 0, 0);
+          }
         }
       }
       // accumulator element v of a lane: token row 8*(v/4) + 4*half + v%4, query column `col`
-      if (nvalid < kTile) {
+      if (shift > 0) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = 8 * (v / 4) + 4 * half + (v % 4);
-          if (row >= nvalid) {
+          if (row < shift) {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) acc[nt][v] = -INFINITY;
           }
@@ -235,15 +284,15 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
             a_tok = 0.f;
 #pragma unroll
             for (int w = 0; w < WQ; ++w) a_tok += sm_alpha[wave + w][lane];
-            if (lane < nvalid) {
-              float* dst = alpha_bar + un.in_row + tile_t0 + lane;
+            if (lane >= shift) {
+              float* dst = alpha_bar + un.in_row + base_t + lane;
               if (!first_pass) a_tok += *dst;
               *dst = a_tok;
             }
           }
           __syncthreads();
-        } else if ((lane & 1) == 0 && row < nvalid) {
-          float* dst = alpha_bar + un.in_row + tile_t0 + row;
+        } else if ((lane & 1) == 0 && row >= shift) {
+          float* dst = alpha_bar + un.in_row + base_t + row;
           if (!first_pass) a_tok += *dst;
           *dst = a_tok;
         }
@@ -310,7 +359,13 @@ hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const 
 
 }  // namespace
 
-bool score_mfma_supported(const Shape& sh, kvs_dtype dt) { return dt == KVS_BF16 && sh.R >= 16; }
+bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
+  if (dt != KVS_BF16 || sh.R < 16) return false;
+  for (int i = 0; i < tab.n_units; ++i) {
+    if (tab.u[i].len < kTile) return false;   // the tile loads assume 32 whole rows per unit
+  }
+  return true;
+}
 
 hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
                              const Workspace& ws, hipStream_t stream) {

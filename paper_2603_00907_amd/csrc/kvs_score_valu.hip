@@ -29,6 +29,7 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
 
   __shared__ float2 sm_stats[(kThreads / kWave) * RPW][kQB];
   __shared__ float sm_c[KVS_MAX_Q_ROWS];
+  __shared__ float2 sm_pair[2][128];
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -43,20 +44,7 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
   const uint4* Kp = reinterpret_cast<const uint4*>(K + (size_t)un.in_row * D) + piece;
   const uint4* Qp = reinterpret_cast<const uint4*>(Q + (size_t)un.index * R * D) + piece;
 
-  if (PHASE == 1) {
-    // unit-wide statistics of every query row from the chunks' partials
-    for (int q = tid; q < R; q += kThreads) {
-      float M = -INFINITY;
-      for (int c = 0; c < un.n_chunks; ++c) M = fmaxf(M, stats_part[(part_base + c) * R + q].x);
-      float Z = 0.f;
-      for (int c = 0; c < un.n_chunks; ++c) {
-        const float2 s = stats_part[(part_base + c) * R + q];
-        Z += s.y * __builtin_amdgcn_exp2f(s.x - M);
-      }
-      sm_c[q] = M + log2f(Z * (float)R);      // alpha / R = exp2(logit2 - sm_c)
-    }
-    __syncthreads();
-  }
+  if (PHASE == 1) finalize_stats(stats_part, part_base, un.n_chunks, R, sm_c, sm_pair);
 
   for (int qb = 0; qb < R; qb += kQB) {
     float qf[kQB][EPL];
