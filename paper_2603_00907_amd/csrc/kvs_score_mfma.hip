@@ -36,6 +36,34 @@ constexpr int kTile = 32;                 // tokens per MFMA tile
 
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Four 16-byte LDS reads at byte addresses ad[0..3] + OFF, complete on return.  Written as inline
+// assembly on purpose: the compiler treats every LDS read as dependent on ALL outstanding
+// global->LDS loads and would wait for the tile that is still being prefetched into the other buffer;
+// here the wait on the right tile is the explicit vmcnt above the call.
+template <int OFF>
+__device__ __forceinline__ void lds_read_4x16(bf16x8& a0, bf16x8& a1, bf16x8& a2, bf16x8& a3, const uint32_t* ad) {
+  asm volatile(
+      "ds_read_b128 %0, %4 offset:%8\n\t"
+      "ds_read_b128 %1, %5 offset:%8\n\t"
+      "ds_read_b128 %2, %6 offset:%8\n\t"
+      "ds_read_b128 %3, %7 offset:%8\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(a0), "=&v"(a1), "=&v"(a2), "=&v"(a3)
+      : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3]), "n"(OFF)
+      : "memory");
+}
+
+#ifdef KVS_TRACE
+// Developer build only: per-wavefront time stamps of the sweep's stages.
+__device__ long long g_trace[8192 * 16];
+#define KVS_STAMP(slot)                                                                      \
+  do {                                                                                       \
+    if (lane == 0 && PHASE == KVS_TRACE) g_trace[(blockIdx.x * kWaves + wave) * 16 + (slot)] = clock64(); \
+  } while (0)
+#else
+#define KVS_STAMP(slot) do { } while (0)
+#endif
+
 #define KVS_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define KVS_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
@@ -52,13 +80,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   constexpr int QROWS = 32 * NT;            // query rows per wavefront
   constexpr int PASS_ROWS = QROWS * WQ;
 
-  __shared__ __attribute__((aligned(1024))) unsigned char sm_k[kWaves][kTile * ROWB];
+  __shared__ __attribute__((aligned(1024))) unsigned char sm_k[kWaves][2][kTile * ROWB];
   __shared__ float sm_c[KVS_MAX_Q_ROWS];
   __shared__ float2 sm_stats[kWaves][QROWS];
   __shared__ float sm_alpha[kWaves][kTile];
   __shared__ float2 sm_pair[2][128];
-  // the Q block of a pass, staged once per workgroup when all wavefronts share it (WQ == 1)
-  __shared__ __attribute__((aligned(1024))) unsigned char sm_q[WQ == 1 ? QROWS * ROWB : 16];
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -76,7 +102,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
 
   const uint4* Kg = reinterpret_cast<const uint4*>(K + (size_t)un.in_row * D);
   const uint16_t* Qu = Q + (size_t)un.index * R * D;
-  unsigned char* my_k = sm_k[wave];
+  unsigned char* my_k = sm_k[wave][0];        // two tile buffers per wavefront: my_k, my_k + TILEB
+  constexpr int TILEB = kTile * ROWB;
   // staging: lane -> (row within the instruction's block of RPI rows, LDS slot); the piece fetched
   // into slot s of row r is s ^ (r % LPR)
   const int st_row = lane / LPR, st_slot = lane % LPR;
@@ -88,56 +115,75 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     const int row = st_row + i * RPI;
     ld_off[i] = row * ROWB + (st_slot ^ (row % LPR)) * 16;
   }
+  // LDS byte addresses of this lane's A operands (k-step kk) in tile buffer 0
+  uint32_t a_addr[KS];
+  {
+    const uint32_t base = (uint32_t)(size_t)KVS_LDS_PTR(my_k) + col * ROWB;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) a_addr[kk] = base + ((2 * kk + half) ^ (col % LPR)) * 16;
+  }
   // A tile always holds 32 whole rows of the chunk: the ragged last tile is moved back so that it ends
   // at the chunk's end, and the rows it shares with the tile before it are masked out (`shift` of
   // them).  Every unit has at least 32 tokens on this path, so the moved tile stays inside the unit.
-  auto issue_tile = [&](int j) {
+  auto issue_tile = [&](int j, int buf) {
     const int tile_t0 = t0 + j * kTile;
-    if (tile_t0 >= t1) return;                // no such tile
+    if (tile_t0 >= t1) return false;          // no such tile
     const int base_t = min(tile_t0, t1 - kTile);
     const unsigned char* base = reinterpret_cast<const unsigned char*>(Kg) + (size_t)base_t * ROWB;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]), KVS_LDS_PTR(my_k + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]), KVS_LDS_PTR(my_k + buf * TILEB + i * 1024),
+                                       16, 0, 0);
     }
+    return true;
   };
 
+  KVS_STAMP(0);
   if (PHASE == 1) finalize_stats(stats_part, part_base, un.n_chunks, R, sm_c, sm_pair);
+  KVS_STAMP(1);
 
   for (int qp = 0; qp < R; qp += PASS_ROWS) {
     const bool first_pass = (qp == 0);
 
-    issue_tile(wt);                           // flies while the Q block is fetched
+    issue_tile(wt, 0);                        // flies while the Q block is fetched
 
     // this wavefront's block of query rows, kept in registers as MFMA B operands
     bf16x8 bq[NT][KS];
     float cq[NT];
     if (WQ == 1) {
-      // one coalesced, swizzled copy of the block in LDS per workgroup (every wavefront fetches a
-      // quarter), then operand reads from LDS: 4x less L2 traffic than per-wavefront row gathers
-      constexpr int QLD = QROWS / RPI / kWaves;       // load instructions per wavefront
+      // One coalesced, swizzled copy of the block in LDS per workgroup, then operand reads from LDS:
+      // 4x less L2 traffic than per-wavefront row gathers.  Every wavefront fetches a quarter of the
+      // rows into its own second tile buffer, which is idle until the operands are in registers.
+      constexpr int RW = QROWS / kWaves;              // rows staged per wavefront
+      constexpr int QLD = RW / RPI > 0 ? RW / RPI : 1;
       const uint4* Qg = reinterpret_cast<const uint4*>(Qu);
 #pragma unroll
       for (int i = 0; i < QLD; ++i) {
-        const int row = (wave * QLD + i) * RPI + st_row;
-        const int qrow = min(qp + row, R - 1);        // rows past R repeat the last row (never used)
-        const int piece = st_slot ^ (row % LPR);
+        const int lr = i * RPI + st_row;              // local row in this wavefront's buffer
+        const int qrow = min(qp + wave * RW + min(lr, RW - 1), R - 1);   // rows past R repeat the last row
+        const int piece = st_slot ^ (lr % LPR);
         __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(Qg + (size_t)qrow * LPR + piece),
-                                         KVS_LDS_PTR(sm_q + (wave * QLD + i) * 1024), 16, 0, 0);
+                                         KVS_LDS_PTR(my_k + TILEB + i * 1024), 16, 0, 0);
       }
+      KVS_STAMP(11);
       __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0)
+      KVS_STAMP(12);
       __syncthreads();
+      KVS_STAMP(13);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const int row = nt * 32 + col;
+        const int lr = row % RW;
+        const unsigned char* src = sm_k[row / RW][1] + lr * ROWB;
         cq[nt] = (PHASE == 1 && qp + row < R) ? sm_c[qp + row] : INFINITY;
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
-          const int slot = (2 * kk + half) ^ (row % LPR);
-          bq[nt][kk] = *reinterpret_cast<const bf16x8*>(sm_q + row * ROWB + slot * 16);
+          const int slot = (2 * kk + half) ^ (lr % LPR);
+          bq[nt][kk] = *reinterpret_cast<const bf16x8*>(src + slot * 16);
         }
       }
-      __syncthreads();                                // sm_q is refilled by the next pass
+      KVS_STAMP(14);
+      __syncthreads();                                // the second buffers go back to the K tiles
     } else {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
@@ -152,6 +198,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         }
       }
     }
+    bool next_in_flight = (iters > 1) && issue_tile(wt + WT, 1);   // loads of the tile after the current one
+    KVS_STAMP(2);
 
     float m_run[NT], l_run[NT];
 #pragma unroll
@@ -164,18 +212,20 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       const int shift = (tile_t0 >= t1) ? kTile : tile_t0 - base_t;   // leading rows that are not ours
       if (WQ == 1 && shift == kTile) break;         // this wavefront has run out of tiles
 
-      // wait for the tile; first half of the k-steps: operands to registers, MFMAs
-      __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0)
+      // wait for this tile only (loads return in order: at most the NLD loads of the next tile may
+      // still be in flight); first half of the k-steps: operands to registers, MFMAs
+      if (next_in_flight) __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));   // vmcnt(NLD)
+      else __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
       asm volatile("" ::: "memory");
-      constexpr int KH = KS / 2;
+      if (it < 6) KVS_STAMP(3 + 2 * it);
+      static_assert(KS == 4 || KS == 8, "operand reads come in groups of four");
+      constexpr int KH = 4;
       f32x16 acc[NT];
       {
         bf16x8 a[KH];
-#pragma unroll
-        for (int kk = 0; kk < KH; ++kk) {
-          const int slot = (2 * kk + half) ^ (col % LPR);
-          a[kk] = *reinterpret_cast<const bf16x8*>(my_k + col * ROWB + slot * 16);
-        }
+        if (it & 1) lds_read_4x16<TILEB>(a[0], a[1], a[2], a[3], a_addr);
+        else lds_read_4x16<0>(a[0], a[1], a[2], a[3], a_addr);
+        if (KS == 4) next_in_flight = (it + 2 < iters) && issue_tile(j + 2 * WT, it & 1);
 #pragma unroll
         for (int kk = 0; kk < KH; ++kk) {
 #pragma unroll
@@ -189,23 +239,17 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
           }
         }
       }
-      // second half; once its operands have left LDS the tile buffer goes to the next load
-      asm volatile("" ::: "memory");
-      {
+      // second half; once its operands have left LDS the tile buffer goes to the load after next
+      if (KS == 8) {
         bf16x8 a[KH];
-#pragma unroll
-        for (int kk = 0; kk < KH; ++kk) {
-          const int slot = (2 * (kk + KH) + half) ^ (col % LPR);
-          a[kk] = *reinterpret_cast<const bf16x8*>(my_k + col * ROWB + slot * 16);
-        }
-        __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0)
-        asm volatile("" ::: "memory");
-        if (it + 1 < iters) issue_tile(j + WT);
+        if (it & 1) lds_read_4x16<TILEB>(a[0], a[1], a[2], a[3], a_addr + (KS == 8 ? 4 : 0));
+        else lds_read_4x16<0>(a[0], a[1], a[2], a[3], a_addr + (KS == 8 ? 4 : 0));
+        next_in_flight = (it + 2 < iters) && issue_tile(j + 2 * WT, it & 1);
 #pragma unroll
         for (int kk = 0; kk < KH; ++kk) {
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
-            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bq[nt][kk + KH], acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bq[nt][(kk + KH) % KS], acc[nt], 0, 0, 0);
           }
         }
       }
@@ -221,6 +265,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         }
       }
 
+      if (it < 6) KVS_STAMP(4 + 2 * it);            // MFMAs issued
       if (PHASE == 0) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -299,6 +344,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       }
     }
 
+    KVS_STAMP(15);
     if (PHASE == 0) {
       // the two halves of a wavefront hold the same query column for different token rows
 #pragma unroll
@@ -349,12 +395,14 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const 
 template <int D>
 hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
                     const Workspace& ws, hipStream_t stream) {
+  // At most 64 query rows per wavefront: with more, the stationary Q operands, the accumulators and
+  // the tile operands no longer fit the 256 registers that two wavefronts per SIMD leave each, and
+  // every spill reload waits for ALL loads in flight, the tile prefetch included.
   const int R = sh.R;
   if (R <= 32) return launch_t<D, 1, 1>(tab, sh, Q, K, alpha_bar, ws, stream);
-  if (R <= 64) return launch_t<D, 2, 1>(tab, sh, Q, K, alpha_bar, ws, stream);
-  if (R <= 128) return launch_t<D, 4, 1>(tab, sh, Q, K, alpha_bar, ws, stream);
-  if (R <= 256) return launch_t<D, 4, 2>(tab, sh, Q, K, alpha_bar, ws, stream);
-  return launch_t<D, 4, 4>(tab, sh, Q, K, alpha_bar, ws, stream);
+  if (R <= 128) return launch_t<D, 2, 1>(tab, sh, Q, K, alpha_bar, ws, stream);    // above 64 rows: two passes
+  if (R <= 256) return launch_t<D, 2, 2>(tab, sh, Q, K, alpha_bar, ws, stream);    // two passes of 128 rows
+  return launch_t<D, 2, 4>(tab, sh, Q, K, alpha_bar, ws, stream);                  // passes of 256 rows
 }
 
 }  // namespace
@@ -372,5 +420,11 @@ hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* 
   return sh.D == 64 ? launch_d<64>(tab, sh, Q, K, alpha_bar, ws, stream)
                     : launch_d<128>(tab, sh, Q, K, alpha_bar, ws, stream);
 }
+
+#ifdef KVS_TRACE
+extern "C" int kvs_debug_trace(void* host, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes);
+}
+#endif
 
 }  // namespace kvs
