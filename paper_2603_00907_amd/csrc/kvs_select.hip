@@ -38,15 +38,69 @@ __device__ __forceinline__ int lanes_below(uint64_t ballot, int lane) {
   return __popcll(ballot & ((1ull << lane) - 1ull));
 }
 
+#ifdef KVS_TRACE_SEL
+__device__ long long g_trace_sel[64 * 16];
+#define KVS_SSTAMP(slot) do { if (threadIdx.x == 0) g_trace_sel[blockIdx.x * 16 + (slot)] = clock64(); } while (0)
+#else
+#define KVS_SSTAMP(slot) do { } while (0)
+#endif
+
+constexpr int kCand = 2048;               // keys of the first-pass bin that are refined in LDS
+
 struct SelectSmem {
   uint32_t keys[kLdsKeys];
+  uint32_t cand[kCand];
   int hist[kBins];
   int wave[kSelWaves];
   int pick[2];           // digit, keys below it
   int lt[kSelWaves], eq[kSelWaves];
+  int ncand;
 };
 
-__device__ void select_unit(const Unit& un, const Shape& sh, const float* __restrict__ alpha_bar,
+// Adds one to hist[d] for every active lane.  Neighbouring tokens have similar scores, so most lanes of
+// a wavefront want the same bin and a plain LDS atomic would serialise them: up to two groups of equal
+// digits are peeled off and added once by their first lane, the rest goes through individual atomics.
+__device__ __forceinline__ void hist_add(int* hist, uint32_t d, bool act, int lane) {
+#pragma unroll
+  for (int peel = 0; peel < 2; ++peel) {
+    const uint64_t am = __ballot(act);
+    if (am == 0) return;
+    const int leader = __ffsll((long long)am) - 1;
+    const uint32_t d0 = __builtin_amdgcn_readlane(d, leader);
+    const uint64_t same = __ballot(act && d == d0);
+    if (lane == leader) atomicAdd(&hist[d0], __popcll(same));
+    act = act && (d != d0);
+  }
+  if (act) atomicAdd(&hist[d], 1);
+}
+
+// Exclusive scan of the histogram (two bins per thread); finds the bin that holds rank `want`
+// (1-based) and extends (prefix, pmask, want) by that digit.
+__device__ __forceinline__ void pick_bin(SelectSmem& sm, int shift, int bins, uint32_t& prefix, uint32_t& pmask,
+                                         int& want) {
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int h0 = sm.hist[2 * tid], h1 = sm.hist[2 * tid + 1];
+  int incl = h0 + h1;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int v = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += v;
+  }
+  if (lane == kWave - 1) sm.wave[wave] = incl;
+  __syncthreads();
+  int base = 0;
+  for (int w = 0; w < wave; ++w) base += sm.wave[w];
+  const int excl = base + incl - (h0 + h1);
+  if (want > excl && want <= excl + h0) { sm.pick[0] = 2 * tid; sm.pick[1] = excl; }
+  else if (want > excl + h0 && want <= excl + h0 + h1) { sm.pick[0] = 2 * tid + 1; sm.pick[1] = excl + h0; }
+  __syncthreads();
+  prefix |= (uint32_t)sm.pick[0] << shift;
+  pmask |= (uint32_t)(bins - 1) << shift;
+  want -= sm.pick[1];
+  __syncthreads();
+}
+
+__device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, const float* __restrict__ alpha_bar,
                             uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, SelectSmem& sm) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int n = un.len;
@@ -63,49 +117,72 @@ __device__ void select_unit(const Unit& un, const Shape& sh, const float* __rest
     return;
   }
   const bool cached = (E <= kLdsKeys);
-  if (cached) {
-    for (int i = tid; i < E; i += kSelThreads) sm.keys[i] = edge_key(a, lo + i);
+  KVS_SSTAMP(0);
+
+  // ---- keys (to LDS when they fit) and the histogram of their top 11 bits, four keys per thread at a
+  //      time with the loads batched
+  for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
+  if (tid == 0) sm.ncand = 0;
+  __syncthreads();
+  for (int base = 0; base < E; base += 4 * kSelThreads) {
+    float x[4], y[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int m = lo + min(base + u * kSelThreads + tid, E - 1);
+      x[u] = a[m];
+      y[u] = a[m + 1];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = base + u * kSelThreads + tid;
+      const uint32_t k = __float_as_uint(x[u] + y[u]);
+      if (cached && i < E) sm.keys[i] = k;
+      hist_add(sm.hist, k >> 21, i < E, lane);
+    }
   }
   __syncthreads();
-
-  // ---- radix select of the r-th smallest key
   uint32_t prefix = 0, pmask = 0;
   int want = r;                        // rank (1-based) among the keys that share `prefix`
-  const int shifts[3] = {21, 10, 0};
-  const int widths[3] = {11, 11, 10};
+  KVS_SSTAMP(1);
+  pick_bin(sm, 21, 2048, prefix, pmask, want);
+  KVS_SSTAMP(2);
+
+  // ---- the keys of that bin go to a short list; the remaining 21 bits are settled on the list
+  for (int i = tid; i < E; i += kSelThreads) {
+    const uint32_t k = cached ? sm.keys[i] : edge_key(a, lo + i);
+    if ((k & pmask) == prefix) {
+      const int pos = atomicAdd(&sm.ncand, 1);
+      if (pos < kCand) sm.cand[pos] = k;
+    }
+  }
+  __syncthreads();
+  const int ncand = sm.ncand;
+  KVS_SSTAMP(3);
+  const bool listed = (ncand <= kCand);
+  const int shifts[2] = {10, 0};
+  const int widths[2] = {11, 10};
 #pragma unroll
-  for (int pass = 0; pass < 3; ++pass) {
+  for (int pass = 0; pass < 2; ++pass) {
     const int shift = shifts[pass];
     const int bins = 1 << widths[pass];
     for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
     __syncthreads();
-    for (int i = tid; i < E; i += kSelThreads) {
-      const uint32_t k = cached ? sm.keys[i] : edge_key(a, lo + i);
-      if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
+    if (listed) {
+      for (int i = tid; i < ncand; i += kSelThreads) {
+        const uint32_t k = sm.cand[i];
+        if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
+      }
+    } else {                            // a bin too crowded for the list: full passes over the keys
+      for (int i = tid; i < E; i += kSelThreads) {
+        const uint32_t k = cached ? sm.keys[i] : edge_key(a, lo + i);
+        hist_add(sm.hist, (k >> shift) & (bins - 1), (k & pmask) == prefix, lane);
+      }
     }
     __syncthreads();
-    // exclusive scan over the bins, two bins per thread
-    const int h0 = sm.hist[2 * tid], h1 = sm.hist[2 * tid + 1];
-    int incl = h0 + h1;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const int v = __shfl_up(incl, off, kWave);
-      if (lane >= off) incl += v;
-    }
-    if (lane == kWave - 1) sm.wave[wave] = incl;
-    __syncthreads();
-    int base = 0;
-    for (int w = 0; w < wave; ++w) base += sm.wave[w];
-    const int excl = base + incl - (h0 + h1);
-    if (want > excl && want <= excl + h0) { sm.pick[0] = 2 * tid; sm.pick[1] = excl; }
-    else if (want > excl + h0 && want <= excl + h0 + h1) { sm.pick[0] = 2 * tid + 1; sm.pick[1] = excl + h0; }
-    __syncthreads();
-    prefix |= (uint32_t)sm.pick[0] << shift;
-    pmask |= (uint32_t)(bins - 1) << shift;
-    want -= sm.pick[1];
-    __syncthreads();
+    pick_bin(sm, shift, bins, prefix, pmask, want);
   }
   const uint32_t T = prefix;           // `want` keys equal to T are taken, the lowest indices first
+  KVS_SSTAMP(4);
 
   // ---- ordered pass: every wavefront owns a contiguous range of edges
   const int per = ((E + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
@@ -119,6 +196,7 @@ __device__ void select_unit(const Unit& un, const Shape& sh, const float* __rest
   }
   if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
   __syncthreads();
+  KVS_SSTAMP(5);
   int eq_before = 0, sel_before = 0;
   for (int w = 0; w < wave; ++w) {
     const int take = min(max(want - eq_before, 0), sm.eq[w]);
@@ -143,10 +221,11 @@ __device__ void select_unit(const Unit& un, const Shape& sh, const float* __rest
   // tokens outside the eligible edge range
   for (int t = tid; t < lo && t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t; }
   for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
+  KVS_SSTAMP(6);
 }
 
 template <typename T, int D>
-__device__ void obar_chunk(const Unit& un, int chunk, const T* __restrict__ V, const float* __restrict__ alpha_bar,
+__device__ __forceinline__ void obar_chunk(const Unit& un, int chunk, const T* __restrict__ V, const float* __restrict__ alpha_bar,
                            float* __restrict__ o_part, float (*sm_o)[128]) {
   constexpr int EPL = Piece<T>::N;
   constexpr int LPR = D / EPL;
@@ -258,5 +337,11 @@ hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float
   hipLaunchKernelGGL(obar_reduce_kernel, dim3(tab.n_units), dim3(128), 0, stream, tab, sh, o_part, o_bar);
   return hipGetLastError();
 }
+
+#ifdef KVS_TRACE_SEL
+extern "C" int kvs_debug_trace_sel(void* host, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_sel), bytes);
+}
+#endif
 
 }  // namespace kvs
