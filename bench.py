@@ -35,7 +35,10 @@ def parse():
     ap.add_argument("--workload", default="llama8b_32k")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching from the host")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (known HBM bytes) for scaling rocprofv3 byte counters")
     return ap.parse_args()
 
 
@@ -45,6 +48,18 @@ def phase_bytes(n, B, R, D, b):
     select = 4 * n + n + 4 * n                                 # read alpha_bar; write edge mask, slot map
     merge = 2 * n * D * b + 9 * n + 4 * D + 2 * B * D * b + 4 * B   # read K, V, alpha, mask, slot, o_bar; write K', V', counts
     return {"score": score, "select": select, "merge_compact": merge}
+
+
+def measured_traffic(workload):
+    """HBM-side bytes per launch of each phase, from the committed rocprofv3 counter summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("bench-traffic-bytes-per-launch:"):
+                return {k: float(v) for k, v in (kv.split("=") for kv in line.split(":", 1)[1].split())}
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -110,14 +125,33 @@ def main():
         for l in range(layers):
             kvs.kvs_step(problem, Qs[l], Ks[l], Vs[l], K_out[l], V_out[l], counts[l], ws, stream=stream)
 
-    for _ in range(args.warmup):
+    # Optionally the launches of one step (4 kernels per layer) are captured once into a HIP graph and
+    # replayed: the library never allocates, synchronises or memsets, so a step is capturable as it is.
+    # (Measured: no gain here, the kernels are long enough for the host to run ahead.)
+    run_step = one_step
+    graph = None
+    if args.graph:
         one_step()
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            stream = side.cuda_stream
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                one_step()
+        torch.cuda.current_stream().wait_stream(side)
+        stream = torch.cuda.current_stream().cuda_stream
+        run_step = graph.replay
+
+    for _ in range(args.warmup):
+        run_step()
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
     for _ in range(args.steps):
-        one_step()
+        run_step()
     ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -166,15 +200,23 @@ def main():
         "config": {"workload": w.name, "layers": layers, "kv_heads": w.n_kv_heads, "q_heads": w.group * w.n_kv_heads,
                    "head_dim": D, "window": w.window, "tokens": lens_seq if w.n_seq > 1 else lens_seq[0],
                    "budget": budgets[0] if w.n_seq == 1 else "25% of length", "n_sink": w.n_sink,
-                   "us_per_layer": ms_per_step * 1e3 / layers, "input_generation_s": round(t_gen, 1)},
+                   "launch": "hip graph replay" if args.graph else "host", "us_per_layer": ms_per_step * 1e3 / layers, "input_generation_s": round(t_gen, 1)},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": (measured_traffic(w.name) or {}).get(dominant),
                      "us_per_launch": phase_ms[dominant] * 1e3, "algorithmic_bytes_per_launch": pb[dominant],
                      "phases_us": {p: phase_ms[p] * 1e3 for p in phases},
                      "phases_frac": {p: pb[p] / (phase_ms[p] * 1e-3) / 1e9 / HBM_PEAK_GBS for p in phases},
                      "step": {"algorithmic_bytes_per_layer": step_bytes, "achieved": step_gbs,
                               "frac": step_gbs / HBM_PEAK_GBS}},
     }
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, keep_host, args.cpu_seconds, workers)

@@ -76,8 +76,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   __shared__ float sm_frag[GROUPS][2][FRAG];   // [g][0]: head fragment, [g][1]: tail / through fragment
   __shared__ int sm_flag[GROUPS];              // bit 0: head fragment ends here, 1: through, 2: tail starts here
   __shared__ int sm_tail_slot[GROUPS];
-  __shared__ int sm_scan[1 + kThreads / kWave];
-  __shared__ float sm_obar[2][D];
+  __shared__ int sm_scan[2 * (kThreads / kWave)];
+  __shared__ float sm_obar[kThreads / D][D];
 
   int ui = 0;
   while (ui + 1 < tab.n_units && tab.u[ui + 1].m_base <= (int)blockIdx.x) ++ui;
@@ -89,8 +89,44 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 
   const int nom_a = ((int)blockIdx.x - un.m_base) * kMergeTokens;
   const int nom_b = min(n, nom_a + kMergeTokens);
-  const int A = first_slot_start(mk, nom_a, n, sm_scan);
-  const int B = (nom_b >= n) ? n : first_slot_start(mk, nom_b, n, sm_scan);
+
+  // Everything the prologue needs is requested at once (one round trip): the edge-mask bytes that
+  // decide where the workgroup's real range begins and ends, and the chunk sums of o_bar.
+  const int wave = tid / kWave, lane = tid % kWave;
+  const int ta = nom_a + tid, tb = nom_b + tid;
+  const bool start_a = (ta >= n) || (ta == 0) || (mk[ta - 1] == 0);
+  const bool start_b = (tb >= n) || (tb == 0) || (mk[tb - 1] == 0);
+  constexpr int PARTS = kThreads / D;          // threads per channel when adding up the chunk sums
+  constexpr int PER = kMaxChunks / PARTS;
+  float part_sum = 0.f;
+  if (o_bar == nullptr) {
+    const int nc = obar_chunks(un.len);
+    const int d = tid % D, h = tid / D;
+    float v[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int c = h * PER + i;
+      v[i] = (c < nc) ? o_part[((size_t)un.index * kMaxChunks + c) * D + d] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) part_sum += v[i];
+    sm_obar[h][d] = part_sum;
+  }
+  {
+    const uint64_t ba = __ballot(start_a), bb = __ballot(start_b);
+    if (lane == 0) {
+      sm_scan[wave] = ba ? nom_a + wave * kWave + (__ffsll((long long)ba) - 1) : 0x7fffffff;
+      sm_scan[4 + wave] = bb ? nom_b + wave * kWave + (__ffsll((long long)bb) - 1) : 0x7fffffff;
+    }
+  }
+  __syncthreads();
+  int A = 0x7fffffff, B = 0x7fffffff;
+#pragma unroll
+  for (int w = 0; w < kThreads / kWave; ++w) { A = min(A, sm_scan[w]); B = min(B, sm_scan[4 + w]); }
+  __syncthreads();
+  // a slot longer than the probe window: keep looking (rare)
+  A = (A == 0x7fffffff) ? first_slot_start(mk, nom_a + kThreads, n, sm_scan) : min(A, n);
+  B = (B == 0x7fffffff) ? first_slot_start(mk, nom_b + kThreads, n, sm_scan) : min(B, n);
   if (A >= B) return;                          // the whole nominal range lies inside a slot owned earlier
 #if defined(KVS_MERGE_DEBUG_STOP) && KVS_MERGE_DEBUG_STOP == 1
   return;
@@ -104,24 +140,19 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   const float* al = alpha_bar + un.in_row;
   const int32_t* sl = slot + un.in_row;
 
+  // o_bar: final values, or the chunk sums added in a fixed order (every workgroup gets the same bits)
   float o[EPL];
-  if (o_bar != nullptr) {
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) o[i] = o_bar[(size_t)un.index * D + piece * EPL + i];
-  } else {
-    // o_bar = sum of the chunk sums of the o_bar pass, in a fixed order: every workgroup gets the same bits
-    const int nc = obar_chunks(un.len);
-    const int half_nc = (nc + 1) / 2;
-    for (int i = tid; i < 2 * D; i += kThreads) {
-      const int d = i % D, h = i / D;
-      float s = 0.f;
-      for (int c = h * half_nc; c < min(nc, (h + 1) * half_nc); ++c)
-        s += o_part[((size_t)un.index * kMaxChunks + c) * D + d];
-      sm_obar[h][d] = s;
+  for (int i = 0; i < EPL; ++i) {
+    const int d = piece * EPL + i;
+    if (o_bar != nullptr) {
+      o[i] = o_bar[(size_t)un.index * D + d];
+    } else {
+      float s = sm_obar[0][d];
+#pragma unroll
+      for (int h = 1; h < PARTS; ++h) s += sm_obar[h][d];
+      o[i] = s;
     }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) o[i] = sm_obar[0][piece * EPL + i] + sm_obar[1][piece * EPL + i];
   }
 
   // One finished slot -> global memory (all lanes of the group call it together).  `raw_*` are the
