@@ -29,7 +29,7 @@ namespace {
 
 constexpr int kThreads = 256;
 #ifndef KVS_MERGE_PREFETCH
-#define KVS_MERGE_PREFETCH 4
+#define KVS_MERGE_PREFETCH 2
 #endif
 constexpr int kPrefetch = KVS_MERGE_PREFETCH;
 
@@ -177,7 +177,10 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 #pragma unroll
       for (int i = 0; i < EPL; ++i) outk[i] *= inv;
     }
-    uint4 ok = Piece<T>::pack(outk), ov = Piece<T>::pack(accV);
+    float outv[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) outv[i] = fmaf((float)count, o[i], accV[i]);   // accV sums (v - o_bar)
+    uint4 ok = Piece<T>::pack(outk), ov = Piece<T>::pack(outv);
     if (count == 1) { ok = raw_k; ov = raw_v; }
     if ((unsigned)out_slot < (unsigned)un.n_out) {   // a slot map from outside the library is not trusted
       Ko[(size_t)out_slot * LPR] = ok;
@@ -205,40 +208,55 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 
   if (ga < gb) {
     const bool head_open = (ga > A) && (mk[ga - 1] != 0);
-    const bool tail_open = (gb < n) && (mk[gb - 1] != 0);  // for a consistent mask gb < B then
-
-    // rows needed besides the group's own: V[ga-1] for C_{ga-1}, V[gb] for C_{gb-1}
-    uint4 v_before = make_uint4(0, 0, 0, 0), v_after = make_uint4(0, 0, 0, 0);
-    float a_before = 0.f, a_after = 0.f;
-    if (head_open) { v_before = Vp[(size_t)(ga - 1) * LPR]; a_before = al[ga - 1]; }
-    if (tail_open) { v_after = Vp[(size_t)gb * LPR]; a_after = al[gb]; }
-    // slots are numbered consecutively: only the first one is looked up
-    int out_slot = sl[ga];
+    // Token t's weight needs C_t, i.e. the NEXT token's Value row: the walk therefore reads V one token
+    // ahead of K, and the last step looks at row gb (which exists whenever the slot is still open).
+    const int last_v = min(gb, n - 1);
+    const int out_slot0 = sl[ga];                    // slots are numbered consecutively from here
 
     uint4 rk[kPrefetch], rv[kPrefetch];
     float ra[kPrefetch];
     int rm[kPrefetch];
 #pragma unroll
     for (int j = 0; j < kPrefetch; ++j) {
-      const int tt = min(ga + j, gb - 1);
-      rk[j] = Kp[(size_t)tt * LPR];
-      rv[j] = Vp[(size_t)tt * LPR];
-      ra[j] = al[tt];
-      rm[j] = mk[tt];
+      rk[j] = Kp[(size_t)min(ga + j, gb - 1) * LPR];
+      const int tv = min(ga + 1 + j, last_v);
+      rv[j] = Vp[(size_t)tv * LPR];
+      ra[j] = al[tv];
+      rm[j] = mk[tv];
     }
+    uint4 vraw_cur = Vp[(size_t)ga * LPR];
+    float alpha_cur = al[ga];
+    int mask_cur = mk[ga];
 
-    // state of the open slot; between slots the accumulators are zero
-    float accK[EPL], accV[EPL], kprev[EPL], rprev[EPL];
-    float U = 0.f, pend = 0.f, aprev = a_before;
-    int count = 0, first_tok = ga;
-    bool cont = head_open;          // the current token continues a slot
+    float r_cur[EPL], accK[EPL], accV[EPL];
+    float ss_cur = 0.f, Cprev = 0.f, U = 0.f;
+    int count = 0, first_tok = ga, out_slot = out_slot0;
     bool is_head = head_open;       // the open slot began before this group
-    bool own_prev = false;          // the previous token belongs to this group
     {
       float vf[EPL];
-      Piece<T>::unpack(v_before, vf);
+      Piece<T>::unpack(vraw_cur, vf);
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) { rprev[i] = vf[i] - o[i]; accK[i] = 0.f; accV[i] = 0.f; kprev[i] = 0.f; }
+      for (int i = 0; i < EPL; ++i) {
+        r_cur[i] = vf[i] - o[i];
+        ss_cur = fmaf(r_cur[i], r_cur[i], ss_cur);
+        accK[i] = 0.f;
+        accV[i] = 0.f;
+      }
+      float sc = 0.f;
+      float a_before = 0.f;
+      if (head_open) {                               // C_{ga-1} from the row before the group
+        float vb[EPL];
+        Piece<T>::unpack(Vp[(size_t)(ga - 1) * LPR], vb);
+        a_before = al[ga - 1];
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+          const float p = (vb[i] - o[i]) + r_cur[i];
+          sc = fmaf(p, p, sc);
+        }
+      }
+      ss_cur = group_sum<LPR>(ss_cur);
+      sc = group_sum<LPR>(sc);
+      Cprev = a_before * alpha_cur * __builtin_amdgcn_sqrtf(sc);
     }
 
     for (int t0 = ga; t0 < gb; t0 += kPrefetch) {
@@ -246,57 +264,48 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       for (int j = 0; j < kPrefetch; ++j) {
         const int t = t0 + j;
         if (t >= gb) break;
-        const uint4 kraw = rk[j], vraw = rv[j];
-        const float alpha_t = ra[j];
-        const int mask_t = rm[j];
+        const uint4 kraw = rk[j], vraw_n = rv[j];
+        const float alpha_n = ra[j];
+        const int mask_n = rm[j];
         {
-          const int tt = min(t + kPrefetch, gb - 1);
-          rk[j] = Kp[(size_t)tt * LPR];
-          rv[j] = Vp[(size_t)tt * LPR];
-          ra[j] = al[tt];
-          rm[j] = mk[tt];
+          rk[j] = Kp[(size_t)min(t + kPrefetch, gb - 1) * LPR];
+          const int tv = min(t + 1 + kPrefetch, last_v);
+          rv[j] = Vp[(size_t)tv * LPR];
+          ra[j] = al[tv];
+          rm[j] = mk[tv];
         }
         // the same straight-line code for every token: lane groups of a wavefront stay converged
-        float kf[EPL], vf[EPL], rr[EPL];
+        float kf[EPL], vn[EPL], r_next[EPL];
         Piece<T>::unpack(kraw, kf);
-        Piece<T>::unpack(vraw, vf);
-        float ss = 0.f, sc = 0.f;
+        Piece<T>::unpack(vraw_n, vn);
+        float ss_next = 0.f, sc = 0.f;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
-          rr[i] = vf[i] - o[i];
-          ss = fmaf(rr[i], rr[i], ss);
-          const float p = rprev[i] + rr[i];
+          r_next[i] = vn[i] - o[i];
+          ss_next = fmaf(r_next[i], r_next[i], ss_next);
+          const float p = r_cur[i] + r_next[i];
           sc = fmaf(p, p, sc);
         }
-        ss = group_sum<LPR>(ss);
+        ss_next = group_sum<LPR>(ss_next);
         sc = group_sum<LPR>(sc);
-        const float Anorm = alpha_t * fabsf(1.f - 2.f * alpha_t) * __builtin_amdgcn_sqrtf(ss);
-        const float C = cont ? aprev * alpha_t * __builtin_amdgcn_sqrtf(sc) : 0.f;
-        const float w_prev = (cont && own_prev) ? pend - C : 0.f;   // completed weight of token t-1
-        first_tok = cont ? first_tok : t;
-        U += w_prev;
-        pend = Anorm - C;
+        const float Anorm = alpha_cur * fabsf(1.f - 2.f * alpha_cur) * __builtin_amdgcn_sqrtf(ss_cur);
+        const float C = mask_cur ? alpha_cur * alpha_n * __builtin_amdgcn_sqrtf(sc) : 0.f;
+        const float u = Anorm - Cprev - C;
+        first_tok = (count == 0) ? t : first_tok;
+        U += u;
         ++count;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
-          accK[i] = fmaf(w_prev, kprev[i], accK[i]);
-          accV[i] += vf[i];
-          kprev[i] = kf[i];
-          rprev[i] = rr[i];
+          accK[i] = fmaf(u, kf[i], accK[i]);
+          accV[i] += r_cur[i];                       // sum of (v - o); count * o is added at the end
         }
-        aprev = alpha_t;
-        own_prev = true;
-        cont = (mask_t != 0);
-        if (!cont) {                               // the slot ends at t
-          U += pend;
-#pragma unroll
-          for (int i = 0; i < EPL; ++i) accK[i] = fmaf(pend, kf[i], accK[i]);
+        if (mask_cur == 0) {                         // the slot ends at t
           if (is_head) {
             store_frag(sm_frag[group][0], accK, accV, U, count, first_tok);
             flags |= 1;
             is_head = false;
           } else {
-            finish(out_slot, accK, accV, U, count, first_tok, kraw, vraw);
+            finish(out_slot, accK, accV, U, count, first_tok, kraw, vraw_cur);
           }
           ++out_slot;
           U = 0.f;
@@ -304,27 +313,21 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 #pragma unroll
           for (int i = 0; i < EPL; ++i) { accK[i] = 0.f; accV[i] = 0.f; }
         }
+        Cprev = C;
+        ss_cur = ss_next;
+        alpha_cur = alpha_n;
+        mask_cur = mask_n;
+        vraw_cur = vraw_n;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) r_cur[i] = r_next[i];
       }
     }
-    if (cont) {                                    // the last token's weight still lacks C_{gb-1}
-      float vf[EPL];
-      Piece<T>::unpack(v_after, vf);
-      float sc = 0.f;
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        const float p = rprev[i] + (vf[i] - o[i]);
-        sc = fmaf(p, p, sc);
-      }
-      sc = group_sum<LPR>(sc);
-      const float u_prev = pend - aprev * a_after * __builtin_amdgcn_sqrtf(sc);
-      U += u_prev;
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) accK[i] = fmaf(u_prev, kprev[i], accK[i]);
+    if (count > 0) {                                 // a slot is still open at the end of the group
       store_frag(sm_frag[group][1], accK, accV, U, count, first_tok);
       if (is_head) {
-        flags |= 2;                                // the whole group lies inside one slot
+        flags |= 2;                                  // the whole group lies inside one slot
       } else {
-        flags |= 4;                                // the slot began in this group
+        flags |= 4;                                  // the slot began in this group
         tail_slot = out_slot;
       }
     }

@@ -57,20 +57,10 @@ struct SelectSmem {
   int ncand;
 };
 
-// Adds one to hist[d] for every active lane.  Neighbouring tokens have similar scores, so most lanes of
-// a wavefront want the same bin and a plain LDS atomic would serialise them: up to two groups of equal
-// digits are peeled off and added once by their first lane, the rest goes through individual atomics.
+// Adds one to hist[d] for every active lane.  (Peeling groups of equal digits off with ballots before
+// the atomics was measured and is slower than letting the LDS serialise equal addresses.)
 __device__ __forceinline__ void hist_add(int* hist, uint32_t d, bool act, int lane) {
-#pragma unroll
-  for (int peel = 0; peel < 2; ++peel) {
-    const uint64_t am = __ballot(act);
-    if (am == 0) return;
-    const int leader = __ffsll((long long)am) - 1;
-    const uint32_t d0 = __builtin_amdgcn_readlane(d, leader);
-    const uint64_t same = __ballot(act && d == d0);
-    if (lane == leader) atomicAdd(&hist[d0], __popcll(same));
-    act = act && (d != d0);
-  }
+  (void)lane;
   if (act) atomicAdd(&hist[d], 1);
 }
 
@@ -140,6 +130,7 @@ __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, con
       hist_add(sm.hist, k >> 21, i < E, lane);
     }
   }
+  if (cached && tid < 4 && E + tid < ((E + 3) & ~3)) sm.keys[E + tid] = 0xffffffffu;   // pad to groups of four
   __syncthreads();
   uint32_t prefix = 0, pmask = 0;
   int want = r;                        // rank (1-based) among the keys that share `prefix`
@@ -148,11 +139,28 @@ __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, con
   KVS_SSTAMP(2);
 
   // ---- the keys of that bin go to a short list; the remaining 21 bits are settled on the list
-  for (int i = tid; i < E; i += kSelThreads) {
-    const uint32_t k = cached ? sm.keys[i] : edge_key(a, lo + i);
-    if ((k & pmask) == prefix) {
-      const int pos = atomicAdd(&sm.ncand, 1);
-      if (pos < kCand) sm.cand[pos] = k;
+  // (cached keys are scanned four at a time with 16-byte LDS reads: a quarter of the loop overhead)
+  const uint4* k4 = reinterpret_cast<const uint4*>(sm.keys);
+  const int G = (E + 3) / 4;           // groups of four keys
+  if (cached) {
+    for (int g = tid; g < G; g += kSelThreads) {
+      const uint4 q = k4[g];
+      const uint32_t kk[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if ((kk[u] & pmask) == prefix && 4 * g + u < E) {
+          const int pos = atomicAdd(&sm.ncand, 1);
+          if (pos < kCand) sm.cand[pos] = kk[u];
+        }
+      }
+    }
+  } else {
+    for (int i = tid; i < E; i += kSelThreads) {
+      const uint32_t k = edge_key(a, lo + i);
+      if ((k & pmask) == prefix) {
+        const int pos = atomicAdd(&sm.ncand, 1);
+        if (pos < kCand) sm.cand[pos] = k;
+      }
     }
   }
   __syncthreads();
@@ -185,38 +193,118 @@ __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, con
   KVS_SSTAMP(4);
 
   // ---- ordered pass: every wavefront owns a contiguous range of edges
-  const int per = ((E + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
-  const int e0 = min(E, wave * per), e1 = min(E, e0 + per);
-  int n_lt = 0, n_eq = 0;
-  for (int i = e0 + lane; i < e1 + lane; i += kWave) {     // whole wavefront iterates together
-    uint32_t k = 0xffffffffu;
-    if (i < e1) k = cached ? sm.keys[i] : edge_key(a, lo + i);
-    n_lt += __popcll(__ballot(k < T));
-    n_eq += __popcll(__ballot(k == T && i < e1));
-  }
-  if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
-  __syncthreads();
-  KVS_SSTAMP(5);
-  int eq_before = 0, sel_before = 0;
-  for (int w = 0; w < wave; ++w) {
-    const int take = min(max(want - eq_before, 0), sm.eq[w]);
-    sel_before += sm.lt[w] + take;
-    eq_before += sm.eq[w];
-  }
-  for (int i = e0 + lane; i < e1 + lane; i += kWave) {
-    uint32_t k = 0xffffffffu;
-    if (i < e1) k = cached ? sm.keys[i] : edge_key(a, lo + i);
-    const bool is_eq = (k == T) && (i < e1);
-    const uint64_t beq = __ballot(is_eq);
-    const bool sel = (k < T) || (is_eq && (eq_before + lanes_below(beq, lane) < want));
-    const uint64_t bsel = __ballot(sel);
-    if (i < e1) {
-      const int m = lo + i;
-      mk[m] = sel ? 1 : 0;
-      sl[m] = m - (sel_before + lanes_below(bsel, lane));   // selected edges below token m
+  if (cached) {
+    // four consecutive keys per lane: wavefront w owns groups [g0, g1)
+    const int per_g = ((G + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
+    const int g0 = min(G, wave * per_g), g1 = min(G, g0 + per_g);
+    int n_lt = 0, n_eq = 0;
+    for (int g = g0 + lane; g < g1; g += kWave) {
+      const uint4 q = k4[g];
+      n_lt += (q.x < T) + (q.y < T) + (q.z < T) + (q.w < T);
+      n_eq += (q.x == T && 4 * g < E) + (q.y == T && 4 * g + 1 < E) + (q.z == T && 4 * g + 2 < E) +
+              (q.w == T && 4 * g + 3 < E);
     }
-    eq_before += __popcll(beq);
-    sel_before += __popcll(bsel);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      n_lt += __shfl_xor(n_lt, off, kWave);
+      n_eq += __shfl_xor(n_eq, off, kWave);
+    }
+    if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
+    __syncthreads();
+    KVS_SSTAMP(5);
+    int eq_before = 0, sel_before = 0;
+    for (int w = 0; w < wave; ++w) {
+      const int take = min(max(want - eq_before, 0), sm.eq[w]);
+      sel_before += sm.lt[w] + take;
+      eq_before += sm.eq[w];
+    }
+    const bool vec_ok = ((un.in_row + lo) & 3) == 0;       // 4-byte mask stores and 16-byte slot stores
+    for (int gb = g0; gb < g1; gb += kWave) {              // whole wavefront iterates together
+      const int g = gb + lane;
+      uint4 q = make_uint4(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
+      if (g < g1) q = k4[g];
+      const uint32_t kk[4] = {q.x, q.y, q.z, q.w};
+      bool sel[4], eq[4];
+      int lane_eq = 0;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        sel[u] = kk[u] < T;
+        eq[u] = (kk[u] == T) && (4 * g + u < E) && (g < g1);
+        lane_eq += eq[u];
+      }
+      if (__ballot(lane_eq != 0) != 0) {                  // ties with the threshold: rare, ranked in index order
+        int incl = lane_eq;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+          const int v = __shfl_up(incl, off, kWave);
+          if (lane >= off) incl += v;
+        }
+        int rank = eq_before + incl - lane_eq;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (eq[u]) { sel[u] = rank < want; ++rank; }
+        }
+        eq_before += __shfl(incl, kWave - 1, kWave);
+      }
+      const int lane_cnt = sel[0] + sel[1] + sel[2] + sel[3];
+      int incl = lane_cnt;
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const int v = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += v;
+      }
+      int below = sel_before + incl - lane_cnt;              // selected edges below this lane's first key
+      sel_before += __shfl(incl, kWave - 1, kWave);
+      if (g < g1) {
+        const int m0 = lo + 4 * g;
+        int s4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { s4[u] = m0 + u - below; below += sel[u]; }
+        if (vec_ok && 4 * g + 3 < E) {
+          *reinterpret_cast<uint32_t*>(mk + m0) =
+              (uint32_t)sel[0] | ((uint32_t)sel[1] << 8) | ((uint32_t)sel[2] << 16) | ((uint32_t)sel[3] << 24);
+          *reinterpret_cast<int4*>(sl + m0) = make_int4(s4[0], s4[1], s4[2], s4[3]);
+        } else {
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            if (4 * g + u < E) { mk[m0 + u] = sel[u] ? 1 : 0; sl[m0 + u] = s4[u]; }
+          }
+        }
+      }
+    }
+  } else {
+    const int per = ((E + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
+    const int e0 = min(E, wave * per), e1 = min(E, e0 + per);
+    int n_lt = 0, n_eq = 0;
+    for (int i = e0 + lane; i < e1 + lane; i += kWave) {     // whole wavefront iterates together
+      uint32_t k = 0xffffffffu;
+      if (i < e1) k = edge_key(a, lo + i);
+      n_lt += __popcll(__ballot(k < T));
+      n_eq += __popcll(__ballot(k == T && i < e1));
+    }
+    if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
+    __syncthreads();
+    int eq_before = 0, sel_before = 0;
+    for (int w = 0; w < wave; ++w) {
+      const int take = min(max(want - eq_before, 0), sm.eq[w]);
+      sel_before += sm.lt[w] + take;
+      eq_before += sm.eq[w];
+    }
+    for (int i = e0 + lane; i < e1 + lane; i += kWave) {
+      uint32_t k = 0xffffffffu;
+      if (i < e1) k = edge_key(a, lo + i);
+      const bool is_eq = (k == T) && (i < e1);
+      const uint64_t beq = __ballot(is_eq);
+      const bool sel = (k < T) || (is_eq && (eq_before + lanes_below(beq, lane) < want));
+      const uint64_t bsel = __ballot(sel);
+      if (i < e1) {
+        const int m = lo + i;
+        mk[m] = sel ? 1 : 0;
+        sl[m] = m - (sel_before + lanes_below(bsel, lane));   // selected edges below token m
+      }
+      eq_before += __popcll(beq);
+      sel_before += __popcll(bsel);
+    }
   }
   // tokens outside the eligible edge range
   for (int t = tid; t < lo && t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t; }
