@@ -379,6 +379,274 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   }
 }
 
+// Two 16-byte LDS reads at each of two addresses (offsets OFF0 and OFF1), complete on return.
+template <int OFF0, int OFF1>
+__device__ __forceinline__ void lds_read_2x2(bf16x8& b00, bf16x8& b01, bf16x8& b10, bf16x8& b11, uint32_t ad0,
+                                             uint32_t ad1) {
+  asm volatile(
+      "ds_read_b128 %0, %4 offset:%6\n\t"
+      "ds_read_b128 %1, %4 offset:%7\n\t"
+      "ds_read_b128 %2, %5 offset:%6\n\t"
+      "ds_read_b128 %3, %5 offset:%7\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(b00), "=&v"(b01), "=&v"(b10), "=&v"(b11)
+      : "v"(ad0), "v"(ad1), "n"(OFF0), "n"(OFF1)
+      : "memory");
+}
+
+// 65..128 query rows in ONE pass over K.  All 128 rows' operands plus the accumulators do not fit the
+// registers of a wavefront at two wavefronts per SIMD, so only rows 0..63 are register-stationary;
+// rows 64..127 stay in the workgroup's swizzled LDS copy of the Q block and are re-read for every
+// tile (16 KB of LDS reads per tile, hidden behind the MFMAs already in the pipe).  The K tile is
+// moved to registers whole (all k-steps) at the start of a tile, which frees its single LDS buffer
+// for the wavefront's next tile at once: that load flies during both halves' MFMAs and softmax work.
+template <int D, int PHASE>
+__global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
+    const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+    float* __restrict__ alpha_bar, float2* __restrict__ stats_part) {
+  constexpr int KS = D / 16;
+  constexpr int LPR = D / 8;
+  constexpr int RPI = kWave / LPR;
+  constexpr int NLD = kTile / RPI;
+  constexpr int ROWB = D * 2;
+  constexpr int TILEB = kTile * ROWB;
+  constexpr int QROWS = 128;                // query rows per wavefront (two halves of 64)
+  static_assert(KS == 4 || KS == 8, "operand reads come in groups of four");
+
+  __shared__ __attribute__((aligned(1024))) unsigned char sm_k[kWaves][TILEB];
+  __shared__ __attribute__((aligned(1024))) unsigned char sm_q[QROWS * ROWB];
+  __shared__ float sm_c[QROWS];
+  __shared__ float2 sm_stats[kWaves][QROWS];
+  __shared__ float2 sm_pair[2][128];
+
+  const int ui = find_unit(tab, blockIdx.x);
+  const Unit un = tab.u[ui];
+  const int chunk = blockIdx.x - un.chunk_base;
+  const int t0 = chunk * un.chunk_len;
+  const int t1 = min(un.len, t0 + un.chunk_len);
+  const int ntiles = (t1 - t0 + kTile - 1) / kTile;
+  const int iters = (ntiles + kWaves - 1) / kWaves;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int col = lane % 32, half = lane / 32;
+  const int R = sh.R;
+  const float sl2 = sh.scale_log2;
+  const size_t part_base = (size_t)un.index * kMaxChunks;
+
+  const unsigned char* Kg = reinterpret_cast<const unsigned char*>(K + (size_t)un.in_row * D);
+  const uint4* Qg = reinterpret_cast<const uint4*>(Q + (size_t)un.index * R * D);
+  unsigned char* my_k = sm_k[wave];
+  const int st_row = lane / LPR, st_slot = lane % LPR;
+
+  int ld_off[NLD];
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    const int row = st_row + i * RPI;
+    ld_off[i] = row * ROWB + (st_slot ^ (row % LPR)) * 16;
+  }
+  // LDS byte addresses of this lane's operand pieces: K tile row `col`, Q block row `col` (+ 32, 64, 96)
+  uint32_t a_addr[KS], q_addr[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    const uint32_t off = col * ROWB + ((2 * kk + half) ^ (col % LPR)) * 16;
+    a_addr[kk] = (uint32_t)(size_t)KVS_LDS_PTR(my_k) + off;
+    q_addr[kk] = (uint32_t)(size_t)KVS_LDS_PTR(sm_q) + off;
+  }
+  // the ragged last tile is moved back to end at the chunk's end, see score_mfma_kernel
+  auto issue_tile = [&](int j) {
+    const int tile_t0 = t0 + j * kTile;
+    if (tile_t0 >= t1) return false;
+    const int base_t = min(tile_t0, t1 - kTile);
+    const unsigned char* base = Kg + (size_t)base_t * ROWB;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]), KVS_LDS_PTR(my_k + i * 1024), 16, 0, 0);
+    }
+    return true;
+  };
+
+  if (PHASE == 1) finalize_stats(stats_part, part_base, un.n_chunks, R, sm_c, sm_pair);
+  // normalisers first: an ordinary LDS read after the loads below would wait for all of them
+  float cq[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b) cq[b] = (PHASE == 1 && b * 32 + col < R) ? sm_c[b * 32 + col] : INFINITY;
+
+  // the Q block, once per workgroup: every wavefront fetches 32 rows (rows past R repeat the last one)
+  {
+    constexpr int QLD = 32 / RPI;
+#pragma unroll
+    for (int i = 0; i < QLD; ++i) {
+      const int lr = wave * 32 + i * RPI + st_row;
+      const int qrow = min(lr, R - 1);
+      const int piece = st_slot ^ (lr % LPR);
+      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(Qg + (size_t)qrow * LPR + piece),
+                                       KVS_LDS_PTR(sm_q + (wave * 32 + i * RPI) * ROWB), 16, 0, 0);
+    }
+  }
+  // first K tile flies while Q lands; loads return in order, so leaving NLD in flight means Q is there
+  if (issue_tile(wave)) __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));
+  else __builtin_amdgcn_s_waitcnt(0x0F70);
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+
+  bf16x8 bq[2][KS];                         // rows 0..63, register-stationary
+#pragma unroll
+  for (int g = 0; g < KS / 4; ++g) {
+    lds_read_4x16<0>(bq[0][4 * g], bq[0][4 * g + 1], bq[0][4 * g + 2], bq[0][4 * g + 3], q_addr + 4 * g);
+    lds_read_4x16<32 * ROWB>(bq[1][4 * g], bq[1][4 * g + 1], bq[1][4 * g + 2], bq[1][4 * g + 3], q_addr + 4 * g);
+  }
+
+  float m_run[4], l_run[4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b) { m_run[b] = -INFINITY; l_run[b] = 0.f; }
+
+  for (int it = 0; it < iters; ++it) {
+    const int j = it * kWaves + wave;
+    const int tile_t0 = t0 + j * kTile;
+    if (tile_t0 >= t1) break;                       // this wavefront has run out of tiles
+    const int base_t = min(tile_t0, t1 - kTile);
+    const int shift = tile_t0 - base_t;             // leading rows that belong to the tile before
+
+    __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): this tile (nothing else is in flight)
+    asm volatile("" ::: "memory");
+    bf16x8 a[KS];
+#pragma unroll
+    for (int g = 0; g < KS / 4; ++g)
+      lds_read_4x16<0>(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3], a_addr + 4 * g);
+    issue_tile(j + kWaves);                         // the buffer is free again
+
+    float p[16];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      f32x16 acc[2];
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      if (h == 0) {
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+#pragma unroll
+          for (int nt = 0; nt < 2; ++nt)
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bq[nt][kk], kk == 0 ? zero : acc[nt], 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int kp = 0; kp < KS / 2; ++kp) {
+          bf16x8 b00, b01, b10, b11;
+          lds_read_2x2<64 * ROWB, 96 * ROWB>(b00, b01, b10, b11, q_addr[2 * kp], q_addr[2 * kp + 1]);
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp], b00, kp == 0 ? zero : acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp], b01, kp == 0 ? zero : acc[1], 0, 0, 0);
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp + 1], b10, acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp + 1], b11, acc[1], 0, 0, 0);
+        }
+      }
+      // accumulator element v of a lane: token row 8*(v/4) + 4*half + v%4, query column `col`
+      if (shift > 0) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = 8 * (v / 4) + 4 * half + (v % 4);
+          if (row < shift) { acc[0][v] = -INFINITY; acc[1][v] = -INFINITY; }
+        }
+      }
+      if (PHASE == 0) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+          const int b = 2 * h + nt;
+          float tm = acc[nt][0];
+#pragma unroll
+          for (int v = 1; v < 16; ++v) tm = fmaxf(tm, acc[nt][v]);
+          const float m_new = fmaxf(m_run[b], tm * sl2);
+          const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+          float s = 0.f;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) s += ex2(fmaf(acc[nt][v], sl2, -m_safe));
+          l_run[b] = l_run[b] * ex2(m_run[b] - m_safe) + s;
+          m_run[b] = m_new;
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float s = ex2(fmaf(acc[0][v], sl2, -cq[2 * h])) + ex2(fmaf(acc[1][v], sl2, -cq[2 * h + 1]));
+          p[v] = (h == 0) ? s : p[v] + s;
+        }
+      }
+    }
+
+    if (PHASE == 1) {
+      // sum over the 32 query columns of each half: reduce-scatter, lane bits 4..1 pick v
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const bool up = lane & 16;
+        const float send = up ? p[i] : p[i + 8];
+        const float keep = up ? p[i + 8] : p[i];
+        p[i] = keep + __shfl_xor(send, 16, kWave);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool up = lane & 8;
+        const float send = up ? p[i] : p[i + 4];
+        const float keep = up ? p[i + 4] : p[i];
+        p[i] = keep + __shfl_xor(send, 8, kWave);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const bool up = lane & 4;
+        const float send = up ? p[i] : p[i + 2];
+        const float keep = up ? p[i + 2] : p[i];
+        p[i] = keep + __shfl_xor(send, 4, kWave);
+      }
+      {
+        const bool up = lane & 2;
+        const float send = up ? p[0] : p[1];
+        const float keep = up ? p[1] : p[0];
+        p[0] = keep + __shfl_xor(send, 2, kWave);
+      }
+      p[0] += __shfl_xor(p[0], 1, kWave);
+      const int v = (lane >> 1) & 15;
+      const int row = 8 * (v / 4) + 4 * half + (v % 4);
+      if ((lane & 1) == 0 && row >= shift) alpha_bar[un.in_row + base_t + row] = p[0];
+    }
+  }
+
+  if (PHASE == 0) {
+    // the two halves of a wavefront hold the same query column for different token rows
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const float m_o = __shfl_xor(m_run[b], 32, kWave);
+      const float l_o = __shfl_xor(l_run[b], 32, kWave);
+      const float m_n = fmaxf(m_run[b], m_o);
+      const float m_s = (m_n == -INFINITY) ? 0.f : m_n;
+      l_run[b] = l_run[b] * ex2(m_run[b] - m_s) + l_o * ex2(m_o - m_s);
+      m_run[b] = m_n;
+      if (half == 0) sm_stats[wave][b * 32 + col] = make_float2(m_run[b], l_run[b]);
+    }
+    __syncthreads();
+    if (tid < R) {
+      float M = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm_stats[w][tid].x);
+      float Z = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float2 s = sm_stats[w][tid];
+        if (s.y > 0.f) Z += s.y * ex2(s.x - M);
+      }
+      stats_part[(part_base + chunk) * R + tid] = make_float2(M, Z);
+    }
+  }
+}
+
+template <int D>
+hipError_t launch_wide(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
+                       const Workspace& ws, hipStream_t stream) {
+  dim3 grid(tab.total_chunks), block(kThreads);
+  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
+                     (const uint16_t*)K, alpha_bar, ws.stats_part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
+                     (const uint16_t*)K, alpha_bar, ws.stats_part);
+  return hipGetLastError();
+}
+
 template <int D, int NT, int WQ>
 hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
                     const Workspace& ws, hipStream_t stream) {
@@ -400,7 +668,8 @@ hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const 
   // every spill reload waits for ALL loads in flight, the tile prefetch included.
   const int R = sh.R;
   if (R <= 32) return launch_t<D, 1, 1>(tab, sh, Q, K, alpha_bar, ws, stream);
-  if (R <= 128) return launch_t<D, 2, 1>(tab, sh, Q, K, alpha_bar, ws, stream);    // above 64 rows: two passes
+  if (R <= 64) return launch_t<D, 2, 1>(tab, sh, Q, K, alpha_bar, ws, stream);
+  if (R <= 128) return launch_wide<D>(tab, sh, Q, K, alpha_bar, ws, stream);      // rows 64.. from LDS, one pass
   if (R <= 256) return launch_t<D, 2, 2>(tab, sh, Q, K, alpha_bar, ws, stream);    // two passes of 128 rows
   return launch_t<D, 2, 4>(tab, sh, Q, K, alpha_bar, ws, stream);                  // passes of 256 rows
 }
