@@ -156,9 +156,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   }
 
   // One finished slot -> global memory (all lanes of the group call it together).  `raw_*` are the
-  // untouched rows of the slot's last token: a slot of one token is copied bit for bit.
   auto finish = [&](int out_slot, const float* accK, const float* accV, float U, int count, int first_tok,
-                    const uint4& raw_k, const uint4& raw_v) {
+                    const uint4& raw_k) {
     float outk[EPL];
     if (U > 0.f && U < INFINITY) {
       const float inv = __builtin_amdgcn_rcpf(U);
@@ -177,11 +176,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 #pragma unroll
       for (int i = 0; i < EPL; ++i) outk[i] *= inv;
     }
-    float outv[EPL];
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) outv[i] = fmaf((float)count, o[i], accV[i]);   // accV sums (v - o_bar)
-    uint4 ok = Piece<T>::pack(outk), ov = Piece<T>::pack(outv);
-    if (count == 1) { ok = raw_k; ov = raw_v; }
+    uint4 ok = Piece<T>::pack(outk);
+    const uint4 ov = Piece<T>::pack(accV);       // a single row converts back to its own bits
+    if (count == 1) ok = raw_k;
     if ((unsigned)out_slot < (unsigned)un.n_out) {   // a slot map from outside the library is not trusted
       Ko[(size_t)out_slot * LPR] = ok;
       Vo[(size_t)out_slot * LPR] = ov;
@@ -213,36 +210,39 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     const int last_v = min(gb, n - 1);
     const int out_slot0 = sl[ga];                    // slots are numbered consecutively from here
 
+    // kPrefetch register sets (K row, the Value row one token later, its alpha and edge bit), used in
+    // rotation by an equally unrolled loop: a set is refilled for token t + kPrefetch at the end of
+    // the step that consumed it, so no set is ever copied and a step waits for its own set only.
     uint4 rk[kPrefetch], rv[kPrefetch];
     float ra[kPrefetch];
-    int rm[kPrefetch];
-#pragma unroll
-    for (int j = 0; j < kPrefetch; ++j) {
-      rk[j] = Kp[(size_t)min(ga + j, gb - 1) * LPR];
-      const int tv = min(ga + 1 + j, last_v);
+    uint8_t rm[kPrefetch];          // kept as loaded: widening at the load would wait for it there
+    auto refill = [&](int j, int t) {                // the set that token t will consume
+      rk[j] = Kp[(size_t)min(t, gb - 1) * LPR];
+      const int tv = min(t + 1, last_v);
       rv[j] = Vp[(size_t)tv * LPR];
       ra[j] = al[tv];
       rm[j] = mk[tv];
-    }
-    uint4 vraw_cur = Vp[(size_t)ga * LPR];
+    };
+#pragma unroll
+    for (int j = 0; j < kPrefetch; ++j) refill(j, ga + j);
+    const uint4 vraw_first = Vp[(size_t)ga * LPR];
     float alpha_cur = al[ga];
-    int mask_cur = mk[ga];
+    uint32_t mask_cur = mk[ga];
 
-    float r_cur[EPL], accK[EPL], accV[EPL];
+    float v_cur[EPL], r_cur[EPL], accK[EPL], accV[EPL];
     float ss_cur = 0.f, Cprev = 0.f, U = 0.f;
     int count = 0, first_tok = ga, out_slot = out_slot0;
     bool is_head = head_open;       // the open slot began before this group
     {
-      float vf[EPL];
-      Piece<T>::unpack(vraw_cur, vf);
+      Piece<T>::unpack(vraw_first, v_cur);
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
-        r_cur[i] = vf[i] - o[i];
+        r_cur[i] = v_cur[i] - o[i];
         ss_cur = fmaf(r_cur[i], r_cur[i], ss_cur);
         accK[i] = 0.f;
         accV[i] = 0.f;
       }
-      float sc = 0.f;
+      float dot = 0.f, ss_b = 0.f;
       float a_before = 0.f;
       if (head_open) {                               // C_{ga-1} from the row before the group
         float vb[EPL];
@@ -250,77 +250,83 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
         a_before = al[ga - 1];
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
-          const float p = (vb[i] - o[i]) + r_cur[i];
-          sc = fmaf(p, p, sc);
+          const float rb = vb[i] - o[i];
+          ss_b = fmaf(rb, rb, ss_b);
+          dot = fmaf(rb, r_cur[i], dot);
         }
       }
       ss_cur = group_sum<LPR>(ss_cur);
-      sc = group_sum<LPR>(sc);
-      Cprev = a_before * alpha_cur * __builtin_amdgcn_sqrtf(sc);
+      ss_b = group_sum<LPR>(ss_b);
+      dot = group_sum<LPR>(dot);
+      Cprev = a_before * alpha_cur * __builtin_amdgcn_sqrtf(fmaxf(fmaf(2.f, dot, ss_b + ss_cur), 0.f));
     }
 
-    for (int t0 = ga; t0 < gb; t0 += kPrefetch) {
+    // One token.  The same straight-line code for every token: lane groups of a wavefront stay converged.
+    auto step = [&](int t, int j) {
+      const uint4 kraw = rk[j], vraw_n = rv[j];
+      // alpha and the edge bit outlive this step (they are the next step's current token): move them
+      // out of the set here, or the refill below is given other registers and copied back after a wait
+      float alpha_n;
+      uint32_t mask_n;
+      asm volatile("v_mov_b32 %0, %2\n\tv_mov_b32 %1, %3"
+                   : "=&v"(alpha_n), "=&v"(mask_n)
+                   : "v"(ra[j]), "v"((uint32_t)rm[j]));
+      float kf[EPL], vn[EPL], r_next[EPL];
+      Piece<T>::unpack(kraw, kf);
+      Piece<T>::unpack(vraw_n, vn);
+      // ||r_t + r_{t+1}||^2 = ||r_t||^2 + ||r_{t+1}||^2 + 2 r_t . r_{t+1}
+      float ss_next = 0.f, dot = 0.f;
 #pragma unroll
-      for (int j = 0; j < kPrefetch; ++j) {
-        const int t = t0 + j;
-        if (t >= gb) break;
-        const uint4 kraw = rk[j], vraw_n = rv[j];
-        const float alpha_n = ra[j];
-        const int mask_n = rm[j];
-        {
-          rk[j] = Kp[(size_t)min(t + kPrefetch, gb - 1) * LPR];
-          const int tv = min(t + 1 + kPrefetch, last_v);
-          rv[j] = Vp[(size_t)tv * LPR];
-          ra[j] = al[tv];
-          rm[j] = mk[tv];
-        }
-        // the same straight-line code for every token: lane groups of a wavefront stay converged
-        float kf[EPL], vn[EPL], r_next[EPL];
-        Piece<T>::unpack(kraw, kf);
-        Piece<T>::unpack(vraw_n, vn);
-        float ss_next = 0.f, sc = 0.f;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) {
-          r_next[i] = vn[i] - o[i];
-          ss_next = fmaf(r_next[i], r_next[i], ss_next);
-          const float p = r_cur[i] + r_next[i];
-          sc = fmaf(p, p, sc);
-        }
-        ss_next = group_sum<LPR>(ss_next);
-        sc = group_sum<LPR>(sc);
-        const float Anorm = alpha_cur * fabsf(1.f - 2.f * alpha_cur) * __builtin_amdgcn_sqrtf(ss_cur);
-        const float C = mask_cur ? alpha_cur * alpha_n * __builtin_amdgcn_sqrtf(sc) : 0.f;
-        const float u = Anorm - Cprev - C;
-        first_tok = (count == 0) ? t : first_tok;
-        U += u;
-        ++count;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) {
-          accK[i] = fmaf(u, kf[i], accK[i]);
-          accV[i] += r_cur[i];                       // sum of (v - o); count * o is added at the end
-        }
-        if (mask_cur == 0) {                         // the slot ends at t
-          if (is_head) {
-            store_frag(sm_frag[group][0], accK, accV, U, count, first_tok);
-            flags |= 1;
-            is_head = false;
-          } else {
-            finish(out_slot, accK, accV, U, count, first_tok, kraw, vraw_cur);
-          }
-          ++out_slot;
-          U = 0.f;
-          count = 0;
-#pragma unroll
-          for (int i = 0; i < EPL; ++i) { accK[i] = 0.f; accV[i] = 0.f; }
-        }
-        Cprev = C;
-        ss_cur = ss_next;
-        alpha_cur = alpha_n;
-        mask_cur = mask_n;
-        vraw_cur = vraw_n;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) r_cur[i] = r_next[i];
+      for (int i = 0; i < EPL; ++i) {
+        r_next[i] = vn[i] - o[i];
+        ss_next = fmaf(r_next[i], r_next[i], ss_next);
+        dot = fmaf(r_cur[i], r_next[i], dot);
       }
+      ss_next = group_sum<LPR>(ss_next);
+      dot = group_sum<LPR>(dot);
+      const float Anorm = alpha_cur * fabsf(1.f - 2.f * alpha_cur) * __builtin_amdgcn_sqrtf(ss_cur);
+      const float pair2 = fmaxf(fmaf(2.f, dot, ss_cur + ss_next), 0.f);
+      const float C = mask_cur ? alpha_cur * alpha_n * __builtin_amdgcn_sqrtf(pair2) : 0.f;
+      const float u = Anorm - Cprev - C;
+      first_tok = (count == 0) ? t : first_tok;
+      U += u;
+      ++count;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        accK[i] = fmaf(u, kf[i], accK[i]);
+        accV[i] += v_cur[i];
+      }
+      if (mask_cur == 0) {                           // the slot ends at t
+        if (is_head) {
+          store_frag(sm_frag[group][0], accK, accV, U, count, first_tok);
+          flags |= 1;
+          is_head = false;
+        } else {
+          finish(out_slot, accK, accV, U, count, first_tok, kraw);
+        }
+        ++out_slot;
+        U = 0.f;
+        count = 0;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) { accK[i] = 0.f; accV[i] = 0.f; }
+      }
+      refill(j, t + kPrefetch);
+      Cprev = C;
+      ss_cur = ss_next;
+      alpha_cur = alpha_n;
+      mask_cur = mask_n;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) { r_cur[i] = r_next[i]; v_cur[i] = vn[i]; }
+    };
+
+    int t = ga;
+    for (; t + kPrefetch <= gb; t += kPrefetch) {
+#pragma unroll
+      for (int j = 0; j < kPrefetch; ++j) step(t + j, j);
+    }
+#pragma unroll
+    for (int j = 0; j < kPrefetch - 1; ++j) {
+      if (t + j < gb) step(t + j, j);
     }
     if (count > 0) {                                 // a slot is still open at the end of the group
       store_frag(sm_frag[group][1], accK, accV, U, count, first_tok);
@@ -354,7 +360,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       count += __float_as_int(h[2 * D + 1]);
       if (fl & 1) break;                           // the slot ended in group g
     }
-    finish(tail_slot, accK, accV, U, count, first_tok, make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0));
+    finish(tail_slot, accK, accV, U, count, first_tok, make_uint4(0, 0, 0, 0));
   }
 }
 
