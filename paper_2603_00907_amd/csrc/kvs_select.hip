@@ -52,8 +52,9 @@ struct SelectSmem {
   uint32_t cand[kCand];
   int hist[kBins];
   int wave[kSelWaves];
-  int pick[2];           // digit, keys below it
+  int pick[3];           // digit, keys below it, keys in it
   int lt[kSelWaves], eq[kSelWaves];
+  uint32_t wmin[kSelWaves], wmax[kSelWaves];
   int ncand;
 };
 
@@ -64,30 +65,399 @@ __device__ __forceinline__ void hist_add(int* hist, uint32_t d, bool act, int la
   if (act) atomicAdd(&hist[d], 1);
 }
 
+// Inclusive prefix sum over the 64 lanes with DPP moves only (no LDS crossbar): four shifts inside
+// every row of 16 lanes, then the last lane of row 0 / row 2 is broadcast into the next row, then
+// lane 31 into the upper half.
+__device__ __forceinline__ int wave_incl_scan(int x) {
+  x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xF, 0xF, true);    // row_shr:1
+  x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xF, 0xF, true);    // row_shr:2
+  x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xF, 0xF, true);    // row_shr:4
+  x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xF, 0xF, true);    // row_shr:8
+  x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+  x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
+// Sum of x[w] over the wavefronts before wavefront `wave` (x: kSelWaves ints in LDS): lanes 0..15 take
+// one entry each and scan them inside their DPP row.
+__device__ __forceinline__ int waves_before(const int* x, int wave, int lane) {
+  static_assert(kSelWaves == 16, "one DPP row");
+  int v = lane < kSelWaves ? x[lane] : 0;
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);
+  const int idx = __builtin_amdgcn_readfirstlane(wave);
+  return idx ? __builtin_amdgcn_readlane(v, idx - 1) : 0;
+}
+
 // Exclusive scan of the histogram (two bins per thread); finds the bin that holds rank `want`
-// (1-based) and extends (prefix, pmask, want) by that digit.
-__device__ __forceinline__ void pick_bin(SelectSmem& sm, int shift, int bins, uint32_t& prefix, uint32_t& pmask,
-                                         int& want) {
+// (1-based), extends (prefix, pmask, want) by that digit and returns the number of keys in the bin.
+__device__ __forceinline__ int pick_bin(SelectSmem& sm, int shift, int bins, uint32_t& prefix, uint32_t& pmask,
+                                        int& want) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int h0 = sm.hist[2 * tid], h1 = sm.hist[2 * tid + 1];
-  int incl = h0 + h1;
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const int v = __shfl_up(incl, off, kWave);
-    if (lane >= off) incl += v;
-  }
+  const int incl = wave_incl_scan(h0 + h1);
   if (lane == kWave - 1) sm.wave[wave] = incl;
   __syncthreads();
-  int base = 0;
-  for (int w = 0; w < wave; ++w) base += sm.wave[w];
+  const int base = waves_before(sm.wave, wave, lane);
   const int excl = base + incl - (h0 + h1);
-  if (want > excl && want <= excl + h0) { sm.pick[0] = 2 * tid; sm.pick[1] = excl; }
-  else if (want > excl + h0 && want <= excl + h0 + h1) { sm.pick[0] = 2 * tid + 1; sm.pick[1] = excl + h0; }
+  if (want > excl && want <= excl + h0) { sm.pick[0] = 2 * tid; sm.pick[1] = excl; sm.pick[2] = h0; }
+  else if (want > excl + h0 && want <= excl + h0 + h1) { sm.pick[0] = 2 * tid + 1; sm.pick[1] = excl + h0; sm.pick[2] = h1; }
   __syncthreads();
   prefix |= (uint32_t)sm.pick[0] << shift;
   pmask |= (uint32_t)(bins - 1) << shift;
   want -= sm.pick[1];
+  const int in_bin = sm.pick[2];
   __syncthreads();
+  return in_bin;
+}
+
+// Minimum / maximum over the 64 lanes (same DPP walk as the scan; lane 63 ends up with the result).
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x) {
+  const int id = -1;
+  x = min(x, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)x, 0x111, 0xF, 0xF, false));
+  x = min(x, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)x, 0x112, 0xF, 0xF, false));
+  x = min(x, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)x, 0x114, 0xF, 0xF, false));
+  x = min(x, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)x, 0x118, 0xF, 0xF, false));
+  x = min(x, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)x, 0x142, 0xA, 0xF, false));
+  x = min(x, (uint32_t)__builtin_amdgcn_update_dpp(id, (int)x, 0x143, 0xC, 0xF, false));
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, kWave - 1);
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+  x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xF, 0xF, false));
+  x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xF, 0xF, false));
+  x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xF, 0xF, false));
+  x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xF, 0xF, false));
+  x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xA, 0xF, false));
+  x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xC, 0xF, false));
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, kWave - 1);
+}
+
+// Select for a unit whose keys fit the LDS.  Key i' belongs to the edge after token lo_al + i', where
+// lo_al <= lo is the first token whose alpha_bar element sits on a 16-byte boundary: groups of four
+// keys then coincide with aligned groups of four elements of alpha_bar, edge_mask and slot.  Keys
+// of tokens outside [lo, hi] are 0xffffffff: no threshold reaches them.  One CU does all of this,
+// so the instruction count per key is what matters: groups that lie wholly inside [lo, hi] (all but
+// the first and the last) take paths without per-key checks.
+__device__ __forceinline__ void select_unit_cached(const Unit& un, const float* __restrict__ a,
+                                                   uint8_t* __restrict__ mk, int32_t* __restrict__ sl, SelectSmem& sm,
+                                                   int lo, int hi, int r) {
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int n = un.len;
+  const int pad0 = (int)((un.in_row + lo) & 3);
+  const int lo_al = lo - pad0;
+  const int G = (hi - lo_al + 4) / 4;              // groups of four keys, at most kLdsKeys / 4
+  constexpr int GPT = kLdsKeys / 4 / kSelThreads;  // groups per thread
+  constexpr uint32_t kNone = 0xffffffffu;
+  uint4* k4 = reinterpret_cast<uint4*>(sm.keys);
+  KVS_SSTAMP(0);
+
+  // ---- keys and the histogram of their first digit: all of a thread's loads are in flight together
+  for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
+  if (tid == 0) sm.ncand = 0;
+  __syncthreads();
+  KVS_SSTAMP(7);
+  {
+    float4 v[GPT];
+    float nx[GPT];
+#pragma unroll
+    for (int u = 0; u < GPT; ++u) {
+      const int g = u * kSelThreads + tid;
+      const int m0 = lo_al + 4 * g;                // may lie up to 3 tokens before the unit: still alpha_bar
+      v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      nx[u] = 0.f;
+      if (m0 >= lo && m0 + 3 <= hi) {              // hi <= n - 2: element m0 + 4 exists
+        v[u] = *reinterpret_cast<const float4*>(a + m0);
+        nx[u] = a[m0 + 4];
+      } else if (g < G) {                          // first or last group: nothing is read past the unit's end
+        v[u].x = a[min(m0, n - 1)];
+        v[u].y = a[min(m0 + 1, n - 1)];
+        v[u].z = a[min(m0 + 2, n - 1)];
+        v[u].w = a[min(m0 + 3, n - 1)];
+        nx[u] = a[min(m0 + 4, n - 1)];
+      }
+    }
+    // raw keys, their minimum and maximum
+    uint32_t k[GPT][4];
+    uint32_t kmin = kNone, kmax = 0;
+#pragma unroll
+    for (int u = 0; u < GPT; ++u) {
+      const int g = u * kSelThreads + tid;
+      const int m0 = lo_al + 4 * g;
+      k[u][0] = __float_as_uint(v[u].x + v[u].y);
+      k[u][1] = __float_as_uint(v[u].y + v[u].z);
+      k[u][2] = __float_as_uint(v[u].z + v[u].w);
+      k[u][3] = __float_as_uint(v[u].w + nx[u]);
+      if (m0 >= lo && m0 + 3 <= hi) {
+        kmin = min(kmin, min(min(k[u][0], k[u][1]), min(k[u][2], k[u][3])));
+        kmax = max(kmax, max(max(k[u][0], k[u][1]), max(k[u][2], k[u][3])));
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const bool ok = (g < G) && (m0 + j >= lo) && (m0 + j <= hi);
+          k[u][j] = ok ? k[u][j] : kNone;
+          kmin = min(kmin, k[u][j]);
+          kmax = max(kmax, ok ? k[u][j] : 0u);
+        }
+      }
+    }
+    KVS_SSTAMP(8);
+#ifdef KVS_TRACE_SEL
+    if (tid == 15 * 64) g_trace_sel[blockIdx.x * 16 + 13] = clock64();
+    if (tid == 8 * 64) g_trace_sel[blockIdx.x * 16 + 14] = clock64();
+#endif
+    kmin = wave_min_u32(kmin);
+    kmax = wave_max_u32(kmax);
+    if (lane == 0) { sm.wmin[wave] = kmin; sm.wmax[wave] = kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) { kmin = min(kmin, sm.wmin[w]); kmax = max(kmax, sm.wmax[w]); }
+    // Keys are ranked as (key - kmin) << lshift, the span stretched to 31 bits: monotone, and the
+    // first digit then separates neighbouring tokens' keys, which mostly share their top IEEE bits
+    // (equal digits in one wavefront instruction serialise in the LDS atomics).  Bit 31 stays clear,
+    // so the out-of-range marker shares no digit with a real key.
+    const uint32_t span = kmax - kmin;             // < 2^31: the keys are bit patterns of non-negative floats
+    const int lshift = span ? __clz(span) - 1 : 0;
+#pragma unroll
+    for (int u = 0; u < GPT; ++u) {
+      const int g = u * kSelThreads + tid;
+      const int m0 = lo_al + 4 * g;
+      if (m0 >= lo && m0 + 3 <= hi) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          k[u][j] = (k[u][j] - kmin) << lshift;
+          atomicAdd(&sm.hist[k[u][j] >> 21], 1);
+        }
+        k4[g] = make_uint4(k[u][0], k[u][1], k[u][2], k[u][3]);
+      } else if (g < G) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (k[u][j] != kNone) {
+            k[u][j] = (k[u][j] - kmin) << lshift;
+            atomicAdd(&sm.hist[k[u][j] >> 21], 1);
+          }
+        }
+        k4[g] = make_uint4(k[u][0], k[u][1], k[u][2], k[u][3]);
+      }
+    }
+  }
+  KVS_SSTAMP(9);
+  __syncthreads();
+  uint32_t prefix = 0, pmask = 0;
+  int want = r;                        // rank (1-based) among the keys that share `prefix`
+  KVS_SSTAMP(1);
+  pick_bin(sm, 21, 2048, prefix, pmask, want);
+  KVS_SSTAMP(2);
+
+  // ---- the keys of that bin go to a short list (one LDS atomic per wavefront: every lane counts its
+  //      matches, a scan gives it its place); the remaining 21 bits are settled on the list
+  {
+    uint4 q[GPT];
+    int c = 0;
+#pragma unroll
+    for (int u = 0; u < GPT; ++u) {
+      const int g = u * kSelThreads + tid;
+      q[u] = make_uint4(kNone, kNone, kNone, kNone);
+      if (g < G) q[u] = k4[g];
+      c += (((q[u].x ^ prefix) >> 21) == 0) + (((q[u].y ^ prefix) >> 21) == 0) + (((q[u].z ^ prefix) >> 21) == 0) +
+           (((q[u].w ^ prefix) >> 21) == 0);
+    }
+    const int incl = wave_incl_scan(c);
+    const int tot = __builtin_amdgcn_readlane(incl, kWave - 1);
+    if (tot > 0) {                                 // wavefront-uniform
+      int base = 0;
+      if (lane == 0) base = atomicAdd(&sm.ncand, tot);
+      int pos = __builtin_amdgcn_readfirstlane(base) + incl - c;
+      if (c > 0) {
+#pragma unroll
+        for (int u = 0; u < GPT; ++u) {
+          const uint32_t kk[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            if (((kk[j] ^ prefix) >> 21) == 0) {
+              if (pos < kCand) sm.cand[pos] = kk[j];
+              ++pos;
+            }
+          }
+        }
+      }
+    }
+  }
+  KVS_SSTAMP(10);
+  __syncthreads();
+  const int ncand = sm.ncand;
+  KVS_SSTAMP(3);
+#ifdef KVS_TRACE_SEL
+  if (tid == 0) g_trace_sel[blockIdx.x * 16 + 12] = ncand;
+#endif
+  int n_equal;                         // keys equal to the threshold
+  if (ncand <= kWave) {
+    // A handful of candidates: all against all.  Lane i of every wavefront holds candidate i, wavefront
+    // w compares with candidates 4w..4w+3 (one LDS address per read: a broadcast), and the partial
+    // counts meet in LDS.  Ties go by list position: equal keys are interchangeable here, only the
+    // counts below and at the threshold matter.
+    int* below = sm.hist;              // the histogram is idle now
+    int* same = sm.hist + kWave;
+    int* before = sm.hist + 2 * kWave;
+    if (tid < 3 * kWave) sm.hist[tid] = 0;
+    __syncthreads();
+    const uint32_t c = lane < ncand ? sm.cand[lane] : kNone;
+    int b = 0, e = 0, f = 0;
+#pragma unroll
+    for (int jj = 0; jj < kWave / kSelWaves; ++jj) {
+      const int j = wave * (kWave / kSelWaves) + jj;
+      const uint32_t cj = j < ncand ? sm.cand[j] : kNone;
+      b += cj < c;
+      e += cj == c;
+      f += (cj == c) & (j < lane);
+    }
+    if (lane < ncand) {
+      if (b) atomicAdd(&below[lane], b);
+      if (e) atomicAdd(&same[lane], e);
+      if (f) atomicAdd(&before[lane], f);
+    }
+    __syncthreads();
+    if (tid < ncand && below[tid] + before[tid] == want - 1) {
+      sm.pick[0] = (int)c;
+      sm.pick[1] = below[tid];
+      sm.pick[2] = same[tid];
+    }
+    __syncthreads();
+    prefix = (uint32_t)sm.pick[0];
+    want -= sm.pick[1];
+    n_equal = sm.pick[2];
+  } else {
+    const bool listed = (ncand <= kCand);
+    const int shifts[2] = {10, 0};
+    const int widths[2] = {11, 10};
+    n_equal = 0;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int shift = shifts[pass];
+      const int bins = 1 << widths[pass];
+      for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
+      __syncthreads();
+      if (listed) {
+        for (int i = tid; i < ncand; i += kSelThreads) {
+          const uint32_t k = sm.cand[i];
+          if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
+        }
+      } else {                            // a bin too crowded for the list: full passes over the keys
+        for (int i = tid; i < 4 * G; i += kSelThreads) {
+          const uint32_t k = sm.keys[i];
+          if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
+        }
+      }
+      __syncthreads();
+      n_equal = pick_bin(sm, shift, bins, prefix, pmask, want);
+    }
+  }
+  const uint32_t T = prefix;           // `want` keys equal to T are taken, the lowest indices first
+  // When every key equal to T is taken (nearly always: T is then the only one), "selected" is simply
+  // "below T + 1" and nothing has to be ranked.
+  const bool simple = (n_equal == want);
+  const uint32_t Tc = simple ? T + 1 : T;
+  KVS_SSTAMP(4);
+
+  // ---- ordered pass: wavefront w owns the groups [g0, g1), lane l the groups g0 + it * 64 + l
+  constexpr int ITS = kLdsKeys / 4 / kSelWaves / kWave;      // rounds per wavefront
+  const int per_g = ((G + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
+  const int g0 = min(G, wave * per_g), g1 = min(G, g0 + per_g);
+  uint4 q[ITS];
+  int n_lt = 0, n_eq = 0;               // wavefront totals: keys below Tc, keys equal to T (if they matter)
+#pragma unroll
+  for (int it = 0; it < ITS; ++it) {
+    const int g = g0 + it * kWave + lane;
+    q[it] = make_uint4(kNone, kNone, kNone, kNone);
+    if (g < g1) q[it] = k4[g];
+    n_lt += __popcll(__ballot(q[it].x < Tc)) + __popcll(__ballot(q[it].y < Tc)) + __popcll(__ballot(q[it].z < Tc)) +
+            __popcll(__ballot(q[it].w < Tc));
+  }
+  if (!simple) {
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) {
+      n_eq += __popcll(__ballot(q[it].x == T)) + __popcll(__ballot(q[it].y == T)) + __popcll(__ballot(q[it].z == T)) +
+              __popcll(__ballot(q[it].w == T));
+    }
+  }
+  if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
+  __syncthreads();
+  KVS_SSTAMP(5);
+  int eq_before = 0, sel_before = waves_before(sm.lt, wave, lane);
+  if (!simple) {
+    for (int w = 0; w < wave; ++w) {
+      const int e = sm.eq[w];
+      sel_before += min(max(want - eq_before, 0), e);
+      eq_before += e;
+    }
+  }
+
+  // Four tokens' mask bytes and slots; whole groups inside [lo, hi] go out as one 4-byte and one
+  // 16-byte store.  `below`: selected edges before the group's first token.
+  auto write_group = [&](int g, const bool* sel, int below) {
+    const int m0 = lo_al + 4 * g;
+    int s4[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { s4[j] = m0 + j - below; below += sel[j]; }
+    if (m0 >= lo && m0 + 3 <= hi) {
+      *reinterpret_cast<uint32_t*>(mk + m0) =
+          (uint32_t)sel[0] | ((uint32_t)sel[1] << 8) | ((uint32_t)sel[2] << 16) | ((uint32_t)sel[3] << 24);
+      *reinterpret_cast<int4*>(sl + m0) = make_int4(s4[0], s4[1], s4[2], s4[3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (m0 + j >= lo && m0 + j <= hi) { mk[m0 + j] = sel[j] ? 1 : 0; sl[m0 + j] = s4[j]; }
+      }
+    }
+  };
+
+  if (n_eq == 0) {
+    // nothing to rank in this wavefront (the usual case): all rounds' scans at once
+    int cnt[ITS], incl[ITS];
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) {
+      cnt[it] = (q[it].x < Tc) + (q[it].y < Tc) + (q[it].z < Tc) + (q[it].w < Tc);
+      incl[it] = wave_incl_scan(cnt[it]);
+    }
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) {
+      const int g = g0 + it * kWave + lane;
+      const bool sel[4] = {q[it].x < Tc, q[it].y < Tc, q[it].z < Tc, q[it].w < Tc};
+      if (g < g1) write_group(g, sel, sel_before + incl[it] - cnt[it]);
+      sel_before += __builtin_amdgcn_readlane(incl[it], kWave - 1);
+    }
+  } else {
+    // ties with the threshold: ranked in index order, round by round
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) {
+      const int g = g0 + it * kWave + lane;
+      const uint32_t kk[4] = {q[it].x, q[it].y, q[it].z, q[it].w};
+      bool sel[4], eq[4];
+      int lane_eq = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        sel[j] = kk[j] < T;
+        eq[j] = kk[j] == T;
+        lane_eq += eq[j];
+      }
+      const int incl_eq = wave_incl_scan(lane_eq);
+      int rank = eq_before + incl_eq - lane_eq;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (eq[j]) { sel[j] = rank < want; ++rank; }
+      }
+      eq_before += __builtin_amdgcn_readlane(incl_eq, kWave - 1);
+      const int lane_cnt = sel[0] + sel[1] + sel[2] + sel[3];
+      const int incl = wave_incl_scan(lane_cnt);
+      if (g < g1) write_group(g, sel, sel_before + incl - lane_cnt);
+      sel_before += __builtin_amdgcn_readlane(incl, kWave - 1);
+    }
+  }
+  // tokens outside the eligible edge range
+  for (int t = tid; t < lo && t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t; }
+  for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
+  KVS_SSTAMP(6);
 }
 
 __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, const float* __restrict__ alpha_bar,
@@ -106,67 +476,19 @@ __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, con
     for (int t = tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t; }
     return;
   }
-  const bool cached = (E <= kLdsKeys);
-  KVS_SSTAMP(0);
-
-  // ---- keys (to LDS when they fit) and the histogram of their top 11 bits, four keys per thread at a
-  //      time with the loads batched
-  for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
-  if (tid == 0) sm.ncand = 0;
-  __syncthreads();
-  for (int base = 0; base < E; base += 4 * kSelThreads) {
-    float x[4], y[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int m = lo + min(base + u * kSelThreads + tid, E - 1);
-      x[u] = a[m];
-      y[u] = a[m + 1];
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int i = base + u * kSelThreads + tid;
-      const uint32_t k = __float_as_uint(x[u] + y[u]);
-      if (cached && i < E) sm.keys[i] = k;
-      hist_add(sm.hist, k >> 21, i < E, lane);
-    }
+  if (E + 6 <= kLdsKeys) {             // with the padding to aligned groups of four at both ends
+    select_unit_cached(un, a, mk, sl, sm, lo, hi, r);
+    return;
   }
-  if (cached && tid < 4 && E + tid < ((E + 3) & ~3)) sm.keys[E + tid] = 0xffffffffu;   // pad to groups of four
+
+  // ---- longer units: every pass recomputes the keys from alpha_bar (L2-resident)
+  for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
+  __syncthreads();
+  for (int i = tid; i < E; i += kSelThreads) atomicAdd(&sm.hist[edge_key(a, lo + i) >> 21], 1);
   __syncthreads();
   uint32_t prefix = 0, pmask = 0;
   int want = r;                        // rank (1-based) among the keys that share `prefix`
-  KVS_SSTAMP(1);
   pick_bin(sm, 21, 2048, prefix, pmask, want);
-  KVS_SSTAMP(2);
-
-  // ---- the keys of that bin go to a short list; the remaining 21 bits are settled on the list
-  // (cached keys are scanned four at a time with 16-byte LDS reads: a quarter of the loop overhead)
-  const uint4* k4 = reinterpret_cast<const uint4*>(sm.keys);
-  const int G = (E + 3) / 4;           // groups of four keys
-  if (cached) {
-    for (int g = tid; g < G; g += kSelThreads) {
-      const uint4 q = k4[g];
-      const uint32_t kk[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        if ((kk[u] & pmask) == prefix && 4 * g + u < E) {
-          const int pos = atomicAdd(&sm.ncand, 1);
-          if (pos < kCand) sm.cand[pos] = kk[u];
-        }
-      }
-    }
-  } else {
-    for (int i = tid; i < E; i += kSelThreads) {
-      const uint32_t k = edge_key(a, lo + i);
-      if ((k & pmask) == prefix) {
-        const int pos = atomicAdd(&sm.ncand, 1);
-        if (pos < kCand) sm.cand[pos] = k;
-      }
-    }
-  }
-  __syncthreads();
-  const int ncand = sm.ncand;
-  KVS_SSTAMP(3);
-  const bool listed = (ncand <= kCand);
   const int shifts[2] = {10, 0};
   const int widths[2] = {11, 10};
 #pragma unroll
@@ -175,141 +497,51 @@ __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, con
     const int bins = 1 << widths[pass];
     for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
     __syncthreads();
-    if (listed) {
-      for (int i = tid; i < ncand; i += kSelThreads) {
-        const uint32_t k = sm.cand[i];
-        if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
-      }
-    } else {                            // a bin too crowded for the list: full passes over the keys
-      for (int i = tid; i < E; i += kSelThreads) {
-        const uint32_t k = cached ? sm.keys[i] : edge_key(a, lo + i);
-        hist_add(sm.hist, (k >> shift) & (bins - 1), (k & pmask) == prefix, lane);
-      }
+    for (int i = tid; i < E; i += kSelThreads) {
+      const uint32_t k = edge_key(a, lo + i);
+      if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
     }
     __syncthreads();
     pick_bin(sm, shift, bins, prefix, pmask, want);
   }
   const uint32_t T = prefix;           // `want` keys equal to T are taken, the lowest indices first
-  KVS_SSTAMP(4);
 
   // ---- ordered pass: every wavefront owns a contiguous range of edges
-  if (cached) {
-    // four consecutive keys per lane: wavefront w owns groups [g0, g1)
-    const int per_g = ((G + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
-    const int g0 = min(G, wave * per_g), g1 = min(G, g0 + per_g);
-    int n_lt = 0, n_eq = 0;
-    for (int g = g0 + lane; g < g1; g += kWave) {
-      const uint4 q = k4[g];
-      n_lt += (q.x < T) + (q.y < T) + (q.z < T) + (q.w < T);
-      n_eq += (q.x == T && 4 * g < E) + (q.y == T && 4 * g + 1 < E) + (q.z == T && 4 * g + 2 < E) +
-              (q.w == T && 4 * g + 3 < E);
+  const int per = ((E + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
+  const int e0 = min(E, wave * per), e1 = min(E, e0 + per);
+  int n_lt = 0, n_eq = 0;
+  for (int i = e0 + lane; i < e1 + lane; i += kWave) {     // whole wavefront iterates together
+    uint32_t k = 0xffffffffu;
+    if (i < e1) k = edge_key(a, lo + i);
+    n_lt += __popcll(__ballot(k < T));
+    n_eq += __popcll(__ballot(k == T && i < e1));
+  }
+  if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
+  __syncthreads();
+  int eq_before = 0, sel_before = 0;
+  for (int w = 0; w < wave; ++w) {
+    const int take = min(max(want - eq_before, 0), sm.eq[w]);
+    sel_before += sm.lt[w] + take;
+    eq_before += sm.eq[w];
+  }
+  for (int i = e0 + lane; i < e1 + lane; i += kWave) {
+    uint32_t k = 0xffffffffu;
+    if (i < e1) k = edge_key(a, lo + i);
+    const bool is_eq = (k == T) && (i < e1);
+    const uint64_t beq = __ballot(is_eq);
+    const bool sel = (k < T) || (is_eq && (eq_before + lanes_below(beq, lane) < want));
+    const uint64_t bsel = __ballot(sel);
+    if (i < e1) {
+      const int m = lo + i;
+      mk[m] = sel ? 1 : 0;
+      sl[m] = m - (sel_before + lanes_below(bsel, lane));   // selected edges below token m
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      n_lt += __shfl_xor(n_lt, off, kWave);
-      n_eq += __shfl_xor(n_eq, off, kWave);
-    }
-    if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
-    __syncthreads();
-    KVS_SSTAMP(5);
-    int eq_before = 0, sel_before = 0;
-    for (int w = 0; w < wave; ++w) {
-      const int take = min(max(want - eq_before, 0), sm.eq[w]);
-      sel_before += sm.lt[w] + take;
-      eq_before += sm.eq[w];
-    }
-    const bool vec_ok = ((un.in_row + lo) & 3) == 0;       // 4-byte mask stores and 16-byte slot stores
-    for (int gb = g0; gb < g1; gb += kWave) {              // whole wavefront iterates together
-      const int g = gb + lane;
-      uint4 q = make_uint4(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
-      if (g < g1) q = k4[g];
-      const uint32_t kk[4] = {q.x, q.y, q.z, q.w};
-      bool sel[4], eq[4];
-      int lane_eq = 0;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        sel[u] = kk[u] < T;
-        eq[u] = (kk[u] == T) && (4 * g + u < E) && (g < g1);
-        lane_eq += eq[u];
-      }
-      if (__ballot(lane_eq != 0) != 0) {                  // ties with the threshold: rare, ranked in index order
-        int incl = lane_eq;
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-          const int v = __shfl_up(incl, off, kWave);
-          if (lane >= off) incl += v;
-        }
-        int rank = eq_before + incl - lane_eq;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (eq[u]) { sel[u] = rank < want; ++rank; }
-        }
-        eq_before += __shfl(incl, kWave - 1, kWave);
-      }
-      const int lane_cnt = sel[0] + sel[1] + sel[2] + sel[3];
-      int incl = lane_cnt;
-#pragma unroll
-      for (int off = 1; off < kWave; off <<= 1) {
-        const int v = __shfl_up(incl, off, kWave);
-        if (lane >= off) incl += v;
-      }
-      int below = sel_before + incl - lane_cnt;              // selected edges below this lane's first key
-      sel_before += __shfl(incl, kWave - 1, kWave);
-      if (g < g1) {
-        const int m0 = lo + 4 * g;
-        int s4[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) { s4[u] = m0 + u - below; below += sel[u]; }
-        if (vec_ok && 4 * g + 3 < E) {
-          *reinterpret_cast<uint32_t*>(mk + m0) =
-              (uint32_t)sel[0] | ((uint32_t)sel[1] << 8) | ((uint32_t)sel[2] << 16) | ((uint32_t)sel[3] << 24);
-          *reinterpret_cast<int4*>(sl + m0) = make_int4(s4[0], s4[1], s4[2], s4[3]);
-        } else {
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            if (4 * g + u < E) { mk[m0 + u] = sel[u] ? 1 : 0; sl[m0 + u] = s4[u]; }
-          }
-        }
-      }
-    }
-  } else {
-    const int per = ((E + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
-    const int e0 = min(E, wave * per), e1 = min(E, e0 + per);
-    int n_lt = 0, n_eq = 0;
-    for (int i = e0 + lane; i < e1 + lane; i += kWave) {     // whole wavefront iterates together
-      uint32_t k = 0xffffffffu;
-      if (i < e1) k = edge_key(a, lo + i);
-      n_lt += __popcll(__ballot(k < T));
-      n_eq += __popcll(__ballot(k == T && i < e1));
-    }
-    if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
-    __syncthreads();
-    int eq_before = 0, sel_before = 0;
-    for (int w = 0; w < wave; ++w) {
-      const int take = min(max(want - eq_before, 0), sm.eq[w]);
-      sel_before += sm.lt[w] + take;
-      eq_before += sm.eq[w];
-    }
-    for (int i = e0 + lane; i < e1 + lane; i += kWave) {
-      uint32_t k = 0xffffffffu;
-      if (i < e1) k = edge_key(a, lo + i);
-      const bool is_eq = (k == T) && (i < e1);
-      const uint64_t beq = __ballot(is_eq);
-      const bool sel = (k < T) || (is_eq && (eq_before + lanes_below(beq, lane) < want));
-      const uint64_t bsel = __ballot(sel);
-      if (i < e1) {
-        const int m = lo + i;
-        mk[m] = sel ? 1 : 0;
-        sl[m] = m - (sel_before + lanes_below(bsel, lane));   // selected edges below token m
-      }
-      eq_before += __popcll(beq);
-      sel_before += __popcll(bsel);
-    }
+    eq_before += __popcll(beq);
+    sel_before += __popcll(bsel);
   }
   // tokens outside the eligible edge range
   for (int t = tid; t < lo && t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t; }
   for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
-  KVS_SSTAMP(6);
 }
 
 template <typename T, int D>
