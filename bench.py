@@ -3,8 +3,10 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama8b_32k]
 
-One *step* is one pass of the whole hot path (score -> select -> merge_compact, one kvs_step call
-per layer) over every layer of the workload, layers one after the other, inputs resident in HBM.
+One *step* is one pass of the whole hot path (score -> select -> merge_compact) over every layer of
+the workload, inputs resident in HBM.  A (layer, sequence, KV head) cache is one independent unit of
+the library, so the layers are simply more units of the same kvs_step call (--layers-per-call, all of
+them by default; the library launches its kernels over at most 64 units at a time).
 Prints ONE JSON line: whole-job merged KV tokens/s, the roofline of the dominant phase (timed live
 with events on the launch stream) and the fp64 oracle's rate on the host cores of this machine.
 """
@@ -34,6 +36,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama8b_32k")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
+    ap.add_argument("--layers-per-call", type=int, default=0,
+                    help="layers handed to one kvs_step call (0 = all; 1 = one call per layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching from the host")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -80,13 +84,18 @@ def main():
     w = WORKLOADS[args.workload]
     layers = args.layers or w.layers
     lens_seq = unit_lengths(w)
-    lens = [lens_seq[s] for s in range(w.n_seq) for _ in range(w.n_kv_heads)]
+    lens = [lens_seq[s] for s in range(w.n_seq) for _ in range(w.n_kv_heads)]       # the units of one layer
     budgets = [unit_budget(w, n) for n in lens]
     D, R = w.head_dim, w.q_rows
     b = 4 if w.dtype == "f32" else 2
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
-    problem = kvs.Problem(lens=lens, budgets=budgets, group=w.group, window=w.window, head_dim=D, dtype=w.dtype,
-                          n_sink=w.n_sink, n_recent=w.n_recent)
+    lpc = args.layers_per_call or layers
+    batches = [list(range(l0, min(layers, l0 + lpc))) for l0 in range(0, layers, lpc)]
+    problems = {}
+    for nl in {len(bt) for bt in batches}:
+        problems[nl] = kvs.Problem(lens=lens * nl, budgets=budgets * nl, group=w.group, window=w.window, head_dim=D,
+                                   dtype=w.dtype, n_sink=w.n_sink, n_recent=w.n_recent)
+    rows_layer = sum(lens)
 
     # ---- synthetic inputs, one independent draw per (layer, sequence, head), uploaded once
     t_gen = time.time()
@@ -99,31 +108,40 @@ def main():
             return torch.from_numpy(np.ascontiguousarray(x32, dtype=np.float32)).to(dev)
         return torch.from_numpy(f32_to_bf16_bits(x32).view(np.int16)).to(dev).view(torch.bfloat16)
 
-    Ks, Vs, Qs = [], [], []
+    Ks, Vs, Qs = [], [], []            # one tensor per batch of layers
     with ThreadPoolExecutor(max_workers=workers) as pool:
-        for layer in range(layers):
-            ids = [(s, h) for s in range(w.n_seq) for h in range(w.n_kv_heads)]
-            units = list(pool.map(lambda sh: generate_unit(w, layer, sh[0], sh[1]), ids))
-            Ks.append(upload(np.concatenate([u.K for u in units])))
-            Vs.append(upload(np.concatenate([u.V for u in units])))
-            Qs.append(upload(np.stack([u.Q.reshape(R, D) for u in units])))
-            if layer < n_keep_layers:
-                keep_host[layer] = units
+        for bt in batches:
+            Kb = torch.empty((rows_layer * len(bt), D), dtype=tdt, device=dev)
+            Vb = torch.empty_like(Kb)
+            Qb = torch.empty((len(lens) * len(bt), R, D), dtype=tdt, device=dev)
+            for i, layer in enumerate(bt):
+                ids = [(s, h) for s in range(w.n_seq) for h in range(w.n_kv_heads)]
+                units = list(pool.map(lambda sh: generate_unit(w, layer, sh[0], sh[1]), ids))
+                Kb[i * rows_layer:(i + 1) * rows_layer] = upload(np.concatenate([u.K for u in units]))
+                Vb[i * rows_layer:(i + 1) * rows_layer] = upload(np.concatenate([u.V for u in units]))
+                Qb[i * len(lens):(i + 1) * len(lens)] = upload(np.stack([u.Q.reshape(R, D) for u in units]))
+                if layer < n_keep_layers:
+                    keep_host[layer] = units
+            Ks.append(Kb)
+            Vs.append(Vb)
+            Qs.append(Qb)
     t_gen = time.time() - t_gen
 
-    K_out = [torch.empty((problem.rows_out, D), dtype=tdt, device=dev) for _ in range(layers)]
-    V_out = [torch.empty((problem.rows_out, D), dtype=tdt, device=dev) for _ in range(layers)]
-    counts = [torch.empty(problem.rows_out, dtype=torch.int32, device=dev) for _ in range(layers)]
-    ws = torch.empty(kvs.kvs_workspace_size(problem), dtype=torch.uint8, device=dev)
-    alpha = torch.empty(problem.rows_in, dtype=torch.float32, device=dev)
-    obar = torch.empty((len(lens), D), dtype=torch.float32, device=dev)
-    mask = torch.empty(problem.rows_in, dtype=torch.uint8, device=dev)
-    slot = torch.empty(problem.rows_in, dtype=torch.int32, device=dev)
+    probs = [problems[len(bt)] for bt in batches]
+    K_out = [torch.empty((pr.rows_out, D), dtype=tdt, device=dev) for pr in probs]
+    V_out = [torch.empty((pr.rows_out, D), dtype=tdt, device=dev) for pr in probs]
+    counts = [torch.empty(pr.rows_out, dtype=torch.int32, device=dev) for pr in probs]
+    big = probs[0]                                               # the first batch is the largest
+    ws = torch.empty(kvs.kvs_workspace_size(big), dtype=torch.uint8, device=dev)
+    alpha = torch.empty(big.rows_in, dtype=torch.float32, device=dev)
+    obar = torch.empty((big.n_units, D), dtype=torch.float32, device=dev)
+    mask = torch.empty(big.rows_in, dtype=torch.uint8, device=dev)
+    slot = torch.empty(big.rows_in, dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
 
     def one_step():
-        for l in range(layers):
-            kvs.kvs_step(problem, Qs[l], Ks[l], Vs[l], K_out[l], V_out[l], counts[l], ws, stream=stream)
+        for i, pr in enumerate(probs):
+            kvs.kvs_step(pr, Qs[i], Ks[i], Vs[i], K_out[i], V_out[i], counts[i], ws, stream=stream)
 
     # Optionally the launches of one step (4 kernels per layer) are captured once into a HIP graph and
     # replayed: the library never allocates, synchronises or memsets, so a step is capturable as it is.
@@ -162,34 +180,37 @@ def main():
 
     # ---- per-phase timing, same inputs, the three entry points one after the other with events between
     phases = ["score", "select", "merge_compact"]
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(layers)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in probs]
     reps = max(1, min(args.steps, 5))
     phase_ms = {p: 0.0 for p in phases}
     for rep in range(reps + 1):
-        for l in range(layers):
-            evs[l][0].record()
-            kvs.kvs_score(problem, Qs[l], Ks[l], Vs[l], alpha, obar, ws, stream=stream)
-            evs[l][1].record()
-            kvs.kvs_select(problem, alpha, mask, slot, stream=stream)
-            evs[l][2].record()
-            kvs.kvs_merge_compact(problem, Ks[l], Vs[l], alpha, obar, mask, slot, K_out[l], V_out[l], counts[l],
-                                  stream=stream)
-            evs[l][3].record()
+        for i, pr in enumerate(probs):
+            evs[i][0].record()
+            kvs.kvs_score(pr, Qs[i], Ks[i], Vs[i], alpha, obar, ws, stream=stream)
+            evs[i][1].record()
+            kvs.kvs_select(pr, alpha, mask, slot, stream=stream)
+            evs[i][2].record()
+            kvs.kvs_merge_compact(pr, Ks[i], Vs[i], alpha, obar, mask, slot, K_out[i], V_out[i], counts[i], stream=stream)
+            evs[i][3].record()
         torch.cuda.synchronize()
         if rep == 0:
             continue                                   # warm-up of the stand-alone entry points
-        for l in range(layers):
-            for i, p in enumerate(phases):
-                phase_ms[p] += evs[l][i].elapsed_time(evs[l][i + 1])
-    launches = reps * layers
+        for i in range(len(probs)):
+            for j, p in enumerate(phases):
+                phase_ms[p] += evs[i][j].elapsed_time(evs[i][j + 1])
+    # One kernel launch of the library covers at most 64 units; the figures below are per such launch.
+    UNITS_PER_LAUNCH = 64
+    launches = reps * sum((pr.n_units + UNITS_PER_LAUNCH - 1) // UNITS_PER_LAUNCH for pr in probs)
+    layers_per_launch = layers * reps / launches
     phase_ms = {p: v / launches for p, v in phase_ms.items()}
-    pb = {p: 0 for p in phases}
+    pb = {p: 0 for p in phases}                       # bytes of one layer's units
     for n, B in zip(lens, budgets):
         for p, v in phase_bytes(n, min(n, B), R, D, b).items():
             pb[p] += v
+    step_bytes = sum(pb.values())
+    pb = {p: v * layers_per_launch for p, v in pb.items()}     # ... of one launch's units
     dominant = max(phases, key=lambda p: phase_ms[p])
     achieved = pb[dominant] / (phase_ms[dominant] * 1e-3) / 1e9
-    step_bytes = sum(pb.values())
     step_gbs = step_bytes * layers / (ms_per_step * 1e-3) / 1e9
 
     result = {
@@ -200,11 +221,12 @@ def main():
         "config": {"workload": w.name, "layers": layers, "kv_heads": w.n_kv_heads, "q_heads": w.group * w.n_kv_heads,
                    "head_dim": D, "window": w.window, "tokens": lens_seq if w.n_seq > 1 else lens_seq[0],
                    "budget": budgets[0] if w.n_seq == 1 else "25% of length", "n_sink": w.n_sink,
-                   "launch": "hip graph replay" if args.graph else "host", "us_per_layer": ms_per_step * 1e3 / layers, "input_generation_s": round(t_gen, 1)},
+                   "layers_per_call": lpc, "launch": "hip graph replay" if args.graph else "host", "us_per_layer": ms_per_step * 1e3 / layers, "input_generation_s": round(t_gen, 1)},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": (measured_traffic(w.name) or {}).get(dominant),
                      "us_per_launch": phase_ms[dominant] * 1e3, "algorithmic_bytes_per_launch": pb[dominant],
+                     "units_per_launch": min(UNITS_PER_LAUNCH, big.n_units),
                      "phases_us": {p: phase_ms[p] * 1e3 for p in phases},
                      "phases_frac": {p: pb[p] / (phase_ms[p] * 1e-3) / 1e9 / HBM_PEAK_GBS for p in phases},
                      "step": {"algorithmic_bytes_per_layer": step_bytes, "achieved": step_gbs,

@@ -104,6 +104,7 @@ class Problem:
         self._budget = (C.c_int32 * n)(*self.budgets)
         self._in = (C.c_int64 * n)(*self.in_rows)
         self._out = (C.c_int64 * n)(*self.out_rows)
+        self.n_units = n
         self.group, self.window, self.head_dim, self.dtype = group, window, head_dim, dtype
         self.struct = KvsProblemStruct(
             n_units=n, group=group, window=window, head_dim=head_dim, n_sink=n_sink, n_recent=n_recent,

@@ -95,6 +95,7 @@ Workspace carve(const Plan& plan, void* base) {
   };
   const size_t nu = (size_t)plan.n_units;
   w.stats_part = (float2*)take(nu * kMaxChunks * plan.shape.R * sizeof(float2));
+  w.c_row = (float*)take(nu * plan.shape.R * sizeof(float));
   w.o_part = (float*)take(nu * kMaxChunks * plan.shape.D * sizeof(float));
   w.alpha_bar = (float*)take((size_t)plan.rows_in * sizeof(float));
   w.o_bar = (float*)take(nu * plan.shape.D * sizeof(float));

@@ -62,6 +62,7 @@ struct Shape {
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
   float2* stats_part;   // [n_units][kMaxChunks][R]  (running max, sum) of every chunk, base-2 domain
+  float* c_row;         // [n_units][R]  unit-wide normaliser of every query row, see score_finalize_kernel
   float* o_part;        // [n_units][kMaxChunks][D]  partial o_bar of every chunk of the o_bar pass
   float* alpha_bar;     // [rows]    (kvs_step only)
   float* o_bar;         // [n_units][D] (kvs_step only)
@@ -130,44 +131,10 @@ __device__ __forceinline__ float row_group_sum(float x) {
   return x;
 }
 
-// Unit-wide softmax statistics of every query row from the chunks' (max, sum) pairs, as the one
-// constant sweep 1 needs: c[q] = M_q + log2(Z_q * R), so that alpha[q,t] / R = exp2(logit2 - c[q]).
-// Called by a whole workgroup of 256 threads; two threads share a row and take half of the chunks
-// each, with all their loads in flight at once (a loop with a run-time trip count would serialise
-// the round trips).  The order of the additions is fixed.  sm_pair: [2][128] float2 of scratch.
-__device__ __forceinline__ void finalize_stats(const float2* __restrict__ stats_part, size_t part_base, int n_chunks,
-                                               int R, float* sm_c, float2 (*sm_pair)[128]) {
-  constexpr int HALF = kMaxChunks / 2;
-  const int tid = threadIdx.x;
-  const int h = tid / 128, r = tid % 128;
-  for (int q0 = 0; q0 < R; q0 += 128) {
-    const int q = q0 + r;
-    float2 v[HALF];
-#pragma unroll
-    for (int i = 0; i < HALF; ++i) {
-      const int c = h * HALF + i;
-      v[i] = make_float2(-INFINITY, 0.f);
-      if (q < R && c < n_chunks) v[i] = stats_part[(part_base + c) * R + q];
-    }
-    float M = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < HALF; ++i) M = fmaxf(M, v[i].x);
-    float Z = 0.f;
-#pragma unroll
-    for (int i = 0; i < HALF; ++i) {
-      if (v[i].y > 0.f) Z += v[i].y * __builtin_amdgcn_exp2f(v[i].x - M);
-    }
-    sm_pair[h][r] = make_float2(M, Z);
-    __syncthreads();
-    if (h == 0 && q < R) {
-      const float2 a = sm_pair[0][r], b = sm_pair[1][r];
-      const float Mq = fmaxf(a.x, b.x);
-      float Zq = a.y * __builtin_amdgcn_exp2f(a.x - Mq);
-      if (b.y > 0.f) Zq += b.y * __builtin_amdgcn_exp2f(b.x - Mq);
-      sm_c[q] = Mq + log2f(Zq * (float)R);
-    }
-    __syncthreads();
-  }
+// The unit's normalisers c[q] (written by the finalize kernel between the two sweeps) -> LDS.
+__device__ __forceinline__ void load_row_consts(const float* __restrict__ c_row, int unit_index, int R, float* sm_c) {
+  for (int q = threadIdx.x; q < R; q += blockDim.x) sm_c[q] = c_row[(size_t)unit_index * R + q];
+  __syncthreads();
 }
 
 // Which unit and which chunk a workgroup of a chunk-indexed launch works on.
@@ -178,7 +145,9 @@ __device__ __forceinline__ int find_unit(const UnitTable& tab, int chunk) {
 }
 
 // Launchers (defined next to their kernels).  All enqueue on `stream` and return the launch status.
-// Both score sweeps: chunk statistics, then alpha_bar.
+// Unit-wide softmax statistics from the chunks' partial ones (one small workgroup per unit).
+hipError_t launch_score_finalize(const UnitTable& tab, const Shape& sh, const Workspace& ws, hipStream_t stream);
+// Both score sweeps: chunk statistics, the finalize kernel, then alpha_bar.
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
                         float* alpha_bar, const Workspace& ws, hipStream_t stream);
 // One launch, two kinds of workgroups: the first `with_select ? n_units : 0` select the edges of one unit

@@ -70,7 +70,7 @@ __device__ long long g_trace[8192 * 16];
 template <int D, int NT, int WQ, int PHASE>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
-    float* __restrict__ alpha_bar, float2* __restrict__ stats_part) {
+    float* __restrict__ alpha_bar, float2* __restrict__ stats_part, const float* __restrict__ c_row) {
   constexpr int WT = kWaves / WQ;           // wavefronts that split the tiles
   constexpr int KS = D / 16;                // MFMA k-steps per tile
   constexpr int LPR = D / 8;                // 16-byte pieces (= lanes) per row
@@ -84,7 +84,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   __shared__ float sm_c[KVS_MAX_Q_ROWS];
   __shared__ float2 sm_stats[kWaves][QROWS];
   __shared__ float sm_alpha[kWaves][kTile];
-  __shared__ float2 sm_pair[2][128];
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -139,7 +138,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   };
 
   KVS_STAMP(0);
-  if (PHASE == 1) finalize_stats(stats_part, part_base, un.n_chunks, R, sm_c, sm_pair);
+  if (PHASE == 1) load_row_consts(c_row, un.index, R, sm_c);
   KVS_STAMP(1);
 
   for (int qp = 0; qp < R; qp += PASS_ROWS) {
@@ -403,7 +402,7 @@ __device__ __forceinline__ void lds_read_2x2(bf16x8& b00, bf16x8& b01, bf16x8& b
 template <int D, int PHASE>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
-    float* __restrict__ alpha_bar, float2* __restrict__ stats_part) {
+    float* __restrict__ alpha_bar, float2* __restrict__ stats_part, const float* __restrict__ c_row) {
   constexpr int KS = D / 16;
   constexpr int LPR = D / 8;
   constexpr int RPI = kWave / LPR;
@@ -415,9 +414,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
 
   __shared__ __attribute__((aligned(1024))) unsigned char sm_k[kWaves][TILEB];
   __shared__ __attribute__((aligned(1024))) unsigned char sm_q[QROWS * ROWB];
-  __shared__ float sm_c[QROWS];
   __shared__ float2 sm_stats[kWaves][QROWS];
-  __shared__ float2 sm_pair[2][128];
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -464,11 +461,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     return true;
   };
 
-  if (PHASE == 1) finalize_stats(stats_part, part_base, un.n_chunks, R, sm_c, sm_pair);
-  // normalisers first: an ordinary LDS read after the loads below would wait for all of them
+  // this lane's four normalisers (written by the finalize kernel between the sweeps)
   float cq[4];
 #pragma unroll
-  for (int b = 0; b < 4; ++b) cq[b] = (PHASE == 1 && b * 32 + col < R) ? sm_c[b * 32 + col] : INFINITY;
+  for (int b = 0; b < 4; ++b)
+    cq[b] = (PHASE == 1 && b * 32 + col < R) ? c_row[(size_t)un.index * R + b * 32 + col] : INFINITY;
 
   // the Q block, once per workgroup: every wavefront fetches 32 rows (rows past R repeat the last one)
   {
@@ -639,11 +636,12 @@ hipError_t launch_wide(const UnitTable& tab, const Shape& sh, const void* Q, con
                        const Workspace& ws, hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
   hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, alpha_bar, ws.stats_part);
+                     (const uint16_t*)K, alpha_bar, ws.stats_part, ws.c_row);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
   hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, alpha_bar, ws.stats_part);
+                     (const uint16_t*)K, alpha_bar, ws.stats_part, ws.c_row);
   return hipGetLastError();
 }
 
@@ -652,11 +650,12 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const 
                     const Workspace& ws, hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
   hipLaunchKernelGGL((score_mfma_kernel<D, NT, WQ, 0>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, alpha_bar, ws.stats_part);
+                     (const uint16_t*)K, alpha_bar, ws.stats_part, ws.c_row);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
   hipLaunchKernelGGL((score_mfma_kernel<D, NT, WQ, 1>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, alpha_bar, ws.stats_part);
+                     (const uint16_t*)K, alpha_bar, ws.stats_part, ws.c_row);
   return hipGetLastError();
 }
 

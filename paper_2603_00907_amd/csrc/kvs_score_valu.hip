@@ -21,7 +21,7 @@ constexpr int kThreads = 256;
 template <typename T, int D, int PHASE>
 __global__ __launch_bounds__(kThreads) void score_valu_kernel(
     const UnitTable tab, const Shape sh, const T* __restrict__ Q, const T* __restrict__ K,
-    float* __restrict__ alpha_bar, float2* __restrict__ stats_part) {
+    float* __restrict__ alpha_bar, float2* __restrict__ stats_part, const float* __restrict__ c_row) {
   constexpr int EPL = Piece<T>::N;          // elements per lane
   constexpr int LPR = D / EPL;              // lanes per row
   constexpr int RPW = kWave / LPR;          // rows per wavefront load
@@ -29,7 +29,6 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
 
   __shared__ float2 sm_stats[(kThreads / kWave) * RPW][kQB];
   __shared__ float sm_c[KVS_MAX_Q_ROWS];
-  __shared__ float2 sm_pair[2][128];
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -44,7 +43,7 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
   const uint4* Kp = reinterpret_cast<const uint4*>(K + (size_t)un.in_row * D) + piece;
   const uint4* Qp = reinterpret_cast<const uint4*>(Q + (size_t)un.index * R * D) + piece;
 
-  if (PHASE == 1) finalize_stats(stats_part, part_base, un.n_chunks, R, sm_c, sm_pair);
+  if (PHASE == 1) load_row_consts(c_row, un.index, R, sm_c);
 
   for (int qb = 0; qb < R; qb += kQB) {
     float qf[kQB][EPL];
@@ -114,18 +113,71 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
   }
 }
 
+// Unit-wide softmax statistics of every query row from the chunks' (max, sum) pairs, as the one
+// constant sweep 1 needs: c[q] = M_q + log2(Z_q * R), so that alpha[q,t] / R = exp2(logit2 - c[q]).
+// One workgroup per unit: every sweep-1 workgroup needs all of c, and 64 chunks x R pairs fetched
+// and reduced by each of them cost a fifth of that sweep.  Two threads share a row and take half of
+// the chunks each, all their loads in flight at once (a loop with a run-time trip count would
+// serialise the round trips); the order of the additions is fixed.
+__global__ __launch_bounds__(kThreads) void score_finalize_kernel(const UnitTable tab, const Shape sh,
+                                                                  const float2* __restrict__ stats_part,
+                                                                  float* __restrict__ c_row) {
+  constexpr int HALF = kMaxChunks / 2;
+  __shared__ float2 sm_pair[2][128];
+  const Unit un = tab.u[blockIdx.x];
+  const int R = sh.R;
+  const size_t part_base = (size_t)un.index * kMaxChunks;
+  const int tid = threadIdx.x;
+  const int h = tid / 128, r = tid % 128;
+  for (int q0 = 0; q0 < R; q0 += 128) {
+    const int q = q0 + r;
+    float2 v[HALF];
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const int c = h * HALF + i;
+      v[i] = make_float2(-INFINITY, 0.f);
+      if (q < R && c < un.n_chunks) v[i] = stats_part[(part_base + c) * R + q];
+    }
+    float M = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) M = fmaxf(M, v[i].x);
+    float Z = 0.f;
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      if (v[i].y > 0.f) Z += v[i].y * __builtin_amdgcn_exp2f(v[i].x - M);
+    }
+    sm_pair[h][r] = make_float2(M, Z);
+    __syncthreads();
+    if (h == 0 && q < R) {
+      const float2 a = sm_pair[0][r], b = sm_pair[1][r];
+      const float Mq = fmaxf(a.x, b.x);
+      float Zq = a.y * __builtin_amdgcn_exp2f(a.x - Mq);
+      if (b.y > 0.f) Zq += b.y * __builtin_amdgcn_exp2f(b.x - Mq);
+      c_row[(size_t)un.index * R + q] = Mq + log2f(Zq * (float)R);
+    }
+    __syncthreads();
+  }
+}
+
 }  // namespace
+
+hipError_t launch_score_finalize(const UnitTable& tab, const Shape& sh, const Workspace& ws, hipStream_t stream) {
+  hipLaunchKernelGGL(score_finalize_kernel, dim3(tab.n_units), dim3(kThreads), 0, stream, tab, sh, ws.stats_part,
+                     ws.c_row);
+  return hipGetLastError();
+}
 
 template <typename T, int D>
 static hipError_t launch_score_valu_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
                                       float* alpha_bar, const Workspace& ws, hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
   hipLaunchKernelGGL((score_valu_kernel<T, D, 0>), grid, block, 0, stream, tab, sh, (const T*)Q, (const T*)K,
-                     alpha_bar, ws.stats_part);
+                     alpha_bar, ws.stats_part, ws.c_row);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
   hipLaunchKernelGGL((score_valu_kernel<T, D, 1>), grid, block, 0, stream, tab, sh, (const T*)Q, (const T*)K,
-                     alpha_bar, ws.stats_part);
+                     alpha_bar, ws.stats_part, ws.c_row);
   return hipGetLastError();
 }
 
