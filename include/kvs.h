@@ -43,6 +43,7 @@ extern "C" {
 
 #define KVS_VERSION 100          /* major*10000 + minor*100 + patch */
 #define KVS_MAX_Q_ROWS 1024      /* largest supported G*W */
+#define KVS_MAX_LEN (1 << 22)    /* largest supported cache length of one unit, in tokens */
 
 typedef enum {
   KVS_OK = 0,
@@ -67,7 +68,7 @@ typedef struct {
   int32_t n_recent;         /* the last n_recent tokens are never merged (default 0)                 */
   kvs_dtype io_dtype;       /* dtype of Q, K, V, K_out, V_out                                        */
   float scale;              /* logit scale; 0 selects 1/sqrt(head_dim)                               */
-  const int32_t* len;       /* HOST [n_units] cached tokens per unit (>= 1)                          */
+  const int32_t* len;       /* HOST [n_units] cached tokens per unit (1 .. KVS_MAX_LEN)              */
   const int32_t* budget;    /* HOST [n_units] tokens to keep per unit                                */
   const int64_t* in_row;    /* HOST [n_units] first row of the unit in K, V, alpha_bar, edge_mask,
                                slot_of_token; the units' row ranges [in_row, in_row + len) must be

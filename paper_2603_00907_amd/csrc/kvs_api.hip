@@ -53,7 +53,8 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
 
   for (int u = 0; u < p->n_units; ++u) {
     const long long len = p->len[u], budget = p->budget[u];
-    if (len < 1 || len > (1ll << 30) || p->in_row[u] < 0 || p->out_row[u] < 0) return KVS_ERR_INVALID_ARG;
+    // (kernels address a unit's rows with 32-bit byte offsets: KVS_MAX_LEN rows of 512 bytes stay below 4 GB)
+    if (len < 1 || len > KVS_MAX_LEN || p->in_row[u] < 0 || p->out_row[u] < 0) return KVS_ERR_INVALID_ARG;
     if (budget < 1) return KVS_ERR_BUDGET;
     if (len > budget && budget < (long long)p->n_sink + 1 + p->n_recent) return KVS_ERR_BUDGET;
     Unit& un = plan->units[u];

@@ -29,7 +29,7 @@ namespace {
 
 constexpr int kThreads = 256;
 #ifndef KVS_MERGE_PREFETCH
-#define KVS_MERGE_PREFETCH 2
+#define KVS_MERGE_PREFETCH 3
 #endif
 constexpr int kPrefetch = KVS_MERGE_PREFETCH;
 
@@ -132,13 +132,22 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   return;
 #endif
 
-  const uint4* Kp = reinterpret_cast<const uint4*>(K + (size_t)un.in_row * D) + piece;
-  const uint4* Vp = reinterpret_cast<const uint4*>(V + (size_t)un.in_row * D) + piece;
-  uint4* Ko = reinterpret_cast<uint4*>(K_out + (size_t)un.out_row * D) + piece;
-  uint4* Vo = reinterpret_cast<uint4*>(V_out + (size_t)un.out_row * D) + piece;
+  // Unit-wide base pointers (uniform: they live in scalar registers) plus 32-bit byte offsets per lane:
+  // a unit's rows span less than 4 GB (the host checks the length), and a 32-bit offset costs one
+  // instruction per address where a 64-bit per-lane pointer costs four.
+  constexpr uint32_t ROWB = D * sizeof(T);
+  const char* Kb = reinterpret_cast<const char*>(K + (size_t)un.in_row * D);
+  const char* Vb = reinterpret_cast<const char*>(V + (size_t)un.in_row * D);
+  char* Kob = reinterpret_cast<char*>(K_out + (size_t)un.out_row * D);
+  char* Vob = reinterpret_cast<char*>(V_out + (size_t)un.out_row * D);
+  const uint32_t pofs = piece * 16;
+  auto k_row = [&](int t) { return *reinterpret_cast<const uint4*>(Kb + ((uint32_t)t * ROWB + pofs)); };
+  auto v_row = [&](int t) { return *reinterpret_cast<const uint4*>(Vb + ((uint32_t)t * ROWB + pofs)); };
   int32_t* cnt = counts + un.out_row;
   const float* al = alpha_bar + un.in_row;
   const int32_t* sl = slot + un.in_row;
+  auto alpha_at = [&](int t) { return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(al) + (uint32_t)t * 4u); };
+  auto mask_at = [&](int t) { return *(mk + (uint32_t)t); };
 
   // o_bar: final values, or the chunk sums added in a fixed order (every workgroup gets the same bits)
   float o[EPL];
@@ -168,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       for (int i = 0; i < EPL; ++i) outk[i] = 0.f;
       for (int j = first_tok; j < first_tok + count; ++j) {
         float kj[EPL];
-        Piece<T>::unpack(Kp[(size_t)j * LPR], kj);
+        Piece<T>::unpack(k_row(j), kj);
 #pragma unroll
         for (int i = 0; i < EPL; ++i) outk[i] += kj[i];
       }
@@ -180,9 +189,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     const uint4 ov = Piece<T>::pack(accV);       // a single row converts back to its own bits
     if (count == 1) ok = raw_k;
     if ((unsigned)out_slot < (unsigned)un.n_out) {   // a slot map from outside the library is not trusted
-      Ko[(size_t)out_slot * LPR] = ok;
-      Vo[(size_t)out_slot * LPR] = ov;
-      if (piece == 0) cnt[out_slot] = count;
+      *reinterpret_cast<uint4*>(Kob + ((uint32_t)out_slot * ROWB + pofs)) = ok;
+      *reinterpret_cast<uint4*>(Vob + ((uint32_t)out_slot * ROWB + pofs)) = ov;
+      if (piece == 0) *reinterpret_cast<int32_t*>(reinterpret_cast<char*>(cnt) + (uint32_t)out_slot * 4u) = count;
     }
   };
   auto store_frag = [&](float* f, const float* accK, const float* accV, float U, int count, int first_tok) {
@@ -217,15 +226,15 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     float ra[kPrefetch];
     uint8_t rm[kPrefetch];          // kept as loaded: widening at the load would wait for it there
     auto refill = [&](int j, int t) {                // the set that token t will consume
-      rk[j] = Kp[(size_t)min(t, gb - 1) * LPR];
+      rk[j] = k_row(min(t, gb - 1));
       const int tv = min(t + 1, last_v);
-      rv[j] = Vp[(size_t)tv * LPR];
-      ra[j] = al[tv];
-      rm[j] = mk[tv];
+      rv[j] = v_row(tv);
+      ra[j] = alpha_at(tv);
+      rm[j] = mask_at(tv);
     };
 #pragma unroll
     for (int j = 0; j < kPrefetch; ++j) refill(j, ga + j);
-    const uint4 vraw_first = Vp[(size_t)ga * LPR];
+    const uint4 vraw_first = v_row(ga);
     float alpha_cur = al[ga];
     uint32_t mask_cur = mk[ga];
 
@@ -246,7 +255,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       float a_before = 0.f;
       if (head_open) {                               // C_{ga-1} from the row before the group
         float vb[EPL];
-        Piece<T>::unpack(Vp[(size_t)(ga - 1) * LPR], vb);
+        Piece<T>::unpack(v_row(ga - 1), vb);
         a_before = al[ga - 1];
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {

@@ -50,10 +50,10 @@ def test_workspace_size_grows_with_the_problem():
     small = kvs.kvs_workspace_size(problem())
     big = kvs.kvs_workspace_size(problem(lens=[100000, 500]))
     assert small % 256 == 0 and big > small
-    # pieces: chunk statistics, chunk o_bar, alpha_bar, o_bar, edge mask, slot map
+    # pieces: chunk statistics, row normalisers, chunk o_bar, alpha_bar, o_bar, edge mask, slot map
     rows, nu, R, D = 1524, 2, 8, 64
-    lower = nu * 64 * R * 8 + nu * 64 * D * 4 + rows * 4 + nu * D * 4 + rows + rows * 4
-    assert lower <= small <= lower + 6 * 256
+    lower = nu * 64 * R * 8 + nu * R * 4 + nu * 64 * D * 4 + rows * 4 + nu * D * 4 + rows + rows * 4
+    assert lower <= small <= lower + 7 * 256
 
 
 @pytest.mark.parametrize("kw,want", [
@@ -61,6 +61,8 @@ def test_workspace_size_grows_with_the_problem():
     (dict(group=0), kvs.KVS_ERR_INVALID_ARG),
     (dict(group=64, window=32), kvs.KVS_ERR_INVALID_ARG),          # G*W above KVS_MAX_Q_ROWS
     (dict(lens=[0, 5]), kvs.KVS_ERR_INVALID_ARG),
+    (dict(lens=[(1 << 22) + 1, 5], budgets=[1 << 21, 5]), kvs.KVS_ERR_INVALID_ARG),   # above KVS_MAX_LEN
+    (dict(lens=[1 << 22, 5], budgets=[1 << 21, 5]), kvs.KVS_OK),
     (dict(n_sink=-1), kvs.KVS_ERR_INVALID_ARG),
     (dict(scale=float("nan")), kvs.KVS_ERR_INVALID_ARG),
     (dict(dtype=7), kvs.KVS_ERR_DTYPE),
