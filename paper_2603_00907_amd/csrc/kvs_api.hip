@@ -62,14 +62,29 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
     un.out_row = p->out_row[u];
     un.len = (int)len;
     un.n_out = (int)std::min(len, budget);
-    const int per = (int)((len + kMaxChunks - 1) / kMaxChunks);
-    un.chunk_len = std::max(kMinChunkLen, (per + kWave - 1) / kWave * kWave);
-    un.n_chunks = (int)((len + un.chunk_len - 1) / un.chunk_len);
+    un.chunk_len = 0;                 // set below, once the total amount of work is known
+    un.n_chunks = 0;
     un.chunk_base = un.m_base = 0;
     un.index = u;
     un.o_base = 0;
     plan->rows_in = std::max(plan->rows_in, un.in_row + len);
     plan->rows_out = std::max(plan->rows_out, un.out_row + (long long)un.n_out);
+  }
+  // Score chunks (one workgroup each): long enough that a workgroup's prologue (Q block, statistics)
+  // is a small part of its life, short enough that one launch (at most kMaxUnitsPerLaunch units) still
+  // has a few workgroups for every slot of the chip; never more than kMaxChunks per unit.
+  {
+    long long total = 0;
+    for (int u = 0; u < std::min(p->n_units, kMaxUnitsPerLaunch); ++u) total += p->len[u];
+    long long want = total / kScoreWorkgroups;
+    if (const char* e = std::getenv("KVS_SCORE_CHUNK")) want = std::atoll(e);   // tuning aid
+    want = std::min<long long>(std::max<long long>(want, kMinChunkLen), kMaxChunkLen);
+    for (int u = 0; u < p->n_units; ++u) {
+      Unit& un = plan->units[u];
+      const long long per = std::max<long long>(want, (un.len + kMaxChunks - 1) / kMaxChunks);
+      un.chunk_len = (int)((per + kWave - 1) / kWave * kWave);
+      un.n_chunks = (un.len + un.chunk_len - 1) / un.chunk_len;
+    }
   }
   // the units' row ranges must not overlap, on the input and on the output side
   std::vector<std::pair<long long, long long>> in(p->n_units), out(p->n_units);

@@ -11,6 +11,8 @@ namespace kvs {
 constexpr int kMaxUnitsPerLaunch = 64;   // unit descriptors travel by value in the kernel arguments
 constexpr int kMaxChunks = 64;           // token chunks (= score workgroups) per unit
 constexpr int kMinChunkLen = 256;        // tokens
+constexpr int kMaxChunkLen = 2048;       // tokens
+constexpr int kScoreWorkgroups = 1024;   // score workgroups a launch aims for (4 per CU)
 constexpr int kObarMinChunk = 1024;      // tokens per workgroup of the o_bar pass (at most kMaxChunks per unit)
 #ifndef KVS_MERGE_TOKENS
 #define KVS_MERGE_TOKENS 256
