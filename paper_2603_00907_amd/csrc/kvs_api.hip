@@ -172,7 +172,11 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
     tab.total_chunks = chunks;
     tab.total_mblocks = mblocks;
     tab.total_ochunks = ochunks;
-    if (f(tab) != hipSuccess) return KVS_ERR_DEVICE;
+    long long rows = 0;
+    for (int i = 0; i < tab.n_units; ++i) rows += tab.u[i].len;
+    Shape sh = plan.shape;
+    sh.stream = 2 * rows * sh.D * (long long)plan.elt > kStreamBytes;
+    if (f(tab, sh) != hipSuccess) return KVS_ERR_DEVICE;
   }
   return KVS_OK;
 }
@@ -220,12 +224,12 @@ kvs_status kvs_score(const kvs_problem* p, const void* Q, const void* K, const v
                      {ws, w.bytes, true}});
   if (st != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
-  return for_each_group(plan, [&](const UnitTable& tab) {
-    hipError_t e = launch_score(tab, plan.shape, plan.dtype, Q, K, alpha_bar, w, s);
+  return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, alpha_bar, w, s);
     if (e != hipSuccess) return e;
-    e = launch_select_obar(tab, plan.shape, plan.dtype, false, alpha_bar, nullptr, nullptr, V, w.o_part, s);
+    e = launch_select_obar(tab, sh, plan.dtype, false, alpha_bar, nullptr, nullptr, V, w.o_part, s);
     if (e != hipSuccess) return e;
-    return launch_obar_reduce(tab, plan.shape, w.o_part, o_bar, s);
+    return launch_obar_reduce(tab, sh, w.o_part, o_bar, s);
   });
 }
 
@@ -241,8 +245,8 @@ kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar, uint8_t* edg
                      {slot_of_token, (size_t)plan.rows_in * 4, true}});
   if (st != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
-  return for_each_group(plan, [&](const UnitTable& tab) {
-    return launch_select_obar(tab, plan.shape, plan.dtype, true, alpha_bar, edge_mask, slot_of_token, nullptr,
+  return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
+    return launch_select_obar(tab, sh, plan.dtype, true, alpha_bar, edge_mask, slot_of_token, nullptr,
                               nullptr, s);
   });
 }
@@ -269,8 +273,8 @@ kvs_status kvs_merge_compact(const kvs_problem* p, const void* K, const void* V,
                      {counts_out, (size_t)plan.rows_out * 4, true}});
   if (st != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
-  return for_each_group(plan, [&](const UnitTable& tab) {
-    return launch_merge(tab, plan.shape, plan.dtype, K, V, alpha_bar, o_bar, nullptr, edge_mask, slot_of_token,
+  return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
+    return launch_merge(tab, sh, plan.dtype, K, V, alpha_bar, o_bar, nullptr, edge_mask, slot_of_token,
                         K_out, V_out, counts_out, s);
   });
 }
@@ -299,12 +303,12 @@ kvs_status kvs_step(const kvs_problem* p, const void* Q, const void* K, const vo
   uint8_t* mask = edge_mask_out ? edge_mask_out : w.edge_mask;
   int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
   hipStream_t s = (hipStream_t)hip_stream;
-  return for_each_group(plan, [&](const UnitTable& tab) {
-    hipError_t e = launch_score(tab, plan.shape, plan.dtype, Q, K, w.alpha_bar, w, s);
+  return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, w.alpha_bar, w, s);
     if (e != hipSuccess) return e;
-    e = launch_select_obar(tab, plan.shape, plan.dtype, true, w.alpha_bar, mask, slot, V, w.o_part, s);
+    e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, V, w.o_part, s);
     if (e != hipSuccess) return e;
-    return launch_merge(tab, plan.shape, plan.dtype, K, V, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,
+    return launch_merge(tab, sh, plan.dtype, K, V, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,
                         V_out, counts_out, s);
   });
 }

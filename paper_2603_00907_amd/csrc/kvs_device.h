@@ -19,6 +19,9 @@ constexpr int kObarMinChunk = 1024;      // tokens per workgroup of the o_bar pa
 #endif
 constexpr int kMergeTokens = KVS_MERGE_TOKENS;   // tokens per merge workgroup
 constexpr int kWave = 64;
+// K plus V bytes of one launch above which rows are streamed past the caches (256 MB of memory-side
+// cache: below that, a sweep finds the rows its predecessor left there)
+constexpr long long kStreamBytes = 192ll << 20;
 
 // One (sequence, KV head).  Rows are in elements of D, not bytes.
 struct Unit {
@@ -59,6 +62,7 @@ struct Shape {
   int n_sink;
   int n_recent;
   float scale_log2; // logit scale * log2(e): logits are kept in the base-2 domain
+  int stream;       // 1: the launch's K and V exceed the last-level cache, rows are read non-temporally
 };
 
 // Workspace carve-up (all offsets multiples of 256 bytes).

@@ -33,6 +33,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kTile = 32;                 // tokens per MFMA tile
+constexpr int kNonTemporal = 2;           // cache-policy bit of K tile loads that no later sweep finds cached anyway
 
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -399,7 +400,7 @@ __device__ __forceinline__ void lds_read_2x2(bf16x8& b00, bf16x8& b01, bf16x8& b
 // tile (16 KB of LDS reads per tile, hidden behind the MFMAs already in the pipe).  The K tile is
 // moved to registers whole (all k-steps) at the start of a tile, which frees its single LDS buffer
 // for the wavefront's next tile at once: that load flies during both halves' MFMAs and softmax work.
-template <int D, int PHASE>
+template <int D, int PHASE, bool STREAM>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     float* __restrict__ alpha_bar, float2* __restrict__ stats_part, const float* __restrict__ c_row) {
@@ -456,7 +457,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     const unsigned char* base = Kg + (size_t)base_t * ROWB;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]), KVS_LDS_PTR(my_k + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]), KVS_LDS_PTR(my_k + i * 1024), 16, 0,
+                                       STREAM ? kNonTemporal : 0);
     }
     return true;
   };
@@ -631,18 +633,25 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   }
 }
 
-template <int D>
-hipError_t launch_wide(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
-                       const Workspace& ws, hipStream_t stream) {
+template <int D, bool STREAM>
+hipError_t launch_wide_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
+                         const Workspace& ws, hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
-  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
+  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0, STREAM>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
                      (const uint16_t*)K, alpha_bar, ws.stats_part, ws.c_row);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
-  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
+  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
                      (const uint16_t*)K, alpha_bar, ws.stats_part, ws.c_row);
   return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_wide(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
+                       const Workspace& ws, hipStream_t stream) {
+  return sh.stream ? launch_wide_t<D, true>(tab, sh, Q, K, alpha_bar, ws, stream)
+                   : launch_wide_t<D, false>(tab, sh, Q, K, alpha_bar, ws, stream);
 }
 
 template <int D, int NT, int WQ>

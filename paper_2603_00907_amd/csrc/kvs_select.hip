@@ -544,7 +544,7 @@ __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, con
   for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
 }
 
-template <typename T, int D>
+template <typename T, int D, bool STREAM>
 __device__ __forceinline__ void obar_chunk(const Unit& un, int chunk, const T* __restrict__ V, const float* __restrict__ alpha_bar,
                            float* __restrict__ o_part, float (*sm_o)[128]) {
   constexpr int EPL = Piece<T>::N;
@@ -570,7 +570,12 @@ __device__ __forceinline__ void obar_chunk(const Unit& un, int chunk, const T* _
     for (int u = 0; u < UNROLL; ++u) {
       const int t = tb + u * RPB;
       const int tc = min(t, t1 - 1);
-      raw[u] = Vp[(size_t)tc * LPR];
+      {   // a launch larger than the caches reads V non-temporally: the stream then does not sweep L2
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4* src = reinterpret_cast<const u32x4*>(Vp + (size_t)tc * LPR);
+        const u32x4 r = STREAM ? __builtin_nontemporal_load(src) : *src;
+        raw[u] = make_uint4(r.x, r.y, r.z, r.w);
+      }
       a[u] = (t < t1) ? al[tc] : 0.f;
     }
 #pragma unroll
@@ -613,7 +618,8 @@ __global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
     const int c = b - n_select;
     int ui = 0;
     while (ui + 1 < tab.n_units && tab.u[ui + 1].o_base <= c) ++ui;
-    obar_chunk<T, D>(tab.u[ui], c - tab.u[ui].o_base, V, alpha_bar, o_part, sm_o);
+    if (sh.stream) obar_chunk<T, D, true>(tab.u[ui], c - tab.u[ui].o_base, V, alpha_bar, o_part, sm_o);
+    else obar_chunk<T, D, false>(tab.u[ui], c - tab.u[ui].o_base, V, alpha_bar, o_part, sm_o);
   }
 }
 
