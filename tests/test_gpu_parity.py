@@ -358,6 +358,14 @@ def test_step_ragged_batch_reduced():
     check_step(w, accepted)
 
 
+def test_step_more_units_than_one_launch_takes():
+    """70 short units of the headline shape (bf16, 128 query rows) in ONE call: the library splits them into
+    launch groups of 64; every unit is checked like any other."""
+    w = WORKLOADS["llama8b_32k"].scaled(length=("fixed", 1500), budget=("fixed", 400))
+    accepted = [accepted_unit(w, layer, 0, layer % w.n_kv_heads, n=1500 - 13 * (layer % 7)) for layer in range(70)]
+    check_step(w, accepted)
+
+
 def test_step_stress_reduced():
     """Stress recipe (512 query rows, Student-t Values, rho 0.95) at 16384 tokens -> 1024, two heads."""
     w = WORKLOADS["stress128k"].scaled(length=("fixed", 16384), budget=("fixed", 1024))
