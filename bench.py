@@ -101,7 +101,7 @@ def main():
     t_gen = time.time()
     workers = min(16, os.cpu_count() or 1)
     keep_host = {}                     # units kept on the host for the oracle sample
-    n_keep_layers = 0 if args.no_cpu_baseline else min(layers, 4)
+    n_keep_layers = 0 if args.no_cpu_baseline else layers       # fp32 copies on the host, 34 MB per unit
 
     def upload(x32):
         if w.dtype == "f32":

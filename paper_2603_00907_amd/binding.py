@@ -51,6 +51,13 @@ def load_library(path: Optional[str] = None):
     if not os.path.exists(path):
         raise FileNotFoundError(
             f"{path} is missing: build it with `python -m paper_2603_00907_amd.build` (hipcc, gfx950)")
+    # The device pointers handed to the library come from PyTorch, so both must talk to ONE HIP runtime:
+    # torch's.  torch bundles its own libamdhip64 under the same SONAME as the system's; whichever is
+    # loaded first serves both, and with the system's loaded first the library's launches find no device.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(path)
     P, vp, sz = C.POINTER(KvsProblemStruct), C.c_void_p, C.c_size_t
     lib.kvs_workspace_size.argtypes = [P, C.POINTER(sz)]

@@ -2,6 +2,7 @@
 // Everything that can fail because of the arguments fails here, before the first launch.
 #include <algorithm>
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <vector>
@@ -176,7 +177,14 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
     for (int i = 0; i < tab.n_units; ++i) rows += tab.u[i].len;
     Shape sh = plan.shape;
     sh.stream = 2 * rows * sh.D * (long long)plan.elt > kStreamBytes;
-    if (f(tab, sh) != hipSuccess) return KVS_ERR_DEVICE;
+    const hipError_t e = f(tab, sh);
+    if (e != hipSuccess) {
+      if (std::getenv("KVS_VERBOSE")) {
+        std::fprintf(stderr, "libkvs: launch failed in the group of units %d..%d: %s\n", first, first + tab.n_units - 1,
+                     hipGetErrorString(e));
+      }
+      return KVS_ERR_DEVICE;
+    }
   }
   return KVS_OK;
 }
