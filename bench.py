@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
     ap.add_argument("--layers-per-call", type=int, default=0,
                     help="layers handed to one kvs_step call (0 = all; 1 = one call per layer)")
+    ap.add_argument("--streams", type=int, default=1, help="deal the kvs_step calls of a step round-robin to this many streams")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching from the host")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -139,9 +140,25 @@ def main():
     slot = torch.empty(big.rows_in, dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
 
+    n_streams = max(1, args.streams)
+    side_streams = [torch.cuda.Stream() for _ in range(n_streams - 1)]
+    wss = [ws] + [torch.empty_like(ws) for _ in side_streams]
+
     def one_step():
+        if n_streams == 1:
+            for i, pr in enumerate(probs):
+                kvs.kvs_step(pr, Qs[i], Ks[i], Vs[i], K_out[i], V_out[i], counts[i], ws, stream=stream)
+            return
+        # calls dealt round-robin to several streams (each with its own workspace): independent calls overlap
+        main = torch.cuda.current_stream()
+        for st in side_streams:
+            st.wait_stream(main)
         for i, pr in enumerate(probs):
-            kvs.kvs_step(pr, Qs[i], Ks[i], Vs[i], K_out[i], V_out[i], counts[i], ws, stream=stream)
+            j = i % n_streams
+            sj = stream if j == 0 else side_streams[j - 1].cuda_stream
+            kvs.kvs_step(pr, Qs[i], Ks[i], Vs[i], K_out[i], V_out[i], counts[i], wss[j], stream=sj)
+        for st in side_streams:
+            main.wait_stream(st)
 
     # Optionally the launches of one step (4 kernels per layer) are captured once into a HIP graph and
     # replayed: the library never allocates, synchronises or memsets, so a step is capturable as it is.
@@ -177,6 +194,30 @@ def main():
     ms_per_step = max(wall_ms, gpu_ms) / args.steps
     tokens_per_step = layers * sum(lens_seq)          # one token = the K and V rows of all KV heads at one position
     value = tokens_per_step / (ms_per_step * 1e-3)
+
+    # ---- for comparison: the same step as one kvs_step call per layer, layer after layer on the same stream
+    seq_ms = None
+    if lpc != 1 and not args.graph:
+        one = kvs.Problem(lens=lens, budgets=budgets, group=w.group, window=w.window, head_dim=D, dtype=w.dtype,
+                          n_sink=w.n_sink, n_recent=w.n_recent)
+        nu = len(lens)
+
+        def layer_calls():
+            for i, bt in enumerate(batches):
+                for j in range(len(bt)):
+                    r0, r1, o0, o1 = j * rows_layer, (j + 1) * rows_layer, j * one.rows_out, (j + 1) * one.rows_out
+                    kvs.kvs_step(one, Qs[i][j * nu:(j + 1) * nu], Ks[i][r0:r1], Vs[i][r0:r1], K_out[i][o0:o1],
+                                 V_out[i][o0:o1], counts[i][o0:o1], ws, stream=stream)
+
+        layer_calls()
+        torch.cuda.synchronize()
+        n_rep = max(1, min(args.steps, 5))
+        ev0.record()
+        for _ in range(n_rep):
+            layer_calls()
+        ev1.record()
+        torch.cuda.synchronize()
+        seq_ms = ev0.elapsed_time(ev1) / n_rep
 
     # ---- per-phase timing, same inputs, the three entry points one after the other with events between
     phases = ["score", "select", "merge_compact"]
@@ -225,7 +266,12 @@ def main():
         "config": {"workload": w.name, "layers": layers, "kv_heads": w.n_kv_heads, "q_heads": w.group * w.n_kv_heads,
                    "head_dim": D, "window": w.window, "tokens": lens_seq if w.n_seq > 1 else lens_seq[0],
                    "budget": budgets[0] if w.n_seq == 1 else "25% of length", "n_sink": w.n_sink,
-                   "layers_per_call": lpc, "launch": "hip graph replay" if args.graph else "host", "us_per_layer": ms_per_step * 1e3 / layers, "input_generation_s": round(t_gen, 1)},
+                   "layers_per_call": lpc, "streams": n_streams, "launch": "hip graph replay" if args.graph else "host",
+                   "us_per_layer": ms_per_step * 1e3 / layers,
+                   "one_call_per_layer": None if seq_ms is None else {
+                       "ms_per_step": seq_ms, "us_per_layer": seq_ms * 1e3 / layers,
+                       "value": tokens_per_step / (seq_ms * 1e-3)},
+                   "input_generation_s": round(t_gen, 1)},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": (measured_traffic(w.name) or {}).get(dominant),
