@@ -54,17 +54,6 @@ __device__ __forceinline__ void lds_read_4x16(bf16x8& a0, bf16x8& a1, bf16x8& a2
       : "memory");
 }
 
-#ifdef KVS_TRACE
-// Developer build only: per-wavefront time stamps of the sweep's stages.
-__device__ long long g_trace[8192 * 16];
-#define KVS_STAMP(slot)                                                                      \
-  do {                                                                                       \
-    if (lane == 0 && PHASE == KVS_TRACE) g_trace[(blockIdx.x * kWaves + wave) * 16 + (slot)] = clock64(); \
-  } while (0)
-#else
-#define KVS_STAMP(slot) do { } while (0)
-#endif
-
 #define KVS_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define KVS_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
@@ -138,9 +127,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     return true;
   };
 
-  KVS_STAMP(0);
   if (PHASE == 1) load_row_consts(c_row, un.index, R, sm_c);
-  KVS_STAMP(1);
 
   for (int qp = 0; qp < R; qp += PASS_ROWS) {
     const bool first_pass = (qp == 0);
@@ -165,11 +152,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(Qg + (size_t)qrow * LPR + piece),
                                          KVS_LDS_PTR(my_k + TILEB + i * 1024), 16, 0, 0);
       }
-      KVS_STAMP(11);
       __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0)
-      KVS_STAMP(12);
       __syncthreads();
-      KVS_STAMP(13);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const int row = nt * 32 + col;
@@ -182,7 +166,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
           bq[nt][kk] = *reinterpret_cast<const bf16x8*>(src + slot * 16);
         }
       }
-      KVS_STAMP(14);
       __syncthreads();                                // the second buffers go back to the K tiles
     } else {
 #pragma unroll
@@ -199,7 +182,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       }
     }
     bool next_in_flight = (iters > 1) && issue_tile(wt + WT, 1);   // loads of the tile after the current one
-    KVS_STAMP(2);
 
     float m_run[NT], l_run[NT];
 #pragma unroll
@@ -217,7 +199,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       if (next_in_flight) __builtin_amdgcn_s_waitcnt(0x0F70 | (NLD & 15) | ((NLD >> 4) << 14));   // vmcnt(NLD)
       else __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
       asm volatile("" ::: "memory");
-      if (it < 6) KVS_STAMP(3 + 2 * it);
       static_assert(KS == 4 || KS == 8, "operand reads come in groups of four");
       constexpr int KH = 4;
       f32x16 acc[NT];
@@ -265,7 +246,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         }
       }
 
-      if (it < 6) KVS_STAMP(4 + 2 * it);            // MFMAs issued
       if (PHASE == 0) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
@@ -344,7 +324,6 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
       }
     }
 
-    KVS_STAMP(15);
     if (PHASE == 0) {
       // the two halves of a wavefront hold the same query column for different token rows
 #pragma unroll
@@ -697,11 +676,5 @@ hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* 
   return sh.D == 64 ? launch_d<64>(tab, sh, Q, K, alpha_bar, ws, stream)
                     : launch_d<128>(tab, sh, Q, K, alpha_bar, ws, stream);
 }
-
-#ifdef KVS_TRACE
-extern "C" int kvs_debug_trace(void* host, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace), bytes);
-}
-#endif
 
 }  // namespace kvs

@@ -38,13 +38,6 @@ __device__ __forceinline__ int lanes_below(uint64_t ballot, int lane) {
   return __popcll(ballot & ((1ull << lane) - 1ull));
 }
 
-#ifdef KVS_TRACE_SEL
-__device__ long long g_trace_sel[64 * 16];
-#define KVS_SSTAMP(slot) do { if (threadIdx.x == 0) g_trace_sel[blockIdx.x * 16 + (slot)] = clock64(); } while (0)
-#else
-#define KVS_SSTAMP(slot) do { } while (0)
-#endif
-
 constexpr int kCand = 2048;               // keys of the first-pass bin that are refined in LDS
 
 struct SelectSmem {
@@ -151,13 +144,11 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
   constexpr int GPT = kLdsKeys / 4 / kSelThreads;  // groups per thread
   constexpr uint32_t kNone = 0xffffffffu;
   uint4* k4 = reinterpret_cast<uint4*>(sm.keys);
-  KVS_SSTAMP(0);
 
   // ---- keys and the histogram of their first digit: all of a thread's loads are in flight together
   for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
   if (tid == 0) sm.ncand = 0;
   __syncthreads();
-  KVS_SSTAMP(7);
   {
     float4 v[GPT];
     float nx[GPT];
@@ -202,11 +193,6 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
         }
       }
     }
-    KVS_SSTAMP(8);
-#ifdef KVS_TRACE_SEL
-    if (tid == 15 * 64) g_trace_sel[blockIdx.x * 16 + 13] = clock64();
-    if (tid == 8 * 64) g_trace_sel[blockIdx.x * 16 + 14] = clock64();
-#endif
     kmin = wave_min_u32(kmin);
     kmax = wave_max_u32(kmax);
     if (lane == 0) { sm.wmin[wave] = kmin; sm.wmax[wave] = kmax; }
@@ -242,13 +228,10 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
       }
     }
   }
-  KVS_SSTAMP(9);
   __syncthreads();
   uint32_t prefix = 0, pmask = 0;
   int want = r;                        // rank (1-based) among the keys that share `prefix`
-  KVS_SSTAMP(1);
   pick_bin(sm, 21, 2048, prefix, pmask, want);
-  KVS_SSTAMP(2);
 
   // ---- the keys of that bin go to a short list (one LDS atomic per wavefront: every lane counts its
   //      matches, a scan gives it its place); the remaining 21 bits are settled on the list
@@ -284,13 +267,8 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
       }
     }
   }
-  KVS_SSTAMP(10);
   __syncthreads();
   const int ncand = sm.ncand;
-  KVS_SSTAMP(3);
-#ifdef KVS_TRACE_SEL
-  if (tid == 0) g_trace_sel[blockIdx.x * 16 + 12] = ncand;
-#endif
   int n_equal;                         // keys equal to the threshold
   if (ncand <= kWave) {
     // A handful of candidates: all against all.  Lane i of every wavefront holds candidate i, wavefront
@@ -358,7 +336,6 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
   // "below T + 1" and nothing has to be ranked.
   const bool simple = (n_equal == want);
   const uint32_t Tc = simple ? T + 1 : T;
-  KVS_SSTAMP(4);
 
   // ---- ordered pass: wavefront w owns the groups [g0, g1), lane l the groups g0 + it * 64 + l
   constexpr int ITS = kLdsKeys / 4 / kSelWaves / kWave;      // rounds per wavefront
@@ -383,7 +360,6 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
   }
   if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
   __syncthreads();
-  KVS_SSTAMP(5);
   int eq_before = 0, sel_before = waves_before(sm.lt, wave, lane);
   if (!simple) {
     for (int w = 0; w < wave; ++w) {
@@ -457,7 +433,6 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
   // tokens outside the eligible edge range
   for (int t = tid; t < lo && t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t; }
   for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
-  KVS_SSTAMP(6);
 }
 
 __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, const float* __restrict__ alpha_bar,
@@ -664,10 +639,5 @@ hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float
   return hipGetLastError();
 }
 
-#ifdef KVS_TRACE_SEL
-extern "C" int kvs_debug_trace_sel(void* host, size_t bytes) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_sel), bytes);
-}
-#endif
 
 }  // namespace kvs
