@@ -33,6 +33,16 @@ head):
          adjacent blocks kept.  Merged Value: the sum (Sec. 3.1, v* = v_m + v_{m+1}),
          with the slot's cardinality returned beside it.
 
+Streaming regime (Sec. 3.1, last paragraph, and Sec. 5: the cache is compressed
+again every time it exceeds the budget by a chunk): the input may itself be a
+merged cache, every row a slot (k, V, c) that stands for c tokens sharing the Key
+k whose Values add up to V (the "(k, k)" replacement of Sec. 3.1 carried along
+with its cardinality).  For the attention output such a slot is exactly one token
+with logit e + ln c and value V / c, and that is how every function below treats
+it when `counts` is given: alpha_bar is then the slot's total mass, the residual
+of O8 is V / c - o, merged Values stay sums and merged cardinalities add up.
+Without `counts` every row is a plain token (c = 1).
+
 Readings of points the paper leaves open (many query rows, ranking score, runs
 longer than two, a non-positive denominator) are this module's and are listed
 in the repository's design notes.
@@ -57,24 +67,39 @@ F64 = np.float64
 
 
 # --------------------------------------------------------------------------- O1-O4
-def attention_rows(Q: np.ndarray, K: np.ndarray, scale: Optional[float] = None) -> np.ndarray:
-    """alpha[q, t] of Eq. "attn_def_vec" for every row q of Q [R, D] over K [n, D]."""
+def attention_rows(Q: np.ndarray, K: np.ndarray, scale: Optional[float] = None,
+                   counts: Optional[np.ndarray] = None) -> np.ndarray:
+    """alpha[q, t] of Eq. "attn_def_vec" for every row q of Q [R, D] over K [n, D].
+
+    With `counts`, row t of K stands for counts[t] tokens with that Key and alpha[q, t] is their total
+    mass: c equal terms exp(e) in the softmax sums are one term exp(e + ln c)."""
     Q = np.asarray(Q, dtype=F64).reshape(-1, K.shape[-1])
     K = np.asarray(K, dtype=F64)
     if scale is None:
         scale = 1.0 / np.sqrt(K.shape[1])
     e = scale * (Q @ K.T)                                   # O1
+    if counts is not None:
+        e = e + np.log(np.asarray(counts, dtype=F64))[None, :]
     e = e - e.max(axis=1, keepdims=True)
     p = np.exp(e)
     return p / p.sum(axis=1, keepdims=True)                 # O2
 
 
-def score(Q: np.ndarray, K: np.ndarray, V: np.ndarray,
-          scale: Optional[float] = None) -> Tuple[np.ndarray, np.ndarray]:
-    """alpha_bar[n] (mean of the rows' attention) and o_bar[D] = sum_t alpha_bar[t] V[t]."""
-    alpha = attention_rows(Q, K, scale)
+def slot_values(V: np.ndarray, counts: Optional[np.ndarray]) -> np.ndarray:
+    """The value a row contributes per unit of attention mass: V[t], or V[t] / counts[t] for a merged slot
+    (its Values are a sum over counts[t] tokens)."""
+    V = np.asarray(V, dtype=F64)
+    if counts is None:
+        return V
+    return V / np.asarray(counts, dtype=F64)[:, None]
+
+
+def score(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: Optional[float] = None,
+          counts: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+    """alpha_bar[n] (mean of the rows' attention) and o_bar[D] = sum_t alpha_bar[t] v[t]."""
+    alpha = attention_rows(Q, K, scale, counts)
     alpha_bar = alpha.mean(axis=0)                          # O3
-    o_bar = alpha_bar @ np.asarray(V, dtype=F64)            # O4
+    o_bar = alpha_bar @ slot_values(V, counts)              # O4
     return alpha_bar, o_bar
 
 
@@ -128,10 +153,11 @@ def boundary_gap(alpha_bar: np.ndarray, budget: int, n_sink: int = 32, n_recent:
 
 
 # --------------------------------------------------------------------------- O8-O9
-def token_and_edge_norms(alpha_bar: np.ndarray, V: np.ndarray, o_bar: np.ndarray):
+def token_and_edge_norms(alpha_bar: np.ndarray, V: np.ndarray, o_bar: np.ndarray,
+                         counts: Optional[np.ndarray] = None):
     """A_t = ||c_tt||_2 for every token and C_t = ||c_{t,t+1}||_2 for every edge (Eqs. c11_def-c12_def)."""
     a = np.asarray(alpha_bar, dtype=F64)
-    resid = np.asarray(V, dtype=F64) - np.asarray(o_bar, dtype=F64)[None, :]      # r_t = v_t - o
+    resid = slot_values(V, counts) - np.asarray(o_bar, dtype=F64)[None, :]        # r_t = v_t - o
     A = np.linalg.norm((a * (1.0 - 2.0 * a))[:, None] * resid, axis=1)
     C = np.linalg.norm(-(a[:-1] * a[1:])[:, None] * (resid[:-1] + resid[1:]), axis=1)
     return A, C
@@ -141,22 +167,25 @@ def token_and_edge_norms(alpha_bar: np.ndarray, V: np.ndarray, o_bar: np.ndarray
 class MergeResult:
     K_out: np.ndarray        # [n_out, D] fp64
     V_out: np.ndarray        # [n_out, D] fp64
-    counts: np.ndarray       # [n_out] int32
+    counts: np.ndarray       # [n_out] int32: tokens the slot stands for
+    n_rows: np.ndarray       # [n_out] int32: input rows merged into the slot
     U: np.ndarray            # [n_out] denominator of the Key weights (A_t for singletons)
     A_sum: np.ndarray        # [n_out] sum of A_t over the slot
     fallback: np.ndarray     # [n_out] bool: arithmetic-mean fallback taken
 
 
 def merge_compact(K: np.ndarray, V: np.ndarray, alpha_bar: np.ndarray, o_bar: np.ndarray,
-                  mask: np.ndarray, slot: np.ndarray) -> MergeResult:
+                  mask: np.ndarray, slot: np.ndarray, counts_in: Optional[np.ndarray] = None) -> MergeResult:
     K = np.asarray(K, dtype=F64)
     V = np.asarray(V, dtype=F64)
     n, D = K.shape
-    A, C = token_and_edge_norms(alpha_bar, V, o_bar)
+    c_in = np.ones(n, dtype=np.int64) if counts_in is None else np.asarray(counts_in, dtype=np.int64)
+    A, C = token_and_edge_norms(alpha_bar, V, o_bar, counts_in)
     n_out = int(slot[-1]) + 1 if n else 0
     K_out = np.zeros((n_out, D), dtype=F64)
     V_out = np.zeros((n_out, V.shape[1]), dtype=F64)
     counts = np.zeros(n_out, dtype=np.int32)
+    n_rows = np.zeros(n_out, dtype=np.int32)
     U_all = np.zeros(n_out, dtype=F64)
     A_sum = np.zeros(n_out, dtype=F64)
     fallback = np.zeros(n_out, dtype=bool)
@@ -168,7 +197,8 @@ def merge_compact(K: np.ndarray, V: np.ndarray, alpha_bar: np.ndarray, o_bar: np
         t1 = t                                              # slot S = tokens t0..t1 inclusive
         t += 1
         assert slot[t0] == S and slot[t1] == S
-        counts[S] = t1 - t0 + 1
+        counts[S] = c_in[t0:t1 + 1].sum()                   # cardinalities add up
+        n_rows[S] = t1 - t0 + 1
         V_out[S] = V[t0:t1 + 1].sum(axis=0)
         A_sum[S] = A[t0:t1 + 1].sum()
         if t1 == t0:
@@ -183,15 +213,15 @@ def merge_compact(K: np.ndarray, V: np.ndarray, alpha_bar: np.ndarray, o_bar: np
         if np.isfinite(U) and U > 0.0:
             K_out[S] = (u[:, None] * K[t0:t1 + 1]).sum(axis=0) / U
         else:
-            fallback[S] = True
-            K_out[S] = K[t0:t1 + 1].mean(axis=0)
+            fallback[S] = True                              # mean over the tokens the rows stand for
+            K_out[S] = (c_in[t0:t1 + 1, None] * K[t0:t1 + 1]).sum(axis=0) / c_in[t0:t1 + 1].sum()
     assert t == n
-    return MergeResult(K_out, V_out, counts, U_all, A_sum, fallback)
+    return MergeResult(K_out, V_out, counts, n_rows, U_all, A_sum, fallback)
 
 
 def conditioning(res: MergeResult) -> float:
     """min over merged slots of U / sum_t A_t (1 for an input without merged slots)."""
-    multi = res.counts > 1
+    multi = res.n_rows > 1
     if not multi.any():
         return 1.0
     with np.errstate(divide="ignore", invalid="ignore"):
@@ -211,10 +241,10 @@ class StepResult:
 
 
 def step(Q: np.ndarray, K: np.ndarray, V: np.ndarray, budget: int, n_sink: int = 32,
-         n_recent: int = 0, scale: Optional[float] = None) -> StepResult:
-    alpha_bar, o_bar = score(Q, K, V, scale)
+         n_recent: int = 0, scale: Optional[float] = None, counts: Optional[np.ndarray] = None) -> StepResult:
+    alpha_bar, o_bar = score(Q, K, V, scale, counts)
     mask, slot = select(alpha_bar, budget, n_sink, n_recent)
-    merged = merge_compact(K, V, alpha_bar, o_bar, mask, slot)
+    merged = merge_compact(K, V, alpha_bar, o_bar, mask, slot, counts)
     return StepResult(alpha_bar, o_bar, mask, slot, merged)
 
 

@@ -439,3 +439,102 @@ def test_pair_denominator_positive_when_mass_below_half():
         for m in range(n - 1):
             if ab[m] + ab[m + 1] < 0.5:
                 assert A[m] - 2 * C[m] + A[m + 1] > 0
+
+
+# --------------------------------------------------------------------------------------------
+# Streaming regime: rows that are already merged slots (k, V, c)
+def expanded_cache(K, V, c):
+    """The cache a merged one stands for: slot t becomes c[t] tokens with Key K[t]; their Values are
+    unknown one by one, only their sum V[t] is, so every copy gets V[t] / c[t]."""
+    return np.repeat(K, c, axis=0), np.repeat(V / c[:, None], c, axis=0), np.repeat(np.arange(len(c)), c)
+
+
+def test_counts_of_one_change_nothing():
+    rng = np.random.default_rng(40)
+    Q, K, V = rng.standard_normal((3, 8)), rng.standard_normal((60, 8)) * 2.0, rng.standard_normal((60, 8))
+    a = O.step(Q, K, V, budget=25, n_sink=2)
+    b = O.step(Q, K, V, budget=25, n_sink=2, counts=np.ones(60, dtype=np.int32))
+    assert np.array_equal(a.alpha_bar, b.alpha_bar) and np.array_equal(a.mask, b.mask)
+    assert np.array_equal(a.merged.K_out, b.merged.K_out) and np.array_equal(a.merged.V_out, b.merged.V_out)
+    assert np.array_equal(a.merged.counts, b.merged.counts)
+
+
+@pytest.mark.parametrize("seed", [41, 42])
+def test_slot_of_cardinality_c_attends_like_c_copies(seed):
+    rng = np.random.default_rng(seed)
+    n, d = 9, 5
+    K, V = rng.standard_normal((n, d)) * 1.5, rng.standard_normal((n, d)) * 3.0
+    c = rng.integers(1, 6, size=n)
+    Ke, Ve, owner = expanded_cache(K, V, c)
+    Q = rng.standard_normal((4, d))
+    ab, ob = O.score(Q, K, V, counts=c)
+    rows = [softmax_attention(q, Ke, Ve) for q in Q]            # textbook attention over the expanded cache
+    a_exp = np.mean([r[0] for r in rows], axis=0)
+    mass = np.array([a_exp[owner == t].sum() for t in range(n)])
+    np.testing.assert_allclose(ab, mass, rtol=1e-13)
+    np.testing.assert_allclose(ob, np.mean([r[1] for r in rows], axis=0), rtol=1e-12, atol=1e-15)
+    # and the consumer formula for merged caches (pinned above) gives the same output for one query
+    np.testing.assert_allclose(O.score(Q[:1], K, V, counts=c)[1], O.merged_attention(Q[0], K, V, c), rtol=1e-12)
+
+
+@pytest.mark.parametrize("seed", [43, 44])
+def test_norms_with_counts_match_finite_difference_of_s(seed):
+    """A slot is one token with logit e + ln c and value V / c: the c-vectors are the logit derivatives of
+    s_t = alpha_t (V_t / c_t - o) with alpha the softmax of the shifted logits (textbook side: s_of_logits)."""
+    q, K, V = tiny_head(seed, n=6, d=4, dv=5, spread=1.5)
+    c = np.array([1, 3, 2, 1, 4, 2])
+    e0 = K @ q / np.sqrt(q.shape[0]) + np.log(c)
+    Vs = V / c[:, None]
+    h = 1e-5
+    J = np.zeros((6, 6, 5))
+    for j in range(6):
+        ep, em = e0.copy(), e0.copy()
+        ep[j] += h
+        em[j] -= h
+        J[:, j, :] = (s_of_logits(ep, Vs) - s_of_logits(em, Vs)) / (2 * h)
+    ab, ob = O.score(q[None, :], K, V, counts=c)
+    A, C = O.token_and_edge_norms(ab, V, ob, counts=c)
+    np.testing.assert_allclose(A, [np.linalg.norm(J[i, i]) for i in range(6)], rtol=1e-7)
+    np.testing.assert_allclose(C, [np.linalg.norm(J[i, i + 1]) for i in range(5)], rtol=1e-7)
+
+
+def test_merge_with_counts_invariants_and_lossless_chain():
+    """Cardinalities add up, Values stay sums, single rows are copied, and when the Keys of every run
+    coincide the re-merged cache attends exactly like the cache it was made from (Sec. 3.1)."""
+    rng = np.random.default_rng(45)
+    n, d = 14, 4
+    K, V = rng.standard_normal((n, d)), rng.standard_normal((n, d)) * 2.0
+    c = rng.integers(1, 5, size=n)
+    K[3:6] = K[3]
+    K[9:11] = K[9]
+    mask = np.zeros(n, dtype=np.uint8)
+    mask[3:5] = 1
+    mask[9] = 1
+    slot = np.concatenate([[0], np.cumsum(mask[:-1] == 0)]).astype(np.int32)
+    q = rng.standard_normal(d)
+    ab, ob = O.score(q[None, :], K, V, counts=c)
+    res = O.merge_compact(K, V, ab, ob, mask, slot, counts_in=c)
+    assert res.counts.sum() == c.sum() and res.counts[3] == c[3:6].sum() and res.n_rows[3] == 3
+    np.testing.assert_allclose(res.V_out.sum(axis=0), V.sum(axis=0), rtol=1e-13)
+    assert np.array_equal(res.K_out[0], K[0]) and np.array_equal(res.V_out[0], V[0]) and res.counts[0] == c[0]
+    Ke, Ve, _ = expanded_cache(K, V, c)
+    for _ in range(5):
+        qn = rng.standard_normal(d)
+        want = softmax_attention(qn, Ke, Ve)[1]                  # the tokens the input stood for
+        np.testing.assert_allclose(O.merged_attention(qn, res.K_out, res.V_out, res.counts), want,
+                                   rtol=1e-12, atol=1e-14)
+
+
+def test_fallback_with_counts_is_the_mean_over_the_tokens_the_rows_stand_for():
+    rng = np.random.default_rng(46)
+    K = rng.standard_normal((6, 4))
+    c = np.array([2, 1, 3, 2, 1, 1])
+    V = np.ones((6, 4)) * c[:, None]                             # V / c identical: every residual vanishes
+    q = rng.standard_normal(4)
+    mask = np.array([0, 1, 1, 0, 0, 0], dtype=np.uint8)
+    slot = np.concatenate([[0], np.cumsum(mask[:-1] == 0)]).astype(np.int32)
+    ab, ob = O.score(q[None, :], K, V, counts=c)
+    res = O.merge_compact(K, V, ab, ob, mask, slot, counts_in=c)
+    assert res.fallback[1] and not res.fallback[0]
+    Ke, _, owner = expanded_cache(K, V, c)
+    np.testing.assert_allclose(res.K_out[1], Ke[(owner >= 1) & (owner <= 3)].mean(axis=0), rtol=1e-14)
