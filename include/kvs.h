@@ -41,7 +41,7 @@
 extern "C" {
 #endif
 
-#define KVS_VERSION 100          /* major*10000 + minor*100 + patch */
+#define KVS_VERSION 200          /* major*10000 + minor*100 + patch */
 #define KVS_MAX_Q_ROWS 1024      /* largest supported G*W */
 #define KVS_MAX_LEN (1 << 22)    /* largest supported cache length of one unit, in tokens */
 
@@ -117,6 +117,29 @@ kvs_status kvs_step(const kvs_problem* p, const void* Q, const void* K, const vo
                     void* K_out, void* V_out, int32_t* counts_out,
                     int32_t* slot_of_token_out, uint8_t* edge_mask_out,
                     void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Streaming regime (Sec. 3.1, last paragraph; Sec. 5): the cache is compressed again whenever it has grown
+ * past the budget by a chunk, so the input of a step is itself a merged cache.  Row t then is a slot
+ * (k, V, c): c = counts_in[t] tokens that share the Key k and whose Values add up to V (what
+ * kvs_merge_compact returns as K_out, V_out, counts_out).  Such a slot enters every formula as one token
+ * with logit e + ln c and value V / c: alpha_bar[t] is the slot's total attention mass, o_bar = sum_t
+ * alpha_bar[t] V[t] / c_t, the residual of the Key rule is V[t] / c_t - o_bar, merged Values stay sums,
+ * counts_out[S] = sum of counts_in over the slot, and the fallback Key is the mean over the tokens the rows
+ * stand for.  kvs_select is unchanged (it sees alpha_bar only).
+ *   counts_in DEVICE in [rows] i32, every entry >= 1; NULL = plain tokens, i.e. exactly the calls above.
+ * All other arguments, layouts, ownership and error behaviour are those of the calls above.              */
+kvs_status kvs_score_counts(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                            const int32_t* counts_in, float* alpha_bar, float* o_bar,
+                            void* ws, size_t ws_bytes, void* hip_stream);
+kvs_status kvs_merge_compact_counts(const kvs_problem* p, const void* K, const void* V, const int32_t* counts_in,
+                                    const float* alpha_bar, const float* o_bar,
+                                    const uint8_t* edge_mask, const int32_t* slot_of_token,
+                                    void* K_out, void* V_out, int32_t* counts_out,
+                                    void* ws, size_t ws_bytes, void* hip_stream);
+kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, const void* V, const int32_t* counts_in,
+                           void* K_out, void* V_out, int32_t* counts_out,
+                           int32_t* slot_of_token_out, uint8_t* edge_mask_out,
+                           void* ws, size_t ws_bytes, void* hip_stream);
 
 const char* kvs_status_str(kvs_status s);
 int kvs_version(void);

@@ -20,9 +20,12 @@ from .binding import (  # noqa: F401
     KvsError,
     Problem,
     kvs_merge_compact,
+    kvs_merge_compact_counts,
     kvs_score,
+    kvs_score_counts,
     kvs_select,
     kvs_step,
+    kvs_step_counts,
     kvs_version,
     kvs_workspace_size,
     load_library,

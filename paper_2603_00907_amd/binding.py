@@ -21,7 +21,7 @@ KVS_F32, KVS_BF16 = 0, 1
 DTYPES = {"f32": KVS_F32, "bf16": KVS_BF16}
 
 EXPORTS = ["kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step",
-           "kvs_status_str", "kvs_version"]
+           "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_status_str", "kvs_version"]
 
 
 class KvsProblemStruct(C.Structure):
@@ -65,7 +65,11 @@ def load_library(path: Optional[str] = None):
     lib.kvs_select.argtypes = [P, vp, vp, vp, vp, sz, vp]
     lib.kvs_merge_compact.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_step.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
-    for name in ("kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step"):
+    lib.kvs_score_counts.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_merge_compact_counts.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_step_counts.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    for name in ("kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step",
+                 "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts"):
         getattr(lib, name).restype = C.c_int
     lib.kvs_status_str.argtypes = [C.c_int]
     lib.kvs_status_str.restype = C.c_char_p
@@ -170,3 +174,26 @@ def kvs_step(problem: Problem, Q, K, V, K_out, V_out, counts_out, ws, slot_of_to
         problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out), _ptr(counts_out),
         _ptr(slot_of_token_out), _ptr(edge_mask_out), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
         stream), "kvs_step")
+
+
+def kvs_score_counts(problem: Problem, Q, K, V, counts_in, alpha_bar, o_bar, ws, stream: int = 0,
+                     ws_bytes: Optional[int] = None):
+    _check(load_library().kvs_score_counts(
+        problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(counts_in), _ptr(alpha_bar), _ptr(o_bar), _ptr(ws),
+        _nbytes(ws) if ws_bytes is None else ws_bytes, stream), "kvs_score_counts")
+
+
+def kvs_merge_compact_counts(problem: Problem, K, V, counts_in, alpha_bar, o_bar, edge_mask, slot_of_token, K_out,
+                             V_out, counts_out, ws=None, stream: int = 0):
+    _check(load_library().kvs_merge_compact_counts(
+        problem.ref, _ptr(K), _ptr(V), _ptr(counts_in), _ptr(alpha_bar), _ptr(o_bar), _ptr(edge_mask),
+        _ptr(slot_of_token), _ptr(K_out), _ptr(V_out), _ptr(counts_out), _ptr(ws),
+        _nbytes(ws) if ws is not None else 0, stream), "kvs_merge_compact_counts")
+
+
+def kvs_step_counts(problem: Problem, Q, K, V, counts_in, K_out, V_out, counts_out, ws, slot_of_token_out=None,
+                    edge_mask_out=None, stream: int = 0, ws_bytes: Optional[int] = None):
+    _check(load_library().kvs_step_counts(
+        problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(counts_in), _ptr(K_out), _ptr(V_out), _ptr(counts_out),
+        _ptr(slot_of_token_out), _ptr(edge_mask_out), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
+        stream), "kvs_step_counts")

@@ -12,9 +12,9 @@
 namespace kvs {
 
 hipError_t launch_score_valu(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
-                             float* alpha_bar, const Workspace& ws, hipStream_t stream);
+                             const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream);
 hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                             float* alpha_bar, const Workspace& ws, hipStream_t stream);
+                             const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream);
 bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt);
 
 namespace {
@@ -192,12 +192,14 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
 }  // namespace
 
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
-                        float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+                        const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
   // KVS_SCORE_PATH=valu forces the vector-ALU kernels (used by the tests to cover both paths).
   const char* force = std::getenv("KVS_SCORE_PATH");
   const bool force_valu = force && std::strcmp(force, "valu") == 0;
-  if (!force_valu && score_mfma_supported(tab, sh, dt)) return launch_score_mfma(tab, sh, Q, K, alpha_bar, ws, stream);
-  return launch_score_valu(tab, sh, dt, Q, K, alpha_bar, ws, stream);
+  if (!force_valu && score_mfma_supported(tab, sh, dt)) {
+    return launch_score_mfma(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+  }
+  return launch_score_valu(tab, sh, dt, Q, K, counts_in, alpha_bar, ws, stream);
 }
 
 }  // namespace kvs
@@ -217,6 +219,12 @@ kvs_status kvs_workspace_size(const kvs_problem* p, size_t* bytes) {
 
 kvs_status kvs_score(const kvs_problem* p, const void* Q, const void* K, const void* V, float* alpha_bar,
                      float* o_bar, void* ws, size_t ws_bytes, void* hip_stream) {
+  return kvs_score_counts(p, Q, K, V, nullptr, alpha_bar, o_bar, ws, ws_bytes, hip_stream);
+}
+
+kvs_status kvs_score_counts(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                            const int32_t* counts_in, float* alpha_bar, float* o_bar, void* ws, size_t ws_bytes,
+                            void* hip_stream) {
   Plan plan;
   kvs_status st = make_plan(p, &plan);
   if (st != KVS_OK) return st;
@@ -224,18 +232,19 @@ kvs_status kvs_score(const kvs_problem* p, const void* Q, const void* K, const v
   if ((st = check_ws(plan, ws, ws_bytes, &w, ws)) != KVS_OK) return st;
   const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
   const size_t nu = (size_t)plan.n_units;
-  st = check_ranges({{Q, nu * plan.shape.R * plan.shape.D * plan.elt, false},
-                     {K, kv, false},
-                     {V, kv, false},
-                     {alpha_bar, (size_t)plan.rows_in * 4, true},
-                     {o_bar, nu * plan.shape.D * 4, true},
-                     {ws, w.bytes, true}});
-  if (st != KVS_OK) return st;
+  std::vector<Range> rs = {{Q, nu * plan.shape.R * plan.shape.D * plan.elt, false},
+                           {K, kv, false},
+                           {V, kv, false},
+                           {alpha_bar, (size_t)plan.rows_in * 4, true},
+                           {o_bar, nu * plan.shape.D * 4, true},
+                           {ws, w.bytes, true}};
+  if (counts_in) rs.push_back({counts_in, (size_t)plan.rows_in * 4, false});
+  if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
-    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, alpha_bar, w, s);
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, alpha_bar, w, s);
     if (e != hipSuccess) return e;
-    e = launch_select_obar(tab, sh, plan.dtype, false, alpha_bar, nullptr, nullptr, V, w.o_part, s);
+    e = launch_select_obar(tab, sh, plan.dtype, false, alpha_bar, nullptr, nullptr, V, counts_in, w.o_part, s);
     if (e != hipSuccess) return e;
     return launch_obar_reduce(tab, sh, w.o_part, o_bar, s);
   });
@@ -255,7 +264,7 @@ kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar, uint8_t* edg
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     return launch_select_obar(tab, sh, plan.dtype, true, alpha_bar, edge_mask, slot_of_token, nullptr,
-                              nullptr, s);
+                              nullptr, nullptr, s);
   });
 }
 
@@ -263,6 +272,14 @@ kvs_status kvs_merge_compact(const kvs_problem* p, const void* K, const void* V,
                              const float* o_bar, const uint8_t* edge_mask, const int32_t* slot_of_token,
                              void* K_out, void* V_out, int32_t* counts_out, void* ws, size_t ws_bytes,
                              void* hip_stream) {
+  return kvs_merge_compact_counts(p, K, V, nullptr, alpha_bar, o_bar, edge_mask, slot_of_token, K_out, V_out,
+                                  counts_out, ws, ws_bytes, hip_stream);
+}
+
+kvs_status kvs_merge_compact_counts(const kvs_problem* p, const void* K, const void* V, const int32_t* counts_in,
+                                    const float* alpha_bar, const float* o_bar, const uint8_t* edge_mask,
+                                    const int32_t* slot_of_token, void* K_out, void* V_out, int32_t* counts_out,
+                                    void* ws, size_t ws_bytes, void* hip_stream) {
   (void)ws;
   (void)ws_bytes;
   Plan plan;
@@ -270,19 +287,20 @@ kvs_status kvs_merge_compact(const kvs_problem* p, const void* K, const void* V,
   if (st != KVS_OK) return st;
   const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
   const size_t kvo = (size_t)plan.rows_out * plan.shape.D * plan.elt;
-  st = check_ranges({{K, kv, false},
-                     {V, kv, false},
-                     {alpha_bar, (size_t)plan.rows_in * 4, false},
-                     {o_bar, (size_t)plan.n_units * plan.shape.D * 4, false},
-                     {edge_mask, (size_t)plan.rows_in, false},
-                     {slot_of_token, (size_t)plan.rows_in * 4, false},
-                     {K_out, kvo, true},
-                     {V_out, kvo, true},
-                     {counts_out, (size_t)plan.rows_out * 4, true}});
-  if (st != KVS_OK) return st;
+  std::vector<Range> rs = {{K, kv, false},
+                           {V, kv, false},
+                           {alpha_bar, (size_t)plan.rows_in * 4, false},
+                           {o_bar, (size_t)plan.n_units * plan.shape.D * 4, false},
+                           {edge_mask, (size_t)plan.rows_in, false},
+                           {slot_of_token, (size_t)plan.rows_in * 4, false},
+                           {K_out, kvo, true},
+                           {V_out, kvo, true},
+                           {counts_out, (size_t)plan.rows_out * 4, true}};
+  if (counts_in) rs.push_back({counts_in, (size_t)plan.rows_in * 4, false});
+  if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
-    return launch_merge(tab, sh, plan.dtype, K, V, alpha_bar, o_bar, nullptr, edge_mask, slot_of_token,
+    return launch_merge(tab, sh, plan.dtype, K, V, counts_in, alpha_bar, o_bar, nullptr, edge_mask, slot_of_token,
                         K_out, V_out, counts_out, s);
   });
 }
@@ -290,6 +308,13 @@ kvs_status kvs_merge_compact(const kvs_problem* p, const void* K, const void* V,
 kvs_status kvs_step(const kvs_problem* p, const void* Q, const void* K, const void* V, void* K_out, void* V_out,
                     int32_t* counts_out, int32_t* slot_of_token_out, uint8_t* edge_mask_out, void* ws,
                     size_t ws_bytes, void* hip_stream) {
+  return kvs_step_counts(p, Q, K, V, nullptr, K_out, V_out, counts_out, slot_of_token_out, edge_mask_out, ws,
+                         ws_bytes, hip_stream);
+}
+
+kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, const void* V, const int32_t* counts_in,
+                           void* K_out, void* V_out, int32_t* counts_out, int32_t* slot_of_token_out,
+                           uint8_t* edge_mask_out, void* ws, size_t ws_bytes, void* hip_stream) {
   Plan plan;
   kvs_status st = make_plan(p, &plan);
   if (st != KVS_OK) return st;
@@ -306,17 +331,18 @@ kvs_status kvs_step(const kvs_problem* p, const void* Q, const void* K, const vo
                            {ws, w.bytes, true}};
   if (slot_of_token_out) rs.push_back({slot_of_token_out, (size_t)plan.rows_in * 4, true});
   if (edge_mask_out) rs.push_back({edge_mask_out, (size_t)plan.rows_in, true});
+  if (counts_in) rs.push_back({counts_in, (size_t)plan.rows_in * 4, false});
   if ((st = check_ranges(rs)) != KVS_OK) return st;
 
   uint8_t* mask = edge_mask_out ? edge_mask_out : w.edge_mask;
   int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
-    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, w.alpha_bar, w, s);
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, w.alpha_bar, w, s);
     if (e != hipSuccess) return e;
-    e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, V, w.o_part, s);
+    e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, V, counts_in, w.o_part, s);
     if (e != hipSuccess) return e;
-    return launch_merge(tab, sh, plan.dtype, K, V, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,
+    return launch_merge(tab, sh, plan.dtype, K, V, counts_in, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,
                         V_out, counts_out, s);
   });
 }

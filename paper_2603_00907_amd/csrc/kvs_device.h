@@ -154,19 +154,21 @@ __device__ __forceinline__ int find_unit(const UnitTable& tab, int chunk) {
 // Unit-wide softmax statistics from the chunks' partial ones (one small workgroup per unit).
 hipError_t launch_score_finalize(const UnitTable& tab, const Shape& sh, const Workspace& ws, hipStream_t stream);
 // Both score sweeps: chunk statistics, the finalize kernel, then alpha_bar.
+// counts_in (here and below): cardinalities of the input rows when the cache is already a merged one, or null.
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
-                        float* alpha_bar, const Workspace& ws, hipStream_t stream);
+                        const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream);
 // One launch, two kinds of workgroups: the first `with_select ? n_units : 0` select the edges of one unit
 // each, the others stream one chunk of V each into o_part (skipped when V is null).
 hipError_t launch_select_obar(const UnitTable& tab, const Shape& sh, kvs_dtype dt, bool with_select,
                               const float* alpha_bar, uint8_t* edge_mask, int32_t* slot, const void* V,
-                              float* o_part, hipStream_t stream);
+                              const int32_t* counts_in, float* o_part, hipStream_t stream);
 // o_bar[u] = sum of the unit's o_part chunks, in chunk order (only when o_bar itself is an output).
 hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float* o_part, float* o_bar,
                               hipStream_t stream);
 // Exactly one of o_bar (final values) and o_part (chunk sums, added up by every workgroup) is non-null.
 hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* K, const void* V,
-                        const float* alpha_bar, const float* o_bar, const float* o_part, const uint8_t* edge_mask,
+                        const int32_t* counts_in, const float* alpha_bar, const float* o_bar, const float* o_part,
+                        const uint8_t* edge_mask,
                         const int32_t* slot, void* K_out, void* V_out, int32_t* counts, hipStream_t stream);
 
 }  // namespace kvs

@@ -11,6 +11,10 @@
 //   V_out[S] = sum V[t]                            (Sec. 3.1), counts[S] = t1 - t0 + 1
 // A slot of one token is copied bit for bit.
 //
+// COUNTS: the rows are slots of an already merged cache, row t standing for c_t tokens whose Values add
+// up to V[t] (Sec. 3.1, streaming regime): r_t = V[t] / c_t - o_bar, counts[S] = sum c_t, the fallback is
+// the mean over the tokens the rows stand for; everything else is unchanged.
+//
 // Work split.  A workgroup is responsible for the slots that BEGIN in its nominal range of
 // kMergeTokens tokens: its real range [A, B) runs from the first slot start at or after the
 // nominal begin to the first slot start at or after the nominal end, so it owns whole slots and
@@ -56,16 +60,16 @@ __device__ __forceinline__ int first_slot_start(const uint8_t* __restrict__ mk, 
   }
 }
 
-template <typename T, int D, bool STREAM>
+template <typename T, int D, bool STREAM, bool COUNTS>
 __global__ __launch_bounds__(kThreads) void merge_kernel(
     const UnitTable tab, const Shape sh, const T* __restrict__ K, const T* __restrict__ V,
-    const float* __restrict__ alpha_bar, const float* __restrict__ o_bar, const float* __restrict__ o_part,
+    const int32_t* __restrict__ counts_in, const float* __restrict__ alpha_bar, const float* __restrict__ o_bar, const float* __restrict__ o_part,
     const uint8_t* __restrict__ edge_mask, const int32_t* __restrict__ slot, T* __restrict__ K_out,
     T* __restrict__ V_out, int32_t* __restrict__ counts) {
   constexpr int EPL = Piece<T>::N;
   constexpr int LPR = D / EPL;
   constexpr int GROUPS = kThreads / LPR;
-  constexpr int FRAG = 2 * D + 4;           // accK[D], accV[D], U, count, first token, pad
+  constexpr int FRAG = 2 * D + 4;           // accK[D], accV[D], U, rows, first token, cardinality
 
   __shared__ float sm_frag[GROUPS][2][FRAG];   // [g][0]: head fragment, [g][1]: tail / through fragment
   __shared__ int sm_flag[GROUPS];              // bit 0: head fragment ends here, 1: through, 2: tail starts here
@@ -155,6 +159,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   const int32_t* sl = slot + un.in_row;
   auto alpha_at = [&](int t) { return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(al) + (uint32_t)t * 4u); };
   auto mask_at = [&](int t) { return *(mk + (uint32_t)t); };
+  const int32_t* cin = COUNTS ? counts_in + un.in_row : nullptr;
+  auto count_at = [&](int t) { return COUNTS ? *reinterpret_cast<const int32_t*>(reinterpret_cast<const char*>(cin) + (uint32_t)t * 4u) : 1; };
 
   // o_bar: final values, or the chunk sums added in a fixed order (every workgroup gets the same bits)
   float o[EPL];
@@ -172,7 +178,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   }
 
   // One finished slot -> global memory (all lanes of the group call it together).  `raw_*` are the
-  auto finish = [&](int out_slot, const float* accK, const float* accV, float U, int count, int first_tok,
+  auto finish = [&](int out_slot, const float* accK, const float* accV, float U, int count, int csum, int first_tok,
                     const uint4& raw_k) {
     float outk[EPL];
     if (U > 0.f && U < INFINITY) {
@@ -185,10 +191,11 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       for (int j = first_tok; j < first_tok + count; ++j) {
         float kj[EPL];
         Piece<T>::unpack(k_row(j), kj);
+        const float cj = (float)count_at(j);
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) outk[i] += kj[i];
+        for (int i = 0; i < EPL; ++i) outk[i] = fmaf(cj, kj[i], outk[i]);
       }
-      const float inv = 1.f / (float)count;
+      const float inv = 1.f / (float)csum;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) outk[i] *= inv;
     }
@@ -198,10 +205,10 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     if ((unsigned)out_slot < (unsigned)un.n_out) {   // a slot map from outside the library is not trusted
       store_row(Kob, out_slot, ok);
       store_row(Vob, out_slot, ov);
-      if (piece == 0) *reinterpret_cast<int32_t*>(reinterpret_cast<char*>(cnt) + (uint32_t)out_slot * 4u) = count;
+      if (piece == 0) *reinterpret_cast<int32_t*>(reinterpret_cast<char*>(cnt) + (uint32_t)out_slot * 4u) = csum;
     }
   };
-  auto store_frag = [&](float* f, const float* accK, const float* accV, float U, int count, int first_tok) {
+  auto store_frag = [&](float* f, const float* accK, const float* accV, float U, int count, int csum, int first_tok) {
 #pragma unroll
     for (int i = 0; i < EPL; ++i) {
       f[piece * EPL + i] = accK[i];
@@ -211,6 +218,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       f[2 * D] = U;
       f[2 * D + 1] = __int_as_float(count);
       f[2 * D + 2] = __int_as_float(first_tok);
+      f[2 * D + 3] = __int_as_float(csum);
     }
   };
 
@@ -232,12 +240,14 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     uint4 rk[kPrefetch], rv[kPrefetch];
     float ra[kPrefetch];
     uint8_t rm[kPrefetch];          // kept as loaded: widening at the load would wait for it there
+    int rc[kPrefetch];              // cardinality of the Value row's token (COUNTS only)
     auto refill = [&](int j, int t) {                // the set that token t will consume
       rk[j] = k_row(min(t, gb - 1));
       const int tv = min(t + 1, last_v);
       rv[j] = v_row(tv);
       ra[j] = alpha_at(tv);
       rm[j] = mask_at(tv);
+      if (COUNTS) rc[j] = count_at(tv);
     };
 #pragma unroll
     for (int j = 0; j < kPrefetch; ++j) refill(j, ga + j);
@@ -248,12 +258,14 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     float v_cur[EPL], r_cur[EPL], accK[EPL], accV[EPL];
     float ss_cur = 0.f, Cprev = 0.f, U = 0.f;
     int count = 0, first_tok = ga, out_slot = out_slot0;
+    int c_cur = count_at(ga), csum = 0;              // COUNTS: this row's cardinality, the open slot's so far
     bool is_head = head_open;       // the open slot began before this group
     {
       Piece<T>::unpack(vraw_first, v_cur);
+      const float ic0 = COUNTS ? __builtin_amdgcn_rcpf((float)c_cur) : 1.f;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
-        r_cur[i] = v_cur[i] - o[i];
+        r_cur[i] = COUNTS ? fmaf(v_cur[i], ic0, -o[i]) : v_cur[i] - o[i];
         ss_cur = fmaf(r_cur[i], r_cur[i], ss_cur);
         accK[i] = 0.f;
         accV[i] = 0.f;
@@ -264,9 +276,10 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
         float vb[EPL];
         Piece<T>::unpack(v_row(ga - 1), vb);
         a_before = al[ga - 1];
+        const float icb = COUNTS ? __builtin_amdgcn_rcpf((float)count_at(ga - 1)) : 1.f;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
-          const float rb = vb[i] - o[i];
+          const float rb = COUNTS ? fmaf(vb[i], icb, -o[i]) : vb[i] - o[i];
           ss_b = fmaf(rb, rb, ss_b);
           dot = fmaf(rb, r_cur[i], dot);
         }
@@ -287,6 +300,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       asm volatile("v_mov_b32 %0, %2\n\tv_mov_b32 %1, %3"
                    : "=&v"(alpha_n), "=&v"(mask_n)
                    : "v"(ra[j]), "v"((uint32_t)rm[j]));
+      int c_n = 1;
+      if (COUNTS) asm volatile("v_mov_b32 %0, %1" : "=&v"(c_n) : "v"(rc[j]));
+      const float icn = COUNTS ? __builtin_amdgcn_rcpf((float)c_n) : 1.f;
       float kf[EPL], vn[EPL], r_next[EPL];
       Piece<T>::unpack(kraw, kf);
       Piece<T>::unpack(vraw_n, vn);
@@ -294,7 +310,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       float ss_next = 0.f, dot = 0.f;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
-        r_next[i] = vn[i] - o[i];
+        r_next[i] = COUNTS ? fmaf(vn[i], icn, -o[i]) : vn[i] - o[i];
         ss_next = fmaf(r_next[i], r_next[i], ss_next);
         dot = fmaf(r_cur[i], r_next[i], dot);
       }
@@ -307,6 +323,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       first_tok = (count == 0) ? t : first_tok;
       U += u;
       ++count;
+      if (COUNTS) csum += c_cur;
 #pragma unroll
       for (int i = 0; i < EPL; ++i) {
         accK[i] = fmaf(u, kf[i], accK[i]);
@@ -314,19 +331,21 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       }
       if (mask_cur == 0) {                           // the slot ends at t
         if (is_head) {
-          store_frag(sm_frag[group][0], accK, accV, U, count, first_tok);
+          store_frag(sm_frag[group][0], accK, accV, U, count, COUNTS ? csum : count, first_tok);
           flags |= 1;
           is_head = false;
         } else {
-          finish(out_slot, accK, accV, U, count, first_tok, kraw);
+          finish(out_slot, accK, accV, U, count, COUNTS ? csum : count, first_tok, kraw);
         }
         ++out_slot;
         U = 0.f;
         count = 0;
+        csum = 0;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) { accK[i] = 0.f; accV[i] = 0.f; }
       }
       refill(j, t + kPrefetch);
+      c_cur = c_n;
       Cprev = C;
       ss_cur = ss_next;
       alpha_cur = alpha_n;
@@ -345,7 +364,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       if (t + j < gb) step(t + j, j);
     }
     if (count > 0) {                                 // a slot is still open at the end of the group
-      store_frag(sm_frag[group][1], accK, accV, U, count, first_tok);
+      store_frag(sm_frag[group][1], accK, accV, U, count, COUNTS ? csum : count, first_tok);
       if (is_head) {
         flags |= 2;                                  // the whole group lies inside one slot
       } else {
@@ -366,6 +385,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     float U = f[2 * D];
     int count = __float_as_int(f[2 * D + 1]);
     const int first_tok = __float_as_int(f[2 * D + 2]);
+    int csum = __float_as_int(f[2 * D + 3]);
     for (int g = group + 1; g < GROUPS; ++g) {
       const int fl = sm_flag[g];
       const float* h = sm_frag[g][(fl & 2) ? 1 : 0];
@@ -374,42 +394,47 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       for (int i = 0; i < EPL; ++i) { accK[i] += h[piece * EPL + i]; accV[i] += h[D + piece * EPL + i]; }
       U += h[2 * D];
       count += __float_as_int(h[2 * D + 1]);
+      csum += __float_as_int(h[2 * D + 3]);
       if (fl & 1) break;                           // the slot ended in group g
     }
-    finish(tail_slot, accK, accV, U, count, first_tok, make_uint4(0, 0, 0, 0));
+    finish(tail_slot, accK, accV, U, count, csum, first_tok, make_uint4(0, 0, 0, 0));
   }
 }
 
 }  // namespace
 
-template <typename T, int D>
-static hipError_t launch_merge_t(const UnitTable& tab, const Shape& sh, const void* K, const void* V,
-                                 const float* alpha_bar, const float* o_bar, const float* o_part,
-                                 const uint8_t* edge_mask, const int32_t* slot, void* K_out, void* V_out,
-                                 int32_t* counts, hipStream_t stream) {
-  if (sh.stream) {
-    hipLaunchKernelGGL((merge_kernel<T, D, true>), dim3(tab.total_mblocks), dim3(kThreads), 0, stream, tab, sh,
-                       (const T*)K, (const T*)V, alpha_bar, o_bar, o_part, edge_mask, slot, (T*)K_out, (T*)V_out,
-                       counts);
-  } else {
-    hipLaunchKernelGGL((merge_kernel<T, D, false>), dim3(tab.total_mblocks), dim3(kThreads), 0, stream, tab, sh,
-                       (const T*)K, (const T*)V, alpha_bar, o_bar, o_part, edge_mask, slot, (T*)K_out, (T*)V_out,
-                       counts);
-  }
+template <typename T, int D, bool STREAM, bool COUNTS>
+static hipError_t launch_merge_k(const UnitTable& tab, const Shape& sh, const void* K, const void* V,
+                                 const int32_t* counts_in, const float* alpha_bar, const float* o_bar,
+                                 const float* o_part, const uint8_t* edge_mask, const int32_t* slot, void* K_out,
+                                 void* V_out, int32_t* counts, hipStream_t stream) {
+  hipLaunchKernelGGL((merge_kernel<T, D, STREAM, COUNTS>), dim3(tab.total_mblocks), dim3(kThreads), 0, stream, tab, sh,
+                     (const T*)K, (const T*)V, counts_in, alpha_bar, o_bar, o_part, edge_mask, slot, (T*)K_out,
+                     (T*)V_out, counts);
   return hipGetLastError();
 }
 
-hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* K, const void* V,
-                        const float* alpha_bar, const float* o_bar, const float* o_part, const uint8_t* edge_mask,
-                        const int32_t* slot, void* K_out, void* V_out, int32_t* counts, hipStream_t stream) {
-  if (dt == KVS_F32) {
-    return sh.D == 64
-               ? launch_merge_t<float, 64>(tab, sh, K, V, alpha_bar, o_bar, o_part, edge_mask, slot, K_out, V_out, counts, stream)
-               : launch_merge_t<float, 128>(tab, sh, K, V, alpha_bar, o_bar, o_part, edge_mask, slot, K_out, V_out, counts, stream);
+template <typename T, int D>
+static hipError_t launch_merge_t(const UnitTable& tab, const Shape& sh, const void* K, const void* V,
+                                 const int32_t* counts_in, const float* alpha_bar, const float* o_bar,
+                                 const float* o_part, const uint8_t* edge_mask, const int32_t* slot, void* K_out,
+                                 void* V_out, int32_t* counts, hipStream_t stream) {
+#define KVS_MERGE_ARGS tab, sh, K, V, counts_in, alpha_bar, o_bar, o_part, edge_mask, slot, K_out, V_out, counts, stream
+  if (counts_in) {
+    return sh.stream ? launch_merge_k<T, D, true, true>(KVS_MERGE_ARGS) : launch_merge_k<T, D, false, true>(KVS_MERGE_ARGS);
   }
-  return sh.D == 64
-             ? launch_merge_t<uint16_t, 64>(tab, sh, K, V, alpha_bar, o_bar, o_part, edge_mask, slot, K_out, V_out, counts, stream)
-             : launch_merge_t<uint16_t, 128>(tab, sh, K, V, alpha_bar, o_bar, o_part, edge_mask, slot, K_out, V_out, counts, stream);
+  return sh.stream ? launch_merge_k<T, D, true, false>(KVS_MERGE_ARGS) : launch_merge_k<T, D, false, false>(KVS_MERGE_ARGS);
+}
+
+hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* K, const void* V,
+                        const int32_t* counts_in, const float* alpha_bar, const float* o_bar, const float* o_part,
+                        const uint8_t* edge_mask, const int32_t* slot, void* K_out, void* V_out, int32_t* counts,
+                        hipStream_t stream) {
+  if (dt == KVS_F32) {
+    return sh.D == 64 ? launch_merge_t<float, 64>(KVS_MERGE_ARGS) : launch_merge_t<float, 128>(KVS_MERGE_ARGS);
+  }
+  return sh.D == 64 ? launch_merge_t<uint16_t, 64>(KVS_MERGE_ARGS) : launch_merge_t<uint16_t, 128>(KVS_MERGE_ARGS);
+#undef KVS_MERGE_ARGS
 }
 
 }  // namespace kvs

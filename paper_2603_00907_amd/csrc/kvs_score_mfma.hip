@@ -54,13 +54,29 @@ __device__ __forceinline__ void lds_read_4x16(bf16x8& a0, bf16x8& a1, bf16x8& a2
       : "memory");
 }
 
+// Rows that stand for c tokens with one Key (an already merged cache) enter the softmax as c equal
+// terms, i.e. with log2(c) added to the base-2 logit.  Turns the raw dot products of this lane's 16
+// accumulator rows (tile at token base_t of the unit whose cardinalities start at cnt) into logits.
+template <int NACC>
+__device__ __forceinline__ void logits_with_counts(f32x16 (&acc)[NACC], const int32_t* __restrict__ cnt, int base_t,
+                                                   int half, float sl2) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int row = 8 * (v / 4) + 4 * half + (v % 4);
+    const float lc = log2f((float)cnt[base_t + row]);
+#pragma unroll
+    for (int nt = 0; nt < NACC; ++nt) acc[nt][v] = fmaf(acc[nt][v], sl2, lc);
+  }
+}
+
 #define KVS_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define KVS_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
 template <int D, int NT, int WQ, int PHASE>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
-    float* __restrict__ alpha_bar, float2* __restrict__ stats_part, const float* __restrict__ c_row) {
+    const int32_t* __restrict__ counts_in, float* __restrict__ alpha_bar, float2* __restrict__ stats_part,
+    const float* __restrict__ c_row) {
   constexpr int WT = kWaves / WQ;           // wavefronts that split the tiles
   constexpr int KS = D / 16;                // MFMA k-steps per tile
   constexpr int LPR = D / 8;                // 16-byte pieces (= lanes) per row
@@ -87,6 +103,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   const int col = lane % 32, half = lane / 32;
   const int R = sh.R;
   const float sl2 = sh.scale_log2;
+  const int32_t* cnt = counts_in ? counts_in + un.in_row : nullptr;
+  const float sc = cnt ? 1.f : sl2;        // the accumulators hold finished logits when cardinalities were added
   const size_t part_base = (size_t)un.index * kMaxChunks;
 
   const uint4* Kg = reinterpret_cast<const uint4*>(K + (size_t)un.in_row * D);
@@ -246,17 +264,18 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         }
       }
 
+      if (cnt) logits_with_counts<NT>(acc, cnt, base_t, half, sl2);
       if (PHASE == 0) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
           float tm = acc[nt][0];
 #pragma unroll
           for (int v = 1; v < 16; ++v) tm = fmaxf(tm, acc[nt][v]);
-          const float m_new = fmaxf(m_run[nt], tm * sl2);
+          const float m_new = fmaxf(m_run[nt], tm * sc);
           const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
           float s = 0.f;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) s += ex2(fmaf(acc[nt][v], sl2, -m_safe));
+          for (int v = 0; v < 16; ++v) s += ex2(fmaf(acc[nt][v], sc, -m_safe));
           l_run[nt] = l_run[nt] * ex2(m_run[nt] - m_safe) + s;
           m_run[nt] = m_new;
         }
@@ -266,7 +285,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         for (int v = 0; v < 16; ++v) {
           float s = 0.f;
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt) s += ex2(fmaf(acc[nt][v], sl2, -cq[nt]));
+          for (int nt = 0; nt < NT; ++nt) s += ex2(fmaf(acc[nt][v], sc, -cq[nt]));
           p[v] = s;
         }
         // sum over the 32 query columns of each half: reduce-scatter, lane bits 4..1 pick v
@@ -382,7 +401,8 @@ __device__ __forceinline__ void lds_read_2x2(bf16x8& b00, bf16x8& b01, bf16x8& b
 template <int D, int PHASE, bool STREAM>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
-    float* __restrict__ alpha_bar, float2* __restrict__ stats_part, const float* __restrict__ c_row) {
+    const int32_t* __restrict__ counts_in, float* __restrict__ alpha_bar, float2* __restrict__ stats_part,
+    const float* __restrict__ c_row) {
   constexpr int KS = D / 16;
   constexpr int LPR = D / 8;
   constexpr int RPI = kWave / LPR;
@@ -407,6 +427,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   const int col = lane % 32, half = lane / 32;
   const int R = sh.R;
   const float sl2 = sh.scale_log2;
+  const int32_t* cnt = counts_in ? counts_in + un.in_row : nullptr;
+  const float sc = cnt ? 1.f : sl2;        // the accumulators hold finished logits when cardinalities were added
   const size_t part_base = (size_t)un.index * kMaxChunks;
 
   const unsigned char* Kg = reinterpret_cast<const unsigned char*>(K + (size_t)un.in_row * D);
@@ -524,6 +546,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
           if (row < shift) { acc[0][v] = -INFINITY; acc[1][v] = -INFINITY; }
         }
       }
+      if (cnt) logits_with_counts<2>(acc, cnt, base_t, half, sl2);
       if (PHASE == 0) {
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
@@ -531,18 +554,18 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
           float tm = acc[nt][0];
 #pragma unroll
           for (int v = 1; v < 16; ++v) tm = fmaxf(tm, acc[nt][v]);
-          const float m_new = fmaxf(m_run[b], tm * sl2);
+          const float m_new = fmaxf(m_run[b], tm * sc);
           const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
           float s = 0.f;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) s += ex2(fmaf(acc[nt][v], sl2, -m_safe));
+          for (int v = 0; v < 16; ++v) s += ex2(fmaf(acc[nt][v], sc, -m_safe));
           l_run[b] = l_run[b] * ex2(m_run[b] - m_safe) + s;
           m_run[b] = m_new;
         }
       } else {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const float s = ex2(fmaf(acc[0][v], sl2, -cq[2 * h])) + ex2(fmaf(acc[1][v], sl2, -cq[2 * h + 1]));
+          const float s = ex2(fmaf(acc[0][v], sc, -cq[2 * h])) + ex2(fmaf(acc[1][v], sc, -cq[2 * h + 1]));
           p[v] = (h == 0) ? s : p[v] + s;
         }
       }
@@ -613,52 +636,52 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
 }
 
 template <int D, bool STREAM>
-hipError_t launch_wide_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
-                         const Workspace& ws, hipStream_t stream) {
+hipError_t launch_wide_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+                         const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
   hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0, STREAM>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, alpha_bar, ws.stats_part, ws.c_row);
+                     (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
   hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, alpha_bar, ws.stats_part, ws.c_row);
+                     (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row);
   return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_wide(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
-                       const Workspace& ws, hipStream_t stream) {
-  return sh.stream ? launch_wide_t<D, true>(tab, sh, Q, K, alpha_bar, ws, stream)
-                   : launch_wide_t<D, false>(tab, sh, Q, K, alpha_bar, ws, stream);
+hipError_t launch_wide(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+                       const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+  return sh.stream ? launch_wide_t<D, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
+                   : launch_wide_t<D, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
 }
 
 template <int D, int NT, int WQ>
-hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
-                    const Workspace& ws, hipStream_t stream) {
+hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+                    const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
   hipLaunchKernelGGL((score_mfma_kernel<D, NT, WQ, 0>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, alpha_bar, ws.stats_part, ws.c_row);
+                     (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
   hipLaunchKernelGGL((score_mfma_kernel<D, NT, WQ, 1>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, alpha_bar, ws.stats_part, ws.c_row);
+                     (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row);
   return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
-                    const Workspace& ws, hipStream_t stream) {
+hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+                    const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
   // At most 64 query rows per wavefront: with more, the stationary Q operands, the accumulators and
   // the tile operands no longer fit the 256 registers that two wavefronts per SIMD leave each, and
   // every spill reload waits for ALL loads in flight, the tile prefetch included.
   const int R = sh.R;
-  if (R <= 32) return launch_t<D, 1, 1>(tab, sh, Q, K, alpha_bar, ws, stream);
-  if (R <= 64) return launch_t<D, 2, 1>(tab, sh, Q, K, alpha_bar, ws, stream);
-  if (R <= 128) return launch_wide<D>(tab, sh, Q, K, alpha_bar, ws, stream);      // rows 64.. from LDS, one pass
-  if (R <= 256) return launch_t<D, 2, 2>(tab, sh, Q, K, alpha_bar, ws, stream);    // two passes of 128 rows
-  return launch_t<D, 2, 4>(tab, sh, Q, K, alpha_bar, ws, stream);                  // passes of 256 rows
+  if (R <= 32) return launch_t<D, 1, 1>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+  if (R <= 64) return launch_t<D, 2, 1>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+  if (R <= 128) return launch_wide<D>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);      // rows 64.. from LDS, one pass
+  if (R <= 256) return launch_t<D, 2, 2>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);    // two passes of 128 rows
+  return launch_t<D, 2, 4>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);                  // passes of 256 rows
 }
 
 }  // namespace
@@ -671,10 +694,10 @@ bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
   return true;
 }
 
-hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, float* alpha_bar,
-                             const Workspace& ws, hipStream_t stream) {
-  return sh.D == 64 ? launch_d<64>(tab, sh, Q, K, alpha_bar, ws, stream)
-                    : launch_d<128>(tab, sh, Q, K, alpha_bar, ws, stream);
+hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+                             const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+  return sh.D == 64 ? launch_d<64>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
+                    : launch_d<128>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
 }
 
 }  // namespace kvs

@@ -21,7 +21,8 @@ constexpr int kThreads = 256;
 template <typename T, int D, int PHASE>
 __global__ __launch_bounds__(kThreads) void score_valu_kernel(
     const UnitTable tab, const Shape sh, const T* __restrict__ Q, const T* __restrict__ K,
-    float* __restrict__ alpha_bar, float2* __restrict__ stats_part, const float* __restrict__ c_row) {
+    const int32_t* __restrict__ counts_in, float* __restrict__ alpha_bar, float2* __restrict__ stats_part,
+    const float* __restrict__ c_row) {
   constexpr int EPL = Piece<T>::N;          // elements per lane
   constexpr int LPR = D / EPL;              // lanes per row
   constexpr int RPW = kWave / LPR;          // rows per wavefront load
@@ -67,13 +68,15 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
     for (int t = t0 + wave * RPW + grp; t < t1; t += RPB) {
       float kf[EPL];
       Piece<T>::unpack(Kp[(size_t)t * LPR], kf);
+      // a row that stands for c tokens with this Key: c equal softmax terms, i.e. the logit plus log c
+      const float lc = counts_in ? log2f((float)counts_in[un.in_row + t]) : 0.f;
       float a = 0.f;
 #pragma unroll
       for (int j = 0; j < kQB; ++j) {
         float d = 0.f;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) d = fmaf(qf[j][i], kf[i], d);
-        const float s = row_group_sum<LPR>(d) * sh.scale_log2;
+        const float s = fmaf(row_group_sum<LPR>(d), sh.scale_log2, lc);
         if (PHASE == 0) {
           if (s > m[j]) {
             l[j] = l[j] * __builtin_amdgcn_exp2f(m[j] - s) + 1.f;
@@ -169,26 +172,27 @@ hipError_t launch_score_finalize(const UnitTable& tab, const Shape& sh, const Wo
 
 template <typename T, int D>
 static hipError_t launch_score_valu_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                                      float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+                                      const int32_t* counts_in, float* alpha_bar, const Workspace& ws,
+                                      hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
   hipLaunchKernelGGL((score_valu_kernel<T, D, 0>), grid, block, 0, stream, tab, sh, (const T*)Q, (const T*)K,
-                     alpha_bar, ws.stats_part, ws.c_row);
+                     counts_in, alpha_bar, ws.stats_part, ws.c_row);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
   hipLaunchKernelGGL((score_valu_kernel<T, D, 1>), grid, block, 0, stream, tab, sh, (const T*)Q, (const T*)K,
-                     alpha_bar, ws.stats_part, ws.c_row);
+                     counts_in, alpha_bar, ws.stats_part, ws.c_row);
   return hipGetLastError();
 }
 
 hipError_t launch_score_valu(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
-                             float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+                             const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
   if (dt == KVS_F32) {
-    return sh.D == 64 ? launch_score_valu_t<float, 64>(tab, sh, Q, K, alpha_bar, ws, stream)
-                      : launch_score_valu_t<float, 128>(tab, sh, Q, K, alpha_bar, ws, stream);
+    return sh.D == 64 ? launch_score_valu_t<float, 64>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
+                      : launch_score_valu_t<float, 128>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
   }
-  return sh.D == 64 ? launch_score_valu_t<uint16_t, 64>(tab, sh, Q, K, alpha_bar, ws, stream)
-                    : launch_score_valu_t<uint16_t, 128>(tab, sh, Q, K, alpha_bar, ws, stream);
+  return sh.D == 64 ? launch_score_valu_t<uint16_t, 64>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
+                    : launch_score_valu_t<uint16_t, 128>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
 }
 
 }  // namespace kvs

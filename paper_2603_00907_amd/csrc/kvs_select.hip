@@ -520,8 +520,9 @@ __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, con
 }
 
 template <typename T, int D, bool STREAM>
-__device__ __forceinline__ void obar_chunk(const Unit& un, int chunk, const T* __restrict__ V, const float* __restrict__ alpha_bar,
-                           float* __restrict__ o_part, float (*sm_o)[128]) {
+__device__ __forceinline__ void obar_chunk(const Unit& un, int chunk, const T* __restrict__ V,
+                                           const int32_t* __restrict__ counts_in, const float* __restrict__ alpha_bar,
+                                           float* __restrict__ o_part, float (*sm_o)[128]) {
   constexpr int EPL = Piece<T>::N;
   constexpr int LPR = D / EPL;
   constexpr int RPW = kWave / LPR;
@@ -534,6 +535,7 @@ __device__ __forceinline__ void obar_chunk(const Unit& un, int chunk, const T* _
   const int t1 = min(un.len, t0 + clen);
   const uint4* Vp = reinterpret_cast<const uint4*>(V + (size_t)un.in_row * D) + piece;
   const float* al = alpha_bar + un.in_row;
+  const int32_t* cnt = counts_in ? counts_in + un.in_row : nullptr;   // rows that are sums over c tokens: v = V / c
 
   float acc[EPL];
 #pragma unroll
@@ -552,6 +554,7 @@ __device__ __forceinline__ void obar_chunk(const Unit& un, int chunk, const T* _
         raw[u] = make_uint4(r.x, r.y, r.z, r.w);
       }
       a[u] = (t < t1) ? al[tc] : 0.f;
+      if (cnt) a[u] = a[u] / (float)cnt[tc];
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
@@ -583,7 +586,7 @@ template <typename T, int D>
 __global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
     const UnitTable tab, const Shape sh, const int n_select, const float* __restrict__ alpha_bar,
     uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, const T* __restrict__ V,
-    float* __restrict__ o_part) {
+    const int32_t* __restrict__ counts_in, float* __restrict__ o_part) {
   __shared__ SelectSmem sm;
   __shared__ float sm_o[kSelWaves][128];
   const int b = blockIdx.x;
@@ -593,8 +596,8 @@ __global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
     const int c = b - n_select;
     int ui = 0;
     while (ui + 1 < tab.n_units && tab.u[ui + 1].o_base <= c) ++ui;
-    if (sh.stream) obar_chunk<T, D, true>(tab.u[ui], c - tab.u[ui].o_base, V, alpha_bar, o_part, sm_o);
-    else obar_chunk<T, D, false>(tab.u[ui], c - tab.u[ui].o_base, V, alpha_bar, o_part, sm_o);
+    if (sh.stream) obar_chunk<T, D, true>(tab.u[ui], c - tab.u[ui].o_base, V, counts_in, alpha_bar, o_part, sm_o);
+    else obar_chunk<T, D, false>(tab.u[ui], c - tab.u[ui].o_base, V, counts_in, alpha_bar, o_part, sm_o);
   }
 }
 
@@ -611,12 +614,13 @@ __global__ void obar_reduce_kernel(const UnitTable tab, const Shape sh, const fl
 
 template <typename T, int D>
 hipError_t launch_t(const UnitTable& tab, const Shape& sh, bool with_select, const float* alpha_bar,
-                    uint8_t* edge_mask, int32_t* slot, const void* V, float* o_part, hipStream_t stream) {
+                    uint8_t* edge_mask, int32_t* slot, const void* V, const int32_t* counts_in, float* o_part,
+                    hipStream_t stream) {
   const int n_select = with_select ? tab.n_units : 0;
   const int n_obar = V ? tab.total_ochunks : 0;
   if (n_select + n_obar == 0) return hipSuccess;
   hipLaunchKernelGGL((select_obar_kernel<T, D>), dim3(n_select + n_obar), dim3(kSelThreads), 0, stream, tab, sh,
-                     n_select, alpha_bar, edge_mask, slot, (const T*)V, o_part);
+                     n_select, alpha_bar, edge_mask, slot, (const T*)V, counts_in, o_part);
   return hipGetLastError();
 }
 
@@ -624,13 +628,13 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, bool with_select, con
 
 hipError_t launch_select_obar(const UnitTable& tab, const Shape& sh, kvs_dtype dt, bool with_select,
                               const float* alpha_bar, uint8_t* edge_mask, int32_t* slot, const void* V,
-                              float* o_part, hipStream_t stream) {
+                              const int32_t* counts_in, float* o_part, hipStream_t stream) {
   if (dt == KVS_F32) {
-    return sh.D == 64 ? launch_t<float, 64>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, o_part, stream)
-                      : launch_t<float, 128>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, o_part, stream);
+    return sh.D == 64 ? launch_t<float, 64>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream)
+                      : launch_t<float, 128>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream);
   }
-  return sh.D == 64 ? launch_t<uint16_t, 64>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, o_part, stream)
-                    : launch_t<uint16_t, 128>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, o_part, stream);
+  return sh.D == 64 ? launch_t<uint16_t, 64>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream)
+                    : launch_t<uint16_t, 128>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream);
 }
 
 hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float* o_part, float* o_bar,

@@ -55,12 +55,12 @@ def accepted_unit(w: Workload, layer: int, seq: int, head: int, n: Optional[int]
     for attempt in range(start, MAX_ATTEMPTS):
         u = generate_unit(w, layer, seq, head, attempt=attempt, n=n, kv_from=base)
         base = u
-        alpha_bar, o_bar = O.score(u.Q, u.K, u.V)
+        alpha_bar, o_bar = O.score(u.Q, u.K, u.V, counts=u.counts)
         gap = O.boundary_gap(alpha_bar, u.budget, w.n_sink, w.n_recent)
         if gap < GAP_MIN:
             continue
         mask, slot = O.select(alpha_bar, u.budget, w.n_sink, w.n_recent)
-        merged = O.merge_compact(u.K, u.V, alpha_bar, o_bar, mask, slot)
+        merged = O.merge_compact(u.K, u.V, alpha_bar, o_bar, mask, slot, counts_in=u.counts)
         cond = O.conditioning(merged)
         if cond < COND_MIN:
             continue
@@ -130,6 +130,14 @@ class DeviceBatch:
         self.K = to_device(Kall, dtype)
         self.V = to_device(Vall, dtype)
         self.Q = to_device(np.stack([u.Q.reshape(group * window, D) for u in units]), dtype)
+        # cardinalities of the rows, when the units are slots of an already merged cache (else None)
+        self.counts_in = None
+        if any(getattr(u, "counts", None) is not None for u in units):
+            call = np.ones(p.rows_in, dtype=np.int32)
+            for u, r0 in zip(units, in_rows):
+                if u.counts is not None:
+                    call[r0:r0 + u.K.shape[0]] = u.counts
+            self.counts_in = torch.from_numpy(call).cuda()
         tdt = torch_io_dtype(dtype)
         G = self.GUARD
         self.K_out = torch.full((p.rows_out + G, D), 512.0, dtype=tdt, device="cuda")

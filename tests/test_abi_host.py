@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert kvs.kvs_version() == 100
+    assert kvs.kvs_version() == 200
     assert kvs.status_str(kvs.KVS_OK) == "ok"
     for code in range(1, 7):
         assert kvs.status_str(code) not in ("ok", "unknown status")

@@ -66,6 +66,12 @@ SCORE_CASES = [
     ("stress128k", "bf16", 128, 8, 100, [1200], None),
     ("llama8b_8k", "bf16", 64, 1, 4, [500], None),
     ("ragged16", "bf16", 128, 4, 32, [300, 5000, 33000], None),
+    # rows that are slots of an already merged cache (cardinalities): every score kernel
+    ("stream2560", "bf16", 128, 4, 32, [2560, 700], None),
+    ("stream2560", "bf16", 128, 4, 32, [900], "valu"),
+    ("stream2560", "bf16", 128, 1, 20, [1500], None),
+    ("stream2560", "bf16", 64, 8, 40, [1100], None),
+    ("stream2560", "f32", 64, 2, 5, [600], None),
 ]
 
 
@@ -75,19 +81,23 @@ def test_score_matches_oracle(base, dtype, D, G, W, lens, path):
     units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
     batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype=dtype, n_sink=w.n_sink, gap_rows=3)
     with env_override("KVS_SCORE_PATH", path):
-        batch.kvs.kvs_score(batch.problem, batch.Q, batch.K, batch.V, batch.alpha_bar, batch.o_bar, batch.ws,
-                            stream=batch.stream())
+        if batch.counts_in is None:
+            batch.kvs.kvs_score(batch.problem, batch.Q, batch.K, batch.V, batch.alpha_bar, batch.o_bar, batch.ws,
+                                stream=batch.stream())
+        else:
+            batch.kvs.kvs_score_counts(batch.problem, batch.Q, batch.K, batch.V, batch.counts_in, batch.alpha_bar,
+                                       batch.o_bar, batch.ws, stream=batch.stream())
         torch_sync()
     batch.check_guards()
     alpha = from_device(batch.alpha_bar)
     obar = from_device(batch.o_bar)
     for i, u in enumerate(units):
-        ra, ro = O.score(u.Q, u.K, u.V)
+        ra, ro = O.score(u.Q, u.K, u.V, counts=u.counts)
         r0 = batch.problem.in_rows[i]
         got = alpha[r0:r0 + len(ra)]
         assert np.isfinite(got).all()
         assert np.max(np.abs(got - ra) / ra) < TOL_ALPHA, (i, np.max(np.abs(got - ra) / ra))
-        bound = TOL_ALPHA * (ra @ np.abs(u.V.astype(np.float64))) + 1e-7
+        bound = TOL_ALPHA * (ra @ np.abs(O.slot_values(u.V, u.counts))) + 1e-7
         assert (np.abs(obar[i] - ro) <= bound).all(), (i, np.max(np.abs(obar[i] - ro) / bound))
     # rows between units are never touched
     for i in range(len(units) - 1):
@@ -174,6 +184,9 @@ def merge_case(base, dtype, D, lens, budgets=None, R=(1, 4), seed_layer=0):
     ("llama8b_8k", "bf16", 64, [2000], [1999]),
     ("tiny", "f32", 64, [600], [33]),            # one run swallows everything after the sinks
     ("tiny", "f32", 64, [300, 200], [300, 500]),  # pass-through
+    ("stream2560", "bf16", 128, [2560, 300], None),          # rows with cardinalities
+    ("stream2560", "f32", 64, [1200], [500]),
+    ("stream2560", "bf16", 64, [900], [899]),
 ])
 def test_merge_compact_matches_oracle(base, dtype, D, lens, budgets):
     import torch
@@ -186,19 +199,24 @@ def test_merge_compact_matches_oracle(base, dtype, D, lens, budgets):
     slot_all = np.zeros(p.rows_in, dtype=np.int32)
     obar_all = np.zeros((len(units), D), dtype=np.float32)
     for i, u in enumerate(units):
-        a, o = O.score(u.Q, u.K, u.V)
+        a, o = O.score(u.Q, u.K, u.V, counts=u.counts)
         a32, o32 = a.astype(np.float32), o.astype(np.float32)
         mask, slot = O.select(a32, u.budget, w.n_sink, 0, sigma_dtype=np.float32)
-        refs.append(O.merge_compact(u.K, u.V, a32.astype(np.float64), o32.astype(np.float64), mask, slot))
+        refs.append(O.merge_compact(u.K, u.V, a32.astype(np.float64), o32.astype(np.float64), mask, slot,
+                                    counts_in=u.counts))
         r0 = p.in_rows[i]
         alpha_all[r0:r0 + len(a)] = a32
         mask_all[r0:r0 + len(a)] = mask
         slot_all[r0:r0 + len(a)] = slot
         obar_all[i] = o32
-    batch.kvs.kvs_merge_compact(p, batch.K, batch.V, torch.from_numpy(alpha_all).cuda(),
-                                torch.from_numpy(obar_all).cuda(), torch.from_numpy(mask_all).cuda(),
-                                torch.from_numpy(slot_all).cuda(), batch.K_out, batch.V_out, batch.counts,
-                                stream=batch.stream())
+    dev_args = (torch.from_numpy(alpha_all).cuda(), torch.from_numpy(obar_all).cuda(),
+                torch.from_numpy(mask_all).cuda(), torch.from_numpy(slot_all).cuda())
+    if batch.counts_in is None:
+        batch.kvs.kvs_merge_compact(p, batch.K, batch.V, *dev_args, batch.K_out, batch.V_out, batch.counts,
+                                    stream=batch.stream())
+    else:
+        batch.kvs.kvs_merge_compact_counts(p, batch.K, batch.V, batch.counts_in, *dev_args, batch.K_out,
+                                           batch.V_out, batch.counts, stream=batch.stream())
     torch_sync()
     batch.check_guards()
     compare_outputs(batch, refs, dtype)
@@ -216,7 +234,7 @@ def compare_outputs(batch, refs, dtype, strict_guard=True):
         ev = rel_err_rows(Vo[r0:r0 + n_out], ref.V_out)
         assert ek <= TOL_KV[dtype], f"unit {i}: merged K rel err {ek:.3e}"
         assert ev <= TOL_KV[dtype], f"unit {i}: merged V rel err {ev:.3e}"
-        single = ref.counts == 1
+        single = ref.n_rows == 1
         assert (Ko[r0:r0 + n_out][single] == ref.K_out[single]).all(), f"unit {i}: singleton K not a copy"
         assert (Vo[r0:r0 + n_out][single] == ref.V_out[single]).all(), f"unit {i}: singleton V not a copy"
 
@@ -293,8 +311,14 @@ def run_step(w, accepted, path=None):
     batch = DeviceBatch(units, group=w.group, window=w.window, head_dim=w.head_dim, dtype=w.dtype,
                         n_sink=w.n_sink, n_recent=w.n_recent)
     with env_override("KVS_SCORE_PATH", path):
-        batch.kvs.kvs_step(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out, batch.counts,
-                           batch.ws, slot_of_token_out=batch.slot, edge_mask_out=batch.mask, stream=batch.stream())
+        if batch.counts_in is None:
+            batch.kvs.kvs_step(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out, batch.counts,
+                               batch.ws, slot_of_token_out=batch.slot, edge_mask_out=batch.mask,
+                               stream=batch.stream())
+        else:
+            batch.kvs.kvs_step_counts(batch.problem, batch.Q, batch.K, batch.V, batch.counts_in, batch.K_out,
+                                      batch.V_out, batch.counts, batch.ws, slot_of_token_out=batch.slot,
+                                      edge_mask_out=batch.mask, stream=batch.stream())
         torch_sync()
     batch.check_guards()
     return batch
@@ -364,6 +388,39 @@ def test_step_more_units_than_one_launch_takes():
     w = WORKLOADS["llama8b_32k"].scaled(length=("fixed", 1500), budget=("fixed", 400))
     accepted = [accepted_unit(w, layer, 0, layer % w.n_kv_heads, n=1500 - 13 * (layer % 7)) for layer in range(70)]
     check_step(w, accepted)
+
+
+def test_step_streaming_regime_full_size():
+    """Sec. 5's streaming regime at full size: 8 KV heads, each a merged cache of 2048 + 512 slots (the old
+    slots stand for 4 tokens on average) merged back to 2048; cardinalities must add up bit-exactly."""
+    w = WORKLOADS["stream2560"]
+    batch = check_step(w, [accepted_unit(w, 0, 0, h) for h in range(w.n_kv_heads)])
+    total_in = sum(int(u.counts.sum()) for u in batch.units)
+    assert int(batch.counts[:batch.problem.rows_out].sum().item()) == total_in
+
+
+def test_step_streaming_regime_fp32_and_small_window():
+    w = WORKLOADS["stream2560"].scaled(dtype="f32", head_dim=64, group=2, window=5, length=("fixed", 1500),
+                                       budget=("fixed", 1100), fresh_tail=300, k_outlier_channels=0)
+    check_step(w, [accepted_unit(w, 0, 0, h) for h in range(2)])
+
+
+def test_counts_of_one_are_the_plain_step():
+    """Cardinalities of one select the same edges and give the same cache as the plain entry point (the
+    logits take one more rounding on that path, so merged rows agree to the tolerance, not bit for bit)."""
+    import torch
+    w = WORKLOADS["llama8b_8k"].scaled(length=("fixed", 3000), budget=("fixed", 800))
+    acc = [accepted_unit(w, 0, 0, h) for h in range(2)]
+    plain = run_step(w, acc)
+    for a in acc:
+        a.inputs.counts = np.ones(a.inputs.n, dtype=np.int32)
+    ones = run_step(w, acc)
+    for a in acc:
+        a.inputs.counts = None
+    assert torch.equal(plain.counts, ones.counts) and torch.equal(plain.slot, ones.slot)
+    n_out = plain.problem.rows_out
+    assert torch.equal(plain.V_out.view(torch.int16), ones.V_out.view(torch.int16))      # sums of the same rows
+    assert rel_err_rows(from_device(ones.K_out)[:n_out], from_device(plain.K_out)[:n_out].astype(np.float64)) <= 1e-2
 
 
 def test_step_stress_reduced():

@@ -36,6 +36,12 @@ class Workload:
     v_dist: str = "normal"          # "normal" | "student_t4" (scaled to unit variance)
     n_sink: int = 32
     n_recent: int = 0
+    # Streaming regime: the rows are slots of an already merged cache.  fresh_tail = number of trailing
+    # rows that are new tokens (cardinality 1, like the sinks); every other row stands for
+    # 1 + Geometric(1 / mean_count) - 1 tokens (mean `mean_count`) and its Value row is the sum of that
+    # many unit-variance draws.  mean_count = 0: plain tokens, no cardinalities.
+    mean_count: float = 0.0
+    fresh_tail: int = 0
     seed: int = 20260300907
 
     @property
@@ -77,6 +83,12 @@ WORKLOADS = {
         name="stress128k", cfg_id=5, layers=1, n_seq=1, n_kv_heads=8, group=8, window=64,
         head_dim=128, dtype="bf16", length=("fixed", 131072), budget=("fixed", 8192),
         k_rho=("fixed", 0.95), v_dist="student_t4"),
+    # streaming regime of Sec. 5: a cache of budget + chunk = 2048 + 512 slots is merged back to 2048;
+    # the 2016 old non-sink slots stand for 4 tokens on average (about 8.6 K tokens seen so far).
+    "stream2560": Workload(
+        name="stream2560", cfg_id=6, layers=32, n_seq=1, n_kv_heads=8, group=4, window=32,
+        head_dim=128, dtype="bf16", length=("fixed", 2560), budget=("fixed", 2048),
+        k_rho=("fixed", 0.9), k_outlier_channels=4, k_outlier_scale=8.0, mean_count=4.0, fresh_tail=512),
 }
 
 

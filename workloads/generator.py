@@ -22,7 +22,7 @@ from scipy.signal import lfilter
 
 from .configs import Workload
 
-_T_LEN, _T_RHO, _T_OUTLIER, _T_K, _T_V, _T_Q = range(6)
+_T_LEN, _T_RHO, _T_OUTLIER, _T_K, _T_V, _T_Q, _T_COUNT = range(7)
 
 
 def _rng(w: Workload, layer: int, seq: int, head: int, tensor: int, attempt: int = 0):
@@ -83,6 +83,7 @@ class UnitInputs:
     Q: np.ndarray   # [G, W, D] float32, values representable in the I/O dtype
     K: np.ndarray   # [n, D]
     V: np.ndarray   # [n, D]
+    counts: Optional[np.ndarray] = None   # [n] int32 tokens every row stands for (streaming workloads only)
 
 
 def _draw_k(w: Workload, layer: int, seq: int, head: int, n: int):
@@ -112,6 +113,16 @@ def _draw_v(w: Workload, layer: int, seq: int, head: int, n: int):
     raise ValueError(w.v_dist)
 
 
+def _draw_counts(w: Workload, layer: int, seq: int, head: int, n: int) -> np.ndarray:
+    """Cardinality of every row: 1 for the sink rows and the fresh tail, geometric with mean mean_count
+    for the slots in between."""
+    c = np.ones(n, dtype=np.int32)
+    lo, hi = min(w.n_sink, n), max(min(w.n_sink, n), n - w.fresh_tail)
+    if hi > lo:
+        c[lo:hi] = _rng(w, layer, seq, head, _T_COUNT).geometric(1.0 / w.mean_count, size=hi - lo)
+    return c
+
+
 def _draw_q(w: Workload, layer: int, seq: int, head: int, attempt: int):
     return _rng(w, layer, seq, head, _T_Q, attempt).standard_normal(
         (w.group, w.window, w.head_dim), dtype=np.float32)
@@ -122,12 +133,19 @@ def generate_unit(w: Workload, layer: int, seq: int, head: int, attempt: int = 0
     """Draw one unit.  `kv_from` reuses K and V of an earlier attempt (only Q is redrawn)."""
     if n is None:
         n = unit_lengths(w)[seq]
+    counts = None
     if kv_from is not None:
-        rho, K, V = kv_from.rho, kv_from.K, kv_from.V
+        rho, K, V, counts = kv_from.rho, kv_from.K, kv_from.V, kv_from.counts
     else:
         rho, k = _draw_k(w, layer, seq, head, n)
         K = _round_io(k, w.dtype)
-        V = _round_io(_draw_v(w, layer, seq, head, n), w.dtype)
+        v = _draw_v(w, layer, seq, head, n)
+        if w.mean_count > 0:
+            # a slot's Value row is a sum over its tokens: the sum of c unit-variance draws is one draw
+            # scaled by sqrt(c)
+            counts = _draw_counts(w, layer, seq, head, n)
+            v = v * np.sqrt(counts.astype(np.float64))[:, None]
+        V = _round_io(v, w.dtype)
     Q = _round_io(_draw_q(w, layer, seq, head, attempt), w.dtype)
     return UnitInputs(layer=layer, seq=seq, head=head, attempt=attempt, n=n,
-                      budget=unit_budget(w, n), rho=rho, Q=Q, K=K, V=V)
+                      budget=unit_budget(w, n), rho=rho, Q=Q, K=K, V=V, counts=counts)
