@@ -39,6 +39,7 @@ def parse():
     ap.add_argument("--layers-per-call", type=int, default=0,
                     help="layers handed to one kvs_step call (0 = all; 1 = one call per layer)")
     ap.add_argument("--streams", type=int, default=1, help="deal the kvs_step calls of a step round-robin to this many streams")
+    ap.add_argument("--no-per-layer-calls", action="store_true", help="skip the one-call-per-layer comparison loop")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching from the host")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -47,11 +48,12 @@ def parse():
     return ap.parse_args()
 
 
-def phase_bytes(n, B, R, D, b):
+def phase_bytes(n, B, R, D, b, with_counts=False):
     """Algorithmic HBM bytes of one unit, per phase (each tensor counted once per phase that needs it)."""
-    score = 2 * n * D * b + R * D * b + 4 * n + 4 * D          # read K, V, Q; write alpha_bar, o_bar
+    c = 4 * n if with_counts else 0                            # input cardinalities (streaming regime)
+    score = 2 * n * D * b + R * D * b + 4 * n + 4 * D + c      # read K, V, Q; write alpha_bar, o_bar
     select = 4 * n + n + 4 * n                                 # read alpha_bar; write edge mask, slot map
-    merge = 2 * n * D * b + 9 * n + 4 * D + 2 * B * D * b + 4 * B   # read K, V, alpha, mask, slot, o_bar; write K', V', counts
+    merge = 2 * n * D * b + 9 * n + 4 * D + 2 * B * D * b + 4 * B + c   # read K, V, alpha, mask, slot, o_bar; write K', V', counts
     return {"score": score, "select": select, "merge_compact": merge}
 
 
@@ -109,23 +111,27 @@ def main():
             return torch.from_numpy(np.ascontiguousarray(x32, dtype=np.float32)).to(dev)
         return torch.from_numpy(f32_to_bf16_bits(x32).view(np.int16)).to(dev).view(torch.bfloat16)
 
-    Ks, Vs, Qs = [], [], []            # one tensor per batch of layers
+    Ks, Vs, Qs, Cs = [], [], [], []    # one tensor per batch of layers (Cs: row cardinalities or None)
     with ThreadPoolExecutor(max_workers=workers) as pool:
         for bt in batches:
             Kb = torch.empty((rows_layer * len(bt), D), dtype=tdt, device=dev)
             Vb = torch.empty_like(Kb)
             Qb = torch.empty((len(lens) * len(bt), R, D), dtype=tdt, device=dev)
+            Cb = torch.ones(rows_layer * len(bt), dtype=torch.int32, device=dev) if w.mean_count > 0 else None
             for i, layer in enumerate(bt):
                 ids = [(s, h) for s in range(w.n_seq) for h in range(w.n_kv_heads)]
                 units = list(pool.map(lambda sh: generate_unit(w, layer, sh[0], sh[1]), ids))
                 Kb[i * rows_layer:(i + 1) * rows_layer] = upload(np.concatenate([u.K for u in units]))
                 Vb[i * rows_layer:(i + 1) * rows_layer] = upload(np.concatenate([u.V for u in units]))
                 Qb[i * len(lens):(i + 1) * len(lens)] = upload(np.stack([u.Q.reshape(R, D) for u in units]))
+                if Cb is not None:
+                    Cb[i * rows_layer:(i + 1) * rows_layer] = torch.from_numpy(np.concatenate([u.counts for u in units])).to(dev)
                 if layer < n_keep_layers:
                     keep_host[layer] = units
             Ks.append(Kb)
             Vs.append(Vb)
             Qs.append(Qb)
+            Cs.append(Cb)
     t_gen = time.time() - t_gen
 
     probs = [problems[len(bt)] for bt in batches]
@@ -147,7 +153,7 @@ def main():
     def one_step():
         if n_streams == 1:
             for i, pr in enumerate(probs):
-                kvs.kvs_step(pr, Qs[i], Ks[i], Vs[i], K_out[i], V_out[i], counts[i], ws, stream=stream)
+                kvs.kvs_step_counts(pr, Qs[i], Ks[i], Vs[i], Cs[i], K_out[i], V_out[i], counts[i], ws, stream=stream)
             return
         # calls dealt round-robin to several streams (each with its own workspace): independent calls overlap
         main = torch.cuda.current_stream()
@@ -156,7 +162,7 @@ def main():
         for i, pr in enumerate(probs):
             j = i % n_streams
             sj = stream if j == 0 else side_streams[j - 1].cuda_stream
-            kvs.kvs_step(pr, Qs[i], Ks[i], Vs[i], K_out[i], V_out[i], counts[i], wss[j], stream=sj)
+            kvs.kvs_step_counts(pr, Qs[i], Ks[i], Vs[i], Cs[i], K_out[i], V_out[i], counts[i], wss[j], stream=sj)
         for st in side_streams:
             main.wait_stream(st)
 
@@ -197,7 +203,7 @@ def main():
 
     # ---- for comparison: the same step as one kvs_step call per layer, layer after layer on the same stream
     seq_ms = None
-    if lpc != 1 and not args.graph:
+    if lpc != 1 and not args.graph and not args.no_per_layer_calls:
         one = kvs.Problem(lens=lens, budgets=budgets, group=w.group, window=w.window, head_dim=D, dtype=w.dtype,
                           n_sink=w.n_sink, n_recent=w.n_recent)
         nu = len(lens)
@@ -206,8 +212,9 @@ def main():
             for i, bt in enumerate(batches):
                 for j in range(len(bt)):
                     r0, r1, o0, o1 = j * rows_layer, (j + 1) * rows_layer, j * one.rows_out, (j + 1) * one.rows_out
-                    kvs.kvs_step(one, Qs[i][j * nu:(j + 1) * nu], Ks[i][r0:r1], Vs[i][r0:r1], K_out[i][o0:o1],
-                                 V_out[i][o0:o1], counts[i][o0:o1], ws, stream=stream)
+                    kvs.kvs_step_counts(one, Qs[i][j * nu:(j + 1) * nu], Ks[i][r0:r1], Vs[i][r0:r1],
+                                        None if Cs[i] is None else Cs[i][r0:r1], K_out[i][o0:o1], V_out[i][o0:o1],
+                                        counts[i][o0:o1], ws, stream=stream)
 
         layer_calls()
         torch.cuda.synchronize()
@@ -227,11 +234,12 @@ def main():
     for rep in range(reps + 1):
         for i, pr in enumerate(probs):
             evs[i][0].record()
-            kvs.kvs_score(pr, Qs[i], Ks[i], Vs[i], alpha, obar, ws, stream=stream)
+            kvs.kvs_score_counts(pr, Qs[i], Ks[i], Vs[i], Cs[i], alpha, obar, ws, stream=stream)
             evs[i][1].record()
             kvs.kvs_select(pr, alpha, mask, slot, stream=stream)
             evs[i][2].record()
-            kvs.kvs_merge_compact(pr, Ks[i], Vs[i], alpha, obar, mask, slot, K_out[i], V_out[i], counts[i], stream=stream)
+            kvs.kvs_merge_compact_counts(pr, Ks[i], Vs[i], Cs[i], alpha, obar, mask, slot, K_out[i], V_out[i], counts[i],
+                                         stream=stream)
             evs[i][3].record()
         torch.cuda.synchronize()
         if rep == 0:
@@ -246,7 +254,7 @@ def main():
     phase_ms = {p: v / launches for p, v in phase_ms.items()}
     pb = {p: 0 for p in phases}                       # bytes of one layer's units
     for n, B in zip(lens, budgets):
-        for p, v in phase_bytes(n, min(n, B), R, D, b).items():
+        for p, v in phase_bytes(n, min(n, B), R, D, b, w.mean_count > 0).items():
             pb[p] += v
     step_bytes = sum(pb.values())
     pb = {p: v * layers_per_launch for p, v in pb.items()}     # ... of one launch's units
@@ -259,7 +267,8 @@ def main():
     step_gbs = step_bytes * layers / (ms_per_step * 1e-3) / 1e9
 
     result = {
-        "metric": "merged KV tokens/s and achieved HBM GB/s (% of peak), 8B-shape 32K merge step",
+        "metric": ("merged KV tokens/s and achieved HBM GB/s (% of peak), 8B-shape 32K merge step"
+                   if w.name == "llama8b_32k" else f"merged KV cache rows/s and achieved HBM GB/s (% of peak), {w.name}"),
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 in/out, f32 accumulate" if w.dtype == "bf16" else "f32", "data": "synthetic",
@@ -306,7 +315,7 @@ def cpu_baseline(w, keep_host, target_s, workers):
         return None
 
     def run(u):
-        O.step(u.Q, u.K, u.V, u.budget, w.n_sink, w.n_recent)
+        O.step(u.Q, u.K, u.V, u.budget, w.n_sink, w.n_recent, counts=u.counts)
         return u.n
 
     with threadpool_limits(limits=1):
