@@ -43,6 +43,11 @@ it when `counts` is given: alpha_bar is then the slot's total mass, the residual
 of O8 is V / c - o, merged Values stay sums and merged cardinalities add up.
 Without `counts` every row is a plain token (c = 1).
 
+Ablation rules for the merged Key (the paper's comparison of Sec. 3.1 / Sec. 4: what the off-diagonal
+coupling buys): `rule="diagonal"` drops the coupling blocks (C_t := 0, the diagonal-only Hessian the
+paper calls overlooked coupling), `rule="mean"` is the plain arithmetic mean of the run (over the tokens
+the rows stand for).  Values, cardinalities and the partition are the same for every rule.
+
 Readings of points the paper leaves open (many query rows, ranking score, runs
 longer than two, a non-positive denominator) are this module's and are listed
 in the repository's design notes.
@@ -174,8 +179,13 @@ class MergeResult:
     fallback: np.ndarray     # [n_out] bool: arithmetic-mean fallback taken
 
 
+RULES = ("hessian", "diagonal", "mean")
+
+
 def merge_compact(K: np.ndarray, V: np.ndarray, alpha_bar: np.ndarray, o_bar: np.ndarray,
-                  mask: np.ndarray, slot: np.ndarray, counts_in: Optional[np.ndarray] = None) -> MergeResult:
+                  mask: np.ndarray, slot: np.ndarray, counts_in: Optional[np.ndarray] = None,
+                  rule: str = "hessian") -> MergeResult:
+    assert rule in RULES
     K = np.asarray(K, dtype=F64)
     V = np.asarray(V, dtype=F64)
     n, D = K.shape
@@ -205,9 +215,13 @@ def merge_compact(K: np.ndarray, V: np.ndarray, alpha_bar: np.ndarray, o_bar: np
             K_out[S] = K[t0]
             U_all[S] = A[t0]
             continue
-        u = A[t0:t1 + 1].copy()
-        u[:-1] -= C[t0:t1]                                  # coupling with the next token
-        u[1:] -= C[t0:t1]                                   # coupling with the previous token
+        if rule == "mean":
+            u = c_in[t0:t1 + 1].astype(F64)                 # every token the rows stand for counts once
+        else:
+            u = A[t0:t1 + 1].copy()
+            if rule == "hessian":
+                u[:-1] -= C[t0:t1]                          # coupling with the next token
+                u[1:] -= C[t0:t1]                           # coupling with the previous token
         U = u.sum()
         U_all[S] = U
         if np.isfinite(U) and U > 0.0:
@@ -241,10 +255,11 @@ class StepResult:
 
 
 def step(Q: np.ndarray, K: np.ndarray, V: np.ndarray, budget: int, n_sink: int = 32,
-         n_recent: int = 0, scale: Optional[float] = None, counts: Optional[np.ndarray] = None) -> StepResult:
+         n_recent: int = 0, scale: Optional[float] = None, counts: Optional[np.ndarray] = None,
+         rule: str = "hessian") -> StepResult:
     alpha_bar, o_bar = score(Q, K, V, scale, counts)
     mask, slot = select(alpha_bar, budget, n_sink, n_recent)
-    merged = merge_compact(K, V, alpha_bar, o_bar, mask, slot, counts)
+    merged = merge_compact(K, V, alpha_bar, o_bar, mask, slot, counts, rule)
     return StepResult(alpha_bar, o_bar, mask, slot, merged)
 
 

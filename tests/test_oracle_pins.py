@@ -538,3 +538,47 @@ def test_fallback_with_counts_is_the_mean_over_the_tokens_the_rows_stand_for():
     assert res.fallback[1] and not res.fallback[0]
     Ke, _, owner = expanded_cache(K, V, c)
     np.testing.assert_allclose(res.K_out[1], Ke[(owner >= 1) & (owner <= 3)].mean(axis=0), rtol=1e-14)
+
+
+# --------------------------------------------------------------------------------------------
+# Ablation rules of the merged Key
+def test_mean_rule_is_the_arithmetic_mean_of_the_tokens():
+    rng = np.random.default_rng(50)
+    n, d = 10, 4
+    K, V = rng.standard_normal((n, d)), rng.standard_normal((n, d))
+    c = rng.integers(1, 4, size=n)
+    mask = np.zeros(n, dtype=np.uint8)
+    mask[2:5] = 1
+    slot = np.concatenate([[0], np.cumsum(mask[:-1] == 0)]).astype(np.int32)
+    q = rng.standard_normal(d)
+    ab, ob = O.score(q[None, :], K, V)
+    res = O.merge_compact(K, V, ab, ob, mask, slot, rule="mean")
+    np.testing.assert_allclose(res.K_out[2], K[2:6].mean(axis=0), rtol=1e-14)
+    ab, ob = O.score(q[None, :], K, V, counts=c)
+    res = O.merge_compact(K, V, ab, ob, mask, slot, counts_in=c, rule="mean")
+    Ke, _, owner = expanded_cache(K, V, c)
+    np.testing.assert_allclose(res.K_out[2], Ke[(owner >= 2) & (owner <= 5)].mean(axis=0), rtol=1e-14)
+    full = O.merge_compact(K, V, ab, ob, mask, slot, counts_in=c)
+    assert np.array_equal(full.V_out, res.V_out) and np.array_equal(full.counts, res.counts)
+
+
+@pytest.mark.parametrize("seed,L", [(51, 2), (52, 3), (53, 4)])
+def test_diagonal_rule_minimises_the_objective_without_coupling(seed, L):
+    """C := 0: the minimiser of sum_a g_aa (q.(k - k_a))^2 with g_aa from finite differences."""
+    n = 8
+    q, K, V = tiny_head(seed, n=n, d=4, dv=6, spread=1.2)
+    t0, t1 = 2, 2 + L - 1
+    mask = np.zeros(n, dtype=np.uint8)
+    mask[t0:t1] = 1
+    slot = np.concatenate([[0], np.cumsum(mask[:-1] == 0)]).astype(np.int32)
+    ab, ob = O.score(q[None, :], K, V)
+    res = O.merge_compact(K, V, ab, ob, mask, slot, rule="diagonal")
+    J = fd_ds_de(q, K, V)
+    g = np.array([np.linalg.norm(J[t, t]) for t in range(t0, t1 + 1)])
+    x = K[t0:t1 + 1] @ q
+    xstar = minimize_scalar(lambda z: ((z - x) ** 2 * g).sum(), bracket=(x.min() - 1, x.mean(), x.max() + 1),
+                            tol=1e-14).x
+    assert abs(q @ res.K_out[t0] - xstar) < 2e-6 * max(1.0, abs(xstar))
+    # and it differs from the full rule: the coupling term is visible on a tiny head
+    full = O.merge_compact(K, V, ab, ob, mask, slot)
+    assert np.linalg.norm(full.K_out[t0] - res.K_out[t0]) > 1e-4 * np.linalg.norm(full.K_out[t0])
