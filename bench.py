@@ -40,6 +40,8 @@ def parse():
                     help="layers handed to one kvs_step call (0 = all; 1 = one call per layer)")
     ap.add_argument("--streams", type=int, default=1, help="deal the kvs_step calls of a step round-robin to this many streams")
     ap.add_argument("--no-per-layer-calls", action="store_true", help="skip the one-call-per-layer comparison loop")
+    ap.add_argument("--key-rule", default="hessian", choices=["hessian", "diagonal", "mean"],
+                    help="rule for the merged Key (the ablations run the same kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching from the host")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -97,7 +99,7 @@ def main():
     problems = {}
     for nl in {len(bt) for bt in batches}:
         problems[nl] = kvs.Problem(lens=lens * nl, budgets=budgets * nl, group=w.group, window=w.window, head_dim=D,
-                                   dtype=w.dtype, n_sink=w.n_sink, n_recent=w.n_recent)
+                                   dtype=w.dtype, n_sink=w.n_sink, n_recent=w.n_recent, key_rule=args.key_rule)
     rows_layer = sum(lens)
 
     # ---- synthetic inputs, one independent draw per (layer, sequence, head), uploaded once
@@ -205,7 +207,7 @@ def main():
     seq_ms = None
     if lpc != 1 and not args.graph and not args.no_per_layer_calls:
         one = kvs.Problem(lens=lens, budgets=budgets, group=w.group, window=w.window, head_dim=D, dtype=w.dtype,
-                          n_sink=w.n_sink, n_recent=w.n_recent)
+                          n_sink=w.n_sink, n_recent=w.n_recent, key_rule=args.key_rule)
         nu = len(lens)
 
         def layer_calls():
@@ -275,7 +277,7 @@ def main():
         "config": {"workload": w.name, "layers": layers, "kv_heads": w.n_kv_heads, "q_heads": w.group * w.n_kv_heads,
                    "head_dim": D, "window": w.window, "tokens": lens_seq if w.n_seq > 1 else lens_seq[0],
                    "budget": budgets[0] if w.n_seq == 1 else "25% of length", "n_sink": w.n_sink,
-                   "layers_per_call": lpc, "streams": n_streams, "launch": "hip graph replay" if args.graph else "host",
+                   "key_rule": args.key_rule, "layers_per_call": lpc, "streams": n_streams, "launch": "hip graph replay" if args.graph else "host",
                    "us_per_layer": ms_per_step * 1e3 / layers,
                    "one_call_per_layer": None if seq_ms is None else {
                        "ms_per_step": seq_ms, "us_per_layer": seq_ms * 1e3 / layers,
@@ -300,11 +302,11 @@ def main():
         torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, keep_host, args.cpu_seconds, workers)
+        result["cpu_baseline"] = cpu_baseline(w, keep_host, args.cpu_seconds, workers, args.key_rule)
     print(json.dumps(result))
 
 
-def cpu_baseline(w, keep_host, target_s, workers):
+def cpu_baseline(w, keep_host, target_s, workers, rule="hessian"):
     """The fp64 oracle as it stands, on this machine's host cores, over a bounded sample of the same units."""
     from threadpoolctl import threadpool_limits
 
@@ -315,7 +317,7 @@ def cpu_baseline(w, keep_host, target_s, workers):
         return None
 
     def run(u):
-        O.step(u.Q, u.K, u.V, u.budget, w.n_sink, w.n_recent, counts=u.counts)
+        O.step(u.Q, u.K, u.V, u.budget, w.n_sink, w.n_recent, counts=u.counts, rule=rule)
         return u.n
 
     with threadpool_limits(limits=1):

@@ -48,7 +48,7 @@ extern "C" {
 typedef enum {
   KVS_OK = 0,
   KVS_ERR_INVALID_ARG = 1,  /* null pointer, misaligned pointer, non-positive size, head_dim not 64/128,
-                               G*W above KVS_MAX_Q_ROWS, overlapping units */
+                               G*W above KVS_MAX_Q_ROWS, overlapping units, unknown key_rule */
   KVS_ERR_DTYPE = 2,        /* io_dtype is neither KVS_F32 nor KVS_BF16 */
   KVS_ERR_BUDGET = 3,       /* budget < n_sink + 1 + n_recent for a unit that has to merge (len > budget),
                                or budget < 1 */
@@ -58,6 +58,13 @@ typedef enum {
 } kvs_status;
 
 typedef enum { KVS_F32 = 0, KVS_BF16 = 1 } kvs_dtype;
+
+/* Rule for the merged Key of a slot of several rows (Values, cardinalities and slots do not depend on it). */
+typedef enum {
+  KVS_RULE_HESSIAN = 0,     /* Sec. 4.2, Eq. kstar_final: exact-Hessian weights with the off-diagonal coupling */
+  KVS_RULE_DIAGONAL = 1,    /* ablation: the coupling blocks dropped (C_t := 0), weights proportional to A_t   */
+  KVS_RULE_MEAN = 2         /* ablation: arithmetic mean over the tokens the rows stand for                    */
+} kvs_key_rule;
 
 typedef struct {
   int32_t n_units;          /* n_seq * n_kv_heads; one unit = one sequence's one KV head            */
@@ -75,6 +82,7 @@ typedef struct {
                                disjoint                                                              */
   const int64_t* out_row;   /* HOST [n_units] first row of the unit in K_out, V_out, counts_out;
                                ranges [out_row, out_row + min(len, budget)) must be disjoint         */
+  kvs_key_rule key_rule;    /* KVS_RULE_HESSIAN (0) unless an ablation is wanted                     */
 } kvs_problem;
 
 /* Bytes of DEVICE workspace (256-byte aligned) that the calls below need for this problem. */

@@ -24,12 +24,16 @@ EXPORTS = ["kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact",
            "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_status_str", "kvs_version"]
 
 
+KEY_RULES = {"hessian": 0, "diagonal": 1, "mean": 2}
+
+
 class KvsProblemStruct(C.Structure):
     _fields_ = [
         ("n_units", C.c_int32), ("group", C.c_int32), ("window", C.c_int32), ("head_dim", C.c_int32),
         ("n_sink", C.c_int32), ("n_recent", C.c_int32), ("io_dtype", C.c_int), ("scale", C.c_float),
         ("len", C.POINTER(C.c_int32)), ("budget", C.POINTER(C.c_int32)),
         ("in_row", C.POINTER(C.c_int64)), ("out_row", C.POINTER(C.c_int64)),
+        ("key_rule", C.c_int),
     ]
 
 
@@ -92,7 +96,8 @@ class Problem:
 
     def __init__(self, *, lens: Sequence[int], budgets: Sequence[int], group: int, window: int, head_dim: int,
                  dtype: str, n_sink: int = 32, n_recent: int = 0, scale: float = 0.0,
-                 in_rows: Optional[Sequence[int]] = None, out_rows: Optional[Sequence[int]] = None):
+                 in_rows: Optional[Sequence[int]] = None, out_rows: Optional[Sequence[int]] = None,
+                 key_rule=0):
         n = len(lens)
         if in_rows is None:
             in_rows, acc = [], 0
@@ -120,7 +125,8 @@ class Problem:
         self.struct = KvsProblemStruct(
             n_units=n, group=group, window=window, head_dim=head_dim, n_sink=n_sink, n_recent=n_recent,
             io_dtype=DTYPES[dtype] if isinstance(dtype, str) else int(dtype), scale=float(scale),
-            len=self._len, budget=self._budget, in_row=self._in, out_row=self._out)
+            len=self._len, budget=self._budget, in_row=self._in, out_row=self._out,
+            key_rule=KEY_RULES[key_rule] if isinstance(key_rule, str) else int(key_rule))
 
     @property
     def ref(self):

@@ -40,6 +40,9 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
   if (p->io_dtype != KVS_F32 && p->io_dtype != KVS_BF16) return KVS_ERR_DTYPE;
   if (!(p->scale >= 0.f) || !std::isfinite(p->scale)) return KVS_ERR_INVALID_ARG;
   if (!p->len || !p->budget || !p->in_row || !p->out_row) return KVS_ERR_INVALID_ARG;
+  if (p->key_rule != KVS_RULE_HESSIAN && p->key_rule != KVS_RULE_DIAGONAL && p->key_rule != KVS_RULE_MEAN) {
+    return KVS_ERR_INVALID_ARG;
+  }
 
   plan->n_units = p->n_units;
   plan->dtype = p->io_dtype;
@@ -48,6 +51,7 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
   plan->shape.D = p->head_dim;
   plan->shape.n_sink = p->n_sink;
   plan->shape.n_recent = p->n_recent;
+  plan->shape.rule = (int)p->key_rule;
   const double scale = (p->scale == 0.f) ? 1.0 / std::sqrt((double)p->head_dim) : (double)p->scale;
   plan->shape.scale_log2 = (float)(scale * 1.4426950408889634);
   plan->units.resize(p->n_units);

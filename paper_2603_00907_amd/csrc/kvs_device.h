@@ -63,6 +63,7 @@ struct Shape {
   int n_recent;
   float scale_log2; // logit scale * log2(e): logits are kept in the base-2 domain
   int stream;       // 1: the launch's K and V exceed the last-level cache, rows are read non-temporally
+  int rule;         // kvs_key_rule of the merged Key
 };
 
 // Workspace carve-up (all offsets multiples of 256 bytes).

@@ -9,7 +9,8 @@
 //                                                    for a longer run), arithmetic mean of the run if
 //                                                    the denominator is not positive and finite
 //   V_out[S] = sum V[t]                            (Sec. 3.1), counts[S] = t1 - t0 + 1
-// A slot of one token is copied bit for bit.
+// A slot of one token is copied bit for bit.  Ablation rules (kvs_key_rule): C_t := 0, or u_t := the
+// number of tokens row t stands for (arithmetic mean).
 //
 // COUNTS: the rows are slots of an already merged cache, row t standing for c_t tokens whose Values add
 // up to V[t] (Sec. 3.1, streaming regime): r_t = V[t] / c_t - o_bar, counts[S] = sum c_t, the fallback is
@@ -222,6 +223,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     }
   };
 
+  // ablations of the Key rule (uniform): no coupling blocks, or plain token-count weights
+  const bool coupled = sh.rule == KVS_RULE_HESSIAN;
+  const bool mean_rule = sh.rule == KVS_RULE_MEAN;
   const int per = (B - A + GROUPS - 1) / GROUPS;
   const int ga = A + group * per;
   const int gb = min(B, ga + per);
@@ -287,7 +291,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       ss_cur = group_sum<LPR>(ss_cur);
       ss_b = group_sum<LPR>(ss_b);
       dot = group_sum<LPR>(dot);
-      Cprev = a_before * alpha_cur * __builtin_amdgcn_sqrtf(fmaxf(fmaf(2.f, dot, ss_b + ss_cur), 0.f));
+      Cprev = coupled ? a_before * alpha_cur * __builtin_amdgcn_sqrtf(fmaxf(fmaf(2.f, dot, ss_b + ss_cur), 0.f)) : 0.f;
     }
 
     // One token.  The same straight-line code for every token: lane groups of a wavefront stay converged.
@@ -318,8 +322,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       dot = group_sum<LPR>(dot);
       const float Anorm = alpha_cur * fabsf(1.f - 2.f * alpha_cur) * __builtin_amdgcn_sqrtf(ss_cur);
       const float pair2 = fmaxf(fmaf(2.f, dot, ss_cur + ss_next), 0.f);
-      const float C = mask_cur ? alpha_cur * alpha_n * __builtin_amdgcn_sqrtf(pair2) : 0.f;
-      const float u = Anorm - Cprev - C;
+      const float C = (mask_cur && coupled) ? alpha_cur * alpha_n * __builtin_amdgcn_sqrtf(pair2) : 0.f;
+      const float u = mean_rule ? (float)c_cur : Anorm - Cprev - C;
       first_tok = (count == 0) ? t : first_tok;
       U += u;
       ++count;

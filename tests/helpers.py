@@ -106,7 +106,8 @@ class DeviceBatch:
     GUARD = 64     # rows of guard band after each output buffer
 
     def __init__(self, units: List, *, group: int, window: int, head_dim: int, dtype: str,
-                 n_sink: int, n_recent: int = 0, budgets: Optional[List[int]] = None, gap_rows: int = 0):
+                 n_sink: int, n_recent: int = 0, budgets: Optional[List[int]] = None, gap_rows: int = 0,
+                 key_rule="hessian"):
         import torch
         import paper_2603_00907_amd as kvs
         self.kvs = kvs
@@ -118,7 +119,8 @@ class DeviceBatch:
             in_rows.append(acc)
             acc += l + gap_rows
         self.problem = kvs.Problem(lens=lens, budgets=budgets, group=group, window=window, head_dim=head_dim,
-                                   dtype=dtype, n_sink=n_sink, n_recent=n_recent, in_rows=in_rows)
+                                   dtype=dtype, n_sink=n_sink, n_recent=n_recent, in_rows=in_rows,
+                                   key_rule=key_rule)
         p = self.problem
         D = head_dim
         self.dtype = dtype

@@ -64,6 +64,8 @@ def test_workspace_size_grows_with_the_problem():
     (dict(lens=[(1 << 22) + 1, 5], budgets=[1 << 21, 5]), kvs.KVS_ERR_INVALID_ARG),   # above KVS_MAX_LEN
     (dict(lens=[1 << 22, 5], budgets=[1 << 21, 5]), kvs.KVS_OK),
     (dict(n_sink=-1), kvs.KVS_ERR_INVALID_ARG),
+    (dict(key_rule=3), kvs.KVS_ERR_INVALID_ARG),
+    (dict(key_rule="mean"), kvs.KVS_OK),
     (dict(scale=float("nan")), kvs.KVS_ERR_INVALID_ARG),
     (dict(dtype=7), kvs.KVS_ERR_DTYPE),
     (dict(budgets=[20, 600]), kvs.KVS_ERR_BUDGET),                 # must merge but budget < n_sink + 1

@@ -189,9 +189,26 @@ def merge_case(base, dtype, D, lens, budgets=None, R=(1, 4), seed_layer=0):
     ("stream2560", "bf16", 64, [900], [899]),
 ])
 def test_merge_compact_matches_oracle(base, dtype, D, lens, budgets):
+    check_merge_compact(base, dtype, D, lens, budgets, "hessian")
+
+
+@pytest.mark.parametrize("rule", ["diagonal", "mean"])
+@pytest.mark.parametrize("base,dtype,D,lens,budgets", [
+    ("tiny", "f32", 64, [1024, 90], None),
+    ("llama8b_8k", "bf16", 128, [3000], [700]),
+    ("stream2560", "bf16", 128, [1300], [1000]),
+    ("stream2560", "f32", 64, [700], [200]),
+])
+def test_merge_compact_ablation_rules(base, dtype, D, lens, budgets, rule):
+    """The Key rule without the coupling blocks, and the plain mean, on the same ABI (kvs_problem.key_rule)."""
+    check_merge_compact(base, dtype, D, lens, budgets, rule)
+
+
+def check_merge_compact(base, dtype, D, lens, budgets, rule):
     import torch
     w, units = merge_case(base, dtype, D, lens, budgets)
-    batch = DeviceBatch(units, group=w.group, window=w.window, head_dim=D, dtype=dtype, n_sink=w.n_sink)
+    batch = DeviceBatch(units, group=w.group, window=w.window, head_dim=D, dtype=dtype, n_sink=w.n_sink,
+                        key_rule=rule)
     p = batch.problem
     refs = []
     alpha_all = np.zeros(p.rows_in, dtype=np.float32)
@@ -203,7 +220,7 @@ def test_merge_compact_matches_oracle(base, dtype, D, lens, budgets):
         a32, o32 = a.astype(np.float32), o.astype(np.float32)
         mask, slot = O.select(a32, u.budget, w.n_sink, 0, sigma_dtype=np.float32)
         refs.append(O.merge_compact(u.K, u.V, a32.astype(np.float64), o32.astype(np.float64), mask, slot,
-                                    counts_in=u.counts))
+                                    counts_in=u.counts, rule=rule))
         r0 = p.in_rows[i]
         alpha_all[r0:r0 + len(a)] = a32
         mask_all[r0:r0 + len(a)] = mask
