@@ -278,3 +278,12 @@ def merged_attention(q: np.ndarray, K_out: np.ndarray, V_out: np.ndarray, counts
     e = scale * (np.asarray(K_out, dtype=F64) @ q)
     w = np.exp(e - e.max())
     return (w @ np.asarray(V_out, dtype=F64)) / (w @ np.asarray(counts, dtype=F64))
+
+
+def decode_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, counts: Optional[np.ndarray] = None,
+                     scale: Optional[float] = None) -> np.ndarray:
+    """merged_attention for every row of Q [..., D]: out [R, D].  counts = None: a plain cache (c = 1)."""
+    K = np.asarray(K, dtype=F64)
+    Q = np.asarray(Q, dtype=F64).reshape(-1, K.shape[1])
+    c = np.ones(K.shape[0], dtype=F64) if counts is None else np.asarray(counts, dtype=F64)
+    return np.stack([merged_attention(q, K, V, c, scale) for q in Q])

@@ -582,3 +582,19 @@ def test_diagonal_rule_minimises_the_objective_without_coupling(seed, L):
     # and it differs from the full rule: the coupling term is visible on a tiny head
     full = O.merge_compact(K, V, ab, ob, mask, slot)
     assert np.linalg.norm(full.K_out[t0] - res.K_out[t0]) > 1e-4 * np.linalg.norm(full.K_out[t0])
+
+
+# --------------------------------------------------------------------------------------------
+# The consumer of a merged cache
+def test_decode_attention_over_a_merged_cache_is_attention_over_the_tokens_it_stands_for():
+    rng = np.random.default_rng(60)
+    n, d = 11, 6
+    K, V = rng.standard_normal((n, d)) * 1.5, rng.standard_normal((n, d)) * 2.0
+    c = rng.integers(1, 5, size=n)
+    Ke, Ve, _ = expanded_cache(K, V, c)
+    Q = rng.standard_normal((2, 3, d))
+    got = O.decode_attention(Q, K, V, c)
+    want = np.stack([softmax_attention(q, Ke, Ve)[1] for q in Q.reshape(-1, d)])
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
+    plain = O.decode_attention(Q, K, V)
+    np.testing.assert_allclose(plain, np.stack([softmax_attention(q, K, V)[1] for q in Q.reshape(-1, d)]), rtol=1e-12)
