@@ -43,6 +43,7 @@ extern "C" {
 
 #define KVS_VERSION 200          /* major*10000 + minor*100 + patch */
 #define KVS_MAX_Q_ROWS 1024      /* largest supported G*W */
+#define KVS_MAX_DECODE_ROWS 64   /* largest G*W of kvs_decode_attention */
 #define KVS_MAX_LEN (1 << 22)    /* largest supported cache length of one unit, in tokens */
 
 typedef enum {
@@ -148,6 +149,24 @@ kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, c
                            void* K_out, void* V_out, int32_t* counts_out,
                            int32_t* slot_of_token_out, uint8_t* edge_mask_out,
                            void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Sec. 3.1 (sum-merged Values with cardinality normalisation): attention of the problem's G*W query rows
+ * over a merged cache, the consumer of kvs_merge_compact's outputs.  Row t of unit u (rows in_row[u] ..
+ * in_row[u] + len[u] of K, V, counts) is a slot (k', V', c) standing for c tokens with the Key k' whose
+ * Values add up to V':
+ *   out[u, q, :] = sum_t exp(e_t) V[t] / sum_t counts[t] exp(e_t),   e_t = scale * Q[u, q] . K[t]
+ * which is attention over the tokens the rows stand for.  budget, n_sink, n_recent and key_rule of the
+ * problem are not used (pass budget = len); G*W <= KVS_MAX_DECODE_ROWS (KVS_ERR_INVALID_ARG above).
+ *   Q       DEVICE in  [n_units, G, W, D] io_dtype
+ *   K, V    DEVICE in  [rows, D] io_dtype (for example K_out, V_out of a merge step)
+ *   counts  DEVICE in  [rows] i32, or NULL for a cache of plain tokens
+ *   out     DEVICE out [n_units, G*W, D] fp32
+ *   ws      DEVICE workspace of kvs_decode_workspace_size(p) bytes, 256-byte aligned (KVS_ERR_WORKSPACE)
+ * Asynchronous on hip_stream; nothing is allocated; errors are found on the host before any launch.     */
+kvs_status kvs_decode_workspace_size(const kvs_problem* p, size_t* bytes);
+kvs_status kvs_decode_attention(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                                const int32_t* counts, float* out,
+                                void* ws, size_t ws_bytes, void* hip_stream);
 
 const char* kvs_status_str(kvs_status s);
 int kvs_version(void);

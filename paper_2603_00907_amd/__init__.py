@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     KVS_OK,
     KvsError,
     Problem,
+    kvs_decode_attention,
+    kvs_decode_workspace_size,
     kvs_merge_compact,
     kvs_merge_compact_counts,
     kvs_score,

@@ -21,7 +21,8 @@ KVS_F32, KVS_BF16 = 0, 1
 DTYPES = {"f32": KVS_F32, "bf16": KVS_BF16}
 
 EXPORTS = ["kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step",
-           "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_status_str", "kvs_version"]
+           "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_decode_workspace_size",
+           "kvs_decode_attention", "kvs_status_str", "kvs_version"]
 
 
 KEY_RULES = {"hessian": 0, "diagonal": 1, "mean": 2}
@@ -72,8 +73,11 @@ def load_library(path: Optional[str] = None):
     lib.kvs_score_counts.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_merge_compact_counts.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_step_counts.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_decode_workspace_size.argtypes = [P, C.POINTER(sz)]
+    lib.kvs_decode_attention.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
     for name in ("kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step",
-                 "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts"):
+                 "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_decode_workspace_size",
+                 "kvs_decode_attention"):
         getattr(lib, name).restype = C.c_int
     lib.kvs_status_str.argtypes = [C.c_int]
     lib.kvs_status_str.restype = C.c_char_p
@@ -203,3 +207,15 @@ def kvs_step_counts(problem: Problem, Q, K, V, counts_in, K_out, V_out, counts_o
         problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(counts_in), _ptr(K_out), _ptr(V_out), _ptr(counts_out),
         _ptr(slot_of_token_out), _ptr(edge_mask_out), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
         stream), "kvs_step_counts")
+
+
+def kvs_decode_workspace_size(problem: Problem) -> int:
+    out = C.c_size_t(0)
+    _check(load_library().kvs_decode_workspace_size(problem.ref, C.byref(out)), "kvs_decode_workspace_size")
+    return int(out.value)
+
+
+def kvs_decode_attention(problem: Problem, Q, K, V, counts, out, ws, stream: int = 0, ws_bytes: Optional[int] = None):
+    _check(load_library().kvs_decode_attention(
+        problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(counts), _ptr(out), _ptr(ws),
+        _nbytes(ws) if ws_bytes is None else ws_bytes, stream), "kvs_decode_attention")

@@ -351,6 +351,36 @@ kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, c
   });
 }
 
+kvs_status kvs_decode_workspace_size(const kvs_problem* p, size_t* bytes) {
+  if (bytes == nullptr) return KVS_ERR_INVALID_ARG;
+  Plan plan;
+  const kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  if (plan.shape.R > KVS_MAX_DECODE_ROWS) return KVS_ERR_INVALID_ARG;
+  *bytes = align_up((size_t)plan.n_units * kMaxChunks * plan.shape.R * (plan.shape.D + 2) * sizeof(float));
+  return KVS_OK;
+}
+
+kvs_status kvs_decode_attention(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                                const int32_t* counts, float* out, void* ws, size_t ws_bytes, void* hip_stream) {
+  Plan plan;
+  kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  if (plan.shape.R > KVS_MAX_DECODE_ROWS) return KVS_ERR_INVALID_ARG;
+  const size_t need = align_up((size_t)plan.n_units * kMaxChunks * plan.shape.R * (plan.shape.D + 2) * sizeof(float));
+  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < need) return KVS_ERR_WORKSPACE;
+  const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
+  const size_t qo = (size_t)plan.n_units * plan.shape.R * plan.shape.D;
+  std::vector<Range> rs = {{Q, qo * plan.elt, false}, {K, kv, false}, {V, kv, false},
+                           {out, qo * sizeof(float), true}, {ws, need, true}};
+  if (counts) rs.push_back({counts, (size_t)plan.rows_in * 4, false});
+  if ((st = check_ranges(rs)) != KVS_OK) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
+    return launch_decode(tab, sh, plan.dtype, Q, K, V, counts, (float*)ws, out, s);
+  });
+}
+
 const char* kvs_status_str(kvs_status s) {
   switch (s) {
     case KVS_OK: return "ok";

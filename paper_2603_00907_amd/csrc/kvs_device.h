@@ -172,4 +172,8 @@ hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, con
                         const uint8_t* edge_mask,
                         const int32_t* slot, void* K_out, void* V_out, int32_t* counts, hipStream_t stream);
 
+// Decode attention over a (merged) cache: chunk partials into `part`, then out[n_units, R, D].
+hipError_t launch_decode(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
+                         const void* V, const int32_t* counts, float* part, float* out, hipStream_t stream);
+
 }  // namespace kvs

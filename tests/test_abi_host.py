@@ -162,3 +162,23 @@ def test_generator_is_order_independent_and_rounds_once():
     # four outlier channels, scaled 8x
     var = a.K.var(axis=0)
     assert (var > 20 * np.median(var)).sum() == 4
+
+
+def test_decode_and_counts_entry_points_validate_on_the_host():
+    p = problem()
+    b = fake_buffers(p)
+    dws = FakeBuf(b["ws"].addr, kvs.kvs_decode_workspace_size(p))
+    out = FakeBuf(1 << 40, len(p.lens) * p.group * p.window * 64 * 4)
+    cin = FakeBuf((1 << 40) + (1 << 30), p.rows_in * 4)
+    dec = lambda **o: status_of(  # noqa: E731
+        kvs.kvs_decode_attention, p, o.get("Q", b["Q"]), b["K"], b["V"], o.get("counts", cin), o.get("out", out),
+        o.get("ws", dws), ws_bytes=o.get("ws_bytes"))
+    assert dec(Q=None) == kvs.KVS_ERR_INVALID_ARG
+    assert dec(out=b["K"]) == kvs.KVS_ERR_ALIAS
+    assert dec(ws_bytes=dws.nbytes - 1) == kvs.KVS_ERR_WORKSPACE
+    assert dec(counts=FakeBuf(cin.addr + 2, 16)) == kvs.KVS_ERR_INVALID_ARG          # misaligned
+    wide = problem(group=9, window=8)                                                # 72 rows > KVS_MAX_DECODE_ROWS
+    assert status_of(kvs.kvs_decode_workspace_size, wide) == kvs.KVS_ERR_INVALID_ARG
+    # cardinalities that overlap an output are an alias error like any other input
+    assert status_of(kvs.kvs_step_counts, p, b["Q"], b["K"], b["V"], b["K_out"], b["K_out"], b["V_out"], b["counts"],
+                     b["ws"]) == kvs.KVS_ERR_ALIAS

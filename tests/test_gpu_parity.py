@@ -466,3 +466,65 @@ def test_step_passthrough_and_single_token_units():
         r0 = batch.problem.out_rows[i]
         assert (Ko[r0:r0 + u.n] == u.K).all() and (Vo[r0:r0 + u.n] == u.V).all()
         assert (cnt[r0:r0 + u.n] == 1).all()
+
+
+# ------------------------------------------------------------------------------------------------
+# the consumer: decode attention over a (merged) cache
+@pytest.mark.parametrize("base,dtype,D,G,W,lens", [
+    ("tiny", "f32", 64, 1, 1, [1024]),
+    ("tiny", "f32", 128, 3, 2, [700, 41, 5000]),
+    ("llama8b_8k", "bf16", 128, 4, 1, [2048, 300]),
+    ("stream2560", "bf16", 128, 4, 1, [2560, 2049]),
+    ("stream2560", "bf16", 64, 4, 3, [1111]),
+    ("stream2560", "f32", 64, 2, 5, [2300]),
+])
+def test_decode_attention_matches_oracle(base, dtype, D, G, W, lens):
+    import torch
+    w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
+    units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
+    batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype=dtype, n_sink=0, budgets=lens, gap_rows=2)
+    p = batch.problem
+    R = G * W
+    out = torch.full((len(units) + 1, R, D), -7.0, dtype=torch.float32, device="cuda")
+    ws = torch.empty(batch.kvs.kvs_decode_workspace_size(p), dtype=torch.uint8, device="cuda")
+    batch.kvs.kvs_decode_attention(p, batch.Q, batch.K, batch.V, batch.counts_in, out, ws, stream=batch.stream())
+    torch_sync()
+    assert (out[len(units):] == -7.0).all()
+    got = out.cpu().numpy()
+    for i, u in enumerate(units):
+        want = O.decode_attention(u.Q, u.K, u.V, u.counts)
+        # every weight carries the relative error of a softmax weight; bound the sum term by term
+        c = np.ones(u.n) if u.counts is None else u.counts
+        alpha = O.attention_rows(u.Q, u.K, counts=c)                    # [R, n] masses of the rows
+        bound = TOL_ALPHA * (alpha @ np.abs(O.slot_values(u.V, c))) + 1e-7
+        assert np.isfinite(got[i]).all()
+        assert (np.abs(got[i] - want) <= bound).all(), (i, np.max(np.abs(got[i] - want) / bound))
+
+
+def test_decode_attention_over_the_output_of_a_step():
+    """End to end: merge a cache, then attend over (K', V', counts) with fresh queries; the GPU result equals
+    the oracle's attention over the oracle's merged cache (both within their tolerances)."""
+    import torch
+    w = WORKLOADS["llama8b_8k"].scaled(length=("fixed", 4000), budget=("fixed", 1000))
+    acc = [accepted_unit(w, 0, 0, h) for h in range(2)]
+    batch = check_step(w, acc)
+    p = batch.problem
+    rng = np.random.default_rng(5)
+    G = w.group
+    qn = rng.standard_normal((len(acc), G, 1, w.head_dim)).astype(np.float32)
+    from workloads import bf16_bits_to_f32, f32_to_bf16_bits
+    qn = bf16_bits_to_f32(f32_to_bf16_bits(qn)).reshape(qn.shape)
+    dp = batch.kvs.Problem(lens=p.n_out, budgets=p.n_out, group=G, window=1, head_dim=w.head_dim, dtype=w.dtype,
+                           n_sink=0, in_rows=p.out_rows)
+    from helpers import to_device
+    Qd = to_device(qn.reshape(len(acc), G, w.head_dim), w.dtype)
+    out = torch.empty((len(acc), G, w.head_dim), dtype=torch.float32, device="cuda")
+    ws = torch.empty(batch.kvs.kvs_decode_workspace_size(dp), dtype=torch.uint8, device="cuda")
+    batch.kvs.kvs_decode_attention(dp, Qd, batch.K_out, batch.V_out, batch.counts, out, ws, stream=batch.stream())
+    torch_sync()
+    got = out.cpu().numpy()
+    for i, a in enumerate(acc):
+        m = a.ref.merged
+        want = O.decode_attention(qn[i], m.K_out, m.V_out, m.counts)
+        err = np.linalg.norm(got[i] - want, axis=1) / np.linalg.norm(want, axis=1)
+        assert err.max() < 2e-2, err.max()       # the merged rows themselves carry the bf16 tolerance
