@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--no-per-layer-calls", action="store_true", help="skip the one-call-per-layer comparison loop")
     ap.add_argument("--key-rule", default="hessian", choices=["hessian", "diagonal", "mean"],
                     help="rule for the merged Key (the ablations run the same kernels)")
+    ap.add_argument("--decode", action="store_true",
+                    help="also time kvs_decode_attention (one new query per query head) over the merged caches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching from the host")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -293,6 +295,30 @@ def main():
                      "step": {"algorithmic_bytes_per_layer": step_bytes, "achieved": step_gbs,
                               "frac": step_gbs / HBM_PEAK_GBS}},
     }
+
+    if args.decode:
+        # the consumer: every query head's next query attends over its KV head's merged cache (K', V', counts)
+        dec = {}
+        t_ms, nbytes = 0.0, 0
+        reps = max(1, min(args.steps, 5))
+        for i, pr in enumerate(probs):
+            dp = kvs.Problem(lens=pr.n_out, budgets=pr.n_out, group=w.group, window=1, head_dim=D, dtype=w.dtype,
+                             n_sink=0, in_rows=pr.out_rows)
+            Qd = Qs[i][:, :w.group].contiguous()                     # [units, G, D]: one row per query head
+            out = torch.empty((dp.n_units, w.group, D), dtype=torch.float32, device=dev)
+            dws = torch.empty(kvs.kvs_decode_workspace_size(dp), dtype=torch.uint8, device=dev)
+            for rep in range(reps + 1):
+                if rep == 1:
+                    ev0.record()
+                kvs.kvs_decode_attention(dp, Qd, K_out[i], V_out[i], counts[i], out, dws, stream=stream)
+            ev1.record()
+            torch.cuda.synchronize()
+            t_ms += ev0.elapsed_time(ev1) / reps
+            nbytes += sum(pr.n_out) * (2 * D * b + 4) + dp.n_units * w.group * D * (b + 4)
+        result["decode_attention"] = {"ms": t_ms, "us_per_layer": t_ms * 1e3 / layers, "algorithmic_bytes": nbytes,
+                                      "achieved": nbytes / (t_ms * 1e-3) / 1e9, "unit": "GB/s",
+                                      "frac": nbytes / (t_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                      "query_rows_per_unit": w.group}
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)

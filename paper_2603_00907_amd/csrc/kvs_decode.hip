@@ -6,13 +6,15 @@
 //   o = sum_S exp(e_S) V'_S / sum_S c_S exp(e_S),      e_S = scale * q . k'_S,
 // i.e. ordinary attention over the c_S copies of every slot.  With c = 1 it is plain attention.
 //
-// Split over the rows of a unit like the o_bar pass (chunks of at least 1024 rows, one workgroup
-// each): LPR adjacent lanes read one K row and one V row (16 bytes each), four query rows at a time
+// Split over the rows of a unit (chunks of at least 512 rows, at most 64 per unit, one workgroup
+// each; the grid is chunks x units): LPR adjacent lanes read one K row and one V row (16 bytes each), four query rows at a time
 // sit in registers, every lane group keeps an online softmax (running maximum, denominator,
 // D-wide numerator) for its rows, the groups of a workgroup are combined through LDS, and a second
 // small kernel combines the chunks.  Everything is ordered: no atomics, results do not depend on
 // timing.  The kernel is meant for decode-sized query blocks (at most KVS_MAX_DECODE_ROWS rows per
 // unit); it reads the cache once per block of four query rows.
+#include <algorithm>
+
 #include "kvs_device.h"
 
 namespace kvs {
@@ -20,6 +22,22 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kQB = 4;                    // query rows per block
+constexpr int kUnroll = 2;                // cache rows per lane group in flight
+#ifndef KVS_DEC_CHUNK
+#define KVS_DEC_CHUNK 512
+#endif
+constexpr int kDecMinChunk = KVS_DEC_CHUNK;   // rows per workgroup, at least
+
+// Chunking of a unit's rows: a function of its length only.
+__host__ __device__ inline int dec_chunk_len(int len) {
+  const int per = (len + kMaxChunks - 1) / kMaxChunks;
+  const int rounded = (per + kWave - 1) / kWave * kWave;
+  return rounded > kDecMinChunk ? rounded : kDecMinChunk;
+}
+__host__ __device__ inline int dec_chunks(int len) {
+  const int cl = dec_chunk_len(len);
+  return (len + cl - 1) / cl;
+}
 
 // partial result of one (unit, chunk, query row): numerator[D], running maximum, denominator
 __device__ __forceinline__ size_t part_index(int unit_index, int chunk, int R, int row, int D) {
@@ -38,11 +56,10 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
   __shared__ float sm_acc[GROUPS][kQB][D];
   __shared__ float2 sm_ml[GROUPS][kQB];
 
-  int ui = 0;
-  while (ui + 1 < tab.n_units && tab.u[ui + 1].o_base <= (int)blockIdx.x) ++ui;
-  const Unit un = tab.u[ui];
-  const int chunk = blockIdx.x - un.o_base;
-  const int clen = obar_chunk_len(un.len);
+  const Unit un = tab.u[blockIdx.y];
+  const int chunk = blockIdx.x;
+  if (chunk >= dec_chunks(un.len)) return;               // the grid is as wide as the longest unit needs
+  const int clen = dec_chunk_len(un.len);
   const int t0 = chunk * clen;
   const int t1 = min(un.len, t0 + clen);
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
@@ -71,25 +88,45 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
       for (int i = 0; i < EPL; ++i) acc[j][i] = 0.f;
     }
 
-    for (int t = t0 + group; t < t1; t += GROUPS) {
-      float kf[EPL], vf[EPL];
-      Piece<T>::unpack(Kp[(size_t)t * LPR], kf);
-      Piece<T>::unpack(Vp[(size_t)t * LPR], vf);
-      const float c = cnt ? (float)cnt[t] : 1.f;
+    // kUnroll rows per lane group and trip, all their loads issued before the first use
+    for (int tb = t0 + group; tb < t1; tb += GROUPS * kUnroll) {
+      uint4 kraw[kUnroll], vraw[kUnroll];
+      float cc[kUnroll];
 #pragma unroll
-      for (int j = 0; j < kQB; ++j) {
-        float d = 0.f;
+      for (int u = 0; u < kUnroll; ++u) {
+        const int t = tb + u * GROUPS;
+        const int tc = min(t, t1 - 1);
+        kraw[u] = Kp[(size_t)tc * LPR];
+        vraw[u] = Vp[(size_t)tc * LPR];
+        cc[u] = cnt ? (float)cnt[tc] : 1.f;
+      }
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) d = fmaf(qf[j][i], kf[i], d);
-        const float s = row_group_sum<LPR>(d) * sh.scale_log2;
-        // online softmax, branch-free: the first row of a group meets m = -inf and corr = 0
-        const float m_new = fmaxf(m[j], s);
-        const float corr = __builtin_amdgcn_exp2f(m[j] - m_new);
-        const float p = __builtin_amdgcn_exp2f(s - m_new);
-        l[j] = fmaf(l[j], corr, c * p);                          // c copies of the slot in the denominator
+      for (int u = 0; u < kUnroll; ++u) {
+        if (tb + u * GROUPS >= t1) break;                        // uniform per lane group
+        float kf[EPL], vf[EPL];
+        Piece<T>::unpack(kraw[u], kf);
+        Piece<T>::unpack(vraw[u], vf);
+        const float c = cc[u];
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[j][i] = fmaf(acc[j][i], corr, p * vf[i]);
-        m[j] = m_new;
+        for (int j = 0; j < kQB; ++j) {
+          float d = 0.f;
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) d = fmaf(qf[j][i], kf[i], d);
+          const float s = row_group_sum<LPR>(d) * sh.scale_log2;
+          // online softmax; the running maximum rises only a few times per lane group, so the rescale of
+          // the numerator stays out of the common path (the first row meets m = -inf: corr = 0)
+          if (s > m[j]) {
+            const float corr = __builtin_amdgcn_exp2f(m[j] - s);
+            l[j] *= corr;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[j][i] *= corr;
+            m[j] = s;
+          }
+          const float p = __builtin_amdgcn_exp2f(s - m[j]);
+          l[j] = fmaf(c, p, l[j]);                               // c copies of the slot in the denominator
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) acc[j][i] = fmaf(p, vf[i], acc[j][i]);
+        }
       }
     }
 
@@ -133,7 +170,7 @@ __global__ __launch_bounds__(D) void decode_reduce_kernel(const UnitTable tab, c
   const int R = sh.R;
   const Unit un = tab.u[blockIdx.x / R];
   const int row = blockIdx.x % R;
-  const int nc = obar_chunks(un.len);
+  const int nc = dec_chunks(un.len);
   const int d = threadIdx.x;
   float M = -INFINITY;
   for (int c = 0; c < nc; ++c) M = fmaxf(M, part[part_index(un.index, c, R, row, D) + D]);
@@ -152,7 +189,9 @@ __global__ __launch_bounds__(D) void decode_reduce_kernel(const UnitTable tab, c
 template <typename T, int D>
 hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
                     const int32_t* counts, float* part, float* out, hipStream_t stream) {
-  hipLaunchKernelGGL((decode_partial_kernel<T, D>), dim3(tab.total_ochunks), dim3(kThreads), 0, stream, tab, sh,
+  int widest = 1;
+  for (int i = 0; i < tab.n_units; ++i) widest = std::max(widest, dec_chunks(tab.u[i].len));
+  hipLaunchKernelGGL((decode_partial_kernel<T, D>), dim3(widest, tab.n_units), dim3(kThreads), 0, stream, tab, sh,
                      (const T*)Q, (const T*)K, (const T*)V, counts, part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
