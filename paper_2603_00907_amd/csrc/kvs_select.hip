@@ -51,13 +51,6 @@ struct SelectSmem {
   int ncand;
 };
 
-// Adds one to hist[d] for every active lane.  (Peeling groups of equal digits off with ballots before
-// the atomics was measured and is slower than letting the LDS serialise equal addresses.)
-__device__ __forceinline__ void hist_add(int* hist, uint32_t d, bool act, int lane) {
-  (void)lane;
-  if (act) atomicAdd(&hist[d], 1);
-}
-
 // Inclusive prefix sum over the 64 lanes with DPP moves only (no LDS crossbar): four shifts inside
 // every row of 16 lanes, then the last lane of row 0 / row 2 is broadcast into the next row, then
 // lane 31 into the upper half.
