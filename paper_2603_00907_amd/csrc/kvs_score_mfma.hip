@@ -2,26 +2,28 @@
 //
 // Two sweeps over K (Sec. 4.1, Eq. attn_def_vec: logits, softmax over all cached Keys, here
 // averaged over the unit's query rows): sweep 0 leaves per-chunk softmax statistics (running
-// maximum and sum of exponentials, base-2 domain), sweep 1 recomputes the logits, normalises them
-// with the unit-wide statistics and writes alpha_bar.  (o_bar is accumulated by a separate
-// streaming pass over V, see kvs_select.hip.)
+// maximum and sum of exponentials, base-2 domain), a small kernel reduces them to one normaliser
+// per query row and unit, sweep 1 recomputes the logits, normalises them and writes alpha_bar.
+// (o_bar is accumulated by a separate streaming pass over V, see kvs_select.hip.)
 //
 // The logit tile is computed transposed, S^T[token, query] = K_tile * Q^T, with
 // v_mfma_f32_32x32x16_bf16: the A operand is a 32-token tile of K, the B operand a block of
-// 32 query rows.  The Q block of a wavefront (32*NT rows, NT <= 4) stays in registers for the whole
-// sweep.  K streams from HBM straight into LDS (global_load_lds_dwordx4: 16 lanes fetch one
-// 256-byte row, every instruction four whole rows) into a wavefront-private 8 KB tile; the 16-byte
-// pieces of a row are stored XOR-swizzled by the row number so that the operand reads
-// (ds_read_b128, 32 rows at the same piece) spread over all banks.  Once the operands of a tile
-// sit in registers the same LDS tile is refilled with the wavefront's next tile, which flies while
-// the MFMAs and the softmax arithmetic of the current tile run; wavefronts never wait for each
-// other inside the sweep.  In the accumulator a lane holds ONE query column and 16 token rows, so
-// the running softmax statistics are lane-private (NT pairs per lane); the sum over queries of
-// sweep 1 is a 16-value reduce-scatter over 32 lanes (16 shuffles per tile).
+// 32 query rows.  K streams from HBM straight into LDS (global_load_lds_dwordx4: 16 lanes fetch
+// one 256-byte row, every instruction four whole rows) into a wavefront-private 8 KB tile; the
+// 16-byte pieces of a row are stored XOR-swizzled by the row number so that the operand reads
+// (ds_read_b128, 32 rows at the same piece) spread over all banks.  Wavefronts never wait for
+// each other inside a sweep unless they share query rows.  In the accumulator a lane holds ONE
+// query column and 16 token rows, so the running softmax statistics are lane-private; the sum
+// over queries of sweep 1 is a 16-value reduce-scatter over 32 lanes (16 shuffles per tile).
 //
-// A workgroup has four wavefronts.  Up to 128 query rows every wavefront holds all of them (WQ = 1)
-// and the four split the chunk's tiles.  Above that, WQ of them split the query rows of a pass
-// and share tiles; then alpha_bar is combined through LDS with a workgroup barrier per tile.
+// A workgroup has four wavefronts that split the chunk's tiles.  Two kernels:
+//   score_mfma_kernel       up to 64 query rows per wavefront, all register-stationary, two tile
+//                           buffers per wavefront.  Windows of at most 64 rows (WQ = 1); windows above
+//                           128 rows, where WQ wavefronts split the rows of a pass, share tiles and
+//                           combine alpha_bar through LDS with a workgroup barrier per tile.
+//   score_mfma_wide_kernel  65..128 rows in one pass: half of the rows register-stationary, the other
+//                           half re-read from an LDS copy of the Q block for every tile.
+// Rows of an already merged cache (cardinalities c given) enter with log2(c) added to the logit.
 #include "kvs_device.h"
 
 namespace kvs {

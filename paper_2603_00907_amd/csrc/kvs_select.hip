@@ -9,11 +9,13 @@
 // selected in one parallel step (Sec. 3.1), ties going to the lower index; consecutive selected
 // edges chain into one output slot.  One workgroup of 1024 threads per unit.  Scores are
 // non-negative floats, so their bit patterns order like unsigned integers: an MSB-first radix
-// select (11 + 11 + 10 bits, LDS histograms) finds the r-th smallest key T and how many keys equal
-// to T are still wanted; a final pass in index order takes every key below T and the first `want`
-// keys equal to T, and turns the selection into the slot map with wavefront ballots and a scan
-// over the 16 wavefronts.  Keys of units up to kLdsKeys edges are kept in LDS between the passes;
-// longer units recompute them from alpha_bar (L2-resident).
+// select (11 + 11 + 10 bits, LDS histograms; the keys stretched to their full span first, the
+// digits after the first settled on a short list) finds the r-th smallest key T and how many
+// keys equal to T are still wanted; a final pass in index order takes every key below T and the
+// first `want` keys equal to T, and turns the selection into the slot map with DPP prefix scans
+// and a scan over the 16 wavefronts.  Keys of units up to kLdsKeys edges are kept in LDS between
+// the passes; longer units recompute them from alpha_bar (L2-resident) in every pass with the
+// plain IEEE digits.
 //
 // o_bar pass, per chunk of a unit: rows of V are read by LPR adjacent lanes (16 bytes each), scaled
 // by alpha_bar[t] and summed per lane, then over the workgroup; the chunk's sum goes to the
