@@ -48,6 +48,13 @@ coupling buys): `rule="diagonal"` drops the coupling blocks (C_t := 0, the diago
 paper calls overlooked coupling), `rule="mean"` is the plain arithmetic mean of the run (over the tokens
 the rows stand for).  Values, cardinalities and the partition are the same for every rule.
 
+Per-query aggregation (an alternative to averaging the rows' attention first): Sec. 4 derives the
+vectors c_tt, c_{t,t+1} for ONE query.  `per_query_norms` keeps every query row q of the window apart,
+with its own alpha^{(q)} and its own output o^{(q)}, and averages the NORMS over the rows:
+A_t = mean_q ||c_tt^{(q)}||, C_t = mean_q ||c_{t,t+1}^{(q)}||; `merge_compact(..., norms=(A, C))` then
+uses them in the same weight form.  With one row it is the plain rule.  The partition still comes from
+alpha_bar.
+
 Readings of points the paper leaves open (many query rows, ranking score, runs
 longer than two, a non-positive denominator) are this module's and are listed
 in the repository's design notes.
@@ -168,6 +175,23 @@ def token_and_edge_norms(alpha_bar: np.ndarray, V: np.ndarray, o_bar: np.ndarray
     return A, C
 
 
+def per_query_norms(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: Optional[float] = None):
+    """A_t and C_t with every query row kept apart: row q has its own attention alpha^{(q)} (Eq. attn_def_vec)
+    and its own output o^{(q)}; the vectors of Eqs. c11_def-c12_def are formed per row and their norms are
+    averaged over the rows.  Q [R, D] (or [G, W, D]), K, V [n, D]; returns A [n], C [n - 1]."""
+    V = np.asarray(V, dtype=F64)
+    alpha = attention_rows(Q, K, scale)
+    R, n = alpha.shape
+    A = np.zeros(n, dtype=F64)
+    C = np.zeros(max(n - 1, 0), dtype=F64)
+    for q in range(R):
+        o_q = alpha[q] @ V                                  # this row's attention output
+        A_q, C_q = token_and_edge_norms(alpha[q], V, o_q)
+        A += A_q
+        C += C_q
+    return A / R, C / R
+
+
 @dataclass
 class MergeResult:
     K_out: np.ndarray        # [n_out, D] fp64
@@ -184,13 +208,19 @@ RULES = ("hessian", "diagonal", "mean")
 
 def merge_compact(K: np.ndarray, V: np.ndarray, alpha_bar: np.ndarray, o_bar: np.ndarray,
                   mask: np.ndarray, slot: np.ndarray, counts_in: Optional[np.ndarray] = None,
-                  rule: str = "hessian") -> MergeResult:
+                  rule: str = "hessian", norms=None) -> MergeResult:
+    """`norms = (A, C)` replaces the norms computed from alpha_bar and o_bar (per-query aggregation);
+    alpha_bar and o_bar are then not used."""
     assert rule in RULES
     K = np.asarray(K, dtype=F64)
     V = np.asarray(V, dtype=F64)
     n, D = K.shape
     c_in = np.ones(n, dtype=np.int64) if counts_in is None else np.asarray(counts_in, dtype=np.int64)
-    A, C = token_and_edge_norms(alpha_bar, V, o_bar, counts_in)
+    if norms is None:
+        A, C = token_and_edge_norms(alpha_bar, V, o_bar, counts_in)
+    else:
+        assert counts_in is None
+        A, C = (np.asarray(x, dtype=F64) for x in norms)
     n_out = int(slot[-1]) + 1 if n else 0
     K_out = np.zeros((n_out, D), dtype=F64)
     V_out = np.zeros((n_out, V.shape[1]), dtype=F64)
@@ -256,10 +286,11 @@ class StepResult:
 
 def step(Q: np.ndarray, K: np.ndarray, V: np.ndarray, budget: int, n_sink: int = 32,
          n_recent: int = 0, scale: Optional[float] = None, counts: Optional[np.ndarray] = None,
-         rule: str = "hessian") -> StepResult:
+         rule: str = "hessian", per_query: bool = False) -> StepResult:
     alpha_bar, o_bar = score(Q, K, V, scale, counts)
     mask, slot = select(alpha_bar, budget, n_sink, n_recent)
-    merged = merge_compact(K, V, alpha_bar, o_bar, mask, slot, counts, rule)
+    norms = per_query_norms(Q, K, V, scale) if per_query else None
+    merged = merge_compact(K, V, alpha_bar, o_bar, mask, slot, counts, rule, norms)
     return StepResult(alpha_bar, o_bar, mask, slot, merged)
 
 

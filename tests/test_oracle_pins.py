@@ -598,3 +598,96 @@ def test_decode_attention_over_a_merged_cache_is_attention_over_the_tokens_it_st
     np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-14)
     plain = O.decode_attention(Q, K, V)
     np.testing.assert_allclose(plain, np.stack([softmax_attention(q, K, V)[1] for q in Q.reshape(-1, d)]), rtol=1e-12)
+
+
+# --------------------------------------------------------------------------------------------
+# per-query aggregation: every query row keeps its own attention and output; the norms are averaged
+def test_per_query_norms_are_the_mean_of_single_query_finite_difference_norms():
+    """Each row q by itself is the paper's single-query case: its blocks d s_i / d e_j come from central
+    differences of textbook attention (nothing of the oracle), and the aggregate is their norms' mean."""
+    rng = np.random.default_rng(60)
+    n, d, dv, R = 6, 4, 5, 3
+    Q = rng.standard_normal((R, d)) * 1.5
+    K = rng.standard_normal((n, d)) * 1.5
+    V = rng.standard_normal((n, dv))
+    A_want = np.zeros(n)
+    C_want = np.zeros(n - 1)
+    for q in Q:
+        J = fd_ds_de(q, K, V)
+        A_want += [np.linalg.norm(J[i, i]) for i in range(n)]
+        C_want += [np.linalg.norm(J[i, i + 1]) for i in range(n - 1)]
+    A, C = O.per_query_norms(Q, K, V)
+    np.testing.assert_allclose(A, A_want / R, rtol=1e-7)
+    np.testing.assert_allclose(C, C_want / R, rtol=1e-7)
+
+
+def test_per_query_norms_special_cases():
+    rng = np.random.default_rng(61)
+    n, d = 40, 8
+    K = rng.standard_normal((n, d)) * 2.0
+    V = rng.standard_normal((n, d))
+    q = rng.standard_normal(d)
+    # identical rows: every row has the mean attention and the mean output, the two aggregations agree
+    Q = np.tile(q, (5, 1))
+    ab, ob = O.score(Q, K, V)
+    A0, C0 = O.token_and_edge_norms(ab, V, ob)
+    A, C = O.per_query_norms(Q, K, V)
+    np.testing.assert_allclose(A, A0, rtol=1e-12)
+    np.testing.assert_allclose(C, C0, rtol=1e-12)
+    # the order of the rows does not matter; [G, W, D] is read as G*W rows
+    Q = rng.standard_normal((2, 3, d))
+    A1, C1 = O.per_query_norms(Q, K, V)
+    A2, C2 = O.per_query_norms(Q.reshape(6, d)[::-1], K, V)
+    np.testing.assert_allclose(A1, A2, rtol=1e-13)
+    np.testing.assert_allclose(C1, C2, rtol=1e-13)
+    # rows that disagree: the aggregate differs from the mean-first norms (the mode is not a no-op)
+    ab, ob = O.score(Q, K, V)
+    A0, _ = O.token_and_edge_norms(ab, V, ob)
+    assert np.max(np.abs(A1 - A0) / A0) > 1e-3
+
+
+@pytest.mark.parametrize("seed,L", [(62, 2), (63, 3)])
+def test_per_query_merged_key_minimises_the_summed_surrogate(seed, L):
+    """With norms=(A, C) the merged Key of a run minimises, along q-independent weights, the surrogate
+    sum_ab g_ab (k - k_a).(k - k_b)-type objective whose blocks are the AVERAGED norms: the stationary point
+    is K' = sum_a w_a k_a with w_a = sum_b g_ab / sum_ab g_ab, g_tt = A_t, g_{t,t+1} = -C_t, written here as
+    a dense solve."""
+    rng = np.random.default_rng(seed)
+    n, d, R = L + 3, 4, 4
+    Q = rng.standard_normal((R, d)) * 0.3
+    K = rng.standard_normal((n, d))
+    V = rng.standard_normal((n, d))
+    mask = np.zeros(n, dtype=np.uint8)
+    t0 = 1
+    mask[t0:t0 + L - 1] = 1
+    starts = np.ones(n, dtype=np.int64)
+    starts[1:] = 1 - mask[:-1]
+    slot = (np.cumsum(starts) - 1).astype(np.int32)
+    A, C = O.per_query_norms(Q, K, V)
+    ab, ob = O.score(Q, K, V)
+    res = O.merge_compact(K, V, ab, ob, mask, slot, norms=(A, C))
+    G = np.diag(A[t0:t0 + L])
+    for i in range(L - 1):
+        G[i, i + 1] = G[i + 1, i] = -C[t0 + i]
+    w = G.sum(axis=1) / G.sum()
+    assert G.sum() > 0
+    np.testing.assert_allclose(res.K_out[t0], w @ K[t0:t0 + L], rtol=1e-12)
+    # the other rows and all Values do not depend on the aggregation
+    base = O.merge_compact(K, V, ab, ob, mask, slot)
+    np.testing.assert_array_equal(res.V_out, base.V_out)
+    np.testing.assert_array_equal(res.counts, base.counts)
+    keep = np.ones(res.K_out.shape[0], dtype=bool)
+    keep[t0] = False
+    np.testing.assert_array_equal(res.K_out[keep], base.K_out[keep])
+
+
+def test_step_per_query_with_one_row_is_the_plain_step():
+    rng = np.random.default_rng(64)
+    n, d = 96, 8
+    Q = rng.standard_normal((1, d))
+    K = rng.standard_normal((n, d)) * 2
+    V = rng.standard_normal((n, d))
+    a = O.step(Q, K, V, 48, n_sink=4)
+    b = O.step(Q, K, V, 48, n_sink=4, per_query=True)
+    np.testing.assert_array_equal(a.mask, b.mask)
+    np.testing.assert_allclose(a.merged.K_out, b.merged.K_out, rtol=1e-11, atol=1e-13)
