@@ -41,7 +41,7 @@
 extern "C" {
 #endif
 
-#define KVS_VERSION 200          /* major*10000 + minor*100 + patch */
+#define KVS_VERSION 300          /* major*10000 + minor*100 + patch */
 #define KVS_MAX_Q_ROWS 1024      /* largest supported G*W */
 #define KVS_MAX_DECODE_ROWS 64   /* largest G*W of kvs_decode_attention */
 #define KVS_MAX_LEN (1 << 22)    /* largest supported cache length of one unit, in tokens */
@@ -50,7 +50,7 @@ typedef enum {
   KVS_OK = 0,
   KVS_ERR_INVALID_ARG = 1,  /* null pointer, misaligned pointer, non-positive size, head_dim not 64/128,
                                G*W above KVS_MAX_Q_ROWS, overlapping units, unknown key_rule */
-  KVS_ERR_DTYPE = 2,        /* io_dtype is neither KVS_F32 nor KVS_BF16 */
+  KVS_ERR_DTYPE = 2,        /* io_dtype is neither KVS_F32 nor KVS_BF16, or not the one the call supports */
   KVS_ERR_BUDGET = 3,       /* budget < n_sink + 1 + n_recent for a unit that has to merge (len > budget),
                                or budget < 1 */
   KVS_ERR_WORKSPACE = 4,    /* workspace null, misaligned (256 B) or smaller than kvs_workspace_size() */
@@ -167,6 +167,40 @@ kvs_status kvs_decode_workspace_size(const kvs_problem* p, size_t* bytes);
 kvs_status kvs_decode_attention(const kvs_problem* p, const void* Q, const void* K, const void* V,
                                 const int32_t* counts, float* out,
                                 void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Per-query aggregation: an alternative to averaging the query rows' attention before the Key rule.
+ * Sec. 4 derives c_tt = alpha_t (1 - 2 alpha_t)(v_t - o) and c_{t,t+1} = -alpha_t alpha_{t+1}(v_t + v_{t+1} - 2o)
+ * (Eqs. c11_def-c12_def) for one query.  Here every query row q of the unit keeps its own attention
+ * alpha^{(q)} = softmax_t(scale * Q[q].K[t]) and its own output o^{(q)} = sum_t alpha^{(q)}_t V[t] (Eq.
+ * attn_def_vec), and the norms are averaged over the G*W rows:
+ *   A_t = mean_q alpha^{(q)}_t |1 - 2 alpha^{(q)}_t| ||v_t - o^{(q)}||
+ *   C_t = mean_q alpha^{(q)}_t alpha^{(q)}_{t+1} ||v_t + v_{t+1} - 2 o^{(q)}||      (edge t, t+1)
+ * kvs_merge_compact_norms is kvs_merge_compact with these A and C in u_t = A_t - C_{t-1} - C_t (Eq.
+ * kstar_final); Values, cardinalities, key_rule and the fallback are as there.  The partition still comes from
+ * kvs_select on alpha_bar.  With one query row the results are those of the calls above.
+ * Restrictions: io_dtype KVS_BF16 (KVS_ERR_DTYPE otherwise), every unit at least 32 rows
+ * (KVS_ERR_INVALID_ARG), plain tokens only (no input cardinalities).  kvs_merge_compact_norms takes both dtypes
+ * and any length.
+ *   alpha_bar DEVICE out [rows] fp32, as from kvs_score
+ *   a_tok     DEVICE out / in [rows] fp32: A_t
+ *   c_edge    DEVICE out / in [rows] fp32: C_t; the entry of a unit's last row is 0 and never read
+ *   ws        DEVICE workspace of kvs_per_query_workspace_size(p) bytes, 256-byte aligned (kvs_sensitivity,
+ *             kvs_step_per_query; kvs_merge_compact_norms uses none)
+ * All other arguments, layouts, ownership and error behaviour are those of kvs_score, kvs_merge_compact and
+ * kvs_step.                                                                                                   */
+kvs_status kvs_per_query_workspace_size(const kvs_problem* p, size_t* bytes);
+kvs_status kvs_sensitivity(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                           float* alpha_bar, float* a_tok, float* c_edge,
+                           void* ws, size_t ws_bytes, void* hip_stream);
+kvs_status kvs_merge_compact_norms(const kvs_problem* p, const void* K, const void* V,
+                                   const float* a_tok, const float* c_edge,
+                                   const uint8_t* edge_mask, const int32_t* slot_of_token,
+                                   void* K_out, void* V_out, int32_t* counts_out,
+                                   void* ws, size_t ws_bytes, void* hip_stream);
+kvs_status kvs_step_per_query(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                              void* K_out, void* V_out, int32_t* counts_out,
+                              int32_t* slot_of_token_out, uint8_t* edge_mask_out,
+                              void* ws, size_t ws_bytes, void* hip_stream);
 
 const char* kvs_status_str(kvs_status s);
 int kvs_version(void);

@@ -23,11 +23,15 @@ from .binding import (  # noqa: F401
     kvs_decode_workspace_size,
     kvs_merge_compact,
     kvs_merge_compact_counts,
+    kvs_merge_compact_norms,
+    kvs_per_query_workspace_size,
     kvs_score,
     kvs_score_counts,
     kvs_select,
+    kvs_sensitivity,
     kvs_step,
     kvs_step_counts,
+    kvs_step_per_query,
     kvs_version,
     kvs_workspace_size,
     load_library,

@@ -22,7 +22,8 @@ DTYPES = {"f32": KVS_F32, "bf16": KVS_BF16}
 
 EXPORTS = ["kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step",
            "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_decode_workspace_size",
-           "kvs_decode_attention", "kvs_status_str", "kvs_version"]
+           "kvs_decode_attention", "kvs_per_query_workspace_size", "kvs_sensitivity", "kvs_merge_compact_norms",
+           "kvs_step_per_query", "kvs_status_str", "kvs_version"]
 
 
 KEY_RULES = {"hessian": 0, "diagonal": 1, "mean": 2}
@@ -75,9 +76,14 @@ def load_library(path: Optional[str] = None):
     lib.kvs_step_counts.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_decode_workspace_size.argtypes = [P, C.POINTER(sz)]
     lib.kvs_decode_attention.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_per_query_workspace_size.argtypes = [P, C.POINTER(sz)]
+    lib.kvs_sensitivity.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_merge_compact_norms.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_step_per_query.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     for name in ("kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step",
                  "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_decode_workspace_size",
-                 "kvs_decode_attention"):
+                 "kvs_decode_attention", "kvs_per_query_workspace_size", "kvs_sensitivity",
+                 "kvs_merge_compact_norms", "kvs_step_per_query"):
         getattr(lib, name).restype = C.c_int
     lib.kvs_status_str.argtypes = [C.c_int]
     lib.kvs_status_str.restype = C.c_char_p
@@ -219,3 +225,32 @@ def kvs_decode_attention(problem: Problem, Q, K, V, counts, out, ws, stream: int
     _check(load_library().kvs_decode_attention(
         problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(counts), _ptr(out), _ptr(ws),
         _nbytes(ws) if ws_bytes is None else ws_bytes, stream), "kvs_decode_attention")
+
+
+def kvs_per_query_workspace_size(problem: Problem) -> int:
+    out = C.c_size_t(0)
+    _check(load_library().kvs_per_query_workspace_size(problem.ref, C.byref(out)), "kvs_per_query_workspace_size")
+    return int(out.value)
+
+
+def kvs_sensitivity(problem: Problem, Q, K, V, alpha_bar, a_tok, c_edge, ws, stream: int = 0,
+                    ws_bytes: Optional[int] = None):
+    _check(load_library().kvs_sensitivity(
+        problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(alpha_bar), _ptr(a_tok), _ptr(c_edge), _ptr(ws),
+        _nbytes(ws) if ws_bytes is None else ws_bytes, stream), "kvs_sensitivity")
+
+
+def kvs_merge_compact_norms(problem: Problem, K, V, a_tok, c_edge, edge_mask, slot_of_token, K_out, V_out,
+                            counts_out, ws=None, stream: int = 0):
+    _check(load_library().kvs_merge_compact_norms(
+        problem.ref, _ptr(K), _ptr(V), _ptr(a_tok), _ptr(c_edge), _ptr(edge_mask), _ptr(slot_of_token),
+        _ptr(K_out), _ptr(V_out), _ptr(counts_out), _ptr(ws), _nbytes(ws) if ws is not None else 0, stream),
+        "kvs_merge_compact_norms")
+
+
+def kvs_step_per_query(problem: Problem, Q, K, V, K_out, V_out, counts_out, ws, slot_of_token_out=None,
+                       edge_mask_out=None, stream: int = 0, ws_bytes: Optional[int] = None):
+    _check(load_library().kvs_step_per_query(
+        problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out), _ptr(counts_out),
+        _ptr(slot_of_token_out), _ptr(edge_mask_out), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
+        stream), "kvs_step_per_query")

@@ -126,6 +126,52 @@ Workspace carve(const Plan& plan, void* base) {
   return w;
 }
 
+// Extra workspace of the per-query aggregation, laid out behind the ordinary one.
+struct PerQueryWs {
+  float* o_part;     // [largest launch's chunks][R][D]
+  uint16_t* o_hi;    // [n_units][R][D]
+  uint16_t* o_lo;
+  float* oo;         // [n_units][R]
+  float* a_tok;      // [rows]  (kvs_step_per_query only)
+  float* c_edge;     // [rows]
+  size_t bytes;      // ordinary workspace included
+};
+
+PerQueryWs carve_per_query(const Plan& plan, void* base, Workspace* w) {
+  *w = carve(plan, base);
+  PerQueryWs q{};
+  size_t off = w->bytes;
+  auto take = [&](size_t bytes) {
+    char* ptr = base ? (char*)base + off : nullptr;
+    off += align_up(bytes);
+    return (void*)ptr;
+  };
+  long long max_chunks = 0;
+  for (int first = 0; first < plan.n_units; first += kMaxUnitsPerLaunch) {
+    long long c = 0;
+    for (int u = first; u < std::min(plan.n_units, first + kMaxUnitsPerLaunch); ++u) c += plan.units[u].n_chunks;
+    max_chunks = std::max(max_chunks, c);
+  }
+  const size_t rd = (size_t)plan.shape.R * plan.shape.D;
+  q.o_part = (float*)take((size_t)max_chunks * rd * sizeof(float));
+  q.o_hi = (uint16_t*)take((size_t)plan.n_units * rd * sizeof(uint16_t));
+  q.o_lo = (uint16_t*)take((size_t)plan.n_units * rd * sizeof(uint16_t));
+  q.oo = (float*)take((size_t)plan.n_units * plan.shape.R * sizeof(float));
+  q.a_tok = (float*)take((size_t)plan.rows_in * sizeof(float));
+  q.c_edge = (float*)take((size_t)plan.rows_in * sizeof(float));
+  q.bytes = off;
+  return q;
+}
+
+// The per-query kernels are bf16 MFMA kernels whose tiles hold 32 whole rows of a unit.
+kvs_status check_per_query(const Plan& plan) {
+  if (plan.dtype != KVS_BF16) return KVS_ERR_DTYPE;
+  for (const Unit& un : plan.units) {
+    if (un.len < 32) return KVS_ERR_INVALID_ARG;
+  }
+  return KVS_OK;
+}
+
 struct Range {
   const void* p;
   size_t bytes;
@@ -348,6 +394,110 @@ kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, c
     if (e != hipSuccess) return e;
     return launch_merge(tab, sh, plan.dtype, K, V, counts_in, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,
                         V_out, counts_out, s);
+  });
+}
+
+kvs_status kvs_per_query_workspace_size(const kvs_problem* p, size_t* bytes) {
+  if (bytes == nullptr) return KVS_ERR_INVALID_ARG;
+  Plan plan;
+  kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  if ((st = check_per_query(plan)) != KVS_OK) return st;
+  Workspace w;
+  *bytes = carve_per_query(plan, nullptr, &w).bytes;
+  return KVS_OK;
+}
+
+kvs_status kvs_sensitivity(const kvs_problem* p, const void* Q, const void* K, const void* V, float* alpha_bar,
+                           float* a_tok, float* c_edge, void* ws, size_t ws_bytes, void* hip_stream) {
+  Plan plan;
+  kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  if ((st = check_per_query(plan)) != KVS_OK) return st;
+  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0) return KVS_ERR_WORKSPACE;
+  Workspace w;
+  const PerQueryWs q = carve_per_query(plan, ws, &w);
+  if (ws_bytes < q.bytes) return KVS_ERR_WORKSPACE;
+  const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
+  const size_t rows4 = (size_t)plan.rows_in * 4;
+  st = check_ranges({{Q, (size_t)plan.n_units * plan.shape.R * plan.shape.D * plan.elt, false},
+                     {K, kv, false},
+                     {V, kv, false},
+                     {alpha_bar, rows4, true},
+                     {a_tok, rows4, true},
+                     {c_edge, rows4, true},
+                     {ws, q.bytes, true}});
+  if (st != KVS_OK) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, nullptr, alpha_bar, w, s);
+    if (e != hipSuccess) return e;
+    return launch_per_query_norms(tab, sh, Q, K, V, w.c_row, q.o_part, q.o_hi, q.o_lo, q.oo, a_tok, c_edge, s);
+  });
+}
+
+kvs_status kvs_merge_compact_norms(const kvs_problem* p, const void* K, const void* V, const float* a_tok,
+                                   const float* c_edge, const uint8_t* edge_mask, const int32_t* slot_of_token,
+                                   void* K_out, void* V_out, int32_t* counts_out, void* ws, size_t ws_bytes,
+                                   void* hip_stream) {
+  (void)ws;
+  (void)ws_bytes;
+  Plan plan;
+  kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
+  const size_t kvo = (size_t)plan.rows_out * plan.shape.D * plan.elt;
+  st = check_ranges({{K, kv, false},
+                     {V, kv, false},
+                     {a_tok, (size_t)plan.rows_in * 4, false},
+                     {c_edge, (size_t)plan.rows_in * 4, false},
+                     {edge_mask, (size_t)plan.rows_in, false},
+                     {slot_of_token, (size_t)plan.rows_in * 4, false},
+                     {K_out, kvo, true},
+                     {V_out, kvo, true},
+                     {counts_out, (size_t)plan.rows_out * 4, true}});
+  if (st != KVS_OK) return st;
+  hipStream_t s = (hipStream_t)hip_stream;
+  return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
+    return launch_merge_norms(tab, sh, plan.dtype, K, V, a_tok, c_edge, edge_mask, slot_of_token, K_out, V_out,
+                              counts_out, s);
+  });
+}
+
+kvs_status kvs_step_per_query(const kvs_problem* p, const void* Q, const void* K, const void* V, void* K_out,
+                              void* V_out, int32_t* counts_out, int32_t* slot_of_token_out, uint8_t* edge_mask_out,
+                              void* ws, size_t ws_bytes, void* hip_stream) {
+  Plan plan;
+  kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  if ((st = check_per_query(plan)) != KVS_OK) return st;
+  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0) return KVS_ERR_WORKSPACE;
+  Workspace w;
+  const PerQueryWs q = carve_per_query(plan, ws, &w);
+  if (ws_bytes < q.bytes) return KVS_ERR_WORKSPACE;
+  const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
+  const size_t kvo = (size_t)plan.rows_out * plan.shape.D * plan.elt;
+  std::vector<Range> rs = {{Q, (size_t)plan.n_units * plan.shape.R * plan.shape.D * plan.elt, false},
+                           {K, kv, false},
+                           {V, kv, false},
+                           {K_out, kvo, true},
+                           {V_out, kvo, true},
+                           {counts_out, (size_t)plan.rows_out * 4, true},
+                           {ws, q.bytes, true}};
+  if (slot_of_token_out) rs.push_back({slot_of_token_out, (size_t)plan.rows_in * 4, true});
+  if (edge_mask_out) rs.push_back({edge_mask_out, (size_t)plan.rows_in, true});
+  if ((st = check_ranges(rs)) != KVS_OK) return st;
+  uint8_t* mask = edge_mask_out ? edge_mask_out : w.edge_mask;
+  int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
+  hipStream_t s = (hipStream_t)hip_stream;
+  return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, nullptr, w.alpha_bar, w, s);
+    if (e != hipSuccess) return e;
+    e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, nullptr, nullptr, nullptr, s);
+    if (e != hipSuccess) return e;
+    e = launch_per_query_norms(tab, sh, Q, K, V, w.c_row, q.o_part, q.o_hi, q.o_lo, q.oo, q.a_tok, q.c_edge, s);
+    if (e != hipSuccess) return e;
+    return launch_merge_norms(tab, sh, plan.dtype, K, V, q.a_tok, q.c_edge, mask, slot, K_out, V_out, counts_out, s);
   });
 }
 

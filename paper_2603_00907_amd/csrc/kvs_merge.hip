@@ -16,6 +16,10 @@
 // up to V[t] (Sec. 3.1, streaming regime): r_t = V[t] / c_t - o_bar, counts[S] = sum c_t, the fallback is
 // the mean over the tokens the rows stand for; everything else is unchanged.
 //
+// NORMS: A_t and C_t are not formed from alpha_bar and o_bar but read from two arrays (per-query
+// aggregation: every query row with its own attention and output, the norms averaged over the rows);
+// the weight form, the Values and the cardinalities are the same.
+//
 // Work split.  A workgroup is responsible for the slots that BEGIN in its nominal range of
 // kMergeTokens tokens: its real range [A, B) runs from the first slot start at or after the
 // nominal begin to the first slot start at or after the nominal end, so it owns whole slots and
@@ -61,10 +65,12 @@ __device__ __forceinline__ int first_slot_start(const uint8_t* __restrict__ mk, 
   }
 }
 
-template <typename T, int D, bool STREAM, bool COUNTS>
+// NORMS: `alpha_bar` holds A_t and `c_edge` C_t (o_bar and o_part are not used); otherwise c_edge is not used.
+template <typename T, int D, bool STREAM, bool COUNTS, bool NORMS>
 __global__ __launch_bounds__(kThreads) void merge_kernel(
     const UnitTable tab, const Shape sh, const T* __restrict__ K, const T* __restrict__ V,
     const int32_t* __restrict__ counts_in, const float* __restrict__ alpha_bar, const float* __restrict__ o_bar, const float* __restrict__ o_part,
+    const float* __restrict__ c_edge,
     const uint8_t* __restrict__ edge_mask, const int32_t* __restrict__ slot, T* __restrict__ K_out,
     T* __restrict__ V_out, int32_t* __restrict__ counts) {
   constexpr int EPL = Piece<T>::N;
@@ -98,7 +104,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   constexpr int PARTS = kThreads / D;          // threads per channel when adding up the chunk sums
   constexpr int PER = kMaxChunks / PARTS;
   float part_sum = 0.f;
-  if (o_bar == nullptr) {
+  if (!NORMS && o_bar == nullptr) {
     const int nc = obar_chunks(un.len);
     const int d = tid % D, h = tid / D;
     float v[PER];
@@ -157,6 +163,8 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   auto v_row = [&](int t) { return load_row(Vb, t); };
   int32_t* cnt = counts + un.out_row;
   const float* al = alpha_bar + un.in_row;
+  const float* ce = NORMS ? c_edge + un.in_row : nullptr;
+  auto cedge_at = [&](int t) { return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(ce) + (uint32_t)t * 4u); };
   const int32_t* sl = slot + un.in_row;
   auto alpha_at = [&](int t) { return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(al) + (uint32_t)t * 4u); };
   auto mask_at = [&](int t) { return *(mk + (uint32_t)t); };
@@ -168,7 +176,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 #pragma unroll
   for (int i = 0; i < EPL; ++i) {
     const int d = piece * EPL + i;
-    if (o_bar != nullptr) {
+    if (NORMS) {
+      o[i] = 0.f;
+    } else if (o_bar != nullptr) {
       o[i] = o_bar[(size_t)un.index * D + d];
     } else {
       float s = sm_obar[0][d];
@@ -245,6 +255,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
     float ra[kPrefetch];
     uint8_t rm[kPrefetch];          // kept as loaded: widening at the load would wait for it there
     int rc[kPrefetch];              // cardinality of the Value row's token (COUNTS only)
+    float re[kPrefetch];            // C of the edge after the Value row's token (NORMS only)
     auto refill = [&](int j, int t) {                // the set that token t will consume
       rk[j] = k_row(min(t, gb - 1));
       const int tv = min(t + 1, last_v);
@@ -252,6 +263,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       ra[j] = alpha_at(tv);
       rm[j] = mask_at(tv);
       if (COUNTS) rc[j] = count_at(tv);
+      if (NORMS) re[j] = cedge_at(tv);
     };
 #pragma unroll
     for (int j = 0; j < kPrefetch; ++j) refill(j, ga + j);
@@ -261,10 +273,16 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 
     float v_cur[EPL], r_cur[EPL], accK[EPL], accV[EPL];
     float ss_cur = 0.f, Cprev = 0.f, U = 0.f;
+    float ce_cur = NORMS ? ce[ga] : 0.f;             // NORMS: C of the edge after the current token
     int count = 0, first_tok = ga, out_slot = out_slot0;
     int c_cur = count_at(ga), csum = 0;              // COUNTS: this row's cardinality, the open slot's so far
     bool is_head = head_open;       // the open slot began before this group
-    {
+    if (NORMS) {
+      Piece<T>::unpack(vraw_first, v_cur);
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) { r_cur[i] = 0.f; accK[i] = 0.f; accV[i] = 0.f; }
+      Cprev = (head_open && coupled) ? ce[ga - 1] : 0.f;
+    } else {
       Piece<T>::unpack(vraw_first, v_cur);
       const float ic0 = COUNTS ? __builtin_amdgcn_rcpf((float)c_cur) : 1.f;
 #pragma unroll
@@ -306,23 +324,33 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
                    : "v"(ra[j]), "v"((uint32_t)rm[j]));
       int c_n = 1;
       if (COUNTS) asm volatile("v_mov_b32 %0, %1" : "=&v"(c_n) : "v"(rc[j]));
+      float ce_n = 0.f;
+      if (NORMS) asm volatile("v_mov_b32 %0, %1" : "=&v"(ce_n) : "v"(re[j]));
       const float icn = COUNTS ? __builtin_amdgcn_rcpf((float)c_n) : 1.f;
       float kf[EPL], vn[EPL], r_next[EPL];
       Piece<T>::unpack(kraw, kf);
       Piece<T>::unpack(vraw_n, vn);
       // ||r_t + r_{t+1}||^2 = ||r_t||^2 + ||r_{t+1}||^2 + 2 r_t . r_{t+1}
       float ss_next = 0.f, dot = 0.f;
+      float Anorm, C;
+      if (NORMS) {
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        r_next[i] = COUNTS ? fmaf(vn[i], icn, -o[i]) : vn[i] - o[i];
-        ss_next = fmaf(r_next[i], r_next[i], ss_next);
-        dot = fmaf(r_cur[i], r_next[i], dot);
+        for (int i = 0; i < EPL; ++i) r_next[i] = 0.f;
+        Anorm = alpha_cur;
+        C = (mask_cur && coupled) ? ce_cur : 0.f;
+      } else {
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+          r_next[i] = COUNTS ? fmaf(vn[i], icn, -o[i]) : vn[i] - o[i];
+          ss_next = fmaf(r_next[i], r_next[i], ss_next);
+          dot = fmaf(r_cur[i], r_next[i], dot);
+        }
+        ss_next = group_sum<LPR>(ss_next);
+        dot = group_sum<LPR>(dot);
+        Anorm = alpha_cur * fabsf(1.f - 2.f * alpha_cur) * __builtin_amdgcn_sqrtf(ss_cur);
+        const float pair2 = fmaxf(fmaf(2.f, dot, ss_cur + ss_next), 0.f);
+        C = (mask_cur && coupled) ? alpha_cur * alpha_n * __builtin_amdgcn_sqrtf(pair2) : 0.f;
       }
-      ss_next = group_sum<LPR>(ss_next);
-      dot = group_sum<LPR>(dot);
-      const float Anorm = alpha_cur * fabsf(1.f - 2.f * alpha_cur) * __builtin_amdgcn_sqrtf(ss_cur);
-      const float pair2 = fmaxf(fmaf(2.f, dot, ss_cur + ss_next), 0.f);
-      const float C = (mask_cur && coupled) ? alpha_cur * alpha_n * __builtin_amdgcn_sqrtf(pair2) : 0.f;
       const float u = mean_rule ? (float)c_cur : Anorm - Cprev - C;
       first_tok = (count == 0) ? t : first_tok;
       U += u;
@@ -350,6 +378,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       }
       refill(j, t + kPrefetch);
       c_cur = c_n;
+      ce_cur = ce_n;
       Cprev = C;
       ss_cur = ss_next;
       alpha_cur = alpha_n;
@@ -407,14 +436,14 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 
 }  // namespace
 
-template <typename T, int D, bool STREAM, bool COUNTS>
+template <typename T, int D, bool STREAM, bool COUNTS, bool NORMS = false>
 static hipError_t launch_merge_k(const UnitTable& tab, const Shape& sh, const void* K, const void* V,
                                  const int32_t* counts_in, const float* alpha_bar, const float* o_bar,
                                  const float* o_part, const uint8_t* edge_mask, const int32_t* slot, void* K_out,
-                                 void* V_out, int32_t* counts, hipStream_t stream) {
-  hipLaunchKernelGGL((merge_kernel<T, D, STREAM, COUNTS>), dim3(tab.total_mblocks), dim3(kThreads), 0, stream, tab, sh,
-                     (const T*)K, (const T*)V, counts_in, alpha_bar, o_bar, o_part, edge_mask, slot, (T*)K_out,
-                     (T*)V_out, counts);
+                                 void* V_out, int32_t* counts, hipStream_t stream, const float* c_edge = nullptr) {
+  hipLaunchKernelGGL((merge_kernel<T, D, STREAM, COUNTS, NORMS>), dim3(tab.total_mblocks), dim3(kThreads), 0, stream,
+                     tab, sh, (const T*)K, (const T*)V, counts_in, alpha_bar, o_bar, o_part, c_edge, edge_mask, slot,
+                     (T*)K_out, (T*)V_out, counts);
   return hipGetLastError();
 }
 
@@ -439,6 +468,28 @@ hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, con
   }
   return sh.D == 64 ? launch_merge_t<uint16_t, 64>(KVS_MERGE_ARGS) : launch_merge_t<uint16_t, 128>(KVS_MERGE_ARGS);
 #undef KVS_MERGE_ARGS
+}
+
+template <typename T, int D>
+static hipError_t launch_merge_norms_t(const UnitTable& tab, const Shape& sh, const void* K, const void* V,
+                                       const float* a_tok, const float* c_edge, const uint8_t* edge_mask,
+                                       const int32_t* slot, void* K_out, void* V_out, int32_t* counts,
+                                       hipStream_t stream) {
+  return sh.stream ? launch_merge_k<T, D, true, false, true>(tab, sh, K, V, nullptr, a_tok, nullptr, nullptr, edge_mask,
+                                                             slot, K_out, V_out, counts, stream, c_edge)
+                   : launch_merge_k<T, D, false, false, true>(tab, sh, K, V, nullptr, a_tok, nullptr, nullptr,
+                                                              edge_mask, slot, K_out, V_out, counts, stream, c_edge);
+}
+
+hipError_t launch_merge_norms(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* K, const void* V,
+                              const float* a_tok, const float* c_edge, const uint8_t* edge_mask, const int32_t* slot,
+                              void* K_out, void* V_out, int32_t* counts, hipStream_t stream) {
+  if (dt == KVS_F32) {
+    return sh.D == 64 ? launch_merge_norms_t<float, 64>(tab, sh, K, V, a_tok, c_edge, edge_mask, slot, K_out, V_out, counts, stream)
+                      : launch_merge_norms_t<float, 128>(tab, sh, K, V, a_tok, c_edge, edge_mask, slot, K_out, V_out, counts, stream);
+  }
+  return sh.D == 64 ? launch_merge_norms_t<uint16_t, 64>(tab, sh, K, V, a_tok, c_edge, edge_mask, slot, K_out, V_out, counts, stream)
+                    : launch_merge_norms_t<uint16_t, 128>(tab, sh, K, V, a_tok, c_edge, edge_mask, slot, K_out, V_out, counts, stream);
 }
 
 }  // namespace kvs

@@ -1,0 +1,474 @@
+// Per-query aggregation of the sensitivity norms (bf16 inputs).
+//
+// Sec. 4 derives the forward-only vectors c_tt = alpha_t (1 - 2 alpha_t)(v_t - o) and
+// c_{t,t+1} = -alpha_t alpha_{t+1} (v_t + v_{t+1} - 2o) (Eqs. c11_def-c12_def) for ONE query.  Here every
+// query row q of the window keeps its own attention alpha^{(q)} and its own output o^{(q)} (Eq.
+// attn_def_vec), and the NORMS are averaged over the R rows:
+//   A_t = (1/R) sum_q alpha_t^{(q)} |1 - 2 alpha_t^{(q)}| ||v_t - o^{(q)}||
+//   C_t = (1/R) sum_q alpha_t^{(q)} alpha_{t+1}^{(q)} ||v_t + v_{t+1} - 2 o^{(q)}||
+// The merge kernel then uses A and C in the weight form of Eq. kstar_final.
+//
+// Three kernels after the two score sweeps (which leave the normaliser c[q] of every row):
+//   pq_out_kernel         O^T[d, q] = sum_t V[t, d] P[t, q], P = alpha / R recomputed from K Q^T tile by tile.
+//                         Both products run on v_mfma_f32_32x32x16_bf16.  The contraction over tokens needs
+//                         V with the token index along the MFMA k dimension; a 32x32 block of the V tile is
+//                         turned by one more MFMA against an identity operand (exact in bf16), which leaves it
+//                         in the accumulator layout that IS the k-major operand layout of the next product.
+//                         P enters as a bf16 pair hi + lo, so that the rounding of P to bf16 does not limit
+//                         the accuracy of o.  Chunk partials go to memory and are added in chunk order.
+//   pq_out_reduce_kernel  o^{(q)} = R * sum of the chunk partials, stored as a bf16 pair hi + lo, and
+//                         ||o^{(q)}||^2.
+//   pq_norms_kernel       per tile of 32 tokens: S = K Q^T (logits), X = V O^T (hi and lo), then per (t, q)
+//                         ||v_t - o||^2 = ||v_t||^2 - 2 X + ||o||^2,
+//                         ||v_t + v_{t+1} - 2o||^2 = ||v_t + v_{t+1}||^2 - 4 (X_t + X_{t+1}) + 4 ||o||^2,
+//                         two square roots, and the sums over q.  Tiles overlap by one row (stride 31), so
+//                         the next token of every output row is in the same tile.
+// A workgroup has four wavefronts; wavefront w owns query rows 32w .. 32w+31 of a pass of 128 rows and
+// keeps their operands in registers; all four walk the same K and V tiles, staged through LDS (XOR-swizzled
+// 16-byte pieces, as in the score kernels).  Results do not depend on timing: no atomics, fixed orders.
+#include "kvs_device.h"
+
+namespace kvs {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kTile = 32;                 // tokens per MFMA tile
+constexpr int kPassRows = 32 * kWaves;    // query rows per pass over the chunk
+
+__device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint4& u) { return __builtin_bit_cast(bf16x8, u); }
+
+// eight floats -> bf16 operand (round to nearest even)
+__device__ __forceinline__ bf16x8 pack8(const float* f) {
+  return as_bf16x8(make_uint4(cvt_pk_bf16(f[0], f[1]), cvt_pk_bf16(f[2], f[3]), cvt_pk_bf16(f[4], f[5]),
+                              cvt_pk_bf16(f[6], f[7])));
+}
+// eight floats -> hi + lo: hi = bf16(f), lo = bf16(f - hi)
+__device__ __forceinline__ void split8(const float* f, bf16x8& hi, bf16x8& lo) {
+  uint32_t h[4];
+  float r[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    h[i] = cvt_pk_bf16(f[2 * i], f[2 * i + 1]);
+    r[2 * i] = f[2 * i] - bf16_lo(h[i]);
+    r[2 * i + 1] = f[2 * i + 1] - bf16_hi(h[i]);
+  }
+  hi = as_bf16x8(make_uint4(h[0], h[1], h[2], h[3]));
+  lo = pack8(r);
+}
+
+// A 32-row tile of K or V: global -> registers -> LDS.  Piece p of row r lands in slot p ^ (r % LPR).
+template <int D>
+struct Tile {
+  static constexpr int LPR = D / 8;                       // 16-byte pieces per row
+  static constexpr int ROWB = D * 2;
+  static constexpr int BYTES = kTile * ROWB;
+  static constexpr int NP = kTile * LPR / kThreads;       // pieces per thread
+  __device__ __forceinline__ static void load(uint4 (&r)[NP], const unsigned char* tile_base, int tid) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) r[i] = *reinterpret_cast<const uint4*>(tile_base + (size_t)(tid + i * kThreads) * 16);
+  }
+  __device__ __forceinline__ static void store(unsigned char* sm, const uint4 (&r)[NP], int tid) {
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const int pi = tid + i * kThreads;
+      const int row = pi / LPR, piece = pi % LPR;
+      *reinterpret_cast<uint4*>(sm + row * ROWB + ((piece ^ (row % LPR)) * 16)) = r[i];
+    }
+  }
+  // MFMA operand of k-step kk for this lane: row `row`, elements 16 kk + 8 half .. + 7
+  __device__ __forceinline__ static bf16x8 operand(const unsigned char* sm, int row, int kk, int half) {
+    const int piece = 2 * kk + half;
+    return *reinterpret_cast<const bf16x8*>(sm + row * ROWB + ((piece ^ (row % LPR)) * 16));
+  }
+  __device__ __forceinline__ static uint4 piece_at(const unsigned char* sm, int row, int piece) {
+    return *reinterpret_cast<const uint4*>(sm + row * ROWB + ((piece ^ (row % LPR)) * 16));
+  }
+};
+
+// Operand of k-step kk from a row-major [rows, D] bf16 matrix in memory (zero for a row that does not exist).
+template <int D>
+__device__ __forceinline__ bf16x8 row_operand(const uint16_t* __restrict__ m, int row, bool ok, int kk, int half) {
+  uint4 raw = make_uint4(0, 0, 0, 0);
+  if (ok) raw = *reinterpret_cast<const uint4*>(m + (size_t)row * D + kk * 16 + 8 * half);
+  return as_bf16x8(raw);
+}
+
+// Sum over the 32 lanes of a half-wavefront of 16 values per lane: reduce-scatter, afterwards the even
+// lanes hold in p[0] the total of value index v = (lane >> 1) & 15.
+__device__ __forceinline__ void colsum16(float (&p)[16], int lane) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const bool up = lane & 16;
+    const float send = up ? p[i] : p[i + 8];
+    const float keep = up ? p[i + 8] : p[i];
+    p[i] = keep + __shfl_xor(send, 16, kWave);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bool up = lane & 8;
+    const float send = up ? p[i] : p[i + 4];
+    const float keep = up ? p[i + 4] : p[i];
+    p[i] = keep + __shfl_xor(send, 8, kWave);
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const bool up = lane & 4;
+    const float send = up ? p[i] : p[i + 2];
+    const float keep = up ? p[i + 2] : p[i];
+    p[i] = keep + __shfl_xor(send, 4, kWave);
+  }
+  {
+    const bool up = lane & 2;
+    const float send = up ? p[0] : p[1];
+    const float keep = up ? p[1] : p[0];
+    p[0] = keep + __shfl_xor(send, 2, kWave);
+  }
+  p[0] += __shfl_xor(p[0], 1, kWave);
+}
+
+// ------------------------------------------------------------------------------------------------
+// o_part[(chunk of the launch), q, :] = sum over the chunk's tokens of (alpha^{(q)}_t / R) V[t]
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void pq_out_kernel(
+    const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+    const uint16_t* __restrict__ V, const float* __restrict__ c_row, float* __restrict__ o_part) {
+  typedef Tile<D> TL;
+  constexpr int KS = D / 16;
+  constexpr int DB = D / 32;                // 32-wide blocks of the value dimension
+  __shared__ __attribute__((aligned(16))) unsigned char sm_k[2][TL::BYTES];
+  __shared__ __attribute__((aligned(16))) unsigned char sm_v[2][TL::BYTES];
+
+  const int ui = find_unit(tab, blockIdx.x);
+  const Unit un = tab.u[ui];
+  const int chunk = blockIdx.x - un.chunk_base;
+  const int t0 = chunk * un.chunk_len;
+  const int t1 = min(un.len, t0 + un.chunk_len);
+  const int ntiles = (t1 - t0 + kTile - 1) / kTile;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int col = lane % 32, half = lane / 32;
+  const int R = sh.R;
+  const float sl2 = sh.scale_log2;
+  const unsigned char* Kg = reinterpret_cast<const unsigned char*>(K + (size_t)un.in_row * D);
+  const unsigned char* Vg = reinterpret_cast<const unsigned char*>(V + (size_t)un.in_row * D);
+  const uint16_t* Qu = Q + (size_t)un.index * R * D;
+
+  // identity operand: element i of k-step kk is 1 where 16 kk + 8 half + i is this lane's column
+  bf16x8 ident[2];
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int k0 = 16 * kk + 8 * half + 2 * i;
+      w[i] = (k0 == col ? 0x3F80u : 0u) | (k0 + 1 == col ? 0x3F800000u : 0u);
+    }
+    ident[kk] = as_bf16x8(make_uint4(w[0], w[1], w[2], w[3]));
+  }
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  // a tile always holds 32 whole rows: the ragged last one is moved back to end at the chunk's end and the
+  // rows it shares with the tile before are skipped (every unit on this path has at least 32 rows)
+  auto tile_base = [&](int j) { return min(t0 + j * kTile, t1 - kTile); };
+
+  for (int qp = 0; qp < R; qp += kPassRows) {
+    const int qrow = qp + 32 * wave + col;
+    const bool ok = qrow < R;
+    bf16x8 bq[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) bq[kk] = row_operand<D>(Qu, qrow, ok, kk, half);
+    const float cq = ok ? c_row[(size_t)un.index * R + qrow] : INFINITY;   // exp2(-inf) = 0: no such row
+    f32x16 accO[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) accO[db] = zero;
+
+    uint4 rk[TL::NP], rv[TL::NP];
+    TL::load(rk, Kg + (size_t)tile_base(0) * TL::ROWB, tid);
+    TL::load(rv, Vg + (size_t)tile_base(0) * TL::ROWB, tid);
+    for (int j = 0; j < ntiles; ++j) {
+      const int buf = j & 1;
+      TL::store(sm_k[buf], rk, tid);
+      TL::store(sm_v[buf], rv, tid);
+      __syncthreads();
+      const int shift = t0 + j * kTile - tile_base(j);       // leading rows that belong to the tile before
+      if (j + 1 < ntiles) {
+        TL::load(rk, Kg + (size_t)tile_base(j + 1) * TL::ROWB, tid);
+        TL::load(rv, Vg + (size_t)tile_base(j + 1) * TL::ROWB, tid);
+      }
+      // logits of the tile against this wavefront's 32 query rows
+      f32x16 acc = zero;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::operand(sm_k[buf], col, kk, half), bq[kk], acc, 0, 0, 0);
+      // accumulator element v: token row 8 (v / 4) + 4 half + v % 4, query column `col`
+      float p[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = 8 * (v / 4) + 4 * half + (v % 4);
+        p[v] = (row >= shift) ? ex2(fmaf(acc[v], sl2, -cq)) : 0.f;
+      }
+      // as the operand of the next product, element i of k-step s is accumulator element 8 s + i
+      bf16x8 ph[2], pl[2];
+      split8(p, ph[0], pl[0]);
+      split8(p + 8, ph[1], pl[1]);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        // the block V[tile rows, 32 db .. 32 db + 31] into the same (token-major) accumulator layout
+        f32x16 y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::operand(sm_v[buf], col, 2 * db, half), ident[0], zero, 0, 0, 0);
+        y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::operand(sm_v[buf], col, 2 * db + 1, half), ident[1], y, 0, 0, 0);
+        float yf[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) yf[v] = y[v];
+        const bf16x8 vt0 = pack8(yf), vt1 = pack8(yf + 8);     // exact: the values are bf16 numbers
+        accO[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt0, ph[0], accO[db], 0, 0, 0);
+        accO[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt1, ph[1], accO[db], 0, 0, 0);
+        accO[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt0, pl[0], accO[db], 0, 0, 0);
+        accO[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt1, pl[1], accO[db], 0, 0, 0);
+      }
+    }
+    __syncthreads();                        // the next pass starts with buffer 0 again
+    if (ok) {
+      float* dst = o_part + ((size_t)(un.chunk_base + chunk) * R + qrow) * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 o4 = make_float4(accO[db][4 * g], accO[db][4 * g + 1], accO[db][4 * g + 2], accO[db][4 * g + 3]);
+          *reinterpret_cast<float4*>(dst + 32 * db + 8 * g + 4 * half) = o4;
+        }
+      }
+    }
+  }
+}
+
+// o^{(q)} from the chunk partials (in chunk order), as a bf16 pair hi + lo, and its squared norm.
+// One workgroup of D threads per (unit, query row).
+template <int D>
+__global__ __launch_bounds__(D) void pq_out_reduce_kernel(const UnitTable tab, const Shape sh,
+                                                          const float* __restrict__ o_part,
+                                                          uint16_t* __restrict__ o_hi, uint16_t* __restrict__ o_lo,
+                                                          float* __restrict__ oo) {
+  __shared__ float sm_ss[D / kWave];
+  const int R = sh.R;
+  const Unit un = tab.u[blockIdx.x / R];
+  const int q = blockIdx.x % R;
+  const int d = threadIdx.x;
+  float s = 0.f;
+  for (int c = 0; c < un.n_chunks; ++c) s += o_part[((size_t)(un.chunk_base + c) * R + q) * D + d];
+  const float o = s * (float)R;
+  const uint32_t hi = f32_to_bf16(o);
+  const uint32_t lo = f32_to_bf16(o - bf16_lo(hi));
+  const size_t idx = ((size_t)un.index * R + q) * D + d;
+  o_hi[idx] = (uint16_t)hi;
+  o_lo[idx] = (uint16_t)lo;
+  const float oe = bf16_lo(hi) + bf16_lo(lo);              // the value the products below see
+  float ss = oe * oe;
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) ss += __shfl_xor(ss, m, kWave);
+  if (d % kWave == 0) sm_ss[d / kWave] = ss;
+  __syncthreads();
+  if (d == 0) {
+    float t = sm_ss[0];
+#pragma unroll
+    for (int w = 1; w < D / kWave; ++w) t += sm_ss[w];
+    oo[(size_t)un.index * R + q] = t;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// A_t and C_t of every token of the chunk.
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
+    const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+    const uint16_t* __restrict__ V, const float* __restrict__ c_row, const uint16_t* __restrict__ o_hi,
+    const uint16_t* __restrict__ o_lo, const float* __restrict__ oo, float* __restrict__ a_tok,
+    float* __restrict__ c_edge) {
+  typedef Tile<D> TL;
+  constexpr int KS = D / 16;
+  constexpr int STRIDE = kTile - 1;         // output rows per tile: the last row only serves as "next token"
+  constexpr int PPT = TL::LPR / 8;          // pieces per thread when 8 threads share a row
+  __shared__ __attribute__((aligned(16))) unsigned char sm_k[2][TL::BYTES];
+  __shared__ __attribute__((aligned(16))) unsigned char sm_v[2][TL::BYTES];
+  __shared__ __attribute__((aligned(16))) float sm_vv[2][kTile];     // ||v_r||^2
+  __shared__ __attribute__((aligned(16))) float sm_vp[2][kTile];     // ||v_r + v_{r+1}||^2
+  __shared__ float2 sm_out[2][kWaves][kTile];                        // (sum_q A, sum_q C) of every wavefront
+
+  const int ui = find_unit(tab, blockIdx.x);
+  const Unit un = tab.u[ui];
+  const int chunk = blockIdx.x - un.chunk_base;
+  const int t0 = chunk * un.chunk_len;
+  const int t1 = min(un.len, t0 + un.chunk_len);
+  const int ntiles = (t1 - t0 + STRIDE - 1) / STRIDE;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int col = lane % 32, half = lane / 32;
+  const int R = sh.R;
+  const float Rf = (float)R;
+  const float sl2 = sh.scale_log2;
+  const unsigned char* Kg = reinterpret_cast<const unsigned char*>(K + (size_t)un.in_row * D);
+  const unsigned char* Vg = reinterpret_cast<const unsigned char*>(V + (size_t)un.in_row * D);
+  const uint16_t* Qu = Q + (size_t)un.index * R * D;
+  const uint16_t* Oh = o_hi + (size_t)un.index * R * D;
+  const uint16_t* Ol = o_lo + (size_t)un.index * R * D;
+  float* At = a_tok + un.in_row;
+  float* Ce = c_edge + un.in_row;
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  // Tile j puts out tokens t0 + 31 j .. + 30 and reads one row more.  Near the unit's end it is moved back
+  // to hold 32 existing rows; the `shift` leading rows then belong to earlier tiles.
+  auto tile_first = [&](int j) { return t0 + j * STRIDE; };
+  auto tile_base = [&](int j) { return min(tile_first(j), un.len - kTile); };
+
+  for (int qp = 0; qp < R; qp += kPassRows) {
+    const int qrow = qp + 32 * wave + col;
+    const bool ok = qrow < R;
+    bf16x8 bq[KS], boh[KS], bol[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      bq[kk] = row_operand<D>(Qu, qrow, ok, kk, half);
+      boh[kk] = row_operand<D>(Oh, qrow, ok, kk, half);
+      bol[kk] = row_operand<D>(Ol, qrow, ok, kk, half);
+    }
+    const float cq = ok ? c_row[(size_t)un.index * R + qrow] : INFINITY;
+    const float ooq = ok ? oo[(size_t)un.index * R + qrow] : 0.f;
+
+    // sums of the tile before -> memory (threads 0..31, one row each; the wavefronts in a fixed order)
+    auto flush = [&](int j) {
+      if (tid < kTile) {
+        const int buf = j & 1;
+        const int base = tile_base(j), shift = tile_first(j) - base;
+        const int r = tid, t = base + r;
+        if (r >= shift && r <= shift + STRIDE - 1 && t < t1) {
+          float a = 0.f, c = 0.f;
+#pragma unroll
+          for (int w = 0; w < kWaves; ++w) { a += sm_out[buf][w][r].x; c += sm_out[buf][w][r].y; }
+          if (r == kTile - 1) c = 0.f;                     // only the unit's last token: it has no next one
+          if (qp > 0) { a += At[t]; c += Ce[t]; }          // later passes add their query rows
+          At[t] = a;
+          Ce[t] = c;
+        }
+      }
+    };
+
+    uint4 rk[TL::NP], rv[TL::NP];
+    TL::load(rk, Kg + (size_t)tile_base(0) * TL::ROWB, tid);
+    TL::load(rv, Vg + (size_t)tile_base(0) * TL::ROWB, tid);
+    for (int j = 0; j < ntiles; ++j) {
+      const int buf = j & 1;
+      TL::store(sm_k[buf], rk, tid);
+      TL::store(sm_v[buf], rv, tid);
+      __syncthreads();
+      if (j + 1 < ntiles) {
+        TL::load(rk, Kg + (size_t)tile_base(j + 1) * TL::ROWB, tid);
+        TL::load(rv, Vg + (size_t)tile_base(j + 1) * TL::ROWB, tid);
+      }
+      if (j > 0) flush(j - 1);
+      // squared norms of the rows and of the sums of adjacent rows: eight threads per row
+      {
+        const int r = tid / 8, part = tid % 8;
+        const int rn = min(r + 1, kTile - 1);
+        float s_rr = 0.f, s_nn = 0.f, s_rn = 0.f;
+#pragma unroll
+        for (int x = 0; x < PPT; ++x) {
+          float a[8], b[8];
+          Piece<uint16_t>::unpack(TL::piece_at(sm_v[buf], r, part * PPT + x), a);
+          Piece<uint16_t>::unpack(TL::piece_at(sm_v[buf], rn, part * PPT + x), b);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            s_rr = fmaf(a[i], a[i], s_rr);
+            s_nn = fmaf(b[i], b[i], s_nn);
+            s_rn = fmaf(a[i], b[i], s_rn);
+          }
+        }
+        s_rr = row_group_sum<8>(s_rr);
+        s_nn = row_group_sum<8>(s_nn);
+        s_rn = row_group_sum<8>(s_rn);
+        if (part == 0) {
+          sm_vv[buf][r] = s_rr;
+          sm_vp[buf][r] = fmaf(2.f, s_rn, s_rr + s_nn);
+        }
+      }
+      // S = K Q^T and X = V O^T for this wavefront's 32 query rows
+      f32x16 accS = zero, accX = zero;
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk)
+        accS = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::operand(sm_k[buf], col, kk, half), bq[kk], accS, 0, 0, 0);
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        const bf16x8 av = TL::operand(sm_v[buf], col, kk, half);
+        accX = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, boh[kk], accX, 0, 0, 0);
+        accX = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bol[kk], accX, 0, 0, 0);
+      }
+      __syncthreads();                      // sm_vv / sm_vp of this tile are complete
+      // accumulator element v: token row 8 (v / 4) + 4 half + v % 4, query column `col`
+      float a[16], x[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        a[v] = ex2(fmaf(accS[v], sl2, -cq));              // alpha / R
+        x[v] = accX[v];
+      }
+      float pa[16], pc[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        // the row after element 4 g + 3 lives in the other half of the wavefront
+        const float a_far = __shfl_xor(half ? a[4 * g] : a[(4 * g + 4) & 15], 32, kWave);
+        const float x_far = __shfl_xor(half ? x[4 * g] : x[(4 * g + 4) & 15], 32, kWave);
+        const float4 vv4 = *reinterpret_cast<const float4*>(&sm_vv[buf][8 * g + 4 * half]);
+        const float4 vp4 = *reinterpret_cast<const float4*>(&sm_vp[buf][8 * g + 4 * half]);
+        const float vv[4] = {vv4.x, vv4.y, vv4.z, vv4.w};
+        const float vp[4] = {vp4.x, vp4.y, vp4.z, vp4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int v = 4 * g + i;
+          const float an = (i < 3) ? a[(v + 1) & 15] : a_far;
+          const float xn = (i < 3) ? x[(v + 1) & 15] : x_far;
+          const float d2 = fmaxf(fmaf(-2.f, x[v], vv[i]) + ooq, 0.f);
+          const float p2 = fmaxf(fmaf(-4.f, x[v] + xn, vp[i]) + 4.f * ooq, 0.f);
+          pa[v] = a[v] * fabsf(fmaf(-2.f * Rf, a[v], 1.f)) * __builtin_amdgcn_sqrtf(d2);
+          pc[v] = a[v] * (Rf * an) * __builtin_amdgcn_sqrtf(p2);
+        }
+      }
+      colsum16(pa, lane);
+      colsum16(pc, lane);
+      if ((lane & 1) == 0) {
+        const int v = (lane >> 1) & 15;
+        sm_out[buf][wave][8 * (v / 4) + 4 * half + (v % 4)] = make_float2(pa[0], pc[0]);
+      }
+    }
+    __syncthreads();
+    flush(ntiles - 1);
+    __syncthreads();                        // the next pass reuses the buffers
+  }
+}
+
+template <int D>
+hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
+                    const float* c_row, float* o_part, uint16_t* o_hi, uint16_t* o_lo, float* oo, float* a_tok,
+                    float* c_edge, hipStream_t stream) {
+  const dim3 grid(tab.total_chunks), block(kThreads);
+  hipLaunchKernelGGL((pq_out_kernel<D>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q, (const uint16_t*)K,
+                     (const uint16_t*)V, c_row, o_part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((pq_out_reduce_kernel<D>), dim3(tab.n_units * sh.R), dim3(D), 0, stream, tab, sh, o_part, o_hi,
+                     o_lo, oo);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL((pq_norms_kernel<D>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q, (const uint16_t*)K,
+                     (const uint16_t*)V, c_row, o_hi, o_lo, oo, a_tok, c_edge);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_per_query_norms(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
+                                  const float* c_row, float* o_part, uint16_t* o_hi, uint16_t* o_lo, float* oo,
+                                  float* a_tok, float* c_edge, hipStream_t stream) {
+  return sh.D == 64 ? launch_t<64>(tab, sh, Q, K, V, c_row, o_part, o_hi, o_lo, oo, a_tok, c_edge, stream)
+                    : launch_t<128>(tab, sh, Q, K, V, c_row, o_part, o_hi, o_lo, oo, a_tok, c_edge, stream);
+}
+
+}  // namespace kvs

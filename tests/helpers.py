@@ -68,6 +68,36 @@ def accepted_unit(w: Workload, layer: int, seq: int, head: int, n: Optional[int]
     raise RuntimeError("no accepted attempt found")
 
 
+PQ_COND_MIN = 3e-2
+
+
+def accepted_unit_per_query(w: Workload, layer: int, seq: int, head: int, n: Optional[int] = None) -> AcceptedUnit:
+    """The same for the per-query aggregation of the norms.  Its kernels recompute attention rows and outputs in
+    bf16 products (split into two bf16 terms), so A_t and C_t carry relative differences of the order of 1e-4
+    instead of fp32 rounding; a slot's Key moves by about that divided by its conditioning U / sum A_t, hence the
+    larger minimum here (the 1e-2 bar of bf16 outputs then leaves a factor of three)."""
+    if n is None:
+        n = unit_lengths(w)[seq]
+    start = load_manifest().get(manifest_key(w, layer, seq, head, n), 0)
+    base = None
+    for attempt in range(start, MAX_ATTEMPTS):
+        u = generate_unit(w, layer, seq, head, attempt=attempt, n=n, kv_from=base)
+        base = u
+        assert u.counts is None
+        alpha_bar, o_bar = O.score(u.Q, u.K, u.V)
+        gap = O.boundary_gap(alpha_bar, u.budget, w.n_sink, w.n_recent)
+        if gap < GAP_MIN:
+            continue
+        mask, slot = O.select(alpha_bar, u.budget, w.n_sink, w.n_recent)
+        norms = O.per_query_norms(u.Q, u.K, u.V)
+        merged = O.merge_compact(u.K, u.V, alpha_bar, o_bar, mask, slot, norms=norms)
+        cond = O.conditioning(merged)
+        if cond < PQ_COND_MIN:
+            continue
+        return AcceptedUnit(u, O.StepResult(alpha_bar, o_bar, mask, slot, merged), gap, cond)
+    raise RuntimeError("no accepted attempt found")
+
+
 # ------------------------------------------------------------------------------------------------
 # device marshalling (torch is used for memory only)
 def to_device(x32: np.ndarray, dtype: str):

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(binding.EXPORTS)
     for name in names:
         assert getattr(lib, name) is not None
-    assert kvs.kvs_version() == 200
+    assert kvs.kvs_version() == 300
     assert kvs.status_str(kvs.KVS_OK) == "ok"
     for code in range(1, 7):
         assert kvs.status_str(code) not in ("ok", "unknown status")
@@ -182,3 +182,33 @@ def test_decode_and_counts_entry_points_validate_on_the_host():
     # cardinalities that overlap an output are an alias error like any other input
     assert status_of(kvs.kvs_step_counts, p, b["Q"], b["K"], b["V"], b["K_out"], b["K_out"], b["V_out"], b["counts"],
                      b["ws"]) == kvs.KVS_ERR_ALIAS
+
+
+def test_per_query_entry_points_validate_on_the_host():
+    assert status_of(kvs.kvs_per_query_workspace_size, problem()) == kvs.KVS_ERR_DTYPE          # fp32
+    assert status_of(kvs.kvs_per_query_workspace_size,
+                     problem(dtype="bf16", lens=[1024, 31], budgets=[512, 31])) == kvs.KVS_ERR_INVALID_ARG
+    p = problem(dtype="bf16")
+    need = kvs.kvs_per_query_workspace_size(p)
+    assert need % 256 == 0 and need > kvs.kvs_workspace_size(p)
+    b = fake_buffers(p, elt=2)
+    ws = FakeBuf(b["ws"].addr, need)
+    a_tok = FakeBuf(1 << 40, p.rows_in * 4)
+    c_edge = FakeBuf((1 << 40) + (1 << 30), p.rows_in * 4)
+    sens = lambda **o: status_of(  # noqa: E731
+        kvs.kvs_sensitivity, p, b["Q"], o.get("K", b["K"]), b["V"], b["alpha"], o.get("a_tok", a_tok), c_edge,
+        o.get("ws", ws), ws_bytes=o.get("ws_bytes"))
+    assert sens(K=None) == kvs.KVS_ERR_INVALID_ARG
+    assert sens(a_tok=c_edge) == kvs.KVS_ERR_ALIAS
+    assert sens(ws_bytes=need - 256) == kvs.KVS_ERR_WORKSPACE
+    assert sens(ws=FakeBuf(ws.addr + 16, need)) == kvs.KVS_ERR_WORKSPACE
+    step = lambda **o: status_of(  # noqa: E731
+        kvs.kvs_step_per_query, p, b["Q"], b["K"], b["V"], o.get("K_out", b["K_out"]), b["V_out"], b["counts"],
+        o.get("ws", ws), ws_bytes=o.get("ws_bytes"))
+    assert step(K_out=b["V"]) == kvs.KVS_ERR_ALIAS
+    assert step(ws_bytes=kvs.kvs_workspace_size(p)) == kvs.KVS_ERR_WORKSPACE
+    norms = lambda **o: status_of(  # noqa: E731
+        kvs.kvs_merge_compact_norms, p, b["K"], b["V"], o.get("a_tok", a_tok), c_edge, b["mask"], b["slot"],
+        b["K_out"], o.get("V_out", b["V_out"]), b["counts"])
+    assert norms(a_tok=None) == kvs.KVS_ERR_INVALID_ARG
+    assert norms(V_out=b["K_out"]) == kvs.KVS_ERR_ALIAS

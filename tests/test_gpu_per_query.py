@@ -1,0 +1,167 @@
+"""GPU-vs-oracle parity of the per-query aggregation (kvs_sensitivity, kvs_merge_compact_norms,
+kvs_step_per_query), called through the C ABI.
+
+Bars: selected edges, slot maps and counts bit-exact; merged K / V within 1e-2 (bf16 I/O; 1e-5 for
+kvs_merge_compact_norms with fp32 I/O) relative L2 error per output row; A_t and C_t within TOL_NORMS
+relative.  TOL_NORMS: the kernels form alpha in fp32 (as the score sweeps, 3e-5), the attention outputs
+o^{(q)} and the products v.o from bf16 operand pairs hi + lo (2^-16 relative per term), and the squared
+distances by the expansion ||v||^2 - 2 v.o + ||o||^2 in fp32, whose cancellation is mild because
+||o|| is well below ||v|| on every workload here.
+"""
+
+import numpy as np
+import pytest
+
+from oracle import kvs_oracle as O
+from workloads import WORKLOADS, generate_unit
+
+from helpers import DeviceBatch, accepted_unit_per_query, from_device
+from test_gpu_parity import TOL_ALPHA, compare_outputs, merge_case, torch_sync, variant
+
+pytestmark = pytest.mark.gpu
+
+TOL_NORMS = 3e-4
+
+
+def per_query_buffers(batch):
+    import torch
+    p = batch.problem
+    G = batch.GUARD
+    a_tok = torch.full((p.rows_in + G,), -7.0, dtype=torch.float32, device="cuda")
+    c_edge = torch.full((p.rows_in + G,), -7.0, dtype=torch.float32, device="cuda")
+    ws = torch.empty(batch.kvs.kvs_per_query_workspace_size(p) + 256, dtype=torch.uint8, device="cuda")
+    return a_tok, c_edge, ws
+
+
+SENS_CASES = [
+    # base, D, G, W, lengths
+    ("llama8b_8k", 128, 4, 32, [2500]),              # one pass of 128 rows, ten chunks, ragged tail
+    ("llama8b_8k", 128, 1, 20, [700, 33]),           # fewer rows than one wavefront's block; a 33-row unit
+    ("llama8b_8k", 64, 2, 16, [900, 32]),            # head dim 64; a unit of exactly one tile
+    ("llama8b_8k", 128, 5, 20, [1500]),              # 100 rows: the last wavefront's block is ragged
+    ("llama8b_8k", 128, 5, 32, [1111, 300]),         # 160 rows: two passes
+    ("stress128k", 128, 8, 40, [1200]),              # 320 rows: three passes
+    ("ragged16", 128, 4, 32, [300, 5000, 9000]),     # chunks of different units in one launch
+    ("llama8b_8k", 128, 1, 1, [257]),                # a single query row
+]
+
+
+@pytest.mark.parametrize("base,D,G,W,lens", SENS_CASES)
+def test_sensitivity_matches_oracle(base, D, G, W, lens):
+    w = variant(base, dtype="bf16", head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
+    units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
+    batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype="bf16", n_sink=w.n_sink, gap_rows=3)
+    a_tok, c_edge, ws = per_query_buffers(batch)
+    batch.kvs.kvs_sensitivity(batch.problem, batch.Q, batch.K, batch.V, batch.alpha_bar, a_tok, c_edge, ws,
+                              stream=batch.stream())
+    torch_sync()
+    batch.check_guards()
+    p = batch.problem
+    assert (a_tok[p.rows_in:] == -7.0).all() and (c_edge[p.rows_in:] == -7.0).all()
+    alpha, A, C = from_device(batch.alpha_bar), from_device(a_tok), from_device(c_edge)
+    for i, u in enumerate(units):
+        n = lens[i]
+        r0 = p.in_rows[i]
+        ra, _ = O.score(u.Q, u.K, u.V)
+        A_ref, C_ref = O.per_query_norms(u.Q, u.K, u.V)
+        assert np.max(np.abs(alpha[r0:r0 + n] - ra) / ra) < TOL_ALPHA
+        gA, gC = A[r0:r0 + n], C[r0:r0 + n - 1]
+        assert np.isfinite(gA).all() and np.isfinite(gC).all()
+        eA = np.max(np.abs(gA - A_ref) / A_ref)
+        eC = np.max(np.abs(gC - C_ref) / C_ref)
+        assert eA < TOL_NORMS, (i, "A", eA)
+        assert eC < TOL_NORMS, (i, "C", eC)
+        assert C[r0 + n - 1] == 0.0                  # a unit's last row has no edge
+    for i in range(len(units) - 1):                  # rows between units are never touched
+        gap0 = p.in_rows[i] + lens[i]
+        assert (A[gap0:gap0 + 3] == -7.0).all() and (C[gap0:gap0 + 3] == -7.0).all()
+
+
+@pytest.mark.parametrize("rule", ["hessian", "diagonal"])
+@pytest.mark.parametrize("base,dtype,D,lens,budgets", [
+    ("tiny", "f32", 64, [1024, 300], [256, 100]),
+    ("llama8b_8k", "bf16", 128, [3000, 777], [700, 300]),
+])
+def test_merge_compact_norms_matches_oracle(base, dtype, D, lens, budgets, rule):
+    """The merge pass with A_t and C_t handed in (here the oracle's, rounded to fp32)."""
+    import torch
+    w, units = merge_case(base, dtype, D, lens, budgets)
+    batch = DeviceBatch(units, group=w.group, window=w.window, head_dim=D, dtype=dtype, n_sink=w.n_sink,
+                        key_rule=rule)
+    p = batch.problem
+    refs = []
+    A_all = np.zeros(p.rows_in, dtype=np.float32)
+    C_all = np.zeros(p.rows_in, dtype=np.float32)
+    mask_all = np.zeros(p.rows_in, dtype=np.uint8)
+    slot_all = np.zeros(p.rows_in, dtype=np.int32)
+    for i, u in enumerate(units):
+        n = u.K.shape[0]
+        a, o = O.score(u.Q, u.K, u.V)
+        mask, slot = O.select(a.astype(np.float32), u.budget, w.n_sink, 0, sigma_dtype=np.float32)
+        A, C = O.per_query_norms(u.Q, u.K, u.V)
+        A32, C32 = A.astype(np.float32), C.astype(np.float32)
+        refs.append(O.merge_compact(u.K, u.V, a, o, mask, slot, rule=rule,
+                                    norms=(A32.astype(np.float64), C32.astype(np.float64))))
+        r0 = p.in_rows[i]
+        A_all[r0:r0 + n] = A32
+        C_all[r0:r0 + n - 1] = C32
+        mask_all[r0:r0 + n] = mask
+        slot_all[r0:r0 + n] = slot
+    batch.kvs.kvs_merge_compact_norms(p, batch.K, batch.V, torch.from_numpy(A_all).cuda(),
+                                      torch.from_numpy(C_all).cuda(), torch.from_numpy(mask_all).cuda(),
+                                      torch.from_numpy(slot_all).cuda(), batch.K_out, batch.V_out, batch.counts,
+                                      stream=batch.stream())
+    torch_sync()
+    batch.check_guards()
+    compare_outputs(batch, refs, dtype)
+
+
+def check_step_per_query(w, accepted):
+    batch = DeviceBatch([a.inputs for a in accepted], group=w.group, window=w.window, head_dim=w.head_dim,
+                        dtype=w.dtype, n_sink=w.n_sink, n_recent=w.n_recent)
+    _, _, ws = per_query_buffers(batch)
+    batch.kvs.kvs_step_per_query(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out, batch.counts,
+                                 ws, slot_of_token_out=batch.slot, edge_mask_out=batch.mask, stream=batch.stream())
+    torch_sync()
+    batch.check_guards()
+    p = batch.problem
+    mask, slot = batch.mask.cpu().numpy(), batch.slot.cpu().numpy()
+    for i, a in enumerate(accepted):
+        r0, n = p.in_rows[i], a.inputs.n
+        assert (mask[r0:r0 + n] == a.ref.mask).all(), f"unit {i}: selected edges differ (gap {a.gap:.2e})"
+        assert (slot[r0:r0 + n] == a.ref.slot).all(), f"unit {i}: slot map differs"
+    compare_outputs(batch, [a.ref.merged for a in accepted], w.dtype)
+    return batch
+
+
+def test_step_per_query_8k_config():
+    w = WORKLOADS["llama8b_8k"]
+    check_step_per_query(w, [accepted_unit_per_query(w, 0, 0, h) for h in range(3)])
+
+
+def test_step_per_query_32k_two_heads_full_length():
+    """The headline shape (32768 -> 4096 tokens, 128 query rows), two of the layer's KV heads."""
+    import torch
+    w = WORKLOADS["llama8b_32k"]
+    acc = [accepted_unit_per_query(w, 5, 0, h) for h in range(2)]
+    b1 = check_step_per_query(w, acc)
+    b2 = check_step_per_query(w, acc)
+    assert torch.equal(b1.K_out.view(torch.int16), b2.K_out.view(torch.int16))     # run-to-run bitwise
+
+
+def test_step_per_query_with_one_row_is_the_plain_step():
+    """R = 1: the aggregation over query rows is the identity, the step equals kvs_step up to rounding."""
+    w = WORKLOADS["llama8b_8k"].scaled(group=1, window=1, length=("fixed", 3000), budget=("fixed", 1000))
+    acc = [accepted_unit_per_query(w, 0, 0, 0)]
+    batch = check_step_per_query(w, acc)
+    plain = DeviceBatch([a.inputs for a in acc], group=1, window=1, head_dim=w.head_dim, dtype=w.dtype,
+                        n_sink=w.n_sink)
+    plain.kvs.kvs_step(plain.problem, plain.Q, plain.K, plain.V, plain.K_out, plain.V_out, plain.counts, plain.ws,
+                       stream=plain.stream())
+    torch_sync()
+    import torch
+    assert torch.equal(batch.counts, plain.counts)
+    assert torch.equal(batch.V_out.view(torch.int16), plain.V_out.view(torch.int16))
+    n_out = plain.problem.rows_out
+    d = (batch.K_out[:n_out].float() - plain.K_out[:n_out].float()).norm(dim=1) / plain.K_out[:n_out].float().norm(dim=1)
+    assert float(d.max()) < 1e-2
