@@ -44,6 +44,8 @@ def parse():
                     help="rule for the merged Key (the ablations run the same kernels)")
     ap.add_argument("--decode", action="store_true",
                     help="also time kvs_decode_attention (one new query per query head) over the merged caches")
+    ap.add_argument("--per-query", action="store_true",
+                    help="also time the step with per-query aggregation of the norms (kvs_step_per_query, bf16 only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching from the host")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -319,6 +321,47 @@ def main():
                                       "achieved": nbytes / (t_ms * 1e-3) / 1e9, "unit": "GB/s",
                                       "frac": nbytes / (t_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                       "query_rows_per_unit": w.group}
+
+    if args.per_query:
+        # the same step with the norms aggregated per query row: four MFMA products per (token, query row)
+        # instead of the streaming passes, so this leg is priced against the matrix cores, not HBM
+        pws = torch.empty(kvs.kvs_per_query_workspace_size(big), dtype=torch.uint8, device=dev)
+        a_tok = torch.empty(big.rows_in, dtype=torch.float32, device=dev)
+        c_edge = torch.empty(big.rows_in, dtype=torch.float32, device=dev)
+        reps = max(1, min(args.steps, 5))
+
+        def timed(fn):
+            fn()
+            torch.cuda.synchronize()
+            ev0.record()
+            for _ in range(reps):
+                fn()
+            ev1.record()
+            torch.cuda.synchronize()
+            return ev0.elapsed_time(ev1) / reps
+
+        def pq_step():
+            for i, pr in enumerate(probs):
+                kvs.kvs_step_per_query(pr, Qs[i], Ks[i], Vs[i], K_out[i], V_out[i], counts[i], pws, stream=stream)
+
+        def pq_sens():
+            for i, pr in enumerate(probs):
+                kvs.kvs_sensitivity(pr, Qs[i], Ks[i], Vs[i], alpha, a_tok, c_edge, pws, stream=stream)
+
+        def plain_score():
+            for i, pr in enumerate(probs):
+                kvs.kvs_score(pr, Qs[i], Ks[i], Vs[i], alpha, obar, ws, stream=stream)
+
+        step_ms, sens_ms, score_ms = timed(pq_step), timed(pq_sens), timed(plain_score)
+        # algorithmic work of the two per-query kernels: K Q^T twice, P V and V O^T once, 2 n R D flops each
+        flops = layers * sum(8.0 * n * R * D for n in lens)
+        norms_ms = max(sens_ms - score_ms, 1e-6)             # kvs_sensitivity = the score sweeps + those kernels
+        result["per_query"] = {
+            "ms_per_step": step_ms, "us_per_layer": step_ms * 1e3 / layers, "value": tokens_per_step / (step_ms * 1e-3),
+            "unit": "tokens/s", "sensitivity_ms": sens_ms, "norm_kernels_ms": norms_ms,
+            "roofline": {"bound": "mfma", "kernels": "pq_out_kernel + pq_norms_kernel", "algorithmic_flops": flops,
+                         "achieved": flops / (norms_ms * 1e-3) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                         "frac": flops / (norms_ms * 1e-3) / 1e12 / 2500.0}}
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)

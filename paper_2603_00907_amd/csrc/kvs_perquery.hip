@@ -68,18 +68,23 @@ struct Tile {
   static constexpr int LPR = D / 8;                       // 16-byte pieces per row
   static constexpr int ROWB = D * 2;
   static constexpr int BYTES = kTile * ROWB;
-  static constexpr int NP = kTile * LPR / kThreads;       // pieces per thread
-  __device__ __forceinline__ static void load(uint4 (&r)[NP], const unsigned char* tile_base, int tid) {
-#pragma unroll
-    for (int i = 0; i < NP; ++i) r[i] = *reinterpret_cast<const uint4*>(tile_base + (size_t)(tid + i * kThreads) * 16);
+  static constexpr int NP = kTile * LPR / kThreads;       // pieces per thread: 1 or 2
+  // (two named registers instead of an array: an array handed on by reference across the loop stayed in
+  // scratch memory, with a wait after every load)
+  struct Regs { uint4 a, b; };
+  __device__ __forceinline__ static Regs load(const unsigned char* tile_base, int tid) {
+    Regs r;
+    r.a = *reinterpret_cast<const uint4*>(tile_base + (size_t)tid * 16);
+    r.b = (NP > 1) ? *reinterpret_cast<const uint4*>(tile_base + (size_t)(tid + kThreads) * 16) : make_uint4(0, 0, 0, 0);
+    return r;
   }
-  __device__ __forceinline__ static void store(unsigned char* sm, const uint4 (&r)[NP], int tid) {
-#pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      const int pi = tid + i * kThreads;
-      const int row = pi / LPR, piece = pi % LPR;
-      *reinterpret_cast<uint4*>(sm + row * ROWB + ((piece ^ (row % LPR)) * 16)) = r[i];
-    }
+  __device__ __forceinline__ static void store_piece(unsigned char* sm, const uint4& x, int pi) {
+    const int row = pi / LPR, piece = pi % LPR;
+    *reinterpret_cast<uint4*>(sm + row * ROWB + ((piece ^ (row % LPR)) * 16)) = x;
+  }
+  __device__ __forceinline__ static void store(unsigned char* sm, const Regs& r, int tid) {
+    store_piece(sm, r.a, tid);
+    if (NP > 1) store_piece(sm, r.b, tid + kThreads);
   }
   // MFMA operand of k-step kk for this lane: row `row`, elements 16 kk + 8 half .. + 7
   __device__ __forceinline__ static bf16x8 operand(const unsigned char* sm, int row, int kk, int half) {
@@ -187,18 +192,19 @@ __global__ __launch_bounds__(kThreads, 2) void pq_out_kernel(
 #pragma unroll
     for (int db = 0; db < DB; ++db) accO[db] = zero;
 
-    uint4 rk[TL::NP], rv[TL::NP];
-    TL::load(rk, Kg + (size_t)tile_base(0) * TL::ROWB, tid);
-    TL::load(rv, Vg + (size_t)tile_base(0) * TL::ROWB, tid);
+    typename TL::Regs rk = TL::load(Kg + (size_t)tile_base(0) * TL::ROWB, tid);
+    typename TL::Regs rv = TL::load(Vg + (size_t)tile_base(0) * TL::ROWB, tid);
     for (int j = 0; j < ntiles; ++j) {
       const int buf = j & 1;
       TL::store(sm_k[buf], rk, tid);
       TL::store(sm_v[buf], rv, tid);
       __syncthreads();
       const int shift = t0 + j * kTile - tile_base(j);       // leading rows that belong to the tile before
-      if (j + 1 < ntiles) {
-        TL::load(rk, Kg + (size_t)tile_base(j + 1) * TL::ROWB, tid);
-        TL::load(rv, Vg + (size_t)tile_base(j + 1) * TL::ROWB, tid);
+      {                                     // the next tile flies during this one (the last one is fetched twice)
+        const int jn = min(j + 1, ntiles - 1);
+        rk = TL::load(Kg + (size_t)tile_base(jn) * TL::ROWB, tid);
+        rv = TL::load(Vg + (size_t)tile_base(jn) * TL::ROWB, tid);
+        asm volatile("" ::: "memory");        // issue them here: sunk below the products they would be waited for at once
       }
       // logits of the tile against this wavefront's 32 query rows
       f32x16 acc = zero;
@@ -354,17 +360,18 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
       }
     };
 
-    uint4 rk[TL::NP], rv[TL::NP];
-    TL::load(rk, Kg + (size_t)tile_base(0) * TL::ROWB, tid);
-    TL::load(rv, Vg + (size_t)tile_base(0) * TL::ROWB, tid);
+    typename TL::Regs rk = TL::load(Kg + (size_t)tile_base(0) * TL::ROWB, tid);
+    typename TL::Regs rv = TL::load(Vg + (size_t)tile_base(0) * TL::ROWB, tid);
     for (int j = 0; j < ntiles; ++j) {
       const int buf = j & 1;
       TL::store(sm_k[buf], rk, tid);
       TL::store(sm_v[buf], rv, tid);
       __syncthreads();
-      if (j + 1 < ntiles) {
-        TL::load(rk, Kg + (size_t)tile_base(j + 1) * TL::ROWB, tid);
-        TL::load(rv, Vg + (size_t)tile_base(j + 1) * TL::ROWB, tid);
+      {                                     // the next tile flies during this one (the last one is fetched twice)
+        const int jn = min(j + 1, ntiles - 1);
+        rk = TL::load(Kg + (size_t)tile_base(jn) * TL::ROWB, tid);
+        rv = TL::load(Vg + (size_t)tile_base(jn) * TL::ROWB, tid);
+        asm volatile("" ::: "memory");        // issue them here: sunk below the products they would be waited for at once
       }
       if (j > 0) flush(j - 1);
       // squared norms of the rows and of the sums of adjacent rows: eight threads per row

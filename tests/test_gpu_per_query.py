@@ -4,7 +4,7 @@ kvs_step_per_query), called through the C ABI.
 Bars: selected edges, slot maps and counts bit-exact; merged K / V within 1e-2 (bf16 I/O; 1e-5 for
 kvs_merge_compact_norms with fp32 I/O) relative L2 error per output row; A_t and C_t within TOL_NORMS
 relative.  TOL_NORMS: the kernels form alpha in fp32 (as the score sweeps, 3e-5), the attention outputs
-o^{(q)} and the products v.o from bf16 operand pairs hi + lo (2^-16 relative per term), and the squared
+o^{(q)} and the products v.o from bf16 operand pairs hi + lo (2^-17 relative per term), and the squared
 distances by the expansion ||v||^2 - 2 v.o + ||o||^2 in fp32, whose cancellation is mild because
 ||o|| is well below ||v|| on every workload here.
 """
@@ -20,7 +20,7 @@ from test_gpu_parity import TOL_ALPHA, compare_outputs, merge_case, torch_sync, 
 
 pytestmark = pytest.mark.gpu
 
-TOL_NORMS = 3e-4
+TOL_NORMS = 5e-5     # measured: at most 1.1e-5 over the cases below
 
 
 def per_query_buffers(batch):
