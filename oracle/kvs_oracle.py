@@ -55,6 +55,10 @@ A_t = mean_q ||c_tt^{(q)}||, C_t = mean_q ||c_{t,t+1}^{(q)}||; `merge_compact(..
 uses them in the same weight form.  With one row it is the plain rule.  The partition still comes from
 alpha_bar.
 
+Causal window (`causal_window = W`): the paper does not say whether the window's queries see each other's
+tokens.  With the mask, the W queries are those of the last W positions and each attends to the rows up
+to its own position; without it (the default) every query row sees the whole cache.
+
 Readings of points the paper leaves open (many query rows, ranking score, runs
 longer than two, a non-positive denominator) are this module's and are listed
 in the repository's design notes.
@@ -80,11 +84,15 @@ F64 = np.float64
 
 # --------------------------------------------------------------------------- O1-O4
 def attention_rows(Q: np.ndarray, K: np.ndarray, scale: Optional[float] = None,
-                   counts: Optional[np.ndarray] = None) -> np.ndarray:
+                   counts: Optional[np.ndarray] = None, causal_window: int = 0) -> np.ndarray:
     """alpha[q, t] of Eq. "attn_def_vec" for every row q of Q [R, D] over K [n, D].
 
     With `counts`, row t of K stands for counts[t] tokens with that Key and alpha[q, t] is their total
-    mass: c equal terms exp(e) in the softmax sums are one term exp(e + ln c)."""
+    mass: c equal terms exp(e) in the softmax sums are one term exp(e + ln c).
+
+    `causal_window = W > 0`: the rows of Q are [G, W] queries of the LAST W positions of the sequence,
+    whose Keys are the last W rows of K; the query at window position w (row q with q mod W = w) sits
+    at position n - W + w and attends to rows t <= n - W + w only (decoder attention)."""
     Q = np.asarray(Q, dtype=F64).reshape(-1, K.shape[-1])
     K = np.asarray(K, dtype=F64)
     if scale is None:
@@ -92,6 +100,11 @@ def attention_rows(Q: np.ndarray, K: np.ndarray, scale: Optional[float] = None,
     e = scale * (Q @ K.T)                                   # O1
     if counts is not None:
         e = e + np.log(np.asarray(counts, dtype=F64))[None, :]
+    if causal_window:
+        n, W = K.shape[0], int(causal_window)
+        assert n >= W and Q.shape[0] % W == 0
+        last_seen = n - W + (np.arange(Q.shape[0]) % W)
+        e = np.where(np.arange(n)[None, :] <= last_seen[:, None], e, -np.inf)
     e = e - e.max(axis=1, keepdims=True)
     p = np.exp(e)
     return p / p.sum(axis=1, keepdims=True)                 # O2
@@ -107,9 +120,9 @@ def slot_values(V: np.ndarray, counts: Optional[np.ndarray]) -> np.ndarray:
 
 
 def score(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: Optional[float] = None,
-          counts: Optional[np.ndarray] = None) -> Tuple[np.ndarray, np.ndarray]:
+          counts: Optional[np.ndarray] = None, causal_window: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     """alpha_bar[n] (mean of the rows' attention) and o_bar[D] = sum_t alpha_bar[t] v[t]."""
-    alpha = attention_rows(Q, K, scale, counts)
+    alpha = attention_rows(Q, K, scale, counts, causal_window)
     alpha_bar = alpha.mean(axis=0)                          # O3
     o_bar = alpha_bar @ slot_values(V, counts)              # O4
     return alpha_bar, o_bar
@@ -175,12 +188,13 @@ def token_and_edge_norms(alpha_bar: np.ndarray, V: np.ndarray, o_bar: np.ndarray
     return A, C
 
 
-def per_query_norms(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: Optional[float] = None):
+def per_query_norms(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: Optional[float] = None,
+                    causal_window: int = 0):
     """A_t and C_t with every query row kept apart: row q has its own attention alpha^{(q)} (Eq. attn_def_vec)
     and its own output o^{(q)}; the vectors of Eqs. c11_def-c12_def are formed per row and their norms are
     averaged over the rows.  Q [R, D] (or [G, W, D]), K, V [n, D]; returns A [n], C [n - 1]."""
     V = np.asarray(V, dtype=F64)
-    alpha = attention_rows(Q, K, scale)
+    alpha = attention_rows(Q, K, scale, causal_window=causal_window)
     R, n = alpha.shape
     A = np.zeros(n, dtype=F64)
     C = np.zeros(max(n - 1, 0), dtype=F64)
@@ -286,10 +300,10 @@ class StepResult:
 
 def step(Q: np.ndarray, K: np.ndarray, V: np.ndarray, budget: int, n_sink: int = 32,
          n_recent: int = 0, scale: Optional[float] = None, counts: Optional[np.ndarray] = None,
-         rule: str = "hessian", per_query: bool = False) -> StepResult:
-    alpha_bar, o_bar = score(Q, K, V, scale, counts)
+         rule: str = "hessian", per_query: bool = False, causal_window: int = 0) -> StepResult:
+    alpha_bar, o_bar = score(Q, K, V, scale, counts, causal_window)
     mask, slot = select(alpha_bar, budget, n_sink, n_recent)
-    norms = per_query_norms(Q, K, V, scale) if per_query else None
+    norms = per_query_norms(Q, K, V, scale, causal_window) if per_query else None
     merged = merge_compact(K, V, alpha_bar, o_bar, mask, slot, counts, rule, norms)
     return StepResult(alpha_bar, o_bar, mask, slot, merged)
 

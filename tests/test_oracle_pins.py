@@ -691,3 +691,55 @@ def test_step_per_query_with_one_row_is_the_plain_step():
     b = O.step(Q, K, V, 48, n_sink=4, per_query=True)
     np.testing.assert_array_equal(a.mask, b.mask)
     np.testing.assert_allclose(a.merged.K_out, b.merged.K_out, rtol=1e-11, atol=1e-13)
+
+
+# --------------------------------------------------------------------------------------------
+# causal mask inside the window
+def test_causal_rows_are_textbook_attention_over_the_cache_up_to_their_position():
+    rng = np.random.default_rng(70)
+    n, d, G, W = 40, 8, 2, 5
+    Q = rng.standard_normal((G, W, d))
+    K = rng.standard_normal((n, d)) * 2.0
+    V = rng.standard_normal((n, d))
+    alpha = O.attention_rows(Q, K, causal_window=W)
+    for g in range(G):
+        for w in range(W):
+            seen = n - W + w + 1                         # the query at window position w sits at row n - W + w
+            a, _ = softmax_attention(Q[g, w], K[:seen], V[:seen])
+            np.testing.assert_allclose(alpha[g * W + w, :seen], a, rtol=1e-13)
+            assert (alpha[g * W + w, seen:] == 0).all()
+    # the last position sees everything: same as without the mask
+    full = O.attention_rows(Q, K)
+    np.testing.assert_allclose(alpha[W - 1::W], full[W - 1::W], rtol=1e-14)
+    # score and the per-query norms are built on these rows
+    ab, ob = O.score(Q, K, V, causal_window=W)
+    np.testing.assert_allclose(ab, alpha.mean(axis=0), rtol=1e-14)
+    np.testing.assert_allclose(ob, alpha.mean(axis=0) @ V, rtol=1e-13)
+    A, C = O.per_query_norms(Q, K, V, causal_window=W)
+    A_want = np.zeros(n)
+    for q in range(G * W):
+        seen = n - W + q % W + 1
+        a_q, o_q = softmax_attention(Q.reshape(-1, d)[q], K[:seen], V[:seen])
+        Aq, _ = O.token_and_edge_norms(a_q, V[:seen], o_q)   # (pinned by finite differences above)
+        A_want[:seen] += Aq
+    np.testing.assert_allclose(A, A_want / (G * W), rtol=1e-12)
+    assert C[-1] > 0 and A[-1] > 0                       # the last token is seen by the last position only
+
+
+def test_causal_window_of_one_and_with_counts():
+    rng = np.random.default_rng(71)
+    n, d = 30, 4
+    Q = rng.standard_normal((3, 1, d))
+    K = rng.standard_normal((n, d))
+    V = rng.standard_normal((n, d))
+    np.testing.assert_array_equal(O.attention_rows(Q, K, causal_window=1), O.attention_rows(Q, K))
+    # a masked row of cardinality c: c copies of the row, all masked or all seen
+    c = rng.integers(1, 4, size=n)
+    c[-4:] = 1                                           # the window's own rows are fresh tokens
+    Q4 = rng.standard_normal((1, 4, d))
+    a = O.attention_rows(Q4, K, counts=c, causal_window=4)
+    Kx = np.repeat(K, c, axis=0)
+    ax = O.attention_rows(Q4, Kx, causal_window=4)
+    ends = np.cumsum(c)
+    for t in range(n):
+        np.testing.assert_allclose(a[:, t], ax[:, ends[t] - c[t]:ends[t]].sum(axis=1), rtol=1e-12, atol=1e-300)
