@@ -49,7 +49,7 @@ extern "C" {
 typedef enum {
   KVS_OK = 0,
   KVS_ERR_INVALID_ARG = 1,  /* null pointer, misaligned pointer, non-positive size, head_dim not 64/128,
-                               G*W above KVS_MAX_Q_ROWS, overlapping units, unknown key_rule */
+                               G*W above KVS_MAX_Q_ROWS, overlapping units, unknown key_rule, causal not 0/1 */
   KVS_ERR_DTYPE = 2,        /* io_dtype is neither KVS_F32 nor KVS_BF16, or not the one the call supports */
   KVS_ERR_BUDGET = 3,       /* budget < n_sink + 1 + n_recent for a unit that has to merge (len > budget),
                                or budget < 1 */
@@ -84,6 +84,13 @@ typedef struct {
   const int64_t* out_row;   /* HOST [n_units] first row of the unit in K_out, V_out, counts_out;
                                ranges [out_row, out_row + min(len, budget)) must be disjoint         */
   kvs_key_rule key_rule;    /* KVS_RULE_HESSIAN (0) unless an ablation is wanted                     */
+  int32_t causal;           /* 0: every query row attends to the whole cache.  1: causal mask inside the
+                               window: the W queries of a head are those of the last W positions, whose
+                               Keys and Values are the unit's last W rows, and the query at window position
+                               w (row g*W + w of the unit's block of Q) attends to rows t <= len - W + w
+                               only (Eq. attn_def_vec over that prefix).  Needs len >= window
+                               (KVS_ERR_INVALID_ARG).  Read by kvs_score*, kvs_step*, kvs_sensitivity and
+                               kvs_step_per_query; kvs_decode_attention ignores it.                     */
 } kvs_problem;
 
 /* Bytes of DEVICE workspace (256-byte aligned) that the calls below need for this problem. */

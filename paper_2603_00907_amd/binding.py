@@ -35,7 +35,7 @@ class KvsProblemStruct(C.Structure):
         ("n_sink", C.c_int32), ("n_recent", C.c_int32), ("io_dtype", C.c_int), ("scale", C.c_float),
         ("len", C.POINTER(C.c_int32)), ("budget", C.POINTER(C.c_int32)),
         ("in_row", C.POINTER(C.c_int64)), ("out_row", C.POINTER(C.c_int64)),
-        ("key_rule", C.c_int),
+        ("key_rule", C.c_int), ("causal", C.c_int32),
     ]
 
 
@@ -107,7 +107,7 @@ class Problem:
     def __init__(self, *, lens: Sequence[int], budgets: Sequence[int], group: int, window: int, head_dim: int,
                  dtype: str, n_sink: int = 32, n_recent: int = 0, scale: float = 0.0,
                  in_rows: Optional[Sequence[int]] = None, out_rows: Optional[Sequence[int]] = None,
-                 key_rule=0):
+                 key_rule=0, causal: bool = False):
         n = len(lens)
         if in_rows is None:
             in_rows, acc = [], 0
@@ -136,7 +136,7 @@ class Problem:
             n_units=n, group=group, window=window, head_dim=head_dim, n_sink=n_sink, n_recent=n_recent,
             io_dtype=DTYPES[dtype] if isinstance(dtype, str) else int(dtype), scale=float(scale),
             len=self._len, budget=self._budget, in_row=self._in, out_row=self._out,
-            key_rule=KEY_RULES[key_rule] if isinstance(key_rule, str) else int(key_rule))
+            key_rule=KEY_RULES[key_rule] if isinstance(key_rule, str) else int(key_rule), causal=int(causal))
 
     @property
     def ref(self):

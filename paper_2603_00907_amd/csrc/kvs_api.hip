@@ -52,6 +52,8 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
   plan->shape.n_sink = p->n_sink;
   plan->shape.n_recent = p->n_recent;
   plan->shape.rule = (int)p->key_rule;
+  if (p->causal != 0 && p->causal != 1) return KVS_ERR_INVALID_ARG;
+  plan->shape.causal = p->causal ? p->window : 0;
   const double scale = (p->scale == 0.f) ? 1.0 / std::sqrt((double)p->head_dim) : (double)p->scale;
   plan->shape.scale_log2 = (float)(scale * 1.4426950408889634);
   plan->units.resize(p->n_units);
@@ -60,6 +62,7 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
     const long long len = p->len[u], budget = p->budget[u];
     // (kernels address a unit's rows with 32-bit byte offsets: KVS_MAX_LEN rows of 512 bytes stay below 4 GB)
     if (len < 1 || len > KVS_MAX_LEN || p->in_row[u] < 0 || p->out_row[u] < 0) return KVS_ERR_INVALID_ARG;
+    if (p->causal && len < p->window) return KVS_ERR_INVALID_ARG;   // the window's own rows are part of the cache
     if (budget < 1) return KVS_ERR_BUDGET;
     if (len > budget && budget < (long long)p->n_sink + 1 + p->n_recent) return KVS_ERR_BUDGET;
     Unit& un = plan->units[u];

@@ -64,6 +64,7 @@ struct Shape {
   float scale_log2; // logit scale * log2(e): logits are kept in the base-2 domain
   int stream;       // 1: the launch's K and V exceed the last-level cache, rows are read non-temporally
   int rule;         // kvs_key_rule of the merged Key
+  int causal;       // 0, or the window W when query row q only sees the rows up to its own position n - W + q % W
 };
 
 // Workspace carve-up (all offsets multiples of 256 bytes).
@@ -136,6 +137,11 @@ __device__ __forceinline__ float row_group_sum(float x) {
     x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));  // row_mirror
   if (LPR >= 32) x += __shfl_xor(x, 16, kWave);
   return x;
+}
+
+// Causal window: the last row that query row `qrow` of a unit with n rows attends to.
+__device__ __forceinline__ int last_seen_row(int causal_w, int n, int qrow) {
+  return causal_w > 0 ? n - causal_w + qrow % causal_w : 0x7fffffff;
 }
 
 // The unit's normalisers c[q] (written by the finalize kernel between the two sweeps) -> LDS.

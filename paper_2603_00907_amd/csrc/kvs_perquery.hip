@@ -188,6 +188,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_out_kernel(
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) bq[kk] = row_operand<D>(Qu, qrow, ok, kk, half);
     const float cq = ok ? c_row[(size_t)un.index * R + qrow] : INFINITY;   // exp2(-inf) = 0: no such row
+    const int lim = last_seen_row(sh.causal, un.len, qrow);               // causal window: last row attended to
     f32x16 accO[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) accO[db] = zero;
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_out_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int row = 8 * (v / 4) + 4 * half + (v % 4);
-        p[v] = (row >= shift) ? ex2(fmaf(acc[v], sl2, -cq)) : 0.f;
+        p[v] = (row >= shift && tile_base(j) + row <= lim) ? ex2(fmaf(acc[v], sl2, -cq)) : 0.f;
       }
       // as the operand of the next product, element i of k-step s is accumulator element 8 s + i
       bf16x8 ph[2], pl[2];
@@ -340,6 +341,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
       bol[kk] = row_operand<D>(Ol, qrow, ok, kk, half);
     }
     const float cq = ok ? c_row[(size_t)un.index * R + qrow] : INFINITY;
+    const int lim = last_seen_row(sh.causal, un.len, qrow);               // causal window: last row attended to
     const float ooq = ok ? oo[(size_t)un.index * R + qrow] : 0.f;
 
     // sums of the tile before -> memory (threads 0..31, one row each; the wavefronts in a fixed order)
@@ -416,6 +418,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         a[v] = ex2(fmaf(accS[v], sl2, -cq));              // alpha / R
+        if (tile_base(j) + 8 * (v / 4) + 4 * half + (v % 4) > lim) a[v] = 0.f;   // (never true without the mask)
         x[v] = accX[v];
       }
       float pa[16], pc[16];

@@ -71,6 +71,20 @@ __device__ __forceinline__ void logits_with_counts(f32x16 (&acc)[NACC], const in
   }
 }
 
+// Causal window: accumulator rows past the last row a query column attends to leave the softmax
+// (lim[i]: that row for the query column of accumulator i).
+template <int NACC>
+__device__ __forceinline__ void mask_causal(f32x16 (&acc)[NACC], const int (&lim)[NACC], int base_t, int half) {
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int t = base_t + 8 * (v / 4) + 4 * half + (v % 4);
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) {
+      if (t > lim[i]) acc[i][v] = -INFINITY;
+    }
+  }
+}
+
 #define KVS_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define KVS_GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
@@ -201,6 +215,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
         }
       }
     }
+    int lim[NT];                                      // causal window: last row each query column attends to
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) lim[nt] = last_seen_row(sh.causal, un.len, qp + wq * QROWS + nt * 32 + col);
     bool next_in_flight = (iters > 1) && issue_tile(wt + WT, 1);   // loads of the tile after the current one
 
     float m_run[NT], l_run[NT];
@@ -265,6 +282,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
           }
         }
       }
+      if (sh.causal > 0 && base_t + kTile > un.len - sh.causal + 1) mask_causal<NT>(acc, lim, base_t, half);
 
       if (cnt) logits_with_counts<NT>(acc, cnt, base_t, half, sl2);
       if (PHASE == 0) {
@@ -400,7 +418,7 @@ __device__ __forceinline__ void lds_read_2x2(bf16x8& b00, bf16x8& b01, bf16x8& b
 // tile (16 KB of LDS reads per tile, hidden behind the MFMAs already in the pipe).  The K tile is
 // moved to registers whole (all k-steps) at the start of a tile, which frees its single LDS buffer
 // for the wavefront's next tile at once: that load flies during both halves' MFMAs and softmax work.
-template <int D, int PHASE, bool STREAM>
+template <int D, int PHASE, bool STREAM, bool CAUSAL>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const int32_t* __restrict__ counts_in, float* __restrict__ alpha_bar, float2* __restrict__ stats_part,
@@ -471,6 +489,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
 #pragma unroll
   for (int b = 0; b < 4; ++b)
     cq[b] = (PHASE == 1 && b * 32 + col < R) ? c_row[(size_t)un.index * R + b * 32 + col] : INFINITY;
+
+  int lim[4];                               // causal window: last row each of the lane's query columns attends to
+#pragma unroll
+  for (int b = 0; b < 4; ++b) lim[b] = last_seen_row(CAUSAL ? sh.causal : 0, un.len, b * 32 + col);
 
   // the Q block, once per workgroup: every wavefront fetches 32 rows (rows past R repeat the last one)
   {
@@ -547,6 +569,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
           const int row = 8 * (v / 4) + 4 * half + (v % 4);
           if (row < shift) { acc[0][v] = -INFINITY; acc[1][v] = -INFINITY; }
         }
+      }
+      if (CAUSAL && base_t + kTile > un.len - sh.causal + 1) {
+        const int lim2[2] = {lim[2 * h], lim[2 * h + 1]};
+        mask_causal<2>(acc, lim2, base_t, half);
       }
       if (cnt) logits_with_counts<2>(acc, cnt, base_t, half, sl2);
       if (PHASE == 0) {
@@ -637,16 +663,16 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   }
 }
 
-template <int D, bool STREAM>
+template <int D, bool STREAM, bool CAUSAL>
 hipError_t launch_wide_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
                          const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
-  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0, STREAM>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
+  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0, STREAM, CAUSAL>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
                      (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
-  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
+  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
                      (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row);
   return hipGetLastError();
 }
@@ -654,8 +680,12 @@ hipError_t launch_wide_t(const UnitTable& tab, const Shape& sh, const void* Q, c
 template <int D>
 hipError_t launch_wide(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
                        const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
-  return sh.stream ? launch_wide_t<D, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
-                   : launch_wide_t<D, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+  if (sh.causal > 0) {
+    return sh.stream ? launch_wide_t<D, true, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
+                     : launch_wide_t<D, false, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+  }
+  return sh.stream ? launch_wide_t<D, true, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
+                   : launch_wide_t<D, false, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
 }
 
 template <int D, int NT, int WQ>

@@ -49,8 +49,10 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
   for (int qb = 0; qb < R; qb += kQB) {
     float qf[kQB][EPL];
     float cq[kQB];
+    int lim[kQB];                              // causal window: the last row query qb + j attends to
 #pragma unroll
     for (int j = 0; j < kQB; ++j) {
+      lim[j] = last_seen_row(sh.causal, un.len, qb + j);
       if (qb + j < R) {
         const uint4 raw = Qp[(size_t)(qb + j) * LPR];
         Piece<T>::unpack(raw, qf[j]);
@@ -77,6 +79,7 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
 #pragma unroll
         for (int i = 0; i < EPL; ++i) d = fmaf(qf[j][i], kf[i], d);
         const float s = fmaf(row_group_sum<LPR>(d), sh.scale_log2, lc);
+        if (t > lim[j]) continue;              // masked: no term in this row's softmax
         if (PHASE == 0) {
           if (s > m[j]) {
             l[j] = l[j] * __builtin_amdgcn_exp2f(m[j] - s) + 1.f;

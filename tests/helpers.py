@@ -45,17 +45,19 @@ class AcceptedUnit:
 
 
 def accepted_unit(w: Workload, layer: int, seq: int, head: int, n: Optional[int] = None,
-                  manifest: Optional[Dict[str, int]] = None) -> AcceptedUnit:
-    """First attempt of this unit that passes the acceptance rule, with its oracle result."""
+                  manifest: Optional[Dict[str, int]] = None, causal: bool = False) -> AcceptedUnit:
+    """First attempt of this unit that passes the acceptance rule, with its oracle result.
+    causal: with the causal mask inside the query window (its own acceptance, the manifest is not used)."""
     if n is None:
         n = unit_lengths(w)[seq]
     manifest = load_manifest() if manifest is None else manifest
-    start = manifest.get(manifest_key(w, layer, seq, head, n), 0)
+    start = 0 if causal else manifest.get(manifest_key(w, layer, seq, head, n), 0)
+    cw = w.window if causal else 0
     base = None
     for attempt in range(start, MAX_ATTEMPTS):
         u = generate_unit(w, layer, seq, head, attempt=attempt, n=n, kv_from=base)
         base = u
-        alpha_bar, o_bar = O.score(u.Q, u.K, u.V, counts=u.counts)
+        alpha_bar, o_bar = O.score(u.Q, u.K, u.V, counts=u.counts, causal_window=cw)
         gap = O.boundary_gap(alpha_bar, u.budget, w.n_sink, w.n_recent)
         if gap < GAP_MIN:
             continue
@@ -71,25 +73,27 @@ def accepted_unit(w: Workload, layer: int, seq: int, head: int, n: Optional[int]
 PQ_COND_MIN = 3e-2
 
 
-def accepted_unit_per_query(w: Workload, layer: int, seq: int, head: int, n: Optional[int] = None) -> AcceptedUnit:
+def accepted_unit_per_query(w: Workload, layer: int, seq: int, head: int, n: Optional[int] = None,
+                            causal: bool = False) -> AcceptedUnit:
     """The same for the per-query aggregation of the norms.  Its kernels recompute attention rows and outputs in
     bf16 products (split into two bf16 terms), so A_t and C_t carry relative differences of the order of 1e-4
     instead of fp32 rounding; a slot's Key moves by about that divided by its conditioning U / sum A_t, hence the
     larger minimum here (the 1e-2 bar of bf16 outputs then leaves a factor of three)."""
     if n is None:
         n = unit_lengths(w)[seq]
-    start = load_manifest().get(manifest_key(w, layer, seq, head, n), 0)
+    start = 0 if causal else load_manifest().get(manifest_key(w, layer, seq, head, n), 0)
+    cw = w.window if causal else 0
     base = None
     for attempt in range(start, MAX_ATTEMPTS):
         u = generate_unit(w, layer, seq, head, attempt=attempt, n=n, kv_from=base)
         base = u
         assert u.counts is None
-        alpha_bar, o_bar = O.score(u.Q, u.K, u.V)
+        alpha_bar, o_bar = O.score(u.Q, u.K, u.V, causal_window=cw)
         gap = O.boundary_gap(alpha_bar, u.budget, w.n_sink, w.n_recent)
         if gap < GAP_MIN:
             continue
         mask, slot = O.select(alpha_bar, u.budget, w.n_sink, w.n_recent)
-        norms = O.per_query_norms(u.Q, u.K, u.V)
+        norms = O.per_query_norms(u.Q, u.K, u.V, causal_window=cw)
         merged = O.merge_compact(u.K, u.V, alpha_bar, o_bar, mask, slot, norms=norms)
         cond = O.conditioning(merged)
         if cond < PQ_COND_MIN:
@@ -137,7 +141,7 @@ class DeviceBatch:
 
     def __init__(self, units: List, *, group: int, window: int, head_dim: int, dtype: str,
                  n_sink: int, n_recent: int = 0, budgets: Optional[List[int]] = None, gap_rows: int = 0,
-                 key_rule="hessian"):
+                 key_rule="hessian", causal: bool = False):
         import torch
         import paper_2603_00907_amd as kvs
         self.kvs = kvs
@@ -150,7 +154,7 @@ class DeviceBatch:
             acc += l + gap_rows
         self.problem = kvs.Problem(lens=lens, budgets=budgets, group=group, window=window, head_dim=head_dim,
                                    dtype=dtype, n_sink=n_sink, n_recent=n_recent, in_rows=in_rows,
-                                   key_rule=key_rule)
+                                   key_rule=key_rule, causal=causal)
         p = self.problem
         D = head_dim
         self.dtype = dtype

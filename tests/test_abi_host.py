@@ -212,3 +212,12 @@ def test_per_query_entry_points_validate_on_the_host():
         b["K_out"], o.get("V_out", b["V_out"]), b["counts"])
     assert norms(a_tok=None) == kvs.KVS_ERR_INVALID_ARG
     assert norms(V_out=b["K_out"]) == kvs.KVS_ERR_ALIAS
+
+
+def test_causal_flag_is_validated_on_the_host():
+    assert status_of(kvs.kvs_workspace_size, problem(causal=True)) == kvs.KVS_OK
+    assert status_of(kvs.kvs_workspace_size, problem(causal=2)) == kvs.KVS_ERR_INVALID_ARG
+    # the window's own rows are part of the cache: a unit shorter than the window cannot be masked
+    assert status_of(kvs.kvs_workspace_size, problem(causal=True, lens=[1024, 3], budgets=[512, 3])) \
+        == kvs.KVS_ERR_INVALID_ARG
+    assert status_of(kvs.kvs_workspace_size, problem(lens=[1024, 3], budgets=[512, 3])) == kvs.KVS_OK

@@ -322,11 +322,48 @@ def test_merge_bf16_output_rounds_to_nearest_even():
     assert (Vg[0] == V[0]).all() and (Ko.float().cpu().numpy()[3] == K[4]).all()
 
 
+CAUSAL_CASES = [
+    # base, dtype, D, G, W, lengths, path: every score kernel, masked rows across tile and chunk borders
+    ("tiny", "f32", 64, 2, 5, [777, 5], None),                  # vector-ALU kernel; a unit that is all window
+    ("llama8b_8k", "bf16", 128, 1, 20, [700, 33], None),        # 20 rows in one MFMA block
+    ("llama8b_8k", "bf16", 64, 2, 32, [900], None),             # 64 rows
+    ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053], None),     # 128 rows in one pass; a last chunk of 5 rows, all
+    ("llama8b_8k", "bf16", 128, 4, 32, [2053], "valu"),         # of them masked for most rows
+    ("llama8b_8k", "bf16", 128, 8, 32, [3000], None),           # 256 rows, two wavefronts per pass
+    ("stress128k", "bf16", 128, 8, 40, [1200], None),           # 320 rows, window 40 crosses two tiles
+    ("stream2560", "bf16", 128, 4, 32, [2560], None),           # with cardinalities (the tail rows are fresh tokens)
+]
+
+
+@pytest.mark.parametrize("base,dtype,D,G,W,lens,path", CAUSAL_CASES)
+def test_score_with_causal_window_matches_oracle(base, dtype, D, G, W, lens, path):
+    w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
+    units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
+    batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype=dtype, n_sink=w.n_sink, gap_rows=3, causal=True)
+    with env_override("KVS_SCORE_PATH", path):
+        batch.kvs.kvs_score_counts(batch.problem, batch.Q, batch.K, batch.V, batch.counts_in, batch.alpha_bar,
+                                   batch.o_bar, batch.ws, stream=batch.stream())
+        torch_sync()
+    batch.check_guards()
+    alpha = from_device(batch.alpha_bar)
+    obar = from_device(batch.o_bar)
+    for i, u in enumerate(units):
+        ra, ro = O.score(u.Q, u.K, u.V, counts=u.counts, causal_window=W)
+        plain, _ = O.score(u.Q, u.K, u.V, counts=u.counts)
+        assert np.max(np.abs(plain - ra) / ra) > 1e-2            # the mask matters on this input
+        r0 = batch.problem.in_rows[i]
+        got = alpha[r0:r0 + len(ra)]
+        assert np.isfinite(got).all()
+        assert np.max(np.abs(got - ra) / ra) < TOL_ALPHA, (i, np.max(np.abs(got - ra) / ra))
+        bound = TOL_ALPHA * (ra @ np.abs(O.slot_values(u.V, u.counts))) + 1e-7
+        assert (np.abs(obar[i] - ro) <= bound).all(), (i, np.max(np.abs(obar[i] - ro) / bound))
+
+
 # ------------------------------------------------------------------------------------------------
-def run_step(w, accepted, path=None):
+def run_step(w, accepted, path=None, causal=False):
     units = [a.inputs for a in accepted]
     batch = DeviceBatch(units, group=w.group, window=w.window, head_dim=w.head_dim, dtype=w.dtype,
-                        n_sink=w.n_sink, n_recent=w.n_recent)
+                        n_sink=w.n_sink, n_recent=w.n_recent, causal=causal)
     with env_override("KVS_SCORE_PATH", path):
         if batch.counts_in is None:
             batch.kvs.kvs_step(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out, batch.counts,
@@ -341,8 +378,8 @@ def run_step(w, accepted, path=None):
     return batch
 
 
-def check_step(w, accepted, path=None):
-    batch = run_step(w, accepted, path)
+def check_step(w, accepted, path=None, causal=False):
+    batch = run_step(w, accepted, path, causal)
     p = batch.problem
     mask, slot = batch.mask.cpu().numpy(), batch.slot.cpu().numpy()
     for i, a in enumerate(accepted):
@@ -374,6 +411,14 @@ def test_step_llama8b_8k_config(path):
     w = WORKLOADS["llama8b_8k"]
     heads = range(w.n_kv_heads) if path is None else range(2)
     check_step(w, [accepted_unit(w, 0, 0, h) for h in heads], path)
+
+
+def test_step_with_causal_window():
+    """The whole step with the causal mask inside the window, bf16 (MFMA score) and fp32 (vector-ALU score)."""
+    w = WORKLOADS["llama8b_8k"]
+    check_step(w, [accepted_unit(w, 0, 0, h, causal=True) for h in range(2)], causal=True)
+    w = WORKLOADS["tiny"]
+    check_step(w, [accepted_unit(w, 0, 0, 0, causal=True)], causal=True)
 
 
 def test_step_llama8b_32k_one_layer_full_size():

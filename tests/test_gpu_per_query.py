@@ -46,11 +46,14 @@ SENS_CASES = [
 ]
 
 
+@pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("base,D,G,W,lens", SENS_CASES)
-def test_sensitivity_matches_oracle(base, D, G, W, lens):
+def test_sensitivity_matches_oracle(base, D, G, W, lens, causal):
     w = variant(base, dtype="bf16", head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
     units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
-    batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype="bf16", n_sink=w.n_sink, gap_rows=3)
+    batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype="bf16", n_sink=w.n_sink, gap_rows=3,
+                        causal=causal)
+    cw = W if causal else 0
     a_tok, c_edge, ws = per_query_buffers(batch)
     batch.kvs.kvs_sensitivity(batch.problem, batch.Q, batch.K, batch.V, batch.alpha_bar, a_tok, c_edge, ws,
                               stream=batch.stream())
@@ -62,8 +65,8 @@ def test_sensitivity_matches_oracle(base, D, G, W, lens):
     for i, u in enumerate(units):
         n = lens[i]
         r0 = p.in_rows[i]
-        ra, _ = O.score(u.Q, u.K, u.V)
-        A_ref, C_ref = O.per_query_norms(u.Q, u.K, u.V)
+        ra, _ = O.score(u.Q, u.K, u.V, causal_window=cw)
+        A_ref, C_ref = O.per_query_norms(u.Q, u.K, u.V, causal_window=cw)
         assert np.max(np.abs(alpha[r0:r0 + n] - ra) / ra) < TOL_ALPHA
         gA, gC = A[r0:r0 + n], C[r0:r0 + n - 1]
         assert np.isfinite(gA).all() and np.isfinite(gC).all()
@@ -116,9 +119,9 @@ def test_merge_compact_norms_matches_oracle(base, dtype, D, lens, budgets, rule)
     compare_outputs(batch, refs, dtype)
 
 
-def check_step_per_query(w, accepted):
+def check_step_per_query(w, accepted, causal=False):
     batch = DeviceBatch([a.inputs for a in accepted], group=w.group, window=w.window, head_dim=w.head_dim,
-                        dtype=w.dtype, n_sink=w.n_sink, n_recent=w.n_recent)
+                        dtype=w.dtype, n_sink=w.n_sink, n_recent=w.n_recent, causal=causal)
     _, _, ws = per_query_buffers(batch)
     batch.kvs.kvs_step_per_query(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out, batch.counts,
                                  ws, slot_of_token_out=batch.slot, edge_mask_out=batch.mask, stream=batch.stream())
@@ -137,6 +140,11 @@ def check_step_per_query(w, accepted):
 def test_step_per_query_8k_config():
     w = WORKLOADS["llama8b_8k"]
     check_step_per_query(w, [accepted_unit_per_query(w, 0, 0, h) for h in range(3)])
+
+
+def test_step_per_query_with_causal_window():
+    w = WORKLOADS["llama8b_8k"]
+    check_step_per_query(w, [accepted_unit_per_query(w, 0, 0, h, causal=True) for h in range(2)], causal=True)
 
 
 def test_step_per_query_32k_two_heads_full_length():
