@@ -16,16 +16,19 @@
 //                         in the accumulator layout that IS the k-major operand layout of the next product.
 //                         P enters as a bf16 pair hi + lo, so that the rounding of P to bf16 does not limit
 //                         the accuracy of o.  Chunk partials go to memory and are added in chunk order.
-//   pq_out_reduce_kernel  o^{(q)} = R * sum of the chunk partials, stored as a bf16 pair hi + lo, and
+//   pq_out_reduce_kernel  o^{(q)} = R * sum of the chunk partials; -2 o^{(q)} stored as a bf16 pair hi + lo, and
 //                         ||o^{(q)}||^2.
-//   pq_norms_kernel       per tile of 32 tokens: S = K Q^T (logits), X = V O^T (hi and lo), then per (t, q)
-//                         ||v_t - o||^2 = ||v_t||^2 - 2 X + ||o||^2,
-//                         ||v_t + v_{t+1} - 2o||^2 = ||v_t + v_{t+1}||^2 - 4 (X_t + X_{t+1}) + 4 ||o||^2,
+//   pq_norms_kernel       per tile of 32 tokens: S' = Q K^T (logits), X' = (-2 O) V^T (hi and lo), then per (t, q)
+//                         (accumulated on top of ||o||^2), then per (t, q)
+//                         ||v_t - o||^2 = ||v_t||^2 + X',
+//                         ||v_t + v_{t+1} - 2o||^2 = ||v_t + v_{t+1}||^2 + 2 (X'_t + X'_{t+1}),
 //                         two square roots, and the sums over q.  Tiles overlap by one row (stride 31), so
 //                         the next token of every output row is in the same tile.
 // A workgroup has four wavefronts; wavefront w owns query rows 32w .. 32w+31 of a pass of 128 rows and
 // keeps their operands in registers; all four walk the same K and V tiles, staged through LDS (XOR-swizzled
 // 16-byte pieces, as in the score kernels).  Results do not depend on timing: no atomics, fixed orders.
+#include <type_traits>
+
 #include "kvs_device.h"
 
 namespace kvs {
@@ -267,13 +270,13 @@ __global__ __launch_bounds__(D) void pq_out_reduce_kernel(const UnitTable tab, c
   const int d = threadIdx.x;
   float s = 0.f;
   for (int c = 0; c < un.n_chunks; ++c) s += o_part[((size_t)(un.chunk_base + c) * R + q) * D + d];
-  const float o = s * (float)R;
-  const uint32_t hi = f32_to_bf16(o);
-  const uint32_t lo = f32_to_bf16(o - bf16_lo(hi));
+  const float m2o = -2.f * (s * (float)R);                 // stored with the factor of ||v - o||^2 = ||v||^2 - 2 v.o + ||o||^2
+  const uint32_t hi = f32_to_bf16(m2o);
+  const uint32_t lo = f32_to_bf16(m2o - bf16_lo(hi));
   const size_t idx = ((size_t)un.index * R + q) * D + d;
   o_hi[idx] = (uint16_t)hi;
   o_lo[idx] = (uint16_t)lo;
-  const float oe = bf16_lo(hi) + bf16_lo(lo);              // the value the products below see
+  const float oe = -0.5f * (bf16_lo(hi) + bf16_lo(lo));    // the o the products below see
   float ss = oe * oe;
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) ss += __shfl_xor(ss, m, kWave);
@@ -289,6 +292,11 @@ __global__ __launch_bounds__(D) void pq_out_reduce_kernel(const UnitTable tab, c
 
 // ------------------------------------------------------------------------------------------------
 // A_t and C_t of every token of the chunk.
+//
+// Both products are taken with the query rows as the accumulator ROWS: S'[q, t] = Q K^T, X'[q, t] = (-2 O) V^T.
+// A lane then holds ONE token (column t = lane % 32) and 16 query rows, so the sums over q are plain
+// register additions (plus one exchange between the wavefront's halves), and token t + 1 is the next lane
+// (one DPP wavefront shift).  Per (t, q): one exp2, two square roots, eleven other instructions.
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
@@ -301,9 +309,11 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
   constexpr int PPT = TL::LPR / 8;          // pieces per thread when 8 threads share a row
   __shared__ __attribute__((aligned(16))) unsigned char sm_k[2][TL::BYTES];
   __shared__ __attribute__((aligned(16))) unsigned char sm_v[2][TL::BYTES];
-  __shared__ __attribute__((aligned(16))) float sm_vv[2][kTile];     // ||v_r||^2
-  __shared__ __attribute__((aligned(16))) float sm_vp[2][kTile];     // ||v_r + v_{r+1}||^2
+  __shared__ float sm_vv[2][kTile + 1];                              // ||v_r||^2 (one spare entry: the last row's "next")
+  __shared__ float sm_vd[2][kTile];                                  // v_r . v_{r+1}
   __shared__ float2 sm_out[2][kWaves][kTile];                        // (sum_q A, sum_q C) of every wavefront
+  __shared__ __attribute__((aligned(16))) float sm_negc[kPassRows];  // per query row of the pass: -c[q]
+  __shared__ __attribute__((aligned(16))) int sm_lim[kPassRows];     // causal window: last row attended to
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -333,16 +343,25 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
   for (int qp = 0; qp < R; qp += kPassRows) {
     const int qrow = qp + 32 * wave + col;
     const bool ok = qrow < R;
-    bf16x8 bq[KS], boh[KS], bol[KS];
+    bf16x8 bq[KS], boh[KS], bol[KS];        // this wavefront's 32 query rows: Q, and -2 o as hi + lo
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
       bq[kk] = row_operand<D>(Qu, qrow, ok, kk, half);
       boh[kk] = row_operand<D>(Oh, qrow, ok, kk, half);
       bol[kk] = row_operand<D>(Ol, qrow, ok, kk, half);
     }
-    const float cq = ok ? c_row[(size_t)un.index * R + qrow] : INFINITY;
-    const int lim = last_seen_row(sh.causal, un.len, qrow);               // causal window: last row attended to
-    const float ooq = ok ? oo[(size_t)un.index * R + qrow] : 0.f;
+    if (tid < kPassRows) {                  // (read after the first tile's barriers)
+      const int q = qp + tid;
+      sm_negc[tid] = (q < R) ? -c_row[(size_t)un.index * R + q] : -INFINITY;   // exp2(-inf) = 0: no such row
+      sm_lim[tid] = last_seen_row(sh.causal, un.len, q);
+    }
+    // ||o^{(q)}||^2 of this lane's 16 accumulator rows: the value the X' accumulator starts from
+    f32x16 oo_init;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int q = qp + 32 * wave + 8 * (v / 4) + 4 * half + (v % 4);
+      oo_init[v] = (q < R) ? oo[(size_t)un.index * R + q] : 0.f;
+    }
 
     // sums of the tile before -> memory (threads 0..31, one row each; the wavefronts in a fixed order)
     auto flush = [&](int j) {
@@ -380,7 +399,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
       {
         const int r = tid / 8, part = tid % 8;
         const int rn = min(r + 1, kTile - 1);
-        float s_rr = 0.f, s_nn = 0.f, s_rn = 0.f;
+        float s_rr = 0.f, s_rn = 0.f;
 #pragma unroll
         for (int x = 0; x < PPT; ++x) {
           float a[8], b[8];
@@ -389,65 +408,70 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             s_rr = fmaf(a[i], a[i], s_rr);
-            s_nn = fmaf(b[i], b[i], s_nn);
             s_rn = fmaf(a[i], b[i], s_rn);
           }
         }
         s_rr = row_group_sum<8>(s_rr);
-        s_nn = row_group_sum<8>(s_nn);
         s_rn = row_group_sum<8>(s_rn);
         if (part == 0) {
           sm_vv[buf][r] = s_rr;
-          sm_vp[buf][r] = fmaf(2.f, s_rn, s_rr + s_nn);
+          sm_vd[buf][r] = s_rn;
+          if (r == kTile - 1) sm_vv[buf][kTile] = 0.f;       // read by the last column, whose edge is never used
         }
       }
-      // S = K Q^T and X = V O^T for this wavefront's 32 query rows
-      f32x16 accS = zero, accX = zero;
+      // S' = Q K^T and X' = (-2 O) V^T for this wavefront's 32 query rows
+      f32x16 accS = zero, accX = oo_init;     // X'' = ||o||^2 - 2 v.o
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk)
-        accS = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::operand(sm_k[buf], col, kk, half), bq[kk], accS, 0, 0, 0);
+        accS = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[kk], TL::operand(sm_k[buf], col, kk, half), accS, 0, 0, 0);
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
-        const bf16x8 av = TL::operand(sm_v[buf], col, kk, half);
-        accX = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, boh[kk], accX, 0, 0, 0);
-        accX = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bol[kk], accX, 0, 0, 0);
+        const bf16x8 bv = TL::operand(sm_v[buf], col, kk, half);
+        accX = __builtin_amdgcn_mfma_f32_32x32x16_bf16(boh[kk], bv, accX, 0, 0, 0);
+        accX = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bol[kk], bv, accX, 0, 0, 0);
       }
       __syncthreads();                      // sm_vv / sm_vp of this tile are complete
-      // accumulator element v: token row 8 (v / 4) + 4 half + v % 4, query column `col`
-      float a[16], x[16];
+      // accumulator element v: query row 32 wave + 8 (v / 4) + 4 half + v % 4 of the pass, token column `col`
+      const float vv = sm_vv[buf][col];
+      const float vp = fmaf(2.f, sm_vd[buf][col], vv + sm_vv[buf][col + 1]);   // ||v_t + v_{t+1}||^2
+      const int t_abs = tile_base(j) + col;
+      float sumA = 0.f, sumC = 0.f;
+      // TAIL: the tile reaches into the causal window's masked rows (a uniform condition)
+      auto rows = [&](auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        a[v] = ex2(fmaf(accS[v], sl2, -cq));              // alpha / R
-        if (tile_base(j) + 8 * (v / 4) + 4 * half + (v % 4) > lim) a[v] = 0.f;   // (never true without the mask)
-        x[v] = accX[v];
-      }
-      float pa[16], pc[16];
+        for (int g = 0; g < 4; ++g) {
+          const int q0 = 32 * wave + 8 * g + 4 * half;
+          const float4 nc4 = *reinterpret_cast<const float4*>(&sm_negc[q0]);
+          const float nc[4] = {nc4.x, nc4.y, nc4.z, nc4.w};
+          int lim[4] = {0, 0, 0, 0};
+          if (TAIL) {
+            const int4 l4 = *reinterpret_cast<const int4*>(&sm_lim[q0]);
+            lim[0] = l4.x; lim[1] = l4.y; lim[2] = l4.z; lim[3] = l4.w;
+          }
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        // the row after element 4 g + 3 lives in the other half of the wavefront
-        const float a_far = __shfl_xor(half ? a[4 * g] : a[(4 * g + 4) & 15], 32, kWave);
-        const float x_far = __shfl_xor(half ? x[4 * g] : x[(4 * g + 4) & 15], 32, kWave);
-        const float4 vv4 = *reinterpret_cast<const float4*>(&sm_vv[buf][8 * g + 4 * half]);
-        const float4 vp4 = *reinterpret_cast<const float4*>(&sm_vp[buf][8 * g + 4 * half]);
-        const float vv[4] = {vv4.x, vv4.y, vv4.z, vv4.w};
-        const float vp[4] = {vp4.x, vp4.y, vp4.z, vp4.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int v = 4 * g + i;
-          const float an = (i < 3) ? a[(v + 1) & 15] : a_far;
-          const float xn = (i < 3) ? x[(v + 1) & 15] : x_far;
-          const float d2 = fmaxf(fmaf(-2.f, x[v], vv[i]) + ooq, 0.f);
-          const float p2 = fmaxf(fmaf(-4.f, x[v] + xn, vp[i]) + 4.f * ooq, 0.f);
-          pa[v] = a[v] * fabsf(fmaf(-2.f * Rf, a[v], 1.f)) * __builtin_amdgcn_sqrtf(d2);
-          pc[v] = a[v] * (Rf * an) * __builtin_amdgcn_sqrtf(p2);
+          for (int i = 0; i < 4; ++i) {
+            const int v = 4 * g + i;
+            float a = ex2(fmaf(accS[v], sl2, nc[i]));                      // alpha / R
+            if (TAIL && t_abs > lim[i]) a = 0.f;
+            const float x = accX[v];                                       // ||o||^2 - 2 v_t . o
+            // the same quantities of token t + 1: the next lane (the last column's are not used)
+            const float a_n = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x130, 0xF, 0xF, true));
+            const float x_n = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x130, 0xF, 0xF, true));
+            const float d2 = vv + x;                                       // ||v_t - o||^2
+            const float p2 = fmaf(2.f, x + x_n, vp);                       // ||v_t + v_{t+1} - 2o||^2
+            // (a rounding-size negative value stands for zero: the square roots take the magnitude)
+            sumA = fmaf(a * fabsf(fmaf(-2.f * Rf, a, 1.f)), __builtin_amdgcn_sqrtf(fabsf(d2)), sumA);
+            sumC = fmaf(a * a_n, __builtin_amdgcn_sqrtf(fabsf(p2)), sumC);
+          }
+          __builtin_amdgcn_sched_barrier(0);  // four rows at a time: interleaving all sixteen runs out of registers
         }
-      }
-      colsum16(pa, lane);
-      colsum16(pc, lane);
-      if ((lane & 1) == 0) {
-        const int v = (lane >> 1) & 15;
-        sm_out[buf][wave][8 * (v / 4) + 4 * half + (v % 4)] = make_float2(pa[0], pc[0]);
-      }
+      };
+      if (sh.causal > 0 && tile_base(j) + kTile > un.len - sh.causal + 1) rows(std::true_type{});
+      else rows(std::false_type{});
+      sumA += __shfl_xor(sumA, 32, kWave);    // the other half's 16 query rows
+      sumC += __shfl_xor(sumC, 32, kWave);
+      if (half == 0) sm_out[buf][wave][col] = make_float2(sumA, sumC * Rf);
     }
     __syncthreads();
     flush(ntiles - 1);
