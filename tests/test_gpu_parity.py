@@ -430,6 +430,67 @@ def test_step_llama8b_32k_one_layer_full_size():
     assert torch.equal(batch.K_out.view(torch.int16), b2.K_out.view(torch.int16))     # run-to-run bitwise
 
 
+def test_step_headline_workload_in_the_launch_configuration_of_the_bench():
+    """All 32 layers x 8 KV heads of the headline workload as the 256 units of ONE kvs_step call, which is what
+    bench.py times (launch groups of 64 units = 8 layers).  Four sampled units, the first and the last of the
+    call and the two on either side of the first group border, are compared with the oracle like any other
+    unit; every unit must satisfy the invariants that hold at any size."""
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    import paper_2603_00907_amd as kvs
+    from helpers import to_device
+    from workloads import unit_budget
+    w = WORKLOADS["llama8b_32k"]
+    H, D, R, n = w.n_kv_heads, w.head_dim, w.q_rows, unit_lengths(w)[0]
+    B = unit_budget(w, n)
+    nu = w.layers * H
+    sampled = {(0, 0): None, (7, 7): None, (8, 0): None, (w.layers - 1, H - 1): None}
+    for layer, head in sampled:
+        sampled[(layer, head)] = accepted_unit(w, layer, 0, head)
+    K = torch.empty((nu * n, D), dtype=torch.bfloat16, device="cuda")
+    V = torch.empty_like(K)
+    Q = torch.empty((nu, R, D), dtype=torch.bfloat16, device="cuda")
+
+    def unit(layer, head):
+        a = sampled.get((layer, head))
+        return a.inputs if a is not None else generate_unit(w, layer, 0, head)
+
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+        for layer in range(w.layers):
+            for head, u in enumerate(pool.map(lambda h: unit(layer, h), range(H))):
+                i = layer * H + head
+                K[i * n:(i + 1) * n] = to_device(u.K, "bf16")
+                V[i * n:(i + 1) * n] = to_device(u.V, "bf16")
+                Q[i] = to_device(u.Q.reshape(R, D), "bf16")
+    p = kvs.Problem(lens=[n] * nu, budgets=[B] * nu, group=w.group, window=w.window, head_dim=D, dtype="bf16",
+                    n_sink=w.n_sink, n_recent=w.n_recent)
+    K_out = torch.empty((p.rows_out, D), dtype=torch.bfloat16, device="cuda")
+    V_out = torch.empty_like(K_out)
+    counts = torch.empty(p.rows_out, dtype=torch.int32, device="cuda")
+    mask = torch.empty(p.rows_in, dtype=torch.uint8, device="cuda")
+    slot = torch.empty(p.rows_in, dtype=torch.int32, device="cuda")
+    ws = torch.empty(kvs.kvs_workspace_size(p), dtype=torch.uint8, device="cuda")
+    kvs.kvs_step(p, Q, K, V, K_out, V_out, counts, ws, slot_of_token_out=slot, edge_mask_out=mask,
+                 stream=torch.cuda.current_stream().cuda_stream)
+    torch_sync()
+    # every unit: r edges selected, none in the sink, slots numbered 0 .. B-1, cardinalities add up to n
+    m2, s2, c2 = mask.view(nu, n), slot.view(nu, n), counts.view(nu, B)
+    assert (m2.sum(dim=1) == n - B).all()
+    assert (m2[:, :w.n_sink] == 0).all() and (m2[:, -1] == 0).all()
+    assert (s2[:, 0] == 0).all() and (s2[:, -1] == B - 1).all()
+    assert (c2.sum(dim=1) == n).all() and (c2 >= 1).all()
+    assert torch.isfinite(K_out.float()).all() and torch.isfinite(V_out.float()).all()
+    for (layer, head), a in sampled.items():
+        i = layer * H + head
+        assert (m2[i].cpu().numpy() == a.ref.mask).all(), f"unit {i}: selected edges differ (gap {a.gap:.2e})"
+        assert (s2[i].cpu().numpy() == a.ref.slot).all(), f"unit {i}: slot map differs"
+        ref = a.ref.merged
+        assert (c2[i].cpu().numpy() == ref.counts).all()
+        ek = rel_err_rows(from_device(K_out[i * B:(i + 1) * B]), ref.K_out)
+        ev = rel_err_rows(from_device(V_out[i * B:(i + 1) * B]), ref.V_out)
+        assert ek <= TOL_KV["bf16"] and ev <= TOL_KV["bf16"], (i, ek, ev)
+
+
 def test_step_ragged_batch_reduced():
     """Ragged batch recipe (lengths and rho drawn per sequence) on 5 of the 16 sequences, 2 heads each, capped
     at 20000 tokens so the oracle finishes in seconds; more than 64 units are covered by the select test."""
