@@ -142,8 +142,13 @@ __device__ __forceinline__ void colsum16(float (&p)[16], int lane) {
 
 // ------------------------------------------------------------------------------------------------
 // o_part[(chunk of the launch), q, :] = sum over the chunk's tokens of (alpha^{(q)}_t / R) V[t]
+// Two workgroups per CU: the 64 accumulator registers of O^T and the 32 of the Q operands leave no room for a
+// third wavefront per SIMD (at 168 registers the compiler spills inside the tile loop).
+#ifndef KVS_PQ_OUT_OCC
+#define KVS_PQ_OUT_OCC 2
+#endif
 template <int D>
-__global__ __launch_bounds__(kThreads, 2) void pq_out_kernel(
+__global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ V, const float* __restrict__ c_row, float* __restrict__ o_part) {
   typedef Tile<D> TL;
@@ -218,14 +223,23 @@ __global__ __launch_bounds__(kThreads, 2) void pq_out_kernel(
       // accumulator element v: token row 8 (v / 4) + 4 half + v % 4, query column `col`
       float p[16];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = 8 * (v / 4) + 4 * half + (v % 4);
-        p[v] = (row >= shift && tile_base(j) + row <= lim) ? ex2(fmaf(acc[v], sl2, -cq)) : 0.f;
+      for (int v = 0; v < 16; ++v) p[v] = ex2(fmaf(acc[v], sl2, -cq));
+      // rows of the tile before (a moved-back last tile) and rows behind the causal window's limit drop out;
+      // both are rare and uniform per tile, so the common tile carries no per-element test
+      if (shift > 0 || (sh.causal > 0 && tile_base(j) + kTile > un.len - sh.causal + 1)) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = 8 * (v / 4) + 4 * half + (v % 4);
+          p[v] = (row >= shift && tile_base(j) + row <= lim) ? p[v] : 0.f;
+        }
       }
       // as the operand of the next product, element i of k-step s is accumulator element 8 s + i
       bf16x8 ph[2], pl[2];
       split8(p, ph[0], pl[0]);
       split8(p + 8, ph[1], pl[1]);
+      // (taking all four blocks of V through the identity first, to run them beside the exponentials and to
+      // have four independent accumulators in the products below, was measured 6 % slower: 64 more live
+      // registers)
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         // the block V[tile rows, 32 db .. 32 db + 31] into the same (token-major) accumulator layout
