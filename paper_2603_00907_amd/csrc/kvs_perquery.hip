@@ -107,39 +107,6 @@ __device__ __forceinline__ bf16x8 row_operand(const uint16_t* __restrict__ m, in
   return as_bf16x8(raw);
 }
 
-// Sum over the 32 lanes of a half-wavefront of 16 values per lane: reduce-scatter, afterwards the even
-// lanes hold in p[0] the total of value index v = (lane >> 1) & 15.
-__device__ __forceinline__ void colsum16(float (&p)[16], int lane) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const bool up = lane & 16;
-    const float send = up ? p[i] : p[i + 8];
-    const float keep = up ? p[i + 8] : p[i];
-    p[i] = keep + __shfl_xor(send, 16, kWave);
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const bool up = lane & 8;
-    const float send = up ? p[i] : p[i + 4];
-    const float keep = up ? p[i + 4] : p[i];
-    p[i] = keep + __shfl_xor(send, 8, kWave);
-  }
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const bool up = lane & 4;
-    const float send = up ? p[i] : p[i + 2];
-    const float keep = up ? p[i + 2] : p[i];
-    p[i] = keep + __shfl_xor(send, 4, kWave);
-  }
-  {
-    const bool up = lane & 2;
-    const float send = up ? p[0] : p[1];
-    const float keep = up ? p[1] : p[0];
-    p[0] = keep + __shfl_xor(send, 2, kWave);
-  }
-  p[0] += __shfl_xor(p[0], 1, kWave);
-}
-
 // ------------------------------------------------------------------------------------------------
 // o_part[(chunk of the launch), q, :] = sum over the chunk's tokens of (alpha^{(q)}_t / R) V[t]
 // Two workgroups per CU: the 64 accumulator registers of O^T and the 32 of the Q operands leave no room for a

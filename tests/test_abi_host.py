@@ -221,3 +221,14 @@ def test_causal_flag_is_validated_on_the_host():
     assert status_of(kvs.kvs_workspace_size, problem(causal=True, lens=[1024, 3], budgets=[512, 3])) \
         == kvs.KVS_ERR_INVALID_ARG
     assert status_of(kvs.kvs_workspace_size, problem(lens=[1024, 3], budgets=[512, 3])) == kvs.KVS_OK
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; any other --gpus value ends with a message and a non-zero status before
+    anything touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
