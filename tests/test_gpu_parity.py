@@ -576,15 +576,21 @@ def test_step_passthrough_and_single_token_units():
 
 # ------------------------------------------------------------------------------------------------
 # the consumer: decode attention over a (merged) cache
-@pytest.mark.parametrize("base,dtype,D,G,W,lens", [
-    ("tiny", "f32", 64, 1, 1, [1024]),
-    ("tiny", "f32", 128, 3, 2, [700, 41, 5000]),
-    ("llama8b_8k", "bf16", 128, 4, 1, [2048, 300]),
-    ("stream2560", "bf16", 128, 4, 1, [2560, 2049]),
-    ("stream2560", "bf16", 64, 4, 3, [1111]),
-    ("stream2560", "f32", 64, 2, 5, [2300]),
+@pytest.mark.parametrize("base,dtype,D,G,W,lens,path", [
+    ("tiny", "f32", 64, 1, 1, [1024], None),
+    ("tiny", "f32", 128, 3, 2, [700, 41, 5000], None),
+    ("llama8b_8k", "bf16", 128, 4, 1, [2048, 300], "mfma"),          # MFMA kernel, plain tokens
+    ("llama8b_8k", "bf16", 128, 4, 1, [2048, 300], None),            # (four rows: the vector-ALU kernel)
+    ("stream2560", "bf16", 128, 4, 1, [2560, 2049], "mfma"),         # with cardinalities; a chunk of one row
+    ("stream2560", "bf16", 128, 4, 1, [2560, 2049], None),
+    ("stream2560", "bf16", 64, 4, 3, [1111, 32, 33], None),          # head dim 64; units of one tile and one row more
+    ("stream2560", "bf16", 64, 4, 3, [1111], "valu"),
+    ("stream2560", "bf16", 128, 8, 5, [777], None),                  # 40 query rows: two blocks of 32
+    ("stream2560", "bf16", 128, 8, 8, [40000], None),                # 64 query rows; chunks longer than 256 rows
+    ("llama8b_8k", "bf16", 128, 4, 1, [500, 31], None),              # a unit below 32 rows: the vector-ALU kernel
+    ("stream2560", "f32", 64, 2, 5, [2300], None),
 ])
-def test_decode_attention_matches_oracle(base, dtype, D, G, W, lens):
+def test_decode_attention_matches_oracle(base, dtype, D, G, W, lens, path):
     import torch
     w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
     units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
@@ -593,8 +599,9 @@ def test_decode_attention_matches_oracle(base, dtype, D, G, W, lens):
     R = G * W
     out = torch.full((len(units) + 1, R, D), -7.0, dtype=torch.float32, device="cuda")
     ws = torch.empty(batch.kvs.kvs_decode_workspace_size(p), dtype=torch.uint8, device="cuda")
-    batch.kvs.kvs_decode_attention(p, batch.Q, batch.K, batch.V, batch.counts_in, out, ws, stream=batch.stream())
-    torch_sync()
+    with env_override("KVS_DECODE_PATH", path):
+        batch.kvs.kvs_decode_attention(p, batch.Q, batch.K, batch.V, batch.counts_in, out, ws, stream=batch.stream())
+        torch_sync()
     assert (out[len(units):] == -7.0).all()
     got = out.cpu().numpy()
     for i, u in enumerate(units):
