@@ -135,7 +135,8 @@ def check_select(alphas, budgets, n_sink, n_recent):
     (1024, 512, 32, 0, "dirichlet"), (1000, 100, 32, 0, "lognormal"), (5000, 4999, 32, 0, "lognormal"),
     (5000, 33, 32, 0, "lognormal"), (4096, 1024, 0, 0, "ties"), (4096, 1024, 32, 100, "ties"),
     (3000, 700, 32, 0, "uniform"), (32801, 4096, 32, 0, "lognormal"), (32802, 4096, 32, 0, "lognormal"),
-    (40000, 10000, 32, 0, "ties"), (131072, 8192, 32, 0, "lognormal"), (50, 50, 32, 0, "dirichlet"),
+    (40000, 10000, 32, 0, "ties"), (131072, 8192, 32, 0, "lognormal"), (1 << 22, 1 << 20, 32, 0, "lognormal"),
+    (50, 50, 32, 0, "dirichlet"),
     (50, 80, 32, 0, "dirichlet"), (34, 33, 32, 0, "dirichlet"), (1, 1, 32, 0, "dirichlet"),
     (20, 6, 2, 3, "zeros")])
 def test_select_bit_exact(n, budget, s, nr, kind):
@@ -572,6 +573,61 @@ def test_step_passthrough_and_single_token_units():
         r0 = batch.problem.out_rows[i]
         assert (Ko[r0:r0 + u.n] == u.K).all() and (Vo[r0:r0 + u.n] == u.V).all()
         assert (cnt[r0:r0 + u.n] == 1).all()
+
+
+def test_step_at_the_maximum_length():
+    """One unit of KVS_MAX_LEN = 2^22 rows (bf16, head dim 64, 16 query rows) merged to a quarter.  At this length
+    neighbouring edge scores at the budget boundary differ by less than fp32 resolves, so the selected set is not
+    unique: it is checked for validity (the right number of edges, none of the selected scores above an
+    unselected one beyond the tolerance of alpha_bar), slot map and cardinalities must follow from it exactly,
+    merged Values are compared for every slot and merged Keys on windows the oracle merges with the same edges."""
+    import torch
+    import paper_2603_00907_amd as kvs
+    from helpers import to_device
+    from workloads import gaussian_unit
+    n, D, G, W, n_sink = 1 << 22, 64, 4, 4, 32
+    B = n // 4
+    Q, K, V = gaussian_unit(1, n, D, G, W, "bf16")
+    p = kvs.Problem(lens=[n], budgets=[B], group=G, window=W, head_dim=D, dtype="bf16", n_sink=n_sink)
+    Kd, Vd, Qd = to_device(K, "bf16"), to_device(V, "bf16"), to_device(Q.reshape(1, G * W, D), "bf16")
+    K_out = torch.empty((B, D), dtype=torch.bfloat16, device="cuda")
+    V_out = torch.empty_like(K_out)
+    counts = torch.empty(B, dtype=torch.int32, device="cuda")
+    mask_d = torch.empty(n, dtype=torch.uint8, device="cuda")
+    slot_d = torch.empty(n, dtype=torch.int32, device="cuda")
+    ws = torch.empty(kvs.kvs_workspace_size(p), dtype=torch.uint8, device="cuda")
+    kvs.kvs_step(p, Qd, Kd, Vd, K_out, V_out, counts, ws, slot_of_token_out=slot_d, edge_mask_out=mask_d,
+                 stream=torch.cuda.current_stream().cuda_stream)
+    torch_sync()
+    mask, slot, cnt = mask_d.cpu().numpy(), slot_d.cpu().numpy(), counts.cpu().numpy()
+    # the selection is a valid one
+    alpha_bar, o_bar = O.score(Q, K, V)
+    sigma = alpha_bar[:-1] + alpha_bar[1:]
+    sel = mask[:-1] == 1
+    assert sel.sum() == n - B and mask[-1] == 0 and not sel[:n_sink].any()
+    assert sigma[sel].max() <= sigma[n_sink:][~sel[n_sink:]].min() * (1 + 4 * TOL_ALPHA)
+    # slot map and cardinalities follow from the edges
+    starts = np.ones(n, dtype=np.int64)
+    starts[1:] = 1 - mask[:-1]
+    assert (slot == np.cumsum(starts) - 1).all()
+    first = np.flatnonzero(starts)
+    assert len(first) == B
+    assert (cnt == np.diff(np.append(first, n))).all()
+    # every merged Value row is the sum of its run
+    Vo = from_device(V_out)
+    want_v = np.add.reduceat(V.astype(np.float64), first, axis=0)
+    assert rel_err_rows(Vo, want_v) <= TOL_KV["bf16"]
+    # merged Keys on windows of whole slots: head of the cache, two places inside, the tail
+    Ko = from_device(K_out)
+    for s0 in (0, B // 3, (2 * B) // 3 + 7, B - 700):
+        s1 = s0 + 700
+        a, b = first[s0], (first[s1] if s1 < B else n)
+        ref = O.merge_compact(K[a:b], V[a:b], alpha_bar[a:b], o_bar, mask[a:b] * (np.arange(a, b) < b - 1),
+                              slot[a:b] - s0)
+        assert (cnt[s0:s1] == ref.counts).all()
+        assert rel_err_rows(Ko[s0:s1], ref.K_out) <= TOL_KV["bf16"], s0
+        single = ref.n_rows == 1
+        assert (Ko[s0:s1][single] == ref.K_out[single]).all()
 
 
 # ------------------------------------------------------------------------------------------------

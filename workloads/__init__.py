@@ -12,6 +12,7 @@ from .generator import (
     UnitInputs,
     bf16_bits_to_f32,
     f32_to_bf16_bits,
+    gaussian_unit,
     generate_unit,
     unit_budget,
     unit_lengths,
@@ -23,6 +24,7 @@ __all__ = [
     "get_workload",
     "UnitInputs",
     "generate_unit",
+    "gaussian_unit",
     "unit_lengths",
     "unit_budget",
     "f32_to_bf16_bits",

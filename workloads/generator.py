@@ -149,3 +149,14 @@ def generate_unit(w: Workload, layer: int, seq: int, head: int, attempt: int = 0
     Q = _round_io(_draw_q(w, layer, seq, head, attempt), w.dtype)
     return UnitInputs(layer=layer, seq=seq, head=head, attempt=attempt, n=n,
                       budget=unit_budget(w, n), rho=rho, Q=Q, K=K, V=V, counts=counts)
+
+
+def gaussian_unit(seed: int, n: int, head_dim: int, group: int, window: int, dtype: str, k_scale: float = 2.0):
+    """A unit of independent Gaussian rows (no correlation along tokens, no outlier channels), for tests whose
+    length makes the recipe above too slow to draw: (Q [G, W, D], K [n, D], V [n, D]) as float32 arrays that are
+    exactly representable in `dtype`."""
+    rng = np.random.default_rng([0x6B7673, seed])
+    K = _round_io(k_scale * rng.standard_normal((n, head_dim), dtype=np.float32), dtype)
+    V = _round_io(rng.standard_normal((n, head_dim), dtype=np.float32), dtype)
+    Q = _round_io(rng.standard_normal((group, window, head_dim), dtype=np.float32), dtype)
+    return Q, K, V
