@@ -78,8 +78,8 @@ def measured_traffic(workload):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (units are independent; sharding is by KV head, "
-              "see DESIGN.md); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (units are independent: more GPUs would each take a share "
+              "of the KV heads, with nothing to exchange); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
