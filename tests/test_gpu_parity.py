@@ -409,6 +409,48 @@ def test_step_tiny_config_is_deterministic():
     assert torch.equal(b1.counts, b2.counts)
 
 
+def test_step_replayed_from_a_hip_graph_equals_the_eager_step():
+    """The library never allocates, memsets or synchronises, so a step can be captured as it is.  The graph is
+    replayed three times, with the outputs scrubbed and other work on the device in between; every replay must
+    reproduce the eager result bit for bit."""
+    import torch
+    w = WORKLOADS["llama8b_8k"].scaled(length=("fixed", 3000), budget=("fixed", 800))
+    acc = [accepted_unit(w, 0, 0, h) for h in range(3)]
+    eager = check_step(w, acc)
+    batch = DeviceBatch([a.inputs for a in acc], group=w.group, window=w.window, head_dim=w.head_dim, dtype=w.dtype,
+                        n_sink=w.n_sink)
+
+    def step(stream):
+        batch.kvs.kvs_step(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out, batch.counts,
+                           batch.ws, slot_of_token_out=batch.slot, edge_mask_out=batch.mask, stream=stream)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step(side.cuda_stream)                               # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    n_out = batch.problem.rows_out
+    for replay in range(3):
+        batch.K_out.fill_(512.0)                             # eager work between the replays
+        batch.V_out.fill_(512.0)
+        batch.counts.fill_(-7)
+        batch.ws.zero_()
+        scratch = torch.randn(1 << 20, device="cuda").sum()
+        torch_sync()
+        graph.replay()
+        torch_sync()
+        assert torch.isfinite(scratch)
+        assert torch.equal(batch.K_out[:n_out].view(torch.int16), eager.K_out[:n_out].view(torch.int16)), replay
+        assert torch.equal(batch.V_out[:n_out].view(torch.int16), eager.V_out[:n_out].view(torch.int16)), replay
+        assert torch.equal(batch.counts[:n_out], eager.counts[:n_out]), replay
+        assert torch.equal(batch.slot, eager.slot) and torch.equal(batch.mask, eager.mask)
+        batch.check_guards()
+
+
 @pytest.mark.parametrize("path", [None, "valu"])
 def test_step_llama8b_8k_config(path):
     w = WORKLOADS["llama8b_8k"]
