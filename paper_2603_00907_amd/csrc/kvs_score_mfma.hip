@@ -14,7 +14,9 @@
 // (ds_read_b128, 32 rows at the same piece) spread over all banks.  Wavefronts never wait for
 // each other inside a sweep unless they share query rows.  In the accumulator a lane holds ONE
 // query column and 16 token rows, so the running softmax statistics are lane-private; the sum
-// over queries of sweep 1 is a 16-value reduce-scatter over 32 lanes (16 shuffles per tile).
+// over queries of sweep 1 is a 16-value reduce-scatter over 32 lanes (16 shuffles per tile), except in
+// the wide kernel, whose sweep 1 takes the products the other way round (Q K^T): a lane then holds one
+// token and the sum over queries is a sum over registers.
 //
 // A workgroup has four wavefronts that split the chunk's tiles.  Two kernels:
 //   score_mfma_kernel       up to 64 query rows per wavefront, all register-stationary, two tile
@@ -435,6 +437,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   __shared__ __attribute__((aligned(1024))) unsigned char sm_k[kWaves][TILEB];
   __shared__ __attribute__((aligned(1024))) unsigned char sm_q[QROWS * ROWB];
   __shared__ float2 sm_stats[kWaves][QROWS];
+  __shared__ __attribute__((aligned(16))) float sm_cq[QROWS];     // sweep 1: the rows' normalisers ...
+  __shared__ __attribute__((aligned(16))) int sm_lim[QROWS];      // ... and the last row each attends to
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -484,11 +488,16 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     return true;
   };
 
-  // this lane's four normalisers (written by the finalize kernel between the sweeps)
-  float cq[4];
-#pragma unroll
-  for (int b = 0; b < 4; ++b)
-    cq[b] = (PHASE == 1 && b * 32 + col < R) ? c_row[(size_t)un.index * R + b * 32 + col] : INFINITY;
+  // Sweep 1 takes the products the other way round (query rows as accumulator rows, see below), so the
+  // normalisers (written by the finalize kernel between the sweeps) are indexed by accumulator element and come
+  // from LDS.  exp2(-inf) = 0: a row that does not exist adds nothing.
+  if (PHASE == 1) {
+    if (tid < QROWS) {
+      sm_cq[tid] = (tid < R) ? c_row[(size_t)un.index * R + tid] : INFINITY;
+      sm_lim[tid] = last_seen_row(CAUSAL ? sh.causal : 0, un.len, tid);
+    }
+    __syncthreads();
+  }
 
   int lim[4];                               // causal window: last row each of the lane's query columns attends to
 #pragma unroll
@@ -539,7 +548,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
       lds_read_4x16<0>(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3], a_addr + 4 * g);
     issue_tile(j + kWaves);                         // the buffer is free again
 
-    float p[16];
+    float p_tok = 0.f;                              // sweep 1: this lane's token, summed over its query rows
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       f32x16 acc[2];
@@ -548,34 +557,44 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
 #pragma unroll
-          for (int nt = 0; nt < 2; ++nt)
-            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bq[nt][kk], kk == 0 ? zero : acc[nt], 0, 0, 0);
+          for (int nt = 0; nt < 2; ++nt) {
+            acc[nt] = (PHASE == 0)
+                ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], bq[nt][kk], kk == 0 ? zero : acc[nt], 0, 0, 0)
+                : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[nt][kk], a[kk], kk == 0 ? zero : acc[nt], 0, 0, 0);
+          }
         }
       } else {
 #pragma unroll
         for (int kp = 0; kp < KS / 2; ++kp) {
           bf16x8 b00, b01, b10, b11;
           lds_read_2x2<64 * ROWB, 96 * ROWB>(b00, b01, b10, b11, q_addr[2 * kp], q_addr[2 * kp + 1]);
-          acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp], b00, kp == 0 ? zero : acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp], b01, kp == 0 ? zero : acc[1], 0, 0, 0);
-          acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp + 1], b10, acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp + 1], b11, acc[1], 0, 0, 0);
+          if (PHASE == 0) {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp], b00, kp == 0 ? zero : acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp], b01, kp == 0 ? zero : acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp + 1], b10, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp + 1], b11, acc[1], 0, 0, 0);
+          } else {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b00, a[2 * kp], kp == 0 ? zero : acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b01, a[2 * kp], kp == 0 ? zero : acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b10, a[2 * kp + 1], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b11, a[2 * kp + 1], acc[1], 0, 0, 0);
+          }
         }
       }
-      // accumulator element v of a lane: token row 8*(v/4) + 4*half + v%4, query column `col`
-      if (shift > 0) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = 8 * (v / 4) + 4 * half + (v % 4);
-          if (row < shift) { acc[0][v] = -INFINITY; acc[1][v] = -INFINITY; }
-        }
-      }
-      if (CAUSAL && base_t + kTile > un.len - sh.causal + 1) {
-        const int lim2[2] = {lim[2 * h], lim[2 * h + 1]};
-        mask_causal<2>(acc, lim2, base_t, half);
-      }
-      if (cnt) logits_with_counts<2>(acc, cnt, base_t, half, sl2);
       if (PHASE == 0) {
+        // accumulator element v of a lane: token row 8*(v/4) + 4*half + v%4, query column `col`
+        if (shift > 0) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = 8 * (v / 4) + 4 * half + (v % 4);
+            if (row < shift) { acc[0][v] = -INFINITY; acc[1][v] = -INFINITY; }
+          }
+        }
+        if (CAUSAL && base_t + kTile > un.len - sh.causal + 1) {
+          const int lim2[2] = {lim[2 * h], lim[2 * h + 1]};
+          mask_causal<2>(acc, lim2, base_t, half);
+        }
+        if (cnt) logits_with_counts<2>(acc, cnt, base_t, half, sl2);
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
           const int b = 2 * h + nt;
@@ -591,47 +610,38 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
           m_run[b] = m_new;
         }
       } else {
+        // Sweep 1, products taken as Q K^T: accumulator element v of block nt is query row
+        // 32 (2 h + nt) + 8 (v / 4) + 4 half + v % 4, and the lane's column is ONE token, so the sum over the
+        // query rows is a sum over registers
+        const bool tail = CAUSAL && base_t + kTile > un.len - sh.causal + 1;       // uniform
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float s = ex2(fmaf(acc[0][v], sc, -cq[2 * h])) + ex2(fmaf(acc[1][v], sc, -cq[2 * h + 1]));
-          p[v] = (h == 0) ? s : p[v] + s;
+        for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int q0 = 32 * (2 * h + nt) + 8 * g + 4 * half;
+            const float4 c4 = *reinterpret_cast<const float4*>(&sm_cq[q0]);
+            const float cq[4] = {c4.x, c4.y, c4.z, c4.w};
+            float e[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) e[i] = ex2(fmaf(acc[nt][4 * g + i], sl2, -cq[i]));
+            if (tail) {
+              const int4 l4 = *reinterpret_cast<const int4*>(&sm_lim[q0]);
+              const int lq[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+              for (int i = 0; i < 4; ++i) e[i] = (base_t + col > lq[i]) ? 0.f : e[i];
+            }
+            p_tok += (e[0] + e[1]) + (e[2] + e[3]);
+          }
         }
       }
     }
 
     if (PHASE == 1) {
-      // sum over the 32 query columns of each half: reduce-scatter, lane bits 4..1 pick v
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const bool up = lane & 16;
-        const float send = up ? p[i] : p[i + 8];
-        const float keep = up ? p[i + 8] : p[i];
-        p[i] = keep + __shfl_xor(send, 16, kWave);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool up = lane & 8;
-        const float send = up ? p[i] : p[i + 4];
-        const float keep = up ? p[i + 4] : p[i];
-        p[i] = keep + __shfl_xor(send, 8, kWave);
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const bool up = lane & 4;
-        const float send = up ? p[i] : p[i + 2];
-        const float keep = up ? p[i + 2] : p[i];
-        p[i] = keep + __shfl_xor(send, 4, kWave);
-      }
-      {
-        const bool up = lane & 2;
-        const float send = up ? p[0] : p[1];
-        const float keep = up ? p[1] : p[0];
-        p[0] = keep + __shfl_xor(send, 2, kWave);
-      }
-      p[0] += __shfl_xor(p[0], 1, kWave);
-      const int v = (lane >> 1) & 15;
-      const int row = 8 * (v / 4) + 4 * half + (v % 4);
-      if ((lane & 1) == 0 && row >= shift) alpha_bar[un.in_row + base_t + row] = p[0];
+      // the two halves of the wavefront hold the token's other query rows; a row that stands for c tokens has
+      // c equal terms in every softmax sum (2^(e + log2 c) = c 2^e)
+      p_tok += __shfl_xor(p_tok, 32, kWave);
+      if (cnt) p_tok *= (float)cnt[base_t + col];
+      if (half == 0 && col >= shift) alpha_bar[un.in_row + base_t + col] = p_tok;
     }
   }
 
