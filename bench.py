@@ -265,8 +265,9 @@ def main():
     step_bytes = sum(pb.values())
     pb = {p: v * layers_per_launch for p, v in pb.items()}     # ... of one launch's units
     # The roofline is that of the dominant KERNEL.  kvs_merge_compact and kvs_select are one kernel each;
-    # kvs_score is three streaming kernels (two sweeps over K, one pass over V) plus two small ones, so
-    # the longest of its kernels is at most about its time over three.
+    # kvs_score streams three tensors' worth (K twice, V once) in two or three kernels plus two small ones;
+    # its time over three is compared (its longest kernel, sweep 1 with the pass over V riding along, stays
+    # below the merge kernel, see profiles/).
     streaming_kernels = {"score": 3, "select": 1, "merge_compact": 1}
     dominant = max(phases, key=lambda p: phase_ms[p] / streaming_kernels[p])
     achieved = pb[dominant] / (phase_ms[dominant] * 1e-3) / 1e9

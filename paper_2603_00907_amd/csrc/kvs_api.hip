@@ -14,8 +14,10 @@ namespace kvs {
 hipError_t launch_score_valu(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
                              const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream);
 hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                             const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream);
+                             const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
+                             hipStream_t stream);
 bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt);
+bool score_mfma_takes_values(const Shape& sh);
 
 namespace {
 
@@ -245,12 +247,25 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
 }  // namespace
 
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
-                        const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+                        const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream,
+                        const void* V, bool* o_done) {
   // KVS_SCORE_PATH=valu forces the vector-ALU kernels (used by the tests to cover both paths).
+  // The pass over V rides along in sweep 1 when the launch is a large one (the streaming policy's threshold):
+  // the edge selection then runs as a short launch of its own, one CU per unit, which costs less than the
+  // separate pass over V saves (measured at 64 units of the headline shape: 199 against 226 us for sweep 1,
+  // the pass over V and the selection).  A small launch keeps the selection hidden beside the pass over V
+  // (8 units: 38 against 45 us).  KVS_FUSE_OBAR=0 | 1 forces one or the other.
   const char* force = std::getenv("KVS_SCORE_PATH");
   const bool force_valu = force && std::strcmp(force, "valu") == 0;
+  if (o_done) *o_done = false;
   if (!force_valu && score_mfma_supported(tab, sh, dt)) {
-    return launch_score_mfma(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+    const char* fuse = std::getenv("KVS_FUSE_OBAR");
+    bool want = sh.stream != 0;
+    if (fuse && std::strcmp(fuse, "0") == 0) want = false;
+    if (fuse && std::strcmp(fuse, "1") == 0) want = true;
+    const bool with_v = V != nullptr && o_done != nullptr && score_mfma_takes_values(sh) && want;
+    if (with_v) *o_done = true;
+    return launch_score_mfma(tab, sh, Q, K, counts_in, alpha_bar, ws, with_v ? V : nullptr, stream);
   }
   return launch_score_valu(tab, sh, dt, Q, K, counts_in, alpha_bar, ws, stream);
 }
@@ -295,11 +310,16 @@ kvs_status kvs_score_counts(const kvs_problem* p, const void* Q, const void* K, 
   if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
-    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, alpha_bar, w, s);
+    bool o_done = false;
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, alpha_bar, w, s, V, &o_done);
     if (e != hipSuccess) return e;
-    e = launch_select_obar(tab, sh, plan.dtype, false, alpha_bar, nullptr, nullptr, V, counts_in, w.o_part, s);
-    if (e != hipSuccess) return e;
-    return launch_obar_reduce(tab, sh, w.o_part, o_bar, s);
+    Shape sh2 = sh;
+    sh2.o_from_score = o_done;
+    if (!o_done) {
+      e = launch_select_obar(tab, sh, plan.dtype, false, alpha_bar, nullptr, nullptr, V, counts_in, w.o_part, s);
+      if (e != hipSuccess) return e;
+    }
+    return launch_obar_reduce(tab, sh2, w.o_part, o_bar, s);
   });
 }
 
@@ -391,11 +411,15 @@ kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, c
   int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
-    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, w.alpha_bar, w, s);
+    bool o_done = false;
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, w.alpha_bar, w, s, V, &o_done);
     if (e != hipSuccess) return e;
-    e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, V, counts_in, w.o_part, s);
+    Shape sh2 = sh;
+    sh2.o_from_score = o_done;
+    e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, o_done ? nullptr : V, counts_in,
+                           w.o_part, s);
     if (e != hipSuccess) return e;
-    return launch_merge(tab, sh, plan.dtype, K, V, counts_in, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,
+    return launch_merge(tab, sh2, plan.dtype, K, V, counts_in, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,
                         V_out, counts_out, s);
   });
 }

@@ -65,7 +65,13 @@ struct Shape {
   int stream;       // 1: the launch's K and V exceed the last-level cache, rows are read non-temporally
   int rule;         // kvs_key_rule of the merged Key
   int causal;       // 0, or the window W when query row q only sees the rows up to its own position n - W + q % W
+  int o_from_score; // 1: o_part holds one partial per SCORE chunk (written by sweep 1), else one per chunk of the o_bar pass
 };
+
+// How many partials of o_bar a unit has in o_part.
+__host__ __device__ inline int obar_partials(const Shape& sh, const Unit& un) {
+  return sh.o_from_score ? un.n_chunks : obar_chunks(un.len);
+}
 
 // Workspace carve-up (all offsets multiples of 256 bytes).
 struct Workspace {
@@ -162,8 +168,12 @@ __device__ __forceinline__ int find_unit(const UnitTable& tab, int chunk) {
 hipError_t launch_score_finalize(const UnitTable& tab, const Shape& sh, const Workspace& ws, hipStream_t stream);
 // Both score sweeps: chunk statistics, the finalize kernel, then alpha_bar.
 // counts_in (here and below): cardinalities of the input rows when the cache is already a merged one, or null.
+// V non-null: the caller also needs o_bar; where the score kernel can carry the pass over V along, it does,
+// leaves one partial per score chunk in ws.o_part and sets *o_done (the caller then skips the separate pass and
+// sets Shape::o_from_score for the consumers).
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
-                        const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream);
+                        const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream,
+                        const void* V = nullptr, bool* o_done = nullptr);
 // One launch, two kinds of workgroups: the first `with_select ? n_units : 0` select the edges of one unit
 // each, the others stream one chunk of V each into o_part (skipped when V is null).
 hipError_t launch_select_obar(const UnitTable& tab, const Shape& sh, kvs_dtype dt, bool with_select,

@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   constexpr int PER = kMaxChunks / PARTS;
   float part_sum = 0.f;
   if (!NORMS && o_bar == nullptr) {
-    const int nc = obar_chunks(un.len);
+    const int nc = obar_partials(sh, un);
     const int d = tid % D, h = tid / D;
     float v[PER];
 #pragma unroll

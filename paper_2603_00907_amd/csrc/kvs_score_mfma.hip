@@ -4,7 +4,8 @@
 // averaged over the unit's query rows): sweep 0 leaves per-chunk softmax statistics (running
 // maximum and sum of exponentials, base-2 domain), a small kernel reduces them to one normaliser
 // per query row and unit, sweep 1 recomputes the logits, normalises them and writes alpha_bar.
-// (o_bar is accumulated by a separate streaming pass over V, see kvs_select.hip.)
+// (o_bar needs a pass over V: a streaming pass of its own beside the edge selection, see kvs_select.hip, or,
+// in large launches of the kernel for 65..128 query rows, carried along by sweep 1.)
 //
 // The logit tile is computed transposed, S^T[token, query] = K_tile * Q^T, with
 // v_mfma_f32_32x32x16_bf16: the A operand is a 32-token tile of K, the B operand a block of
@@ -420,11 +421,16 @@ __device__ __forceinline__ void lds_read_2x2(bf16x8& b00, bf16x8& b01, bf16x8& b
 // tile (16 KB of LDS reads per tile, hidden behind the MFMAs already in the pipe).  The K tile is
 // moved to registers whole (all k-steps) at the start of a tile, which frees its single LDS buffer
 // for the wavefront's next tile at once: that load flies during both halves' MFMAs and softmax work.
-template <int D, int PHASE, bool STREAM, bool CAUSAL>
+// OBAR (sweep 1 only): the pass over V that o_bar = sum_t alpha_bar[t] V[t] needs rides along.  A tile's Value
+// rows are requested when the tile starts and used when its alpha_bar values exist, one tile of arithmetic
+// later, so they cost no waiting, and they travel while the sweep's own loads are idle behind its arithmetic.
+// Every workgroup leaves the sum over its chunk in o_part[unit][chunk]; consumers add the chunks in order.
+template <int D, int PHASE, bool STREAM, bool CAUSAL, bool OBAR>
 __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const int32_t* __restrict__ counts_in, float* __restrict__ alpha_bar, float2* __restrict__ stats_part,
-    const float* __restrict__ c_row) {
+    const float* __restrict__ c_row, const uint16_t* __restrict__ V, float* __restrict__ o_part) {
+  static_assert(!OBAR || PHASE == 1, "the Value pass belongs to sweep 1");
   constexpr int KS = D / 16;
   constexpr int LPR = D / 8;
   constexpr int RPI = kWave / LPR;
@@ -532,6 +538,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   float m_run[4], l_run[4];
 #pragma unroll
   for (int b = 0; b < 4; ++b) { m_run[b] = -INFINITY; l_run[b] = 0.f; }
+  // OBAR: this lane's 16-byte piece of sum_t w_t V[t] over the wavefront's tiles (w = alpha_bar, or alpha_bar / c)
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  float o_acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o_acc[e] = 0.f;
+  const unsigned char* Vg = OBAR ? reinterpret_cast<const unsigned char*>(V + (size_t)un.in_row * D) : nullptr;
 
   for (int it = 0; it < iters; ++it) {
     const int j = it * kWaves + wave;
@@ -547,6 +559,16 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     for (int g = 0; g < KS / 4; ++g)
       lds_read_4x16<0>(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3], a_addr + 4 * g);
     issue_tile(j + kWaves);                         // the buffer is free again
+    // OBAR: the tile's Value rows, RPI whole rows per load; they are used at the end of the tile
+    u32x4 vr[NLD];
+    if (OBAR) {
+      const unsigned char* vt = Vg + (size_t)base_t * ROWB + lane * 16;
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(vt + i * 1024);
+        vr[i] = STREAM ? __builtin_nontemporal_load(src) : *src;
+      }
+    }
 
     float p_tok = 0.f;                              // sweep 1: this lane's token, summed over its query rows
 #pragma unroll
@@ -640,8 +662,42 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
       // the two halves of the wavefront hold the token's other query rows; a row that stands for c tokens has
       // c equal terms in every softmax sum (2^(e + log2 c) = c 2^e)
       p_tok += __shfl_xor(p_tok, 32, kWave);
+      if (OBAR) {
+        // lane l holds the weight of tile row l % 32; load i of this lane is row i * RPI + st_row
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+          const int row = i * RPI + st_row;
+          float w = __shfl(p_tok, row, kWave);
+          if (row < shift) w = 0.f;                         // the tile before has counted this row
+          float vf[8];
+          Piece<uint16_t>::unpack(make_uint4(vr[i].x, vr[i].y, vr[i].z, vr[i].w), vf);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o_acc[e] = fmaf(w, vf[e], o_acc[e]);
+        }
+      }
       if (cnt) p_tok *= (float)cnt[base_t + col];
       if (half == 0 && col >= shift) alpha_bar[un.in_row + base_t + col] = p_tok;
+    }
+  }
+
+  if (OBAR) {
+    // lanes that hold the same piece of the row, then the wavefronts, in a fixed order
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o_acc[e] += __shfl_xor(o_acc[e], off, kWave);
+    }
+    float* sm_o = reinterpret_cast<float*>(&sm_stats[0][0]);          // (sweep 0's table, idle in sweep 1)
+    if (st_row == 0) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sm_o[wave * D + st_slot * 8 + e] = o_acc[e];
+    }
+    __syncthreads();
+    if (tid < D) {
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) sum += sm_o[w * D + tid];
+      o_part[((size_t)un.index * kMaxChunks + chunk) * D + tid] = sum;
     }
   }
 
@@ -675,27 +731,37 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
 
 template <int D, bool STREAM, bool CAUSAL>
 hipError_t launch_wide_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                         const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+                         const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
+                         hipStream_t stream) {
   dim3 grid(tab.total_chunks), block(kThreads);
-  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0, STREAM, CAUSAL>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row);
+  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0, STREAM, CAUSAL, false>), grid, block, 0, stream, tab, sh,
+                     (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
+                     (const uint16_t*)nullptr, (float*)nullptr);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
-  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row);
+  if (V != nullptr) {
+    hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL, true>), grid, block, 0, stream, tab, sh,
+                       (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
+                       (const uint16_t*)V, ws.o_part);
+  } else {
+    hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL, false>), grid, block, 0, stream, tab, sh,
+                       (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
+                       (const uint16_t*)nullptr, (float*)nullptr);
+  }
   return hipGetLastError();
 }
 
 template <int D>
 hipError_t launch_wide(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                       const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+                       const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
+                       hipStream_t stream) {
   if (sh.causal > 0) {
-    return sh.stream ? launch_wide_t<D, true, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
-                     : launch_wide_t<D, false, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+    return sh.stream ? launch_wide_t<D, true, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream)
+                     : launch_wide_t<D, false, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
   }
-  return sh.stream ? launch_wide_t<D, true, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
-                   : launch_wide_t<D, false, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+  return sh.stream ? launch_wide_t<D, true, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream)
+                   : launch_wide_t<D, false, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
 }
 
 template <int D, int NT, int WQ>
@@ -714,14 +780,15 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const 
 
 template <int D>
 hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                    const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+                    const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
+                    hipStream_t stream) {
   // At most 64 query rows per wavefront: with more, the stationary Q operands, the accumulators and
   // the tile operands no longer fit the 256 registers that two wavefronts per SIMD leave each, and
   // every spill reload waits for ALL loads in flight, the tile prefetch included.
   const int R = sh.R;
   if (R <= 32) return launch_t<D, 1, 1>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
   if (R <= 64) return launch_t<D, 2, 1>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
-  if (R <= 128) return launch_wide<D>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);      // rows 64.. from LDS, one pass
+  if (R <= 128) return launch_wide<D>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);   // rows 64.. from LDS, one pass
   if (R <= 256) return launch_t<D, 2, 2>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);    // two passes of 128 rows
   return launch_t<D, 2, 4>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);                  // passes of 256 rows
 }
@@ -736,10 +803,16 @@ bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
   return true;
 }
 
+// Sweep 1 of the kernel for 65..128 query rows can carry the pass over V along (o_part then holds one partial
+// per score chunk).
+bool score_mfma_takes_values(const Shape& sh) { return sh.R > 64 && sh.R <= 128; }
+
+// V: non-null asks for that fused pass (only where score_mfma_takes_values says so).
 hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                             const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream) {
-  return sh.D == 64 ? launch_d<64>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
-                    : launch_d<128>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+                             const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
+                             hipStream_t stream) {
+  return sh.D == 64 ? launch_d<64>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream)
+                    : launch_d<128>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
 }
 
 }  // namespace kvs

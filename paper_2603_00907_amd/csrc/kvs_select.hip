@@ -599,7 +599,7 @@ __global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
 __global__ void obar_reduce_kernel(const UnitTable tab, const Shape sh, const float* __restrict__ o_part,
                                    float* __restrict__ o_bar) {
   const Unit un = tab.u[blockIdx.x];
-  const int nc = obar_chunks(un.len);
+  const int nc = obar_partials(sh, un);
   for (int d = threadIdx.x; d < sh.D; d += blockDim.x) {
     float s = 0.f;
     for (int c = 0; c < nc; ++c) s += o_part[((size_t)un.index * kMaxChunks + c) * sh.D + d];

@@ -50,6 +50,16 @@ class env_override:
             os.environ[self.key] = self.old
 
 
+def score_path(path):
+    """None: the library's own choice; "valu": the vector-ALU score kernels; "fuse": the pass over V carried
+    along in sweep 1 (the library does that by itself only for large launches); "nofuse": never."""
+    if path == "fuse":
+        return env_override("KVS_FUSE_OBAR", "1")
+    if path == "nofuse":
+        return env_override("KVS_FUSE_OBAR", "0")
+    return env_override("KVS_SCORE_PATH", path)
+
+
 # ------------------------------------------------------------------------------------------------
 SCORE_CASES = [
     # base, dtype, D, G, W, lengths, path
@@ -59,6 +69,10 @@ SCORE_CASES = [
     ("tiny", "f32", 64, 1, 1, [257], None),
     ("llama8b_8k", "bf16", 128, 4, 32, [2500], None),
     ("llama8b_8k", "bf16", 128, 4, 32, [2500], "valu"),
+    ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053, 40], "fuse"),     # ragged tiles, a last chunk of 5 rows
+    ("llama8b_8k", "bf16", 64, 4, 32, [1900], "fuse"),
+    ("llama8b_8k", "bf16", 128, 5, 20, [1500], "fuse"),               # 100 query rows
+    ("stream2560", "bf16", 128, 4, 32, [2560, 700], "fuse"),          # with cardinalities
     ("llama8b_8k", "bf16", 64, 2, 16, [900], None),
     ("llama8b_8k", "bf16", 128, 1, 20, [700, 33], None),
     ("llama8b_8k", "bf16", 128, 3, 20, [1111], None),
@@ -82,7 +96,7 @@ def test_score_matches_oracle(base, dtype, D, G, W, lens, path):
     w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
     units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
     batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype=dtype, n_sink=w.n_sink, gap_rows=3)
-    with env_override("KVS_SCORE_PATH", path):
+    with score_path(path):
         if batch.counts_in is None:
             batch.kvs.kvs_score(batch.problem, batch.Q, batch.K, batch.V, batch.alpha_bar, batch.o_bar, batch.ws,
                                 stream=batch.stream())
@@ -330,6 +344,7 @@ CAUSAL_CASES = [
     ("tiny", "f32", 64, 2, 5, [777, 5], None),                  # vector-ALU kernel; a unit that is all window
     ("llama8b_8k", "bf16", 128, 1, 20, [700, 33], None),        # 20 rows in one MFMA block
     ("llama8b_8k", "bf16", 64, 2, 32, [900], None),             # 64 rows
+    ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053], "fuse"),   # (with the pass over V carried along)
     ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053], None),     # 128 rows in one pass; a last chunk of 5 rows, all
     ("llama8b_8k", "bf16", 128, 4, 32, [2053], "valu"),         # of them masked for most rows
     ("llama8b_8k", "bf16", 128, 8, 32, [3000], None),           # 256 rows, two wavefronts per pass
@@ -343,7 +358,7 @@ def test_score_with_causal_window_matches_oracle(base, dtype, D, G, W, lens, pat
     w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
     units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
     batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype=dtype, n_sink=w.n_sink, gap_rows=3, causal=True)
-    with env_override("KVS_SCORE_PATH", path):
+    with score_path(path):
         batch.kvs.kvs_score_counts(batch.problem, batch.Q, batch.K, batch.V, batch.counts_in, batch.alpha_bar,
                                    batch.o_bar, batch.ws, stream=batch.stream())
         torch_sync()
@@ -367,7 +382,7 @@ def run_step(w, accepted, path=None, causal=False):
     units = [a.inputs for a in accepted]
     batch = DeviceBatch(units, group=w.group, window=w.window, head_dim=w.head_dim, dtype=w.dtype,
                         n_sink=w.n_sink, n_recent=w.n_recent, causal=causal)
-    with env_override("KVS_SCORE_PATH", path):
+    with score_path(path):
         if batch.counts_in is None:
             batch.kvs.kvs_step(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out, batch.counts,
                                batch.ws, slot_of_token_out=batch.slot, edge_mask_out=batch.mask,
@@ -451,10 +466,10 @@ def test_step_replayed_from_a_hip_graph_equals_the_eager_step():
         batch.check_guards()
 
 
-@pytest.mark.parametrize("path", [None, "valu"])
+@pytest.mark.parametrize("path", [None, "valu", "fuse"])
 def test_step_llama8b_8k_config(path):
     w = WORKLOADS["llama8b_8k"]
-    heads = range(w.n_kv_heads) if path is None else range(2)
+    heads = range(w.n_kv_heads) if path != "valu" else range(2)
     check_step(w, [accepted_unit(w, 0, 0, h) for h in heads], path)
 
 
@@ -558,11 +573,12 @@ def test_step_more_units_than_one_launch_takes():
     check_step(w, accepted)
 
 
-def test_step_streaming_regime_full_size():
+@pytest.mark.parametrize("path", [None, "fuse"])
+def test_step_streaming_regime_full_size(path):
     """Sec. 5's streaming regime at full size: 8 KV heads, each a merged cache of 2048 + 512 slots (the old
     slots stand for 4 tokens on average) merged back to 2048; cardinalities must add up bit-exactly."""
     w = WORKLOADS["stream2560"]
-    batch = check_step(w, [accepted_unit(w, 0, 0, h) for h in range(w.n_kv_heads)])
+    batch = check_step(w, [accepted_unit(w, 0, 0, h) for h in range(w.n_kv_heads)], path)
     total_in = sum(int(u.counts.sum()) for u in batch.units)
     assert int(batch.counts[:batch.problem.rows_out].sum().item()) == total_in
 
