@@ -260,7 +260,11 @@ hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, con
   if (o_done) *o_done = false;
   if (!force_valu && score_mfma_supported(tab, sh, dt)) {
     const char* fuse = std::getenv("KVS_FUSE_OBAR");
-    bool want = sh.stream != 0;
+    // (The selection of a unit too long for the select kernel's LDS cache of keys takes several times longer,
+    // 74 us at 65536 tokens: such launches keep it hidden beside the pass over V.)
+    int longest = 0;
+    for (int i = 0; i < tab.n_units; ++i) longest = std::max(longest, tab.u[i].len);
+    bool want = sh.stream != 0 && longest <= 32768;
     if (fuse && std::strcmp(fuse, "0") == 0) want = false;
     if (fuse && std::strcmp(fuse, "1") == 0) want = true;
     const bool with_v = V != nullptr && o_done != nullptr && score_mfma_takes_values(sh) && want;
