@@ -38,7 +38,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
     ap.add_argument("--layers-per-call", type=int, default=0,
                     help="layers handed to one kvs_step call (0 = all; 1 = one call per layer)")
-    ap.add_argument("--streams", type=int, default=1, help="deal the kvs_step calls of a step round-robin to this many streams")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="deal the kvs_step calls of a step round-robin to this many streams (default 2: the layers go "
+                         "to two calls on two streams, whose kernels fill each other's idle resources)")
     ap.add_argument("--no-per-layer-calls", action="store_true", help="skip the one-call-per-layer comparison loop")
     ap.add_argument("--key-rule", default="hessian", choices=["hessian", "diagonal", "mean"],
                     help="rule for the merged Key (the ablations run the same kernels)")
@@ -98,7 +100,8 @@ def main():
     D, R = w.head_dim, w.q_rows
     b = 4 if w.dtype == "f32" else 2
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
-    lpc = args.layers_per_call or layers
+    # launch shape: by default the layers are split evenly into one kvs_step call per stream
+    lpc = args.layers_per_call or -(-layers // max(1, min(args.streams, layers)))
     batches = [list(range(l0, min(layers, l0 + lpc))) for l0 in range(0, layers, lpc)]
     problems = {}
     for nl in {len(bt) for bt in batches}:
@@ -152,7 +155,7 @@ def main():
     slot = torch.empty(big.rows_in, dtype=torch.int32, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
 
-    n_streams = max(1, args.streams)
+    n_streams = 1 if args.graph else max(1, min(args.streams, len(batches)))
     side_streams = [torch.cuda.Stream() for _ in range(n_streams - 1)]
     wss = [ws] + [torch.empty_like(ws) for _ in side_streams]
 

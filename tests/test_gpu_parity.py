@@ -491,10 +491,10 @@ def test_step_llama8b_32k_one_layer_full_size():
 
 
 def test_step_headline_workload_in_the_launch_configuration_of_the_bench():
-    """All 32 layers x 8 KV heads of the headline workload as the 256 units of ONE kvs_step call, which is what
-    bench.py times (launch groups of 64 units = 8 layers).  Four sampled units, the first and the last of the
-    call and the two on either side of the first group border, are compared with the oracle like any other
-    unit; every unit must satisfy the invariants that hold at any size."""
+    """All 32 layers x 8 KV heads of the headline workload the way bench.py times them: two kvs_step calls of 16
+    layers (128 units, launch groups of 64 units = 8 layers) on two streams, each with its own workspace.  Four
+    sampled units, the first and the last of the step and the two on either side of the first group border, are
+    compared with the oracle like any other unit; every unit must satisfy the invariants that hold at any size."""
     import torch
     from concurrent.futures import ThreadPoolExecutor
     import paper_2603_00907_amd as kvs
@@ -522,16 +522,24 @@ def test_step_headline_workload_in_the_launch_configuration_of_the_bench():
                 K[i * n:(i + 1) * n] = to_device(u.K, "bf16")
                 V[i * n:(i + 1) * n] = to_device(u.V, "bf16")
                 Q[i] = to_device(u.Q.reshape(R, D), "bf16")
-    p = kvs.Problem(lens=[n] * nu, budgets=[B] * nu, group=w.group, window=w.window, head_dim=D, dtype="bf16",
+    half = nu // 2
+    p = kvs.Problem(lens=[n] * half, budgets=[B] * half, group=w.group, window=w.window, head_dim=D, dtype="bf16",
                     n_sink=w.n_sink, n_recent=w.n_recent)
-    K_out = torch.empty((p.rows_out, D), dtype=torch.bfloat16, device="cuda")
+    K_out = torch.empty((nu * B, D), dtype=torch.bfloat16, device="cuda")
     V_out = torch.empty_like(K_out)
-    counts = torch.empty(p.rows_out, dtype=torch.int32, device="cuda")
-    mask = torch.empty(p.rows_in, dtype=torch.uint8, device="cuda")
-    slot = torch.empty(p.rows_in, dtype=torch.int32, device="cuda")
-    ws = torch.empty(kvs.kvs_workspace_size(p), dtype=torch.uint8, device="cuda")
-    kvs.kvs_step(p, Q, K, V, K_out, V_out, counts, ws, slot_of_token_out=slot, edge_mask_out=mask,
-                 stream=torch.cuda.current_stream().cuda_stream)
+    counts = torch.empty(nu * B, dtype=torch.int32, device="cuda")
+    mask = torch.empty(nu * n, dtype=torch.uint8, device="cuda")
+    slot = torch.empty(nu * n, dtype=torch.int32, device="cuda")
+    main = torch.cuda.current_stream()
+    streams = [main, torch.cuda.Stream()]
+    streams[1].wait_stream(main)
+    wss = [torch.empty(kvs.kvs_workspace_size(p), dtype=torch.uint8, device="cuda") for _ in streams]
+    for c, st in enumerate(streams):
+        u0, u1 = c * half, (c + 1) * half
+        kvs.kvs_step(p, Q[u0:u1], K[u0 * n:u1 * n], V[u0 * n:u1 * n], K_out[u0 * B:u1 * B], V_out[u0 * B:u1 * B],
+                     counts[u0 * B:u1 * B], wss[c], slot_of_token_out=slot[u0 * n:u1 * n],
+                     edge_mask_out=mask[u0 * n:u1 * n], stream=st.cuda_stream)
+    main.wait_stream(streams[1])
     torch_sync()
     # every unit: r edges selected, none in the sink, slots numbered 0 .. B-1, cardinalities add up to n
     m2, s2, c2 = mask.view(nu, n), slot.view(nu, n), counts.view(nu, B)
