@@ -27,6 +27,9 @@
 //   score_mfma_wide_kernel  65..128 rows in one pass: half of the rows register-stationary, the other
 //                           half re-read from an LDS copy of the Q block for every tile.
 // Rows of an already merged cache (cardinalities c given) enter with log2(c) added to the logit.
+#include <cstdlib>
+#include <type_traits>
+
 #include "kvs_device.h"
 
 namespace kvs {
@@ -415,18 +418,32 @@ __device__ __forceinline__ void lds_read_2x2(bf16x8& b00, bf16x8& b01, bf16x8& b
       : "memory");
 }
 
-// 65..128 query rows in ONE pass over K.  All 128 rows' operands plus the accumulators do not fit the
-// registers of a wavefront at two wavefronts per SIMD, so only rows 0..63 are register-stationary;
-// rows 64..127 stay in the workgroup's swizzled LDS copy of the Q block and are re-read for every
-// tile (16 KB of LDS reads per tile, hidden behind the MFMAs already in the pipe).  The K tile is
+// One 16-byte LDS read at each of two addresses (offset OFF), complete on return.
+template <int OFF>
+__device__ __forceinline__ void lds_read_2x1(bf16x8& b0, bf16x8& b1, uint32_t ad0, uint32_t ad1) {
+  asm volatile(
+      "ds_read_b128 %0, %2 offset:%4\n\t"
+      "ds_read_b128 %1, %3 offset:%4\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(b0), "=&v"(b1)
+      : "v"(ad0), "v"(ad1), "n"(OFF)
+      : "memory");
+}
+
+// 65..256 query rows in ONE pass over K, as QB blocks of 64 rows (QB = 2: up to 128 rows, four wavefronts per
+// workgroup, two workgroups per CU; QB = 3, 4: up to 192 / 256 rows, eight wavefronts per workgroup and one workgroup
+// per CU, because the Q block then takes 48 / 64 KB of LDS).  All rows' operands plus the accumulators do not fit the
+// registers of a wavefront at two wavefronts per SIMD, so only rows 0..63 are register-stationary (QB = 2; none
+// with more blocks); the others stay in the workgroup's swizzled LDS copy of the Q block and are re-read for every
+// tile (16 KB of LDS reads per block and tile, hidden behind the MFMAs already in the pipe).  The K tile is
 // moved to registers whole (all k-steps) at the start of a tile, which frees its single LDS buffer
 // for the wavefront's next tile at once: that load flies during both halves' MFMAs and softmax work.
 // OBAR (sweep 1 only): the pass over V that o_bar = sum_t alpha_bar[t] V[t] needs rides along.  A tile's Value
 // rows are requested when the tile starts and used when its alpha_bar values exist, one tile of arithmetic
 // later, so they cost no waiting, and they travel while the sweep's own loads are idle behind its arithmetic.
 // Every workgroup leaves the sum over its chunk in o_part[unit][chunk]; consumers add the chunks in order.
-template <int D, int PHASE, bool STREAM, bool CAUSAL, bool OBAR>
-__global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
+template <int D, int PHASE, bool STREAM, bool CAUSAL, bool OBAR, int QB>
+__global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mfma_wide_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const int32_t* __restrict__ counts_in, float* __restrict__ alpha_bar, float2* __restrict__ stats_part,
     const float* __restrict__ c_row, const uint16_t* __restrict__ V, float* __restrict__ o_part) {
@@ -437,12 +454,15 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   constexpr int NLD = kTile / RPI;
   constexpr int ROWB = D * 2;
   constexpr int TILEB = kTile * ROWB;
-  constexpr int QROWS = 128;                // query rows per wavefront (two halves of 64)
+  constexpr int QROWS = 64 * QB;            // query rows per wavefront (QB blocks of 64)
+  constexpr int NW = QB == 2 ? 4 : 8;       // wavefronts per workgroup
+  constexpr int NTHR = NW * kWave;
+  static_assert(QB >= 2 && QB <= 4, "the Q block must fit the LDS beside the tile buffers");
   static_assert(KS == 4 || KS == 8, "operand reads come in groups of four");
 
-  __shared__ __attribute__((aligned(1024))) unsigned char sm_k[kWaves][TILEB];
+  __shared__ __attribute__((aligned(1024))) unsigned char sm_k[NW][TILEB];
   __shared__ __attribute__((aligned(1024))) unsigned char sm_q[QROWS * ROWB];
-  __shared__ float2 sm_stats[kWaves][QROWS];
+  __shared__ float2 sm_stats[NW][QROWS];
   __shared__ __attribute__((aligned(16))) float sm_cq[QROWS];     // sweep 1: the rows' normalisers ...
   __shared__ __attribute__((aligned(16))) int sm_lim[QROWS];      // ... and the last row each attends to
 
@@ -452,7 +472,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   const int t0 = chunk * un.chunk_len;
   const int t1 = min(un.len, t0 + un.chunk_len);
   const int ntiles = (t1 - t0 + kTile - 1) / kTile;
-  const int iters = (ntiles + kWaves - 1) / kWaves;
+  const int iters = (ntiles + NW - 1) / NW;
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int col = lane % 32, half = lane / 32;
   const int R = sh.R;
@@ -505,20 +525,22 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     __syncthreads();
   }
 
-  int lim[4];                               // causal window: last row each of the lane's query columns attends to
+  int lim[2 * QB];                          // causal window: last row each of the lane's query columns attends to
 #pragma unroll
-  for (int b = 0; b < 4; ++b) lim[b] = last_seen_row(CAUSAL ? sh.causal : 0, un.len, b * 32 + col);
+  for (int b = 0; b < 2 * QB; ++b) lim[b] = last_seen_row(CAUSAL ? sh.causal : 0, un.len, b * 32 + col);
 
-  // the Q block, once per workgroup: every wavefront fetches 32 rows (rows past R repeat the last one)
+  // the Q block, once per workgroup: every wavefront fetches its share of the rows (rows past R repeat the last one)
   {
-    constexpr int QLD = 32 / RPI;
+    constexpr int RPW = QROWS / NW;           // 32 or 24 rows
+    constexpr int QLD = RPW / RPI;
+    static_assert(RPW % RPI == 0, "whole load instructions");
 #pragma unroll
     for (int i = 0; i < QLD; ++i) {
-      const int lr = wave * 32 + i * RPI + st_row;
+      const int lr = wave * RPW + i * RPI + st_row;
       const int qrow = min(lr, R - 1);
       const int piece = st_slot ^ (lr % LPR);
       __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(Qg + (size_t)qrow * LPR + piece),
-                                       KVS_LDS_PTR(sm_q + (wave * 32 + i * RPI) * ROWB), 16, 0, 0);
+                                       KVS_LDS_PTR(sm_q + (wave * RPW + i * RPI) * ROWB), 16, 0, 0);
     }
   }
   // first K tile flies while Q lands; loads return in order, so leaving NLD in flight means Q is there
@@ -528,16 +550,18 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
-  bf16x8 bq[2][KS];                         // rows 0..63, register-stationary
+  bf16x8 bq[2][KS];                         // rows 0..63, register-stationary (two blocks only: with more, the
+                                            // statistics of eight column blocks take the registers and every block
+                                            // is read from LDS)
 #pragma unroll
-  for (int g = 0; g < KS / 4; ++g) {
+  for (int g = 0; g < (QB == 2 ? KS / 4 : 0); ++g) {
     lds_read_4x16<0>(bq[0][4 * g], bq[0][4 * g + 1], bq[0][4 * g + 2], bq[0][4 * g + 3], q_addr + 4 * g);
     lds_read_4x16<32 * ROWB>(bq[1][4 * g], bq[1][4 * g + 1], bq[1][4 * g + 2], bq[1][4 * g + 3], q_addr + 4 * g);
   }
 
-  float m_run[4], l_run[4];
+  float m_run[2 * QB], l_run[2 * QB];
 #pragma unroll
-  for (int b = 0; b < 4; ++b) { m_run[b] = -INFINITY; l_run[b] = 0.f; }
+  for (int b = 0; b < 2 * QB; ++b) { m_run[b] = -INFINITY; l_run[b] = 0.f; }
   // OBAR: this lane's 16-byte piece of sum_t w_t V[t] over the wavefront's tiles (w = alpha_bar, or alpha_bar / c)
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   float o_acc[8];
@@ -546,7 +570,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   const unsigned char* Vg = OBAR ? reinterpret_cast<const unsigned char*>(V + (size_t)un.in_row * D) : nullptr;
 
   for (int it = 0; it < iters; ++it) {
-    const int j = it * kWaves + wave;
+    const int j = it * NW + wave;
     const int tile_t0 = t0 + j * kTile;
     if (tile_t0 >= t1) break;                       // this wavefront has run out of tiles
     const int base_t = min(tile_t0, t1 - kTile);
@@ -558,7 +582,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
 #pragma unroll
     for (int g = 0; g < KS / 4; ++g)
       lds_read_4x16<0>(a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3], a_addr + 4 * g);
-    issue_tile(j + kWaves);                         // the buffer is free again
+    issue_tile(j + NW);                         // the buffer is free again
     // OBAR: the tile's Value rows, RPI whole rows per load; they are used at the end of the tile
     u32x4 vr[NLD];
     if (OBAR) {
@@ -571,11 +595,15 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     }
 
     float p_tok = 0.f;                              // sweep 1: this lane's token, summed over its query rows
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    // one block of 64 query rows; the block number is a compile-time constant so that the operand reads of the
+    // blocks kept in LDS address them with immediate offsets (no address registers per block)
+    // NTB: column blocks of 32 rows that exist in this block of 64 (the last block may hold one only)
+    auto block = [&](auto hc, auto ntc) {
+      constexpr int h = decltype(hc)::value;
+      constexpr int NTB = decltype(ntc)::value;
       f32x16 acc[2];
       const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      if (h == 0) {
+      if (h == 0 && QB == 2) {
 #pragma unroll
         for (int kk = 0; kk < KS; ++kk) {
 #pragma unroll
@@ -585,11 +613,25 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
                 : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[nt][kk], a[kk], kk == 0 ? zero : acc[nt], 0, 0, 0);
           }
         }
+      } else if (NTB == 1) {
+        acc[1] = zero;
+#pragma unroll
+        for (int kp = 0; kp < KS / 2; ++kp) {
+          bf16x8 b00, b10;
+          lds_read_2x1<64 * h * ROWB>(b00, b10, q_addr[2 * kp], q_addr[2 * kp + 1]);
+          if (PHASE == 0) {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp], b00, kp == 0 ? zero : acc[0], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp + 1], b10, acc[0], 0, 0, 0);
+          } else {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b00, a[2 * kp], kp == 0 ? zero : acc[0], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b10, a[2 * kp + 1], acc[0], 0, 0, 0);
+          }
+        }
       } else {
 #pragma unroll
         for (int kp = 0; kp < KS / 2; ++kp) {
           bf16x8 b00, b01, b10, b11;
-          lds_read_2x2<64 * ROWB, 96 * ROWB>(b00, b01, b10, b11, q_addr[2 * kp], q_addr[2 * kp + 1]);
+          lds_read_2x2<64 * h * ROWB, (64 * h + 32) * ROWB>(b00, b01, b10, b11, q_addr[2 * kp], q_addr[2 * kp + 1]);
           if (PHASE == 0) {
             acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp], b00, kp == 0 ? zero : acc[0], 0, 0, 0);
             acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 * kp], b01, kp == 0 ? zero : acc[1], 0, 0, 0);
@@ -618,7 +660,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
         }
         if (cnt) logits_with_counts<2>(acc, cnt, base_t, half, sl2);
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < NTB; ++nt) {
           const int b = 2 * h + nt;
           float tm = acc[nt][0];
 #pragma unroll
@@ -637,7 +679,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
         // query rows is a sum over registers
         const bool tail = CAUSAL && base_t + kTile > un.len - sh.causal + 1;       // uniform
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
+        for (int nt = 0; nt < NTB; ++nt) {
 #pragma unroll
           for (int g = 0; g < 4; ++g) {
             const int q0 = 32 * (2 * h + nt) + 8 * g + 4 * half;
@@ -656,6 +698,18 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
           }
         }
       }
+    };
+    typedef std::integral_constant<int, 1> one_t;
+    typedef std::integral_constant<int, 2> two_t;
+    block(std::integral_constant<int, 0>{}, two_t{});
+    if constexpr (QB == 2) {
+      block(std::integral_constant<int, 1>{}, two_t{});
+    } else {
+      // the last block holds one or two column blocks of 32 rows (uniform)
+      block(std::integral_constant<int, 1>{}, two_t{});
+      if constexpr (QB == 4) block(std::integral_constant<int, 2>{}, two_t{});
+      if (R > 64 * (QB - 1) + 32) block(std::integral_constant<int, QB - 1>{}, two_t{});
+      else block(std::integral_constant<int, QB - 1>{}, one_t{});
     }
 
     if (PHASE == 1) {
@@ -696,7 +750,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     if (tid < D) {
       float sum = 0.f;
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) sum += sm_o[w * D + tid];
+      for (int w = 0; w < NW; ++w) sum += sm_o[w * D + tid];
       o_part[((size_t)un.index * kMaxChunks + chunk) * D + tid] = sum;
     }
   }
@@ -704,7 +758,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   if (PHASE == 0) {
     // the two halves of a wavefront hold the same query column for different token rows
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
+    for (int b = 0; b < 2 * QB; ++b) {
       const float m_o = __shfl_xor(m_run[b], 32, kWave);
       const float l_o = __shfl_xor(l_run[b], 32, kWave);
       const float m_n = fmaxf(m_run[b], m_o);
@@ -717,10 +771,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
     if (tid < R) {
       float M = -INFINITY;
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm_stats[w][tid].x);
+      for (int w = 0; w < NW; ++w) M = fmaxf(M, sm_stats[w][tid].x);
       float Z = 0.f;
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) {
+      for (int w = 0; w < NW; ++w) {
         const float2 s = sm_stats[w][tid];
         if (s.y > 0.f) Z += s.y * ex2(s.x - M);
       }
@@ -729,39 +783,39 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_wide_kernel(
   }
 }
 
-template <int D, bool STREAM, bool CAUSAL>
+template <int D, bool STREAM, bool CAUSAL, int QB>
 hipError_t launch_wide_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
                          const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
                          hipStream_t stream) {
-  dim3 grid(tab.total_chunks), block(kThreads);
-  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0, STREAM, CAUSAL, false>), grid, block, 0, stream, tab, sh,
+  dim3 grid(tab.total_chunks), block(QB == 2 ? 256 : 512);
+  hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0, STREAM, CAUSAL, false, QB>), grid, block, 0, stream, tab, sh,
                      (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
                      (const uint16_t*)nullptr, (float*)nullptr);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
   if (V != nullptr) {
-    hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL, true>), grid, block, 0, stream, tab, sh,
+    hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL, true, QB>), grid, block, 0, stream, tab, sh,
                        (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
                        (const uint16_t*)V, ws.o_part);
   } else {
-    hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL, false>), grid, block, 0, stream, tab, sh,
+    hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL, false, QB>), grid, block, 0, stream, tab, sh,
                        (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
                        (const uint16_t*)nullptr, (float*)nullptr);
   }
   return hipGetLastError();
 }
 
-template <int D>
+template <int D, int QB>
 hipError_t launch_wide(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
                        const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
                        hipStream_t stream) {
   if (sh.causal > 0) {
-    return sh.stream ? launch_wide_t<D, true, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream)
-                     : launch_wide_t<D, false, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
+    return sh.stream ? launch_wide_t<D, true, true, QB>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream)
+                     : launch_wide_t<D, false, true, QB>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
   }
-  return sh.stream ? launch_wide_t<D, true, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream)
-                   : launch_wide_t<D, false, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
+  return sh.stream ? launch_wide_t<D, true, false, QB>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream)
+                   : launch_wide_t<D, false, false, QB>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
 }
 
 template <int D, int NT, int WQ>
@@ -788,7 +842,12 @@ hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const 
   const int R = sh.R;
   if (R <= 32) return launch_t<D, 1, 1>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
   if (R <= 64) return launch_t<D, 2, 1>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
-  if (R <= 128) return launch_wide<D>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);   // rows 64.. from LDS, one pass
+  // 65..256 rows: rows 64.. from LDS, one pass over K (KVS_SCORE_WIDE=0 keeps the kernel below for more than 128)
+  const char* env = std::getenv("KVS_SCORE_WIDE");
+  const bool wide_off = env && env[0] == '0';
+  if (R <= 128) return launch_wide<D, 2>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
+  if (R <= 192 && !wide_off) return launch_wide<D, 3>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
+  if (R <= 256 && !wide_off) return launch_wide<D, 4>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
   if (R <= 256) return launch_t<D, 2, 2>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);    // two passes of 128 rows
   return launch_t<D, 2, 4>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);                  // passes of 256 rows
 }
@@ -803,9 +862,13 @@ bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
   return true;
 }
 
-// Sweep 1 of the kernel for 65..128 query rows can carry the pass over V along (o_part then holds one partial
+// Sweep 1 of the kernel for 65..256 query rows can carry the pass over V along (o_part then holds one partial
 // per score chunk).
-bool score_mfma_takes_values(const Shape& sh) { return sh.R > 64 && sh.R <= 128; }
+bool score_mfma_takes_values(const Shape& sh) {
+  const char* e = std::getenv("KVS_SCORE_WIDE");
+  const bool wide_off = e && e[0] == '0';
+  return sh.R > 64 && sh.R <= (wide_off ? 128 : 256);
+}
 
 // V: non-null asks for that fused pass (only where score_mfma_takes_values says so).
 hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,

@@ -52,7 +52,10 @@ class env_override:
 
 def score_path(path):
     """None: the library's own choice; "valu": the vector-ALU score kernels; "fuse": the pass over V carried
-    along in sweep 1 (the library does that by itself only for large launches); "nofuse": never."""
+    along in sweep 1 (the library does that by itself only for large launches); "nofuse": never; "narrow": 129..256
+    query rows in two passes of 128 instead of the one-pass kernel."""
+    if path == "narrow":
+        return env_override("KVS_SCORE_WIDE", "0")
     if path == "fuse":
         return env_override("KVS_FUSE_OBAR", "1")
     if path == "nofuse":
@@ -78,6 +81,14 @@ SCORE_CASES = [
     ("llama8b_8k", "bf16", 128, 3, 20, [1111], None),
     ("llama8b_8k", "bf16", 128, 5, 20, [1500], None),
     ("llama8b_8k", "bf16", 128, 8, 32, [3000], None),
+    ("qwen7b_32k", "bf16", 128, 7, 32, [2100, 100], None),            # 224 query rows in four blocks of 64
+    ("qwen7b_32k", "bf16", 128, 7, 32, [2100, 100], "fuse"),
+    ("qwen7b_32k", "bf16", 128, 7, 32, [2100], "narrow"),             # ... as two passes of 128 rows
+    ("llama8b_8k", "bf16", 128, 5, 32, [1700, 40], "fuse"),           # 160 rows: three blocks
+    ("llama8b_8k", "bf16", 128, 5, 29, [1700], None),                 # 145 rows
+    ("llama8b_8k", "bf16", 64, 8, 32, [1900], "fuse"),                # 256 rows, head_dim 64
+    ("llama8b_8k", "bf16", 128, 8, 32, [3000], "narrow"),
+    ("stream2560", "bf16", 128, 7, 32, [2560, 700], "fuse"),          # 224 rows with cardinalities
     ("stress128k", "bf16", 128, 8, 64, [3000], None),
     ("stress128k", "bf16", 128, 8, 100, [1200], None),
     ("llama8b_8k", "bf16", 64, 1, 4, [500], None),
@@ -347,7 +358,10 @@ CAUSAL_CASES = [
     ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053], "fuse"),   # (with the pass over V carried along)
     ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053], None),     # 128 rows in one pass; a last chunk of 5 rows, all
     ("llama8b_8k", "bf16", 128, 4, 32, [2053], "valu"),         # of them masked for most rows
-    ("llama8b_8k", "bf16", 128, 8, 32, [3000], None),           # 256 rows, two wavefronts per pass
+    ("llama8b_8k", "bf16", 128, 8, 32, [3000], None),           # 256 rows in one pass (four blocks of 64)
+    ("llama8b_8k", "bf16", 128, 8, 32, [3000, 2053], "fuse"),
+    ("llama8b_8k", "bf16", 128, 8, 32, [3000], "narrow"),       # 256 rows, two wavefronts per pass
+    ("qwen7b_32k", "bf16", 128, 5, 32, [2053, 40], None),       # 160 rows: three blocks
     ("stress128k", "bf16", 128, 8, 40, [1200], None),           # 320 rows, window 40 crosses two tiles
     ("stream2560", "bf16", 128, 4, 32, [2560], None),           # with cardinalities (the tail rows are fresh tokens)
 ]
@@ -471,6 +485,14 @@ def test_step_llama8b_8k_config(path):
     w = WORKLOADS["llama8b_8k"]
     heads = range(w.n_kv_heads) if path != "valu" else range(2)
     check_step(w, [accepted_unit(w, 0, 0, h) for h in heads], path)
+
+
+@pytest.mark.parametrize("path", [None, "fuse", "narrow"])
+def test_step_qwen_shape_reduced(path):
+    """Qwen2-7B layout (7 query heads per KV head: 224 query rows, the one-pass score kernel with four blocks of 64
+    rows), 8192 -> 2048 tokens."""
+    w = WORKLOADS["qwen7b_32k"].scaled(length=("fixed", 8192), budget=("fixed", 2048))
+    check_step(w, [accepted_unit(w, 0, 0, h) for h in range(2)], path)
 
 
 def test_step_with_causal_window():

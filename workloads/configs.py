@@ -89,6 +89,12 @@ WORKLOADS = {
         name="stream2560", cfg_id=6, layers=32, n_seq=1, n_kv_heads=8, group=4, window=32,
         head_dim=128, dtype="bf16", length=("fixed", 2560), budget=("fixed", 2048),
         k_rho=("fixed", 0.9), k_outlier_channels=4, k_outlier_scale=8.0, mean_count=4.0, fresh_tail=512),
+    # Qwen2-7B layout (Sec. 5 evaluates it beside Llama-3.1-8B and Mistral-7B): 28 q heads over 4 KV heads, so a
+    # window of 32 queries gives 224 query rows per unit (more than one pass of the 128-row score kernel).
+    "qwen7b_32k": Workload(
+        name="qwen7b_32k", cfg_id=7, layers=28, n_seq=1, n_kv_heads=4, group=7, window=32,
+        head_dim=128, dtype="bf16", length=("fixed", 32768), budget=("fixed", 4096),
+        k_rho=("fixed", 0.9), k_outlier_channels=4, k_outlier_scale=8.0),
 }
 
 
