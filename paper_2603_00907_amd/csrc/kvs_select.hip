@@ -430,6 +430,193 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
   for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
 }
 
+// Select for a unit whose keys do not fit the LDS: the passes of the radix select and the ordered pass read
+// alpha_bar again each time.  Same key layout as select_unit_cached (groups of four edges on 16-byte boundaries
+// of alpha_bar, 0xffffffff outside [lo, hi]), same ranking (stretched keys), same tie rule (lowest index first).
+__device__ __forceinline__ void select_unit_long(const Unit& un, const float* __restrict__ a, uint8_t* __restrict__ mk,
+                                                 int32_t* __restrict__ sl, SelectSmem& sm, int lo, int hi, int r) {
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int n = un.len;
+  const int pad0 = (int)((un.in_row + lo) & 3);
+  const int lo_al = lo - pad0;
+  const int G = (hi - lo_al + 4) / 4;              // groups of four keys
+  constexpr uint32_t kNone = 0xffffffffu;
+  constexpr int UN = 4;                            // groups a lane fetches before it uses the first
+
+  // raw keys (IEEE bit patterns) of group g; positions outside [lo, hi] and groups past the end hold kNone
+  auto load4 = [&](int g, uint32_t (&k)[4]) {
+    const int m0 = lo_al + 4 * g;                  // may lie up to 3 tokens before the unit: still alpha_bar
+    if (m0 >= lo && m0 + 3 <= hi) {                // hi <= n - 2: element m0 + 4 exists
+      const float4 v = *reinterpret_cast<const float4*>(a + m0);
+      const float nx = a[m0 + 4];
+      k[0] = __float_as_uint(v.x + v.y);
+      k[1] = __float_as_uint(v.y + v.z);
+      k[2] = __float_as_uint(v.z + v.w);
+      k[3] = __float_as_uint(v.w + nx);
+    } else if (g < G) {                            // first or last group: nothing is read past the unit's end
+      float e[5];
+#pragma unroll
+      for (int j = 0; j < 5; ++j) e[j] = a[min(m0 + j, n - 1)];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool ok = (m0 + j >= lo) && (m0 + j <= hi);
+        k[j] = ok ? __float_as_uint(e[j] + e[j + 1]) : kNone;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) k[j] = kNone;
+    }
+  };
+  // f(k[4]) for every group, any order; UN groups of a lane are in flight together
+  auto for_groups = [&](auto&& f) {
+    for (int base = 0; base < G; base += kSelThreads * UN) {
+      uint32_t k[UN][4];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) load4(base + u * kSelThreads + tid, k[u]);
+#pragma unroll
+      for (int u = 0; u < UN; ++u) f(k[u]);
+    }
+  };
+
+  // ---- minimum and maximum: keys are ranked as (key - kmin) << lshift (monotone, bit 31 clear, and the first digit
+  //      tells neighbouring tokens apart, whose raw keys share their top bits and would serialise the LDS atomics)
+  uint32_t kmin = kNone, kmax = 0;
+  for_groups([&](const uint32_t (&k)[4]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      kmin = min(kmin, k[j]);
+      kmax = max(kmax, k[j] == kNone ? 0u : k[j]);
+    }
+  });
+  kmin = wave_min_u32(kmin);
+  kmax = wave_max_u32(kmax);
+  if (lane == 0) { sm.wmin[wave] = kmin; sm.wmax[wave] = kmax; }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) { kmin = min(kmin, sm.wmin[w]); kmax = max(kmax, sm.wmax[w]); }
+  const uint32_t span = kmax - kmin;               // < 2^31: the keys are bit patterns of non-negative floats
+  const int lshift = span ? __clz(span) - 1 : 0;
+  auto ranked = [&](uint32_t k) { return k == kNone ? kNone : (k - kmin) << lshift; };
+
+  // ---- MSB-first radix select, 11 + 11 + 10 bits, every pass over all keys
+  uint32_t prefix = 0, pmask = 0;
+  int want = r;                        // rank (1-based) among the keys that share `prefix`
+  int n_equal = 0;
+  const int shifts[3] = {21, 10, 0};
+  const int widths[3] = {11, 11, 10};
+#pragma unroll
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = shifts[pass];
+    const int bins = 1 << widths[pass];
+    for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
+    __syncthreads();
+    for_groups([&](const uint32_t (&k)[4]) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t q = ranked(k[j]);
+        if (q != kNone && (q & pmask) == prefix) atomicAdd(&sm.hist[(q >> shift) & (bins - 1)], 1);
+      }
+    });
+    __syncthreads();
+    n_equal = pick_bin(sm, shift, bins, prefix, pmask, want);
+  }
+  const uint32_t T = prefix;           // `want` keys equal to T are taken, the lowest indices first
+  const bool simple = (n_equal == want);          // every key equal to T is taken: "selected" is "below T + 1"
+  const uint32_t Tc = simple ? T + 1 : T;
+
+  // ---- ordered pass: wavefront w owns the groups [g0, g1), lane l the groups g0 + it * 64 + l
+  const int per_g = ((G + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
+  const int g0 = min(G, wave * per_g), g1 = min(G, g0 + per_g);
+  int n_lt = 0, n_eq = 0;               // wavefront totals: keys below Tc, keys equal to T (if they matter)
+  for (int gb = g0; gb < g1; gb += kWave * UN) {
+    uint32_t k[UN][4];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int g = gb + u * kWave + lane;
+      load4(g < g1 ? g : G, k[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t q = ranked(k[u][j]);
+        n_lt += __popcll(__ballot(q < Tc));
+        if (!simple) n_eq += __popcll(__ballot(q == T));
+      }
+    }
+  }
+  if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
+  __syncthreads();
+  int eq_before = 0, sel_before = waves_before(sm.lt, wave, lane);
+  if (!simple) {
+    for (int w = 0; w < wave; ++w) {
+      const int e = sm.eq[w];
+      sel_before += min(max(want - eq_before, 0), e);
+      eq_before += e;
+    }
+  }
+  // Four tokens' mask bytes and slots; whole groups inside [lo, hi] go out as one 4-byte and one 16-byte store.
+  // `below`: selected edges before the group's first token.
+  auto write_group = [&](int g, const bool* sel, int below) {
+    const int m0 = lo_al + 4 * g;
+    int s4[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { s4[j] = m0 + j - below; below += sel[j]; }
+    if (m0 >= lo && m0 + 3 <= hi) {
+      *reinterpret_cast<uint32_t*>(mk + m0) =
+          (uint32_t)sel[0] | ((uint32_t)sel[1] << 8) | ((uint32_t)sel[2] << 16) | ((uint32_t)sel[3] << 24);
+      *reinterpret_cast<int4*>(sl + m0) = make_int4(s4[0], s4[1], s4[2], s4[3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (m0 + j >= lo && m0 + j <= hi) { mk[m0 + j] = sel[j] ? 1 : 0; sl[m0 + j] = s4[j]; }
+      }
+    }
+  };
+  const bool ties = !simple && n_eq > 0;           // wavefront-uniform: keys equal to T must be ranked by index
+  for (int gb = g0; gb < g1; gb += kWave * UN) {
+    uint32_t k[UN][4];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int g = gb + u * kWave + lane;
+      load4(g < g1 ? g : G, k[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int g = gb + u * kWave + lane;
+      bool sel[4];
+      if (!ties) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sel[j] = ranked(k[u][j]) < Tc;
+      } else {
+        bool eq[4];
+        int lane_eq = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t q = ranked(k[u][j]);
+          sel[j] = q < T;
+          eq[j] = q == T;
+          lane_eq += eq[j];
+        }
+        const int incl_eq = wave_incl_scan(lane_eq);
+        int rank = eq_before + incl_eq - lane_eq;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (eq[j]) { sel[j] = rank < want; ++rank; }
+        }
+        eq_before += __builtin_amdgcn_readlane(incl_eq, kWave - 1);
+      }
+      const int lane_cnt = sel[0] + sel[1] + sel[2] + sel[3];
+      const int incl = wave_incl_scan(lane_cnt);
+      if (g < g1) write_group(g, sel, sel_before + incl - lane_cnt);
+      sel_before += __builtin_amdgcn_readlane(incl, kWave - 1);
+    }
+  }
+  // tokens outside the eligible edge range
+  for (int t = tid; t < lo && t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t; }
+  for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
+}
+
 __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, const float* __restrict__ alpha_bar,
                             uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, SelectSmem& sm) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
@@ -451,67 +638,11 @@ __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, con
     return;
   }
 
-  // ---- longer units: every pass recomputes the keys from alpha_bar (L2-resident)
-  for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
-  __syncthreads();
-  for (int i = tid; i < E; i += kSelThreads) atomicAdd(&sm.hist[edge_key(a, lo + i) >> 21], 1);
-  __syncthreads();
-  uint32_t prefix = 0, pmask = 0;
-  int want = r;                        // rank (1-based) among the keys that share `prefix`
-  pick_bin(sm, 21, 2048, prefix, pmask, want);
-  const int shifts[2] = {10, 0};
-  const int widths[2] = {11, 10};
-#pragma unroll
-  for (int pass = 0; pass < 2; ++pass) {
-    const int shift = shifts[pass];
-    const int bins = 1 << widths[pass];
-    for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
-    __syncthreads();
-    for (int i = tid; i < E; i += kSelThreads) {
-      const uint32_t k = edge_key(a, lo + i);
-      if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
-    }
-    __syncthreads();
-    pick_bin(sm, shift, bins, prefix, pmask, want);
-  }
-  const uint32_t T = prefix;           // `want` keys equal to T are taken, the lowest indices first
-
-  // ---- ordered pass: every wavefront owns a contiguous range of edges
-  const int per = ((E + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
-  const int e0 = min(E, wave * per), e1 = min(E, e0 + per);
-  int n_lt = 0, n_eq = 0;
-  for (int i = e0 + lane; i < e1 + lane; i += kWave) {     // whole wavefront iterates together
-    uint32_t k = 0xffffffffu;
-    if (i < e1) k = edge_key(a, lo + i);
-    n_lt += __popcll(__ballot(k < T));
-    n_eq += __popcll(__ballot(k == T && i < e1));
-  }
-  if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
-  __syncthreads();
-  int eq_before = 0, sel_before = 0;
-  for (int w = 0; w < wave; ++w) {
-    const int take = min(max(want - eq_before, 0), sm.eq[w]);
-    sel_before += sm.lt[w] + take;
-    eq_before += sm.eq[w];
-  }
-  for (int i = e0 + lane; i < e1 + lane; i += kWave) {
-    uint32_t k = 0xffffffffu;
-    if (i < e1) k = edge_key(a, lo + i);
-    const bool is_eq = (k == T) && (i < e1);
-    const uint64_t beq = __ballot(is_eq);
-    const bool sel = (k < T) || (is_eq && (eq_before + lanes_below(beq, lane) < want));
-    const uint64_t bsel = __ballot(sel);
-    if (i < e1) {
-      const int m = lo + i;
-      mk[m] = sel ? 1 : 0;
-      sl[m] = m - (sel_before + lanes_below(bsel, lane));   // selected edges below token m
-    }
-    eq_before += __popcll(beq);
-    sel_before += __popcll(bsel);
-  }
-  // tokens outside the eligible edge range
-  for (int t = tid; t < lo && t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t; }
-  for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
+  // ---- longer units: every pass recomputes the keys from alpha_bar (L2-resident).  One CU walks the whole unit
+  //      several times, so the instruction count per key is what counts: as in the cached path a lane takes four
+  //      consecutive edges from one aligned 16-byte load plus one element, whole groups inside [lo, hi] skip the
+  //      per-key checks, keys are ranked stretched, and the ordered pass writes four tokens per lane.
+  select_unit_long(un, a, mk, sl, sm, lo, hi, r);
 }
 
 template <typename T, int D, bool STREAM>
