@@ -442,11 +442,16 @@ __device__ __forceinline__ void lds_read_2x1(bf16x8& b0, bf16x8& b1, uint32_t ad
 // rows are requested when the tile starts and used when its alpha_bar values exist, one tile of arithmetic
 // later, so they cost no waiting, and they travel while the sweep's own loads are idle behind its arithmetic.
 // Every workgroup leaves the sum over its chunk in o_part[unit][chunk]; consumers add the chunks in order.
-template <int D, int PHASE, bool STREAM, bool CAUSAL, bool OBAR, int QB>
+// MULTI: more than 256 query rows, one launch per 256 of them (rows qp0 .. qp0 + 255 of every unit): sweep 0 leaves
+// each launch's rows' statistics, sweep 1 adds its rows' share to what the launches before left in alpha_bar, and
+// the last launch (which alone may carry the pass over V) applies the cardinalities.
+template <int D, int PHASE, bool STREAM, bool CAUSAL, bool OBAR, int QB, bool MULTI = false>
 __global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mfma_wide_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const int32_t* __restrict__ counts_in, float* __restrict__ alpha_bar, float2* __restrict__ stats_part,
-    const float* __restrict__ c_row, const uint16_t* __restrict__ V, float* __restrict__ o_part) {
+    const float* __restrict__ c_row, const uint16_t* __restrict__ V, float* __restrict__ o_part, const int qp0) {
+  static_assert(!MULTI || QB == 4, "passes of 256 rows");
+  const int qp = MULTI ? qp0 : 0;           // first query row of this launch
   static_assert(!OBAR || PHASE == 1, "the Value pass belongs to sweep 1");
   constexpr int KS = D / 16;
   constexpr int LPR = D / 8;
@@ -519,15 +524,15 @@ __global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mf
   // from LDS.  exp2(-inf) = 0: a row that does not exist adds nothing.
   if (PHASE == 1) {
     if (tid < QROWS) {
-      sm_cq[tid] = (tid < R) ? c_row[(size_t)un.index * R + tid] : INFINITY;
-      sm_lim[tid] = last_seen_row(CAUSAL ? sh.causal : 0, un.len, tid);
+      sm_cq[tid] = (qp + tid < R) ? c_row[(size_t)un.index * R + qp + tid] : INFINITY;
+      sm_lim[tid] = last_seen_row(CAUSAL ? sh.causal : 0, un.len, qp + tid);
     }
     __syncthreads();
   }
 
   int lim[2 * QB];                          // causal window: last row each of the lane's query columns attends to
 #pragma unroll
-  for (int b = 0; b < 2 * QB; ++b) lim[b] = last_seen_row(CAUSAL ? sh.causal : 0, un.len, b * 32 + col);
+  for (int b = 0; b < 2 * QB; ++b) lim[b] = last_seen_row(CAUSAL ? sh.causal : 0, un.len, qp + b * 32 + col);
 
   // the Q block, once per workgroup: every wavefront fetches its share of the rows (rows past R repeat the last one)
   {
@@ -537,7 +542,7 @@ __global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mf
 #pragma unroll
     for (int i = 0; i < QLD; ++i) {
       const int lr = wave * RPW + i * RPI + st_row;
-      const int qrow = min(lr, R - 1);
+      const int qrow = min(qp + lr, R - 1);
       const int piece = st_slot ^ (lr % LPR);
       __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(Qg + (size_t)qrow * LPR + piece),
                                        KVS_LDS_PTR(sm_q + (wave * RPW + i * RPI) * ROWB), 16, 0, 0);
@@ -708,7 +713,7 @@ __global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mf
       // the last block holds one or two column blocks of 32 rows (uniform)
       block(std::integral_constant<int, 1>{}, two_t{});
       if constexpr (QB == 4) block(std::integral_constant<int, 2>{}, two_t{});
-      if (R > 64 * (QB - 1) + 32) block(std::integral_constant<int, QB - 1>{}, two_t{});
+      if (R - qp > 64 * (QB - 1) + 32) block(std::integral_constant<int, QB - 1>{}, two_t{});
       else block(std::integral_constant<int, QB - 1>{}, one_t{});
     }
 
@@ -716,6 +721,7 @@ __global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mf
       // the two halves of the wavefront hold the token's other query rows; a row that stands for c tokens has
       // c equal terms in every softmax sum (2^(e + log2 c) = c 2^e)
       p_tok += __shfl_xor(p_tok, 32, kWave);
+      if (MULTI && qp > 0) p_tok += alpha_bar[un.in_row + base_t + col];     // the rows of the launches before
       if (OBAR) {
         // lane l holds the weight of tile row l % 32; load i of this lane is row i * RPI + st_row
 #pragma unroll
@@ -729,7 +735,7 @@ __global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mf
           for (int e = 0; e < 8; ++e) o_acc[e] = fmaf(w, vf[e], o_acc[e]);
         }
       }
-      if (cnt) p_tok *= (float)cnt[base_t + col];
+      if (cnt && (!MULTI || qp + QROWS >= R)) p_tok *= (float)cnt[base_t + col];
       if (half == 0 && col >= shift) alpha_bar[un.in_row + base_t + col] = p_tok;
     }
   }
@@ -768,7 +774,7 @@ __global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mf
       if (half == 0) sm_stats[wave][b * 32 + col] = make_float2(m_run[b], l_run[b]);
     }
     __syncthreads();
-    if (tid < R) {
+    if (tid < QROWS && qp + tid < R) {
       float M = -INFINITY;
 #pragma unroll
       for (int w = 0; w < NW; ++w) M = fmaxf(M, sm_stats[w][tid].x);
@@ -778,7 +784,7 @@ __global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mf
         const float2 s = sm_stats[w][tid];
         if (s.y > 0.f) Z += s.y * ex2(s.x - M);
       }
-      stats_part[(part_base + chunk) * R + tid] = make_float2(M, Z);
+      stats_part[(part_base + chunk) * R + qp + tid] = make_float2(M, Z);
     }
   }
 }
@@ -790,20 +796,62 @@ hipError_t launch_wide_t(const UnitTable& tab, const Shape& sh, const void* Q, c
   dim3 grid(tab.total_chunks), block(QB == 2 ? 256 : 512);
   hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0, STREAM, CAUSAL, false, QB>), grid, block, 0, stream, tab, sh,
                      (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
-                     (const uint16_t*)nullptr, (float*)nullptr);
+                     (const uint16_t*)nullptr, (float*)nullptr, 0);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
   if (V != nullptr) {
     hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL, true, QB>), grid, block, 0, stream, tab, sh,
                        (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
-                       (const uint16_t*)V, ws.o_part);
+                       (const uint16_t*)V, ws.o_part, 0);
   } else {
     hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL, false, QB>), grid, block, 0, stream, tab, sh,
                        (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
-                       (const uint16_t*)nullptr, (float*)nullptr);
+                       (const uint16_t*)nullptr, (float*)nullptr, 0);
   }
   return hipGetLastError();
+}
+
+// More than 256 query rows: one launch of the four-block kernel per 256 rows and sweep.
+template <int D, bool STREAM, bool CAUSAL>
+hipError_t launch_wide_multi_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+                               const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
+                               hipStream_t stream) {
+  dim3 grid(tab.total_chunks), block(512);
+  hipError_t e;
+  for (int qp = 0; qp < sh.R; qp += 256) {
+    hipLaunchKernelGGL((score_mfma_wide_kernel<D, 0, STREAM, CAUSAL, false, 4, true>), grid, block, 0, stream, tab, sh,
+                       (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
+                       (const uint16_t*)nullptr, (float*)nullptr, qp);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
+  for (int qp = 0; qp < sh.R; qp += 256) {
+    const bool last = qp + 256 >= sh.R;
+    if (last && V != nullptr) {
+      hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL, true, 4, true>), grid, block, 0, stream, tab, sh,
+                         (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
+                         (const uint16_t*)V, ws.o_part, qp);
+    } else {
+      hipLaunchKernelGGL((score_mfma_wide_kernel<D, 1, STREAM, CAUSAL, false, 4, true>), grid, block, 0, stream, tab,
+                         sh, (const uint16_t*)Q, (const uint16_t*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row,
+                         (const uint16_t*)nullptr, (float*)nullptr, qp);
+    }
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+template <int D>
+hipError_t launch_wide_multi(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+                             const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
+                             hipStream_t stream) {
+  if (sh.causal > 0) {
+    return sh.stream ? launch_wide_multi_t<D, true, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream)
+                     : launch_wide_multi_t<D, false, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
+  }
+  return sh.stream ? launch_wide_multi_t<D, true, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream)
+                   : launch_wide_multi_t<D, false, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
 }
 
 template <int D, int QB>
@@ -848,6 +896,7 @@ hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const 
   if (R <= 128) return launch_wide<D, 2>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
   if (R <= 192 && !wide_off) return launch_wide<D, 3>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
   if (R <= 256 && !wide_off) return launch_wide<D, 4>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
+  if (!wide_off) return launch_wide_multi<D>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);   // 256 rows per launch
   if (R <= 256) return launch_t<D, 2, 2>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);    // two passes of 128 rows
   return launch_t<D, 2, 4>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);                  // passes of 256 rows
 }
@@ -862,12 +911,12 @@ bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
   return true;
 }
 
-// Sweep 1 of the kernel for 65..256 query rows can carry the pass over V along (o_part then holds one partial
+// Sweep 1 of the kernel for more than 64 query rows can carry the pass over V along (o_part then holds one partial
 // per score chunk).
 bool score_mfma_takes_values(const Shape& sh) {
   const char* e = std::getenv("KVS_SCORE_WIDE");
   const bool wide_off = e && e[0] == '0';
-  return sh.R > 64 && sh.R <= (wide_off ? 128 : 256);
+  return sh.R > 64 && (sh.R <= 128 || !wide_off);
 }
 
 // V: non-null asks for that fused pass (only where score_mfma_takes_values says so).

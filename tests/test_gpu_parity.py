@@ -52,8 +52,9 @@ class env_override:
 
 def score_path(path):
     """None: the library's own choice; "valu": the vector-ALU score kernels; "fuse": the pass over V carried
-    along in sweep 1 (the library does that by itself only for large launches); "nofuse": never; "narrow": 129..256
-    query rows in two passes of 128 instead of the one-pass kernel."""
+    along in sweep 1 (the library does that by itself only for large launches); "nofuse": never; "narrow": more than
+    128 query rows with the kernel that keeps 64 rows per wavefront in registers (passes of 128 or 256 rows) instead
+    of the one that reads blocks of 64 rows from LDS."""
     if path == "narrow":
         return env_override("KVS_SCORE_WIDE", "0")
     if path == "fuse":
@@ -89,8 +90,11 @@ SCORE_CASES = [
     ("llama8b_8k", "bf16", 64, 8, 32, [1900], "fuse"),                # 256 rows, head_dim 64
     ("llama8b_8k", "bf16", 128, 8, 32, [3000], "narrow"),
     ("stream2560", "bf16", 128, 7, 32, [2560, 700], "fuse"),          # 224 rows with cardinalities
-    ("stress128k", "bf16", 128, 8, 64, [3000], None),
-    ("stress128k", "bf16", 128, 8, 100, [1200], None),
+    ("stress128k", "bf16", 128, 8, 64, [3000], None),                 # 512 rows: two launches of 256 per sweep
+    ("stress128k", "bf16", 128, 8, 64, [3000, 77], "fuse"),
+    ("stress128k", "bf16", 128, 8, 64, [3000], "narrow"),             # ... passes of 256 rows, four wavefronts a tile
+    ("stress128k", "bf16", 128, 8, 100, [1200], None),                # 800 rows: four launches, the last of 32 rows
+    ("stress128k", "bf16", 128, 8, 100, [1200], "narrow"),
     ("llama8b_8k", "bf16", 64, 1, 4, [500], None),
     ("ragged16", "bf16", 128, 4, 32, [300, 5000, 33000], None),
     # rows that are slots of an already merged cache (cardinalities): every score kernel
@@ -98,6 +102,7 @@ SCORE_CASES = [
     ("stream2560", "bf16", 128, 4, 32, [900], "valu"),
     ("stream2560", "bf16", 128, 1, 20, [1500], None),
     ("stream2560", "bf16", 64, 8, 40, [1100], None),
+    ("stream2560", "bf16", 64, 8, 40, [1100, 300], "fuse"),           # 320 rows with cardinalities, two launches
     ("stream2560", "f32", 64, 2, 5, [600], None),
 ]
 
@@ -363,6 +368,8 @@ CAUSAL_CASES = [
     ("llama8b_8k", "bf16", 128, 8, 32, [3000], "narrow"),       # 256 rows, two wavefronts per pass
     ("qwen7b_32k", "bf16", 128, 5, 32, [2053, 40], None),       # 160 rows: three blocks
     ("stress128k", "bf16", 128, 8, 40, [1200], None),           # 320 rows, window 40 crosses two tiles
+    ("stress128k", "bf16", 128, 8, 40, [1200, 45], "fuse"),
+    ("stress128k", "bf16", 128, 8, 40, [1200], "narrow"),
     ("stream2560", "bf16", 128, 4, 32, [2560], None),           # with cardinalities (the tail rows are fresh tokens)
 ]
 
