@@ -502,6 +502,12 @@ def test_step_qwen_shape_reduced(path):
     check_step(w, [accepted_unit(w, 0, 0, h) for h in range(2)], path)
 
 
+def test_step_qwen_shape_full_size_two_heads():
+    """The same layout at the headline's length, 32768 -> 4096 tokens, two KV heads of one layer."""
+    w = WORKLOADS["qwen7b_32k"]
+    check_step(w, [accepted_unit(w, 3, 0, h) for h in range(2)])
+
+
 def test_step_with_causal_window():
     """The whole step with the causal mask inside the window, bf16 (MFMA score) and fp32 (vector-ALU score)."""
     w = WORKLOADS["llama8b_8k"]
