@@ -13,11 +13,11 @@ namespace kvs {
 
 hipError_t launch_score_valu(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
                              const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream);
-hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
                              const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
                              hipStream_t stream);
 bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt);
-bool score_mfma_takes_values(const Shape& sh);
+bool score_mfma_takes_values(const Shape& sh, kvs_dtype dt);
 
 namespace {
 
@@ -267,9 +267,9 @@ hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, con
     bool want = sh.stream != 0 && longest <= 32768;
     if (fuse && std::strcmp(fuse, "0") == 0) want = false;
     if (fuse && std::strcmp(fuse, "1") == 0) want = true;
-    const bool with_v = V != nullptr && o_done != nullptr && score_mfma_takes_values(sh) && want;
+    const bool with_v = V != nullptr && o_done != nullptr && score_mfma_takes_values(sh, dt) && want;
     if (with_v) *o_done = true;
-    return launch_score_mfma(tab, sh, Q, K, counts_in, alpha_bar, ws, with_v ? V : nullptr, stream);
+    return launch_score_mfma(tab, sh, dt, Q, K, counts_in, alpha_bar, ws, with_v ? V : nullptr, stream);
   }
   return launch_score_valu(tab, sh, dt, Q, K, counts_in, alpha_bar, ws, stream);
 }

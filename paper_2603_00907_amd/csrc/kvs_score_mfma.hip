@@ -19,13 +19,16 @@
 // the wide kernel, whose sweep 1 takes the products the other way round (Q K^T): a lane then holds one
 // token and the sum over queries is a sum over registers.
 //
-// A workgroup has four wavefronts that split the chunk's tiles.  Two kernels:
+// A workgroup's wavefronts split the chunk's tiles.  Three kernels:
 //   score_mfma_kernel       up to 64 query rows per wavefront, all register-stationary, two tile
-//                           buffers per wavefront.  Windows of at most 64 rows (WQ = 1); windows above
-//                           128 rows, where WQ wavefronts split the rows of a pass, share tiles and
-//                           combine alpha_bar through LDS with a workgroup barrier per tile.
-//   score_mfma_wide_kernel  65..128 rows in one pass: half of the rows register-stationary, the other
-//                           half re-read from an LDS copy of the Q block for every tile.
+//                           buffers per wavefront.  Windows of at most 64 rows (WQ = 1); on request also
+//                           windows above 128 rows, where WQ wavefronts split the rows of a pass, share
+//                           tiles and combine alpha_bar through LDS with a workgroup barrier per tile.
+//   score_mfma_wide_kernel  more than 64 rows, in blocks of 64: up to 128 rows with one block
+//                           register-stationary and one re-read from an LDS copy of the Q block for every
+//                           tile, up to 256 rows with every block read from LDS (eight wavefronts), more
+//                           rows as one launch per 256.
+//   score_mfma_f32_kernel   fp32 inputs, v_mfma_f32_32x32x2_f32, 128 rows per launch.
 // Rows of an already merged cache (cardinalities c given) enter with log2(c) added to the logit.
 #include <cstdlib>
 #include <type_traits>
@@ -901,10 +904,245 @@ hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const 
   return launch_t<D, 2, 4>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);                  // passes of 256 rows
 }
 
+// ------------------------------------------------------------------------------------------------
+// fp32 inputs: the same two sweeps with v_mfma_f32_32x32x2_f32 (full fp32 products and sums).  The contraction
+// index is split between the halves of the wavefront (lanes 0..31 take elements 0..D/2-1 of a row, lanes 32..63
+// the rest: any split works as long as both operands use the same one), so a lane's operands are D/2 contiguous
+// floats of one row.  The K tile (32 rows) goes straight from global memory to registers, the tile after it is
+// requested before the products of this one start; the Q block (up to 128 rows per launch, rows qp.. of every
+// unit) sits in LDS, XOR-swizzled in 16-byte pieces, and is re-read for every tile.  Accumulator layouts, the
+// running statistics of sweep 0, the transposed products of sweep 1 and the row offset qp for windows of more
+// than 128 rows are those of score_mfma_wide_kernel.  The work is bound by the fp32 matrix rate, not by memory.
+template <int D, int PHASE, bool CAUSAL>
+__global__ __launch_bounds__(kThreads, 2) void score_mfma_f32_kernel(
+    const UnitTable tab, const Shape sh, const float* __restrict__ Q, const float* __restrict__ K,
+    const int32_t* __restrict__ counts_in, float* __restrict__ alpha_bar, float2* __restrict__ stats_part,
+    const float* __restrict__ c_row, const int qp) {
+  constexpr int ROWB = D * 4;               // bytes per row
+  constexpr int LPR = ROWB / 16;            // 16-byte pieces per row
+  constexpr int RPI = kWave / LPR;          // rows per load instruction of the Q block
+  constexpr int HALF = D / 2;               // contraction indices per half of the wavefront
+  constexpr int NQ4 = HALF / 4;             // 16-byte operand pieces per lane and row
+  constexpr int QROWS = 128;                // query rows per launch
+  constexpr int NBLK = QROWS / 32;
+
+  __shared__ __attribute__((aligned(1024))) unsigned char sm_q[QROWS * ROWB];
+  __shared__ float2 sm_stats[kWaves][QROWS];
+  __shared__ __attribute__((aligned(16))) float sm_cq[QROWS];
+  __shared__ __attribute__((aligned(16))) int sm_lim[QROWS];
+
+  const int ui = find_unit(tab, blockIdx.x);
+  const Unit un = tab.u[ui];
+  const int chunk = blockIdx.x - un.chunk_base;
+  const int t0 = chunk * un.chunk_len;
+  const int t1 = min(un.len, t0 + un.chunk_len);
+  const int ntiles = (t1 - t0 + kTile - 1) / kTile;
+  const int iters = (ntiles + kWaves - 1) / kWaves;
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int col = lane % 32, half = lane / 32;
+  const int R = sh.R;
+  const int rows_here = min(R - qp, QROWS);                 // query rows of this launch
+  const float sl2 = sh.scale_log2;
+  const int32_t* cnt = counts_in ? counts_in + un.in_row : nullptr;
+  const float sc = cnt ? 1.f : sl2;
+  const size_t part_base = (size_t)un.index * kMaxChunks;
+  const bool last_launch = qp + QROWS >= R;
+
+  const unsigned char* Kg = reinterpret_cast<const unsigned char*>(K + (size_t)un.in_row * D);
+  const uint4* Qg = reinterpret_cast<const uint4*>(Q + (size_t)un.index * R * D);
+
+  if (PHASE == 1) {
+    if (tid < QROWS) {
+      sm_cq[tid] = (qp + tid < R) ? c_row[(size_t)un.index * R + qp + tid] : INFINITY;
+      sm_lim[tid] = last_seen_row(CAUSAL ? sh.causal : 0, un.len, qp + tid);
+    }
+  }
+  int lim[NBLK];
+#pragma unroll
+  for (int b = 0; b < NBLK; ++b) lim[b] = last_seen_row(CAUSAL ? sh.causal : 0, un.len, qp + b * 32 + col);
+
+  // the Q block, once per workgroup: every wavefront fetches 32 rows (rows past R repeat the last one); physical
+  // piece s of local row r holds logical piece s ^ (r % LPR)
+  {
+    const int st_row = lane / LPR, st_slot = lane % LPR;
+    constexpr int QLD = 32 / RPI;
+#pragma unroll
+    for (int i = 0; i < QLD; ++i) {
+      const int lr = wave * 32 + i * RPI + st_row;
+      const int qrow = min(qp + lr, R - 1);
+      const int piece = st_slot ^ (lr % LPR);
+      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(Qg + (size_t)qrow * LPR + piece),
+                                       KVS_LDS_PTR(sm_q + (wave * 32 + i * RPI) * ROWB), 16, 0, 0);
+    }
+  }
+  // this lane's operand pieces of Q block row `col` (+ 32 per block): logical piece half * NQ4 + i
+  const float4* q_ptr[NQ4];
+#pragma unroll
+  for (int i = 0; i < NQ4; ++i) {
+    q_ptr[i] = reinterpret_cast<const float4*>(sm_q + col * ROWB + (((half * NQ4 + i) ^ (col % LPR)) * 16));
+  }
+  // K tile of the wavefront's tile j: row `col`, elements half * HALF .. + HALF - 1 (the ragged last tile is moved
+  // back to end at the chunk's end, see score_mfma_kernel)
+  auto load_tile = [&](int j, float4 (&dst)[NQ4]) {
+    const int tile_t0 = t0 + j * kTile;
+    if (tile_t0 >= t1) return;
+    const int base_t = min(tile_t0, t1 - kTile);
+    const float4* src = reinterpret_cast<const float4*>(Kg + (size_t)(base_t + col) * ROWB + half * (HALF * 4));
+#pragma unroll
+    for (int i = 0; i < NQ4; ++i) dst[i] = src[i];
+  };
+  float4 a4[NQ4], an4[NQ4];
+#pragma unroll
+  for (int i = 0; i < NQ4; ++i) { a4[i] = make_float4(0.f, 0.f, 0.f, 0.f); an4[i] = a4[i]; }
+  load_tile(wave, a4);
+  __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): the Q block has landed in LDS
+  __syncthreads();
+
+  float m_run[NBLK], l_run[NBLK];
+#pragma unroll
+  for (int b = 0; b < NBLK; ++b) { m_run[b] = -INFINITY; l_run[b] = 0.f; }
+
+  for (int it = 0; it < iters; ++it) {
+    const int j = it * kWaves + wave;
+    const int tile_t0 = t0 + j * kTile;
+    if (tile_t0 >= t1) break;                       // this wavefront has run out of tiles
+    const int base_t = min(tile_t0, t1 - kTile);
+    const int shift = tile_t0 - base_t;             // leading rows that belong to the tile before
+    load_tile(j + kWaves, an4);                     // flies during this tile's products
+    asm volatile("" ::: "memory");
+
+    float p_tok = 0.f;                              // sweep 1: this lane's token, summed over its query rows
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+      if (b * 32 >= rows_here) break;               // uniform: no such rows in this launch
+      f32x16 acc[1];
+      acc[0] = f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < NQ4; ++i) {
+        const float4 q4 = *reinterpret_cast<const float4*>(reinterpret_cast<const unsigned char*>(q_ptr[i]) +
+                                                           b * 32 * ROWB);
+        const float qv[4] = {q4.x, q4.y, q4.z, q4.w};
+        const float kv[4] = {a4[i].x, a4[i].y, a4[i].z, a4[i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[0] = (PHASE == 0) ? __builtin_amdgcn_mfma_f32_32x32x2f32(kv[e], qv[e], acc[0], 0, 0, 0)
+                                : __builtin_amdgcn_mfma_f32_32x32x2f32(qv[e], kv[e], acc[0], 0, 0, 0);
+        }
+      }
+      if (PHASE == 0) {
+        // accumulator element v of a lane: token row 8*(v/4) + 4*half + v%4, query column `col`
+        if (shift > 0) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = 8 * (v / 4) + 4 * half + (v % 4);
+            if (row < shift) acc[0][v] = -INFINITY;
+          }
+        }
+        if (CAUSAL && base_t + kTile > un.len - sh.causal + 1) {
+          const int lim1[1] = {lim[b]};
+          mask_causal<1>(acc, lim1, base_t, half);
+        }
+        if (cnt) logits_with_counts<1>(acc, cnt, base_t, half, sl2);
+        float tm = acc[0][0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) tm = fmaxf(tm, acc[0][v]);
+        const float m_new = fmaxf(m_run[b], tm * sc);
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        float sum = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum += ex2(fmaf(acc[0][v], sc, -m_safe));
+        l_run[b] = l_run[b] * ex2(m_run[b] - m_safe) + sum;
+        m_run[b] = m_new;
+      } else {
+        // products taken as Q K^T: accumulator element v is query row 32 b + 8 (v / 4) + 4 half + v % 4 and the
+        // lane's column is ONE token
+        const bool tail = CAUSAL && base_t + kTile > un.len - sh.causal + 1;       // uniform
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int q0 = 32 * b + 8 * g + 4 * half;
+          const float4 c4 = *reinterpret_cast<const float4*>(&sm_cq[q0]);
+          const float cq[4] = {c4.x, c4.y, c4.z, c4.w};
+          float e[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) e[i] = ex2(fmaf(acc[0][4 * g + i], sl2, -cq[i]));
+          if (tail) {
+            const int4 l4 = *reinterpret_cast<const int4*>(&sm_lim[q0]);
+            const int lq[4] = {l4.x, l4.y, l4.z, l4.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) e[i] = (base_t + col > lq[i]) ? 0.f : e[i];
+          }
+          p_tok += (e[0] + e[1]) + (e[2] + e[3]);
+        }
+      }
+    }
+    if (PHASE == 1) {
+      p_tok += __shfl_xor(p_tok, 32, kWave);
+      if (qp > 0) p_tok += alpha_bar[un.in_row + base_t + col];              // the rows of the launches before
+      if (cnt && last_launch) p_tok *= (float)cnt[base_t + col];
+      if (half == 0 && col >= shift) alpha_bar[un.in_row + base_t + col] = p_tok;
+    }
+#pragma unroll
+    for (int i = 0; i < NQ4; ++i) a4[i] = an4[i];
+  }
+
+  if (PHASE == 0) {
+    // the two halves of a wavefront hold the same query column for different token rows
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+      const float m_o = __shfl_xor(m_run[b], 32, kWave);
+      const float l_o = __shfl_xor(l_run[b], 32, kWave);
+      const float m_n = fmaxf(m_run[b], m_o);
+      const float m_s = (m_n == -INFINITY) ? 0.f : m_n;
+      l_run[b] = l_run[b] * ex2(m_run[b] - m_s) + l_o * ex2(m_o - m_s);
+      m_run[b] = m_n;
+      if (half == 0) sm_stats[wave][b * 32 + col] = make_float2(m_run[b], l_run[b]);
+    }
+    __syncthreads();
+    if (tid < rows_here) {
+      float M = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm_stats[w][tid].x);
+      float Z = 0.f;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const float2 st = sm_stats[w][tid];
+        if (st.y > 0.f) Z += st.y * ex2(st.x - M);
+      }
+      stats_part[(part_base + chunk) * R + qp + tid] = make_float2(M, Z);
+    }
+  }
+}
+
+template <int D, bool CAUSAL>
+hipError_t launch_f32_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const int32_t* counts_in,
+                        float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+  dim3 grid(tab.total_chunks), block(kThreads);
+  hipError_t e;
+  for (int qp = 0; qp < sh.R; qp += 128) {
+    hipLaunchKernelGGL((score_mfma_f32_kernel<D, 0, CAUSAL>), grid, block, 0, stream, tab, sh, (const float*)Q,
+                       (const float*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row, qp);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  if ((e = launch_score_finalize(tab, sh, ws, stream)) != hipSuccess) return e;
+  for (int qp = 0; qp < sh.R; qp += 128) {
+    hipLaunchKernelGGL((score_mfma_f32_kernel<D, 1, CAUSAL>), grid, block, 0, stream, tab, sh, (const float*)Q,
+                       (const float*)K, counts_in, alpha_bar, ws.stats_part, ws.c_row, qp);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+template <int D>
+hipError_t launch_f32(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const int32_t* counts_in,
+                      float* alpha_bar, const Workspace& ws, hipStream_t stream) {
+  return sh.causal > 0 ? launch_f32_t<D, true>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
+                       : launch_f32_t<D, false>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+}
+
 }  // namespace
 
 bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
-  if (dt != KVS_BF16 || sh.R < 16) return false;
+  if (sh.R < 16) return false;
   for (int i = 0; i < tab.n_units; ++i) {
     if (tab.u[i].len < kTile) return false;   // the tile loads assume 32 whole rows per unit
   }
@@ -913,16 +1151,21 @@ bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
 
 // Sweep 1 of the kernel for more than 64 query rows can carry the pass over V along (o_part then holds one partial
 // per score chunk).
-bool score_mfma_takes_values(const Shape& sh) {
+bool score_mfma_takes_values(const Shape& sh, kvs_dtype dt) {
+  if (dt != KVS_BF16) return false;
   const char* e = std::getenv("KVS_SCORE_WIDE");
   const bool wide_off = e && e[0] == '0';
   return sh.R > 64 && (sh.R <= 128 || !wide_off);
 }
 
 // V: non-null asks for that fused pass (only where score_mfma_takes_values says so).
-hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
                              const int32_t* counts_in, float* alpha_bar, const Workspace& ws, const void* V,
                              hipStream_t stream) {
+  if (dt == KVS_F32) {
+    return sh.D == 64 ? launch_f32<64>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream)
+                      : launch_f32<128>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
+  }
   return sh.D == 64 ? launch_d<64>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream)
                     : launch_d<128>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
 }

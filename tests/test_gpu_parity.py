@@ -71,6 +71,15 @@ SCORE_CASES = [
     ("tiny", "f32", 128, 2, 3, [777], None),
     ("tiny", "f32", 64, 3, 7, [1300, 64], None),
     ("tiny", "f32", 64, 1, 1, [257], None),
+    # fp32 with 16 query rows or more: the fp32 matrix-core kernel (and the vector-ALU one on the same shapes)
+    ("tiny", "f32", 128, 4, 32, [2100, 45], None),                    # 128 rows, a ragged last tile, a short unit
+    ("tiny", "f32", 128, 4, 32, [2100], "valu"),
+    ("tiny", "f32", 64, 4, 16, [1000, 32], None),                     # head_dim 64, a unit of exactly one tile
+    ("tiny", "f32", 128, 5, 32, [1500], None),                        # 160 rows: two launches per sweep
+    ("tiny", "f32", 64, 7, 40, [900], None),                          # 280 rows: three launches, the last of 24 rows
+    ("tiny", "f32", 128, 1, 16, [5000], None),                        # 16 rows: half a block
+    ("stream2560", "f32", 128, 4, 8, [2560, 700], None),              # with cardinalities
+    ("stream2560", "f32", 128, 5, 32, [1300], None),                  # ... and two launches
     ("llama8b_8k", "bf16", 128, 4, 32, [2500], None),
     ("llama8b_8k", "bf16", 128, 4, 32, [2500], "valu"),
     ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053, 40], "fuse"),     # ragged tiles, a last chunk of 5 rows
@@ -357,6 +366,8 @@ def test_merge_bf16_output_rounds_to_nearest_even():
 
 CAUSAL_CASES = [
     # base, dtype, D, G, W, lengths, path: every score kernel, masked rows across tile and chunk borders
+    ("tiny", "f32", 128, 4, 32, [2053, 40], None),              # fp32 matrix-core kernel, 128 rows
+    ("tiny", "f32", 64, 5, 32, [900], None),                    # ... 160 rows in two launches
     ("tiny", "f32", 64, 2, 5, [777, 5], None),                  # vector-ALU kernel; a unit that is all window
     ("llama8b_8k", "bf16", 128, 1, 20, [700, 33], None),        # 20 rows in one MFMA block
     ("llama8b_8k", "bf16", 64, 2, 32, [900], None),             # 64 rows
@@ -506,6 +517,13 @@ def test_step_qwen_shape_full_size_two_heads():
     """The same layout at the headline's length, 32768 -> 4096 tokens, two KV heads of one layer."""
     w = WORKLOADS["qwen7b_32k"]
     check_step(w, [accepted_unit(w, 3, 0, h) for h in range(2)])
+
+
+def test_step_fp32_on_the_llama_layout_reduced():
+    """fp32 caches with a 128-row window (the fp32 matrix-core score kernel), 4096 -> 1024 tokens: the 1e-5 bar."""
+    w = WORKLOADS["llama8b_8k"].scaled(dtype="f32", length=("fixed", 4096), budget=("fixed", 1024))
+    check_step(w, [accepted_unit(w, 0, 0, h) for h in range(2)])
+    check_step(w, [accepted_unit(w, 0, 0, 0)], "valu")
 
 
 def test_step_with_causal_window():
