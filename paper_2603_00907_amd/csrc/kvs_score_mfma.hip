@@ -1,4 +1,4 @@
-// Score kernels, MFMA path: bf16 inputs, query windows of at least 16 rows.
+// Score kernels, MFMA path: query windows of at least four rows (bf16; fp32 at the end of the file).
 //
 // Two sweeps over K (Sec. 4.1, Eq. attn_def_vec: logits, softmax over all cached Keys, here
 // averaged over the unit's query rows): sweep 0 leaves per-chunk softmax statistics (running
@@ -1141,8 +1141,12 @@ hipError_t launch_f32(const UnitTable& tab, const Shape& sh, const void* Q, cons
 
 }  // namespace
 
+// One to three query rows stay with the vector kernels (a dot product per row and token keeps up with memory
+// there); from four rows on a padded block of 32 on the matrix cores is faster (measured at 8 rows, 32 units of
+// 32768 tokens, bf16: 260 against 420 us for the step).
 bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
-  if (sh.R < 16) return false;
+  (void)dt;
+  if (sh.R < 4) return false;
   for (int i = 0; i < tab.n_units; ++i) {
     if (tab.u[i].len < kTile) return false;   // the tile loads assume 32 whole rows per unit
   }

@@ -8,8 +8,8 @@
 //
 // Layout: a row of K is read by LPR = row_bytes / 16 adjacent lanes, 16 bytes each, so one
 // wavefront load instruction fetches 64 / LPR whole rows.  Dot products are reduced across the
-// LPR lanes with DPP adds.  This is the path for query windows below 16 rows and for fp32 inputs;
-// the bf16 MFMA path lives in kvs_score_mfma.hip.
+// LPR lanes with DPP adds.  This is the path for query windows of one to three rows and for units
+// shorter than an MFMA tile; the matrix-core kernels live in kvs_score_mfma.hip.
 #include "kvs_device.h"
 
 namespace kvs {
@@ -67,34 +67,51 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
 #pragma unroll
     for (int j = 0; j < kQB; ++j) { m[j] = -INFINITY; l[j] = 0.f; }
 
-    for (int t = t0 + wave * RPW + grp; t < t1; t += RPB) {
-      float kf[EPL];
-      Piece<T>::unpack(Kp[(size_t)t * LPR], kf);
-      // a row that stands for c tokens with this Key: c equal softmax terms, i.e. the logit plus log c
-      const float lc = counts_in ? log2f((float)counts_in[un.in_row + t]) : 0.f;
-      float a = 0.f;
+    // kUnroll rows of a lane group are requested before the first is used (one row per trip left the sweep
+    // waiting for memory most of the time)
+    constexpr int kUnroll = 4;
+    for (int tb = t0 + wave * RPW + grp; tb < t1; tb += RPB * kUnroll) {
+      uint4 raw[kUnroll];
+      int cn[kUnroll];
 #pragma unroll
-      for (int j = 0; j < kQB; ++j) {
-        float d = 0.f;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) d = fmaf(qf[j][i], kf[i], d);
-        const float s = fmaf(row_group_sum<LPR>(d), sh.scale_log2, lc);
-        if (t > lim[j]) continue;              // masked: no term in this row's softmax
-        if (PHASE == 0) {
-          if (s > m[j]) {
-            l[j] = l[j] * __builtin_amdgcn_exp2f(m[j] - s) + 1.f;
-            m[j] = s;
-          } else {
-            l[j] += __builtin_amdgcn_exp2f(s - m[j]);
-          }
-        } else {
-          a += __builtin_amdgcn_exp2f(s - cq[j]);
-        }
+      for (int u = 0; u < kUnroll; ++u) {
+        const int tc = min(tb + u * RPB, t1 - 1);
+        raw[u] = Kp[(size_t)tc * LPR];
+        cn[u] = counts_in ? counts_in[un.in_row + tc] : 1;
       }
-      if (PHASE == 1 && piece == 0) {
-        // the lane that owns the row keeps its running sum over the blocks of query rows
-        if (qb != 0) a += alpha_bar[un.in_row + t];
-        alpha_bar[un.in_row + t] = a;
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        const int t = tb + u * RPB;
+        if (t >= t1) break;
+        float kf[EPL];
+        Piece<T>::unpack(raw[u], kf);
+        // a row that stands for c tokens with this Key: c equal softmax terms, i.e. the logit plus log c
+        const float lc = counts_in ? log2f((float)cn[u]) : 0.f;
+        float a = 0.f;
+#pragma unroll
+        for (int j = 0; j < kQB; ++j) {
+          if (qb + j >= R) break;                  // uniform: the last block of rows may be a short one
+          float d = 0.f;
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) d = fmaf(qf[j][i], kf[i], d);
+          const float s = fmaf(row_group_sum<LPR>(d), sh.scale_log2, lc);
+          if (t > lim[j]) continue;              // masked: no term in this row's softmax
+          if (PHASE == 0) {
+            if (s > m[j]) {
+              l[j] = l[j] * __builtin_amdgcn_exp2f(m[j] - s) + 1.f;
+              m[j] = s;
+            } else {
+              l[j] += __builtin_amdgcn_exp2f(s - m[j]);
+            }
+          } else {
+            a += __builtin_amdgcn_exp2f(s - cq[j]);
+          }
+        }
+        if (PHASE == 1 && piece == 0) {
+          // the lane that owns the row keeps its running sum over the blocks of query rows
+          if (qb != 0) a += alpha_bar[un.in_row + t];
+          alpha_bar[un.in_row + t] = a;
+        }
       }
     }
 

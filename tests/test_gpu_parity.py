@@ -71,7 +71,7 @@ SCORE_CASES = [
     ("tiny", "f32", 128, 2, 3, [777], None),
     ("tiny", "f32", 64, 3, 7, [1300, 64], None),
     ("tiny", "f32", 64, 1, 1, [257], None),
-    # fp32 with 16 query rows or more: the fp32 matrix-core kernel (and the vector-ALU one on the same shapes)
+    # fp32 with four query rows or more: the fp32 matrix-core kernel (and the vector-ALU one on the same shapes)
     ("tiny", "f32", 128, 4, 32, [2100, 45], None),                    # 128 rows, a ragged last tile, a short unit
     ("tiny", "f32", 128, 4, 32, [2100], "valu"),
     ("tiny", "f32", 64, 4, 16, [1000, 32], None),                     # head_dim 64, a unit of exactly one tile
