@@ -526,6 +526,39 @@ def test_step_fp32_on_the_llama_layout_reduced():
     check_step(w, [accepted_unit(w, 0, 0, 0)], "valu")
 
 
+def random_step_case(rng):
+    """One random but seeded shape of the step: dtype, head dim, GQA group, window, length, budget, sink and recent
+    rows, cardinalities or the causal mask, the number of units and the score path."""
+    dtype = str(rng.choice(["bf16", "bf16", "f32"]))
+    D = int(rng.choice([64, 128]))
+    G = int(rng.choice([1, 2, 4, 5, 7, 8]))
+    W = int(rng.choice([1, 3, 8, 16, 32, 40]))
+    counts = bool(rng.random() < 0.3)
+    causal = bool(rng.random() < 0.25) and not counts
+    n = int(rng.choice([rng.integers(300, 900), rng.integers(900, 3000), rng.integers(3000, 7000)]))
+    n = max(n, 700 if counts else 0, W + 80)
+    n_sink = int(rng.choice([0, 4, 32]))
+    n_recent = int(rng.choice([0, 0, 16]))
+    budget = max(int(n * float(rng.choice([0.125, 0.25, 0.5, 0.8]))), n_sink + n_recent + 8)
+    kw = dict(dtype=dtype, head_dim=D, group=G, window=W, length=("fixed", n), budget=("fixed", budget),
+              n_sink=n_sink, n_recent=n_recent)
+    if counts:
+        kw["fresh_tail"] = min(512, n // 5)
+    w = WORKLOADS["stream2560" if counts else "llama8b_8k"].scaled(**kw)
+    path = rng.choice([None, None, "fuse", "narrow"])
+    return w, causal, int(rng.integers(1, 4)), path
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_step_random_shapes(seed):
+    """Seeded random shapes (every score kernel, both dtypes, ragged tiles, sink and recent rows, budgets from an
+    eighth to four fifths of the length), each unit accepted and compared like the named configurations."""
+    rng = np.random.default_rng(1000 + seed)
+    w, causal, n_units, path = random_step_case(rng)
+    accepted = [accepted_unit(w, 0, 0, h, causal=causal) for h in range(n_units)]
+    check_step(w, accepted, path, causal=causal)
+
+
 def test_step_with_causal_window():
     """The whole step with the causal mask inside the window, bf16 (MFMA score) and fp32 (vector-ALU score)."""
     w = WORKLOADS["llama8b_8k"]
