@@ -21,6 +21,10 @@ from test_gpu_parity import TOL_ALPHA, compare_outputs, merge_case, torch_sync, 
 pytestmark = pytest.mark.gpu
 
 TOL_NORMS = 5e-5     # measured: at most 1.1e-5 over the cases below
+# A_t carries the factor |1 - 2 alpha|, which vanishes at alpha = 1/2: there the rounding of a row's own attention
+# weight (fp32 softmax, relative 1e-6) is all that is left of A_t, whatever the arithmetic.  Such a row's share is
+# therefore held to its size without that factor, alpha ||v - o||, times this bound on alpha's relative error.
+TOL_ALPHA_ROW = 4e-6
 
 
 def per_query_buffers(batch):
@@ -70,7 +74,13 @@ def test_sensitivity_matches_oracle(base, D, G, W, lens, causal):
         assert np.max(np.abs(alpha[r0:r0 + n] - ra) / ra) < TOL_ALPHA
         gA, gC = A[r0:r0 + n], C[r0:r0 + n - 1]
         assert np.isfinite(gA).all() and np.isfinite(gC).all()
-        eA = np.max(np.abs(gA - A_ref) / A_ref)
+        rows = O.attention_rows(u.Q, u.K, causal_window=cw)
+        V64 = u.V.astype(np.float64)
+        size = np.zeros(n)                           # mean over the rows of alpha ||v_t - o|| (no |1 - 2 alpha|)
+        for a_q in rows:
+            size += a_q * np.linalg.norm(V64 - a_q @ V64, axis=1)
+        size /= rows.shape[0]
+        eA = np.max(np.abs(gA - A_ref) / (A_ref + (TOL_ALPHA_ROW / TOL_NORMS) * size))
         eC = np.max(np.abs(gC - C_ref) / C_ref)
         assert eA < TOL_NORMS, (i, "A", eA)
         assert eC < TOL_NORMS, (i, "C", eC)
