@@ -177,6 +177,7 @@ def check_select(alphas, budgets, n_sink, n_recent):
     (5000, 33, 32, 0, "lognormal"), (4096, 1024, 0, 0, "ties"), (4096, 1024, 32, 100, "ties"),
     (3000, 700, 32, 0, "uniform"), (32801, 4096, 32, 0, "lognormal"), (32802, 4096, 32, 0, "lognormal"),
     (40000, 10000, 32, 0, "ties"), (131072, 8192, 32, 0, "lognormal"), (1 << 22, 1 << 20, 32, 0, "lognormal"),
+    (70001, 9000, 4, 7, "uniform"), (50003, 25000, 0, 100, "zeros"), (100000, 97000, 1, 100, "ties"),
     (50, 50, 32, 0, "dirichlet"),
     (50, 80, 32, 0, "dirichlet"), (34, 33, 32, 0, "dirichlet"), (1, 1, 32, 0, "dirichlet"),
     (20, 6, 2, 3, "zeros")])
