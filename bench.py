@@ -281,11 +281,11 @@ def main():
                    if w.name == "llama8b_32k" else f"merged KV cache rows/s and achieved HBM GB/s (% of peak), {w.name}"),
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 in/out, f32 accumulate" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "layers": layers, "kv_heads": w.n_kv_heads, "q_heads": w.group * w.n_kv_heads,
                    "head_dim": D, "window": w.window, "tokens": lens_seq if w.n_seq > 1 else lens_seq[0],
                    "budget": budgets[0] if w.n_seq == 1 else "25% of length", "n_sink": w.n_sink,
-                   "key_rule": args.key_rule, "layers_per_call": lpc, "streams": n_streams, "launch": "hip graph replay" if args.graph else "host",
+                   "key_rule": args.key_rule, "io_dtype": w.dtype, "accumulate": "f32", "layers_per_call": lpc, "streams": n_streams, "launch": "hip graph replay" if args.graph else "host",
                    "us_per_layer": ms_per_step * 1e3 / layers,
                    "one_call_per_layer": None if seq_ms is None else {
                        "ms_per_step": seq_ms, "us_per_layer": seq_ms * 1e3 / layers,
