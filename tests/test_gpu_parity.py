@@ -13,9 +13,9 @@ import numpy as np
 import pytest
 
 from oracle import kvs_oracle as O
-from workloads import WORKLOADS, generate_unit, unit_lengths
+from workloads import WORKLOADS, generate_unit, unit_budget, unit_lengths
 
-from helpers import DeviceBatch, accepted_unit, from_device, rel_err_rows
+from helpers import DeviceBatch, accepted_unit, from_device, rel_err_rows, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -658,6 +658,69 @@ def test_step_ragged_batch_reduced():
             a = accepted_unit(w, 0, s, h, n=n)
             accepted.append(a)
     check_step(w, accepted)
+
+
+def test_step_ragged_batch_full_size_in_one_call():
+    """The ragged batch at its full size: 16 sequences of 4096..65536 tokens, 8 KV heads each, all 128 units in ONE
+    kvs_step call (two launch groups, units longer than the select kernel's key cache among them).  Three sampled
+    units (the longest sequence, the shortest, the first of the second launch group) are compared with the oracle;
+    every unit must satisfy the invariants that hold at any size."""
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    import paper_2603_00907_amd as kvs
+    w = WORKLOADS["ragged16"]
+    D, R, H = w.head_dim, w.q_rows, w.n_kv_heads
+    seq_lens = unit_lengths(w)
+    ids = [(s, h) for s in range(w.n_seq) for h in range(H)]
+    lens = [seq_lens[s] for s, _ in ids]
+    budgets = [unit_budget(w, n) for n in lens]
+    longest, shortest = int(np.argmax(seq_lens)), int(np.argmin(seq_lens))
+    sampled = {(longest, 3): None, (shortest, 0): None, (8, 0): None}
+    for s, h in sampled:
+        sampled[(s, h)] = accepted_unit(w, 0, s, h)
+    p = kvs.Problem(lens=lens, budgets=budgets, group=w.group, window=w.window, head_dim=D, dtype="bf16",
+                    n_sink=w.n_sink, n_recent=w.n_recent)
+    K = torch.empty((p.rows_in, D), dtype=torch.bfloat16, device="cuda")
+    V = torch.empty_like(K)
+    Q = torch.empty((len(ids), R, D), dtype=torch.bfloat16, device="cuda")
+
+    def unit(sh):
+        a = sampled.get(sh)
+        return a.inputs if a is not None else generate_unit(w, 0, sh[0], sh[1])
+
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+        for i, u in enumerate(pool.map(unit, ids)):
+            r0 = p.in_rows[i]
+            K[r0:r0 + lens[i]] = to_device(u.K, "bf16")
+            V[r0:r0 + lens[i]] = to_device(u.V, "bf16")
+            Q[i] = to_device(u.Q.reshape(R, D), "bf16")
+    K_out = torch.empty((p.rows_out, D), dtype=torch.bfloat16, device="cuda")
+    V_out = torch.empty_like(K_out)
+    counts = torch.empty(p.rows_out, dtype=torch.int32, device="cuda")
+    mask = torch.empty(p.rows_in, dtype=torch.uint8, device="cuda")
+    slot = torch.empty(p.rows_in, dtype=torch.int32, device="cuda")
+    ws = torch.empty(kvs.kvs_workspace_size(p), dtype=torch.uint8, device="cuda")
+    kvs.kvs_step(p, Q, K, V, K_out, V_out, counts, ws, slot_of_token_out=slot, edge_mask_out=mask,
+                 stream=torch.cuda.current_stream().cuda_stream)
+    torch_sync()
+    assert torch.isfinite(K_out.float()).all() and torch.isfinite(V_out.float()).all()
+    mask_h, slot_h, counts_h = mask.cpu().numpy(), slot.cpu().numpy(), counts.cpu().numpy()
+    for i, (n, B) in enumerate(zip(lens, budgets)):
+        r0, o0 = p.in_rows[i], p.out_rows[i]
+        m, s, c = mask_h[r0:r0 + n], slot_h[r0:r0 + n], counts_h[o0:o0 + B]
+        assert m.sum() == n - B and not m[:w.n_sink].any() and m[-1] == 0, i
+        assert s[0] == 0 and s[-1] == B - 1 and (np.diff(s) == 1 - m[:-1]).all(), i
+        assert c.sum() == n and (c >= 1).all(), i
+    for (sq, h), a in sampled.items():
+        i = sq * H + h
+        n, B, r0, o0 = lens[i], budgets[i], p.in_rows[i], p.out_rows[i]
+        assert (mask_h[r0:r0 + n] == a.ref.mask).all(), f"unit {i}: selected edges differ (gap {a.gap:.2e})"
+        assert (slot_h[r0:r0 + n] == a.ref.slot).all(), f"unit {i}: slot map differs"
+        ref = a.ref.merged
+        assert (counts_h[o0:o0 + B] == ref.counts).all()
+        ek = rel_err_rows(from_device(K_out[o0:o0 + B]), ref.K_out)
+        ev = rel_err_rows(from_device(V_out[o0:o0 + B]), ref.V_out)
+        assert ek <= TOL_KV["bf16"] and ev <= TOL_KV["bf16"], (i, ek, ev)
 
 
 def test_step_more_units_than_one_launch_takes():
