@@ -660,24 +660,20 @@ def test_step_ragged_batch_reduced():
     check_step(w, accepted)
 
 
-def test_step_ragged_batch_full_size_in_one_call():
-    """The ragged batch at its full size: 16 sequences of 4096..65536 tokens, 8 KV heads each, all 128 units in ONE
-    kvs_step call (two launch groups, units longer than the select kernel's key cache among them).  Three sampled
-    units (the longest sequence, the shortest, the first of the second launch group) are compared with the oracle;
-    every unit must satisfy the invariants that hold at any size."""
+def check_whole_batch_in_one_call(w, layer, sampled_ids):
+    """Every (sequence, KV head) of a workload's layer as the units of ONE kvs_step call.  The units named in
+    `sampled_ids` are accepted units and are compared with the oracle like any other; every unit must satisfy the
+    invariants that hold at any size (r edges selected, none in the sink, consecutive slot numbers, cardinalities
+    adding up)."""
     import torch
     from concurrent.futures import ThreadPoolExecutor
     import paper_2603_00907_amd as kvs
-    w = WORKLOADS["ragged16"]
     D, R, H = w.head_dim, w.q_rows, w.n_kv_heads
     seq_lens = unit_lengths(w)
     ids = [(s, h) for s in range(w.n_seq) for h in range(H)]
     lens = [seq_lens[s] for s, _ in ids]
     budgets = [unit_budget(w, n) for n in lens]
-    longest, shortest = int(np.argmax(seq_lens)), int(np.argmin(seq_lens))
-    sampled = {(longest, 3): None, (shortest, 0): None, (8, 0): None}
-    for s, h in sampled:
-        sampled[(s, h)] = accepted_unit(w, 0, s, h)
+    sampled = {sh: accepted_unit(w, layer, sh[0], sh[1]) for sh in sampled_ids}
     p = kvs.Problem(lens=lens, budgets=budgets, group=w.group, window=w.window, head_dim=D, dtype="bf16",
                     n_sink=w.n_sink, n_recent=w.n_recent)
     K = torch.empty((p.rows_in, D), dtype=torch.bfloat16, device="cuda")
@@ -686,7 +682,7 @@ def test_step_ragged_batch_full_size_in_one_call():
 
     def unit(sh):
         a = sampled.get(sh)
-        return a.inputs if a is not None else generate_unit(w, 0, sh[0], sh[1])
+        return a.inputs if a is not None else generate_unit(w, layer, sh[0], sh[1])
 
     with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
         for i, u in enumerate(pool.map(unit, ids)):
@@ -721,6 +717,22 @@ def test_step_ragged_batch_full_size_in_one_call():
         ek = rel_err_rows(from_device(K_out[o0:o0 + B]), ref.K_out)
         ev = rel_err_rows(from_device(V_out[o0:o0 + B]), ref.V_out)
         assert ek <= TOL_KV["bf16"] and ev <= TOL_KV["bf16"], (i, ek, ev)
+
+
+def test_step_ragged_batch_full_size_in_one_call():
+    """The ragged batch at its full size: 16 sequences of 4096..65536 tokens, 8 KV heads each, all 128 units in ONE
+    kvs_step call (two launch groups, units longer than the select kernel's key cache among them).  Sampled for the
+    oracle: the longest sequence, the shortest, the first unit of the second launch group."""
+    w = WORKLOADS["ragged16"]
+    seq_lens = unit_lengths(w)
+    check_whole_batch_in_one_call(w, 0, [(int(np.argmax(seq_lens)), 3), (int(np.argmin(seq_lens)), 0), (8, 0)])
+
+
+def test_step_stress_full_size_all_heads_in_one_call():
+    """The stress configuration as it is benchmarked: 8 KV heads of 131072 tokens -> 8192 with 512 query rows
+    (two launches of 256 rows per score sweep, the selection of units four times the key cache) in one call; head 0
+    is compared with the oracle."""
+    check_whole_batch_in_one_call(WORKLOADS["stress128k"], 0, [(0, 0)])
 
 
 def test_step_more_units_than_one_launch_takes():
