@@ -162,10 +162,19 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     if (tile_t0 >= t1) return false;          // no such tile
     const int base_t = min(tile_t0, t1 - kTile);
     const unsigned char* base = reinterpret_cast<const unsigned char*>(Kg) + (size_t)base_t * ROWB;
+    // a launch larger than the caches streams K past them (the cache-policy bit is an immediate: two copies)
+    if (sh.stream) {
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]), KVS_LDS_PTR(my_k + buf * TILEB + i * 1024),
-                                       16, 0, 0);
+      for (int i = 0; i < NLD; ++i) {
+        __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]),
+                                         KVS_LDS_PTR(my_k + buf * TILEB + i * 1024), 16, 0, kNonTemporal);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]),
+                                         KVS_LDS_PTR(my_k + buf * TILEB + i * 1024), 16, 0, 0);
+      }
     }
     return true;
   };
