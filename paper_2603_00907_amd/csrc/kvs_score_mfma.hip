@@ -162,8 +162,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
     if (tile_t0 >= t1) return false;          // no such tile
     const int base_t = min(tile_t0, t1 - kTile);
     const unsigned char* base = reinterpret_cast<const unsigned char*>(Kg) + (size_t)base_t * ROWB;
-    // a launch larger than the caches streams K past them (the cache-policy bit is an immediate: two copies)
-    if (sh.stream) {
+    // a launch larger than the caches streams K past them in sweep 0 (the cache-policy bit is an immediate: two
+    // copies); sweep 1 leaves what it can of K in the memory-side cache for the merge pass
+    if (sh.stream && PHASE == 0) {
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
         __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]),
@@ -525,8 +526,10 @@ __global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mf
     const unsigned char* base = Kg + (size_t)base_t * ROWB;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
+      // (sweep 1 keeps the ordinary policy: what it leaves of K in the memory-side cache is what the merge
+      // pass, two short launches later, starts from: 3 % of the step on one stream, 1 % on two)
       __builtin_amdgcn_global_load_lds(KVS_GLOBAL_PTR(base + ld_off[i]), KVS_LDS_PTR(my_k + i * 1024), 16, 0,
-                                       STREAM ? kNonTemporal : 0);
+                                       (STREAM && PHASE == 0) ? kNonTemporal : 0);
     }
     return true;
   };
