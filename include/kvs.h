@@ -53,9 +53,15 @@ typedef enum {
   KVS_ERR_DTYPE = 2,        /* io_dtype is neither KVS_F32 nor KVS_BF16, or not the one the call supports */
   KVS_ERR_BUDGET = 3,       /* budget < n_sink + 1 + n_recent for a unit that has to merge (len > budget),
                                or budget < 1 */
-  KVS_ERR_WORKSPACE = 4,    /* workspace null, misaligned (256 B) or smaller than kvs_workspace_size() */
+  KVS_ERR_WORKSPACE = 4,    /* workspace null, misaligned (256 B) or smaller than kvs_workspace_size(); only the
+                               calls that use one check it: kvs_select, kvs_merge_compact,
+                               kvs_merge_compact_counts and kvs_merge_compact_norms use none and ignore
+                               ws / ws_bytes (NULL and 0 are fine there)                               */
   KVS_ERR_ALIAS = 5,        /* an output overlaps an input, another output or the workspace */
-  KVS_ERR_DEVICE = 6        /* a HIP launch failed; hipGetLastError() holds the cause */
+  KVS_ERR_DEVICE = 6        /* a HIP launch failed.  The library reads the calling thread's HIP error state after
+                               each launch (which clears it) and drops an error left pending by the caller's own
+                               earlier HIP calls when a call starts; the cause is printed to stderr when the
+                               testing switch KVS_DEBUG_VERBOSE (kvs_debug.h) is set                      */
 } kvs_status;
 
 typedef enum { KVS_F32 = 0, KVS_BF16 = 1 } kvs_dtype;

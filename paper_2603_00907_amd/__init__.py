@@ -32,6 +32,9 @@ from .binding import (  # noqa: F401
     kvs_step,
     kvs_step_counts,
     kvs_step_per_query,
+    kvs_debug_set,
+    kvs_debug_get,
+    DEBUG_SWITCHES,
     kvs_version,
     kvs_workspace_size,
     load_library,

@@ -1,27 +1,32 @@
 """Builds libkvs.so (HIP kernels + C ABI) for gfx950, in-tree, with hipcc.
 
-    python -m paper_2603_00907_amd.build [--report]
+    python -m paper_2603_00907_amd.build [--report] [--incremental]
 
-`--report` prints registers, LDS and occupancy of every kernel as the compiler sees them.
+Every source is compiled to an object of its own (side by side), then linked.  `--report` prints registers,
+LDS and occupancy of every kernel as the compiler sees them; `--incremental` recompiles only the sources that
+are newer than their objects (or older than a header).
 """
 
 from __future__ import annotations
 
+import glob
 import os
 import re
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvs.so")
+OBJ = os.path.join(HERE, "_build")
 
 SOURCES = ["kvs_api.hip", "kvs_score_valu.hip", "kvs_score_mfma.hip", "kvs_select.hip", "kvs_merge.hip", "kvs_decode.hip",
            "kvs_perquery.hip"]
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # hipcc must not form packed-fp32 instructions on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
@@ -35,15 +40,39 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(report: bool = False, defines=(), out: str = LIB) -> str:
-    cmd = [hipcc()] + FLAGS + (["-Rpass-analysis=kernel-resource-usage"] if report else [])
-    cmd += ["-D" + d for d in defines]
-    cmd += ["-o", out] + [os.path.join(CSRC, s) for s in SOURCES]
-    proc = subprocess.run(cmd, capture_output=True, text=True)
+def _stale(src: str, obj: str) -> bool:
+    if not os.path.exists(obj):
+        return True
+    deps = [src] + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    return any(os.path.getmtime(d) > os.path.getmtime(obj) for d in deps)
+
+
+def build(report: bool = False, defines=(), out: str = LIB, incremental: bool = False, jobs: int = 8) -> str:
+    """Compiles every source (all of them unless `incremental`) and links `out`."""
+    tag = ("_" + re.sub(r"\W+", "_", "_".join(defines))) if defines else ""
+    os.makedirs(OBJ, exist_ok=True)
+    base = [hipcc()] + FLAGS + (["-Rpass-analysis=kernel-resource-usage"] if report else [])
+    base += ["-D" + d for d in defines]
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in proc.stderr.splitlines() if noise not in l)
+
+    def compile_one(name):
+        src = os.path.join(CSRC, name)
+        obj = os.path.join(OBJ, os.path.splitext(name)[0] + tag + ".o")
+        if incremental and not report and not _stale(src, obj):
+            return obj, ""
+        proc = subprocess.run(base + ["-c", src, "-o", obj], capture_output=True, text=True)
+        err = "\n".join(l for l in proc.stderr.splitlines() if noise not in l)
+        if proc.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {name}:\n" + err)
+        return obj, err
+
+    with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(SOURCES)))) as pool:
+        done = list(pool.map(compile_one, SOURCES))
+    err = "\n".join(e for _, e in done if e)
+    proc = subprocess.run([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out] + [o for o, _ in done],
+                          capture_output=True, text=True)
     if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
+        raise RuntimeError("link failed:\n" + proc.stderr)
     if report:
         print(_summarise(err))
     elif err.strip() and "warning" in err:
@@ -72,4 +101,4 @@ def _summarise(text: str) -> str:
 
 
 if __name__ == "__main__":
-    print(build(report="--report" in sys.argv))
+    print(build(report="--report" in sys.argv, incremental="--incremental" in sys.argv))

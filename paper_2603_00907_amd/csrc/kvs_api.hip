@@ -1,6 +1,7 @@
 // Host layer of libkvs: argument validation, workspace carve-up, unit tables, launch sequencing.
 // Everything that can fail because of the arguments fails here, before the first launch.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -18,6 +19,35 @@ hipError_t launch_score_mfma(const UnitTable& tab, const Shape& sh, kvs_dtype dt
                              hipStream_t stream);
 bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt);
 bool score_mfma_takes_values(const Shape& sh, kvs_dtype dt);
+
+// ---- testing switches (kvs_debug.h): process-global, initial values read from the environment once, at load
+namespace {
+std::atomic<int> g_switch[KVS_DEBUG_N_SWITCHES];
+
+int env_choice(const char* name, const char* one, const char* two) {
+  const char* e = std::getenv(name);
+  if (e == nullptr) return 0;
+  if (one && std::strcmp(e, one) == 0) return 1;
+  if (two && std::strcmp(e, two) == 0) return 2;
+  return 0;
+}
+
+struct SwitchInit {
+  SwitchInit() {
+    g_switch[KVS_DEBUG_SCORE_PATH] = env_choice("KVS_SCORE_PATH", "valu", nullptr);
+    g_switch[KVS_DEBUG_SCORE_WIDE] = env_choice("KVS_SCORE_WIDE", "0", nullptr);
+    g_switch[KVS_DEBUG_FUSE_OBAR] = env_choice("KVS_FUSE_OBAR", "0", "1");
+    g_switch[KVS_DEBUG_DECODE_PATH] = env_choice("KVS_DECODE_PATH", "valu", "mfma");
+    const char* c = std::getenv("KVS_SCORE_CHUNK");
+    g_switch[KVS_DEBUG_SCORE_CHUNK] = c ? std::max(0, std::atoi(c)) : 0;
+    g_switch[KVS_DEBUG_VERBOSE] = std::getenv("KVS_VERBOSE") != nullptr;
+    g_switch[KVS_DEBUG_SCORE_FUSED] = env_choice("KVS_SCORE_FUSED", "0", "1");
+    g_switch[KVS_DEBUG_SELECT_SPLIT] = env_choice("KVS_SELECT_SPLIT", "0", "1");
+  }
+} g_switch_init;
+}  // namespace
+
+int debug_switch(kvs_debug_switch which) { return g_switch[which].load(std::memory_order_relaxed); }
 
 namespace {
 
@@ -87,7 +117,7 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
     long long total = 0;
     for (int u = 0; u < std::min(p->n_units, kMaxUnitsPerLaunch); ++u) total += p->len[u];
     long long want = total / kScoreWorkgroups;
-    if (const char* e = std::getenv("KVS_SCORE_CHUNK")) want = std::atoll(e);   // tuning aid
+    if (const int forced = debug_switch(KVS_DEBUG_SCORE_CHUNK)) want = forced;   // tuning aid
     want = std::min<long long>(std::max<long long>(want, kMinChunkLen), kMaxChunkLen);
     for (int u = 0; u < p->n_units; ++u) {
       Unit& un = plan->units[u];
@@ -211,6 +241,9 @@ kvs_status check_ws(const Plan& plan, const void* ws, size_t ws_bytes, Workspace
 // Calls f(table) for every group of at most kMaxUnitsPerLaunch units.
 template <typename F>
 kvs_status for_each_group(const Plan& plan, F&& f) {
+  // An error that the calling thread's earlier HIP calls left pending is not this call's: it is dropped here,
+  // so that what the launchers read after their launches is theirs.
+  (void)hipGetLastError();
   for (int first = 0; first < plan.n_units; first += kMaxUnitsPerLaunch) {
     UnitTable tab;
     std::memset(&tab, 0, sizeof(tab));
@@ -234,7 +267,7 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
     sh.stream = 2 * rows * sh.D * (long long)plan.elt > kStreamBytes;
     const hipError_t e = f(tab, sh);
     if (e != hipSuccess) {
-      if (std::getenv("KVS_VERBOSE")) {
+      if (debug_switch(KVS_DEBUG_VERBOSE)) {
         std::fprintf(stderr, "libkvs: launch failed in the group of units %d..%d: %s\n", first, first + tab.n_units - 1,
                      hipGetErrorString(e));
       }
@@ -249,24 +282,23 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
                         const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream,
                         const void* V, bool* o_done) {
-  // KVS_SCORE_PATH=valu forces the vector-ALU kernels (used by the tests to cover both paths).
+  // KVS_DEBUG_SCORE_PATH forces the vector-ALU kernels (used by the tests to cover both paths).
   // The pass over V rides along in sweep 1 when the launch is a large one (the streaming policy's threshold):
   // the edge selection then runs as a short launch of its own, one CU per unit, which costs less than the
   // separate pass over V saves (measured at 64 units of the headline shape: 199 against 226 us for sweep 1,
   // the pass over V and the selection).  A small launch keeps the selection hidden beside the pass over V
-  // (8 units: 38 against 45 us).  KVS_FUSE_OBAR=0 | 1 forces one or the other.
-  const char* force = std::getenv("KVS_SCORE_PATH");
-  const bool force_valu = force && std::strcmp(force, "valu") == 0;
+  // (8 units: 38 against 45 us).  KVS_DEBUG_FUSE_OBAR forces one or the other.
+  const bool force_valu = debug_switch(KVS_DEBUG_SCORE_PATH) == 1;
   if (o_done) *o_done = false;
   if (!force_valu && score_mfma_supported(tab, sh, dt)) {
-    const char* fuse = std::getenv("KVS_FUSE_OBAR");
+    const int fuse = debug_switch(KVS_DEBUG_FUSE_OBAR);
     // (The selection of a unit too long for the select kernel's LDS cache of keys takes several times longer,
     // 74 us at 65536 tokens: such launches keep it hidden beside the pass over V.)
     int longest = 0;
     for (int i = 0; i < tab.n_units; ++i) longest = std::max(longest, tab.u[i].len);
     bool want = sh.stream != 0 && longest <= 32768;
-    if (fuse && std::strcmp(fuse, "0") == 0) want = false;
-    if (fuse && std::strcmp(fuse, "1") == 0) want = true;
+    if (fuse == 1) want = false;
+    if (fuse == 2) want = true;
     const bool with_v = V != nullptr && o_done != nullptr && score_mfma_takes_values(sh, dt) && want;
     if (with_v) *o_done = true;
     return launch_score_mfma(tab, sh, dt, Q, K, counts_in, alpha_bar, ws, with_v ? V : nullptr, stream);
@@ -389,14 +421,10 @@ kvs_status kvs_step(const kvs_problem* p, const void* Q, const void* K, const vo
                          ws_bytes, hip_stream);
 }
 
-kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, const void* V, const int32_t* counts_in,
-                           void* K_out, void* V_out, int32_t* counts_out, int32_t* slot_of_token_out,
-                           uint8_t* edge_mask_out, void* ws, size_t ws_bytes, void* hip_stream) {
-  Plan plan;
-  kvs_status st = make_plan(p, &plan);
-  if (st != KVS_OK) return st;
-  Workspace w;
-  if ((st = check_ws(plan, ws, ws_bytes, &w, ws)) != KVS_OK) return st;
+// Pointer, alignment and overlap checks of a step's arguments; ws may be null (then it is left out).
+static kvs_status check_step_ranges(const Plan& plan, const void* Q, const void* K, const void* V,
+                                    const int32_t* counts_in, void* K_out, void* V_out, int32_t* counts_out,
+                                    int32_t* slot_of_token_out, uint8_t* edge_mask_out, void* ws, size_t ws_used) {
   const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
   const size_t kvo = (size_t)plan.rows_out * plan.shape.D * plan.elt;
   std::vector<Range> rs = {{Q, (size_t)plan.n_units * plan.shape.R * plan.shape.D * plan.elt, false},
@@ -404,12 +432,27 @@ kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, c
                            {V, kv, false},
                            {K_out, kvo, true},
                            {V_out, kvo, true},
-                           {counts_out, (size_t)plan.rows_out * 4, true},
-                           {ws, w.bytes, true}};
+                           {counts_out, (size_t)plan.rows_out * 4, true}};
+  if (ws) rs.push_back({ws, ws_used, true});
   if (slot_of_token_out) rs.push_back({slot_of_token_out, (size_t)plan.rows_in * 4, true});
   if (edge_mask_out) rs.push_back({edge_mask_out, (size_t)plan.rows_in, true});
   if (counts_in) rs.push_back({counts_in, (size_t)plan.rows_in * 4, false});
-  if ((st = check_ranges(rs)) != KVS_OK) return st;
+  return check_ranges(rs);
+}
+
+// kvs_step_counts with the workspace given either by the caller (ws, ws_bytes) or, for kvs_step_static, by
+// `fixed_ws` (then ws_bytes is its capacity and the caller's argument checks have run before any device call).
+static kvs_status step_with_workspace(const Plan& plan, const void* Q, const void* K, const void* V,
+                                      const int32_t* counts_in, void* K_out, void* V_out, int32_t* counts_out,
+                                      int32_t* slot_of_token_out, uint8_t* edge_mask_out, void* ws, size_t ws_bytes,
+                                      void* hip_stream) {
+  kvs_status st;
+  Workspace w;
+  if ((st = check_ws(plan, ws, ws_bytes, &w, ws)) != KVS_OK) return st;
+  if ((st = check_step_ranges(plan, Q, K, V, counts_in, K_out, V_out, counts_out, slot_of_token_out, edge_mask_out, ws,
+                              w.bytes)) != KVS_OK) {
+    return st;
+  }
 
   uint8_t* mask = edge_mask_out ? edge_mask_out : w.edge_mask;
   int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
@@ -426,6 +469,16 @@ kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, c
     return launch_merge(tab, sh2, plan.dtype, K, V, counts_in, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,
                         V_out, counts_out, s);
   });
+}
+
+kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, const void* V, const int32_t* counts_in,
+                           void* K_out, void* V_out, int32_t* counts_out, int32_t* slot_of_token_out,
+                           uint8_t* edge_mask_out, void* ws, size_t ws_bytes, void* hip_stream) {
+  Plan plan;
+  const kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  return step_with_workspace(plan, Q, K, V, counts_in, K_out, V_out, counts_out, slot_of_token_out, edge_mask_out, ws,
+                             ws_bytes, hip_stream);
 }
 
 kvs_status kvs_per_query_workspace_size(const kvs_problem* p, size_t* bytes) {
@@ -560,6 +613,16 @@ kvs_status kvs_decode_attention(const kvs_problem* p, const void* Q, const void*
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     return launch_decode(tab, sh, plan.dtype, Q, K, V, counts, (float*)ws, out, s);
   });
+}
+
+int kvs_debug_set(kvs_debug_switch which, int value) {
+  if ((int)which < 0 || which >= KVS_DEBUG_N_SWITCHES || value < 0) return -1;
+  return g_switch[which].exchange(value, std::memory_order_relaxed);
+}
+
+int kvs_debug_get(kvs_debug_switch which) {
+  if ((int)which < 0 || which >= KVS_DEBUG_N_SWITCHES) return -1;
+  return debug_switch(which);
 }
 
 const char* kvs_status_str(kvs_status s) {

@@ -460,11 +460,11 @@ hipError_t launch_decode(const UnitTable& tab, const Shape& sh, kvs_dtype dt, co
   // The vector-ALU kernel reads the cache once per four query rows: up to four rows it is as fast as the MFMA
   // kernel (both are latency-bound on caches of a few thousand rows), above that the MFMA kernel wins (measured,
   // 64 caches of 4096 rows: 42 against 62 us at 8 rows, 55 against 200 us at 32 rows).
-  // KVS_DECODE_PATH=valu|mfma forces one of them (used by the tests to cover both).
-  const char* force = std::getenv("KVS_DECODE_PATH");
+  // KVS_DEBUG_DECODE_PATH forces one of them (used by the tests to cover both).
+  const int force = debug_switch(KVS_DEBUG_DECODE_PATH);
   bool mfma = sh.R > kQB;
-  if (force && std::strcmp(force, "valu") == 0) mfma = false;
-  if (force && std::strcmp(force, "mfma") == 0) mfma = true;
+  if (force == 1) mfma = false;
+  if (force == 2) mfma = true;
   for (int i = 0; i < tab.n_units; ++i) mfma = mfma && tab.u[i].len >= kTile;   // its tiles hold 32 whole rows
   if (mfma) {
     return sh.D == 64 ? launch_mfma<64>(tab, sh, Q, K, V, counts, part, out, stream)

@@ -5,8 +5,12 @@
 #include <stdint.h>
 
 #include "kvs.h"
+#include "kvs_debug.h"
 
 namespace kvs {
+
+// Current value of a testing switch (kvs_debug.h): one relaxed atomic load, no environment lookup.
+int debug_switch(kvs_debug_switch which);
 
 constexpr int kMaxUnitsPerLaunch = 64;   // unit descriptors travel by value in the kernel arguments
 constexpr int kMaxChunks = 64;           // token chunks (= score workgroups) per unit

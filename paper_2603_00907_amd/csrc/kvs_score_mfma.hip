@@ -905,9 +905,8 @@ hipError_t launch_d(const UnitTable& tab, const Shape& sh, const void* Q, const 
   const int R = sh.R;
   if (R <= 32) return launch_t<D, 1, 1>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
   if (R <= 64) return launch_t<D, 2, 1>(tab, sh, Q, K, counts_in, alpha_bar, ws, stream);
-  // 65..256 rows: rows 64.. from LDS, one pass over K (KVS_SCORE_WIDE=0 keeps the kernel below for more than 128)
-  const char* env = std::getenv("KVS_SCORE_WIDE");
-  const bool wide_off = env && env[0] == '0';
+  // 65..256 rows: rows 64.. from LDS, one pass over K (KVS_DEBUG_SCORE_WIDE keeps the kernel below for more than 128)
+  const bool wide_off = debug_switch(KVS_DEBUG_SCORE_WIDE) == 1;
   if (R <= 128) return launch_wide<D, 2>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
   if (R <= 192 && !wide_off) return launch_wide<D, 3>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
   if (R <= 256 && !wide_off) return launch_wide<D, 4>(tab, sh, Q, K, counts_in, alpha_bar, ws, V, stream);
@@ -1169,8 +1168,7 @@ bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
 // per score chunk).
 bool score_mfma_takes_values(const Shape& sh, kvs_dtype dt) {
   if (dt != KVS_BF16) return false;
-  const char* e = std::getenv("KVS_SCORE_WIDE");
-  const bool wide_off = e && e[0] == '0';
+  const bool wide_off = debug_switch(KVS_DEBUG_SCORE_WIDE) == 1;
   return sh.R > 64 && (sh.R <= 128 || !wide_off);
 }
 

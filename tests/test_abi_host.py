@@ -15,9 +15,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "kvs.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(kvs_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(kvs_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -134,6 +137,25 @@ def test_pointer_workspace_and_alias_errors_are_host_side():
                      b["K_out"], b["K_out"], b["counts"]) == kvs.KVS_ERR_ALIAS
     assert status_of(kvs.kvs_merge_compact, p, b["K"], b["V"], b["alpha"], b["obar"], None, b["slot"],
                      b["K_out"], b["V_out"], b["counts"]) == kvs.KVS_ERR_INVALID_ARG
+
+
+def test_debug_switches_are_process_state_without_environment_lookups():
+    for name, idx in kvs.DEBUG_SWITCHES.items():
+        old = kvs.kvs_debug_get(name)
+        assert old >= 0
+        assert kvs.kvs_debug_set(name, 2) == old and kvs.kvs_debug_get(idx) == 2
+        assert kvs.kvs_debug_set(name, old) == 2
+    assert kvs.kvs_debug_set(len(kvs.DEBUG_SWITCHES), 1) == -1          # unknown switch
+    assert kvs.kvs_debug_set("verbose", -3) == -1 and kvs.kvs_debug_get(99) == -1
+    # the environment is read when the library is loaded, not by the calls
+    os.environ["KVS_SCORE_PATH"] = "valu"
+    try:
+        assert kvs.kvs_debug_get("score_path") == 0
+    finally:
+        del os.environ["KVS_SCORE_PATH"]
+    for src in os.listdir(os.path.join(ROOT, "paper_2603_00907_amd", "csrc")):
+        text = open(os.path.join(ROOT, "paper_2603_00907_amd", "csrc", src)).read()
+        assert "getenv" not in text or src == "kvs_api.hip", src
 
 
 def test_null_problem_and_null_tables():

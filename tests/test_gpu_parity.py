@@ -32,22 +32,20 @@ def variant(base, **kw):
     return WORKLOADS[base].scaled(**kw)
 
 
-class env_override:
-    def __init__(self, key, value):
-        self.key, self.value = key, value
+class switch_override:
+    """Sets one of the library's testing switches (include/kvs_debug.h) for the duration of a block."""
+
+    def __init__(self, name, value):
+        self.name, self.value = name, value
 
     def __enter__(self):
-        self.old = os.environ.get(self.key)
-        if self.value is None:
-            os.environ.pop(self.key, None)
-        else:
-            os.environ[self.key] = self.value
+        import paper_2603_00907_amd as kvs
+        self.old = kvs.kvs_debug_set(self.name, self.value)
+        assert self.old >= 0
 
     def __exit__(self, *a):
-        if self.old is None:
-            os.environ.pop(self.key, None)
-        else:
-            os.environ[self.key] = self.old
+        import paper_2603_00907_amd as kvs
+        kvs.kvs_debug_set(self.name, self.old)
 
 
 def score_path(path):
@@ -56,12 +54,12 @@ def score_path(path):
     128 query rows with the kernel that keeps 64 rows per wavefront in registers (passes of 128 or 256 rows) instead
     of the one that reads blocks of 64 rows from LDS."""
     if path == "narrow":
-        return env_override("KVS_SCORE_WIDE", "0")
+        return switch_override("score_wide", 1)
     if path == "fuse":
-        return env_override("KVS_FUSE_OBAR", "1")
+        return switch_override("fuse_obar", 2)
     if path == "nofuse":
-        return env_override("KVS_FUSE_OBAR", "0")
-    return env_override("KVS_SCORE_PATH", path)
+        return switch_override("fuse_obar", 1)
+    return switch_override("score_path", 1 if path == "valu" else 0)
 
 
 # ------------------------------------------------------------------------------------------------
@@ -885,7 +883,7 @@ def test_decode_attention_matches_oracle(base, dtype, D, G, W, lens, path):
     R = G * W
     out = torch.full((len(units) + 1, R, D), -7.0, dtype=torch.float32, device="cuda")
     ws = torch.empty(batch.kvs.kvs_decode_workspace_size(p), dtype=torch.uint8, device="cuda")
-    with env_override("KVS_DECODE_PATH", path):
+    with switch_override("decode_path", {None: 0, "valu": 1, "mfma": 2}[path]):
         batch.kvs.kvs_decode_attention(p, batch.Q, batch.K, batch.V, batch.counts_in, out, ws, stream=batch.stream())
         torch_sync()
     assert (out[len(units):] == -7.0).all()
