@@ -45,6 +45,7 @@ extern "C" {
 #define KVS_MAX_Q_ROWS 1024      /* largest supported G*W */
 #define KVS_MAX_DECODE_ROWS 64   /* largest G*W of kvs_decode_attention */
 #define KVS_MAX_LEN (1 << 22)    /* largest supported cache length of one unit, in tokens */
+#define KVS_STATIC_SCRATCH_BYTES (16u << 20)   /* workspace that kvs_step_static brings along, per GPU */
 
 typedef enum {
   KVS_OK = 0,
@@ -162,6 +163,23 @@ kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, c
                            void* K_out, void* V_out, int32_t* counts_out,
                            int32_t* slot_of_token_out, uint8_t* edge_mask_out,
                            void* ws, size_t ws_bytes, void* hip_stream);
+
+/* For callers that cannot allocate device memory or keep a workspace around: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  kvs_step_counts (counts_in = NULL: kvs_step) without the
+ * workspace arguments: the intermediates live in a device array of KVS_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object (every GPU the library runs on holds one copy until the process ends).  The call
+ * allocates and frees nothing, on the device or through any allocating runtime routine, and never synchronises.
+ *   - A problem whose kvs_workspace_size() exceeds KVS_STATIC_SCRATCH_BYTES is refused with KVS_ERR_WORKSPACE
+ *     before anything is launched (one layer of 8 KV heads x 32768 tokens, 128 query rows, needs about 3.1 MB).
+ *   - The device of hip_stream must be the calling thread's current device.  The first call on a device looks
+ *     up that device's copy of the array (hipGetSymbolAddress): make it outside a graph capture.
+ *   - All calls on one GPU share the one array: two calls that may overlap in time (different streams, or one
+ *     stream per thread) race.  Calls on one stream are ordered and may follow each other freely; nothing in
+ *     the array has to survive from one call to the next or to start at zero.
+ * Arguments, outputs, layouts and every other error are those of kvs_step_counts.                          */
+kvs_status kvs_step_static(const kvs_problem* p, const void* Q, const void* K, const void* V, const int32_t* counts_in,
+                           void* K_out, void* V_out, int32_t* counts_out,
+                           int32_t* slot_of_token_out, uint8_t* edge_mask_out, void* hip_stream);
 
 /* Sec. 3.1 (sum-merged Values with cardinality normalisation): attention of the problem's G*W query rows
  * over a merged cache, the consumer of kvs_merge_compact's outputs.  Row t of unit u (rows in_row[u] ..

@@ -32,9 +32,11 @@ from .binding import (  # noqa: F401
     kvs_step,
     kvs_step_counts,
     kvs_step_per_query,
+    kvs_step_static,
     kvs_debug_set,
     kvs_debug_get,
     DEBUG_SWITCHES,
+    STATIC_SCRATCH_BYTES,
     kvs_version,
     kvs_workspace_size,
     load_library,

@@ -23,8 +23,9 @@ DTYPES = {"f32": KVS_F32, "bf16": KVS_BF16}
 EXPORTS = ["kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step",
            "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_decode_workspace_size",
            "kvs_decode_attention", "kvs_per_query_workspace_size", "kvs_sensitivity", "kvs_merge_compact_norms",
-           "kvs_step_per_query", "kvs_status_str", "kvs_version", "kvs_debug_set", "kvs_debug_get"]
+           "kvs_step_per_query", "kvs_step_static", "kvs_status_str", "kvs_version", "kvs_debug_set", "kvs_debug_get"]
 
+STATIC_SCRATCH_BYTES = 16 << 20
 # testing switches of include/kvs_debug.h
 DEBUG_SWITCHES = {"score_path": 0, "score_wide": 1, "fuse_obar": 2, "decode_path": 3, "score_chunk": 4, "verbose": 5,
                   "score_fused": 6, "select_split": 7}
@@ -84,12 +85,13 @@ def load_library(path: Optional[str] = None):
     lib.kvs_sensitivity.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_merge_compact_norms.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_step_per_query.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_step_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.kvs_debug_set.argtypes = [C.c_int, C.c_int]
     lib.kvs_debug_get.argtypes = [C.c_int]
     for name in ("kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step",
                  "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_decode_workspace_size",
                  "kvs_decode_attention", "kvs_per_query_workspace_size", "kvs_sensitivity",
-                 "kvs_merge_compact_norms", "kvs_step_per_query", "kvs_debug_set", "kvs_debug_get"):
+                 "kvs_merge_compact_norms", "kvs_step_per_query", "kvs_step_static", "kvs_debug_set", "kvs_debug_get"):
         getattr(lib, name).restype = C.c_int
     lib.kvs_status_str.argtypes = [C.c_int]
     lib.kvs_status_str.restype = C.c_char_p
@@ -260,6 +262,13 @@ def kvs_step_per_query(problem: Problem, Q, K, V, K_out, V_out, counts_out, ws, 
         problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(K_out), _ptr(V_out), _ptr(counts_out),
         _ptr(slot_of_token_out), _ptr(edge_mask_out), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
         stream), "kvs_step_per_query")
+
+
+def kvs_step_static(problem: Problem, Q, K, V, counts_in, K_out, V_out, counts_out, slot_of_token_out=None,
+                    edge_mask_out=None, stream: int = 0):
+    _check(load_library().kvs_step_static(
+        problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(counts_in), _ptr(K_out), _ptr(V_out), _ptr(counts_out),
+        _ptr(slot_of_token_out), _ptr(edge_mask_out), stream), "kvs_step_static")
 
 
 def kvs_debug_set(which, value: int) -> int:

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "kvs_device.h"
@@ -479,6 +480,55 @@ kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, c
   if (st != KVS_OK) return st;
   return step_with_workspace(plan, Q, K, V, counts_in, K_out, V_out, counts_out, slot_of_token_out, edge_mask_out, ws,
                              ws_bytes, hip_stream);
+}
+
+// ---- kvs_step_static: the step for callers that cannot allocate.  Its workspace is this array: one copy per GPU
+// that runs the library, held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the device address it yields (per device) is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[KVS_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];      // device address of `scratch` on every device that has asked for it
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+kvs_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return KVS_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr) {
+      if (debug_switch(KVS_DEBUG_VERBOSE)) {
+        std::fprintf(stderr, "libkvs: hipGetSymbolAddress(scratch) failed on device %d: %s\n", dev, hipGetErrorString(e));
+      }
+      return KVS_ERR_DEVICE;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return KVS_OK;
+}
+}  // namespace
+
+kvs_status kvs_step_static(const kvs_problem* p, const void* Q, const void* K, const void* V, const int32_t* counts_in,
+                           void* K_out, void* V_out, int32_t* counts_out, int32_t* slot_of_token_out,
+                           uint8_t* edge_mask_out, void* hip_stream) {
+  Plan plan;
+  kvs_status st = make_plan(p, &plan);
+  if (st != KVS_OK) return st;
+  // the size check needs no device: a problem beyond the array is refused before anything touches the GPU
+  if (carve(plan, nullptr).bytes > (size_t)KVS_STATIC_SCRATCH_BYTES) return KVS_ERR_WORKSPACE;
+  if ((st = check_step_ranges(plan, Q, K, V, counts_in, K_out, V_out, counts_out, slot_of_token_out, edge_mask_out,
+                              nullptr, 0)) != KVS_OK) {
+    return st;
+  }
+  void* ws = nullptr;
+  if ((st = static_scratch(&ws)) != KVS_OK) return st;
+  return step_with_workspace(plan, Q, K, V, counts_in, K_out, V_out, counts_out, slot_of_token_out, edge_mask_out, ws,
+                             (size_t)KVS_STATIC_SCRATCH_BYTES, hip_stream);
 }
 
 kvs_status kvs_per_query_workspace_size(const kvs_problem* p, size_t* bytes) {

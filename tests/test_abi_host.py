@@ -139,6 +139,24 @@ def test_pointer_workspace_and_alias_errors_are_host_side():
                      b["K_out"], b["V_out"], b["counts"]) == kvs.KVS_ERR_INVALID_ARG
 
 
+def test_static_entry_refuses_large_problems_and_bad_pointers_before_any_device_call():
+    """kvs_step_static brings its own workspace of KVS_STATIC_SCRATCH_BYTES: a problem that needs more is refused,
+    and so is every pointer error, on the host (no GPU is touched before those checks)."""
+    p = problem()
+    b = fake_buffers(p)
+    assert kvs.kvs_workspace_size(p) <= kvs.STATIC_SCRATCH_BYTES
+    st = lambda pr=p, **o: status_of(  # noqa: E731
+        kvs.kvs_step_static, pr, b["Q"], o.get("K", b["K"]), b["V"], None, o.get("K_out", b["K_out"]), b["V_out"],
+        b["counts"])
+    assert st(K=None) == kvs.KVS_ERR_INVALID_ARG
+    assert st(K_out=b["V"]) == kvs.KVS_ERR_ALIAS
+    big = problem(lens=[2_000_000, 500], budgets=[1_000_000, 600])
+    assert kvs.kvs_workspace_size(big) > kvs.STATIC_SCRATCH_BYTES
+    assert st(big) == kvs.KVS_ERR_WORKSPACE
+    header = open(os.path.join(ROOT, "include", "kvs.h")).read()
+    assert re.search(r"#define KVS_STATIC_SCRATCH_BYTES \(16u << 20\)", header) and kvs.STATIC_SCRATCH_BYTES == 16 << 20
+
+
 def test_debug_switches_are_process_state_without_environment_lookups():
     for name, idx in kvs.DEBUG_SWITCHES.items():
         old = kvs.kvs_debug_get(name)
