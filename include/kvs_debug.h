@@ -24,11 +24,17 @@ typedef enum {
   KVS_DEBUG_DECODE_PATH = 3,  /* KVS_DECODE_PATH=valu|mfma   1: vector-ALU decode kernel, 2: MFMA decode kernel         */
   KVS_DEBUG_SCORE_CHUNK = 4,  /* KVS_SCORE_CHUNK=<n>   tokens per score workgroup (clamped to the supported range)      */
   KVS_DEBUG_VERBOSE = 5,      /* KVS_VERBOSE=1         1: the HIP error string of a failed launch goes to stderr        */
-  KVS_DEBUG_SCORE_FUSED = 6,  /* KVS_SCORE_FUSED=0|1   1: never the one-pass score kernel (K kept in LDS between the
-                                                          statistics and the alpha_bar phase), 2: wherever it applies   */
+  KVS_DEBUG_SCORE_FUSED = 6,  /* KVS_SCORE_FUSED=1     2: the one-pass score kernel (K kept in LDS between the statistics
+                                                          and the alpha_bar phase) wherever it applies; it is off
+                                                          otherwise (measured slower than the two sweeps)              */
   KVS_DEBUG_SELECT_SPLIT = 7, /* KVS_SELECT_SPLIT=0|1  1: always one workgroup per unit in the selection,
                                                        2: several workgroups per unit wherever that path applies        */
-  KVS_DEBUG_N_SWITCHES = 8
+  KVS_DEBUG_FUSED_WAIT_US = 8,/* KVS_FUSED_WAIT_US=<n> n + 1: a workgroup of the one-pass score kernel waits at most n
+                                                       microseconds for its unit's normalisers before it hands its
+                                                       item to the second kernel (1: it never waits)                   */
+  KVS_DEBUG_FUSED_STAGGER = 9,/* KVS_FUSED_STAGGER=<n> n + 1: the four cohorts of workgroups of the one-pass score kernel start
+                                                       n tenths of a microsecond apart                                 */
+  KVS_DEBUG_N_SWITCHES = 10
 } kvs_debug_switch;
 
 /* Sets a switch and returns its previous value; -1 (nothing changed) for an unknown switch or a negative value. */

@@ -22,7 +22,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvs.so")
 OBJ = os.path.join(HERE, "_build")
 
-SOURCES = ["kvs_api.hip", "kvs_score_valu.hip", "kvs_score_mfma.hip", "kvs_select.hip", "kvs_merge.hip", "kvs_decode.hip",
+SOURCES = ["kvs_api.hip", "kvs_score_valu.hip", "kvs_score_mfma.hip", "kvs_score_fused.hip", "kvs_select.hip", "kvs_merge.hip", "kvs_decode.hip",
            "kvs_perquery.hip"]
 
 FLAGS = [

@@ -42,8 +42,12 @@ struct SwitchInit {
     const char* c = std::getenv("KVS_SCORE_CHUNK");
     g_switch[KVS_DEBUG_SCORE_CHUNK] = c ? std::max(0, std::atoi(c)) : 0;
     g_switch[KVS_DEBUG_VERBOSE] = std::getenv("KVS_VERBOSE") != nullptr;
-    g_switch[KVS_DEBUG_SCORE_FUSED] = env_choice("KVS_SCORE_FUSED", "0", "1");
+    g_switch[KVS_DEBUG_SCORE_FUSED] = env_choice("KVS_SCORE_FUSED", nullptr, "1");
     g_switch[KVS_DEBUG_SELECT_SPLIT] = env_choice("KVS_SELECT_SPLIT", "0", "1");
+    const char* t = std::getenv("KVS_FUSED_WAIT_US");
+    g_switch[KVS_DEBUG_FUSED_WAIT_US] = t ? std::max(0, std::atoi(t)) + 1 : 0;
+    const char* g = std::getenv("KVS_FUSED_STAGGER");
+    g_switch[KVS_DEBUG_FUSED_STAGGER] = g ? std::max(0, std::atoi(g)) + 1 : 0;
   }
 } g_switch_init;
 }  // namespace
@@ -61,6 +65,7 @@ struct Plan {
   kvs_dtype dtype = KVS_F32;
   size_t elt = 4;
   long long rows_in = 0, rows_out = 0;
+  long long fused_items = 0;     // work items of the largest launch group when the one-pass score kernel applies
   std::vector<Unit> units;       // chunk_base / m_base filled per launch group
 };
 
@@ -108,6 +113,8 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
     un.chunk_base = un.m_base = 0;
     un.index = u;
     un.o_base = 0;
+    un.f_base = 0;
+    un.pad_ = 0;
     plan->rows_in = std::max(plan->rows_in, un.in_row + len);
     plan->rows_out = std::max(plan->rows_out, un.out_row + (long long)un.n_out);
   }
@@ -125,6 +132,16 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
       const long long per = std::max<long long>(want, (un.len + kMaxChunks - 1) / kMaxChunks);
       un.chunk_len = (int)((per + kWave - 1) / kWave * kWave);
       un.n_chunks = (un.len + un.chunk_len - 1) / un.chunk_len;
+    }
+  }
+  // the one-pass score kernel (bf16, 65..128 query rows, every unit at least a tile long) keeps per-item tables
+  if (plan->dtype == KVS_BF16 && plan->shape.R > 64 && plan->shape.R <= 128) {
+    for (int first = 0; first < p->n_units; first += kMaxUnitsPerLaunch) {
+      long long items = 0;
+      for (int u = first; u < std::min(p->n_units, first + kMaxUnitsPerLaunch); ++u) {
+        items += fused_chunks(plan->units[u].len, plan->shape.D);
+      }
+      plan->fused_items = std::max(plan->fused_items, items);
     }
   }
   // the units' row ranges must not overlap, on the input and on the output side
@@ -158,6 +175,12 @@ Workspace carve(const Plan& plan, void* base) {
   w.o_bar = (float*)take(nu * plan.shape.D * sizeof(float));
   w.edge_mask = (uint8_t*)take((size_t)plan.rows_in);
   w.slot = (int32_t*)take((size_t)plan.rows_in * sizeof(int32_t));
+  // one-pass score kernel: statistics and partial o_bar of every work item, counters and flags
+  if (plan.fused_items > 0) {
+    w.fstats = (float*)take((size_t)plan.fused_items * plan.shape.R * sizeof(float));
+    w.fo_part = (float*)take((size_t)plan.fused_items * plan.shape.D * sizeof(float));
+    w.fsync = (unsigned int*)take(((size_t)kFusedSyncInts + plan.fused_items) * sizeof(unsigned int));
+  }
   w.bytes = off;
   return w;
 }
@@ -249,12 +272,14 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
     UnitTable tab;
     std::memset(&tab, 0, sizeof(tab));
     tab.n_units = std::min(kMaxUnitsPerLaunch, plan.n_units - first);
-    int chunks = 0, mblocks = 0, ochunks = 0;
+    int chunks = 0, mblocks = 0, ochunks = 0, fitems = 0;
     for (int i = 0; i < tab.n_units; ++i) {
       tab.u[i] = plan.units[first + i];
       tab.u[i].chunk_base = chunks;
       tab.u[i].m_base = mblocks;
       tab.u[i].o_base = ochunks;
+      tab.u[i].f_base = fitems;
+      fitems += fused_chunks(tab.u[i].len, plan.shape.D);
       ochunks += obar_chunks(tab.u[i].len);
       chunks += tab.u[i].n_chunks;
       mblocks += (tab.u[i].len + kMergeTokens - 1) / kMergeTokens;
@@ -262,6 +287,7 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
     tab.total_chunks = chunks;
     tab.total_mblocks = mblocks;
     tab.total_ochunks = ochunks;
+    tab.total_fitems = fitems;
     long long rows = 0;
     for (int i = 0; i < tab.n_units; ++i) rows += tab.u[i].len;
     Shape sh = plan.shape;
@@ -282,15 +308,26 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
 
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
                         const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream,
-                        const void* V, bool* o_done) {
+                        const void* V, int* o_layout) {
   // KVS_DEBUG_SCORE_PATH forces the vector-ALU kernels (used by the tests to cover both paths).
+  const bool force_valu = debug_switch(KVS_DEBUG_SCORE_PATH) == 1;
+  if (o_layout) *o_layout = 0;
+  const bool wants_o = V != nullptr && o_layout != nullptr;
+  // Windows of 65..128 bf16 rows can take the one-pass kernel, which reads K once, keeps it in LDS between the
+  // statistics and the alpha_bar phase and carries the pass over V along (it needs V: callers that only want
+  // alpha_bar take the two sweeps).  It is correct and saves a third of the score phase's traffic, but on this
+  // chip it is slower than the two sweeps (see the measurements at the kernel), so it runs on request only:
+  // KVS_DEBUG_SCORE_FUSED = 2.
+  if (!force_valu && wants_o && ws.fsync != nullptr && debug_switch(KVS_DEBUG_SCORE_FUSED) == 2 &&
+      score_fused_supported(tab, sh, dt)) {
+    *o_layout = 2;
+    return launch_score_fused(tab, sh, Q, K, V, counts_in, alpha_bar, ws, stream);
+  }
   // The pass over V rides along in sweep 1 when the launch is a large one (the streaming policy's threshold):
   // the edge selection then runs as a short launch of its own, one CU per unit, which costs less than the
   // separate pass over V saves (measured at 64 units of the headline shape: 199 against 226 us for sweep 1,
   // the pass over V and the selection).  A small launch keeps the selection hidden beside the pass over V
   // (8 units: 38 against 45 us).  KVS_DEBUG_FUSE_OBAR forces one or the other.
-  const bool force_valu = debug_switch(KVS_DEBUG_SCORE_PATH) == 1;
-  if (o_done) *o_done = false;
   if (!force_valu && score_mfma_supported(tab, sh, dt)) {
     const int fuse = debug_switch(KVS_DEBUG_FUSE_OBAR);
     // (The selection of a unit too long for the select kernel's LDS cache of keys takes several times longer,
@@ -300,8 +337,8 @@ hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, con
     bool want = sh.stream != 0 && longest <= 32768;
     if (fuse == 1) want = false;
     if (fuse == 2) want = true;
-    const bool with_v = V != nullptr && o_done != nullptr && score_mfma_takes_values(sh, dt) && want;
-    if (with_v) *o_done = true;
+    const bool with_v = wants_o && score_mfma_takes_values(sh, dt) && want;
+    if (with_v) *o_layout = 1;
     return launch_score_mfma(tab, sh, dt, Q, K, counts_in, alpha_bar, ws, with_v ? V : nullptr, stream);
   }
   return launch_score_valu(tab, sh, dt, Q, K, counts_in, alpha_bar, ws, stream);
@@ -347,16 +384,16 @@ kvs_status kvs_score_counts(const kvs_problem* p, const void* Q, const void* K, 
   if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
-    bool o_done = false;
-    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, alpha_bar, w, s, V, &o_done);
+    int o_layout = 0;
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, alpha_bar, w, s, V, &o_layout);
     if (e != hipSuccess) return e;
     Shape sh2 = sh;
-    sh2.o_from_score = o_done;
-    if (!o_done) {
+    sh2.o_from_score = o_layout;
+    if (o_layout == 0) {
       e = launch_select_obar(tab, sh, plan.dtype, false, alpha_bar, nullptr, nullptr, V, counts_in, w.o_part, s);
       if (e != hipSuccess) return e;
     }
-    return launch_obar_reduce(tab, sh2, w.o_part, o_bar, s);
+    return launch_obar_reduce(tab, sh2, o_layout == 2 ? w.fo_part : w.o_part, o_bar, s);
   });
 }
 
@@ -459,12 +496,21 @@ static kvs_status step_with_workspace(const Plan& plan, const void* Q, const voi
   int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
-    bool o_done = false;
-    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, w.alpha_bar, w, s, V, &o_done);
+    int o_layout = 0;
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, w.alpha_bar, w, s, V, &o_layout);
     if (e != hipSuccess) return e;
     Shape sh2 = sh;
-    sh2.o_from_score = o_done;
-    e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, o_done ? nullptr : V, counts_in,
+    sh2.o_from_score = o_layout;
+    if (o_layout == 2) {
+      // the one-pass kernel leaves one partial o_bar per work item (a few hundred per unit): they are added up by
+      // one more workgroup per unit beside the selection, and the merge pass takes the finished o_bar
+      e = launch_select_obar(tab, sh2, plan.dtype, true, w.alpha_bar, mask, slot, nullptr, counts_in, nullptr, s,
+                             w.fo_part, w.o_bar);
+      if (e != hipSuccess) return e;
+      return launch_merge(tab, sh2, plan.dtype, K, V, counts_in, w.alpha_bar, w.o_bar, nullptr, mask, slot, K_out,
+                          V_out, counts_out, s);
+    }
+    e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, o_layout ? nullptr : V, counts_in,
                            w.o_part, s);
     if (e != hipSuccess) return e;
     return launch_merge(tab, sh2, plan.dtype, K, V, counts_in, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,

@@ -26,6 +26,9 @@ constexpr int kWave = 64;
 // K plus V bytes of one launch above which rows are streamed past the caches (256 MB of memory-side
 // cache: below that, a sweep finds the rows its predecessor left there)
 constexpr long long kStreamBytes = 192ll << 20;
+// One-pass score kernel: bytes of K (bf16 rows) that one of its work items keeps in LDS between the statistics
+// phase and the alpha_bar phase (one workgroup per CU: 128 KB of K + 16 KB of Q + tables of 160 KB)
+constexpr int kFusedChunkBytes = 128 * 1024;
 
 // One (sequence, KV head).  Rows are in elements of D, not bytes.
 struct Unit {
@@ -39,7 +42,16 @@ struct Unit {
   int m_base;           // merge workgroups (kMergeTokens tokens each) of the launch's earlier units
   int index;            // position of the unit in the caller's problem (indexes Q, o_bar, partials)
   int o_base;           // o_bar-pass workgroups of the launch's earlier units
+  int f_base;           // work items of the one-pass score kernel that belong to the launch's earlier units
+  int pad_;
 };
+
+// Work items of the one-pass score kernel: chunks of kFusedChunkBytes of K rows (a function of D and the length).
+__host__ __device__ inline int fused_chunk_len(int D) { return kFusedChunkBytes / (D * 2); }
+__host__ __device__ inline int fused_chunks(int len, int D) {
+  const int cl = fused_chunk_len(D);
+  return (len + cl - 1) / cl;
+}
 
 // Chunking of the o_bar pass over V: a function of the unit's length only.
 __host__ __device__ inline int obar_chunk_len(int len) {
@@ -57,6 +69,8 @@ struct UnitTable {
   int total_chunks;
   int total_mblocks;
   int total_ochunks;
+  int total_fitems;     // work items of the one-pass score kernel
+  int pad_;
   Unit u[kMaxUnitsPerLaunch];
 };
 
@@ -69,12 +83,16 @@ struct Shape {
   int stream;       // 1: the launch's K and V exceed the last-level cache, rows are read non-temporally
   int rule;         // kvs_key_rule of the merged Key
   int causal;       // 0, or the window W when query row q only sees the rows up to its own position n - W + q % W
-  int o_from_score; // 1: o_part holds one partial per SCORE chunk (written by sweep 1), else one per chunk of the o_bar pass
+  int o_from_score; // where the partial sums of o_bar are: 0: o_part, one per chunk of the o_bar pass; 1: o_part, one
+                    // per SCORE chunk (written by sweep 1); 2: fo_part, one per work item of the one-pass score kernel
 };
 
-// How many partials of o_bar a unit has in o_part.
+// How many partials of o_bar a unit has, and where its partial c starts (index of its first float).
 __host__ __device__ inline int obar_partials(const Shape& sh, const Unit& un) {
-  return sh.o_from_score ? un.n_chunks : obar_chunks(un.len);
+  return sh.o_from_score == 2 ? fused_chunks(un.len, sh.D) : sh.o_from_score == 1 ? un.n_chunks : obar_chunks(un.len);
+}
+__host__ __device__ inline size_t obar_partial_at(const Shape& sh, const Unit& un, int c) {
+  return sh.o_from_score == 2 ? ((size_t)un.f_base + c) * sh.D : ((size_t)un.index * kMaxChunks + c) * sh.D;
 }
 
 // Workspace carve-up (all offsets multiples of 256 bytes).
@@ -86,8 +104,21 @@ struct Workspace {
   float* o_bar;         // [n_units][D] (kvs_step only)
   uint8_t* edge_mask;   // [rows]    (kvs_step only, when the caller keeps it internal)
   int32_t* slot;        // [rows]
+  // one-pass score kernel (bf16, 65..128 query rows); sized for the largest launch group, null otherwise
+  float* fstats;        // [work items][R]  log2 of the sum of 2^logit over the item's tokens, for every query row
+  float* fo_part;       // [work items][D]  partial o_bar of every item
+  unsigned int* fsync;  // kFusedSyncInts counters and flags, then one entry per work item (items given up on)
   size_t bytes;
 };
+
+// Layout of Workspace::fsync (unsigned ints).
+constexpr int kFusedTicket = 0;                       // next work item
+constexpr int kFusedDeferred = 32;                    // number of items handed to the second kernel
+constexpr int kFusedDone = 64;                        // [kMaxUnitsPerLaunch] items of the unit whose statistics are out
+constexpr int kFusedSyncInts = 64 + kMaxUnitsPerLaunch;       // the list of deferred items starts here
+// A normaliser c_row[unit][q] that the one-pass kernel has not produced yet holds this bit pattern (a NaN that no
+// arithmetic yields): the kernel's workgroups poll the words themselves, so no separate flag has to travel.
+constexpr unsigned int kFusedNotYet = 0xffffffffu;
 
 // Device helpers --------------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -173,19 +204,27 @@ hipError_t launch_score_finalize(const UnitTable& tab, const Shape& sh, const Wo
 // Both score sweeps: chunk statistics, the finalize kernel, then alpha_bar.
 // counts_in (here and below): cardinalities of the input rows when the cache is already a merged one, or null.
 // V non-null: the caller also needs o_bar; where the score kernel can carry the pass over V along, it does,
-// leaves one partial per score chunk in ws.o_part and sets *o_done (the caller then skips the separate pass and
-// sets Shape::o_from_score for the consumers).
+// leaves the partial sums in the workspace and sets *o_layout to where they are (a value for Shape::o_from_score
+// other than 0: the caller then skips the separate pass and tells the consumers).
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
                         const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream,
-                        const void* V = nullptr, bool* o_done = nullptr);
+                        const void* V = nullptr, int* o_layout = nullptr);
 // One launch, two kinds of workgroups: the first `with_select ? n_units : 0` select the edges of one unit
 // each, the others stream one chunk of V each into o_part (skipped when V is null).
+// A third kind (o_bar_out non-null, one workgroup per unit) adds up the partial sums that a score kernel left
+// (sh.o_from_score says where) into o_bar_out[unit][D].
 hipError_t launch_select_obar(const UnitTable& tab, const Shape& sh, kvs_dtype dt, bool with_select,
                               const float* alpha_bar, uint8_t* edge_mask, int32_t* slot, const void* V,
-                              const int32_t* counts_in, float* o_part, hipStream_t stream);
-// o_bar[u] = sum of the unit's o_part chunks, in chunk order (only when o_bar itself is an output).
-hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float* o_part, float* o_bar,
+                              const int32_t* counts_in, float* o_part, hipStream_t stream,
+                              const float* parts_in = nullptr, float* o_bar_out = nullptr);
+// o_bar[u] = sum of the unit's partial sums, in chunk order (only when o_bar itself is an output).
+hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float* parts, float* o_bar,
                               hipStream_t stream);
+// One-pass score for bf16 windows of 65..128 rows (kvs_score_fused.hip): K is read once and kept in LDS between
+// the statistics and the alpha_bar phase; the pass over V rides along (partials in ws.fo_part).
+bool score_fused_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt);
+hipError_t launch_score_fused(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
+                              const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream);
 // Exactly one of o_bar (final values) and o_part (chunk sums, added up by every workgroup) is non-null.
 hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* K, const void* V,
                         const int32_t* counts_in, const float* alpha_bar, const float* o_bar, const float* o_part,

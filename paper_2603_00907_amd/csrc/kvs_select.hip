@@ -708,18 +708,42 @@ __device__ __forceinline__ void obar_chunk(const Unit& un, int chunk, const T* _
   }
 }
 
+// o_bar[unit] = the unit's partial sums added in chunk order (thread d takes channel d; UN loads in flight).
+__device__ __forceinline__ void obar_reduce_unit(const Unit& un, const Shape& sh, const float* __restrict__ parts,
+                                                 float* __restrict__ o_bar) {
+  const int nc = obar_partials(sh, un);
+  const float* src = parts + obar_partial_at(sh, un, 0);
+  constexpr int UN = 8;
+  for (int d = threadIdx.x; d < sh.D; d += blockDim.x) {
+    float s = 0.f;
+    for (int c0 = 0; c0 < nc; c0 += UN) {
+      float v[UN];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) v[u] = (c0 + u < nc) ? src[(size_t)(c0 + u) * sh.D + d] : 0.f;
+#pragma unroll
+      for (int u = 0; u < UN; ++u) s += v[u];
+    }
+    o_bar[(size_t)un.index * sh.D + d] = s;
+  }
+}
+
+// Three kinds of workgroups: blocks [0, n_select) select one unit's edges each, blocks [n_select, n_select +
+// n_reduce) add one unit's partial o_bar sums up each, the others stream one chunk of V each.
 template <typename T, int D>
 __global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
-    const UnitTable tab, const Shape sh, const int n_select, const float* __restrict__ alpha_bar,
+    const UnitTable tab, const Shape sh, const int n_select, const int n_reduce, const float* __restrict__ alpha_bar,
     uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, const T* __restrict__ V,
-    const int32_t* __restrict__ counts_in, float* __restrict__ o_part) {
+    const int32_t* __restrict__ counts_in, float* __restrict__ o_part, const float* __restrict__ parts_in,
+    float* __restrict__ o_bar_out) {
   __shared__ SelectSmem sm;
   __shared__ float sm_o[kSelWaves][128];
   const int b = blockIdx.x;
   if (b < n_select) {
     select_unit(tab.u[b], sh, alpha_bar, edge_mask, slot, sm);
+  } else if (b < n_select + n_reduce) {
+    obar_reduce_unit(tab.u[b - n_select], sh, parts_in, o_bar_out);
   } else {
-    const int c = b - n_select;
+    const int c = b - n_select - n_reduce;
     int ui = 0;
     while (ui + 1 < tab.n_units && tab.u[ui + 1].o_base <= c) ++ui;
     if (sh.stream) obar_chunk<T, D, true>(tab.u[ui], c - tab.u[ui].o_base, V, counts_in, alpha_bar, o_part, sm_o);
@@ -727,26 +751,22 @@ __global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
   }
 }
 
-__global__ void obar_reduce_kernel(const UnitTable tab, const Shape sh, const float* __restrict__ o_part,
+__global__ void obar_reduce_kernel(const UnitTable tab, const Shape sh, const float* __restrict__ parts,
                                    float* __restrict__ o_bar) {
-  const Unit un = tab.u[blockIdx.x];
-  const int nc = obar_partials(sh, un);
-  for (int d = threadIdx.x; d < sh.D; d += blockDim.x) {
-    float s = 0.f;
-    for (int c = 0; c < nc; ++c) s += o_part[((size_t)un.index * kMaxChunks + c) * sh.D + d];
-    o_bar[(size_t)un.index * sh.D + d] = s;
-  }
+  obar_reduce_unit(tab.u[blockIdx.x], sh, parts, o_bar);
 }
 
 template <typename T, int D>
 hipError_t launch_t(const UnitTable& tab, const Shape& sh, bool with_select, const float* alpha_bar,
                     uint8_t* edge_mask, int32_t* slot, const void* V, const int32_t* counts_in, float* o_part,
-                    hipStream_t stream) {
+                    hipStream_t stream, const float* parts_in, float* o_bar_out) {
   const int n_select = with_select ? tab.n_units : 0;
+  const int n_reduce = o_bar_out ? tab.n_units : 0;
   const int n_obar = V ? tab.total_ochunks : 0;
-  if (n_select + n_obar == 0) return hipSuccess;
-  hipLaunchKernelGGL((select_obar_kernel<T, D>), dim3(n_select + n_obar), dim3(kSelThreads), 0, stream, tab, sh,
-                     n_select, alpha_bar, edge_mask, slot, (const T*)V, counts_in, o_part);
+  if (n_select + n_reduce + n_obar == 0) return hipSuccess;
+  hipLaunchKernelGGL((select_obar_kernel<T, D>), dim3(n_select + n_reduce + n_obar), dim3(kSelThreads), 0, stream, tab,
+                     sh, n_select, n_reduce, alpha_bar, edge_mask, slot, (const T*)V, counts_in, o_part, parts_in,
+                     o_bar_out);
   return hipGetLastError();
 }
 
@@ -754,18 +774,17 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, bool with_select, con
 
 hipError_t launch_select_obar(const UnitTable& tab, const Shape& sh, kvs_dtype dt, bool with_select,
                               const float* alpha_bar, uint8_t* edge_mask, int32_t* slot, const void* V,
-                              const int32_t* counts_in, float* o_part, hipStream_t stream) {
-  if (dt == KVS_F32) {
-    return sh.D == 64 ? launch_t<float, 64>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream)
-                      : launch_t<float, 128>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream);
-  }
-  return sh.D == 64 ? launch_t<uint16_t, 64>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream)
-                    : launch_t<uint16_t, 128>(tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream);
+                              const int32_t* counts_in, float* o_part, hipStream_t stream, const float* parts_in,
+                              float* o_bar_out) {
+#define KVS_SEL_ARGS tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream, parts_in, o_bar_out
+  if (dt == KVS_F32) return sh.D == 64 ? launch_t<float, 64>(KVS_SEL_ARGS) : launch_t<float, 128>(KVS_SEL_ARGS);
+  return sh.D == 64 ? launch_t<uint16_t, 64>(KVS_SEL_ARGS) : launch_t<uint16_t, 128>(KVS_SEL_ARGS);
+#undef KVS_SEL_ARGS
 }
 
-hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float* o_part, float* o_bar,
+hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float* parts, float* o_bar,
                               hipStream_t stream) {
-  hipLaunchKernelGGL(obar_reduce_kernel, dim3(tab.n_units), dim3(128), 0, stream, tab, sh, o_part, o_bar);
+  hipLaunchKernelGGL(obar_reduce_kernel, dim3(tab.n_units), dim3(128), 0, stream, tab, sh, parts, o_bar);
   return hipGetLastError();
 }
 

@@ -48,18 +48,39 @@ class switch_override:
         kvs.kvs_debug_set(self.name, self.old)
 
 
+class switches:
+    """Several testing switches at once."""
+
+    def __init__(self, **kw):
+        self.items = [switch_override(k, v) for k, v in kw.items()]
+
+    def __enter__(self):
+        for it in self.items:
+            it.__enter__()
+
+    def __exit__(self, *a):
+        for it in reversed(self.items):
+            it.__exit__(*a)
+
+
 def score_path(path):
-    """None: the library's own choice; "valu": the vector-ALU score kernels; "fuse": the pass over V carried
-    along in sweep 1 (the library does that by itself only for large launches); "nofuse": never; "narrow": more than
-    128 query rows with the kernel that keeps 64 rows per wavefront in registers (passes of 128 or 256 rows) instead
-    of the one that reads blocks of 64 rows from LDS."""
+    """None: the library's own choice; "valu": the vector-ALU score kernels; "fuse": the pass over V carried along in
+    sweep 1 (the library does that by itself only for large launches); "nofuse": never carried along; "onepass": the
+    one-pass kernel that keeps K in LDS between its phases (windows of 65..128 bf16 rows; the library never picks it
+    by itself); "defer": that kernel with a wait limit of zero, so that every work item whose unit is not complete
+    at once goes to its second kernel; "narrow": more than 128 query rows with the kernel that keeps 64 rows per
+    wavefront in registers (passes of 128 or 256 rows) instead of the one that reads blocks of 64 rows from LDS."""
     if path == "narrow":
-        return switch_override("score_wide", 1)
+        return switches(score_wide=1)
     if path == "fuse":
-        return switch_override("fuse_obar", 2)
+        return switches(fuse_obar=2)
     if path == "nofuse":
-        return switch_override("fuse_obar", 1)
-    return switch_override("score_path", 1 if path == "valu" else 0)
+        return switches(fuse_obar=1)
+    if path == "onepass":
+        return switches(score_fused=2)
+    if path == "defer":
+        return switches(score_fused=2, fused_wait_us=1)
+    return switches(score_path=1 if path == "valu" else 0)
 
 
 # ------------------------------------------------------------------------------------------------
@@ -80,6 +101,17 @@ SCORE_CASES = [
     ("stream2560", "f32", 128, 5, 32, [1300], None),                  # ... and two launches
     ("llama8b_8k", "bf16", 128, 4, 32, [2500], None),
     ("llama8b_8k", "bf16", 128, 4, 32, [2500], "valu"),
+    # the one-pass kernel (K kept in LDS between the phases): ragged tiles, a last item of a few rows, a one-tile
+    # unit, a unit longer than the grid can hold at once (its first items go to the second kernel), 100 query rows,
+    # head dim 64, cardinalities, and the same with every wait given up at once
+    ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2565, 40, 32, 9000], "onepass"),
+    ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2565, 40, 32, 9000], "defer"),
+    ("llama8b_8k", "bf16", 128, 4, 32, [300000], "onepass"),
+    ("llama8b_8k", "bf16", 64, 4, 32, [1900, 1027], "onepass"),
+    ("llama8b_8k", "bf16", 64, 3, 22, [5000, 100], "defer"),                  # 66 rows
+    ("llama8b_8k", "bf16", 128, 5, 20, [1500], "onepass"),
+    ("stream2560", "bf16", 128, 4, 32, [2560, 700], "onepass"),
+    ("stream2560", "bf16", 128, 4, 32, [2560, 700], "defer"),
     ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053, 40], "fuse"),     # ragged tiles, a last chunk of 5 rows
     ("llama8b_8k", "bf16", 64, 4, 32, [1900], "fuse"),
     ("llama8b_8k", "bf16", 128, 5, 20, [1500], "fuse"),               # 100 query rows
@@ -497,7 +529,7 @@ def test_step_replayed_from_a_hip_graph_equals_the_eager_step():
         batch.check_guards()
 
 
-@pytest.mark.parametrize("path", [None, "valu", "fuse"])
+@pytest.mark.parametrize("path", [None, "valu", "fuse", "onepass", "defer"])
 def test_step_llama8b_8k_config(path):
     w = WORKLOADS["llama8b_8k"]
     heads = range(w.n_kv_heads) if path != "valu" else range(2)
@@ -741,7 +773,7 @@ def test_step_more_units_than_one_launch_takes():
     check_step(w, accepted)
 
 
-@pytest.mark.parametrize("path", [None, "fuse"])
+@pytest.mark.parametrize("path", [None, "fuse", "onepass"])
 def test_step_streaming_regime_full_size(path):
     """Sec. 5's streaming regime at full size: 8 KV heads, each a merged cache of 2048 + 512 slots (the old
     slots stand for 4 tokens on average) merged back to 2048; cardinalities must add up bit-exactly."""
