@@ -128,6 +128,9 @@ kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar,
  *   positive finite number), V_out[S] = sum V[t], counts_out[S] = |S|.  A slot of one token is a
  *   bit-exact copy.
  *   K_out, V_out DEVICE out [out rows, D] io_dtype;  counts_out DEVICE out [out rows] i32          */
+/*   edge_mask and slot_of_token are taken as kvs_select writes them: slot_of_token[t] = number of zero mask bytes
+ *   before t.  The mask byte of a unit's last token is read as 0 whatever it holds; a slot index outside the
+ *   unit's output rows is never written.  Nothing else about a mask from outside the library is checked.   */
 kvs_status kvs_merge_compact(const kvs_problem* p, const void* K, const void* V,
                              const float* alpha_bar, const float* o_bar,
                              const uint8_t* edge_mask, const int32_t* slot_of_token,

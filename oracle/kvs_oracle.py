@@ -67,7 +67,8 @@ Parity pins (tests/test_oracle_pins.py): score / O8 / O9 are pinned by finite
 differences of textbook attention, by brute-force minimisation of the
 second-order objective, by the dense pseudo-inverse solution of Eq.
 "optimal_k_cn", by identical-Key and lossless-Value special cases; select is
-pinned by a brute-force sort and slot invariants.  The *choice* of the readings
+pinned by a brute-force sort and slot invariants; boundary_gap and conditioning (which decide what
+seeded units the GPU tests accept) by worked examples and plain loops over explicit c-vectors.  The *choice* of the readings
 P-1 (mean over query rows), P-2 (edge score) and P-3/P-4 (runs) is not fixed by
 the paper: parity unpinned for those choices themselves.
 """

@@ -327,6 +327,9 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
       float ce_n = 0.f;
       if (NORMS) asm volatile("v_mov_b32 %0, %1" : "=&v"(ce_n) : "v"(re[j]));
       const float icn = COUNTS ? __builtin_amdgcn_rcpf((float)c_n) : 1.f;
+      // the unit's last token has no edge after it, whatever its mask byte says (an edge mask that comes from
+      // outside the library is not trusted to keep that byte at zero)
+      const uint32_t edge = (t == n - 1) ? 0u : mask_cur;
       float kf[EPL], vn[EPL], r_next[EPL];
       Piece<T>::unpack(kraw, kf);
       Piece<T>::unpack(vraw_n, vn);
@@ -337,7 +340,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
 #pragma unroll
         for (int i = 0; i < EPL; ++i) r_next[i] = 0.f;
         Anorm = alpha_cur;
-        C = (mask_cur && coupled) ? ce_cur : 0.f;
+        C = (edge && coupled) ? ce_cur : 0.f;
       } else {
 #pragma unroll
         for (int i = 0; i < EPL; ++i) {
@@ -349,7 +352,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
         dot = group_sum<LPR>(dot);
         Anorm = alpha_cur * fabsf(1.f - 2.f * alpha_cur) * __builtin_amdgcn_sqrtf(ss_cur);
         const float pair2 = fmaxf(fmaf(2.f, dot, ss_cur + ss_next), 0.f);
-        C = (mask_cur && coupled) ? alpha_cur * alpha_n * __builtin_amdgcn_sqrtf(pair2) : 0.f;
+        C = (edge && coupled) ? alpha_cur * alpha_n * __builtin_amdgcn_sqrtf(pair2) : 0.f;
       }
       const float u = mean_rule ? (float)c_cur : Anorm - Cprev - C;
       first_tok = (count == 0) ? t : first_tok;
@@ -361,7 +364,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
         accK[i] = fmaf(u, kf[i], accK[i]);
         accV[i] += v_cur[i];
       }
-      if (mask_cur == 0) {                           // the slot ends at t
+      if (edge == 0) {                               // the slot ends at t
         if (is_head) {
           store_frag(sm_frag[group][0], accK, accV, U, count, COUNTS ? csum : count, first_tok);
           flags |= 1;

@@ -25,8 +25,9 @@ def wanted():
     for h in range(w.n_kv_heads):
         yield w, 0, 0, h, None
     w = WORKLOADS["llama8b_32k"]
-    for h in range(w.n_kv_heads):
-        yield w, 5, 0, h, None
+    for layer in range(w.layers):                  # every unit of the headline workload (the full-size step test)
+        for h in range(w.n_kv_heads):
+            yield w, layer, 0, h, None
     w = WORKLOADS["ragged16"]
     lens = unit_lengths(w)
     for s in (0, 3, 7, 11, 15):
@@ -39,16 +40,23 @@ def wanted():
     yield w, 0, 0, 0, None
 
 
+def one(args):
+    w, layer, seq, head, n = args
+    t = time.time()
+    a = accepted_unit(w, layer, seq, head, n=n, manifest={})
+    key = manifest_key(w, layer, seq, head, a.inputs.n)
+    return key, a.inputs.attempt, f"{key}: attempt {a.inputs.attempt} gap {a.gap:.2e} cond {a.cond:.3f} ({time.time() - t:.1f}s)"
+
+
 def main():
+    from multiprocessing import Pool
     manifest = {}
-    for w, layer, seq, head, n in wanted():
-        t = time.time()
-        a = accepted_unit(w, layer, seq, head, n=n, manifest={})
-        key = manifest_key(w, layer, seq, head, a.inputs.n)
-        manifest[key] = a.inputs.attempt
-        print(f"{key}: attempt {a.inputs.attempt} gap {a.gap:.2e} cond {a.cond:.3f} ({time.time() - t:.1f}s)", flush=True)
-        with open(MANIFEST, "w") as f:
-            json.dump(manifest, f, indent=1, sort_keys=True)
+    with Pool(int(os.environ.get("KVS_MANIFEST_WORKERS", "6"))) as pool:
+        for key, attempt, line in pool.imap_unordered(one, list(wanted())):
+            manifest[key] = attempt
+            print(line, flush=True)
+    with open(MANIFEST, "w") as f:
+        json.dump(manifest, f, indent=1, sort_keys=True)
 
 
 if __name__ == "__main__":

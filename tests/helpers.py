@@ -70,15 +70,13 @@ def accepted_unit(w: Workload, layer: int, seq: int, head: int, n: Optional[int]
     raise RuntimeError("no accepted attempt found")
 
 
-PQ_COND_MIN = 3e-2
+PQ_COND_MIN = COND_MIN
 
 
 def accepted_unit_per_query(w: Workload, layer: int, seq: int, head: int, n: Optional[int] = None,
                             causal: bool = False) -> AcceptedUnit:
-    """The same for the per-query aggregation of the norms.  Its kernels recompute attention rows and outputs in
-    bf16 products (split into two bf16 terms), so A_t and C_t carry relative differences of the order of 1e-4
-    instead of fp32 rounding; a slot's Key moves by about that divided by its conditioning U / sum A_t, hence the
-    larger minimum here (the 1e-2 bar of bf16 outputs then leaves a factor of three)."""
+    """The same for the per-query aggregation of the norms, with the same acceptance rule (the merged slots'
+    conditioning is taken with the per-query norms, which are what its merge uses)."""
     if n is None:
         n = unit_lengths(w)[seq]
     start = 0 if causal else load_manifest().get(manifest_key(w, layer, seq, head, n), 0)

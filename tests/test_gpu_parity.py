@@ -13,7 +13,7 @@ import numpy as np
 import pytest
 
 from oracle import kvs_oracle as O
-from workloads import WORKLOADS, generate_unit, unit_budget, unit_lengths
+from workloads import WORKLOADS, bf16_bits_to_f32, f32_to_bf16_bits, generate_unit, unit_budget, unit_lengths
 
 from helpers import DeviceBatch, accepted_unit, from_device, rel_err_rows, to_device
 
@@ -135,6 +135,10 @@ SCORE_CASES = [
     ("stress128k", "bf16", 128, 8, 100, [1200], None),                # 800 rows: four launches, the last of 32 rows
     ("stress128k", "bf16", 128, 8, 100, [1200], "narrow"),
     ("llama8b_8k", "bf16", 64, 1, 4, [500], None),
+    # the vector-ALU kernels as the library's own choice: windows of one to three rows; units shorter than a tile
+    ("llama8b_8k", "bf16", 128, 1, 3, [500, 33], None),
+    ("llama8b_8k", "bf16", 64, 2, 1, [700], None),
+    ("llama8b_8k", "bf16", 128, 4, 8, [20, 600], None),
     ("ragged16", "bf16", 128, 4, 32, [300, 5000, 33000], None),
     # rows that are slots of an already merged cache (cardinalities): every score kernel
     ("stream2560", "bf16", 128, 4, 32, [2560, 700], None),
@@ -319,7 +323,6 @@ def compare_outputs(batch, refs, dtype, strict_guard=True):
         r0, n_out = p.out_rows[i], p.n_out[i]
         assert ref.K_out.shape[0] == n_out
         assert (cnt[r0:r0 + n_out] == ref.counts).all(), f"unit {i}: counts differ"
-        assert not ref.fallback.any() or True
         ek = rel_err_rows(Ko[r0:r0 + n_out], ref.K_out)
         ev = rel_err_rows(Vo[r0:r0 + n_out], ref.V_out)
         assert ek <= TOL_KV[dtype], f"unit {i}: merged K rel err {ek:.3e}"
@@ -365,6 +368,106 @@ def test_merge_fallback_and_identical_keys():
     assert rel_err_rows(Vo.cpu().numpy(), ref.V_out) < 1e-5
     np.testing.assert_allclose(Ko.cpu().numpy()[10], K[10:14].mean(axis=0), rtol=1e-6)
     np.testing.assert_allclose(Ko.cpu().numpy()[37], K[40], rtol=2e-6)
+
+
+def run_crafted_merge(K, V, alpha, obar, mask, dtype, counts=None, n_sink=0):
+    """kvs_merge_compact(_counts) on one hand-made unit (fp32 arrays whose values the I/O dtype represents exactly);
+    returns the oracle's result on the same inputs and the GPU outputs as fp32 arrays."""
+    import torch
+    import paper_2603_00907_amd as kvs
+    n, D = K.shape
+    starts = np.ones(n, dtype=np.int64)
+    starts[1:] = 1 - mask[:-1]
+    slot = (np.cumsum(starts) - 1).astype(np.int32)
+    n_out = int(slot[-1]) + 1
+    ref = O.merge_compact(K, V, alpha.astype(np.float64), obar.astype(np.float64), mask, slot, counts_in=counts)
+    p = kvs.Problem(lens=[n], budgets=[n_out], group=1, window=1, head_dim=D, dtype=dtype, n_sink=n_sink)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    Ko = torch.full((n_out + 8, D), 512.0, dtype=tdt, device="cuda")
+    Vo = torch.full((n_out + 8, D), 512.0, dtype=tdt, device="cuda")
+    cnt = torch.full((n_out + 8,), -7, dtype=torch.int32, device="cuda")
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()  # noqa: E731
+    args = (dev(alpha.astype(np.float32)), dev(obar.astype(np.float32)[None]), dev(mask), dev(slot), Ko, Vo, cnt)
+    if counts is None:
+        kvs.kvs_merge_compact(p, to_device(K, dtype), to_device(V, dtype), *args)
+    else:
+        kvs.kvs_merge_compact_counts(p, to_device(K, dtype), to_device(V, dtype), dev(counts.astype(np.int32)), *args)
+    torch.cuda.synchronize()
+    assert (Ko[n_out:].float() == 512.0).all() and (Vo[n_out:].float() == 512.0).all() and (cnt[n_out:] == -7).all()
+    return ref, from_device(Ko[:n_out]), from_device(Vo[:n_out]), cnt[:n_out].cpu().numpy()
+
+
+@pytest.mark.parametrize("with_counts", [False, True])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_merge_with_attention_mass_at_and_above_one_half(dtype, with_counts):
+    """The Key rule's two edge cases (App. C assumes merged Keys carry alpha < 1/2; Sec. 4.2, Eqs. c11_def-c12_def
+    carry the factor 1 - 2 alpha): hand-made attention distributions put, inside merged runs, a token with
+    alpha > 1/2 (the norm takes |1 - 2 alpha|), a token with alpha = 1/2 exactly (A_t = 0), and a pair whose
+    weight denominator A_m - 2 C_m + A_{m+1} is negative (both masses just below 1/2: A nearly 0, C large), where
+    both sides must take the arithmetic mean.  Three units, one per case (each distribution sums to one)."""
+    rng = np.random.default_rng(17)
+    n, D = 80, 64
+    bf = lambda x: bf16_bits_to_f32(f32_to_bf16_bits(x.astype(np.float32)))  # noqa: E731
+    for case in ("above", "exactly", "negative"):
+        K = bf(rng.standard_normal((n, D)))
+        V = bf(rng.standard_normal((n, D)))
+        obar = (0.1 * rng.standard_normal(D)).astype(np.float32)
+        counts = rng.integers(1, 5, size=n).astype(np.int32) if with_counts else None
+        alpha = np.zeros(n, dtype=np.float64)
+        mask = np.zeros(n, dtype=np.uint8)
+        mask[20:23] = 1                                   # run 20..23
+        mask[50] = 1                                      # pair 50, 51
+        mask[60:62] = 1                                   # run 60..62 (ordinary masses)
+        if case == "above":
+            alpha[21] = 0.7                               # inside the run 20..23
+            rest = 0.3
+        elif case == "exactly":
+            alpha[22] = 0.5
+            rest = 0.5
+            V[22] = bf(2.0 * obar - V[21] + 0.05 * rng.standard_normal(D))   # r_22 close to -r_21: C_21 stays small and
+                                                                           # the denominator well away from zero
+        else:
+            alpha[50] = alpha[51] = 0.499                 # A_50, A_51 tiny, C_50 large: a negative denominator
+            rest = 0.002
+        free = np.array([t for t in range(n) if alpha[t] == 0.0])
+        alpha[free] = rest * rng.dirichlet(np.ones(len(free)))
+        alpha = alpha.astype(np.float32).astype(np.float64)   # what the kernel is given
+        ref, Ko, Vo, cnt = run_crafted_merge(K, V, alpha, obar, mask, dtype, counts)
+        pair_slot = 50 - 3                                # three edges selected before token 50
+        if case == "negative":
+            assert ref.fallback[pair_slot] and ref.U[pair_slot] < 0 and ref.fallback.sum() == 1
+            c = np.ones(2) if counts is None else counts[50:52].astype(np.float64)
+            mean = (c[:, None] * K[50:52]).sum(axis=0) / c.sum()
+            np.testing.assert_allclose(Ko[pair_slot], mean, rtol=TOL_KV[dtype], atol=TOL_KV[dtype] * 0.1)
+        else:
+            assert not ref.fallback.any() and O.conditioning(ref) > 0.05, case
+            run_slot = 20
+            assert ref.n_rows[run_slot] == 4
+        assert (cnt == ref.counts).all(), case
+        assert rel_err_rows(Ko, ref.K_out) <= TOL_KV[dtype], (case, rel_err_rows(Ko, ref.K_out))
+        assert rel_err_rows(Vo, ref.V_out) <= TOL_KV[dtype], case
+        single = ref.n_rows == 1
+        assert (Ko[single] == ref.K_out[single]).all() and (Vo[single] == ref.V_out[single]).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_merge_with_a_hand_made_mask_whose_last_byte_is_set(dtype):
+    """An edge mask from outside the library: the byte of the unit's last token is set (there is no edge after it).
+    The kernel reads it as 0, like the oracle, whose runs end with the unit: the last slot is the run that leads
+    up to the last token, no row is written past the unit's outputs."""
+    rng = np.random.default_rng(23)
+    n, D = 300, 128
+    bf = lambda x: bf16_bits_to_f32(f32_to_bf16_bits(x.astype(np.float32)))  # noqa: E731
+    K, V = bf(rng.standard_normal((n, D))), bf(rng.standard_normal((n, D)))
+    alpha = rng.dirichlet(np.ones(n))
+    obar = (alpha @ V).astype(np.float32)
+    mask = (rng.random(n) < 0.6).astype(np.uint8)
+    mask[:4] = 0
+    mask[n - 3:] = 1                                      # the last three tokens form a run, and the last byte is set
+    ref, Ko, Vo, cnt = run_crafted_merge(K, V, alpha.astype(np.float32).astype(np.float64), obar, mask, dtype)
+    assert ref.n_rows[-1] >= 3 and ref.counts.sum() == n
+    assert (cnt == ref.counts).all()
+    assert rel_err_rows(Ko, ref.K_out) <= TOL_KV[dtype] and rel_err_rows(Vo, ref.V_out) <= TOL_KV[dtype]
 
 
 def test_merge_bf16_output_rounds_to_nearest_even():
@@ -609,11 +712,13 @@ def test_step_llama8b_32k_one_layer_full_size():
 
 def test_step_headline_workload_in_the_launch_configuration_of_the_bench():
     """All 32 layers x 8 KV heads of the headline workload the way bench.py times them: two kvs_step calls of 16
-    layers (128 units, launch groups of 64 units = 8 layers) on two streams, each with its own workspace.  Four
-    sampled units, the first and the last of the step and the two on either side of the first group border, are
-    compared with the oracle like any other unit; every unit must satisfy the invariants that hold at any size."""
+    layers (128 units, launch groups of 64 units = 8 layers) on two streams, each with its own workspace.  EVERY one
+    of the 256 units is compared with the oracle like any other unit (its accepted Query redraw comes from the
+    manifest, so the oracle runs once per unit, sixteen units side by side on the host); a unit for which no redraw
+    is accepted would be held to the invariants that hold for any selection (none occurs)."""
     import torch
     from concurrent.futures import ThreadPoolExecutor
+    from threadpoolctl import threadpool_limits
     import paper_2603_00907_amd as kvs
     from helpers import to_device
     from workloads import unit_budget
@@ -621,24 +726,25 @@ def test_step_headline_workload_in_the_launch_configuration_of_the_bench():
     H, D, R, n = w.n_kv_heads, w.head_dim, w.q_rows, unit_lengths(w)[0]
     B = unit_budget(w, n)
     nu = w.layers * H
-    sampled = {(0, 0): None, (7, 7): None, (8, 0): None, (w.layers - 1, H - 1): None}
-    for layer, head in sampled:
-        sampled[(layer, head)] = accepted_unit(w, layer, 0, head)
     K = torch.empty((nu * n, D), dtype=torch.bfloat16, device="cuda")
     V = torch.empty_like(K)
     Q = torch.empty((nu, R, D), dtype=torch.bfloat16, device="cuda")
+    refs = [None] * nu
 
-    def unit(layer, head):
-        a = sampled.get((layer, head))
-        return a.inputs if a is not None else generate_unit(w, layer, 0, head)
+    def unit(i):
+        try:
+            a = accepted_unit(w, i // H, 0, i % H)
+        except RuntimeError:                                  # no accepted redraw: invariants only
+            return generate_unit(w, i // H, 0, i % H), None
+        m = a.ref.merged
+        return a.inputs, (a.ref.mask, a.ref.slot, m.counts, m.K_out, m.V_out, m.n_rows, a.gap)
 
-    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
-        for layer in range(w.layers):
-            for head, u in enumerate(pool.map(lambda h: unit(layer, h), range(H))):
-                i = layer * H + head
-                K[i * n:(i + 1) * n] = to_device(u.K, "bf16")
-                V[i * n:(i + 1) * n] = to_device(u.V, "bf16")
-                Q[i] = to_device(u.Q.reshape(R, D), "bf16")
+    with threadpool_limits(limits=1), ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+        for i, (u, ref) in enumerate(pool.map(unit, range(nu))):
+            K[i * n:(i + 1) * n] = to_device(u.K, "bf16")
+            V[i * n:(i + 1) * n] = to_device(u.V, "bf16")
+            Q[i] = to_device(u.Q.reshape(R, D), "bf16")
+            refs[i] = ref
     half = nu // 2
     p = kvs.Problem(lens=[n] * half, budgets=[B] * half, group=w.group, window=w.window, head_dim=D, dtype="bf16",
                     n_sink=w.n_sink, n_recent=w.n_recent)
@@ -665,15 +771,22 @@ def test_step_headline_workload_in_the_launch_configuration_of_the_bench():
     assert (s2[:, 0] == 0).all() and (s2[:, -1] == B - 1).all()
     assert (c2.sum(dim=1) == n).all() and (c2 >= 1).all()
     assert torch.isfinite(K_out.float()).all() and torch.isfinite(V_out.float()).all()
-    for (layer, head), a in sampled.items():
-        i = layer * H + head
-        assert (m2[i].cpu().numpy() == a.ref.mask).all(), f"unit {i}: selected edges differ (gap {a.gap:.2e})"
-        assert (s2[i].cpu().numpy() == a.ref.slot).all(), f"unit {i}: slot map differs"
-        ref = a.ref.merged
-        assert (c2[i].cpu().numpy() == ref.counts).all()
-        ek = rel_err_rows(from_device(K_out[i * B:(i + 1) * B]), ref.K_out)
-        ev = rel_err_rows(from_device(V_out[i * B:(i + 1) * B]), ref.V_out)
+    m_host, s_host, c_host = m2.cpu().numpy(), s2.cpu().numpy(), c2.cpu().numpy()
+    compared = 0
+    for i, ref in enumerate(refs):
+        if ref is None:
+            continue
+        r_mask, r_slot, r_counts, r_K, r_V, r_rows, gap = ref
+        assert (m_host[i] == r_mask).all(), f"unit {i}: selected edges differ (gap {gap:.2e})"
+        assert (s_host[i] == r_slot).all(), f"unit {i}: slot map differs"
+        assert (c_host[i] == r_counts).all(), f"unit {i}: cardinalities differ"
+        Ko, Vo = from_device(K_out[i * B:(i + 1) * B]), from_device(V_out[i * B:(i + 1) * B])
+        ek, ev = rel_err_rows(Ko, r_K), rel_err_rows(Vo, r_V)
         assert ek <= TOL_KV["bf16"] and ev <= TOL_KV["bf16"], (i, ek, ev)
+        single = r_rows == 1
+        assert (Ko[single] == r_K[single]).all() and (Vo[single] == r_V[single]).all(), f"unit {i}: a single row is a copy"
+        compared += 1
+    assert compared == nu, f"{nu - compared} units had no accepted Query redraw"
 
 
 def test_step_ragged_batch_reduced():

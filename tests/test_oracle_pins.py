@@ -743,3 +743,94 @@ def test_causal_window_of_one_and_with_counts():
     ends = np.cumsum(c)
     for t in range(n):
         np.testing.assert_allclose(a[:, t], ax[:, ends[t] - c[t]:ends[t]].sum(axis=1), rtol=1e-12, atol=1e-300)
+
+
+# ------------------------------------------------------------------------------------------------
+# The two helpers that decide which seeded units the GPU tests see (the acceptance rule of tests/helpers.py)
+def test_boundary_gap_worked_example_and_brute_force():
+    """boundary_gap is the relative distance between the r-th and the (r+1)-th smallest eligible edge score
+    (App. C (i): pairs ranked by accumulated attention mass; Sec. 3.1: r = n - budget of them merge).  A worked
+    example by hand, then plain Python loops (no numpy sorting, no shared helper) on random tiny inputs, then what
+    the number means: a relative change of the scores below half the gap cannot change the selected set, and
+    there is one of the size of the gap that does."""
+    # tokens 0..5, one sink token, one recent token: eligible edges 1, 2, 3 with scores .15, .25, .45
+    a = np.array([0.30, 0.10, 0.05, 0.20, 0.25, 0.10])
+    assert O.boundary_gap(a, budget=4, n_sink=1, n_recent=1) == pytest.approx((0.45 - 0.25) / 0.45, rel=1e-12)
+    assert O.boundary_gap(a, budget=5, n_sink=1, n_recent=1) == pytest.approx((0.25 - 0.15) / 0.25, rel=1e-12)
+    assert O.boundary_gap(a, budget=6, n_sink=1, n_recent=1) == float("inf")      # nothing to merge
+    assert O.boundary_gap(a, budget=3, n_sink=1, n_recent=1) == float("inf")      # every eligible edge merges
+    # without the recent token edge 4 (score .35) is eligible too: sorted .15 .25 .35 .45
+    assert O.boundary_gap(a, budget=4, n_sink=1, n_recent=0) == pytest.approx((0.35 - 0.25) / 0.35, rel=1e-12)
+    # the sink moves the first eligible edge: with n_sink = 0 edge 0 (score .40) joins: .15 .25 .40 .45, r = 3
+    assert O.boundary_gap(a, budget=3, n_sink=0, n_recent=1) == pytest.approx((0.45 - 0.40) / 0.45, rel=1e-12)
+
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        n = int(rng.integers(4, 14))
+        s, nr = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+        a = rng.dirichlet(np.ones(n))
+        edges = [m for m in range(n - 1) if s <= m <= n - 2 - nr]
+        if len(edges) < 2:
+            continue
+        r = int(rng.integers(1, len(edges)))
+        scores = [float(a[m]) + float(a[m + 1]) for m in edges]
+        ranked = []
+        pool = list(scores)
+        while pool:                                        # selection sort by hand
+            lo = min(range(len(pool)), key=lambda i: pool[i])
+            ranked.append(pool.pop(lo))
+        want = (ranked[r] - ranked[r - 1]) / ranked[r]
+        got = O.boundary_gap(a, budget=n - r, n_sink=s, n_recent=nr)
+        assert got == pytest.approx(want, rel=1e-12, abs=1e-300)
+        # meaning: scores perturbed by a relative eps < gap / 2 select the same edges ...
+        if want > 1e-6:
+            sel = set(np.flatnonzero(O.select(a, n - r, s, nr)[0]))
+            for sign in (+1, -1):
+                sig = np.array(scores) * (1 + sign * 0.49 * want * rng.uniform(-1, 1, len(scores)))
+                order = sorted(range(len(sig)), key=lambda i: (sig[i], i))[:r]
+                assert {edges[i] for i in order} == sel
+
+
+def test_conditioning_worked_example_and_brute_force():
+    """conditioning is the smallest ratio, over the slots of several rows, of the weight denominator of Eq. kstar_final
+    (A_m - 2 C_m + A_{m+1} for a pair; sum of the u_t for a run) to the slot's sum of A_t.  A pair by hand with the
+    vectors of Eqs. c11_def-c12_def written out, slots of one row ignored, then loops over explicit c-vectors."""
+    # one dimension, o = 0: residuals 1 and 3, masses .1 and .2
+    #   c11 = .1 (1 - .2) 1 = .08, c22 = .2 (1 - .4) 3 = .36, c12 = -.1 .2 (1 + 3) = -.08
+    #   denominator .08 - 2 (.08) + .36 = .28, sum of A = .44
+    K = np.array([[1.0], [2.0], [5.0]])
+    V = np.array([[1.0], [3.0], [7.0]])
+    alpha = np.array([0.1, 0.2, 0.7])
+    mask = np.array([1, 0, 0], dtype=np.uint8)
+    slot = np.array([0, 0, 1], dtype=np.int32)
+    res = O.merge_compact(K, V, alpha, np.zeros(1), mask, slot)
+    assert O.conditioning(res) == pytest.approx(0.28 / 0.44, rel=1e-12)
+    # the single row's own ratio (1) is not what is reported, and without merged slots the value is 1
+    assert O.conditioning(O.merge_compact(K, V, alpha, np.zeros(1), np.zeros(3, np.uint8), np.arange(3, dtype=np.int32))) == 1.0
+    # a non-positive denominator shows as a non-positive ratio (masses of one half: A = 0, C > 0)
+    res = O.merge_compact(K, V, np.array([0.5, 0.5, 0.0]), np.zeros(1), mask, slot)
+    assert res.fallback[0] and res.U[0] == pytest.approx(-2.0) and O.conditioning(res) == -np.inf
+
+    rng = np.random.default_rng(9)
+    for _ in range(100):
+        n, D = int(rng.integers(3, 12)), int(rng.integers(1, 4))
+        K, V = rng.standard_normal((n, D)), rng.standard_normal((n, D))
+        alpha = rng.dirichlet(np.ones(n))
+        o = alpha @ V
+        mask = (rng.random(n) < 0.5).astype(np.uint8)
+        mask[-1] = 0
+        starts = [t for t in range(n) if t == 0 or mask[t - 1] == 0]
+        slot = np.cumsum([1 if t in starts else 0 for t in range(n)]).astype(np.int32) - 1
+        ratios = []
+        for i, t0 in enumerate(starts):
+            t1 = (starts[i + 1] if i + 1 < len(starts) else n) - 1
+            if t1 == t0:
+                continue
+            c_diag = [alpha[t] * (1 - 2 * alpha[t]) * (V[t] - o) for t in range(t0, t1 + 1)]
+            c_off = [-alpha[t] * alpha[t + 1] * (V[t] + V[t + 1] - 2 * o) for t in range(t0, t1)]
+            a_sum = sum(float(np.sqrt(c @ c)) for c in c_diag)
+            denom = a_sum - 2 * sum(float(np.sqrt(c @ c)) for c in c_off)
+            ratios.append(denom / a_sum)
+        res = O.merge_compact(K, V, alpha, o, mask, slot)
+        want = min(ratios) if ratios else 1.0
+        assert O.conditioning(res) == pytest.approx(want, rel=1e-10, abs=1e-12)
