@@ -48,6 +48,9 @@ def parse():
                     help="also time kvs_decode_attention (one new query per query head) over the merged caches")
     ap.add_argument("--per-query", action="store_true",
                     help="also time the step with per-query aggregation of the norms (kvs_step_per_query, bf16 only)")
+    ap.add_argument("--one-pass-score", action="store_true",
+                    help="take the one-pass score kernel (K kept in LDS between its phases) where it applies; the library "
+                         "does not pick it by itself (measured slower than the two sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true", help="replay the step from a HIP graph instead of launching from the host")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -90,6 +93,8 @@ def main():
     from workloads import WORKLOADS, f32_to_bf16_bits, generate_unit, unit_budget, unit_lengths
 
     kvs.load_library()
+    if args.one_pass_score:
+        kvs.kvs_debug_set("score_fused", 2)
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     w = WORKLOADS[args.workload]
@@ -267,14 +272,17 @@ def main():
             pb[p] += v
     step_bytes = sum(pb.values())
     pb = {p: v * layers_per_launch for p, v in pb.items()}     # ... of one launch's units
-    # The roofline is that of the dominant KERNEL.  kvs_merge_compact and kvs_select are one kernel each;
-    # kvs_score streams three tensors' worth (K twice, V once) in two or three kernels plus two small ones;
-    # its time over three is compared (its longest kernel, sweep 1 with the pass over V riding along, stays
-    # below the merge kernel, see profiles/).
-    streaming_kernels = {"score": 3, "select": 1, "merge_compact": 1}
-    dominant = max(phases, key=lambda p: phase_ms[p] / streaming_kernels[p])
-    achieved = pb[dominant] / (phase_ms[dominant] * 1e-3) / 1e9
+    # The dominant KERNEL of the path is merge_kernel (kvs_merge_compact is exactly that kernel; kvs_score runs
+    # two sweeps and two small kernels, each shorter than it): its algorithmic bytes over its launch time, timed
+    # live above.  The roofline object's own figures are those of the WHOLE STEP (what the target is stated on).
+    kernel = "merge_compact"
+    kernel_gbs = pb[kernel] / (phase_ms[kernel] * 1e-3) / 1e9
     step_gbs = step_bytes * layers / (ms_per_step * 1e-3) / 1e9
+    frac = {p: pb[p] / (phase_ms[p] * 1e-3) / 1e9 / HBM_PEAK_GBS for p in phases}
+    traffic = measured_traffic(w.name)                 # per launch of 64 units, from the committed counter summary
+    traffic_step = None if traffic is None else sum(traffic.values()) / 8.0        # per layer of 8 units
+    flops_score = 2 * 2.0 * R * D * sum(lens)          # both sweeps' Q K^T products, one layer
+    mfma_peak = 2500.0 if w.dtype == "bf16" else 157.3
 
     result = {
         "metric": ("merged KV tokens/s and achieved HBM GB/s (% of peak), 8B-shape 32K merge step"
@@ -285,21 +293,32 @@ def main():
         "config": {"workload": w.name, "layers": layers, "kv_heads": w.n_kv_heads, "q_heads": w.group * w.n_kv_heads,
                    "head_dim": D, "window": w.window, "tokens": lens_seq if w.n_seq > 1 else lens_seq[0],
                    "budget": budgets[0] if w.n_seq == 1 else "25% of length", "n_sink": w.n_sink,
-                   "key_rule": args.key_rule, "io_dtype": w.dtype, "accumulate": "f32", "layers_per_call": lpc, "streams": n_streams, "launch": "hip graph replay" if args.graph else "host",
+                   "key_rule": args.key_rule, "io_dtype": w.dtype, "accumulate": "f32", "layers_per_call": lpc,
+                   "streams": n_streams, "launch": "hip graph replay" if args.graph else "host",
+                   "score_kernels": "one pass" if args.one_pass_score else "two sweeps",
                    "us_per_layer": ms_per_step * 1e3 / layers,
-                   "one_call_per_layer": None if seq_ms is None else {
-                       "ms_per_step": seq_ms, "us_per_layer": seq_ms * 1e3 / layers,
-                       "value": tokens_per_step / (seq_ms * 1e-3)},
+                   "us_per_layer_one_call_per_layer": None if seq_ms is None else seq_ms * 1e3 / layers,
+                   "value_one_call_per_layer": None if seq_ms is None else tokens_per_step / (seq_ms * 1e-3),
                    "input_generation_s": round(t_gen, 1)},
-        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": (measured_traffic(w.name) or {}).get(dominant),
-                     "us_per_launch": phase_ms[dominant] * 1e3, "algorithmic_bytes_per_launch": pb[dominant],
+        # scope "step": algorithmic bytes of score + select + merge_compact of all layers over the timed step
+        "roofline": {"bound": "hbm", "scope": "step", "achieved": step_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": step_gbs / HBM_PEAK_GBS, "target_frac": 0.60,
+                     "traffic": traffic_step, "traffic_source": "committed rocprofv3 counter summary under profiles/"
+                     if traffic else None,
+                     "algorithmic_bytes_per_layer": step_bytes, "step_frac": step_gbs / HBM_PEAK_GBS,
+                     "kernel": "merge_kernel (kvs_merge_compact)", "kernel_achieved": kernel_gbs,
+                     "kernel_frac": kernel_gbs / HBM_PEAK_GBS, "kernel_us_per_launch": phase_ms[kernel] * 1e3,
+                     "kernel_algorithmic_bytes_per_launch": pb[kernel],
+                     "kernel_traffic": (traffic or {}).get(kernel),
                      "units_per_launch": min(UNITS_PER_LAUNCH, big.n_units),
-                     "phases_us": {p: phase_ms[p] * 1e3 for p in phases},
-                     "phases_frac": {p: pb[p] / (phase_ms[p] * 1e-3) / 1e9 / HBM_PEAK_GBS for p in phases},
-                     "step": {"algorithmic_bytes_per_layer": step_bytes, "achieved": step_gbs,
-                              "frac": step_gbs / HBM_PEAK_GBS}},
+                     "score_us_per_launch": phase_ms["score"] * 1e3, "select_us_per_launch": phase_ms["select"] * 1e3,
+                     "merge_compact_us_per_launch": phase_ms["merge_compact"] * 1e3,
+                     "score_frac": frac["score"], "select_frac": frac["select"], "merge_compact_frac": frac["merge_compact"],
+                     "score_traffic_ratio": None if traffic is None else traffic["score"] / pb["score"],
+                     "merge_compact_traffic_ratio": None if traffic is None else traffic["merge_compact"] / pb["merge_compact"],
+                     # the score phase's matrix work against the dense MFMA peak of its dtype (it matters for windows
+                     # of several hundred rows: the stress configuration)
+                     "score_mfma_frac": flops_score * layers_per_launch / (phase_ms["score"] * 1e-3) / 1e12 / mfma_peak},
     }
 
     if args.decode:
@@ -403,8 +422,9 @@ def cpu_baseline(w, keep_host, target_s, workers, rule="hessian"):
     # a token counts K and V rows of ALL KV heads of a layer: n_kv_heads units make one token-layer row
     tokens = done / w.n_kv_heads
     return {"value": tokens / dt, "unit": "tokens/s", "cores": workers, "kind": "oracle",
-            "sample": f"{len(sample)} units (layer 0.., {w.n_kv_heads} KV heads per layer) of the same workload, "
-                      f"numpy fp64, one BLAS thread per unit, {workers} units side by side, {dt:.1f} s"}
+            "sample": f"{len(sample)} units (layer 0.., {w.n_kv_heads} KV heads per layer) of the same workload; the oracle "
+                      f"is numpy fp64 (not a tuned C++/OpenMP program), one BLAS thread per unit, {workers} units side "
+                      f"by side on {workers} of the {os.cpu_count()} host threads the box reports, {dt:.1f} s"}
 
 
 if __name__ == "__main__":

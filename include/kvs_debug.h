@@ -37,10 +37,11 @@ typedef enum {
   KVS_DEBUG_N_SWITCHES = 10
 } kvs_debug_switch;
 
-/* Sets a switch and returns its previous value; -1 (nothing changed) for an unknown switch or a negative value. */
-int kvs_debug_set(kvs_debug_switch which, int value);
+/* Sets a switch (a kvs_debug_switch, passed as an int) and returns its previous value; -1 (nothing changed) for an
+ * unknown switch or a negative value. */
+int kvs_debug_set(int which, int value);
 /* Current value of a switch (-1 for an unknown one). */
-int kvs_debug_get(kvs_debug_switch which);
+int kvs_debug_get(int which);
 
 #ifdef __cplusplus
 }

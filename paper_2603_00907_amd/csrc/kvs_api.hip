@@ -75,10 +75,15 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
   if ((long long)p->group * p->window > KVS_MAX_Q_ROWS) return KVS_ERR_INVALID_ARG;
   if (p->head_dim != 64 && p->head_dim != 128) return KVS_ERR_INVALID_ARG;
   if (p->n_sink < 0 || p->n_recent < 0) return KVS_ERR_INVALID_ARG;
-  if (p->io_dtype != KVS_F32 && p->io_dtype != KVS_BF16) return KVS_ERR_DTYPE;
+  // (a caller may have put any integer into the enum fields: they are read as the ints they are in C)
+  int io_dtype, key_rule;
+  std::memcpy(&io_dtype, &p->io_dtype, sizeof(int));
+  std::memcpy(&key_rule, &p->key_rule, sizeof(int));
+  static_assert(sizeof(p->io_dtype) == sizeof(int) && sizeof(p->key_rule) == sizeof(int), "C enums");
+  if (io_dtype != KVS_F32 && io_dtype != KVS_BF16) return KVS_ERR_DTYPE;
   if (!(p->scale >= 0.f) || !std::isfinite(p->scale)) return KVS_ERR_INVALID_ARG;
   if (!p->len || !p->budget || !p->in_row || !p->out_row) return KVS_ERR_INVALID_ARG;
-  if (p->key_rule != KVS_RULE_HESSIAN && p->key_rule != KVS_RULE_DIAGONAL && p->key_rule != KVS_RULE_MEAN) {
+  if (key_rule != KVS_RULE_HESSIAN && key_rule != KVS_RULE_DIAGONAL && key_rule != KVS_RULE_MEAN) {
     return KVS_ERR_INVALID_ARG;
   }
 
@@ -711,14 +716,14 @@ kvs_status kvs_decode_attention(const kvs_problem* p, const void* Q, const void*
   });
 }
 
-int kvs_debug_set(kvs_debug_switch which, int value) {
-  if ((int)which < 0 || which >= KVS_DEBUG_N_SWITCHES || value < 0) return -1;
+int kvs_debug_set(int which, int value) {
+  if (which < 0 || which >= KVS_DEBUG_N_SWITCHES || value < 0) return -1;
   return g_switch[which].exchange(value, std::memory_order_relaxed);
 }
 
-int kvs_debug_get(kvs_debug_switch which) {
-  if ((int)which < 0 || which >= KVS_DEBUG_N_SWITCHES) return -1;
-  return debug_switch(which);
+int kvs_debug_get(int which) {
+  if (which < 0 || which >= KVS_DEBUG_N_SWITCHES) return -1;
+  return debug_switch((kvs_debug_switch)which);
 }
 
 const char* kvs_status_str(kvs_status s) {
