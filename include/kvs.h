@@ -212,9 +212,10 @@ kvs_status kvs_decode_attention(const kvs_problem* p, const void* Q, const void*
  * kvs_merge_compact_norms is kvs_merge_compact with these A and C in u_t = A_t - C_{t-1} - C_t (Eq.
  * kstar_final); Values, cardinalities, key_rule and the fallback are as there.  The partition still comes from
  * kvs_select on alpha_bar.  With one query row the results are those of the calls above.
- * Restrictions: io_dtype KVS_BF16 (KVS_ERR_DTYPE otherwise), every unit at least 32 rows
- * (KVS_ERR_INVALID_ARG), plain tokens only (no input cardinalities).  kvs_merge_compact_norms takes both dtypes
- * and any length.
+ * Restrictions: with io_dtype KVS_BF16 every unit has at least 32 rows (KVS_ERR_INVALID_ARG; the matrix-core
+ * kernels work on whole tiles), with KVS_F32 any length is taken (vector-ALU kernels, written for the small
+ * configurations, not for speed); plain tokens only (no input cardinalities).  kvs_merge_compact_norms takes
+ * both dtypes and any length.
  *   alpha_bar DEVICE out [rows] fp32, as from kvs_score
  *   a_tok     DEVICE out / in [rows] fp32: A_t
  *   c_edge    DEVICE out / in [rows] fp32: C_t; the entry of a unit's last row is 0 and never read

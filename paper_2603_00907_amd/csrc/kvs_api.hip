@@ -193,8 +193,9 @@ Workspace carve(const Plan& plan, void* base) {
 // Extra workspace of the per-query aggregation, laid out behind the ordinary one.
 struct PerQueryWs {
   float* o_part;     // [largest launch's chunks][R][D]
-  uint16_t* o_hi;    // [n_units][R][D]
+  uint16_t* o_hi;    // [n_units][R][D]  bf16 inputs: -2 o as a bf16 pair hi + lo
   uint16_t* o_lo;
+  float* o_f32;      // [n_units][R][D]  fp32 inputs: o itself
   float* oo;         // [n_units][R]
   float* a_tok;      // [rows]  (kvs_step_per_query only)
   float* c_edge;     // [rows]
@@ -218,8 +219,12 @@ PerQueryWs carve_per_query(const Plan& plan, void* base, Workspace* w) {
   }
   const size_t rd = (size_t)plan.shape.R * plan.shape.D;
   q.o_part = (float*)take((size_t)max_chunks * rd * sizeof(float));
-  q.o_hi = (uint16_t*)take((size_t)plan.n_units * rd * sizeof(uint16_t));
-  q.o_lo = (uint16_t*)take((size_t)plan.n_units * rd * sizeof(uint16_t));
+  if (plan.dtype == KVS_F32) {
+    q.o_f32 = (float*)take((size_t)plan.n_units * rd * sizeof(float));
+  } else {
+    q.o_hi = (uint16_t*)take((size_t)plan.n_units * rd * sizeof(uint16_t));
+    q.o_lo = (uint16_t*)take((size_t)plan.n_units * rd * sizeof(uint16_t));
+  }
   q.oo = (float*)take((size_t)plan.n_units * plan.shape.R * sizeof(float));
   q.a_tok = (float*)take((size_t)plan.rows_in * sizeof(float));
   q.c_edge = (float*)take((size_t)plan.rows_in * sizeof(float));
@@ -229,11 +234,19 @@ PerQueryWs carve_per_query(const Plan& plan, void* base, Workspace* w) {
 
 // The per-query kernels are bf16 MFMA kernels whose tiles hold 32 whole rows of a unit.
 kvs_status check_per_query(const Plan& plan) {
-  if (plan.dtype != KVS_BF16) return KVS_ERR_DTYPE;
-  for (const Unit& un : plan.units) {
+  if (plan.dtype == KVS_F32) return KVS_OK;         // the fp32 kernels take any unit length
+  for (const Unit& un : plan.units) {               // bf16: whole MFMA tiles of 32 rows
     if (un.len < 32) return KVS_ERR_INVALID_ARG;
   }
   return KVS_OK;
+}
+
+hipError_t per_query_norms(const Plan& plan, const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+                           const void* V, const Workspace& w, const PerQueryWs& q, float* a_tok, float* c_edge,
+                           hipStream_t s) {
+  if (plan.dtype == KVS_F32)
+    return launch_per_query_norms_f32(tab, sh, Q, K, V, w.c_row, q.o_part, q.o_f32, a_tok, c_edge, s);
+  return launch_per_query_norms(tab, sh, Q, K, V, w.c_row, q.o_part, q.o_hi, q.o_lo, q.oo, a_tok, c_edge, s);
 }
 
 struct Range {
@@ -617,7 +630,7 @@ kvs_status kvs_sensitivity(const kvs_problem* p, const void* Q, const void* K, c
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, nullptr, alpha_bar, w, s);
     if (e != hipSuccess) return e;
-    return launch_per_query_norms(tab, sh, Q, K, V, w.c_row, q.o_part, q.o_hi, q.o_lo, q.oo, a_tok, c_edge, s);
+    return per_query_norms(plan, tab, sh, Q, K, V, w, q, a_tok, c_edge, s);
   });
 }
 
@@ -680,7 +693,7 @@ kvs_status kvs_step_per_query(const kvs_problem* p, const void* Q, const void* K
     if (e != hipSuccess) return e;
     e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, nullptr, nullptr, nullptr, s);
     if (e != hipSuccess) return e;
-    e = launch_per_query_norms(tab, sh, Q, K, V, w.c_row, q.o_part, q.o_hi, q.o_lo, q.oo, q.a_tok, q.c_edge, s);
+    e = per_query_norms(plan, tab, sh, Q, K, V, w, q, q.a_tok, q.c_edge, s);
     if (e != hipSuccess) return e;
     return launch_merge_norms(tab, sh, plan.dtype, K, V, q.a_tok, q.c_edge, mask, slot, K_out, V_out, counts_out, s);
   });

@@ -241,6 +241,10 @@ hipError_t launch_merge_norms(const UnitTable& tab, const Shape& sh, kvs_dtype d
 hipError_t launch_per_query_norms(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
                                   const float* c_row, float* o_part, uint16_t* o_hi, uint16_t* o_lo, float* oo,
                                   float* a_tok, float* c_edge, hipStream_t stream);
+// The same for fp32 inputs (any unit length, vector ALU).  o: [n_units][R][D] fp32.
+hipError_t launch_per_query_norms_f32(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
+                                      const void* V, const float* c_row, float* o_part, float* o, float* a_tok,
+                                      float* c_edge, hipStream_t stream);
 
 // Decode attention over a (merged) cache: chunk partials into `part`, then out[n_units, R, D].
 hipError_t launch_decode(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,

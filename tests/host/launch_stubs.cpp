@@ -54,6 +54,8 @@ hipError_t launch_merge_norms(const UnitTable& tab, const Shape&, kvs_dtype, con
                               const uint8_t*, const int32_t*, void*, void*, int32_t*, hipStream_t) { check_table(tab); return ok(); }
 hipError_t launch_per_query_norms(const UnitTable& tab, const Shape&, const void*, const void*, const void*, const float*,
                                   float*, uint16_t*, uint16_t*, float*, float*, float*, hipStream_t) { check_table(tab); return ok(); }
+hipError_t launch_per_query_norms_f32(const UnitTable& tab, const Shape&, const void*, const void*, const void*, const float*,
+                                      float*, float*, float*, float*, hipStream_t) { check_table(tab); return ok(); }
 hipError_t launch_decode(const UnitTable& tab, const Shape&, kvs_dtype, const void*, const void*, const void*, const int32_t*,
                          float*, float*, hipStream_t) { check_table(tab); return ok(); }
 

@@ -225,9 +225,11 @@ def test_decode_and_counts_entry_points_validate_on_the_host():
 
 
 def test_per_query_entry_points_validate_on_the_host():
-    assert status_of(kvs.kvs_per_query_workspace_size, problem()) == kvs.KVS_ERR_DTYPE          # fp32
+    assert status_of(kvs.kvs_per_query_workspace_size, problem()) == kvs.KVS_OK                 # fp32: any length
+    assert status_of(kvs.kvs_per_query_workspace_size, problem(lens=[1024, 31], budgets=[512, 31])) == kvs.KVS_OK
     assert status_of(kvs.kvs_per_query_workspace_size,
                      problem(dtype="bf16", lens=[1024, 31], budgets=[512, 31])) == kvs.KVS_ERR_INVALID_ARG
+    assert kvs.kvs_per_query_workspace_size(problem()) > kvs.kvs_workspace_size(problem())
     p = problem(dtype="bf16")
     need = kvs.kvs_per_query_workspace_size(p)
     assert need % 256 == 0 and need > kvs.kvs_workspace_size(p)
