@@ -250,7 +250,7 @@ def main():
             evs[i][0].record()
             kvs.kvs_score_counts(pr, Qs[i], Ks[i], Vs[i], Cs[i], alpha, obar, ws, stream=stream)
             evs[i][1].record()
-            kvs.kvs_select(pr, alpha, mask, slot, stream=stream)
+            kvs.kvs_select(pr, alpha, mask, slot, ws=ws, stream=stream)    # (with the workspace, as inside kvs_step)
             evs[i][2].record()
             kvs.kvs_merge_compact_counts(pr, Ks[i], Vs[i], Cs[i], alpha, obar, mask, slot, K_out[i], V_out[i], counts[i],
                                          stream=stream)

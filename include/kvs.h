@@ -55,9 +55,9 @@ typedef enum {
   KVS_ERR_BUDGET = 3,       /* budget < n_sink + 1 + n_recent for a unit that has to merge (len > budget),
                                or budget < 1 */
   KVS_ERR_WORKSPACE = 4,    /* workspace null, misaligned (256 B) or smaller than kvs_workspace_size(); only the
-                               calls that use one check it: kvs_select, kvs_merge_compact,
-                               kvs_merge_compact_counts and kvs_merge_compact_norms use none and ignore
-                               ws / ws_bytes (NULL and 0 are fine there)                               */
+                               calls that use one check it: kvs_merge_compact, kvs_merge_compact_counts and
+                               kvs_merge_compact_norms use none and ignore ws / ws_bytes (NULL and 0 are fine
+                               there); for kvs_select it is optional (see there)                        */
   KVS_ERR_ALIAS = 5,        /* an output overlaps an input, another output or the workspace */
   KVS_ERR_DEVICE = 6        /* a HIP launch failed.  The library reads the calling thread's HIP error state after
                                each launch (which clears it) and drops an error left pending by the caller's own
@@ -116,7 +116,10 @@ kvs_status kvs_score(const kvs_problem* p, const void* Q, const void* K, const v
  *   edge score sigma[m] = alpha_bar[m] + alpha_bar[m+1], added and compared in fp32, for the eligible
  *   edges n_sink <= m <= len-2-n_recent; the r = len - budget smallest are selected, ties to the lower m.
  *   edge_mask     DEVICE out [rows] u8: 1 = token m+1 joins the slot of token m (last token: 0)
- *   slot_of_token DEVICE out [rows] i32: unit-local output slot of every token (non-decreasing)   */
+ *   slot_of_token DEVICE out [rows] i32: unit-local output slot of every token (non-decreasing)
+ *   ws            optional.  With a workspace (256-byte aligned, at least kvs_workspace_size(p) bytes) a long unit's
+ *                 selection may be spread over several workgroups that meet through it; with NULL, a misaligned or
+ *                 a smaller one, every unit is selected by one workgroup.  The results are the same bit for bit. */
 kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar,
                       uint8_t* edge_mask, int32_t* slot_of_token,
                       void* ws, size_t ws_bytes, void* hip_stream);

@@ -27,8 +27,11 @@ typedef enum {
   KVS_DEBUG_SCORE_FUSED = 6,  /* KVS_SCORE_FUSED=1     2: the one-pass score kernel (K kept in LDS between the statistics
                                                           and the alpha_bar phase) wherever it applies; it is off
                                                           otherwise (measured slower than the two sweeps)              */
-  KVS_DEBUG_SELECT_SPLIT = 7, /* KVS_SELECT_SPLIT=0|1  1: always one workgroup per unit in the selection,
-                                                       2: several workgroups per unit wherever that path applies        */
+  KVS_DEBUG_SELECT_SPLIT = 7, /* KVS_SELECT_SPLIT=<n>  how a unit's edge selection is spread over workgroups.  1: always one
+                                                       workgroup per unit, 2: as many parts as a unit can have (down to
+                                                       64 edges each), whatever the launch, 3: the same with a wait limit
+                                                       of zero, so that the parts give up at their first wait and the
+                                                       unit's first part selects alone (a test of that way out)         */
   KVS_DEBUG_FUSED_WAIT_US = 8,/* KVS_FUSED_WAIT_US=<n> n + 1: a workgroup of the one-pass score kernel waits at most n
                                                        microseconds for its unit's normalisers before it hands its
                                                        item to the second kernel (1: it never waits)                   */

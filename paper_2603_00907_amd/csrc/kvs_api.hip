@@ -119,7 +119,7 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
     un.index = u;
     un.o_base = 0;
     un.f_base = 0;
-    un.pad_ = 0;
+    un.s_base = 0;
     plan->rows_in = std::max(plan->rows_in, un.in_row + len);
     plan->rows_out = std::max(plan->rows_out, un.out_row + (long long)un.n_out);
   }
@@ -186,6 +186,8 @@ Workspace carve(const Plan& plan, void* base) {
     w.fo_part = (float*)take((size_t)plan.fused_items * plan.shape.D * sizeof(float));
     w.fsync = (unsigned int*)take(((size_t)kFusedSyncInts + plan.fused_items) * sizeof(unsigned int));
   }
+  // exchange area of the selection by several workgroups per unit (one launch group at a time)
+  w.sel_shared = (unsigned int*)take((size_t)std::min(plan.n_units, kMaxUnitsPerLaunch) * kSelSharedInts * sizeof(unsigned int));
   w.bytes = off;
   return w;
 }
@@ -281,8 +283,22 @@ kvs_status check_ws(const Plan& plan, const void* ws, size_t ws_bytes, Workspace
 }
 
 // Calls f(table) for every group of at most kMaxUnitsPerLaunch units.
+// Compute units of the current device (asked once per device).
+int compute_units() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+    cached[dev].store(n, std::memory_order_relaxed);
+  }
+  return n;
+}
+
+// split_select: the caller hands the launchers an exchange area, so a unit's selection may take several workgroups.
 template <typename F>
-kvs_status for_each_group(const Plan& plan, F&& f) {
+kvs_status for_each_group(const Plan& plan, F&& f, bool split_select = false) {
   // An error that the calling thread's earlier HIP calls left pending is not this call's: it is dropped here,
   // so that what the launchers read after their launches is theirs.
   (void)hipGetLastError();
@@ -290,9 +306,13 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
     UnitTable tab;
     std::memset(&tab, 0, sizeof(tab));
     tab.n_units = std::min(kMaxUnitsPerLaunch, plan.n_units - first);
-    int chunks = 0, mblocks = 0, ochunks = 0, fitems = 0;
+    int chunks = 0, mblocks = 0, ochunks = 0, fitems = 0, sparts = 0;
+    const int split_mode = split_select ? debug_switch(KVS_DEBUG_SELECT_SPLIT) : 1;
+    const int n_cus = split_mode == 1 ? 0 : compute_units();
     for (int i = 0; i < tab.n_units; ++i) {
       tab.u[i] = plan.units[first + i];
+      tab.u[i].s_base = sparts;
+      sparts += select_parts(tab.u[i], plan.shape, tab.n_units, n_cus, split_mode);
       tab.u[i].chunk_base = chunks;
       tab.u[i].m_base = mblocks;
       tab.u[i].o_base = ochunks;
@@ -306,6 +326,7 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
     tab.total_mblocks = mblocks;
     tab.total_ochunks = ochunks;
     tab.total_fitems = fitems;
+    tab.total_sparts = sparts;
     long long rows = 0;
     for (int i = 0; i < tab.n_units; ++i) rows += tab.u[i].len;
     Shape sh = plan.shape;
@@ -323,6 +344,25 @@ kvs_status for_each_group(const Plan& plan, F&& f) {
 }
 
 }  // namespace
+
+int select_parts(const Unit& un, const Shape& sh, int n_units, int n_cus, int mode) {
+  const int r = un.len - un.n_out;
+  const int E = (un.len - 2 - sh.n_recent) - sh.n_sink + 1;      // eligible edges
+  if (mode == 1 || r <= 0 || E < 64) return 1;
+  const int groups = (E + 6) / 4 + 1;                            // upper bound of the kernel's group count
+  const int fit = (groups + kSelPartKeys / 4 - 1) / (kSelPartKeys / 4);   // fewest parts whose keys fit their LDS
+  // one select workgroup per CU, so that the parts of a launch run together (a test may ask for more)
+  // A launch of many units keeps the chip busy with one workgroup per unit, and on a chip shared with another
+  // stream's kernels its parts would wait for each other's turn (64 units at 4 parts each: 67.0 us per layer of the
+  // two-stream headline run against 65.6): the parts are for launches that leave most compute units idle.
+  if (mode == 0 && n_cus / n_units < 8) return 1;
+  const int most = mode >= 2 ? kSelMaxParts : (n_cus / n_units < kSelMaxParts ? n_cus / n_units : kSelMaxParts);
+  const int min_keys = mode >= 2 ? 64 : kSelMinPartKeys;
+  int P = (E + min_keys - 1) / min_keys;
+  if (P > most) P = most;
+  if (P < 2 || P < fit) return 1;                                // not worth it, or too long for the parts it may have
+  return P;
+}
 
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
                         const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream,
@@ -417,20 +457,30 @@ kvs_status kvs_score_counts(const kvs_problem* p, const void* Q, const void* K, 
 
 kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar, uint8_t* edge_mask, int32_t* slot_of_token,
                       void* ws, size_t ws_bytes, void* hip_stream) {
-  (void)ws;
-  (void)ws_bytes;
   Plan plan;
   kvs_status st = make_plan(p, &plan);
   if (st != KVS_OK) return st;
-  st = check_ranges({{alpha_bar, (size_t)plan.rows_in * 4, false},
-                     {edge_mask, (size_t)plan.rows_in, true},
-                     {slot_of_token, (size_t)plan.rows_in * 4, true}});
-  if (st != KVS_OK) return st;
+  std::vector<Range> rs = {{alpha_bar, (size_t)plan.rows_in * 4, false},
+                           {edge_mask, (size_t)plan.rows_in, true},
+                           {slot_of_token, (size_t)plan.rows_in * 4, true}};
+  // The workspace is optional here: with one (of kvs_workspace_size bytes) a long unit's selection may be spread
+  // over several workgroups, which meet through it; without one every unit takes a single workgroup.
+  Workspace w{};
+  const bool with_ws = ws != nullptr && ((uintptr_t)ws % kAlign) == 0 && ws_bytes >= carve(plan, nullptr).bytes;
+  if (with_ws) {
+    w = carve(plan, ws);
+    rs.push_back({ws, w.bytes, true});
+  }
+  if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
+    if (tab.total_sparts != tab.n_units) {      // (the score kernels clear the area when they run before the selection)
+      const hipError_t e = launch_select_clear(tab, w.sel_shared, s);
+      if (e != hipSuccess) return e;
+    }
     return launch_select_obar(tab, sh, plan.dtype, true, alpha_bar, edge_mask, slot_of_token, nullptr,
-                              nullptr, nullptr, s);
-  });
+                              nullptr, nullptr, s, nullptr, nullptr, w.sel_shared);
+  }, /*split_select=*/with_ws);
 }
 
 kvs_status kvs_merge_compact(const kvs_problem* p, const void* K, const void* V, const float* alpha_bar,
@@ -523,17 +573,17 @@ static kvs_status step_with_workspace(const Plan& plan, const void* Q, const voi
       // the one-pass kernel leaves one partial o_bar per work item (a few hundred per unit): they are added up by
       // one more workgroup per unit beside the selection, and the merge pass takes the finished o_bar
       e = launch_select_obar(tab, sh2, plan.dtype, true, w.alpha_bar, mask, slot, nullptr, counts_in, nullptr, s,
-                             w.fo_part, w.o_bar);
+                             w.fo_part, w.o_bar, w.sel_shared);
       if (e != hipSuccess) return e;
       return launch_merge(tab, sh2, plan.dtype, K, V, counts_in, w.alpha_bar, w.o_bar, nullptr, mask, slot, K_out,
                           V_out, counts_out, s);
     }
     e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, o_layout ? nullptr : V, counts_in,
-                           w.o_part, s);
+                           w.o_part, s, nullptr, nullptr, w.sel_shared);
     if (e != hipSuccess) return e;
     return launch_merge(tab, sh2, plan.dtype, K, V, counts_in, w.alpha_bar, nullptr, w.o_part, mask, slot, K_out,
                         V_out, counts_out, s);
-  });
+  }, /*split_select=*/true);
 }
 
 kvs_status kvs_step_counts(const kvs_problem* p, const void* Q, const void* K, const void* V, const int32_t* counts_in,
@@ -691,12 +741,13 @@ kvs_status kvs_step_per_query(const kvs_problem* p, const void* Q, const void* K
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, nullptr, w.alpha_bar, w, s);
     if (e != hipSuccess) return e;
-    e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, nullptr, nullptr, nullptr, s);
+    e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, nullptr, nullptr, nullptr, s, nullptr,
+                           nullptr, w.sel_shared);
     if (e != hipSuccess) return e;
     e = per_query_norms(plan, tab, sh, Q, K, V, w, q, q.a_tok, q.c_edge, s);
     if (e != hipSuccess) return e;
     return launch_merge_norms(tab, sh, plan.dtype, K, V, q.a_tok, q.c_edge, mask, slot, K_out, V_out, counts_out, s);
-  });
+  }, /*split_select=*/true);
 }
 
 kvs_status kvs_decode_workspace_size(const kvs_problem* p, size_t* bytes) {

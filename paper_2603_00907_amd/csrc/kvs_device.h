@@ -43,7 +43,7 @@ struct Unit {
   int index;            // position of the unit in the caller's problem (indexes Q, o_bar, partials)
   int o_base;           // o_bar-pass workgroups of the launch's earlier units
   int f_base;           // work items of the one-pass score kernel that belong to the launch's earlier units
-  int pad_;
+  int s_base;           // select workgroups of the launch's earlier units (a unit has one, or several parts)
 };
 
 // Work items of the one-pass score kernel: chunks of kFusedChunkBytes of K rows (a function of D and the length).
@@ -64,13 +64,29 @@ __host__ __device__ inline int obar_chunks(int len) {
   return (len + cl - 1) / cl;
 }
 
+// Selection over several workgroups ("parts") per unit.  A part keeps at most kSelPartKeys edge scores in LDS; what
+// the parts of a unit exchange goes through kSelSharedInts unsigned ints of device memory per unit of the launch,
+// which must be zero when the select kernel starts (the score finalize kernel of the same call clears them):
+//   [kSelNotMin] ~(smallest key), [kSelMax] largest key, [kSelNCand] candidates listed so far,
+//   [kSelAbandon] set by a part that gave up waiting, [kSelArrive + phase] parts that finished a phase,
+//   [kSelPartLt + part], [kSelPartEq + part] keys below / equal to the threshold in a part,
+//   [kSelHist + bin] histogram of the first digit, [kSelCand + i] keys of the threshold's bin.
+constexpr int kSelMaxParts = 32;
+constexpr int kSelPartKeys = 8192;
+constexpr int kSelMinPartKeys = 2048;     // parts are not made smaller than this unless a test asks for it
+constexpr int kSelNotMin = 0, kSelMax = 1, kSelNCand = 2, kSelAbandon = 3, kSelArrive = 4;
+constexpr int kSelPartLt = 16, kSelPartEq = kSelPartLt + kSelMaxParts;
+constexpr int kSelHist = 128, kSelHistBins = 2048;
+constexpr int kSelCand = kSelHist + kSelHistBins, kSelCandMax = 2048;
+constexpr int kSelSharedInts = kSelCand + kSelCandMax;
+
 struct UnitTable {
   int n_units;
   int total_chunks;
   int total_mblocks;
   int total_ochunks;
   int total_fitems;     // work items of the one-pass score kernel
-  int pad_;
+  int total_sparts;     // select workgroups
   Unit u[kMaxUnitsPerLaunch];
 };
 
@@ -108,6 +124,7 @@ struct Workspace {
   float* fstats;        // [work items][R]  log2 of the sum of 2^logit over the item's tokens, for every query row
   float* fo_part;       // [work items][D]  partial o_bar of every item
   unsigned int* fsync;  // kFusedSyncInts counters and flags, then one entry per work item (items given up on)
+  unsigned int* sel_shared;  // [kMaxUnitsPerLaunch][kSelSharedInts]  exchange area of the split selection
   size_t bytes;
 };
 
@@ -191,15 +208,28 @@ __device__ __forceinline__ void load_row_consts(const float* __restrict__ c_row,
   __syncthreads();
 }
 
-// Which unit and which chunk a workgroup of a chunk-indexed launch works on.
+// The last unit whose running count BASE (chunks, merge workgroups, ... of the launch's earlier units) is at most x:
+// the unit that work item x of the launch belongs to.  A binary search, because the table lives in the kernel
+// arguments and every probe is a scalar load that the next one depends on (about a quarter of a microsecond when
+// it misses the scalar cache: walking the table unit by unit cost a 64-unit select launch 15 of its 37 us).
+template <int Unit::*BASE>
+__device__ __forceinline__ int find_unit_by(const UnitTable& tab, int x) {
+  int lo = 0, hi = tab.n_units - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (tab.u[mid].*BASE <= x) lo = mid;
+    else hi = mid - 1;
+  }
+  return lo;
+}
+// Which unit a workgroup of a chunk-indexed launch works on.
 __device__ __forceinline__ int find_unit(const UnitTable& tab, int chunk) {
-  int u = 0;
-  while (u + 1 < tab.n_units && tab.u[u + 1].chunk_base <= chunk) ++u;
-  return u;
+  return find_unit_by<&Unit::chunk_base>(tab, chunk);
 }
 
 // Launchers (defined next to their kernels).  All enqueue on `stream` and return the launch status.
 // Unit-wide softmax statistics from the chunks' partial ones (one small workgroup per unit).
+// (it also zeroes ws.sel_shared for the selection that follows, when there is one)
 hipError_t launch_score_finalize(const UnitTable& tab, const Shape& sh, const Workspace& ws, hipStream_t stream);
 // Both score sweeps: chunk statistics, the finalize kernel, then alpha_bar.
 // counts_in (here and below): cardinalities of the input rows when the cache is already a merged one, or null.
@@ -209,14 +239,22 @@ hipError_t launch_score_finalize(const UnitTable& tab, const Shape& sh, const Wo
 hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,
                         const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream,
                         const void* V = nullptr, int* o_layout = nullptr);
-// One launch, two kinds of workgroups: the first `with_select ? n_units : 0` select the edges of one unit
-// each, the others stream one chunk of V each into o_part (skipped when V is null).
+// One launch, several kinds of workgroups: the first `with_select ? tab.total_sparts : 0` select edges (one workgroup
+// per unit, or several parts per unit that meet through sel_shared), the others stream one chunk of V each into
+// o_part (skipped when V is null).
 // A third kind (o_bar_out non-null, one workgroup per unit) adds up the partial sums that a score kernel left
 // (sh.o_from_score says where) into o_bar_out[unit][D].
+// sel_shared: the zeroed exchange area (see kSelSharedInts), needed when any unit has more than one part.
 hipError_t launch_select_obar(const UnitTable& tab, const Shape& sh, kvs_dtype dt, bool with_select,
                               const float* alpha_bar, uint8_t* edge_mask, int32_t* slot, const void* V,
                               const int32_t* counts_in, float* o_part, hipStream_t stream,
-                              const float* parts_in = nullptr, float* o_bar_out = nullptr);
+                              const float* parts_in = nullptr, float* o_bar_out = nullptr,
+                              unsigned int* sel_shared = nullptr);
+// Zeroes the exchange area of the launch's units (callers that did not run the score kernels before the selection).
+hipError_t launch_select_clear(const UnitTable& tab, unsigned int* sel_shared, hipStream_t stream);
+// How many select workgroups a unit gets in a launch of n_units units on a chip of n_cus compute units
+// (mode: the KVS_DEBUG_SELECT_SPLIT switch).  1: the single-workgroup selection.
+int select_parts(const Unit& un, const Shape& sh, int n_units, int n_cus, int mode);
 // o_bar[u] = sum of the unit's partial sums, in chunk order (only when o_bar itself is an output).
 hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float* parts, float* o_bar,
                               hipStream_t stream);

@@ -84,8 +84,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   __shared__ int sm_scan[2 * (kThreads / kWave)];
   __shared__ float sm_obar[kThreads / D][D];
 
-  int ui = 0;
-  while (ui + 1 < tab.n_units && tab.u[ui + 1].m_base <= (int)blockIdx.x) ++ui;
+  const int ui = find_unit_by<&Unit::m_base>(tab, (int)blockIdx.x);
   const Unit un = tab.u[ui];
   const int n = un.len;
   const int tid = threadIdx.x;

@@ -111,8 +111,13 @@ __device__ __forceinline__ float lse2(float a, float b) {
 }
 
 // Before the one-pass kernel: counters to zero, the launch's normalisers to "not yet" (one block per unit).
-__global__ void score_fused_init_kernel(const UnitTable tab, const int R, float* c_row, unsigned int* fsync) {
+__global__ void score_fused_init_kernel(const UnitTable tab, const int R, float* c_row, unsigned int* fsync,
+                                        unsigned int* sel_shared) {
   const Unit un = tab.u[blockIdx.x];
+  if (sel_shared != nullptr) {                    // the exchange area of the selection that follows starts from zero
+    uint4* z = reinterpret_cast<uint4*>(sel_shared + (size_t)blockIdx.x * kSelSharedInts);
+    for (int i = threadIdx.x; i < kSelSharedInts / 4; i += blockDim.x) z[i] = make_uint4(0u, 0u, 0u, 0u);
+  }
   for (int q = threadIdx.x; q < R; q += blockDim.x) {
     reinterpret_cast<unsigned int*>(c_row)[(size_t)un.index * R + q] = kFusedNotYet;
   }
@@ -219,8 +224,7 @@ __global__ __launch_bounds__(kThreads, 1) void score_fused_kernel(
 #ifdef KVS_FUSED_PROFILE
     if (tid == 0) { pf_t = wall_clock64(); ++pf_items; }
 #endif
-    int ui = 0;
-    while (ui + 1 < tab.n_units && tab.u[ui + 1].f_base <= (int)item) ++ui;
+    const int ui = find_unit_by<&Unit::f_base>(tab, (int)item);
     const Unit un = tab.u[ui];
     const int chunk = (int)item - un.f_base;
     const int n_chunks = fused_chunks(un.len, D);
@@ -613,7 +617,8 @@ template <int D, bool STREAM, bool CAUSAL>
 hipError_t launch_fused_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
                           const int32_t* counts_in, float* alpha_bar, const Workspace& ws, hipStream_t stream,
                           int grid_first, int grid_second, unsigned timeout_ticks, unsigned stagger_ticks) {
-  hipLaunchKernelGGL(score_fused_init_kernel, dim3(tab.n_units), dim3(kQRows), 0, stream, tab, sh.R, ws.c_row, ws.fsync);
+  hipLaunchKernelGGL(score_fused_init_kernel, dim3(tab.n_units), dim3(kQRows), 0, stream, tab, sh.R, ws.c_row, ws.fsync,
+                     ws.sel_shared);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((score_fused_kernel<D, STREAM, CAUSAL, false>), dim3(grid_first), dim3(kThreads), 0, stream, tab,

@@ -144,8 +144,13 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
 // serialise the round trips); the order of the additions is fixed.
 __global__ __launch_bounds__(kThreads) void score_finalize_kernel(const UnitTable tab, const Shape sh,
                                                                   const float2* __restrict__ stats_part,
-                                                                  float* __restrict__ c_row) {
+                                                                  float* __restrict__ c_row,
+                                                                  unsigned int* __restrict__ sel_shared) {
   constexpr int HALF = kMaxChunks / 2;
+  if (sel_shared != nullptr) {                    // the exchange area of the selection that follows starts from zero
+    uint4* z = reinterpret_cast<uint4*>(sel_shared + (size_t)blockIdx.x * kSelSharedInts);
+    for (int i = threadIdx.x; i < kSelSharedInts / 4; i += kThreads) z[i] = make_uint4(0u, 0u, 0u, 0u);
+  }
   __shared__ float2 sm_pair[2][128];
   const Unit un = tab.u[blockIdx.x];
   const int R = sh.R;
@@ -186,7 +191,7 @@ __global__ __launch_bounds__(kThreads) void score_finalize_kernel(const UnitTabl
 
 hipError_t launch_score_finalize(const UnitTable& tab, const Shape& sh, const Workspace& ws, hipStream_t stream) {
   hipLaunchKernelGGL(score_finalize_kernel, dim3(tab.n_units), dim3(kThreads), 0, stream, tab, sh, ws.stats_part,
-                     ws.c_row);
+                     ws.c_row, ws.sel_shared);
   return hipGetLastError();
 }
 

@@ -51,6 +51,7 @@ struct SelectSmem {
   int lt[kSelWaves], eq[kSelWaves];
   uint32_t wmin[kSelWaves], wmax[kSelWaves];
   int ncand;
+  int plt[kSelMaxParts], peq[kSelMaxParts];     // split selection: the other parts' counts
 };
 
 // Inclusive prefix sum over the 64 lanes with DPP moves only (no LDS crossbar): four shifts inside
@@ -120,6 +121,79 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
   x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xA, 0xF, false));
   x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xC, 0xF, false));
   return (uint32_t)__builtin_amdgcn_readlane((int)x, kWave - 1);
+}
+
+// The first digit of the threshold is known (prefix, pmask) and `want` is its rank among the keys that share
+// it: settles the remaining 21 bits.  sm.cand[0 .. ncand) lists those keys when ncand <= kCand; otherwise the
+// passes run over sm.keys[0 .. nkeys).  Returns the number of keys equal to the threshold; prefix is then the
+// threshold and `want` the number of keys equal to it that are still wanted.
+__device__ __forceinline__ int refine_threshold(SelectSmem& sm, const int ncand, const int nkeys, uint32_t& prefix,
+                                                uint32_t& pmask, int& want) {
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  constexpr uint32_t kNone = 0xffffffffu;
+  int n_equal;                         // keys equal to the threshold
+  if (ncand <= kWave) {
+    // A handful of candidates: all against all.  Lane i of every wavefront holds candidate i, wavefront
+    // w compares with candidates 4w..4w+3 (one LDS address per read: a broadcast), and the partial
+    // counts meet in LDS.  Ties go by list position: equal keys are interchangeable here, only the
+    // counts below and at the threshold matter.
+    int* below = sm.hist;              // the histogram is idle now
+    int* same = sm.hist + kWave;
+    int* before = sm.hist + 2 * kWave;
+    if (tid < 3 * kWave) sm.hist[tid] = 0;
+    __syncthreads();
+    const uint32_t c = lane < ncand ? sm.cand[lane] : kNone;
+    int b = 0, e = 0, f = 0;
+#pragma unroll
+    for (int jj = 0; jj < kWave / kSelWaves; ++jj) {
+      const int j = wave * (kWave / kSelWaves) + jj;
+      const uint32_t cj = j < ncand ? sm.cand[j] : kNone;
+      b += cj < c;
+      e += cj == c;
+      f += (cj == c) & (j < lane);
+    }
+    if (lane < ncand) {
+      if (b) atomicAdd(&below[lane], b);
+      if (e) atomicAdd(&same[lane], e);
+      if (f) atomicAdd(&before[lane], f);
+    }
+    __syncthreads();
+    if (tid < ncand && below[tid] + before[tid] == want - 1) {
+      sm.pick[0] = (int)c;
+      sm.pick[1] = below[tid];
+      sm.pick[2] = same[tid];
+    }
+    __syncthreads();
+    prefix = (uint32_t)sm.pick[0];
+    want -= sm.pick[1];
+    n_equal = sm.pick[2];
+  } else {
+    const bool listed = (ncand <= kCand);
+    const int shifts[2] = {10, 0};
+    const int widths[2] = {11, 10};
+    n_equal = 0;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      const int shift = shifts[pass];
+      const int bins = 1 << widths[pass];
+      for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
+      __syncthreads();
+      if (listed) {
+        for (int i = tid; i < ncand; i += kSelThreads) {
+          const uint32_t k = sm.cand[i];
+          if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
+        }
+      } else {                            // a bin too crowded for the list: full passes over the keys
+        for (int i = tid; i < nkeys; i += kSelThreads) {
+          const uint32_t k = sm.keys[i];
+          if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
+        }
+      }
+      __syncthreads();
+      n_equal = pick_bin(sm, shift, bins, prefix, pmask, want);
+    }
+  }
+  return n_equal;
 }
 
 // Select for a unit whose keys fit the LDS.  Key i' belongs to the edge after token lo_al + i', where
@@ -263,69 +337,7 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
     }
   }
   __syncthreads();
-  const int ncand = sm.ncand;
-  int n_equal;                         // keys equal to the threshold
-  if (ncand <= kWave) {
-    // A handful of candidates: all against all.  Lane i of every wavefront holds candidate i, wavefront
-    // w compares with candidates 4w..4w+3 (one LDS address per read: a broadcast), and the partial
-    // counts meet in LDS.  Ties go by list position: equal keys are interchangeable here, only the
-    // counts below and at the threshold matter.
-    int* below = sm.hist;              // the histogram is idle now
-    int* same = sm.hist + kWave;
-    int* before = sm.hist + 2 * kWave;
-    if (tid < 3 * kWave) sm.hist[tid] = 0;
-    __syncthreads();
-    const uint32_t c = lane < ncand ? sm.cand[lane] : kNone;
-    int b = 0, e = 0, f = 0;
-#pragma unroll
-    for (int jj = 0; jj < kWave / kSelWaves; ++jj) {
-      const int j = wave * (kWave / kSelWaves) + jj;
-      const uint32_t cj = j < ncand ? sm.cand[j] : kNone;
-      b += cj < c;
-      e += cj == c;
-      f += (cj == c) & (j < lane);
-    }
-    if (lane < ncand) {
-      if (b) atomicAdd(&below[lane], b);
-      if (e) atomicAdd(&same[lane], e);
-      if (f) atomicAdd(&before[lane], f);
-    }
-    __syncthreads();
-    if (tid < ncand && below[tid] + before[tid] == want - 1) {
-      sm.pick[0] = (int)c;
-      sm.pick[1] = below[tid];
-      sm.pick[2] = same[tid];
-    }
-    __syncthreads();
-    prefix = (uint32_t)sm.pick[0];
-    want -= sm.pick[1];
-    n_equal = sm.pick[2];
-  } else {
-    const bool listed = (ncand <= kCand);
-    const int shifts[2] = {10, 0};
-    const int widths[2] = {11, 10};
-    n_equal = 0;
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-      const int shift = shifts[pass];
-      const int bins = 1 << widths[pass];
-      for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
-      __syncthreads();
-      if (listed) {
-        for (int i = tid; i < ncand; i += kSelThreads) {
-          const uint32_t k = sm.cand[i];
-          if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
-        }
-      } else {                            // a bin too crowded for the list: full passes over the keys
-        for (int i = tid; i < 4 * G; i += kSelThreads) {
-          const uint32_t k = sm.keys[i];
-          if ((k & pmask) == prefix) atomicAdd(&sm.hist[(k >> shift) & (bins - 1)], 1);
-        }
-      }
-      __syncthreads();
-      n_equal = pick_bin(sm, shift, bins, prefix, pmask, want);
-    }
-  }
+  const int n_equal = refine_threshold(sm, sm.ncand, 4 * G, prefix, pmask, want);   // keys equal to the threshold
   const uint32_t T = prefix;           // `want` keys equal to T are taken, the lowest indices first
   // When every key equal to T is taken (nearly always: T is then the only one), "selected" is simply
   // "below T + 1" and nothing has to be ranked.
@@ -617,6 +629,335 @@ __device__ __forceinline__ void select_unit_long(const Unit& un, const float* __
   for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
 }
 
+// ---- selection of one unit by several workgroups ("parts") -----------------------------------------------------
+// Every part owns a contiguous range of the unit's key groups and keeps its keys in LDS.  The parts meet five times
+// through the unit's exchange area in device memory (zero at kernel start): smallest and largest key, histogram of
+// the first digit, the keys of the threshold's bin (every part then settles the threshold on the same list), the
+// parts' counts of selected keys (every part then knows how many selected edges lie before its range), and the end.
+// What crosses workgroups moves by agent-scope atomics, loads and stores, which pass the per-XCD L2 caches; a part
+// bumps a phase's counter only after its own stores have completed.  The integer sums do not depend on the order
+// in which the parts arrive, so the result is the single-workgroup one bit for bit.
+// Every wait is bounded (clock and poll count): a part that runs out of time sets the unit's abandon flag and
+// leaves; the others leave when they see it, and part 0 then selects the whole unit by itself.
+constexpr unsigned kSelMaxPolls = 1u << 16;    // second bound on a wait, should the clock ever misbehave
+
+__device__ __forceinline__ unsigned ld_agent(const unsigned* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(unsigned* p, unsigned v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned add_agent(unsigned* p, unsigned v) {
+  return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void max_agent(unsigned* p, unsigned v) {
+  (void)__hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_all_memory_ops() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);           // vmcnt(0): this lane's loads, stores and atomics have completed
+  asm volatile("" ::: "memory");
+}
+
+// This part has finished `phase`: all its threads' exchange-area writes are complete before the counter moves.
+__device__ __forceinline__ void split_arrive(unsigned* g, int phase) {
+  wait_all_memory_ops();
+  __syncthreads();
+  if (threadIdx.x == 0) (void)add_agent(&g[kSelArrive + phase], 1u);
+}
+// True once all P parts have finished `phase`; false when a part has given up or the time is over (the abandon flag
+// is then set).  The answer is the same in every thread.
+__device__ __forceinline__ bool split_wait(unsigned* g, int phase, int P, unsigned timeout_ticks, SelectSmem& sm) {
+  if (threadIdx.x == 0) {
+    int ok = 0;
+    const unsigned long long t_start = wall_clock64();
+    for (unsigned poll = 0; poll < kSelMaxPolls; ++poll) {
+      if (ld_agent(&g[kSelArrive + phase]) >= (unsigned)P) { ok = 1; break; }
+      if (ld_agent(&g[kSelAbandon]) != 0u) break;
+      if (wall_clock64() - t_start >= (unsigned long long)timeout_ticks) break;
+      __builtin_amdgcn_s_sleep(1);
+    }
+    if (!ok) st_agent(&g[kSelAbandon], 1u);
+    sm.pick[0] = ok;
+  }
+  __syncthreads();
+  const bool ok = sm.pick[0] != 0;
+  __syncthreads();
+  return ok;
+}
+
+// (-DKVS_SELECT_PROFILE: part 0 leaves the clock at the end of every phase in spare words of the exchange area)
+#ifdef KVS_SELECT_PROFILE
+#define SEL_STAMP(i) do { if (part == 0 && threadIdx.x == 0) st_agent(&g[96 + (i)], (unsigned)wall_clock64()); } while (0)
+#else
+#define SEL_STAMP(i) do { } while (0)
+#endif
+
+// Returns true when the unit's selection is complete; false when the parts could not finish together (part 0 then
+// does the whole unit alone, the other parts have nothing left to do).
+__device__ __forceinline__ bool select_unit_split(const Unit& un, const float* __restrict__ a, uint8_t* __restrict__ mk,
+                                                  int32_t* __restrict__ sl, SelectSmem& sm, unsigned* g, const int part,
+                                                  const int P, const int lo, const int hi, const int r,
+                                                  const unsigned timeout_ticks) {
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const int n = un.len;
+  const int pad0 = (int)((un.in_row + lo) & 3);
+  const int lo_al = lo - pad0;
+  const int G = (hi - lo_al + 4) / 4;              // groups of four keys of the whole unit
+  const int gpp = (G + P - 1) / P;                 // groups per part: at most kSelPartKeys / 4 (the host has seen to it)
+  const int gp0 = min(G, part * gpp), gp1 = min(G, gp0 + gpp);
+  const int GL = gp1 - gp0;                        // this part's groups; local group lg is group gp0 + lg of the unit
+  constexpr int GPT = kSelPartKeys / 4 / kSelThreads;
+  constexpr uint32_t kNone = 0xffffffffu;
+  uint4* k4 = reinterpret_cast<uint4*>(sm.keys);
+
+  SEL_STAMP(0);
+  for (int b = tid; b < kBins; b += kSelThreads) sm.hist[b] = 0;
+  if (tid == 0) sm.ncand = 0;
+
+  // ---- phase 0: raw keys of this part, their minimum and maximum
+  uint32_t k[GPT][4];
+  uint32_t kmin = kNone, kmax = 0;
+#pragma unroll
+  for (int u = 0; u < GPT; ++u) {
+    const int lg = u * kSelThreads + tid;
+    const int m0 = lo_al + 4 * (gp0 + lg);         // may lie up to 3 tokens before the unit: still alpha_bar
+    if (lg < GL && m0 >= lo && m0 + 3 <= hi) {     // hi <= n - 2: element m0 + 4 exists
+      const float4 v = *reinterpret_cast<const float4*>(a + m0);
+      const float nx = a[m0 + 4];
+      k[u][0] = __float_as_uint(v.x + v.y);
+      k[u][1] = __float_as_uint(v.y + v.z);
+      k[u][2] = __float_as_uint(v.z + v.w);
+      k[u][3] = __float_as_uint(v.w + nx);
+    } else if (lg < GL) {                          // the unit's first or last group: nothing is read past its end
+      float e[5];
+#pragma unroll
+      for (int j = 0; j < 5; ++j) e[j] = a[min(m0 + j, n - 1)];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const bool ok = (m0 + j >= lo) && (m0 + j <= hi);
+        k[u][j] = ok ? __float_as_uint(e[j] + e[j + 1]) : kNone;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) k[u][j] = kNone;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      kmin = min(kmin, k[u][j]);
+      kmax = max(kmax, k[u][j] == kNone ? 0u : k[u][j]);
+    }
+  }
+  kmin = wave_min_u32(kmin);
+  kmax = wave_max_u32(kmax);
+  if (lane == 0) { sm.wmin[wave] = kmin; sm.wmax[wave] = kmax; }
+  __syncthreads();
+  if (tid == 0) {
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) { kmin = min(kmin, sm.wmin[w]); kmax = max(kmax, sm.wmax[w]); }
+    max_agent(&g[kSelNotMin], ~kmin);              // (the area starts from zero: the minimum travels complemented)
+    max_agent(&g[kSelMax], kmax);
+  }
+  SEL_STAMP(1);
+  split_arrive(g, 0);
+  if (!split_wait(g, 0, P, timeout_ticks, sm)) return false;
+  SEL_STAMP(2);
+  kmin = ~ld_agent(&g[kSelNotMin]);
+  kmax = ld_agent(&g[kSelMax]);
+
+  // ---- phase 1: keys ranked as in the single-workgroup selection ((key - kmin) << lshift), this part's histogram
+  //      of the first digit added to the unit's
+  const uint32_t span = kmax - kmin;
+  const int lshift = span ? __clz(span) - 1 : 0;
+#pragma unroll
+  for (int u = 0; u < GPT; ++u) {
+    const int lg = u * kSelThreads + tid;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (k[u][j] != kNone) {
+        k[u][j] = (k[u][j] - kmin) << lshift;
+        atomicAdd(&sm.hist[k[u][j] >> 21], 1);
+      }
+    }
+    if (lg < GL) k4[lg] = make_uint4(k[u][0], k[u][1], k[u][2], k[u][3]);
+  }
+  __syncthreads();
+  {
+    const int h0 = sm.hist[2 * tid], h1 = sm.hist[2 * tid + 1];
+    if (h0) (void)add_agent(&g[kSelHist + 2 * tid], (unsigned)h0);
+    if (h1) (void)add_agent(&g[kSelHist + 2 * tid + 1], (unsigned)h1);
+  }
+  SEL_STAMP(3);
+  split_arrive(g, 1);
+  if (!split_wait(g, 1, P, timeout_ticks, sm)) return false;
+  SEL_STAMP(4);
+  sm.hist[2 * tid] = (int)ld_agent(&g[kSelHist + 2 * tid]);
+  sm.hist[2 * tid + 1] = (int)ld_agent(&g[kSelHist + 2 * tid + 1]);
+  __syncthreads();
+  uint32_t prefix = 0, pmask = 0;
+  int want = r;                        // rank (1-based) among the keys that share `prefix`
+  const int nb = pick_bin(sm, 21, 2048, prefix, pmask, want);
+  if (nb > kSelCandMax) return false;  // a bin too crowded for the list: every part sees that and leaves the same way
+
+  // ---- phase 2: this part's keys of that bin -> the unit's list
+  {
+    int c = 0;
+#pragma unroll
+    for (int u = 0; u < GPT; ++u) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) c += (((k[u][j] ^ prefix) >> 21) == 0);
+    }
+    const int incl = wave_incl_scan(c);
+    const int tot = __builtin_amdgcn_readlane(incl, kWave - 1);
+    if (tot > 0) {                                 // wavefront-uniform
+      int base = 0;
+      if (lane == 0) base = atomicAdd(&sm.ncand, tot);
+      int pos = __builtin_amdgcn_readfirstlane(base) + incl - c;
+#pragma unroll
+      for (int u = 0; u < GPT; ++u) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (((k[u][j] ^ prefix) >> 21) == 0) {
+            if (pos < kCand) sm.cand[pos] = k[u][j];
+            ++pos;
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const int mine = sm.ncand;                       // <= nb <= kSelCandMax
+  if (tid == 0) sm.pick[1] = mine ? (int)add_agent(&g[kSelNCand], (unsigned)mine) : 0;
+  __syncthreads();
+  const int gbase = sm.pick[1];
+  for (int i = tid; i < mine; i += kSelThreads) {
+    if (gbase + i < kSelCandMax) st_agent(&g[kSelCand + gbase + i], sm.cand[i]);
+  }
+  SEL_STAMP(5);
+  split_arrive(g, 2);
+  if (!split_wait(g, 2, P, timeout_ticks, sm)) return false;
+  SEL_STAMP(6);
+  for (int i = tid; i < nb; i += kSelThreads) sm.cand[i] = ld_agent(&g[kSelCand + i]);
+  __syncthreads();
+  const int n_equal = refine_threshold(sm, nb, 0, prefix, pmask, want);
+  const uint32_t T = prefix;           // `want` keys equal to T are taken, the lowest indices first
+  const bool simple = (n_equal == want);
+  const uint32_t Tc = simple ? T + 1 : T;
+
+  // ---- phase 3: ordered pass.  Wavefront w owns the local groups [g0, g1), lane l the groups g0 + it * 64 + l.
+  constexpr int ITS = kSelPartKeys / 4 / kSelWaves / kWave;
+  constexpr int per_g = ITS * kWave;
+  const int g0 = min(GL, wave * per_g), g1 = min(GL, g0 + per_g);
+  uint4 q[ITS];
+  int n_lt = 0, n_eq = 0;               // wavefront totals: keys below Tc, keys equal to T (if they matter)
+#pragma unroll
+  for (int it = 0; it < ITS; ++it) {
+    const int lg = g0 + it * kWave + lane;
+    q[it] = make_uint4(kNone, kNone, kNone, kNone);
+    if (lg < g1) q[it] = k4[lg];
+    n_lt += __popcll(__ballot(q[it].x < Tc)) + __popcll(__ballot(q[it].y < Tc)) + __popcll(__ballot(q[it].z < Tc)) +
+            __popcll(__ballot(q[it].w < Tc));
+    if (!simple) {
+      n_eq += __popcll(__ballot(q[it].x == T)) + __popcll(__ballot(q[it].y == T)) + __popcll(__ballot(q[it].z == T)) +
+              __popcll(__ballot(q[it].w == T));
+    }
+  }
+  if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
+  __syncthreads();
+  if (tid == 0) {
+    int tl = 0, te = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) { tl += sm.lt[w]; te += sm.eq[w]; }
+    st_agent(&g[kSelPartLt + part], (unsigned)tl);
+    st_agent(&g[kSelPartEq + part], (unsigned)te);
+  }
+  SEL_STAMP(7);
+  split_arrive(g, 3);
+  if (!split_wait(g, 3, P, timeout_ticks, sm)) return false;
+  SEL_STAMP(8);
+  if (tid < part) {
+    sm.plt[tid] = (int)ld_agent(&g[kSelPartLt + tid]);
+    sm.peq[tid] = (int)ld_agent(&g[kSelPartEq + tid]);
+  }
+  __syncthreads();
+  int eq_before = 0, sel_before = 0;    // over the parts before this one, then the wavefronts before this one
+  for (int p = 0; p < part; ++p) {
+    sel_before += sm.plt[p];
+    if (!simple) {
+      const int e = sm.peq[p];
+      sel_before += min(max(want - eq_before, 0), e);
+      eq_before += e;
+    }
+  }
+  sel_before += waves_before(sm.lt, wave, lane);
+  if (!simple) {
+    for (int w = 0; w < wave; ++w) {
+      const int e = sm.eq[w];
+      sel_before += min(max(want - eq_before, 0), e);
+      eq_before += e;
+    }
+  }
+  // Four tokens' mask bytes and slots; `below`: selected edges before the group's first token.
+  auto write_group = [&](int gg, const bool* sel, int below) {
+    const int m0 = lo_al + 4 * gg;
+    int s4[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { s4[j] = m0 + j - below; below += sel[j]; }
+    if (m0 >= lo && m0 + 3 <= hi) {
+      *reinterpret_cast<uint32_t*>(mk + m0) =
+          (uint32_t)sel[0] | ((uint32_t)sel[1] << 8) | ((uint32_t)sel[2] << 16) | ((uint32_t)sel[3] << 24);
+      *reinterpret_cast<int4*>(sl + m0) = make_int4(s4[0], s4[1], s4[2], s4[3]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (m0 + j >= lo && m0 + j <= hi) { mk[m0 + j] = sel[j] ? 1 : 0; sl[m0 + j] = s4[j]; }
+      }
+    }
+  };
+#pragma unroll
+  for (int it = 0; it < ITS; ++it) {
+    const int lg = g0 + it * kWave + lane;
+    const uint32_t kk[4] = {q[it].x, q[it].y, q[it].z, q[it].w};
+    bool sel[4];
+    if (n_eq == 0) {                               // wavefront-uniform: nothing to rank here
+#pragma unroll
+      for (int j = 0; j < 4; ++j) sel[j] = kk[j] < Tc;
+    } else {                                       // ties with the threshold: ranked in index order
+      bool eq[4];
+      int lane_eq = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        sel[j] = kk[j] < T;
+        eq[j] = kk[j] == T;
+        lane_eq += eq[j];
+      }
+      const int incl_eq = wave_incl_scan(lane_eq);
+      int rank = eq_before + incl_eq - lane_eq;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (eq[j]) { sel[j] = rank < want; ++rank; }
+      }
+      eq_before += __builtin_amdgcn_readlane(incl_eq, kWave - 1);
+    }
+    const int lane_cnt = sel[0] + sel[1] + sel[2] + sel[3];
+    const int incl = wave_incl_scan(lane_cnt);
+    if (lg < g1) write_group(gp0 + lg, sel, sel_before + incl - lane_cnt);
+    sel_before += __builtin_amdgcn_readlane(incl, kWave - 1);
+  }
+  // tokens outside the eligible edge range
+  if (part == 0) {
+    for (int t = tid; t < lo && t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t; }
+  }
+  if (part == P - 1) {
+    for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
+  }
+  SEL_STAMP(9);
+  split_arrive(g, 4);
+  // part 0 stays until every part is through: if one is not, it is part 0 that does the unit again
+  if (part == 0 && !split_wait(g, 4, P, timeout_ticks, sm)) return false;
+  SEL_STAMP(10);
+  return true;
+}
+
 __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, const float* __restrict__ alpha_bar,
                             uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, SelectSmem& sm) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
@@ -734,18 +1075,32 @@ __global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
     const UnitTable tab, const Shape sh, const int n_select, const int n_reduce, const float* __restrict__ alpha_bar,
     uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, const T* __restrict__ V,
     const int32_t* __restrict__ counts_in, float* __restrict__ o_part, const float* __restrict__ parts_in,
-    float* __restrict__ o_bar_out) {
+    float* __restrict__ o_bar_out, unsigned int* sel_shared, const unsigned timeout_ticks) {
   __shared__ SelectSmem sm;
   __shared__ float sm_o[kSelWaves][128];
   const int b = blockIdx.x;
   if (b < n_select) {
-    select_unit(tab.u[b], sh, alpha_bar, edge_mask, slot, sm);
+    const int ui = n_select == tab.n_units ? b : find_unit_by<&Unit::s_base>(tab, b);     // (one workgroup per unit: no search)
+    const Unit& un = tab.u[ui];
+    const int P = (ui + 1 < tab.n_units ? tab.u[ui + 1].s_base : tab.total_sparts) - un.s_base;
+    if (P <= 1) {
+      select_unit(un, sh, alpha_bar, edge_mask, slot, sm);
+    } else {
+      // (the host gives a unit several parts only when it has edges to select: r > 0, lo <= hi)
+      const int part = b - un.s_base;
+      const bool done = select_unit_split(un, alpha_bar + un.in_row, edge_mask + un.in_row, slot + un.in_row, sm,
+                                          sel_shared + (size_t)ui * kSelSharedInts, part, P, sh.n_sink,
+                                          un.len - 2 - sh.n_recent, un.len - un.n_out, timeout_ticks);
+      if (!done && part == 0) {
+        __syncthreads();
+        select_unit(un, sh, alpha_bar, edge_mask, slot, sm);
+      }
+    }
   } else if (b < n_select + n_reduce) {
     obar_reduce_unit(tab.u[b - n_select], sh, parts_in, o_bar_out);
   } else {
     const int c = b - n_select - n_reduce;
-    int ui = 0;
-    while (ui + 1 < tab.n_units && tab.u[ui + 1].o_base <= c) ++ui;
+    const int ui = find_unit_by<&Unit::o_base>(tab, c);
     if (sh.stream) obar_chunk<T, D, true>(tab.u[ui], c - tab.u[ui].o_base, V, counts_in, alpha_bar, o_part, sm_o);
     else obar_chunk<T, D, false>(tab.u[ui], c - tab.u[ui].o_base, V, counts_in, alpha_bar, o_part, sm_o);
   }
@@ -756,27 +1111,41 @@ __global__ void obar_reduce_kernel(const UnitTable tab, const Shape sh, const fl
   obar_reduce_unit(tab.u[blockIdx.x], sh, parts, o_bar);
 }
 
+__global__ void select_clear_kernel(unsigned int* sel_shared) {
+  uint4* z = reinterpret_cast<uint4*>(sel_shared + (size_t)blockIdx.x * kSelSharedInts);
+  for (int i = threadIdx.x; i < kSelSharedInts / 4; i += blockDim.x) z[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
 template <typename T, int D>
 hipError_t launch_t(const UnitTable& tab, const Shape& sh, bool with_select, const float* alpha_bar,
                     uint8_t* edge_mask, int32_t* slot, const void* V, const int32_t* counts_in, float* o_part,
-                    hipStream_t stream, const float* parts_in, float* o_bar_out) {
-  const int n_select = with_select ? tab.n_units : 0;
+                    hipStream_t stream, const float* parts_in, float* o_bar_out, unsigned int* sel_shared) {
+  const int n_select = with_select ? tab.total_sparts : 0;
   const int n_reduce = o_bar_out ? tab.n_units : 0;
   const int n_obar = V ? tab.total_ochunks : 0;
   if (n_select + n_reduce + n_obar == 0) return hipSuccess;
+  if (with_select && tab.total_sparts != tab.n_units && sel_shared == nullptr) return hipErrorInvalidValue;
+  // a part waits at most 200 us for the others (the clock of wall_clock64() runs at 100 MHz); KVS_DEBUG_SELECT_SPLIT = 3
+  // makes that zero, so that the parts give up at their first wait and part 0 does the unit alone (a test of that way out)
+  const unsigned timeout_ticks = debug_switch(KVS_DEBUG_SELECT_SPLIT) == 3 ? 0u : 20000u;
   hipLaunchKernelGGL((select_obar_kernel<T, D>), dim3(n_select + n_reduce + n_obar), dim3(kSelThreads), 0, stream, tab,
                      sh, n_select, n_reduce, alpha_bar, edge_mask, slot, (const T*)V, counts_in, o_part, parts_in,
-                     o_bar_out);
+                     o_bar_out, sel_shared, timeout_ticks);
   return hipGetLastError();
 }
 
 }  // namespace
 
+hipError_t launch_select_clear(const UnitTable& tab, unsigned int* sel_shared, hipStream_t stream) {
+  hipLaunchKernelGGL(select_clear_kernel, dim3(tab.n_units), dim3(256), 0, stream, sel_shared);
+  return hipGetLastError();
+}
+
 hipError_t launch_select_obar(const UnitTable& tab, const Shape& sh, kvs_dtype dt, bool with_select,
                               const float* alpha_bar, uint8_t* edge_mask, int32_t* slot, const void* V,
                               const int32_t* counts_in, float* o_part, hipStream_t stream, const float* parts_in,
-                              float* o_bar_out) {
-#define KVS_SEL_ARGS tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream, parts_in, o_bar_out
+                              float* o_bar_out, unsigned int* sel_shared) {
+#define KVS_SEL_ARGS tab, sh, with_select, alpha_bar, edge_mask, slot, V, counts_in, o_part, stream, parts_in, o_bar_out, sel_shared
   if (dt == KVS_F32) return sh.D == 64 ? launch_t<float, 64>(KVS_SEL_ARGS) : launch_t<float, 128>(KVS_SEL_ARGS);
   return sh.D == 64 ? launch_t<uint16_t, 64>(KVS_SEL_ARGS) : launch_t<uint16_t, 128>(KVS_SEL_ARGS);
 #undef KVS_SEL_ARGS
@@ -787,6 +1156,5 @@ hipError_t launch_obar_reduce(const UnitTable& tab, const Shape& sh, const float
   hipLaunchKernelGGL(obar_reduce_kernel, dim3(tab.n_units), dim3(128), 0, stream, tab, sh, parts, o_bar);
   return hipGetLastError();
 }
-
 
 }  // namespace kvs

@@ -74,6 +74,9 @@ static void whole_calls(std::mt19937& rng, kvs_dtype dt, int group, int window, 
     EXPECT(kvs_step_counts(&pr.p, Q, K, V, cin, Ko, Vo, cnt, nullptr, nullptr, ws, ws_bytes, nullptr) == KVS_OK);
     EXPECT(kvs_score(&pr.p, Q, K, V, alpha, obar, ws, ws_bytes, nullptr) == KVS_OK);
     EXPECT(kvs_select(&pr.p, alpha, mask, slot, nullptr, 0, nullptr) == KVS_OK);
+    EXPECT(kvs_select(&pr.p, alpha, mask, slot, ws, ws_bytes, nullptr) == KVS_OK);          // several workgroups per unit
+    EXPECT(kvs_select(&pr.p, alpha, mask, slot, ws, ws_bytes - 256, nullptr) == KVS_OK);    // too small: not used
+    EXPECT(kvs_select(&pr.p, alpha, (uint8_t*)ws, slot, ws, ws_bytes, nullptr) == KVS_ERR_ALIAS);
     EXPECT(kvs_merge_compact(&pr.p, K, V, alpha, obar, mask, slot, Ko, Vo, cnt, nullptr, 0, nullptr) == KVS_OK);
     EXPECT(kvs::stub_launches() >= before + 5 * ((nu + 63) / 64));
     EXPECT(kvs_step(&pr.p, Q, K, V, Ko, Vo, cnt, slot, mask, ws, ws_bytes - 1, nullptr) == KVS_ERR_WORKSPACE);
@@ -136,6 +139,11 @@ int main() {
   kvs_debug_set(KVS_DEBUG_SCORE_FUSED, 2);
   whole_calls(rng, KVS_BF16, 4, 32, 128);
   kvs_debug_set(KVS_DEBUG_SCORE_FUSED, 0);
+  kvs_debug_set(KVS_DEBUG_SELECT_SPLIT, 2);     // as many select workgroups per unit as the units can have
+  whole_calls(rng, KVS_BF16, 4, 32, 128);
+  kvs_debug_set(KVS_DEBUG_SELECT_SPLIT, 1);     // never more than one
+  whole_calls(rng, KVS_F32, 1, 8, 64);
+  kvs_debug_set(KVS_DEBUG_SELECT_SPLIT, 0);
   EXPECT(kvs_debug_set(99, 1) == -1);
   std::printf(g_failed ? "host layer: %d checks failed\n" : "host layer: all checks passed (%d stub launches)\n",
               g_failed ? g_failed : kvs::stub_launches());

@@ -25,6 +25,11 @@ static void check_table(const UnitTable& tab) {
     ochunks += obar_chunks(u.len);
   }
   if (tab.total_chunks != chunks || tab.total_mblocks != mblocks || tab.total_ochunks != ochunks) __builtin_trap();
+  for (int i = 0; i < tab.n_units; ++i) {          // select workgroups: one or several per unit, in unit order
+    const int next = i + 1 < tab.n_units ? tab.u[i + 1].s_base : tab.total_sparts;
+    const int parts = next - tab.u[i].s_base;
+    if (tab.u[i].s_base < i || parts < 1 || parts > kSelMaxParts) __builtin_trap();
+  }
 }
 
 hipError_t launch_score_finalize(const UnitTable& tab, const Shape&, const Workspace&, hipStream_t) { check_table(tab); return ok(); }
@@ -46,7 +51,16 @@ hipError_t launch_score_fused(const UnitTable& tab, const Shape&, const void*, c
   return ok();
 }
 hipError_t launch_select_obar(const UnitTable& tab, const Shape&, kvs_dtype, bool, const float*, uint8_t*, int32_t*,
-                              const void*, const int32_t*, float*, hipStream_t, const float*, float*) { check_table(tab); return ok(); }
+                              const void*, const int32_t*, float*, hipStream_t, const float*, float*, unsigned int* sel_shared) {
+  check_table(tab);
+  if (tab.total_sparts != tab.n_units && sel_shared == nullptr) __builtin_trap();
+  return ok();
+}
+hipError_t launch_select_clear(const UnitTable& tab, unsigned int* sel_shared, hipStream_t) {
+  check_table(tab);
+  if (sel_shared == nullptr) __builtin_trap();
+  return ok();
+}
 hipError_t launch_obar_reduce(const UnitTable& tab, const Shape&, const float*, float*, hipStream_t) { check_table(tab); return ok(); }
 hipError_t launch_merge(const UnitTable& tab, const Shape&, kvs_dtype, const void*, const void*, const int32_t*, const float*,
                         const float*, const float*, const uint8_t*, const int32_t*, void*, void*, int32_t*, hipStream_t) { check_table(tab); return ok(); }

@@ -181,7 +181,15 @@ def test_score_matches_oracle(base, dtype, D, G, W, lens, path):
 
 
 # ------------------------------------------------------------------------------------------------
-def run_select(alphas, budgets, n_sink, n_recent):
+# How the selection is spread over workgroups (kvs_debug.h, KVS_DEBUG_SELECT_SPLIT): "none": no workspace is handed
+# over, so every unit takes one workgroup; "auto": the library's own choice (several parts of at least 2048 keys
+# per unit when the launch leaves compute units idle); "one": one workgroup per unit; "parts": as many parts as a
+# unit can have (down to 64 keys each); "give_up": the same with a wait limit of zero, so that the parts leave at
+# their first wait and part 0 selects the unit alone.
+SPLIT_MODES = {"none": None, "auto": 0, "one": 1, "parts": 2, "give_up": 3}
+
+
+def run_select(alphas, budgets, n_sink, n_recent, split="auto"):
     import torch
     import paper_2603_00907_amd as kvs
     lens = [len(a) for a in alphas]
@@ -190,14 +198,19 @@ def run_select(alphas, budgets, n_sink, n_recent):
     flat = torch.from_numpy(np.concatenate(alphas).astype(np.float32)).cuda()
     mask = torch.full((p.rows_in + 64,), 9, dtype=torch.uint8, device="cuda")
     slot = torch.full((p.rows_in + 64,), -7, dtype=torch.int32, device="cuda")
-    kvs.kvs_select(p, flat, mask, slot, stream=torch.cuda.current_stream().cuda_stream)
-    torch.cuda.synchronize()
+    ws = None
+    if SPLIT_MODES[split] is not None:
+        # (filled with ones: the library must not rely on what a workspace holds)
+        ws = torch.full((kvs.kvs_workspace_size(p),), 0xFF, dtype=torch.uint8, device="cuda")
+    with switches(select_split=SPLIT_MODES[split] or 0):
+        kvs.kvs_select(p, flat, mask, slot, ws=ws, stream=torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
     assert (mask[p.rows_in:] == 9).all() and (slot[p.rows_in:] == -7).all()
     return p, mask.cpu().numpy(), slot.cpu().numpy()
 
 
-def check_select(alphas, budgets, n_sink, n_recent):
-    p, mask, slot = run_select(alphas, budgets, n_sink, n_recent)
+def check_select(alphas, budgets, n_sink, n_recent, split="auto"):
+    p, mask, slot = run_select(alphas, budgets, n_sink, n_recent, split)
     for i, a in enumerate(alphas):
         a32 = a.astype(np.float32)
         rm, rs = O.select(a32, budgets[i], n_sink, n_recent, sigma_dtype=np.float32)
@@ -215,7 +228,10 @@ def check_select(alphas, budgets, n_sink, n_recent):
     (50, 50, 32, 0, "dirichlet"),
     (50, 80, 32, 0, "dirichlet"), (34, 33, 32, 0, "dirichlet"), (1, 1, 32, 0, "dirichlet"),
     (20, 6, 2, 3, "zeros")])
-def test_select_bit_exact(n, budget, s, nr, kind):
+@pytest.mark.parametrize("split", list(SPLIT_MODES))
+def test_select_bit_exact(n, budget, s, nr, kind, split):
+    if n == 1 << 22 and split not in ("none", "auto"):
+        pytest.skip("the longest unit's oracle sort is run for two modes only")
     rng = np.random.default_rng(n * 7 + budget)
     if kind == "dirichlet":
         a = rng.dirichlet(np.ones(n) * 0.5)
@@ -228,10 +244,11 @@ def test_select_bit_exact(n, budget, s, nr, kind):
         a = np.full(n, 1.0 / n)
     else:
         a = np.zeros(n)
-    check_select([a], [budget], s, nr)
+    check_select([a], [budget], s, nr, split)
 
 
-def test_select_many_ragged_units():
+@pytest.mark.parametrize("split", list(SPLIT_MODES))
+def test_select_many_ragged_units(split):
     rng = np.random.default_rng(5)
     lens = [int(x) for x in rng.integers(40, 9000, size=70)]       # more than one launch group
     alphas = []
@@ -240,7 +257,27 @@ def test_select_many_ragged_units():
         alphas.append(a / a.sum())
     budgets = [max(33, n // 4) for n in lens]
     budgets[3] = lens[3] + 5                                         # pass-through unit
-    check_select(alphas, budgets, 32, 0)
+    check_select(alphas, budgets, 32, 0, split)
+
+
+@pytest.mark.parametrize("split", ["auto", "parts", "give_up"])
+def test_select_split_units_of_one_launch_side_by_side(split):
+    """Eight long units in one launch (the per-layer call's shape), each selected by several workgroups: heavy ties
+    in one, a crowded threshold bin in another (more keys in it than the parts' list holds: every part leaves and
+    part 0 selects alone), budgets from almost everything to almost nothing."""
+    rng = np.random.default_rng(11)
+    lens = [32768, 32768, 20000, 9000, 32768, 70000, 131072, 4200]
+    alphas = []
+    for i, n in enumerate(lens):
+        if i == 1:
+            a = rng.integers(1, 4, size=n).astype(np.float64)              # three distinct values: ties everywhere
+        elif i == 4:
+            a = 1.0 + 1e-7 * rng.integers(0, 3, size=n)                    # nearly constant: one bin holds most keys
+        else:
+            a = np.exp(3.0 * rng.standard_normal(n))
+        alphas.append(a / a.sum())
+    budgets = [4096, 4096, 19990, 40, 30000, 8192, 8192, 2100]
+    check_select(alphas, budgets, 32, 0, split)
 
 
 # ------------------------------------------------------------------------------------------------
