@@ -29,7 +29,8 @@ namespace {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
-constexpr int kLdsKeys = 32768;
+constexpr int kLdsKeys = 32768;           // keys a workgroup can keep in LDS: the full-size kernel ...
+constexpr int kLdsKeysSmall = kSelPartKeys;   // ... and the one for launches whose units are short or split into parts
 constexpr int kBins = 2048;
 
 __device__ __forceinline__ uint32_t edge_key(const float* __restrict__ a, int m) {
@@ -42,8 +43,10 @@ __device__ __forceinline__ int lanes_below(uint64_t ballot, int lane) {
 
 constexpr int kCand = 2048;               // keys of the first-pass bin that are refined in LDS
 
-struct SelectSmem {
-  uint32_t keys[kLdsKeys];
+template <int KEYS>
+struct SelectSmemT {
+  static constexpr int kKeys = KEYS;
+  uint32_t keys[KEYS];
   uint32_t cand[kCand];
   int hist[kBins];
   int wave[kSelWaves];
@@ -82,7 +85,8 @@ __device__ __forceinline__ int waves_before(const int* x, int wave, int lane) {
 
 // Exclusive scan of the histogram (two bins per thread); finds the bin that holds rank `want`
 // (1-based), extends (prefix, pmask, want) by that digit and returns the number of keys in the bin.
-__device__ __forceinline__ int pick_bin(SelectSmem& sm, int shift, int bins, uint32_t& prefix, uint32_t& pmask,
+template <typename SM>
+__device__ __forceinline__ int pick_bin(SM& sm, int shift, int bins, uint32_t& prefix, uint32_t& pmask,
                                         int& want) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int h0 = sm.hist[2 * tid], h1 = sm.hist[2 * tid + 1];
@@ -127,7 +131,8 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
 // it: settles the remaining 21 bits.  sm.cand[0 .. ncand) lists those keys when ncand <= kCand; otherwise the
 // passes run over sm.keys[0 .. nkeys).  Returns the number of keys equal to the threshold; prefix is then the
 // threshold and `want` the number of keys equal to it that are still wanted.
-__device__ __forceinline__ int refine_threshold(SelectSmem& sm, const int ncand, const int nkeys, uint32_t& prefix,
+template <typename SM>
+__device__ __forceinline__ int refine_threshold(SM& sm, const int ncand, const int nkeys, uint32_t& prefix,
                                                 uint32_t& pmask, int& want) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   constexpr uint32_t kNone = 0xffffffffu;
@@ -202,15 +207,16 @@ __device__ __forceinline__ int refine_threshold(SelectSmem& sm, const int ncand,
 // of tokens outside [lo, hi] are 0xffffffff: no threshold reaches them.  One CU does all of this,
 // so the instruction count per key is what matters: groups that lie wholly inside [lo, hi] (all but
 // the first and the last) take paths without per-key checks.
+template <typename SM>
 __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* __restrict__ a,
-                                                   uint8_t* __restrict__ mk, int32_t* __restrict__ sl, SelectSmem& sm,
+                                                   uint8_t* __restrict__ mk, int32_t* __restrict__ sl, SM& sm,
                                                    int lo, int hi, int r) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int n = un.len;
   const int pad0 = (int)((un.in_row + lo) & 3);
   const int lo_al = lo - pad0;
-  const int G = (hi - lo_al + 4) / 4;              // groups of four keys, at most kLdsKeys / 4
-  constexpr int GPT = kLdsKeys / 4 / kSelThreads;  // groups per thread
+  const int G = (hi - lo_al + 4) / 4;              // groups of four keys, at most SM::kKeys / 4
+  constexpr int GPT = SM::kKeys / 4 / kSelThreads; // groups per thread
   constexpr uint32_t kNone = 0xffffffffu;
   uint4* k4 = reinterpret_cast<uint4*>(sm.keys);
 
@@ -345,7 +351,7 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
   const uint32_t Tc = simple ? T + 1 : T;
 
   // ---- ordered pass: wavefront w owns the groups [g0, g1), lane l the groups g0 + it * 64 + l
-  constexpr int ITS = kLdsKeys / 4 / kSelWaves / kWave;      // rounds per wavefront
+  constexpr int ITS = SM::kKeys / 4 / kSelWaves / kWave;     // rounds per wavefront
   const int per_g = ((G + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
   const int g0 = min(G, wave * per_g), g1 = min(G, g0 + per_g);
   uint4 q[ITS];
@@ -445,8 +451,9 @@ __device__ __forceinline__ void select_unit_cached(const Unit& un, const float* 
 // Select for a unit whose keys do not fit the LDS: the passes of the radix select and the ordered pass read
 // alpha_bar again each time.  Same key layout as select_unit_cached (groups of four edges on 16-byte boundaries
 // of alpha_bar, 0xffffffff outside [lo, hi]), same ranking (stretched keys), same tie rule (lowest index first).
+template <typename SM>
 __device__ __forceinline__ void select_unit_long(const Unit& un, const float* __restrict__ a, uint8_t* __restrict__ mk,
-                                                 int32_t* __restrict__ sl, SelectSmem& sm, int lo, int hi, int r) {
+                                                 int32_t* __restrict__ sl, SM& sm, int lo, int hi, int r) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int n = un.len;
   const int pad0 = (int)((un.in_row + lo) & 3);
@@ -666,7 +673,8 @@ __device__ __forceinline__ void split_arrive(unsigned* g, int phase) {
 }
 // True once all P parts have finished `phase`; false when a part has given up or the time is over (the abandon flag
 // is then set).  The answer is the same in every thread.
-__device__ __forceinline__ bool split_wait(unsigned* g, int phase, int P, unsigned timeout_ticks, SelectSmem& sm) {
+template <typename SM>
+__device__ __forceinline__ bool split_wait(unsigned* g, int phase, int P, unsigned timeout_ticks, SM& sm) {
   if (threadIdx.x == 0) {
     int ok = 0;
     const unsigned long long t_start = wall_clock64();
@@ -694,8 +702,9 @@ __device__ __forceinline__ bool split_wait(unsigned* g, int phase, int P, unsign
 
 // Returns true when the unit's selection is complete; false when the parts could not finish together (part 0 then
 // does the whole unit alone, the other parts have nothing left to do).
+template <typename SM>
 __device__ __forceinline__ bool select_unit_split(const Unit& un, const float* __restrict__ a, uint8_t* __restrict__ mk,
-                                                  int32_t* __restrict__ sl, SelectSmem& sm, unsigned* g, const int part,
+                                                  int32_t* __restrict__ sl, SM& sm, unsigned* g, const int part,
                                                   const int P, const int lo, const int hi, const int r,
                                                   const unsigned timeout_ticks) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
@@ -958,8 +967,9 @@ __device__ __forceinline__ bool select_unit_split(const Unit& un, const float* _
   return true;
 }
 
+template <typename SM>
 __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, const float* __restrict__ alpha_bar,
-                            uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, SelectSmem& sm) {
+                            uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, SM& sm) {
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
   const int n = un.len;
   const int r = n - un.n_out;
@@ -974,7 +984,7 @@ __device__ __forceinline__ void select_unit(const Unit& un, const Shape& sh, con
     for (int t = tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t; }
     return;
   }
-  if (E + 6 <= kLdsKeys) {             // with the padding to aligned groups of four at both ends
+  if (E + 6 <= SM::kKeys) {            // with the padding to aligned groups of four at both ends
     select_unit_cached(un, a, mk, sl, sm, lo, hi, r);
     return;
   }
@@ -1070,13 +1080,15 @@ __device__ __forceinline__ void obar_reduce_unit(const Unit& un, const Shape& sh
 
 // Three kinds of workgroups: blocks [0, n_select) select one unit's edges each, blocks [n_select, n_select +
 // n_reduce) add one unit's partial o_bar sums up each, the others stream one chunk of V each.
-template <typename T, int D>
+// KEYS: edge scores a select workgroup can keep in LDS.  The small size leaves room for three workgroups per CU,
+// which matters to the workgroups of the other kinds in the same launch.
+template <typename T, int D, int KEYS>
 __global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
     const UnitTable tab, const Shape sh, const int n_select, const int n_reduce, const float* __restrict__ alpha_bar,
     uint8_t* __restrict__ edge_mask, int32_t* __restrict__ slot, const T* __restrict__ V,
     const int32_t* __restrict__ counts_in, float* __restrict__ o_part, const float* __restrict__ parts_in,
     float* __restrict__ o_bar_out, unsigned int* sel_shared, const unsigned timeout_ticks) {
-  __shared__ SelectSmem sm;
+  __shared__ SelectSmemT<KEYS> sm;
   __shared__ float sm_o[kSelWaves][128];
   const int b = blockIdx.x;
   if (b < n_select) {
@@ -1128,9 +1140,25 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, bool with_select, con
   // a part waits at most 200 us for the others (the clock of wall_clock64() runs at 100 MHz); KVS_DEBUG_SELECT_SPLIT = 3
   // makes that zero, so that the parts give up at their first wait and part 0 does the unit alone (a test of that way out)
   const unsigned timeout_ticks = debug_switch(KVS_DEBUG_SELECT_SPLIT) == 3 ? 0u : 20000u;
-  hipLaunchKernelGGL((select_obar_kernel<T, D>), dim3(n_select + n_reduce + n_obar), dim3(kSelThreads), 0, stream, tab,
-                     sh, n_select, n_reduce, alpha_bar, edge_mask, slot, (const T*)V, counts_in, o_part, parts_in,
-                     o_bar_out, sel_shared, timeout_ticks);
+  // the small-LDS kernel when no unit needs more keys in one workgroup's LDS than it holds (a unit split into parts
+  // does not; if its parts give up, its first part selects it from alpha_bar, pass by pass)
+  bool small = true;
+  for (int i = 0; with_select && i < tab.n_units; ++i) {
+    const Unit& un = tab.u[i];
+    const int parts = (i + 1 < tab.n_units ? tab.u[i + 1].s_base : tab.total_sparts) - un.s_base;
+    const int E = (un.len - 2 - sh.n_recent) - sh.n_sink + 1;
+    if (parts == 1 && un.len > un.n_out && E + 6 > kLdsKeysSmall) small = false;
+  }
+  const dim3 grid(n_select + n_reduce + n_obar), block(kSelThreads);
+  if (small) {
+    hipLaunchKernelGGL((select_obar_kernel<T, D, kLdsKeysSmall>), grid, block, 0, stream, tab, sh, n_select, n_reduce,
+                       alpha_bar, edge_mask, slot, (const T*)V, counts_in, o_part, parts_in, o_bar_out, sel_shared,
+                       timeout_ticks);
+  } else {
+    hipLaunchKernelGGL((select_obar_kernel<T, D, kLdsKeys>), grid, block, 0, stream, tab, sh, n_select, n_reduce,
+                       alpha_bar, edge_mask, slot, (const T*)V, counts_in, o_part, parts_in, o_bar_out, sel_shared,
+                       timeout_ticks);
+  }
   return hipGetLastError();
 }
 
