@@ -7,8 +7,9 @@ One *step* is one pass of the whole hot path (score -> select -> merge_compact) 
 the workload, inputs resident in HBM.  A (layer, sequence, KV head) cache is one independent unit of
 the library, so the layers are simply more units of the same kvs_step call (--layers-per-call, all of
 them by default; the library launches its kernels over at most 64 units at a time).
-Prints ONE JSON line: whole-job merged KV tokens/s, the roofline of the dominant phase (timed live
-with events on the launch stream) and the fp64 oracle's rate on the host cores of this machine.
+Prints ONE JSON line: whole-job merged KV tokens/s, the roofline of the whole step (with the phases' and the
+dominant kernel's own figures as flat fields beside it, timed live with events on the launch stream) and the
+fp64 oracle's rate on the host cores of this machine.
 """
 
 from __future__ import annotations
