@@ -355,6 +355,9 @@ int select_parts(const Unit& un, const Shape& sh, int n_units, int n_cus, int mo
   // A launch of many units keeps the chip busy with one workgroup per unit, and on a chip shared with another
   // stream's kernels its parts would wait for each other's turn (64 units at 4 parts each: 67.0 us per layer of the
   // two-stream headline run against 65.6): the parts are for launches that leave most compute units idle.
+  // (Splitting only the units that are too long for one workgroup's key cache was measured on the ragged batch,
+  // 64 units of 4 K to 64 K tokens per launch: the launch of selection and pass over V took 117 us against 108,
+  // because the selection is hidden beside that pass anyway and the parts take compute units from it.)
   if (mode == 0 && n_cus / n_units < 8) return 1;
   const int most = mode >= 2 ? kSelMaxParts : (n_cus / n_units < kSelMaxParts ? n_cus / n_units : kSelMaxParts);
   const int min_keys = mode >= 2 ? 64 : kSelMinPartKeys;
@@ -388,11 +391,15 @@ hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, con
   // (8 units: 38 against 45 us).  KVS_DEBUG_FUSE_OBAR forces one or the other.
   if (!force_valu && score_mfma_supported(tab, sh, dt)) {
     const int fuse = debug_switch(KVS_DEBUG_FUSE_OBAR);
-    // (The selection of a unit too long for the select kernel's LDS cache of keys takes several times longer,
-    // 74 us at 65536 tokens: such launches keep it hidden beside the pass over V.)
+    // (The selection of a unit too long for the select kernel's LDS cache of keys takes several times longer when one
+    // workgroup does it, 51 us at 65536 tokens: such launches keep it hidden beside the pass over V, unless the
+    // unit's selection is spread over several workgroups.)
     int longest = 0;
-    for (int i = 0; i < tab.n_units; ++i) longest = std::max(longest, tab.u[i].len);
-    bool want = sh.stream != 0 && longest <= 32768;
+    for (int i = 0; i < tab.n_units; ++i) {
+      const int parts = (i + 1 < tab.n_units ? tab.u[i + 1].s_base : tab.total_sparts) - tab.u[i].s_base;
+      if (parts <= 1) longest = std::max(longest, tab.u[i].len);
+    }
+    bool want = sh.stream != 0 && longest <= kSelUnitKeys;
     if (fuse == 1) want = false;
     if (fuse == 2) want = true;
     const bool with_v = wants_o && score_mfma_takes_values(sh, dt) && want;

@@ -71,6 +71,7 @@ __host__ __device__ inline int obar_chunks(int len) {
 //   [kSelAbandon] set by a part that gave up waiting, [kSelArrive + phase] parts that finished a phase,
 //   [kSelPartLt + part], [kSelPartEq + part] keys below / equal to the threshold in a part,
 //   [kSelHist + bin] histogram of the first digit, [kSelCand + i] keys of the threshold's bin.
+constexpr int kSelUnitKeys = 32768;       // keys that ONE workgroup can keep in LDS (the full-size select kernel)
 constexpr int kSelMaxParts = 32;
 constexpr int kSelPartKeys = 8192;
 constexpr int kSelMinPartKeys = 2048;     // parts are not made smaller than this unless a test asks for it

@@ -29,7 +29,7 @@ namespace {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
-constexpr int kLdsKeys = 32768;           // keys a workgroup can keep in LDS: the full-size kernel ...
+constexpr int kLdsKeys = kSelUnitKeys;    // keys a workgroup can keep in LDS: the full-size kernel ...
 constexpr int kLdsKeysSmall = kSelPartKeys;   // ... and the one for launches whose units are short or split into parts
 constexpr int kBins = 2048;
 

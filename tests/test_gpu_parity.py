@@ -261,6 +261,24 @@ def test_select_many_ragged_units(split):
 
 
 @pytest.mark.parametrize("split", ["auto", "parts", "give_up"])
+def test_select_long_units_in_a_launch_of_many(split):
+    """Forty units in one launch, a quarter of them too long for one workgroup's key cache (more than 32768 tokens),
+    with and without parts (forced: more select workgroups than the chip holds at once, so late parts find their
+    unit given up or wait for their turn)."""
+    rng = np.random.default_rng(23)
+    lens = [int(x) for x in rng.integers(3000, 9000, size=30)] + [40000, 65536, 33000, 70001, 50000, 32769 + 40,
+                                                                  61000, 36000, 45000, 131072]
+    order = rng.permutation(len(lens))
+    lens = [lens[i] for i in order]
+    alphas = []
+    for n in lens:
+        a = np.exp(3.0 * rng.standard_normal(n))
+        alphas.append(a / a.sum())
+    budgets = [max(40, n // 5) for n in lens]
+    check_select(alphas, budgets, 32, 0, split)
+
+
+@pytest.mark.parametrize("split", ["auto", "parts", "give_up"])
 def test_select_split_units_of_one_launch_side_by_side(split):
     """Eight long units in one launch (the per-layer call's shape), each selected by several workgroups: heavy ties
     in one, a crowded threshold bin in another (more keys in it than the parts' list holds: every part leaves and
