@@ -43,7 +43,8 @@ struct SwitchInit {
     g_switch[KVS_DEBUG_SCORE_CHUNK] = c ? std::max(0, std::atoi(c)) : 0;
     g_switch[KVS_DEBUG_VERBOSE] = std::getenv("KVS_VERBOSE") != nullptr;
     g_switch[KVS_DEBUG_SCORE_FUSED] = env_choice("KVS_SCORE_FUSED", nullptr, "1");
-    g_switch[KVS_DEBUG_SELECT_SPLIT] = env_choice("KVS_SELECT_SPLIT", "0", "1");
+    const char* sp = std::getenv("KVS_SELECT_SPLIT");
+    g_switch[KVS_DEBUG_SELECT_SPLIT] = sp ? std::min(3, std::max(0, std::atoi(sp))) : 0;
     const char* t = std::getenv("KVS_FUSED_WAIT_US");
     g_switch[KVS_DEBUG_FUSED_WAIT_US] = t ? std::max(0, std::atoi(t)) + 1 : 0;
     const char* g = std::getenv("KVS_FUSED_STAGGER");
