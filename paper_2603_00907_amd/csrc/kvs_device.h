@@ -68,18 +68,22 @@ __host__ __device__ inline int obar_chunks(int len) {
 // the parts of a unit exchange goes through kSelSharedInts unsigned ints of device memory per unit of the launch,
 // which must be zero when the select kernel starts (the score finalize kernel of the same call clears them):
 //   [kSelNotMin] ~(smallest key), [kSelMax] largest key, [kSelNCand] candidates listed so far,
-//   [kSelAbandon] set by a part that gave up waiting, [kSelArrive + phase] parts that finished a phase,
-//   [kSelPartLt + part], [kSelPartEq + part] keys below / equal to the threshold in a part,
-//   [kSelHist + bin] histogram of the first digit, [kSelCand + i] keys of the threshold's bin.
+//   [kSelArrive + phase] parts that finished a phase (bit kSelGaveUp: a part ran out of time there),
+//   [kSelPartLow + part] keys of a part in the bins below the threshold's,
+//   [kSelHist + bin] histogram of the first digit, [kSelCand + i] keys of the threshold's bin and
+//   [kSelCandPart + i] the parts they came from.
 constexpr int kSelUnitKeys = 32768;       // keys that ONE workgroup can keep in LDS (the full-size select kernel)
 constexpr int kSelMaxParts = 32;
 constexpr int kSelPartKeys = 8192;
 constexpr int kSelMinPartKeys = 2048;     // parts are not made smaller than this unless a test asks for it
-constexpr int kSelNotMin = 0, kSelMax = 1, kSelNCand = 2, kSelAbandon = 3, kSelArrive = 4;
-constexpr int kSelPartLt = 16, kSelPartEq = kSelPartLt + kSelMaxParts;
-constexpr int kSelHist = 128, kSelHistBins = 2048;
+constexpr int kSelNotMin = 0, kSelMax = 1, kSelNCand = 2, kSelArrive = 4, kSelPhases = 3;
+constexpr unsigned int kSelGaveUp = 1u << 16;
+constexpr int kSelPartLow = 16;
+constexpr int kSelHist = 64, kSelHistBins = 2048;
 constexpr int kSelCand = kSelHist + kSelHistBins, kSelCandMax = 2048;
-constexpr int kSelSharedInts = kSelCand + kSelCandMax;
+constexpr int kSelCandPart = kSelCand + kSelCandMax;
+constexpr int kSelSharedInts = kSelCandPart + kSelCandMax;
+static_assert(kSelPartLow + kSelMaxParts <= kSelHist && kSelSharedInts % 4 == 0, "layout of the exchange area");
 
 struct UnitTable {
   int n_units;

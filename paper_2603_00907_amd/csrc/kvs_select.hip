@@ -54,7 +54,8 @@ struct SelectSmemT {
   int lt[kSelWaves], eq[kSelWaves];
   uint32_t wmin[kSelWaves], wmax[kSelWaves];
   int ncand;
-  int plt[kSelMaxParts], peq[kSelMaxParts];     // split selection: the other parts' counts
+  int plt[kSelMaxParts], peq[kSelMaxParts];     // split selection: the parts' counts of selected keys
+  uint8_t cpart[kCand];                         // ... and the part every listed key came from
 };
 
 // Inclusive prefix sum over the 64 lanes with DPP moves only (no LDS crossbar): four shifts inside
@@ -637,15 +638,18 @@ __device__ __forceinline__ void select_unit_long(const Unit& un, const float* __
 }
 
 // ---- selection of one unit by several workgroups ("parts") -----------------------------------------------------
-// Every part owns a contiguous range of the unit's key groups and keeps its keys in LDS.  The parts meet five times
-// through the unit's exchange area in device memory (zero at kernel start): smallest and largest key, histogram of
-// the first digit, the keys of the threshold's bin (every part then settles the threshold on the same list), the
-// parts' counts of selected keys (every part then knows how many selected edges lie before its range), and the end.
-// What crosses workgroups moves by agent-scope atomics, loads and stores, which pass the per-XCD L2 caches; a part
-// bumps a phase's counter only after its own stores have completed.  The integer sums do not depend on the order
-// in which the parts arrive, so the result is the single-workgroup one bit for bit.
-// Every wait is bounded (clock and poll count): a part that runs out of time sets the unit's abandon flag and
-// leaves; the others leave when they see it, and part 0 then selects the whole unit by itself.
+// Every part owns a contiguous range of the unit's key groups and keeps its keys in LDS.  The parts meet three times
+// through the unit's exchange area in device memory (zero at kernel start): smallest and largest key; histogram of
+// the first digit; the keys of the threshold's bin, each with the part it came from, and every part's number of
+// keys in the bins below.  From that list every part settles the same threshold and knows how many selected edges
+// lie before its range, so nothing more has to be exchanged.  What crosses workgroups moves by agent-scope atomics,
+// loads and stores, which pass the per-XCD L2 caches; a part bumps a phase's counter only after its own stores have
+// completed.  The integer sums do not depend on the order in which the parts arrive, so the result is the
+// single-workgroup one bit for bit.
+// Every wait is bounded (clock and poll count).  A phase either completes for all parts or fails for all of them:
+// its counter completes when it reads exactly P, and a part that runs out of time marks the counter with a
+// compare-and-swap that only succeeds while the count is still short; after that it can never read exactly P again.
+// When a phase fails every part leaves and the unit's first part selects the whole unit by itself.
 constexpr unsigned kSelMaxPolls = 1u << 16;    // second bound on a wait, should the clock ever misbehave
 
 __device__ __forceinline__ unsigned ld_agent(const unsigned* p) {
@@ -656,6 +660,10 @@ __device__ __forceinline__ void st_agent(unsigned* p, unsigned v) {
 }
 __device__ __forceinline__ unsigned add_agent(unsigned* p, unsigned v) {
   return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool cas_agent(unsigned* p, unsigned expected, unsigned desired) {
+  return __hip_atomic_compare_exchange_strong(p, &expected, desired, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void max_agent(unsigned* p, unsigned v) {
   (void)__hip_atomic_fetch_max(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -671,20 +679,27 @@ __device__ __forceinline__ void split_arrive(unsigned* g, int phase) {
   __syncthreads();
   if (threadIdx.x == 0) (void)add_agent(&g[kSelArrive + phase], 1u);
 }
-// True once all P parts have finished `phase`; false when a part has given up or the time is over (the abandon flag
-// is then set).  The answer is the same in every thread.
+// True once all P parts have finished `phase`; false when a part has run out of time there.  The answer is the same
+// in every thread, and the same in every part.
 template <typename SM>
 __device__ __forceinline__ bool split_wait(unsigned* g, int phase, int P, unsigned timeout_ticks, SM& sm) {
   if (threadIdx.x == 0) {
+    unsigned* word = &g[kSelArrive + phase];
     int ok = 0;
     const unsigned long long t_start = wall_clock64();
     for (unsigned poll = 0; poll < kSelMaxPolls; ++poll) {
-      if (ld_agent(&g[kSelArrive + phase]) >= (unsigned)P) { ok = 1; break; }
-      if (ld_agent(&g[kSelAbandon]) != 0u) break;
-      if (wall_clock64() - t_start >= (unsigned long long)timeout_ticks) break;
+      const unsigned v = ld_agent(word);
+      if (v == (unsigned)P) { ok = 1; break; }
+      if (v & kSelGaveUp) break;
+      if (poll + 1 == kSelMaxPolls || wall_clock64() - t_start >= (unsigned long long)timeout_ticks) {
+        // out of time: give up, unless the count has completed in the meantime (then the swap fails and the
+        // next look at the counter sees it complete)
+        if (cas_agent(word, v, v | kSelGaveUp)) break;
+        if (poll + 1 == kSelMaxPolls) poll -= 1;     // (the value has changed at most P + 1 times: this ends)
+        continue;
+      }
       __builtin_amdgcn_s_sleep(1);
     }
-    if (!ok) st_agent(&g[kSelAbandon], 1u);
     sm.pick[0] = ok;
   }
   __syncthreads();
@@ -695,7 +710,7 @@ __device__ __forceinline__ bool split_wait(unsigned* g, int phase, int P, unsign
 
 // (-DKVS_SELECT_PROFILE: part 0 leaves the clock at the end of every phase in spare words of the exchange area)
 #ifdef KVS_SELECT_PROFILE
-#define SEL_STAMP(i) do { if (part == 0 && threadIdx.x == 0) st_agent(&g[96 + (i)], (unsigned)wall_clock64()); } while (0)
+#define SEL_STAMP(i) do { if (part == 0 && threadIdx.x == 0) st_agent(&g[48 + (i)], (unsigned)wall_clock64()); } while (0)
 #else
 #define SEL_STAMP(i) do { } while (0)
 #endif
@@ -807,16 +822,23 @@ __device__ __forceinline__ bool select_unit_split(const Unit& un, const float* _
   const int nb = pick_bin(sm, 21, 2048, prefix, pmask, want);
   if (nb > kSelCandMax) return false;  // a bin too crowded for the list: every part sees that and leaves the same way
 
-  // ---- phase 2: this part's keys of that bin -> the unit's list
+  // ---- phase 2: this part's keys of that bin -> the unit's list, each with the number of this part; and how many
+  //      of this part's keys lie in the bins below
+  const uint32_t bstar = prefix >> 21;
   {
-    int c = 0;
+    int c = 0, low = 0;
 #pragma unroll
     for (int u = 0; u < GPT; ++u) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) c += (((k[u][j] ^ prefix) >> 21) == 0);
+      for (int j = 0; j < 4; ++j) {
+        c += (((k[u][j] ^ prefix) >> 21) == 0);
+        low += ((k[u][j] >> 21) < bstar);          // (a position outside the eligible range has the top digit)
+      }
     }
     const int incl = wave_incl_scan(c);
     const int tot = __builtin_amdgcn_readlane(incl, kWave - 1);
+    const int low_w = __builtin_amdgcn_readlane(wave_incl_scan(low), kWave - 1);
+    if (lane == 0) sm.lt[wave] = low_w;
     if (tot > 0) {                                 // wavefront-uniform
       int base = 0;
       if (lane == 0) base = atomicAdd(&sm.ncand, tot);
@@ -835,24 +857,48 @@ __device__ __forceinline__ bool select_unit_split(const Unit& un, const float* _
   }
   __syncthreads();
   const int mine = sm.ncand;                       // <= nb <= kSelCandMax
-  if (tid == 0) sm.pick[1] = mine ? (int)add_agent(&g[kSelNCand], (unsigned)mine) : 0;
+  if (tid == 0) {
+    int low = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) low += sm.lt[w];
+    st_agent(&g[kSelPartLow + part], (unsigned)low);
+    sm.pick[1] = mine ? (int)add_agent(&g[kSelNCand], (unsigned)mine) : 0;
+  }
   __syncthreads();
   const int gbase = sm.pick[1];
   for (int i = tid; i < mine; i += kSelThreads) {
-    if (gbase + i < kSelCandMax) st_agent(&g[kSelCand + gbase + i], sm.cand[i]);
+    if (gbase + i < kSelCandMax) {
+      st_agent(&g[kSelCand + gbase + i], sm.cand[i]);
+      st_agent(&g[kSelCandPart + gbase + i], (unsigned)part);
+    }
   }
   SEL_STAMP(5);
   split_arrive(g, 2);
   if (!split_wait(g, 2, P, timeout_ticks, sm)) return false;
   SEL_STAMP(6);
-  for (int i = tid; i < nb; i += kSelThreads) sm.cand[i] = ld_agent(&g[kSelCand + i]);
+  for (int i = tid; i < nb; i += kSelThreads) {
+    sm.cand[i] = ld_agent(&g[kSelCand + i]);
+    sm.cpart[i] = (uint8_t)ld_agent(&g[kSelCandPart + i]);
+  }
+  if (tid < kSelMaxParts) {                        // the parts' keys below the threshold's bin
+    sm.plt[tid] = tid < P ? (int)ld_agent(&g[kSelPartLow + tid]) : 0;
+    sm.peq[tid] = 0;
+  }
   __syncthreads();
   const int n_equal = refine_threshold(sm, nb, 0, prefix, pmask, want);
   const uint32_t T = prefix;           // `want` keys equal to T are taken, the lowest indices first
   const bool simple = (n_equal == want);
   const uint32_t Tc = simple ? T + 1 : T;
+  // every part's keys of the threshold's bin that lie below Tc, and those equal to T when they have to be ranked
+  for (int i = tid; i < nb; i += kSelThreads) {
+    const uint32_t ck = sm.cand[i];
+    const int cp = sm.cpart[i];
+    if (ck < Tc) atomicAdd(&sm.plt[cp], 1);
+    else if (!simple && ck == T) atomicAdd(&sm.peq[cp], 1);
+  }
+  // (the barrier after the wavefront counts below also covers these sums)
 
-  // ---- phase 3: ordered pass.  Wavefront w owns the local groups [g0, g1), lane l the groups g0 + it * 64 + l.
+  // ---- ordered pass.  Wavefront w owns the local groups [g0, g1), lane l the groups g0 + it * 64 + l.
   constexpr int ITS = kSelPartKeys / 4 / kSelWaves / kWave;
   constexpr int per_g = ITS * kWave;
   const int g0 = min(GL, wave * per_g), g1 = min(GL, g0 + per_g);
@@ -872,22 +918,7 @@ __device__ __forceinline__ bool select_unit_split(const Unit& un, const float* _
   }
   if (lane == 0) { sm.lt[wave] = n_lt; sm.eq[wave] = n_eq; }
   __syncthreads();
-  if (tid == 0) {
-    int tl = 0, te = 0;
-#pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) { tl += sm.lt[w]; te += sm.eq[w]; }
-    st_agent(&g[kSelPartLt + part], (unsigned)tl);
-    st_agent(&g[kSelPartEq + part], (unsigned)te);
-  }
   SEL_STAMP(7);
-  split_arrive(g, 3);
-  if (!split_wait(g, 3, P, timeout_ticks, sm)) return false;
-  SEL_STAMP(8);
-  if (tid < part) {
-    sm.plt[tid] = (int)ld_agent(&g[kSelPartLt + tid]);
-    sm.peq[tid] = (int)ld_agent(&g[kSelPartEq + tid]);
-  }
-  __syncthreads();
   int eq_before = 0, sel_before = 0;    // over the parts before this one, then the wavefronts before this one
   for (int p = 0; p < part; ++p) {
     sel_before += sm.plt[p];
@@ -959,11 +990,7 @@ __device__ __forceinline__ bool select_unit_split(const Unit& un, const float* _
   if (part == P - 1) {
     for (int t = hi + 1 + tid; t < n; t += kSelThreads) { mk[t] = 0; sl[t] = t - r; }
   }
-  SEL_STAMP(9);
-  split_arrive(g, 4);
-  // part 0 stays until every part is through: if one is not, it is part 0 that does the unit again
-  if (part == 0 && !split_wait(g, 4, P, timeout_ticks, sm)) return false;
-  SEL_STAMP(10);
+  SEL_STAMP(8);
   return true;
 }
 

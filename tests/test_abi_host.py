@@ -54,9 +54,9 @@ def test_workspace_size_grows_with_the_problem():
     big = kvs.kvs_workspace_size(problem(lens=[100000, 500]))
     assert small % 256 == 0 and big > small
     # pieces: chunk statistics, row normalisers, chunk o_bar, alpha_bar, o_bar, edge mask, slot map, and the
-    # exchange area of the selection by several workgroups (4224 ints per unit of a launch)
+    # exchange area of the selection by several workgroups (6208 ints per unit of a launch)
     rows, nu, R, D = 1524, 2, 8, 64
-    lower = nu * 64 * R * 8 + nu * R * 4 + nu * 64 * D * 4 + rows * 4 + nu * D * 4 + rows + rows * 4 + nu * 4224 * 4
+    lower = nu * 64 * R * 8 + nu * R * 4 + nu * 64 * D * 4 + rows * 4 + nu * D * 4 + rows + rows * 4 + nu * 6208 * 4
     assert lower <= small <= lower + 8 * 256
 
 

@@ -6,9 +6,11 @@ workgroup at random, lets workgroups start late (not resident yet) and lets wait
 the protocol, not the arithmetic: that every wait ends, that nothing is consumed before it was produced, that
 work is done exactly once, and that the result does not depend on the interleaving.
 
-  * the selection of one unit by several workgroups (kvs_select.hip, select_unit_split): five rendezvous through
-    an exchange area, bounded waits, an abandon flag, the unit's first part selecting alone when the parts cannot
-    finish together or the threshold's bin is too crowded for the list;
+  * the selection of one unit by several workgroups (kvs_select.hip, select_unit_split): three rendezvous through
+    an exchange area, bounded waits, a phase that either completes for every part or fails for every part (a part
+    that runs out of time marks the phase counter with a compare-and-swap that only succeeds while the count is
+    short), the unit's first part selecting alone when a phase fails or the threshold's bin is too crowded for the
+    list;
   * the one-pass score kernel (kvs_score_fused.hip): work items handed out by a ticket counter in unit order, the
     workgroup that publishes a unit's last statistics reduces them to the normalisers, the others wait (bounded) for
     them, and items given up on go to a list that a second launch finishes.
@@ -43,17 +45,19 @@ def run_interleaved(workgroups, rng, resident, max_steps=2_000_000):
 
 
 # ------------------------------------------------------------------------------------------------ split selection
+GAVE_UP = 1 << 16
+
+
 class Exchange:
     def __init__(self, bins, cand_max):
         self.notmin = 0                 # the area starts from zero: the minimum travels complemented
         self.max = 0
         self.ncand = 0
-        self.abandon = 0
-        self.arrive = [0] * 5
+        self.arrive = [0] * 3
         self.hist = [0] * bins
         self.cand = [None] * cand_max
-        self.part_lt = {}
-        self.part_eq = {}
+        self.cand_part = [None] * cand_max
+        self.part_low = {}
 
 
 MASK32 = 0xFFFFFFFF
@@ -79,19 +83,23 @@ def select_part(part, P, keys, r, g, out, log, timeout, bins, cand_max):
         yield
 
     def wait(phase):
-        for _ in range(timeout + 1):
-            if g.arrive[phase] >= P:
+        waited = 0
+        while True:
+            v = g.arrive[phase]
+            yield                                       # (others move between the load and what follows)
+            if v == P:
                 return True
-            if g.abandon:
-                break
-            yield
-        else:
-            pass
-        g.abandon = 1
-        return False
+            if v & GAVE_UP:
+                return False
+            if waited >= timeout:
+                if g.arrive[phase] == v:                # compare-and-swap: only while the count is still what was read
+                    g.arrive[phase] = v | GAVE_UP
+                    return False
+                continue
+            waited += 1
 
-    def give_up():
-        log["gave_up"] += 1
+    def give_up(phase):
+        log["gave_up"].append((part, phase))
         if part == 0:                                  # the unit's first part selects alone
             log["fallback"] += 1
             sel = single_workgroup_select(keys, r)
@@ -108,7 +116,7 @@ def select_part(part, P, keys, r, g, out, log, timeout, bins, cand_max):
         yield
     yield from arrive(0)
     if not (yield from wait(0)):
-        yield from give_up()
+        yield from give_up(0)
         return
     kmin, kmax = (~g.notmin) & MASK32, g.max
     span = max(kmax - kmin, 1)
@@ -119,7 +127,7 @@ def select_part(part, P, keys, r, g, out, log, timeout, bins, cand_max):
     yield
     yield from arrive(1)
     if not (yield from wait(1)):
-        yield from give_up()
+        yield from give_up(1)
         return
     hist = list(g.hist)
     assert sum(hist) == n, "a histogram was read before every part had added to it"
@@ -130,45 +138,42 @@ def select_part(part, P, keys, r, g, out, log, timeout, bins, cand_max):
     want = r - below
     if hist[b] > cand_max:                              # every part sees the same histogram and leaves the same way
         log["crowded"] += 1
-        yield from give_up()
+        yield from give_up(-1)
         return
-    # phase 2: the keys of that bin
+    # phase 2: the keys of that bin with this part's number, and this part's keys in the bins below
     cands = [int(k) for k in mine if digit(k) == b]
+    g.part_low[part] = sum(1 for k in mine if digit(k) < b)
+    yield
     base = g.ncand
     g.ncand += len(cands)
     yield
     for i, k in enumerate(cands):
         g.cand[base + i] = k
+        g.cand_part[base + i] = part
         if i % 3 == 0:
             yield
     yield from arrive(2)
     if not (yield from wait(2)):
-        yield from give_up()
+        yield from give_up(2)
         return
     lst = g.cand[:hist[b]]
-    assert None not in lst, "the list was read before every part had written its keys"
-    lst = sorted(lst)
-    T = lst[want - 1]
-    n_equal = lst.count(T)
-    want_eq = want - sum(1 for k in lst if k < T)
+    tags = g.cand_part[:hist[b]]
+    assert None not in lst and None not in tags, "the list was read before every part had written its keys"
+    srt = sorted(lst)
+    T = srt[want - 1]
+    n_equal = srt.count(T)
+    want_eq = want - sum(1 for k in srt if k < T)
     simple = n_equal == want_eq
-    # phase 3: counts of this part
-    in_bin_or_below = lambda k: digit(k) < b or (digit(k) == b and int(k) < T)
-    lt = sum(1 for k in mine if in_bin_or_below(k) or (simple and int(k) == T))
-    eq = 0 if simple else sum(1 for k in mine if int(k) == T)
-    g.part_lt[part], g.part_eq[part] = lt, eq
-    yield
-    yield from arrive(3)
-    if not (yield from wait(3)):
-        yield from give_up()
-        return
+    # what lies before this part: from the list and the parts' counts alone, nothing more is exchanged
     eq_before = 0
     for p in range(part):
-        assert p in g.part_lt, "a part's count was read before it was written"
-        eq_before += g.part_eq[p]
+        assert p in g.part_low, "a part's count was read before it was written"
+        if not simple:
+            eq_before += sum(1 for k, tg in zip(lst, tags) if tg == p and k == T)
+    selected = lambda k: digit(k) < b or (digit(k) == b and (int(k) < T or (simple and int(k) == T)))
     for t in range(lo, hi):
         k = int(keys[t])
-        if in_bin_or_below(k) or (simple and k == T):
+        if selected(k):
             s = True
         elif k == T:
             s = eq_before < want_eq
@@ -178,10 +183,6 @@ def select_part(part, P, keys, r, g, out, log, timeout, bins, cand_max):
         out[t].append(s)
         if t % 5 == 0:
             yield
-    yield from arrive(4)
-    if part == 0 and not (yield from wait(4)):
-        yield from give_up()
-        return
     log["finished"] += 1
 
 
@@ -203,19 +204,21 @@ def test_split_selection_protocol(seed):
     resident = rng.choice([1, 2, P, P])                # fewer slots than parts: late parts find the unit given up
     g = Exchange(bins=16, cand_max=64)
     out = [[] for _ in range(n)]
-    log = {"gave_up": 0, "fallback": 0, "finished": 0, "crowded": 0}
+    log = {"gave_up": [], "fallback": 0, "finished": 0, "crowded": 0}
     parts = [select_part(p, P, keys, r, g, out, log, timeout, 16, 64) for p in range(P)]
     run_interleaved(parts, rng, resident)
     ref = single_workgroup_select(keys, r)
     for t in range(n):
         assert out[t], f"token {t} was never written"
         assert all(v == bool(ref[t]) for v in out[t]), f"token {t}: a writer disagrees with the single-workgroup result"
-    if log["gave_up"] == 0:
+    if not log["gave_up"]:
         assert log["finished"] == P and log["fallback"] == 0
     else:
-        assert log["fallback"] == 1, "exactly the unit's first part selects alone"
+        # a phase fails for every part or for none: all parts left, at the same phase, and nobody wrote but part 0
+        assert len(log["gave_up"]) == P and len({ph for _, ph in log["gave_up"]}) == 1
+        assert log["fallback"] == 1 and log["finished"] == 0
     if timeout == 10_000 and resident >= P and not log["crowded"]:
-        assert log["gave_up"] == 0, "with every part resident and time to spare nobody gives up"
+        assert not log["gave_up"], "with every part resident and time to spare nobody gives up"
 
 
 def test_split_selection_matches_the_oracle_selection():
