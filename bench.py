@@ -43,6 +43,8 @@ def parse():
                     help="deal the kvs_step calls of a step round-robin to this many streams (default 2: the layers go "
                          "to two calls on two streams, whose kernels fill each other's idle resources)")
     ap.add_argument("--no-per-layer-calls", action="store_true", help="skip the one-call-per-layer comparison loop")
+    ap.add_argument("--io-dtype", default=None, choices=["bf16", "f32"],
+                    help="run the workload's recipe with this I/O dtype instead of its own (fp32: the fp32 kernels at size)")
     ap.add_argument("--key-rule", default="hessian", choices=["hessian", "diagonal", "mean"],
                     help="rule for the merged Key (the ablations run the same kernels)")
     ap.add_argument("--decode", action="store_true",
@@ -99,6 +101,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     w = WORKLOADS[args.workload]
+    if args.io_dtype and args.io_dtype != w.dtype:
+        w = w.scaled(dtype=args.io_dtype)
     layers = args.layers or w.layers
     lens_seq = unit_lengths(w)
     lens = [lens_seq[s] for s in range(w.n_seq) for _ in range(w.n_kv_heads)]       # the units of one layer
