@@ -190,18 +190,20 @@ def token_and_edge_norms(alpha_bar: np.ndarray, V: np.ndarray, o_bar: np.ndarray
 
 
 def per_query_norms(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: Optional[float] = None,
-                    causal_window: int = 0):
+                    causal_window: int = 0, counts: Optional[np.ndarray] = None):
     """A_t and C_t with every query row kept apart: row q has its own attention alpha^{(q)} (Eq. attn_def_vec)
     and its own output o^{(q)}; the vectors of Eqs. c11_def-c12_def are formed per row and their norms are
-    averaged over the rows.  Q [R, D] (or [G, W, D]), K, V [n, D]; returns A [n], C [n - 1]."""
-    V = np.asarray(V, dtype=F64)
-    alpha = attention_rows(Q, K, scale, causal_window=causal_window)
+    averaged over the rows.  Q [R, D] (or [G, W, D]), K, V [n, D]; returns A [n], C [n - 1].
+    With `counts` the rows of K and V are slots of an already merged cache (streaming regime): every query row
+    sees a slot as one token with logit e + ln c and value V / c, as everywhere else in this module."""
+    alpha = attention_rows(Q, K, scale, counts, causal_window)
+    values = slot_values(V, counts)
     R, n = alpha.shape
     A = np.zeros(n, dtype=F64)
     C = np.zeros(max(n - 1, 0), dtype=F64)
     for q in range(R):
-        o_q = alpha[q] @ V                                  # this row's attention output
-        A_q, C_q = token_and_edge_norms(alpha[q], V, o_q)
+        o_q = alpha[q] @ values                             # this row's attention output
+        A_q, C_q = token_and_edge_norms(alpha[q], V, o_q, counts)
         A += A_q
         C += C_q
     return A / R, C / R
@@ -225,7 +227,8 @@ def merge_compact(K: np.ndarray, V: np.ndarray, alpha_bar: np.ndarray, o_bar: np
                   mask: np.ndarray, slot: np.ndarray, counts_in: Optional[np.ndarray] = None,
                   rule: str = "hessian", norms=None) -> MergeResult:
     """`norms = (A, C)` replaces the norms computed from alpha_bar and o_bar (per-query aggregation);
-    alpha_bar and o_bar are then not used."""
+    alpha_bar and o_bar are then not used.  With `counts_in` the rows are slots of a merged cache: cardinalities
+    add up, Values stay sums, the fallback is the mean over the tokens the rows stand for."""
     assert rule in RULES
     K = np.asarray(K, dtype=F64)
     V = np.asarray(V, dtype=F64)
@@ -233,8 +236,7 @@ def merge_compact(K: np.ndarray, V: np.ndarray, alpha_bar: np.ndarray, o_bar: np
     c_in = np.ones(n, dtype=np.int64) if counts_in is None else np.asarray(counts_in, dtype=np.int64)
     if norms is None:
         A, C = token_and_edge_norms(alpha_bar, V, o_bar, counts_in)
-    else:
-        assert counts_in is None
+    else:                                                   # (cardinalities then only enter the sums below)
         A, C = (np.asarray(x, dtype=F64) for x in norms)
     n_out = int(slot[-1]) + 1 if n else 0
     K_out = np.zeros((n_out, D), dtype=F64)
@@ -304,7 +306,7 @@ def step(Q: np.ndarray, K: np.ndarray, V: np.ndarray, budget: int, n_sink: int =
          rule: str = "hessian", per_query: bool = False, causal_window: int = 0) -> StepResult:
     alpha_bar, o_bar = score(Q, K, V, scale, counts, causal_window)
     mask, slot = select(alpha_bar, budget, n_sink, n_recent)
-    norms = per_query_norms(Q, K, V, scale, causal_window) if per_query else None
+    norms = per_query_norms(Q, K, V, scale, causal_window, counts) if per_query else None
     merged = merge_compact(K, V, alpha_bar, o_bar, mask, slot, counts, rule, norms)
     return StepResult(alpha_bar, o_bar, mask, slot, merged)
 

@@ -646,6 +646,49 @@ def test_per_query_norms_special_cases():
     assert np.max(np.abs(A1 - A0) / A0) > 1e-3
 
 
+def test_per_query_norms_with_counts():
+    """Streaming regime, every query row apart.  Each row by itself is the single-query case with slots of
+    cardinality c: the blocks d s_t / d e_j of s_t = alpha_t (V_t / c_t - o) at logits e + ln c, by central
+    differences of textbook attention; cardinalities of one change nothing; one row is the averaged rule; and a
+    row's output is textbook attention over the cache the slots stand for."""
+    rng = np.random.default_rng(64)
+    n, d, dv, R = 6, 4, 5, 3
+    Q = rng.standard_normal((R, d)) * 1.5
+    K = rng.standard_normal((n, d)) * 1.5
+    V = rng.standard_normal((n, dv)) * 2.0
+    c = np.array([2, 1, 3, 1, 4, 2])
+    Vs = V / c[:, None]
+    A_want, C_want = np.zeros(n), np.zeros(n - 1)
+    h = 1e-5
+    for q in Q:
+        e0 = K @ q / np.sqrt(d) + np.log(c)
+        J = np.zeros((n, n, dv))
+        for j in range(n):
+            ep, em = e0.copy(), e0.copy()
+            ep[j] += h
+            em[j] -= h
+            J[:, j, :] = (s_of_logits(ep, Vs) - s_of_logits(em, Vs)) / (2 * h)
+        A_want += [np.linalg.norm(J[i, i]) for i in range(n)]
+        C_want += [np.linalg.norm(J[i, i + 1]) for i in range(n - 1)]
+    A, C = O.per_query_norms(Q, K, V, counts=c)
+    np.testing.assert_allclose(A, A_want / R, rtol=1e-7)
+    np.testing.assert_allclose(C, C_want / R, rtol=1e-7)
+    # cardinalities of one: bit for bit the plain call
+    A1, C1 = O.per_query_norms(Q, K, V, counts=np.ones(n, dtype=np.int32))
+    A0, C0 = O.per_query_norms(Q, K, V)
+    assert np.array_equal(A1, A0) and np.array_equal(C1, C0)
+    # one row: the averaged rule with cardinalities
+    ab, ob = O.score(Q[:1], K, V, counts=c)
+    Aa, Ca = O.token_and_edge_norms(ab, V, ob, counts=c)
+    Ar, Cr = O.per_query_norms(Q[:1], K, V, counts=c)
+    np.testing.assert_allclose(Ar, Aa, rtol=1e-13)
+    np.testing.assert_allclose(Cr, Ca, rtol=1e-13)
+    # the step with both switches uses these norms
+    st = O.step(Q, K, V, budget=4, n_sink=1, counts=c, per_query=True)
+    ref = O.merge_compact(K, V, st.alpha_bar, st.o_bar, st.mask, st.slot, counts_in=c, norms=(A, C))
+    assert np.array_equal(st.merged.K_out, ref.K_out) and np.array_equal(st.merged.counts, ref.counts)
+
+
 @pytest.mark.parametrize("seed,L", [(62, 2), (63, 3)])
 def test_per_query_merged_key_minimises_the_summed_surrogate(seed, L):
     """With norms=(A, C) the merged Key of a run minimises, along q-independent weights, the surrogate
