@@ -217,8 +217,10 @@ kvs_status kvs_decode_attention(const kvs_problem* p, const void* Q, const void*
  * kvs_select on alpha_bar.  With one query row the results are those of the calls above.
  * Restrictions: with io_dtype KVS_BF16 every unit has at least 32 rows (KVS_ERR_INVALID_ARG; the matrix-core
  * kernels work on whole tiles), with KVS_F32 any length is taken (vector-ALU kernels, written for the small
- * configurations, not for speed); plain tokens only (no input cardinalities).  kvs_merge_compact_norms takes
- * both dtypes and any length.
+ * configurations, not for speed).  kvs_merge_compact_norms takes both dtypes and any length.
+ * The *_counts forms take the input rows' cardinalities (streaming regime, as kvs_step_counts; NULL = the plain
+ * call): every query row then sees row t as one token with logit e + ln counts_in[t] and value
+ * V[t] / counts_in[t], and the merge adds the cardinalities up.
  *   alpha_bar DEVICE out [rows] fp32, as from kvs_score
  *   a_tok     DEVICE out / in [rows] fp32: A_t
  *   c_edge    DEVICE out / in [rows] fp32: C_t; the entry of a unit's last row is 0 and never read
@@ -239,6 +241,18 @@ kvs_status kvs_step_per_query(const kvs_problem* p, const void* Q, const void* K
                               void* K_out, void* V_out, int32_t* counts_out,
                               int32_t* slot_of_token_out, uint8_t* edge_mask_out,
                               void* ws, size_t ws_bytes, void* hip_stream);
+kvs_status kvs_sensitivity_counts(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                                  const int32_t* counts_in, float* alpha_bar, float* a_tok, float* c_edge,
+                                  void* ws, size_t ws_bytes, void* hip_stream);
+kvs_status kvs_merge_compact_norms_counts(const kvs_problem* p, const void* K, const void* V,
+                                          const int32_t* counts_in, const float* a_tok, const float* c_edge,
+                                          const uint8_t* edge_mask, const int32_t* slot_of_token,
+                                          void* K_out, void* V_out, int32_t* counts_out,
+                                          void* ws, size_t ws_bytes, void* hip_stream);
+kvs_status kvs_step_per_query_counts(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                                     const int32_t* counts_in, void* K_out, void* V_out, int32_t* counts_out,
+                                     int32_t* slot_of_token_out, uint8_t* edge_mask_out,
+                                     void* ws, size_t ws_bytes, void* hip_stream);
 
 const char* kvs_status_str(kvs_status s);
 int kvs_version(void);

@@ -24,14 +24,17 @@ from .binding import (  # noqa: F401
     kvs_merge_compact,
     kvs_merge_compact_counts,
     kvs_merge_compact_norms,
+    kvs_merge_compact_norms_counts,
     kvs_per_query_workspace_size,
     kvs_score,
     kvs_score_counts,
     kvs_select,
     kvs_sensitivity,
+    kvs_sensitivity_counts,
     kvs_step,
     kvs_step_counts,
     kvs_step_per_query,
+    kvs_step_per_query_counts,
     kvs_step_static,
     kvs_debug_set,
     kvs_debug_get,

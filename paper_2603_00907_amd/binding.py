@@ -23,7 +23,9 @@ DTYPES = {"f32": KVS_F32, "bf16": KVS_BF16}
 EXPORTS = ["kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step",
            "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_decode_workspace_size",
            "kvs_decode_attention", "kvs_per_query_workspace_size", "kvs_sensitivity", "kvs_merge_compact_norms",
-           "kvs_step_per_query", "kvs_step_static", "kvs_status_str", "kvs_version", "kvs_debug_set", "kvs_debug_get"]
+           "kvs_step_per_query", "kvs_sensitivity_counts", "kvs_merge_compact_norms_counts",
+           "kvs_step_per_query_counts", "kvs_step_static", "kvs_status_str", "kvs_version", "kvs_debug_set",
+           "kvs_debug_get"]
 
 STATIC_SCRATCH_BYTES = 16 << 20
 # testing switches of include/kvs_debug.h
@@ -85,13 +87,18 @@ def load_library(path: Optional[str] = None):
     lib.kvs_sensitivity.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_merge_compact_norms.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_step_per_query.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_sensitivity_counts.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_merge_compact_norms_counts.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.kvs_step_per_query_counts.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.kvs_step_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.kvs_debug_set.argtypes = [C.c_int, C.c_int]
     lib.kvs_debug_get.argtypes = [C.c_int]
     for name in ("kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact", "kvs_step",
                  "kvs_score_counts", "kvs_merge_compact_counts", "kvs_step_counts", "kvs_decode_workspace_size",
                  "kvs_decode_attention", "kvs_per_query_workspace_size", "kvs_sensitivity",
-                 "kvs_merge_compact_norms", "kvs_step_per_query", "kvs_step_static", "kvs_debug_set", "kvs_debug_get"):
+                 "kvs_merge_compact_norms", "kvs_step_per_query", "kvs_sensitivity_counts",
+                 "kvs_merge_compact_norms_counts", "kvs_step_per_query_counts", "kvs_step_static", "kvs_debug_set",
+                 "kvs_debug_get"):
         getattr(lib, name).restype = C.c_int
     lib.kvs_status_str.argtypes = [C.c_int]
     lib.kvs_status_str.restype = C.c_char_p
@@ -248,12 +255,36 @@ def kvs_sensitivity(problem: Problem, Q, K, V, alpha_bar, a_tok, c_edge, ws, str
         _nbytes(ws) if ws_bytes is None else ws_bytes, stream), "kvs_sensitivity")
 
 
+def kvs_sensitivity_counts(problem: Problem, Q, K, V, counts_in, alpha_bar, a_tok, c_edge, ws, stream: int = 0,
+                           ws_bytes: Optional[int] = None):
+    _check(load_library().kvs_sensitivity_counts(
+        problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(counts_in), _ptr(alpha_bar), _ptr(a_tok), _ptr(c_edge), _ptr(ws),
+        _nbytes(ws) if ws_bytes is None else ws_bytes, stream), "kvs_sensitivity_counts")
+
+
 def kvs_merge_compact_norms(problem: Problem, K, V, a_tok, c_edge, edge_mask, slot_of_token, K_out, V_out,
                             counts_out, ws=None, stream: int = 0):
     _check(load_library().kvs_merge_compact_norms(
         problem.ref, _ptr(K), _ptr(V), _ptr(a_tok), _ptr(c_edge), _ptr(edge_mask), _ptr(slot_of_token),
         _ptr(K_out), _ptr(V_out), _ptr(counts_out), _ptr(ws), _nbytes(ws) if ws is not None else 0, stream),
         "kvs_merge_compact_norms")
+
+
+def kvs_merge_compact_norms_counts(problem: Problem, K, V, counts_in, a_tok, c_edge, edge_mask, slot_of_token, K_out,
+                                   V_out, counts_out, ws=None, stream: int = 0):
+    _check(load_library().kvs_merge_compact_norms_counts(
+        problem.ref, _ptr(K), _ptr(V), _ptr(counts_in), _ptr(a_tok), _ptr(c_edge), _ptr(edge_mask),
+        _ptr(slot_of_token), _ptr(K_out), _ptr(V_out), _ptr(counts_out), _ptr(ws),
+        _nbytes(ws) if ws is not None else 0, stream), "kvs_merge_compact_norms_counts")
+
+
+def kvs_step_per_query_counts(problem: Problem, Q, K, V, counts_in, K_out, V_out, counts_out, ws,
+                              slot_of_token_out=None, edge_mask_out=None, stream: int = 0,
+                              ws_bytes: Optional[int] = None):
+    _check(load_library().kvs_step_per_query_counts(
+        problem.ref, _ptr(Q), _ptr(K), _ptr(V), _ptr(counts_in), _ptr(K_out), _ptr(V_out), _ptr(counts_out),
+        _ptr(slot_of_token_out), _ptr(edge_mask_out), _ptr(ws), _nbytes(ws) if ws_bytes is None else ws_bytes,
+        stream), "kvs_step_per_query_counts")
 
 
 def kvs_step_per_query(problem: Problem, Q, K, V, K_out, V_out, counts_out, ws, slot_of_token_out=None,

@@ -245,11 +245,11 @@ kvs_status check_per_query(const Plan& plan) {
 }
 
 hipError_t per_query_norms(const Plan& plan, const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                           const void* V, const Workspace& w, const PerQueryWs& q, float* a_tok, float* c_edge,
-                           hipStream_t s) {
+                           const void* V, const int32_t* counts_in, const Workspace& w, const PerQueryWs& q,
+                           float* a_tok, float* c_edge, hipStream_t s) {
   if (plan.dtype == KVS_F32)
-    return launch_per_query_norms_f32(tab, sh, Q, K, V, w.c_row, q.o_part, q.o_f32, a_tok, c_edge, s);
-  return launch_per_query_norms(tab, sh, Q, K, V, w.c_row, q.o_part, q.o_hi, q.o_lo, q.oo, a_tok, c_edge, s);
+    return launch_per_query_norms_f32(tab, sh, Q, K, V, counts_in, w.c_row, q.o_part, q.o_f32, a_tok, c_edge, s);
+  return launch_per_query_norms(tab, sh, Q, K, V, counts_in, w.c_row, q.o_part, q.o_hi, q.o_lo, q.oo, a_tok, c_edge, s);
 }
 
 struct Range {
@@ -666,6 +666,12 @@ kvs_status kvs_per_query_workspace_size(const kvs_problem* p, size_t* bytes) {
 
 kvs_status kvs_sensitivity(const kvs_problem* p, const void* Q, const void* K, const void* V, float* alpha_bar,
                            float* a_tok, float* c_edge, void* ws, size_t ws_bytes, void* hip_stream) {
+  return kvs_sensitivity_counts(p, Q, K, V, nullptr, alpha_bar, a_tok, c_edge, ws, ws_bytes, hip_stream);
+}
+
+kvs_status kvs_sensitivity_counts(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                                  const int32_t* counts_in, float* alpha_bar, float* a_tok, float* c_edge, void* ws,
+                                  size_t ws_bytes, void* hip_stream) {
   Plan plan;
   kvs_status st = make_plan(p, &plan);
   if (st != KVS_OK) return st;
@@ -676,19 +682,20 @@ kvs_status kvs_sensitivity(const kvs_problem* p, const void* Q, const void* K, c
   if (ws_bytes < q.bytes) return KVS_ERR_WORKSPACE;
   const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
   const size_t rows4 = (size_t)plan.rows_in * 4;
-  st = check_ranges({{Q, (size_t)plan.n_units * plan.shape.R * plan.shape.D * plan.elt, false},
-                     {K, kv, false},
-                     {V, kv, false},
-                     {alpha_bar, rows4, true},
-                     {a_tok, rows4, true},
-                     {c_edge, rows4, true},
-                     {ws, q.bytes, true}});
-  if (st != KVS_OK) return st;
+  std::vector<Range> rs = {{Q, (size_t)plan.n_units * plan.shape.R * plan.shape.D * plan.elt, false},
+                           {K, kv, false},
+                           {V, kv, false},
+                           {alpha_bar, rows4, true},
+                           {a_tok, rows4, true},
+                           {c_edge, rows4, true},
+                           {ws, q.bytes, true}};
+  if (counts_in) rs.push_back({counts_in, rows4, false});
+  if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
-    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, nullptr, alpha_bar, w, s);
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, alpha_bar, w, s);
     if (e != hipSuccess) return e;
-    return per_query_norms(plan, tab, sh, Q, K, V, w, q, a_tok, c_edge, s);
+    return per_query_norms(plan, tab, sh, Q, K, V, counts_in, w, q, a_tok, c_edge, s);
   });
 }
 
@@ -696,6 +703,14 @@ kvs_status kvs_merge_compact_norms(const kvs_problem* p, const void* K, const vo
                                    const float* c_edge, const uint8_t* edge_mask, const int32_t* slot_of_token,
                                    void* K_out, void* V_out, int32_t* counts_out, void* ws, size_t ws_bytes,
                                    void* hip_stream) {
+  return kvs_merge_compact_norms_counts(p, K, V, nullptr, a_tok, c_edge, edge_mask, slot_of_token, K_out, V_out,
+                                        counts_out, ws, ws_bytes, hip_stream);
+}
+
+kvs_status kvs_merge_compact_norms_counts(const kvs_problem* p, const void* K, const void* V, const int32_t* counts_in,
+                                          const float* a_tok, const float* c_edge, const uint8_t* edge_mask,
+                                          const int32_t* slot_of_token, void* K_out, void* V_out, int32_t* counts_out,
+                                          void* ws, size_t ws_bytes, void* hip_stream) {
   (void)ws;
   (void)ws_bytes;
   Plan plan;
@@ -703,26 +718,35 @@ kvs_status kvs_merge_compact_norms(const kvs_problem* p, const void* K, const vo
   if (st != KVS_OK) return st;
   const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
   const size_t kvo = (size_t)plan.rows_out * plan.shape.D * plan.elt;
-  st = check_ranges({{K, kv, false},
-                     {V, kv, false},
-                     {a_tok, (size_t)plan.rows_in * 4, false},
-                     {c_edge, (size_t)plan.rows_in * 4, false},
-                     {edge_mask, (size_t)plan.rows_in, false},
-                     {slot_of_token, (size_t)plan.rows_in * 4, false},
-                     {K_out, kvo, true},
-                     {V_out, kvo, true},
-                     {counts_out, (size_t)plan.rows_out * 4, true}});
-  if (st != KVS_OK) return st;
+  std::vector<Range> rs = {{K, kv, false},
+                           {V, kv, false},
+                           {a_tok, (size_t)plan.rows_in * 4, false},
+                           {c_edge, (size_t)plan.rows_in * 4, false},
+                           {edge_mask, (size_t)plan.rows_in, false},
+                           {slot_of_token, (size_t)plan.rows_in * 4, false},
+                           {K_out, kvo, true},
+                           {V_out, kvo, true},
+                           {counts_out, (size_t)plan.rows_out * 4, true}};
+  if (counts_in) rs.push_back({counts_in, (size_t)plan.rows_in * 4, false});
+  if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
-    return launch_merge_norms(tab, sh, plan.dtype, K, V, a_tok, c_edge, edge_mask, slot_of_token, K_out, V_out,
-                              counts_out, s);
+    return launch_merge_norms(tab, sh, plan.dtype, K, V, counts_in, a_tok, c_edge, edge_mask, slot_of_token, K_out,
+                              V_out, counts_out, s);
   });
 }
 
 kvs_status kvs_step_per_query(const kvs_problem* p, const void* Q, const void* K, const void* V, void* K_out,
                               void* V_out, int32_t* counts_out, int32_t* slot_of_token_out, uint8_t* edge_mask_out,
                               void* ws, size_t ws_bytes, void* hip_stream) {
+  return kvs_step_per_query_counts(p, Q, K, V, nullptr, K_out, V_out, counts_out, slot_of_token_out, edge_mask_out, ws,
+                                   ws_bytes, hip_stream);
+}
+
+kvs_status kvs_step_per_query_counts(const kvs_problem* p, const void* Q, const void* K, const void* V,
+                                     const int32_t* counts_in, void* K_out, void* V_out, int32_t* counts_out,
+                                     int32_t* slot_of_token_out, uint8_t* edge_mask_out, void* ws, size_t ws_bytes,
+                                     void* hip_stream) {
   Plan plan;
   kvs_status st = make_plan(p, &plan);
   if (st != KVS_OK) return st;
@@ -742,19 +766,21 @@ kvs_status kvs_step_per_query(const kvs_problem* p, const void* Q, const void* K
                            {ws, q.bytes, true}};
   if (slot_of_token_out) rs.push_back({slot_of_token_out, (size_t)plan.rows_in * 4, true});
   if (edge_mask_out) rs.push_back({edge_mask_out, (size_t)plan.rows_in, true});
+  if (counts_in) rs.push_back({counts_in, (size_t)plan.rows_in * 4, false});
   if ((st = check_ranges(rs)) != KVS_OK) return st;
   uint8_t* mask = edge_mask_out ? edge_mask_out : w.edge_mask;
   int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
   hipStream_t s = (hipStream_t)hip_stream;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
-    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, nullptr, w.alpha_bar, w, s);
+    hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, w.alpha_bar, w, s);
     if (e != hipSuccess) return e;
     e = launch_select_obar(tab, sh, plan.dtype, true, w.alpha_bar, mask, slot, nullptr, nullptr, nullptr, s, nullptr,
                            nullptr, w.sel_shared);
     if (e != hipSuccess) return e;
-    e = per_query_norms(plan, tab, sh, Q, K, V, w, q, q.a_tok, q.c_edge, s);
+    e = per_query_norms(plan, tab, sh, Q, K, V, counts_in, w, q, q.a_tok, q.c_edge, s);
     if (e != hipSuccess) return e;
-    return launch_merge_norms(tab, sh, plan.dtype, K, V, q.a_tok, q.c_edge, mask, slot, K_out, V_out, counts_out, s);
+    return launch_merge_norms(tab, sh, plan.dtype, K, V, counts_in, q.a_tok, q.c_edge, mask, slot, K_out, V_out,
+                              counts_out, s);
   }, /*split_select=*/true);
 }
 

@@ -276,18 +276,19 @@ hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, con
 
 // The same pass with A_t and C_t read from arrays instead of formed from alpha_bar and o_bar (per-query aggregation).
 hipError_t launch_merge_norms(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* K, const void* V,
-                              const float* a_tok, const float* c_edge, const uint8_t* edge_mask, const int32_t* slot,
-                              void* K_out, void* V_out, int32_t* counts, hipStream_t stream);
+                              const int32_t* counts_in, const float* a_tok, const float* c_edge,
+                              const uint8_t* edge_mask, const int32_t* slot, void* K_out, void* V_out, int32_t* counts,
+                              hipStream_t stream);
 // Per-query aggregation (bf16, every unit at least 32 rows): a_tok, c_edge from Q, K, V and the rows' normalisers
 // c_row that the score sweeps leave.  o_part: [chunks of the launch][R][D] fp32; o_hi, o_lo: [n_units][R][D] bf16;
 // oo: [n_units][R].
 hipError_t launch_per_query_norms(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
-                                  const float* c_row, float* o_part, uint16_t* o_hi, uint16_t* o_lo, float* oo,
-                                  float* a_tok, float* c_edge, hipStream_t stream);
+                                  const int32_t* counts_in, const float* c_row, float* o_part, uint16_t* o_hi,
+                                  uint16_t* o_lo, float* oo, float* a_tok, float* c_edge, hipStream_t stream);
 // The same for fp32 inputs (any unit length, vector ALU).  o: [n_units][R][D] fp32.
 hipError_t launch_per_query_norms_f32(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                                      const void* V, const float* c_row, float* o_part, float* o, float* a_tok,
-                                      float* c_edge, hipStream_t stream);
+                                      const void* V, const int32_t* counts_in, const float* c_row, float* o_part,
+                                      float* o, float* a_tok, float* c_edge, hipStream_t stream);
 
 // Decode attention over a (merged) cache: chunk partials into `part`, then out[n_units, R, D].
 hipError_t launch_decode(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* Q, const void* K,

@@ -474,24 +474,27 @@ hipError_t launch_merge(const UnitTable& tab, const Shape& sh, kvs_dtype dt, con
 
 template <typename T, int D>
 static hipError_t launch_merge_norms_t(const UnitTable& tab, const Shape& sh, const void* K, const void* V,
-                                       const float* a_tok, const float* c_edge, const uint8_t* edge_mask,
-                                       const int32_t* slot, void* K_out, void* V_out, int32_t* counts,
-                                       hipStream_t stream) {
-  return sh.stream ? launch_merge_k<T, D, true, false, true>(tab, sh, K, V, nullptr, a_tok, nullptr, nullptr, edge_mask,
-                                                             slot, K_out, V_out, counts, stream, c_edge)
-                   : launch_merge_k<T, D, false, false, true>(tab, sh, K, V, nullptr, a_tok, nullptr, nullptr,
-                                                              edge_mask, slot, K_out, V_out, counts, stream, c_edge);
+                                       const int32_t* counts_in, const float* a_tok, const float* c_edge,
+                                       const uint8_t* edge_mask, const int32_t* slot, void* K_out, void* V_out,
+                                       int32_t* counts, hipStream_t stream) {
+#define KVS_MN_ARGS tab, sh, K, V, counts_in, a_tok, nullptr, nullptr, edge_mask, slot, K_out, V_out, counts, stream, c_edge
+  if (counts_in) {
+    return sh.stream ? launch_merge_k<T, D, true, true, true>(KVS_MN_ARGS) : launch_merge_k<T, D, false, true, true>(KVS_MN_ARGS);
+  }
+  return sh.stream ? launch_merge_k<T, D, true, false, true>(KVS_MN_ARGS) : launch_merge_k<T, D, false, false, true>(KVS_MN_ARGS);
+#undef KVS_MN_ARGS
 }
 
 hipError_t launch_merge_norms(const UnitTable& tab, const Shape& sh, kvs_dtype dt, const void* K, const void* V,
-                              const float* a_tok, const float* c_edge, const uint8_t* edge_mask, const int32_t* slot,
-                              void* K_out, void* V_out, int32_t* counts, hipStream_t stream) {
+                              const int32_t* counts_in, const float* a_tok, const float* c_edge,
+                              const uint8_t* edge_mask, const int32_t* slot, void* K_out, void* V_out, int32_t* counts,
+                              hipStream_t stream) {
+#define KVS_MN_ARGS tab, sh, K, V, counts_in, a_tok, c_edge, edge_mask, slot, K_out, V_out, counts, stream
   if (dt == KVS_F32) {
-    return sh.D == 64 ? launch_merge_norms_t<float, 64>(tab, sh, K, V, a_tok, c_edge, edge_mask, slot, K_out, V_out, counts, stream)
-                      : launch_merge_norms_t<float, 128>(tab, sh, K, V, a_tok, c_edge, edge_mask, slot, K_out, V_out, counts, stream);
+    return sh.D == 64 ? launch_merge_norms_t<float, 64>(KVS_MN_ARGS) : launch_merge_norms_t<float, 128>(KVS_MN_ARGS);
   }
-  return sh.D == 64 ? launch_merge_norms_t<uint16_t, 64>(tab, sh, K, V, a_tok, c_edge, edge_mask, slot, K_out, V_out, counts, stream)
-                    : launch_merge_norms_t<uint16_t, 128>(tab, sh, K, V, a_tok, c_edge, edge_mask, slot, K_out, V_out, counts, stream);
+  return sh.D == 64 ? launch_merge_norms_t<uint16_t, 64>(KVS_MN_ARGS) : launch_merge_norms_t<uint16_t, 128>(KVS_MN_ARGS);
+#undef KVS_MN_ARGS
 }
 
 }  // namespace kvs

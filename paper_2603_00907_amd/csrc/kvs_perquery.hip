@@ -24,6 +24,10 @@
 //                         ||v_t + v_{t+1} - 2o||^2 = ||v_t + v_{t+1}||^2 + 2 (X'_t + X'_{t+1}),
 //                         two square roots, and the sums over q.  Tiles overlap by one row (stride 31), so
 //                         the next token of every output row is in the same tile.
+// COUNTS: the rows are slots of an already merged cache (Sec. 3.1, streaming regime), row t standing for c_t tokens
+// whose Values add up to V[t]: every query row sees it as one token with logit e + ln c_t and value V[t] / c_t.  The
+// products still run on the stored rows; log2 c_t joins the logit, and 1 / c_t scales the attention weight of the
+// Value sum (o), the product V_t . o and the squared norms afterwards.
 // A workgroup has four wavefronts; wavefront w owns query rows 32w .. 32w+31 of a pass of 128 rows and
 // keeps their operands in registers; all four walk the same K and V tiles, staged through LDS (XOR-swizzled
 // 16-byte pieces, as in the score kernels).  Results do not depend on timing: no atomics, fixed orders.
@@ -114,15 +118,17 @@ __device__ __forceinline__ bf16x8 row_operand(const uint16_t* __restrict__ m, in
 #ifndef KVS_PQ_OUT_OCC
 #define KVS_PQ_OUT_OCC 2
 #endif
-template <int D>
+template <int D, bool COUNTS>
 __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
-    const uint16_t* __restrict__ V, const float* __restrict__ c_row, float* __restrict__ o_part) {
+    const uint16_t* __restrict__ V, const int32_t* __restrict__ counts_in, const float* __restrict__ c_row,
+    float* __restrict__ o_part) {
   typedef Tile<D> TL;
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;                // 32-wide blocks of the value dimension
   __shared__ __attribute__((aligned(16))) unsigned char sm_k[2][TL::BYTES];
   __shared__ __attribute__((aligned(16))) unsigned char sm_v[2][TL::BYTES];
+  __shared__ __attribute__((aligned(16))) float sm_lc[2][kTile], sm_ic[2][kTile];   // COUNTS: log2 c and 1 / c of the tile's rows
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -137,6 +143,7 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
   const unsigned char* Kg = reinterpret_cast<const unsigned char*>(K + (size_t)un.in_row * D);
   const unsigned char* Vg = reinterpret_cast<const unsigned char*>(V + (size_t)un.in_row * D);
   const uint16_t* Qu = Q + (size_t)un.index * R * D;
+  const int32_t* cnt = COUNTS ? counts_in + un.in_row : nullptr;
 
   // identity operand: element i of k-step kk is 1 where 16 kk + 8 half + i is this lane's column
   bf16x8 ident[2];
@@ -174,6 +181,11 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
       const int buf = j & 1;
       TL::store(sm_k[buf], rk, tid);
       TL::store(sm_v[buf], rv, tid);
+      if (COUNTS && tid < kTile) {
+        const float c = (float)cnt[tile_base(j) + tid];
+        sm_lc[buf][tid] = __builtin_amdgcn_logf(c);          // (base 2)
+        sm_ic[buf][tid] = __builtin_amdgcn_rcpf(c);
+      }
       __syncthreads();
       const int shift = t0 + j * kTile - tile_base(j);       // leading rows that belong to the tile before
       {                                     // the next tile flies during this one (the last one is fetched twice)
@@ -189,8 +201,21 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::operand(sm_k[buf], col, kk, half), bq[kk], acc, 0, 0, 0);
       // accumulator element v: token row 8 (v / 4) + 4 half + v % 4, query column `col`
       float p[16];
+      if (COUNTS) {
+        // (alpha / R) / c: the weight of the Value SUM of the row
 #pragma unroll
-      for (int v = 0; v < 16; ++v) p[v] = ex2(fmaf(acc[v], sl2, -cq));
+        for (int g = 0; g < 4; ++g) {
+          const float4 lc = *reinterpret_cast<const float4*>(&sm_lc[buf][8 * g + 4 * half]);
+          const float4 ic = *reinterpret_cast<const float4*>(&sm_ic[buf][8 * g + 4 * half]);
+          p[4 * g] = ex2(fmaf(acc[4 * g], sl2, lc.x - cq)) * ic.x;
+          p[4 * g + 1] = ex2(fmaf(acc[4 * g + 1], sl2, lc.y - cq)) * ic.y;
+          p[4 * g + 2] = ex2(fmaf(acc[4 * g + 2], sl2, lc.z - cq)) * ic.z;
+          p[4 * g + 3] = ex2(fmaf(acc[4 * g + 3], sl2, lc.w - cq)) * ic.w;
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) p[v] = ex2(fmaf(acc[v], sl2, -cq));
+      }
       // rows of the tile before (a moved-back last tile) and rows behind the causal window's limit drop out;
       // both are rare and uniform per tile, so the common tile carries no per-element test
       if (shift > 0 || (sh.causal > 0 && tile_base(j) + kTile > un.len - sh.causal + 1)) {
@@ -278,10 +303,11 @@ __global__ __launch_bounds__(D) void pq_out_reduce_kernel(const UnitTable tab, c
 // A lane then holds ONE token (column t = lane % 32) and 16 query rows, so the sums over q are plain
 // register additions (plus one exchange between the wavefront's halves), and token t + 1 is the next lane
 // (one DPP wavefront shift).  Per (t, q): one exp2, two square roots, eleven other instructions.
-template <int D>
+template <int D, bool COUNTS>
 __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
-    const uint16_t* __restrict__ V, const float* __restrict__ c_row, const uint16_t* __restrict__ o_hi,
+    const uint16_t* __restrict__ V, const int32_t* __restrict__ counts_in, const float* __restrict__ c_row,
+    const uint16_t* __restrict__ o_hi,
     const uint16_t* __restrict__ o_lo, const float* __restrict__ oo, float* __restrict__ a_tok,
     float* __restrict__ c_edge) {
   typedef Tile<D> TL;
@@ -295,6 +321,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
   __shared__ float2 sm_out[2][kWaves][kTile];                        // (sum_q A, sum_q C) of every wavefront
   __shared__ __attribute__((aligned(16))) float sm_negc[kPassRows];  // per query row of the pass: -c[q]
   __shared__ __attribute__((aligned(16))) int sm_lim[kPassRows];     // causal window: last row attended to
+  __shared__ float sm_lc[2][kTile + 1], sm_ic[2][kTile + 1];         // COUNTS: log2 c and 1 / c of the tile's rows
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -314,6 +341,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
   const uint16_t* Ol = o_lo + (size_t)un.index * R * D;
   float* At = a_tok + un.in_row;
   float* Ce = c_edge + un.in_row;
+  const int32_t* cnt = COUNTS ? counts_in + un.in_row : nullptr;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   // Tile j puts out tokens t0 + 31 j .. + 30 and reads one row more.  Near the unit's end it is moved back
@@ -368,6 +396,11 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
       const int buf = j & 1;
       TL::store(sm_k[buf], rk, tid);
       TL::store(sm_v[buf], rv, tid);
+      if (COUNTS && tid <= kTile) {           // (the spare entry stands for the last row's "next", which is never used)
+        const float c = tid < kTile ? (float)cnt[tile_base(j) + tid] : 1.f;
+        sm_lc[buf][tid] = __builtin_amdgcn_logf(c);          // (base 2)
+        sm_ic[buf][tid] = __builtin_amdgcn_rcpf(c);
+      }
       __syncthreads();
       {                                     // the next tile flies during this one (the last one is fetched twice)
         const int jn = min(j + 1, ntiles - 1);
@@ -401,7 +434,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
         }
       }
       // S' = Q K^T and X' = (-2 O) V^T for this wavefront's 32 query rows
-      f32x16 accS = zero, accX = oo_init;     // X'' = ||o||^2 - 2 v.o
+      f32x16 accS = zero, accX = COUNTS ? zero : oo_init;     // X'' = ||o||^2 - 2 v.o (COUNTS: -2 V.o, scaled below)
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk)
         accS = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[kk], TL::operand(sm_k[buf], col, kk, half), accS, 0, 0, 0);
@@ -413,8 +446,17 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
       }
       __syncthreads();                      // sm_vv / sm_vp of this tile are complete
       // accumulator element v: query row 32 wave + 8 (v / 4) + 4 half + v % 4 of the pass, token column `col`
-      const float vv = sm_vv[buf][col];
-      const float vp = fmaf(2.f, sm_vd[buf][col], vv + sm_vv[buf][col + 1]);   // ||v_t + v_{t+1}||^2
+      float vv = sm_vv[buf][col];
+      float vp = fmaf(2.f, sm_vd[buf][col], vv + sm_vv[buf][col + 1]);         // ||v_t + v_{t+1}||^2
+      float lc = 0.f, ic = 1.f;               // COUNTS: this lane's token stands for c tokens, v = V / c
+      if (COUNTS) {
+        lc = sm_lc[buf][col];
+        ic = sm_ic[buf][col];
+        const float icn = sm_ic[buf][col + 1];
+        const float vvn = sm_vv[buf][col + 1] * icn * icn;
+        vv = vv * ic * ic;
+        vp = fmaf(2.f * ic * icn, sm_vd[buf][col], vv + vvn);
+      }
       const int t_abs = tile_base(j) + col;
       float sumA = 0.f, sumC = 0.f;
       // TAIL: the tile reaches into the causal window's masked rows (a uniform condition)
@@ -433,9 +475,9 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int v = 4 * g + i;
-            float a = ex2(fmaf(accS[v], sl2, nc[i]));                      // alpha / R
+            float a = ex2(fmaf(accS[v], sl2, COUNTS ? nc[i] + lc : nc[i]));  // alpha / R
             if (TAIL && t_abs > lim[i]) a = 0.f;
-            const float x = accX[v];                                       // ||o||^2 - 2 v_t . o
+            const float x = COUNTS ? fmaf(accX[v], ic, oo_init[v]) : accX[v]; // ||o||^2 - 2 v_t . o
             // the same quantities of token t + 1: the next lane (the last column's are not used)
             const float a_n = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, a), 0x130, 0xF, 0xF, true));
             const float x_n = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x130, 0xF, 0xF, true));
@@ -460,30 +502,32 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
   }
 }
 
-template <int D>
+template <int D, bool COUNTS>
 hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
-                    const float* c_row, float* o_part, uint16_t* o_hi, uint16_t* o_lo, float* oo, float* a_tok,
-                    float* c_edge, hipStream_t stream) {
+                    const int32_t* counts_in, const float* c_row, float* o_part, uint16_t* o_hi, uint16_t* o_lo,
+                    float* oo, float* a_tok, float* c_edge, hipStream_t stream) {
   const dim3 grid(tab.total_chunks), block(kThreads);
-  hipLaunchKernelGGL((pq_out_kernel<D>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q, (const uint16_t*)K,
-                     (const uint16_t*)V, c_row, o_part);
+  hipLaunchKernelGGL((pq_out_kernel<D, COUNTS>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
+                     (const uint16_t*)K, (const uint16_t*)V, counts_in, c_row, o_part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((pq_out_reduce_kernel<D>), dim3(tab.n_units * sh.R), dim3(D), 0, stream, tab, sh, o_part, o_hi,
                      o_lo, oo);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL((pq_norms_kernel<D>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q, (const uint16_t*)K,
-                     (const uint16_t*)V, c_row, o_hi, o_lo, oo, a_tok, c_edge);
+  hipLaunchKernelGGL((pq_norms_kernel<D, COUNTS>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
+                     (const uint16_t*)K, (const uint16_t*)V, counts_in, c_row, o_hi, o_lo, oo, a_tok, c_edge);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_per_query_norms(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
-                                  const float* c_row, float* o_part, uint16_t* o_hi, uint16_t* o_lo, float* oo,
-                                  float* a_tok, float* c_edge, hipStream_t stream) {
-  return sh.D == 64 ? launch_t<64>(tab, sh, Q, K, V, c_row, o_part, o_hi, o_lo, oo, a_tok, c_edge, stream)
-                    : launch_t<128>(tab, sh, Q, K, V, c_row, o_part, o_hi, o_lo, oo, a_tok, c_edge, stream);
+                                  const int32_t* counts_in, const float* c_row, float* o_part, uint16_t* o_hi,
+                                  uint16_t* o_lo, float* oo, float* a_tok, float* c_edge, hipStream_t stream) {
+#define KVS_PQ_ARGS tab, sh, Q, K, V, counts_in, c_row, o_part, o_hi, o_lo, oo, a_tok, c_edge, stream
+  if (counts_in) return sh.D == 64 ? launch_t<64, true>(KVS_PQ_ARGS) : launch_t<128, true>(KVS_PQ_ARGS);
+  return sh.D == 64 ? launch_t<64, false>(KVS_PQ_ARGS) : launch_t<128, false>(KVS_PQ_ARGS);
+#undef KVS_PQ_ARGS
 }
 
 }  // namespace kvs

@@ -8,6 +8,9 @@
 // fp32 caches are the small configurations, so these kernels are written for any shape rather than for speed:
 // all arithmetic is fp32 on the vector ALU, the squared distances are taken directly (sum of squared
 // differences, no expansion), units may be shorter than a tile, and there is no limit on R.
+// counts_in (or null): the rows are slots of an already merged cache (Sec. 3.1, streaming regime), row t standing
+// for c_t tokens whose Values add up to V[t]; every query row then sees it as one token with logit e + ln c_t and
+// value V[t] / c_t.
 //
 // Three kernels after the two score sweeps (which leave the normaliser c[q] of every row):
 //   pq_out_f32_kernel     o_part[chunk, q, :] = sum over the chunk's tokens of (alpha_t^{(q)} / R) V[t]
@@ -42,6 +45,16 @@ __device__ __forceinline__ void load_rows(float* sm, const float* __restrict__ g
   }
 }
 
+// log2 c and 1 / c of the rows [row0, row0 + nrows) -> LDS (1 for plain tokens and for rows at or beyond `limit`)
+__device__ __forceinline__ void load_counts(float* sm_lc, float* sm_ic, const int32_t* __restrict__ cnt, long long row0,
+                                            int nrows, long long limit, int tid) {
+  if (tid < nrows) {
+    const float c = (cnt != nullptr && row0 + tid < limit) ? (float)cnt[row0 + tid] : 1.f;
+    sm_lc[tid] = __builtin_amdgcn_logf(c);         // (the hardware's base-2 logarithm)
+    sm_ic[tid] = __builtin_amdgcn_rcpf(c);
+  }
+}
+
 template <int D>
 __device__ __forceinline__ float dot_rows(const float* a, const float* b) {
   float s = 0.f;
@@ -59,10 +72,12 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void pq_out_f32_kernel(const UnitTable tab, const Shape sh,
                                                               const float* __restrict__ Q, const float* __restrict__ K,
                                                               const float* __restrict__ V,
+                                                              const int32_t* __restrict__ counts_in,
                                                               const float* __restrict__ c_row,
                                                               float* __restrict__ o_part) {
   constexpr int S = Lds<D>::STRIDE;
   constexpr int DPT = D / kTile;                 // output dimensions per thread
+  __shared__ float sm_lc[kTile + 1], sm_ic[kTile + 1];
   __shared__ __attribute__((aligned(16))) float sm_k[kTile * S];
   __shared__ __attribute__((aligned(16))) float sm_v[kTile * S];
   __shared__ __attribute__((aligned(16))) float sm_q[kQB * S];
@@ -78,6 +93,7 @@ __global__ __launch_bounds__(kThreads) void pq_out_f32_kernel(const UnitTable ta
   const float* Kg = K + (size_t)un.in_row * D;
   const float* Vg = V + (size_t)un.in_row * D;
   const float* Qu = Q + (size_t)un.index * R * D;
+  const int32_t* cnt = counts_in ? counts_in + un.in_row : nullptr;
 
   for (int qb = 0; qb < R; qb += kQB) {
     const int q = qb + ql;
@@ -92,10 +108,12 @@ __global__ __launch_bounds__(kThreads) void pq_out_f32_kernel(const UnitTable ta
       __syncthreads();                            // the tile before has been used up
       load_rows<D>(sm_k, Kg, tb, kTile, t1, tid);
       load_rows<D>(sm_v, Vg, tb, kTile, t1, tid);
+      load_counts(sm_lc, sm_ic, cnt, tb, kTile, t1, tid);
       __syncthreads();
       const int t = tb + tl;
       const float x = dot_rows<D>(sm_q + ql * S, sm_k + tl * S);
-      sm_p[ql][tl] = (t < t1 && t <= lim) ? __builtin_amdgcn_exp2f(fmaf(x, sh.scale_log2, -cq)) : 0.f;   // alpha / R
+      // (alpha / R) / c: the row's weight for the Value SUM V[t]
+      sm_p[ql][tl] = (t < t1 && t <= lim) ? __builtin_amdgcn_exp2f(fmaf(x, sh.scale_log2, sm_lc[tl] - cq)) * sm_ic[tl] : 0.f;
       __syncthreads();
 #pragma unroll 4
       for (int r = 0; r < kTile; ++r) {
@@ -131,6 +149,7 @@ __global__ __launch_bounds__(kThreads) void pq_norms_f32_kernel(const UnitTable 
                                                                 const float* __restrict__ Q,
                                                                 const float* __restrict__ K,
                                                                 const float* __restrict__ V,
+                                                                const int32_t* __restrict__ counts_in,
                                                                 const float* __restrict__ c_row,
                                                                 const float* __restrict__ o, float* __restrict__ a_tok,
                                                                 float* __restrict__ c_edge) {
@@ -141,6 +160,7 @@ __global__ __launch_bounds__(kThreads) void pq_norms_f32_kernel(const UnitTable 
   __shared__ __attribute__((aligned(16))) float sm_o[kQB * S];
   __shared__ float sm_a[kQB][kTile + 1];          // alpha / R of the block's rows at the tile's tokens
   __shared__ float2 sm_r[kQB][kTile];             // the rows' shares of A_t and C_t
+  __shared__ float sm_lc[kTile + 1], sm_ic[kTile + 1];
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -154,11 +174,13 @@ __global__ __launch_bounds__(kThreads) void pq_norms_f32_kernel(const UnitTable 
   const float* Vg = V + (size_t)un.in_row * D;
   const float* Qu = Q + (size_t)un.index * R * D;
   const float* Ou = o + (size_t)un.index * R * D;
+  const int32_t* cnt = counts_in ? counts_in + un.in_row : nullptr;
 
   for (int tb = t0; tb < t1; tb += kTile) {
     __syncthreads();
     load_rows<D>(sm_k, Kg, tb, kTile + 1, un.len, tid);      // the neighbour of the chunk's last token is the next chunk's first
     load_rows<D>(sm_v, Vg, tb, kTile + 1, un.len, tid);
+    load_counts(sm_lc, sm_ic, cnt, tb, kTile + 1, un.len, tid);
     const int t = tb + tl;
     float sumA = 0.f, sumC = 0.f;                  // threads 0..31: token tl of the tile, over all query rows
     for (int qb = 0; qb < R; qb += kQB) {
@@ -171,22 +193,24 @@ __global__ __launch_bounds__(kThreads) void pq_norms_f32_kernel(const UnitTable 
       const int lim = last_seen_row(sh.causal, un.len, q);
       const float* qrow = sm_q + ql * S;
       const float x = dot_rows<D>(qrow, sm_k + tl * S);
-      const float a = (t < un.len && t <= lim) ? __builtin_amdgcn_exp2f(fmaf(x, sh.scale_log2, -cq)) : 0.f;
+      const float a = (t < un.len && t <= lim) ? __builtin_amdgcn_exp2f(fmaf(x, sh.scale_log2, sm_lc[tl] - cq)) : 0.f;
       sm_a[ql][tl] = a;
       if (tl == kTile - 1) {                       // the tile's extra row
         const float xn = dot_rows<D>(qrow, sm_k + kTile * S);
-        sm_a[ql][kTile] = (t + 1 < un.len && t + 1 <= lim) ? __builtin_amdgcn_exp2f(fmaf(xn, sh.scale_log2, -cq)) : 0.f;
+        sm_a[ql][kTile] = (t + 1 < un.len && t + 1 <= lim)
+                              ? __builtin_amdgcn_exp2f(fmaf(xn, sh.scale_log2, sm_lc[kTile] - cq)) : 0.f;
       }
-      float d2 = 0.f, p2 = 0.f;                    // ||v_t - o||^2, ||v_t + v_{t+1} - 2o||^2
+      float d2 = 0.f, p2 = 0.f;                    // ||v_t - o||^2, ||v_t + v_{t+1} - 2o||^2 with v = V / c
       const float* vt = sm_v + tl * S;
       const float* orow = sm_o + ql * S;
-#pragma unroll 8
+      const float ic0 = sm_ic[tl], ic1 = sm_ic[tl + 1];
+#pragma unroll 2
       for (int d = 0; d < D; d += 4) {
         const float4 v0 = *reinterpret_cast<const float4*>(vt + d);
         const float4 v1 = *reinterpret_cast<const float4*>(vt + S + d);
         const float4 oq = *reinterpret_cast<const float4*>(orow + d);
-        const float r0[4] = {v0.x - oq.x, v0.y - oq.y, v0.z - oq.z, v0.w - oq.w};
-        const float r1[4] = {v1.x - oq.x, v1.y - oq.y, v1.z - oq.z, v1.w - oq.w};
+        const float r0[4] = {fmaf(v0.x, ic0, -oq.x), fmaf(v0.y, ic0, -oq.y), fmaf(v0.z, ic0, -oq.z), fmaf(v0.w, ic0, -oq.w)};
+        const float r1[4] = {fmaf(v1.x, ic1, -oq.x), fmaf(v1.y, ic1, -oq.y), fmaf(v1.z, ic1, -oq.z), fmaf(v1.w, ic1, -oq.w)};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           d2 = fmaf(r0[i], r0[i], d2);
@@ -216,27 +240,29 @@ __global__ __launch_bounds__(kThreads) void pq_norms_f32_kernel(const UnitTable 
 
 template <int D>
 hipError_t launch_t(const UnitTable& tab, const Shape& sh, const float* Q, const float* K, const float* V,
-                    const float* c_row, float* o_part, float* o, float* a_tok, float* c_edge, hipStream_t stream) {
+                    const int32_t* counts_in, const float* c_row, float* o_part, float* o, float* a_tok, float* c_edge,
+                    hipStream_t stream) {
   const dim3 grid(tab.total_chunks), block(kThreads);
-  hipLaunchKernelGGL((pq_out_f32_kernel<D>), grid, block, 0, stream, tab, sh, Q, K, V, c_row, o_part);
+  hipLaunchKernelGGL((pq_out_f32_kernel<D>), grid, block, 0, stream, tab, sh, Q, K, V, counts_in, c_row, o_part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((pq_reduce_f32_kernel<D>), dim3(tab.n_units * sh.R), dim3(D), 0, stream, tab, sh, o_part, o);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL((pq_norms_f32_kernel<D>), grid, block, 0, stream, tab, sh, Q, K, V, c_row, o, a_tok, c_edge);
+  hipLaunchKernelGGL((pq_norms_f32_kernel<D>), grid, block, 0, stream, tab, sh, Q, K, V, counts_in, c_row, o, a_tok,
+                     c_edge);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_per_query_norms_f32(const UnitTable& tab, const Shape& sh, const void* Q, const void* K,
-                                      const void* V, const float* c_row, float* o_part, float* o, float* a_tok,
-                                      float* c_edge, hipStream_t stream) {
+                                      const void* V, const int32_t* counts_in, const float* c_row, float* o_part,
+                                      float* o, float* a_tok, float* c_edge, hipStream_t stream) {
   const float* q = (const float*)Q;
   const float* k = (const float*)K;
   const float* v = (const float*)V;
-  return sh.D == 64 ? launch_t<64>(tab, sh, q, k, v, c_row, o_part, o, a_tok, c_edge, stream)
-                    : launch_t<128>(tab, sh, q, k, v, c_row, o_part, o, a_tok, c_edge, stream);
+  return sh.D == 64 ? launch_t<64>(tab, sh, q, k, v, counts_in, c_row, o_part, o, a_tok, c_edge, stream)
+                    : launch_t<128>(tab, sh, q, k, v, counts_in, c_row, o_part, o, a_tok, c_edge, stream);
 }
 
 }  // namespace kvs

@@ -85,14 +85,13 @@ def accepted_unit_per_query(w: Workload, layer: int, seq: int, head: int, n: Opt
     for attempt in range(start, MAX_ATTEMPTS):
         u = generate_unit(w, layer, seq, head, attempt=attempt, n=n, kv_from=base)
         base = u
-        assert u.counts is None
-        alpha_bar, o_bar = O.score(u.Q, u.K, u.V, causal_window=cw)
+        alpha_bar, o_bar = O.score(u.Q, u.K, u.V, counts=u.counts, causal_window=cw)
         gap = O.boundary_gap(alpha_bar, u.budget, w.n_sink, w.n_recent)
         if gap < GAP_MIN:
             continue
         mask, slot = O.select(alpha_bar, u.budget, w.n_sink, w.n_recent)
-        norms = O.per_query_norms(u.Q, u.K, u.V, causal_window=cw)
-        merged = O.merge_compact(u.K, u.V, alpha_bar, o_bar, mask, slot, norms=norms)
+        norms = O.per_query_norms(u.Q, u.K, u.V, causal_window=cw, counts=u.counts)
+        merged = O.merge_compact(u.K, u.V, alpha_bar, o_bar, mask, slot, counts_in=u.counts, norms=norms)
         cond = O.conditioning(merged)
         if cond < PQ_COND_MIN:
             continue

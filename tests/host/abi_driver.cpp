@@ -82,7 +82,7 @@ static void whole_calls(std::mt19937& rng, kvs_dtype dt, int group, int window, 
     EXPECT(kvs_step(&pr.p, Q, K, V, Ko, Vo, cnt, slot, mask, ws, ws_bytes - 1, nullptr) == KVS_ERR_WORKSPACE);
     EXPECT(kvs_step(&pr.p, Q, K, V, Ko, Ko, cnt, slot, mask, ws, ws_bytes, nullptr) == KVS_ERR_ALIAS);
     EXPECT(kvs_step(&pr.p, Q, K, V, Ko, Vo, cnt, slot, (uint8_t*)ws + 256, ws, ws_bytes, nullptr) == KVS_ERR_ALIAS);
-    if (dt == KVS_BF16) {
+    {                                          // per-query aggregation: both dtypes
       EXPECT(kvs_per_query_workspace_size(&pr.p, &pq_bytes) == KVS_OK && pq_bytes > ws_bytes);
       void* pws = a.take(pq_bytes);
       float* a_tok = (float*)a.take((size_t)pr.rows_in * 4);
@@ -90,6 +90,10 @@ static void whole_calls(std::mt19937& rng, kvs_dtype dt, int group, int window, 
       EXPECT(kvs_sensitivity(&pr.p, Q, K, V, alpha, a_tok, c_edge, pws, pq_bytes, nullptr) == KVS_OK);
       EXPECT(kvs_step_per_query(&pr.p, Q, K, V, Ko, Vo, cnt, nullptr, nullptr, pws, pq_bytes, nullptr) == KVS_OK);
       EXPECT(kvs_merge_compact_norms(&pr.p, K, V, a_tok, c_edge, mask, slot, Ko, Vo, cnt, nullptr, 0, nullptr) == KVS_OK);
+      EXPECT(kvs_sensitivity_counts(&pr.p, Q, K, V, cin, alpha, a_tok, c_edge, pws, pq_bytes, nullptr) == KVS_OK);
+      EXPECT(kvs_step_per_query_counts(&pr.p, Q, K, V, cin, Ko, Vo, cnt, nullptr, nullptr, pws, pq_bytes, nullptr) == KVS_OK);
+      EXPECT(kvs_merge_compact_norms_counts(&pr.p, K, V, cin, a_tok, c_edge, mask, slot, Ko, Vo, cnt, nullptr, 0, nullptr) == KVS_OK);
+      EXPECT(kvs_sensitivity_counts(&pr.p, Q, K, V, (const int32_t*)a_tok, alpha, a_tok, c_edge, pws, pq_bytes, nullptr) == KVS_ERR_ALIAS);
     }
     if (R <= KVS_MAX_DECODE_ROWS) {
       EXPECT(kvs_decode_workspace_size(&pr.p, &dec_bytes) == KVS_OK);

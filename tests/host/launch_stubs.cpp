@@ -64,12 +64,12 @@ hipError_t launch_select_clear(const UnitTable& tab, unsigned int* sel_shared, h
 hipError_t launch_obar_reduce(const UnitTable& tab, const Shape&, const float*, float*, hipStream_t) { check_table(tab); return ok(); }
 hipError_t launch_merge(const UnitTable& tab, const Shape&, kvs_dtype, const void*, const void*, const int32_t*, const float*,
                         const float*, const float*, const uint8_t*, const int32_t*, void*, void*, int32_t*, hipStream_t) { check_table(tab); return ok(); }
-hipError_t launch_merge_norms(const UnitTable& tab, const Shape&, kvs_dtype, const void*, const void*, const float*, const float*,
-                              const uint8_t*, const int32_t*, void*, void*, int32_t*, hipStream_t) { check_table(tab); return ok(); }
-hipError_t launch_per_query_norms(const UnitTable& tab, const Shape&, const void*, const void*, const void*, const float*,
-                                  float*, uint16_t*, uint16_t*, float*, float*, float*, hipStream_t) { check_table(tab); return ok(); }
-hipError_t launch_per_query_norms_f32(const UnitTable& tab, const Shape&, const void*, const void*, const void*, const float*,
-                                      float*, float*, float*, float*, hipStream_t) { check_table(tab); return ok(); }
+hipError_t launch_merge_norms(const UnitTable& tab, const Shape&, kvs_dtype, const void*, const void*, const int32_t*, const float*,
+                              const float*, const uint8_t*, const int32_t*, void*, void*, int32_t*, hipStream_t) { check_table(tab); return ok(); }
+hipError_t launch_per_query_norms(const UnitTable& tab, const Shape&, const void*, const void*, const void*, const int32_t*,
+                                  const float*, float*, uint16_t*, uint16_t*, float*, float*, float*, hipStream_t) { check_table(tab); return ok(); }
+hipError_t launch_per_query_norms_f32(const UnitTable& tab, const Shape&, const void*, const void*, const void*, const int32_t*,
+                                      const float*, float*, float*, float*, float*, hipStream_t) { check_table(tab); return ok(); }
 hipError_t launch_decode(const UnitTable& tab, const Shape&, kvs_dtype, const void*, const void*, const void*, const int32_t*,
                          float*, float*, hipStream_t) { check_table(tab); return ok(); }
 

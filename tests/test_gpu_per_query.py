@@ -59,20 +59,38 @@ SENS_CASES_F32 = [
 ]
 
 
+# rows with input cardinalities (streaming regime): the recipe of the stream2560 workload at other shapes
+SENS_CASES_COUNTS = [
+    ("stream2560", 128, 4, 32, [2560, 700], "bf16"),   # the streaming configuration's own shape; a ragged second unit
+    ("stream2560", 64, 2, 16, [900, 32], "bf16"),      # head dim 64; a unit of exactly one tile
+    ("stream2560", 128, 5, 32, [1111], "bf16"),        # 160 rows: two passes
+    ("stream2560", 64, 2, 5, [300, 31, 3], "f32"),     # fp32: units shorter than a tile
+    ("stream2560", 128, 4, 8, [1300], "f32"),
+]
+
+
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("base,D,G,W,lens,dtype",
-                         [c + ("bf16",) for c in SENS_CASES] + [c + ("f32",) for c in SENS_CASES_F32])
+                         [c + ("bf16",) for c in SENS_CASES] + [c + ("f32",) for c in SENS_CASES_F32] +
+                         SENS_CASES_COUNTS)
 def test_sensitivity_matches_oracle(base, D, G, W, lens, dtype, causal):
     if causal:
         lens = [n for n in lens if n >= W]           # the window's own rows are part of the cache
     w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
+    if w.mean_count > 0:
+        w = w.scaled(fresh_tail=max(W, 8), n_sink=2)  # short units too have rows that stand for several tokens
     units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
     batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype=dtype, n_sink=w.n_sink, gap_rows=3,
                         causal=causal)
     cw = W if causal else 0
     a_tok, c_edge, ws = per_query_buffers(batch)
-    batch.kvs.kvs_sensitivity(batch.problem, batch.Q, batch.K, batch.V, batch.alpha_bar, a_tok, c_edge, ws,
-                              stream=batch.stream())
+    with_counts = units[0].counts is not None
+    if with_counts:
+        batch.kvs.kvs_sensitivity_counts(batch.problem, batch.Q, batch.K, batch.V, batch.counts_in, batch.alpha_bar,
+                                         a_tok, c_edge, ws, stream=batch.stream())
+    else:
+        batch.kvs.kvs_sensitivity(batch.problem, batch.Q, batch.K, batch.V, batch.alpha_bar, a_tok, c_edge, ws,
+                                  stream=batch.stream())
     torch_sync()
     batch.check_guards()
     p = batch.problem
@@ -81,13 +99,13 @@ def test_sensitivity_matches_oracle(base, D, G, W, lens, dtype, causal):
     for i, u in enumerate(units):
         n = lens[i]
         r0 = p.in_rows[i]
-        ra, _ = O.score(u.Q, u.K, u.V, causal_window=cw)
-        A_ref, C_ref = O.per_query_norms(u.Q, u.K, u.V, causal_window=cw)
+        ra, _ = O.score(u.Q, u.K, u.V, counts=u.counts, causal_window=cw)
+        A_ref, C_ref = O.per_query_norms(u.Q, u.K, u.V, causal_window=cw, counts=u.counts)
         assert np.max(np.abs(alpha[r0:r0 + n] - ra) / ra) < TOL_ALPHA
         gA, gC = A[r0:r0 + n], C[r0:r0 + n - 1]
         assert np.isfinite(gA).all() and np.isfinite(gC).all()
-        rows = O.attention_rows(u.Q, u.K, causal_window=cw)
-        V64 = u.V.astype(np.float64)
+        rows = O.attention_rows(u.Q, u.K, counts=u.counts, causal_window=cw)
+        V64 = O.slot_values(u.V, u.counts)
         size = np.zeros(n)                           # mean over the rows of alpha ||v_t - o|| (no |1 - 2 alpha|)
         for a_q in rows:
             size += a_q * np.linalg.norm(V64 - a_q @ V64, axis=1)
@@ -112,6 +130,8 @@ def test_sensitivity_matches_oracle(base, D, G, W, lens, dtype, causal):
 @pytest.mark.parametrize("base,dtype,D,lens,budgets", [
     ("tiny", "f32", 64, [1024, 300], [256, 100]),
     ("llama8b_8k", "bf16", 128, [3000, 777], [700, 300]),
+    ("stream2560", "bf16", 128, [2560, 777], [2048, 300]),      # rows with input cardinalities
+    ("stream2560", "f32", 64, [900], [400]),
 ])
 def test_merge_compact_norms_matches_oracle(base, dtype, D, lens, budgets, rule):
     """The merge pass with A_t and C_t handed in (here the oracle's, rounded to fp32)."""
@@ -127,21 +147,24 @@ def test_merge_compact_norms_matches_oracle(base, dtype, D, lens, budgets, rule)
     slot_all = np.zeros(p.rows_in, dtype=np.int32)
     for i, u in enumerate(units):
         n = u.K.shape[0]
-        a, o = O.score(u.Q, u.K, u.V)
+        a, o = O.score(u.Q, u.K, u.V, counts=u.counts)
         mask, slot = O.select(a.astype(np.float32), u.budget, w.n_sink, 0, sigma_dtype=np.float32)
-        A, C = O.per_query_norms(u.Q, u.K, u.V)
+        A, C = O.per_query_norms(u.Q, u.K, u.V, counts=u.counts)
         A32, C32 = A.astype(np.float32), C.astype(np.float32)
-        refs.append(O.merge_compact(u.K, u.V, a, o, mask, slot, rule=rule,
+        refs.append(O.merge_compact(u.K, u.V, a, o, mask, slot, counts_in=u.counts, rule=rule,
                                     norms=(A32.astype(np.float64), C32.astype(np.float64))))
         r0 = p.in_rows[i]
         A_all[r0:r0 + n] = A32
         C_all[r0:r0 + n - 1] = C32
         mask_all[r0:r0 + n] = mask
         slot_all[r0:r0 + n] = slot
-    batch.kvs.kvs_merge_compact_norms(p, batch.K, batch.V, torch.from_numpy(A_all).cuda(),
-                                      torch.from_numpy(C_all).cuda(), torch.from_numpy(mask_all).cuda(),
-                                      torch.from_numpy(slot_all).cuda(), batch.K_out, batch.V_out, batch.counts,
-                                      stream=batch.stream())
+    dev = [torch.from_numpy(x).cuda() for x in (A_all, C_all, mask_all, slot_all)]
+    if units[0].counts is not None:
+        batch.kvs.kvs_merge_compact_norms_counts(p, batch.K, batch.V, batch.counts_in, *dev, batch.K_out, batch.V_out,
+                                                 batch.counts, stream=batch.stream())
+    else:
+        batch.kvs.kvs_merge_compact_norms(p, batch.K, batch.V, *dev, batch.K_out, batch.V_out, batch.counts,
+                                          stream=batch.stream())
     torch_sync()
     batch.check_guards()
     compare_outputs(batch, refs, dtype)
@@ -151,8 +174,14 @@ def check_step_per_query(w, accepted, causal=False):
     batch = DeviceBatch([a.inputs for a in accepted], group=w.group, window=w.window, head_dim=w.head_dim,
                         dtype=w.dtype, n_sink=w.n_sink, n_recent=w.n_recent, causal=causal)
     _, _, ws = per_query_buffers(batch)
-    batch.kvs.kvs_step_per_query(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out, batch.counts,
-                                 ws, slot_of_token_out=batch.slot, edge_mask_out=batch.mask, stream=batch.stream())
+    if accepted[0].inputs.counts is not None:
+        batch.kvs.kvs_step_per_query_counts(batch.problem, batch.Q, batch.K, batch.V, batch.counts_in, batch.K_out,
+                                            batch.V_out, batch.counts, ws, slot_of_token_out=batch.slot,
+                                            edge_mask_out=batch.mask, stream=batch.stream())
+    else:
+        batch.kvs.kvs_step_per_query(batch.problem, batch.Q, batch.K, batch.V, batch.K_out, batch.V_out,
+                                     batch.counts, ws, slot_of_token_out=batch.slot, edge_mask_out=batch.mask,
+                                     stream=batch.stream())
     torch_sync()
     batch.check_guards()
     p = batch.problem
@@ -177,6 +206,16 @@ def test_step_per_query_fp32_config():
     w = WORKLOADS["tiny"].scaled(group=3, window=6, length=("fixed", 700), budget=("fixed", 200))
     check_step_per_query(w, [accepted_unit_per_query(w, 0, 0, 0)])
     check_step_per_query(w, [accepted_unit_per_query(w, 0, 0, 0, causal=True)], causal=True)
+
+
+def test_step_per_query_streaming_regime():
+    """Caches of 2048 + 512 slots with input cardinalities, every query row kept apart: bf16 as configured, and the
+    same recipe in fp32 at a smaller size; cardinalities of the merged slots bit-exact."""
+    w = WORKLOADS["stream2560"]
+    check_step_per_query(w, [accepted_unit_per_query(w, 0, 0, h) for h in range(2)])
+    w = WORKLOADS["stream2560"].scaled(dtype="f32", group=2, window=8, length=("fixed", 900), budget=("fixed", 600),
+                                       fresh_tail=64)
+    check_step_per_query(w, [accepted_unit_per_query(w, 0, 0, 0)])
 
 
 def test_step_per_query_with_causal_window():
