@@ -15,7 +15,9 @@
 // first `want` keys equal to T, and turns the selection into the slot map with DPP prefix scans
 // and a scan over the 16 wavefronts.  Keys of units up to kLdsKeys edges are kept in LDS between
 // the passes; longer units recompute them from alpha_bar (L2-resident) in every pass with the
-// plain IEEE digits.
+// same stretched ranking.  In a launch of few units a long unit is selected by several workgroups
+// ("parts") instead, which meet through an exchange area in device memory (see select_unit_split);
+// the kernel exists in two LDS sizes (kLdsKeys and kLdsKeysSmall keys per workgroup).
 //
 // o_bar pass, per chunk of a unit: rows of V are read by LPR adjacent lanes (16 bytes each), scaled
 // by alpha_bar[t] and summed per lane, then over the workgroup; the chunk's sum goes to the
