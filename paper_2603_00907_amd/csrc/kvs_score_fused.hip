@@ -409,10 +409,16 @@ __global__ __launch_bounds__(kThreads, 1) void score_fused_kernel(
         float M = -INFINITY;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm_lse[w][tid]);
-        float S = 0.f;
+        // (a query row that the causal mask cuts off from every token of this item has no finite value here:
+        // its share is log2 0)
+        float lse = -INFINITY;
+        if (M != -INFINITY) {
+          float S = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) S += ex2(sm_lse[w][tid] - M);      // 2^(-inf) = 0; M is finite
-        st_agent_f(&fstats[(size_t)item * R + tid], M + __builtin_amdgcn_logf(S));
+          for (int w = 0; w < kWaves; ++w) S += ex2(sm_lse[w][tid] - M);    // 2^(-inf) = 0
+          lse = M + __builtin_amdgcn_logf(S);
+        }
+        st_agent_f(&fstats[(size_t)item * R + tid], lse);
       }
       if (tid < kQRows) wait_vm<0>();
       __syncthreads();

@@ -563,6 +563,9 @@ CAUSAL_CASES = [
     ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053], "fuse"),   # (with the pass over V carried along)
     ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053], None),     # 128 rows in one pass; a last chunk of 5 rows, all
     ("llama8b_8k", "bf16", 128, 4, 32, [2053], "valu"),         # of them masked for most rows
+    ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053, 600], "onepass"),   # the one-pass kernel: an item of 5 rows that most
+    ("llama8b_8k", "bf16", 128, 4, 32, [2500, 2053, 600], "defer"),     # query rows do not see at all
+    ("llama8b_8k", "bf16", 64, 3, 22, [1500, 1029], "onepass"),         # 66 rows, head dim 64: items of 1024 rows, one of 5
     ("llama8b_8k", "bf16", 128, 8, 32, [3000], None),           # 256 rows in one pass (four blocks of 64)
     ("llama8b_8k", "bf16", 128, 8, 32, [3000, 2053], "fuse"),
     ("llama8b_8k", "bf16", 128, 8, 32, [3000], "narrow"),       # 256 rows, two wavefronts per pass
