@@ -195,7 +195,7 @@ Workspace carve(const Plan& plan, void* base) {
 
 // Extra workspace of the per-query aggregation, laid out behind the ordinary one.
 struct PerQueryWs {
-  float* o_part;     // [largest launch's chunks][R][D]
+  float* o_part;     // [a launch's chunks][R][D] partial outputs, then [a launch's chunks][R] sums of their weights
   uint16_t* o_hi;    // [n_units][R][D]  bf16 inputs: -2 o as a bf16 pair hi + lo
   uint16_t* o_lo;
   float* o_f32;      // [n_units][R][D]  fp32 inputs: o itself
@@ -221,7 +221,7 @@ PerQueryWs carve_per_query(const Plan& plan, void* base, Workspace* w) {
     max_chunks = std::max(max_chunks, c);
   }
   const size_t rd = (size_t)plan.shape.R * plan.shape.D;
-  q.o_part = (float*)take((size_t)max_chunks * rd * sizeof(float));
+  q.o_part = (float*)take((size_t)max_chunks * (rd + plan.shape.R) * sizeof(float));
   if (plan.dtype == KVS_F32) {
     q.o_f32 = (float*)take((size_t)plan.n_units * rd * sizeof(float));
   } else {

@@ -8,22 +8,28 @@
 //   C_t = (1/R) sum_q alpha_t^{(q)} alpha_{t+1}^{(q)} ||v_t + v_{t+1} - 2 o^{(q)}||
 // The merge kernel then uses A and C in the weight form of Eq. kstar_final.
 //
-// Three kernels after the two score sweeps (which leave the normaliser c[q] of every row):
+// Four kernels after the two score sweeps (which leave the normaliser c[q] of every row):
 //   pq_out_kernel         O^T[d, q] = sum_t V[t, d] P[t, q], P = alpha / R recomputed from K Q^T tile by tile.
 //                         Both products run on v_mfma_f32_32x32x16_bf16.  The contraction over tokens needs
 //                         V with the token index along the MFMA k dimension; a 32x32 block of the V tile is
 //                         turned by one more MFMA against an identity operand (exact in bf16), which leaves it
 //                         in the accumulator layout that IS the k-major operand layout of the next product.
 //                         P enters as a bf16 pair hi + lo, so that the rounding of P to bf16 does not limit
-//                         the accuracy of o.  Chunk partials go to memory and are added in chunk order.
-//   pq_out_reduce_kernel  o^{(q)} = R * sum of the chunk partials; -2 o^{(q)} stored as a bf16 pair hi + lo, and
-//                         ||o^{(q)}||^2.
+//                         the accuracy of o; the sum of the weights, as the pairs carry them, is kept beside it.
+//                         Chunk partials go to memory and are added in chunk order.
+//   pq_out_reduce_kernel  o^{(q)} = (sum of the chunk partials) / (sum of their weights): a convex combination of the
+//                         Values with the weights as they were rounded, so that where a row puts nearly all its
+//                         weight on one token, o - v_t is as accurate as the small weights of the others (dividing
+//                         by the nominal sum 1 / R would leave the weights' rounding times ||v_t||).
+//                         -2 o^{(q)} stored as a bf16 pair hi + lo, and ||o^{(q)}||^2.
 //   pq_norms_kernel       per tile of 32 tokens: S' = Q K^T (logits), X' = (-2 O) V^T (hi and lo), then per (t, q)
 //                         (accumulated on top of ||o||^2), then per (t, q)
 //                         ||v_t - o||^2 = ||v_t||^2 + X',
 //                         ||v_t + v_{t+1} - 2o||^2 = ||v_t + v_{t+1}||^2 + 2 (X'_t + X'_{t+1}),
 //                         two square roots, and the sums over q.  Tiles overlap by one row (stride 31), so
-//                         the next token of every output row is in the same tile.
+//                         the next token of every output row is in the same tile.  Tokens where the expansions
+//                         cancel (o^{(q)} close to v_t for some q) are marked.
+//   pq_redo_kernel        the marked tokens once more, every squared norm as a sum of squared differences.
 // COUNTS: the rows are slots of an already merged cache (Sec. 3.1, streaming regime), row t standing for c_t tokens
 // whose Values add up to V[t]: every query row sees it as one token with logit e + ln c_t and value V[t] / c_t.  The
 // products still run on the stored rows; log2 c_t joins the logit, and 1 / c_t scales the attention weight of the
@@ -45,8 +51,17 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kTile = 32;                 // tokens per MFMA tile
 constexpr int kPassRows = 32 * kWaves;    // query rows per pass over the chunk
+constexpr int kRedoSpan = 4096;           // pq_redo: tokens per workgroup
+constexpr float kCancel = 1.f / 16.f;     // pq_norms: a squared norm below this share of its leading term is formed again
 
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// (one instruction; written out because the compiler forms it from nested fminf only now and then)
+__device__ __forceinline__ float min3(float a, float b, float c) {
+  float r;
+  asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& u) { return __builtin_bit_cast(bf16x8, u); }
 
@@ -67,6 +82,26 @@ __device__ __forceinline__ void split8(const float* f, bf16x8& hi, bf16x8& lo) {
   }
   hi = as_bf16x8(make_uint4(h[0], h[1], h[2], h[3]));
   lo = pack8(r);
+}
+
+// The same, and w[i] = the value the pair stands for (hi + lo as floats).
+__device__ __forceinline__ void split8w(const float* f, bf16x8& hi, bf16x8& lo, float* w) {
+  uint32_t h[4], l[4];
+  float r[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    h[i] = cvt_pk_bf16(f[2 * i], f[2 * i + 1]);
+    r[2 * i] = f[2 * i] - bf16_lo(h[i]);
+    r[2 * i + 1] = f[2 * i + 1] - bf16_hi(h[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    l[i] = cvt_pk_bf16(r[2 * i], r[2 * i + 1]);
+    w[2 * i] = bf16_lo(h[i]) + bf16_lo(l[i]);
+    w[2 * i + 1] = bf16_hi(h[i]) + bf16_hi(l[i]);
+  }
+  hi = as_bf16x8(make_uint4(h[0], h[1], h[2], h[3]));
+  lo = as_bf16x8(make_uint4(l[0], l[1], l[2], l[3]));
 }
 
 // A 32-row tile of K or V: global -> registers -> LDS.  Piece p of row r lands in slot p ^ (r % LPR).
@@ -122,13 +157,14 @@ template <int D, bool COUNTS>
 __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
     const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ V, const int32_t* __restrict__ counts_in, const float* __restrict__ c_row,
-    float* __restrict__ o_part) {
+    float* __restrict__ o_part, float* __restrict__ p_part) {
   typedef Tile<D> TL;
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;                // 32-wide blocks of the value dimension
   __shared__ __attribute__((aligned(16))) unsigned char sm_k[2][TL::BYTES];
   __shared__ __attribute__((aligned(16))) unsigned char sm_v[2][TL::BYTES];
   __shared__ __attribute__((aligned(16))) float sm_lc[2][kTile], sm_ic[2][kTile];   // COUNTS: log2 c and 1 / c of the tile's rows
+  __shared__ __attribute__((aligned(16))) float sm_cc[2][kTile];                    // COUNTS: c itself
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -174,6 +210,7 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
     f32x16 accO[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db) accO[db] = zero;
+    float wsum = 0.f;                       // sum of alpha / R over this lane's token rows, as the pairs hi + lo carry it
 
     typename TL::Regs rk = TL::load(Kg + (size_t)tile_base(0) * TL::ROWB, tid);
     typename TL::Regs rv = TL::load(Vg + (size_t)tile_base(0) * TL::ROWB, tid);
@@ -185,6 +222,7 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
         const float c = (float)cnt[tile_base(j) + tid];
         sm_lc[buf][tid] = __builtin_amdgcn_logf(c);          // (base 2)
         sm_ic[buf][tid] = __builtin_amdgcn_rcpf(c);
+        sm_cc[buf][tid] = c;
       }
       __syncthreads();
       const int shift = t0 + j * kTile - tile_base(j);       // leading rows that belong to the tile before
@@ -227,8 +265,22 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
       }
       // as the operand of the next product, element i of k-step s is accumulator element 8 s + i
       bf16x8 ph[2], pl[2];
-      split8(p, ph[0], pl[0]);
-      split8(p + 8, ph[1], pl[1]);
+      float pw[16];
+      split8w(p, ph[0], pl[0], pw);
+      split8w(p + 8, ph[1], pl[1], pw + 8);
+      if (COUNTS) {                         // (the pair carries (alpha / R) / c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 cc = *reinterpret_cast<const float4*>(&sm_cc[buf][8 * g + 4 * half]);
+          wsum = fmaf(pw[4 * g], cc.x, wsum);
+          wsum = fmaf(pw[4 * g + 1], cc.y, wsum);
+          wsum = fmaf(pw[4 * g + 2], cc.z, wsum);
+          wsum = fmaf(pw[4 * g + 3], cc.w, wsum);
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) wsum += pw[v];
+      }
       // (taking all four blocks of V through the identity first, to run them beside the exponentials and to
       // have four independent accumulators in the products below, was measured 6 % slower: 64 more live
       // registers)
@@ -248,6 +300,8 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
       }
     }
     __syncthreads();                        // the next pass starts with buffer 0 again
+    wsum += __shfl_xor(wsum, 32, kWave);    // the other half's token rows
+    if (ok && half == 0) p_part[(size_t)(un.chunk_base + chunk) * R + qrow] = wsum;
     if (ok) {
       float* dst = o_part + ((size_t)(un.chunk_base + chunk) * R + qrow) * D;
 #pragma unroll
@@ -262,11 +316,12 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
   }
 }
 
-// o^{(q)} from the chunk partials (in chunk order), as a bf16 pair hi + lo, and its squared norm.
-// One workgroup of D threads per (unit, query row).
+// o^{(q)} from the chunk partials and the sums of their weights (both in chunk order), as a bf16 pair hi + lo, and
+// its squared norm.  One workgroup of D threads per (unit, query row).
 template <int D>
 __global__ __launch_bounds__(D) void pq_out_reduce_kernel(const UnitTable tab, const Shape sh,
                                                           const float* __restrict__ o_part,
+                                                          const float* __restrict__ p_part,
                                                           uint16_t* __restrict__ o_hi, uint16_t* __restrict__ o_lo,
                                                           float* __restrict__ oo) {
   __shared__ float sm_ss[D / kWave];
@@ -274,9 +329,12 @@ __global__ __launch_bounds__(D) void pq_out_reduce_kernel(const UnitTable tab, c
   const Unit un = tab.u[blockIdx.x / R];
   const int q = blockIdx.x % R;
   const int d = threadIdx.x;
-  float s = 0.f;
-  for (int c = 0; c < un.n_chunks; ++c) s += o_part[((size_t)(un.chunk_base + c) * R + q) * D + d];
-  const float m2o = -2.f * (s * (float)R);                 // stored with the factor of ||v - o||^2 = ||v||^2 - 2 v.o + ||o||^2
+  float s = 0.f, w = 0.f;
+  for (int c = 0; c < un.n_chunks; ++c) {
+    s += o_part[((size_t)(un.chunk_base + c) * R + q) * D + d];
+    w += p_part[(size_t)(un.chunk_base + c) * R + q];
+  }
+  const float m2o = -2.f * (s / w);                        // stored with the factor of ||v - o||^2 = ||v||^2 - 2 v.o + ||o||^2
   const uint32_t hi = f32_to_bf16(m2o);
   const uint32_t lo = f32_to_bf16(m2o - bf16_lo(hi));
   const size_t idx = ((size_t)un.index * R + q) * D + d;
@@ -380,11 +438,22 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
         const int r = tid, t = base + r;
         if (r >= shift && r <= shift + STRIDE - 1 && t < t1) {
           float a = 0.f, c = 0.f;
+          uint32_t mark = 0;                               // sign bit: some wavefront, or an earlier pass, marked the token
 #pragma unroll
-          for (int w = 0; w < kWaves; ++w) { a += sm_out[buf][w][r].x; c += sm_out[buf][w][r].y; }
+          for (int w = 0; w < kWaves; ++w) {
+            const float2 o = sm_out[buf][w][r];
+            mark |= __float_as_uint(o.x);
+            a += fabsf(o.x);
+            c += o.y;
+          }
           if (r == kTile - 1) c = 0.f;                     // only the unit's last token: it has no next one
-          if (qp > 0) { a += At[t]; c += Ce[t]; }          // later passes add their query rows
-          At[t] = a;
+          if (qp > 0) {                                    // later passes add their query rows
+            const float before = At[t];
+            mark |= __float_as_uint(before);
+            a += fabsf(before);
+            c += Ce[t];
+          }
+          At[t] = __uint_as_float(__float_as_uint(a) | (mark & 0x80000000u));
           Ce[t] = c;
         }
       }
@@ -459,6 +528,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
       }
       const int t_abs = tile_base(j) + col;
       float sumA = 0.f, sumC = 0.f;
+      float leastA = INFINITY, leastC = INFINITY;   // smallest squared norms this lane forms in the tile (see below)
       // TAIL: the tile reaches into the causal window's masked rows (a uniform condition)
       auto rows = [&](auto tail_tag) {
         constexpr bool TAIL = decltype(tail_tag)::value;
@@ -472,6 +542,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
             const int4 l4 = *reinterpret_cast<const int4*>(&sm_lim[q0]);
             lim[0] = l4.x; lim[1] = l4.y; lim[2] = l4.z; lim[3] = l4.w;
           }
+          float d2s[4], p2s[4];
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             const int v = 4 * g + i;
@@ -486,19 +557,166 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
             // (a rounding-size negative value stands for zero: the square roots take the magnitude)
             sumA = fmaf(a * fabsf(fmaf(-2.f * Rf, a, 1.f)), __builtin_amdgcn_sqrtf(fabsf(d2)), sumA);
             sumC = fmaf(a * a_n, __builtin_amdgcn_sqrtf(fabsf(p2)), sumC);
+            d2s[i] = d2;
+            p2s[i] = p2;
           }
+          leastA = min3(min3(leastA, d2s[0], d2s[1]), d2s[2], d2s[3]);
+          leastC = min3(min3(leastC, p2s[0], p2s[1]), p2s[2], p2s[3]);
           __builtin_amdgcn_sched_barrier(0);  // four rows at a time: interleaving all sixteen runs out of registers
         }
       };
       if (sh.causal > 0 && tile_base(j) + kTile > un.len - sh.causal + 1) rows(std::true_type{});
       else rows(std::false_type{});
+      // Cancellation.  Where o^{(q)} comes close to v_t (a query row that puts nearly all its weight on one token) the
+      // expansion above loses what is left of ||v_t - o||^2 to the rounding of its terms of size ||v_t||^2.  A token
+      // one of whose squared norms falls below kCancel of its leading term is marked (the sign bit of its A_t, which
+      // is never negative) and formed again by pq_redo_kernel, from differences.  The test costs one three-way
+      // minimum per (t, q).
+      int redo = (leastA < kCancel * vv || leastC < kCancel * vp) ? 1 : 0;
+      redo |= __shfl_xor(redo, 32, kWave);
       sumA += __shfl_xor(sumA, 32, kWave);    // the other half's 16 query rows
       sumC += __shfl_xor(sumC, 32, kWave);
-      if (half == 0) sm_out[buf][wave][col] = make_float2(sumA, sumC * Rf);
+      if (half == 0) sm_out[buf][wave][col] = make_float2(redo ? -sumA : sumA, sumC * Rf);   // (sumA >= 0; -0 counts)
     }
     __syncthreads();
     flush(ntiles - 1);
     __syncthreads();                        // the next pass reuses the buffers
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Tokens that pq_norms_kernel marked (sign bit of A_t): A_t and C_t over all query rows once more, every squared norm
+// as a sum of squared differences: ||v_t - o||^2 from v_t and the stored pair -2 o = hi + lo, likewise
+// ||v_t + v_{t+1} - 2 o||^2.  One workgroup per span of kRedoSpan tokens; the span's marked tokens are listed and
+// taken in turn: D / 8 adjacent lanes share a query row, eight dimensions each (one round of coalesced loads per row), the
+// rows' terms are added per lane group in row order and the groups in a fixed tree order.  Every marked token leaves
+// with a non-negative A_t, so no mark outlives this kernel.
+template <int D, bool COUNTS>
+__global__ __launch_bounds__(kThreads) void pq_redo_kernel(
+    const UnitTable tab, const Shape sh, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
+    const uint16_t* __restrict__ V, const int32_t* __restrict__ counts_in, const float* __restrict__ c_row,
+    const uint16_t* __restrict__ o_hi, const uint16_t* __restrict__ o_lo, float* __restrict__ a_tok,
+    float* __restrict__ c_edge) {
+  constexpr int LPR = D / 8;                // lanes per query row
+  constexpr int RPP = kThreads / LPR;       // query rows per pass of the workgroup
+  __shared__ int sm_list[kRedoSpan];
+  __shared__ int sm_n;
+  __shared__ float sm_row[4][D];            // k_t, k_{t+1}, v_t, v_{t+1} (the Values divided by their cardinalities)
+  __shared__ float sm_sum[2][kThreads];
+  static_assert(kRedoSpan / kThreads <= 32, "one bit per token and thread");
+
+  const Unit un = tab.u[blockIdx.x];
+  const int t0 = blockIdx.y * kRedoSpan;
+  const int t1 = min(un.len, t0 + kRedoSpan);
+  if (t0 >= t1) return;                     // (the grid is sized for the launch's longest unit)
+  const int tid = threadIdx.x, part = tid % LPR;
+  float* At = a_tok + un.in_row;
+  float* Ce = c_edge + un.in_row;
+  // nearly always no token of the span is marked: one look at all of them (bit k: token t0 + tid + 256 k)
+  uint32_t marks = 0;
+#pragma unroll
+  for (int k = 0; k < kRedoSpan / kThreads; ++k) {
+    const int t = t0 + tid + k * kThreads;
+    if (t < t1) marks |= (__float_as_uint(At[t]) >> 31) << k;
+  }
+  if (!__syncthreads_or((int)marks)) return;
+  if (tid == 0) sm_n = 0;
+  __syncthreads();
+  for (int k = 0; k < kRedoSpan / kThreads; ++k) {           // (any order: tokens are independent)
+    if ((marks >> k) & 1) sm_list[atomicAdd(&sm_n, 1)] = t0 + tid + k * kThreads;
+  }
+  __syncthreads();
+  const int n_marked = sm_n;
+  const int R = sh.R;
+  const float Rf = (float)R;
+  const uint16_t* Kg = K + (size_t)un.in_row * D;
+  const uint16_t* Vg = V + (size_t)un.in_row * D;
+  const uint16_t* Qu = Q + (size_t)un.index * R * D + 8 * part;
+  const uint16_t* Oh = o_hi + (size_t)un.index * R * D + 8 * part;
+  const uint16_t* Ol = o_lo + (size_t)un.index * R * D + 8 * part;
+  const float* cr = c_row + (size_t)un.index * R;
+
+  {
+    for (int m = 0; m < n_marked; ++m) {
+      const int t = sm_list[m];
+      const bool has_next = t + 1 < un.len;
+      float lc = 0.f, lcn = 0.f;
+      {
+        float ic = 1.f, icn = 1.f;
+        if (COUNTS) {
+          const float c = (float)counts_in[un.in_row + t];
+          const float cn = has_next ? (float)counts_in[un.in_row + t + 1] : 1.f;
+          lc = __builtin_amdgcn_logf(c);                     // (base 2)
+          lcn = __builtin_amdgcn_logf(cn);
+          ic = __builtin_amdgcn_rcpf(c);
+          icn = __builtin_amdgcn_rcpf(cn);
+        }
+        for (int i = tid; i < 4 * D; i += kThreads) {
+          const int which = i / D, d = i % D;
+          const uint16_t* src = (which < 2 ? Kg : Vg) + (size_t)(t + (which & 1)) * D + d;
+          float x = (which & 1) && !has_next ? 0.f : bf16_lo((uint32_t)*src);
+          if (which >= 2) x *= (which & 1) ? icn : ic;
+          sm_row[which][d] = x;
+        }
+      }
+      __syncthreads();
+      float kt[8], kn[8], vt[8], vn[8];     // this lane's eight dimensions of the four rows
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        kt[i] = sm_row[0][8 * part + i];
+        kn[i] = sm_row[1][8 * part + i];
+        vt[i] = sm_row[2][8 * part + i];
+        vn[i] = sm_row[3][8 * part + i];
+      }
+      float sumA = 0.f, sumC = 0.f;
+#pragma unroll 4
+      for (int q0 = 0; q0 < R; q0 += RPP) {
+        const int q = q0 + tid / LPR;
+        const bool ok = q < R;              // (uniform over the lanes of a row, not over the wavefront: no branch around the sums)
+        const int qc = ok ? q : 0;
+        float qv[8], h[8], l[8];
+        Piece<uint16_t>::unpack(*reinterpret_cast<const uint4*>(Qu + (size_t)qc * D), qv);
+        Piece<uint16_t>::unpack(*reinterpret_cast<const uint4*>(Oh + (size_t)qc * D), h);
+        Piece<uint16_t>::unpack(*reinterpret_cast<const uint4*>(Ol + (size_t)qc * D), l);
+        float e = 0.f, en = 0.f, sA = 0.f, sC = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          e = fmaf(qv[i], kt[i], e);
+          en = fmaf(qv[i], kn[i], en);
+          const float m2o = h[i] + l[i];                                 // -2 o
+          const float da = fmaf(0.5f, m2o, vt[i]);                       // v_t - o
+          const float dc = vt[i] + vn[i] + m2o;                          // v_t + v_{t+1} - 2 o
+          sA = fmaf(da, da, sA);
+          sC = fmaf(dc, dc, sC);
+        }
+        e = row_group_sum<LPR>(e);
+        en = row_group_sum<LPR>(en);
+        sA = row_group_sum<LPR>(sA);
+        sC = row_group_sum<LPR>(sC);
+        const int lim = last_seen_row(sh.causal, un.len, qc);
+        float a = ex2(fmaf(e, sh.scale_log2, lc - cr[qc]));              // alpha / R
+        float a_n = ex2(fmaf(en, sh.scale_log2, lcn - cr[qc]));
+        if (!ok || (sh.causal > 0 && t > lim)) a = 0.f;
+        if (!has_next || (sh.causal > 0 && t + 1 > lim)) a_n = 0.f;
+        sumA = fmaf(a * fabsf(fmaf(-2.f * Rf, a, 1.f)), __builtin_amdgcn_sqrtf(sA), sumA);
+        sumC = fmaf(a * a_n, __builtin_amdgcn_sqrtf(sC), sumC);
+      }
+      sm_sum[0][tid] = part == 0 ? sumA : 0.f;   // (all lanes of a row hold the same sums)
+      sm_sum[1][tid] = part == 0 ? sumC : 0.f;
+      __syncthreads();
+      for (int s2 = kThreads / 2; s2 > 0; s2 /= 2) {
+        if (tid < s2) {
+          sm_sum[0][tid] += sm_sum[0][tid + s2];
+          sm_sum[1][tid] += sm_sum[1][tid + s2];
+        }
+        __syncthreads();
+      }
+      if (tid == 0) {
+        At[t] = sm_sum[0][0];
+        Ce[t] = has_next ? sm_sum[1][0] * Rf : 0.f;
+      }
+      __syncthreads();                      // sm_row and sm_sum are reused by the next token
+    }
   }
 }
 
@@ -507,15 +725,22 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const 
                     const int32_t* counts_in, const float* c_row, float* o_part, uint16_t* o_hi, uint16_t* o_lo,
                     float* oo, float* a_tok, float* c_edge, hipStream_t stream) {
   const dim3 grid(tab.total_chunks), block(kThreads);
+  float* p_part = o_part + (size_t)tab.total_chunks * sh.R * D;   // the weights' sums lie behind the launch's partials
   hipLaunchKernelGGL((pq_out_kernel<D, COUNTS>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
-                     (const uint16_t*)K, (const uint16_t*)V, counts_in, c_row, o_part);
+                     (const uint16_t*)K, (const uint16_t*)V, counts_in, c_row, o_part, p_part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((pq_out_reduce_kernel<D>), dim3(tab.n_units * sh.R), dim3(D), 0, stream, tab, sh, o_part, o_hi,
-                     o_lo, oo);
+  hipLaunchKernelGGL((pq_out_reduce_kernel<D>), dim3(tab.n_units * sh.R), dim3(D), 0, stream, tab, sh, o_part, p_part,
+                     o_hi, o_lo, oo);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((pq_norms_kernel<D, COUNTS>), grid, block, 0, stream, tab, sh, (const uint16_t*)Q,
                      (const uint16_t*)K, (const uint16_t*)V, counts_in, c_row, o_hi, o_lo, oo, a_tok, c_edge);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  int longest = 1;
+  for (int u = 0; u < tab.n_units; ++u) longest = longest > tab.u[u].len ? longest : tab.u[u].len;
+  const dim3 spans(tab.n_units, (longest + kRedoSpan - 1) / kRedoSpan);
+  hipLaunchKernelGGL((pq_redo_kernel<D, COUNTS>), spans, block, 0, stream, tab, sh, (const uint16_t*)Q,
+                     (const uint16_t*)K, (const uint16_t*)V, counts_in, c_row, o_hi, o_lo, a_tok, c_edge);
   return hipGetLastError();
 }
 

@@ -13,8 +13,13 @@
 // value V[t] / c_t.
 //
 // Three kernels after the two score sweeps (which leave the normaliser c[q] of every row):
-//   pq_out_f32_kernel     o_part[chunk, q, :] = sum over the chunk's tokens of (alpha_t^{(q)} / R) V[t]
-//   pq_reduce_f32_kernel  o^{(q)} = R * sum of the chunk partials, in chunk order
+//   pq_out_f32_kernel     o_part[chunk, q, :] = sum over the chunk's tokens of (alpha_t^{(q)} / R) V[t], and
+//                         p_part[chunk, q] = the sum of the same weights alpha_t^{(q)} / R
+//   pq_reduce_f32_kernel  o^{(q)} = (sum of the o_part) / (sum of the p_part), in chunk order: a convex combination
+//                         of the Values with the weights as they were rounded, so that where a row puts nearly all
+//                         its weight on one token, o - v_t is as accurate as the small weights of the others
+//                         (dividing by the weights' nominal sum 1 / R leaves the rounding of the normaliser c[q],
+//                         which grows with the logits, times ||v_t||)
 //   pq_norms_f32_kernel   A_t and C_t of the chunk's tokens
 // A workgroup walks its chunk in tiles of 32 tokens held in LDS and takes the query rows eight at a time:
 // thread (q, t) = (tid / 32, tid % 32) owns one (query row, token) pair.  Sums run in fixed orders; no atomics.
@@ -74,14 +79,14 @@ __global__ __launch_bounds__(kThreads) void pq_out_f32_kernel(const UnitTable ta
                                                               const float* __restrict__ V,
                                                               const int32_t* __restrict__ counts_in,
                                                               const float* __restrict__ c_row,
-                                                              float* __restrict__ o_part) {
+                                                              float* __restrict__ o_part, float* __restrict__ p_part) {
   constexpr int S = Lds<D>::STRIDE;
   constexpr int DPT = D / kTile;                 // output dimensions per thread
   __shared__ float sm_lc[kTile + 1], sm_ic[kTile + 1];
   __shared__ __attribute__((aligned(16))) float sm_k[kTile * S];
   __shared__ __attribute__((aligned(16))) float sm_v[kTile * S];
   __shared__ __attribute__((aligned(16))) float sm_q[kQB * S];
-  __shared__ float sm_p[kQB][kTile];
+  __shared__ float2 sm_p[kQB][kTile];            // (alpha / R, the same divided by the row's cardinality)
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -104,6 +109,7 @@ __global__ __launch_bounds__(kThreads) void pq_out_f32_kernel(const UnitTable ta
     float acc[DPT];
 #pragma unroll
     for (int i = 0; i < DPT; ++i) acc[i] = 0.f;
+    float wsum = 0.f;                             // (every thread of the row adds the same weights in the same order)
     for (int tb = t0; tb < t1; tb += kTile) {
       __syncthreads();                            // the tile before has been used up
       load_rows<D>(sm_k, Kg, tb, kTile, t1, tid);
@@ -112,35 +118,43 @@ __global__ __launch_bounds__(kThreads) void pq_out_f32_kernel(const UnitTable ta
       __syncthreads();
       const int t = tb + tl;
       const float x = dot_rows<D>(sm_q + ql * S, sm_k + tl * S);
-      // (alpha / R) / c: the row's weight for the Value SUM V[t]
-      sm_p[ql][tl] = (t < t1 && t <= lim) ? __builtin_amdgcn_exp2f(fmaf(x, sh.scale_log2, sm_lc[tl] - cq)) * sm_ic[tl] : 0.f;
+      // alpha / R, and (alpha / R) / c: the row's weight for the Value SUM V[t]
+      const float w = (t < t1 && t <= lim) ? __builtin_amdgcn_exp2f(fmaf(x, sh.scale_log2, sm_lc[tl] - cq)) : 0.f;
+      sm_p[ql][tl] = make_float2(w, w * sm_ic[tl]);
       __syncthreads();
 #pragma unroll 4
       for (int r = 0; r < kTile; ++r) {
-        const float p = sm_p[ql][r];
+        const float2 p = sm_p[ql][r];
+        wsum += p.x;
 #pragma unroll
-        for (int i = 0; i < DPT; ++i) acc[i] = fmaf(p, sm_v[r * S + tl + kTile * i], acc[i]);
+        for (int i = 0; i < DPT; ++i) acc[i] = fmaf(p.y, sm_v[r * S + tl + kTile * i], acc[i]);
       }
     }
     if (q < R) {
       float* dst = o_part + ((size_t)(un.chunk_base + chunk) * R + q) * D;
 #pragma unroll
       for (int i = 0; i < DPT; ++i) dst[tl + kTile * i] = acc[i];
+      if (tl == 0) p_part[(size_t)(un.chunk_base + chunk) * R + q] = wsum;
     }
   }
 }
 
-// o[unit, q, :] = R * (sum of the chunk partials, in chunk order).  One workgroup of D threads per (unit, row).
+// o[unit, q, :] = (sum of the chunk partials) / (sum of their weights), both in chunk order.  One workgroup of D
+// threads per (unit, row).
 template <int D>
 __global__ __launch_bounds__(D) void pq_reduce_f32_kernel(const UnitTable tab, const Shape sh,
-                                                          const float* __restrict__ o_part, float* __restrict__ o) {
+                                                          const float* __restrict__ o_part,
+                                                          const float* __restrict__ p_part, float* __restrict__ o) {
   const int R = sh.R;
   const Unit un = tab.u[blockIdx.x / R];
   const int q = blockIdx.x % R;
   const int d = threadIdx.x;
-  float s = 0.f;
-  for (int c = 0; c < un.n_chunks; ++c) s += o_part[((size_t)(un.chunk_base + c) * R + q) * D + d];
-  o[((size_t)un.index * R + q) * D + d] = s * (float)R;
+  float s = 0.f, w = 0.f;
+  for (int c = 0; c < un.n_chunks; ++c) {
+    s += o_part[((size_t)(un.chunk_base + c) * R + q) * D + d];
+    w += p_part[(size_t)(un.chunk_base + c) * R + q];
+  }
+  o[((size_t)un.index * R + q) * D + d] = s / w;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -243,10 +257,13 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, const float* Q, const
                     const int32_t* counts_in, const float* c_row, float* o_part, float* o, float* a_tok, float* c_edge,
                     hipStream_t stream) {
   const dim3 grid(tab.total_chunks), block(kThreads);
-  hipLaunchKernelGGL((pq_out_f32_kernel<D>), grid, block, 0, stream, tab, sh, Q, K, V, counts_in, c_row, o_part);
+  float* p_part = o_part + (size_t)tab.total_chunks * sh.R * D;   // the weights' sums lie behind the launch's partials
+  hipLaunchKernelGGL((pq_out_f32_kernel<D>), grid, block, 0, stream, tab, sh, Q, K, V, counts_in, c_row, o_part,
+                     p_part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((pq_reduce_f32_kernel<D>), dim3(tab.n_units * sh.R), dim3(D), 0, stream, tab, sh, o_part, o);
+  hipLaunchKernelGGL((pq_reduce_f32_kernel<D>), dim3(tab.n_units * sh.R), dim3(D), 0, stream, tab, sh, o_part, p_part,
+                     o);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((pq_norms_f32_kernel<D>), grid, block, 0, stream, tab, sh, Q, K, V, counts_in, c_row, o, a_tok,
                      c_edge);

@@ -5,8 +5,9 @@ Bars: selected edges, slot maps and counts bit-exact; merged K / V within 1e-2 (
 kvs_merge_compact_norms with fp32 I/O) relative L2 error per output row; A_t and C_t within TOL_NORMS
 relative.  TOL_NORMS: the kernels form alpha in fp32 (as the score sweeps, 3e-5), the attention outputs
 o^{(q)} and the products v.o from bf16 operand pairs hi + lo (2^-17 relative per term), and the squared
-distances by the expansion ||v||^2 - 2 v.o + ||o||^2 in fp32, whose cancellation is mild because
-||o|| is well below ||v|| on every workload here.
+distances by the expansion ||v||^2 - 2 v.o + ||o||^2 in fp32 where that loses less than four bits to
+cancellation, else from differences (test_sensitivity_concentrated_rows plants the cases that need it).
+Two absolute terms join the bar where the relative one says nothing: see TOL_ALPHA_ROW and TOL_WEIGHT.
 """
 
 import numpy as np
@@ -22,9 +23,25 @@ pytestmark = pytest.mark.gpu
 
 TOL_NORMS = 5e-5     # measured: at most 1.1e-5 over the cases below
 # A_t carries the factor |1 - 2 alpha|, which vanishes at alpha = 1/2: there the rounding of a row's own attention
-# weight (fp32 softmax, relative 1e-6) is all that is left of A_t, whatever the arithmetic.  Such a row's share is
-# therefore held to its size without that factor, alpha ||v - o||, times this bound on alpha's relative error.
+# weight is all that is left of A_t, whatever the arithmetic.  Such a row's share is therefore held to its size
+# without that factor, alpha ||v - o||, times this bound on alpha's relative error.  The weights are exp2 of fp32
+# logits, so their relative error is an absolute error of the logit, a few units in its last place: the bound holds
+# for base-2 logits up to 32 in size (the generated workloads reach 20 to 36) and grows in proportion beyond
+# (alpha_row_tol below; test_sensitivity_concentrated_rows reaches 150).
 TOL_ALPHA_ROW = 4e-6
+# The bf16 kernels hand o^{(q)} on as a bf16 pair hi + lo, relative 2^-18 per component.  Where a row puts nearly
+# all its weight on one token, o comes close to v_t, and that rounding bounds ||v_t - o|| (and ||v_t + v_{t+1} - 2 o||)
+# from below: an absolute error of up to 2^-18 ||o||, about alpha_t ||v_t|| there, which the bars admit per query
+# row.  (The weights' own rounding does not show: o is formed as a convex combination with the rounded weights.)
+TOL_WEIGHT = 2.0 ** -18
+
+
+def alpha_row_tol(Q, K, counts, head_dim):
+    """TOL_ALPHA_ROW, scaled up where the base-2 logits exceed 32 in size."""
+    logit2 = (Q.reshape(-1, head_dim).astype(np.float64) @ K.astype(np.float64).T) / np.sqrt(head_dim) / np.log(2.0)
+    if counts is not None:
+        logit2 = logit2 + np.log2(counts.astype(np.float64))[None, :]
+    return TOL_ALPHA_ROW * max(1.0, float(np.abs(logit2).max()) / 32.0)
 
 
 def per_query_buffers(batch):
@@ -80,6 +97,11 @@ def test_sensitivity_matches_oracle(base, D, G, W, lens, dtype, causal):
     if w.mean_count > 0:
         w = w.scaled(fresh_tail=max(W, 8), n_sink=2)  # short units too have rows that stand for several tokens
     units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
+    check_sensitivity(w, units, lens, D, G, W, dtype, causal)
+
+
+def check_sensitivity(w, units, lens, D, G, W, dtype, causal):
+    """kvs_sensitivity(_counts) on `units` against the oracle."""
     batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype=dtype, n_sink=w.n_sink, gap_rows=3,
                         causal=causal)
     cw = W if causal else 0
@@ -110,20 +132,75 @@ def test_sensitivity_matches_oracle(base, D, G, W, lens, dtype, causal):
         for a_q in rows:
             size += a_q * np.linalg.norm(V64 - a_q @ V64, axis=1)
         size /= rows.shape[0]
-        den = A_ref + (TOL_ALPHA_ROW / TOL_NORMS) * size
+        vnorm = np.linalg.norm(V64, axis=1)
+        conc = np.mean(rows * rows, axis=0) * vnorm   # mean over the rows of alpha^2 ||v_t||
+        den = A_ref + (alpha_row_tol(u.Q, u.K, u.counts, D) / TOL_NORMS) * size + (TOL_WEIGHT / TOL_NORMS) * conc
+        concC = 2.0 * np.mean(rows[:, :-1] * rows[:, 1:] * (rows[:, :-1] * vnorm[:-1] + rows[:, 1:] * vnorm[1:]), axis=0)
         if n == 1:
             # a unit's only token has alpha = 1 and o = v: A is exactly zero, and what the kernel finds is the
             # rounding of o against v
             assert gA[0] <= 1e-5 * np.linalg.norm(V64[0])
             den = np.ones(1)
         eA = np.max(np.abs(gA - A_ref) / den)
-        eC = np.max(np.abs(gC - C_ref) / C_ref) if n > 1 else 0.0
+        eC = np.max(np.abs(gC - C_ref) / (C_ref + (TOL_WEIGHT / TOL_NORMS) * concC)) if n > 1 else 0.0
         assert eA < TOL_NORMS, (i, "A", eA)
         assert eC < TOL_NORMS, (i, "C", eC)
         assert C[r0 + n - 1] == 0.0                  # a unit's last row has no edge
     for i in range(len(units) - 1):                  # rows between units are never touched
         gap0 = p.in_rows[i] + lens[i]
         assert (A[gap0:gap0 + 3] == -7.0).all() and (C[gap0:gap0 + 3] == -7.0).all()
+
+
+def _bf16(x):
+    from workloads import bf16_bits_to_f32, f32_to_bf16_bits
+    return bf16_bits_to_f32(f32_to_bf16_bits(np.asarray(x, dtype=np.float32)))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("counts", [False, True])
+@pytest.mark.parametrize("causal", [False, True])
+def test_sensitivity_concentrated_rows(causal, counts, dtype):
+    """Query rows that put (nearly) all their weight on one token, or share it between two adjacent ones.
+
+    There o^{(q)} comes close to v_t, resp. to the mean of v_t and v_{t+1}, and ||v_t - o||, resp.
+    ||v_t + v_{t+1} - 2 o||, is what is left when terms of size ||v|| cancel: the kernel has to form these norms
+    from differences (the bf16 kernels do so for the tokens they find affected, the fp32 kernels always).  Tokens are planted inside a tile, at a tile's last row (31 rows are put out per tile) and in
+    the unit's last rows; the rows of the second pass (160 query rows) get some as well.
+    """
+    D, G, W, n = 128, 5, 32, 1200
+    base = "stream2560" if counts else "llama8b_8k"
+    w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=1, n_kv_heads=1)
+    if counts:
+        w = w.scaled(fresh_tail=W, n_sink=2)
+    u = generate_unit(w, 0, 0, 0, n=n)
+    # two adjacent tokens with the same Key share a row's weight: alpha = 1/2 each, o = their mean
+    Kd = u.K.copy()
+    for t in (200, 216, 929):
+        Kd[t + 1] = Kd[t]
+    u.K = Kd
+    K, Q = u.K.astype(np.float64), u.Q.reshape(G * W, D).astype(np.float64).copy()
+    scale = 1.0 / np.sqrt(D)
+
+    def aim(row, t, gap, pair=False):
+        """Query row `row` := the multiple of (K^T K / n)^{-1} k_t whose logit on token t (and on t + 1, for a pair of
+        equal Keys) lies `gap` above that of every other token (natural-log units)."""
+        u_ = np.linalg.solve(K.T @ K / n + 1e-3 * np.eye(D), K[t])
+        logit = K @ u_ * scale
+        others = np.delete(logit, [t, t + 1] if pair else [t])
+        assert logit[t] > others.max()
+        Q[row] = _bf16(gap / (logit[t] - others.max()) * u_)
+
+    aim(3, 500, 16.0)            # inside a tile: alpha within 1e-4 of 1
+    aim(40, 30, 14.0)            # the last row a tile puts out
+    aim(77, 31, 18.0)            # the first row of the next tile
+    aim(130, 640, 9.0)           # a row of the second pass; alpha some 1e-2 below 1
+    aim(159, n - 1, 16.0)        # the unit's last token (no edge behind it)
+    aim(100, n - 2, 7.0)
+    aim(8, 200, 16.0, pair=True)
+    aim(140, 216, 16.0, pair=True)     # second pass
+    aim(64, 929, 15.0, pair=True)      # the pair straddles two tiles (929 = 31 * 29 + 30)
+    u.Q = Q.reshape(G, W, D).astype(np.float32)
+    check_sensitivity(w, [u], [n], D, G, W, dtype, causal)
 
 
 @pytest.mark.parametrize("rule", ["hessian", "diagonal"])
