@@ -1006,8 +1006,10 @@ def test_step_passthrough_and_single_token_units():
         assert (cnt[r0:r0 + u.n] == 1).all()
 
 
-def test_step_at_the_maximum_length():
-    """One unit of KVS_MAX_LEN = 2^22 rows (bf16, head dim 64, 16 query rows) merged to a quarter.  At this length
+@pytest.mark.parametrize("dtype,D", [("bf16", 64), ("f32", 128)])
+def test_step_at_the_maximum_length(dtype, D):
+    """One unit of KVS_MAX_LEN = 2^22 rows (16 query rows) merged to a quarter: bf16 with head dim 64, and fp32 with
+    head dim 128, the longest rows there are (512 bytes: the last row ends one byte short of 2^31).  At this length
     neighbouring edge scores at the budget boundary differ by less than fp32 resolves, so the selected set is not
     unique: it is checked for validity (the right number of edges, none of the selected scores above an
     unselected one beyond the tolerance of alpha_bar), slot map and cardinalities must follow from it exactly,
@@ -1016,12 +1018,12 @@ def test_step_at_the_maximum_length():
     import paper_2603_00907_amd as kvs
     from helpers import to_device
     from workloads import gaussian_unit
-    n, D, G, W, n_sink = 1 << 22, 64, 4, 4, 32
+    n, G, W, n_sink = 1 << 22, 4, 4, 32
     B = n // 4
-    Q, K, V = gaussian_unit(1, n, D, G, W, "bf16")
-    p = kvs.Problem(lens=[n], budgets=[B], group=G, window=W, head_dim=D, dtype="bf16", n_sink=n_sink)
-    Kd, Vd, Qd = to_device(K, "bf16"), to_device(V, "bf16"), to_device(Q.reshape(1, G * W, D), "bf16")
-    K_out = torch.empty((B, D), dtype=torch.bfloat16, device="cuda")
+    Q, K, V = gaussian_unit(1, n, D, G, W, dtype)
+    p = kvs.Problem(lens=[n], budgets=[B], group=G, window=W, head_dim=D, dtype=dtype, n_sink=n_sink)
+    Kd, Vd, Qd = to_device(K, dtype), to_device(V, dtype), to_device(Q.reshape(1, G * W, D), dtype)
+    K_out = torch.empty((B, D), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda")
     V_out = torch.empty_like(K_out)
     counts = torch.empty(B, dtype=torch.int32, device="cuda")
     mask_d = torch.empty(n, dtype=torch.uint8, device="cuda")
@@ -1047,7 +1049,7 @@ def test_step_at_the_maximum_length():
     # every merged Value row is the sum of its run
     Vo = from_device(V_out)
     want_v = np.add.reduceat(V.astype(np.float64), first, axis=0)
-    assert rel_err_rows(Vo, want_v) <= TOL_KV["bf16"]
+    assert rel_err_rows(Vo, want_v) <= TOL_KV[dtype]
     # merged Keys on windows of whole slots: head of the cache, two places inside, the tail
     Ko = from_device(K_out)
     for s0 in (0, B // 3, (2 * B) // 3 + 7, B - 700):
@@ -1056,7 +1058,7 @@ def test_step_at_the_maximum_length():
         ref = O.merge_compact(K[a:b], V[a:b], alpha_bar[a:b], o_bar, mask[a:b] * (np.arange(a, b) < b - 1),
                               slot[a:b] - s0)
         assert (cnt[s0:s1] == ref.counts).all()
-        assert rel_err_rows(Ko[s0:s1], ref.K_out) <= TOL_KV["bf16"], s0
+        assert rel_err_rows(Ko[s0:s1], ref.K_out) <= TOL_KV[dtype], s0
         single = ref.n_rows == 1
         assert (Ko[s0:s1][single] == ref.K_out[single]).all()
 
@@ -1078,9 +1080,26 @@ def test_step_at_the_maximum_length():
     ("stream2560", "f32", 64, 2, 5, [2300], None),
 ])
 def test_decode_attention_matches_oracle(base, dtype, D, G, W, lens, path):
-    import torch
     w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=len(lens), n_kv_heads=1)
     units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
+    check_decode(units, dtype, D, G, W, path)
+
+
+@pytest.mark.parametrize("dtype,G,path", [("f32", 2, None), ("bf16", 8, "mfma"), ("bf16", 2, "valu")])
+def test_decode_attention_at_the_maximum_length(dtype, G, path):
+    """A cache of KVS_MAX_LEN = 2^22 rows with head dim 128 (fp32: the longest rows there are), with cardinalities."""
+    from workloads import gaussian_unit
+    from workloads.generator import UnitInputs
+    n, D = 1 << 22, 128
+    Q, K, V = gaussian_unit(3, n, D, G, 1, dtype, k_scale=1.0)
+    counts = np.random.default_rng(5).integers(1, 9, n).astype(np.int32)
+    u = UnitInputs(layer=0, seq=0, head=0, attempt=0, n=n, budget=n, rho=0.0, Q=Q, K=K, V=V, counts=counts)
+    check_decode([u], dtype, D, G, 1, path)
+
+
+def check_decode(units, dtype, D, G, W, path):
+    import torch
+    lens = [u.n for u in units]
     batch = DeviceBatch(units, group=G, window=W, head_dim=D, dtype=dtype, n_sink=0, budgets=lens, gap_rows=2)
     p = batch.problem
     R = G * W

@@ -151,6 +151,19 @@ def check_sensitivity(w, units, lens, D, G, W, dtype, causal):
         assert (A[gap0:gap0 + 3] == -7.0).all() and (C[gap0:gap0 + 3] == -7.0).all()
 
 
+@pytest.mark.parametrize("dtype,G,W", [("bf16", 4, 1), ("f32", 1, 2)])
+def test_sensitivity_at_the_maximum_length(dtype, G, W):
+    """One unit of KVS_MAX_LEN = 2^22 rows, head dim 128 (with fp32 the longest rows there are: the last one ends one
+    byte short of 2^31), few query rows so that the oracle stays quick; every A_t, C_t and alpha_bar is compared."""
+    from workloads import gaussian_unit
+    from workloads.generator import UnitInputs
+    n, D = 1 << 22, 128
+    Q, K, V = gaussian_unit(2, n, D, G, W, dtype, k_scale=1.0)
+    u = UnitInputs(layer=0, seq=0, head=0, attempt=0, n=n, budget=n, rho=0.0, Q=Q, K=K, V=V)
+    w = variant("llama8b_8k", dtype=dtype, head_dim=D, group=G, window=W, n_seq=1, n_kv_heads=1)
+    check_sensitivity(w, [u], [n], D, G, W, dtype, False)
+
+
 def _bf16(x):
     from workloads import bf16_bits_to_f32, f32_to_bf16_bits
     return bf16_bits_to_f32(f32_to_bf16_bits(np.asarray(x, dtype=np.float32)))
