@@ -669,7 +669,6 @@ __global__ __launch_bounds__(kThreads) void pq_redo_kernel(
         vn[i] = sm_row[3][8 * part + i];
       }
       float sumA = 0.f, sumC = 0.f;
-#pragma unroll 4
       for (int q0 = 0; q0 < R; q0 += RPP) {
         const int q = q0 + tid / LPR;
         const bool ok = q < R;              // (uniform over the lanes of a row, not over the wavefront: no branch around the sums)
