@@ -63,6 +63,12 @@ __device__ __forceinline__ float min3(float a, float b, float c) {
   return r;
 }
 
+// c + a.lo * b.lo + a.hi * b.hi for two packed bf16 pairs (v_dot2c_f32_bf16)
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+}
+
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4& u) { return __builtin_bit_cast(bf16x8, u); }
 
 // eight floats -> bf16 operand (round to nearest even)
@@ -484,15 +490,13 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
         const int rn = min(r + 1, kTile - 1);
         float s_rr = 0.f, s_rn = 0.f;
 #pragma unroll
-        for (int x = 0; x < PPT; ++x) {
-          float a[8], b[8];
-          Piece<uint16_t>::unpack(TL::piece_at(sm_v[buf], r, part * PPT + x), a);
-          Piece<uint16_t>::unpack(TL::piece_at(sm_v[buf], rn, part * PPT + x), b);
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            s_rr = fmaf(a[i], a[i], s_rr);
-            s_rn = fmaf(a[i], b[i], s_rn);
-          }
+        for (int x = 0; x < PPT; ++x) {           // (two bf16 products per instruction, added in fp32)
+          const uint4 a = TL::piece_at(sm_v[buf], r, part * PPT + x);
+          const uint4 b = TL::piece_at(sm_v[buf], rn, part * PPT + x);
+          s_rr = dot2(a.x, a.x, s_rr); s_rn = dot2(a.x, b.x, s_rn);
+          s_rr = dot2(a.y, a.y, s_rr); s_rn = dot2(a.y, b.y, s_rn);
+          s_rr = dot2(a.z, a.z, s_rr); s_rn = dot2(a.z, b.z, s_rn);
+          s_rr = dot2(a.w, a.w, s_rr); s_rn = dot2(a.w, b.w, s_rn);
         }
         s_rr = row_group_sum<8>(s_rr);
         s_rn = row_group_sum<8>(s_rn);
