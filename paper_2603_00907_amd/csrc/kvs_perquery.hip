@@ -13,7 +13,8 @@
 //                         Both products run on v_mfma_f32_32x32x16_bf16.  The contraction over tokens needs
 //                         V with the token index along the MFMA k dimension; a 32x32 block of the V tile is
 //                         turned by one more MFMA against an identity operand (exact in bf16), which leaves it
-//                         in the accumulator layout that IS the k-major operand layout of the next product.
+//                         in the accumulator layout that IS the k-major operand layout of the next product
+//                         (one block per wavefront, shared through LDS).
 //                         P enters as a bf16 pair hi + lo, so that the rounding of P to bf16 does not limit
 //                         the accuracy of o; the sum of the weights, as the pairs carry them, is kept beside it.
 //                         Chunk partials go to memory and are added in chunk order.
@@ -171,6 +172,7 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
   __shared__ __attribute__((aligned(16))) unsigned char sm_v[2][TL::BYTES];
   __shared__ __attribute__((aligned(16))) float sm_lc[2][kTile], sm_ic[2][kTile];   // COUNTS: log2 c and 1 / c of the tile's rows
   __shared__ __attribute__((aligned(16))) float sm_cc[2][kTile];                    // COUNTS: c itself
+  __shared__ uint4 sm_vt[2][DB][2][kWave];   // the V tile's blocks turned token-major: two operands per lane and block
 
   const int ui = find_unit(tab, blockIdx.x);
   const Unit un = tab.u[ui];
@@ -238,6 +240,19 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
         rv = TL::load(Vg + (size_t)tile_base(jn) * TL::ROWB, tid);
         asm volatile("" ::: "memory");        // issue them here: sunk below the products they would be waited for at once
       }
+      // The block V[tile rows, 32 w .. 32 w + 31] into the token-major operand layout, by wavefront w for all four
+      // (every wavefront turning all blocks itself costs six more MFMAs and 48 conversions per tile and wavefront):
+      // one product against the identity (exact: the values are bf16 numbers) leaves it in the accumulator layout,
+      // which is the k-major operand layout of the product with P below.
+      if (wave < DB) {
+        f32x16 y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::operand(sm_v[buf], col, 2 * wave, half), ident[0], zero, 0, 0, 0);
+        y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::operand(sm_v[buf], col, 2 * wave + 1, half), ident[1], y, 0, 0, 0);
+        float yf[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) yf[v] = y[v];
+        sm_vt[buf][wave][0][lane] = __builtin_bit_cast(uint4, pack8(yf));
+        sm_vt[buf][wave][1][lane] = __builtin_bit_cast(uint4, pack8(yf + 8));
+      }
       // logits of the tile against this wavefront's 32 query rows
       f32x16 acc = zero;
 #pragma unroll
@@ -287,18 +302,10 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) wsum += pw[v];
       }
-      // (taking all four blocks of V through the identity first, to run them beside the exponentials and to
-      // have four independent accumulators in the products below, was measured 6 % slower: 64 more live
-      // registers)
+      __syncthreads();                      // the turned blocks are in place
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        // the block V[tile rows, 32 db .. 32 db + 31] into the same (token-major) accumulator layout
-        f32x16 y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::operand(sm_v[buf], col, 2 * db, half), ident[0], zero, 0, 0, 0);
-        y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(TL::operand(sm_v[buf], col, 2 * db + 1, half), ident[1], y, 0, 0, 0);
-        float yf[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) yf[v] = y[v];
-        const bf16x8 vt0 = pack8(yf), vt1 = pack8(yf + 8);     // exact: the values are bf16 numbers
+        const bf16x8 vt0 = as_bf16x8(sm_vt[buf][db][0][lane]), vt1 = as_bf16x8(sm_vt[buf][db][1][lane]);
         accO[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt0, ph[0], accO[db], 0, 0, 0);
         accO[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt1, ph[1], accO[db], 0, 0, 0);
         accO[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt0, pl[0], accO[db], 0, 0, 0);
