@@ -343,6 +343,7 @@ __global__ __launch_bounds__(D) void pq_out_reduce_kernel(const UnitTable tab, c
   const int q = blockIdx.x % R;
   const int d = threadIdx.x;
   float s = 0.f, w = 0.f;
+#pragma unroll 8                            // (the loads of eight chunks in flight; the sums stay in chunk order)
   for (int c = 0; c < un.n_chunks; ++c) {
     s += o_part[((size_t)(un.chunk_base + c) * R + q) * D + d];
     w += p_part[(size_t)(un.chunk_base + c) * R + q];
@@ -600,7 +601,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
 // as a sum of squared differences: ||v_t - o||^2 from v_t and the stored pair -2 o = hi + lo, likewise
 // ||v_t + v_{t+1} - 2 o||^2.  One workgroup per span of kRedoSpan tokens; the span's marked tokens are listed and
 // taken in turn: D / 8 adjacent lanes share a query row, eight dimensions each (one round of coalesced loads per row), the
-// rows' terms are added per lane group in row order and the groups in a fixed tree order.  Every marked token leaves
+// rows' terms are added per lane group in row order and the groups in a fixed butterfly order.  Every marked token leaves
 // with a non-negative A_t, so no mark outlives this kernel.
 template <int D, bool COUNTS>
 __global__ __launch_bounds__(kThreads) void pq_redo_kernel(
@@ -613,7 +614,7 @@ __global__ __launch_bounds__(kThreads) void pq_redo_kernel(
   __shared__ int sm_list[kRedoSpan];
   __shared__ int sm_n;
   __shared__ float sm_row[4][D];            // k_t, k_{t+1}, v_t, v_{t+1} (the Values divided by their cardinalities)
-  __shared__ float sm_sum[2][kThreads];
+  __shared__ float sm_sum[2][kWaves];
   static_assert(kRedoSpan / kThreads <= 32, "one bit per token and thread");
 
   const Unit un = tab.u[blockIdx.x];
@@ -662,12 +663,16 @@ __global__ __launch_bounds__(kThreads) void pq_redo_kernel(
           ic = __builtin_amdgcn_rcpf(c);
           icn = __builtin_amdgcn_rcpf(cn);
         }
-        for (int i = tid; i < 4 * D; i += kThreads) {
-          const int which = i / D, d = i % D;
-          const uint16_t* src = (which < 2 ? Kg : Vg) + (size_t)(t + (which & 1)) * D + d;
-          float x = (which & 1) && !has_next ? 0.f : bf16_lo((uint32_t)*src);
-          if (which >= 2) x *= (which & 1) ? icn : ic;
-          sm_row[which][d] = x;
+        if (tid < 4 * LPR) {                  // one 16-byte piece per thread
+          const int which = tid / LPR, pc = tid % LPR;
+          float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          if (!(which & 1) || has_next) {
+            const uint16_t* src = (which < 2 ? Kg : Vg) + (size_t)(t + (which & 1)) * D + 8 * pc;
+            Piece<uint16_t>::unpack(*reinterpret_cast<const uint4*>(src), x);
+          }
+          const float f = which < 2 ? 1.f : ((which & 1) ? icn : ic);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) sm_row[which][8 * pc + i] = x[i] * f;
         }
       }
       __syncthreads();
@@ -680,50 +685,70 @@ __global__ __launch_bounds__(kThreads) void pq_redo_kernel(
         vn[i] = sm_row[3][8 * part + i];
       }
       float sumA = 0.f, sumC = 0.f;
-      for (int q0 = 0; q0 < R; q0 += RPP) {
-        const int q = q0 + tid / LPR;
-        const bool ok = q < R;              // (uniform over the lanes of a row, not over the wavefront: no branch around the sums)
-        const int qc = ok ? q : 0;
-        float qv[8], h[8], l[8];
-        Piece<uint16_t>::unpack(*reinterpret_cast<const uint4*>(Qu + (size_t)qc * D), qv);
-        Piece<uint16_t>::unpack(*reinterpret_cast<const uint4*>(Oh + (size_t)qc * D), h);
-        Piece<uint16_t>::unpack(*reinterpret_cast<const uint4*>(Ol + (size_t)qc * D), l);
-        float e = 0.f, en = 0.f, sA = 0.f, sC = 0.f;
+      // (four passes of rows per trip, so that their loads are in flight together: the kernel's time is the latency
+      // of these rounds; rows beyond R are computed on row 0's data and dropped)
+      for (int q00 = 0; q00 < R; q00 += 4 * RPP) {
+        uint4 rq[4], rh[4], rl[4];
+        float rc[4];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          e = fmaf(qv[i], kt[i], e);
-          en = fmaf(qv[i], kn[i], en);
-          const float m2o = h[i] + l[i];                                 // -2 o
-          const float da = fmaf(0.5f, m2o, vt[i]);                       // v_t - o
-          const float dc = vt[i] + vn[i] + m2o;                          // v_t + v_{t+1} - 2 o
-          sA = fmaf(da, da, sA);
-          sC = fmaf(dc, dc, sC);
+        for (int u = 0; u < 4; ++u) {
+          const int q = q00 + u * RPP + tid / LPR;
+          const int qc = q < R ? q : 0;
+          rq[u] = *reinterpret_cast<const uint4*>(Qu + (size_t)qc * D);
+          rh[u] = *reinterpret_cast<const uint4*>(Oh + (size_t)qc * D);
+          rl[u] = *reinterpret_cast<const uint4*>(Ol + (size_t)qc * D);
+          rc[u] = cr[qc];
         }
-        e = row_group_sum<LPR>(e);
-        en = row_group_sum<LPR>(en);
-        sA = row_group_sum<LPR>(sA);
-        sC = row_group_sum<LPR>(sC);
-        const int lim = last_seen_row(sh.causal, un.len, qc);
-        float a = ex2(fmaf(e, sh.scale_log2, lc - cr[qc]));              // alpha / R
-        float a_n = ex2(fmaf(en, sh.scale_log2, lcn - cr[qc]));
-        if (!ok || (sh.causal > 0 && t > lim)) a = 0.f;
-        if (!has_next || (sh.causal > 0 && t + 1 > lim)) a_n = 0.f;
-        sumA = fmaf(a * fabsf(fmaf(-2.f * Rf, a, 1.f)), __builtin_amdgcn_sqrtf(sA), sumA);
-        sumC = fmaf(a * a_n, __builtin_amdgcn_sqrtf(sC), sumC);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int q = q00 + u * RPP + tid / LPR;
+          const bool ok = q < R;              // (uniform over the lanes of a row, not over the wavefront: no branch around the sums)
+          const int qc = ok ? q : 0;
+          float qv[8], h[8], l[8];
+          Piece<uint16_t>::unpack(rq[u], qv);
+          Piece<uint16_t>::unpack(rh[u], h);
+          Piece<uint16_t>::unpack(rl[u], l);
+          float e = 0.f, en = 0.f, sA = 0.f, sC = 0.f;
+  #pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            e = fmaf(qv[i], kt[i], e);
+            en = fmaf(qv[i], kn[i], en);
+            const float m2o = h[i] + l[i];                                 // -2 o
+            const float da = fmaf(0.5f, m2o, vt[i]);                       // v_t - o
+            const float dc = vt[i] + vn[i] + m2o;                          // v_t + v_{t+1} - 2 o
+            sA = fmaf(da, da, sA);
+            sC = fmaf(dc, dc, sC);
+          }
+          e = row_group_sum<LPR>(e);
+          en = row_group_sum<LPR>(en);
+          sA = row_group_sum<LPR>(sA);
+          sC = row_group_sum<LPR>(sC);
+          const int lim = last_seen_row(sh.causal, un.len, qc);
+          float a = ex2(fmaf(e, sh.scale_log2, lc - rc[u]));               // alpha / R
+          float a_n = ex2(fmaf(en, sh.scale_log2, lcn - rc[u]));
+          if (!ok || (sh.causal > 0 && t > lim)) a = 0.f;
+          if (!has_next || (sh.causal > 0 && t + 1 > lim)) a_n = 0.f;
+          sumA = fmaf(a * fabsf(fmaf(-2.f * Rf, a, 1.f)), __builtin_amdgcn_sqrtf(sA), sumA);
+          sumC = fmaf(a * a_n, __builtin_amdgcn_sqrtf(sC), sumC);
+        }
       }
-      sm_sum[0][tid] = part == 0 ? sumA : 0.f;   // (all lanes of a row hold the same sums)
-      sm_sum[1][tid] = part == 0 ? sumC : 0.f;
+      if (part != 0) sumA = sumC = 0.f;     // (all lanes of a row hold the same sums: one of them counts)
+#pragma unroll
+      for (int m2 = 32; m2 >= 1; m2 >>= 1) {
+        sumA += __shfl_xor(sumA, m2, kWave);
+        sumC += __shfl_xor(sumC, m2, kWave);
+      }
+      if (tid % kWave == 0) {
+        sm_sum[0][tid / kWave] = sumA;
+        sm_sum[1][tid / kWave] = sumC;
+      }
       __syncthreads();
-      for (int s2 = kThreads / 2; s2 > 0; s2 /= 2) {
-        if (tid < s2) {
-          sm_sum[0][tid] += sm_sum[0][tid + s2];
-          sm_sum[1][tid] += sm_sum[1][tid + s2];
-        }
-        __syncthreads();
-      }
       if (tid == 0) {
-        At[t] = sm_sum[0][0];
-        Ce[t] = has_next ? sm_sum[1][0] * Rf : 0.f;
+        float a = sm_sum[0][0], c = sm_sum[1][0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) { a += sm_sum[0][w]; c += sm_sum[1][w]; }
+        At[t] = a;
+        Ce[t] = has_next ? c * Rf : 0.f;
       }
       __syncthreads();                      // sm_row and sm_sum are reused by the next token
     }
