@@ -29,10 +29,11 @@ TOL_NORMS = 5e-5     # measured: at most 1.1e-5 over the cases below
 # for base-2 logits up to 32 in size (the generated workloads reach 20 to 36) and grows in proportion beyond
 # (alpha_row_tol below; test_sensitivity_concentrated_rows reaches 150).
 TOL_ALPHA_ROW = 4e-6
-# The bf16 kernels hand o^{(q)} on as a bf16 pair hi + lo, relative 2^-18 per component.  Where a row puts nearly
-# all its weight on one token, o comes close to v_t, and that rounding bounds ||v_t - o|| (and ||v_t + v_{t+1} - 2 o||)
-# from below: an absolute error of up to 2^-18 ||o||, about alpha_t ||v_t|| there, which the bars admit per query
-# row.  (The weights' own rounding does not show: o is formed as a convex combination with the rounded weights.)
+# The bf16 kernels hand o^{(q)} on as a bf16 pair hi + lo, relative 2^-18 per component: an absolute error of up to
+# 2^-18 ||o^{(q)}|| in ||v_t - o|| (twice that in ||v_t + v_{t+1} - 2 o||), which the bars admit per query row.  It
+# shows where o comes close to v_t (a row that puts nearly all its weight on one token, or Values that repeat) and
+# the norm itself is small.  (The weights' own rounding does not show: o is formed as a convex combination with the
+# rounded weights.)
 TOL_WEIGHT = 2.0 ** -18
 
 
@@ -132,10 +133,10 @@ def check_sensitivity(w, units, lens, D, G, W, dtype, causal):
         for a_q in rows:
             size += a_q * np.linalg.norm(V64 - a_q @ V64, axis=1)
         size /= rows.shape[0]
-        vnorm = np.linalg.norm(V64, axis=1)
-        conc = np.mean(rows * rows, axis=0) * vnorm   # mean over the rows of alpha^2 ||v_t||
+        onorm = np.linalg.norm(rows @ V64, axis=1)    # ||o^{(q)}|| of every row
+        conc = (rows * onorm[:, None]).mean(axis=0)   # mean over the rows of alpha_t ||o||
         den = A_ref + (alpha_row_tol(u.Q, u.K, u.counts, D) / TOL_NORMS) * size + (TOL_WEIGHT / TOL_NORMS) * conc
-        concC = 2.0 * np.mean(rows[:, :-1] * rows[:, 1:] * (rows[:, :-1] * vnorm[:-1] + rows[:, 1:] * vnorm[1:]), axis=0)
+        concC = 2.0 * (rows[:, :-1] * rows[:, 1:] * onorm[:, None]).mean(axis=0)
         if n == 1:
             # a unit's only token has alpha = 1 and o = v: A is exactly zero, and what the kernel finds is the
             # rounding of o against v
@@ -162,6 +163,29 @@ def test_sensitivity_at_the_maximum_length(dtype, G, W):
     u = UnitInputs(layer=0, seq=0, head=0, attempt=0, n=n, budget=n, rho=0.0, Q=Q, K=K, V=V)
     w = variant("llama8b_8k", dtype=dtype, head_dim=D, group=G, window=W, n_seq=1, n_kv_heads=1)
     check_sensitivity(w, [u], [n], D, G, W, dtype, False)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("counts", [False, True])
+def test_sensitivity_with_values_that_repeat(counts, dtype):
+    """Every token carries the same Value (per token it stands for), so every o^{(q)} equals it and A_t = C_t = 0: all
+    that the kernels may leave is the rounding of o.  In the bf16 kernels every token takes the path that forms its
+    norms from differences (5000 tokens: two of that kernel's spans, the second ragged).  A second unit has two
+    Values that alternate in blocks of 40 tokens: norms of full size beside norms that cancel, in the same tiles."""
+    D, G, W, n = 128, 3, 16, 5000
+    base = "stream2560" if counts else "llama8b_8k"
+    w = variant(base, dtype=dtype, head_dim=D, group=G, window=W, n_seq=2, n_kv_heads=1)
+    if counts:
+        w = w.scaled(fresh_tail=W, n_sink=2)
+    units = [generate_unit(w, 0, s, 0, n=m) for s, m in enumerate([n, 700])]
+    for u, period in zip(units, (0, 40)):
+        c = np.ones(u.n) if u.counts is None else u.counts.astype(np.float64)
+        two = u.V[:2].astype(np.float64) / c[:2, None]
+        which = (np.arange(u.n) // period) % 2 if period else np.zeros(u.n, dtype=np.int64)
+        # (cardinalities are small integers: for a bf16 vector v, c v is exact in fp32 and rounds once to bf16; the
+        # oracle sees the rounded rows, so the per-token Values differ in the last bit and the norms are not exactly 0)
+        u.V = _bf16(two[which] * c[:, None]) if dtype == "bf16" else (two[which] * c[:, None]).astype(np.float32)
+    check_sensitivity(w, units, [n, 700], D, G, W, dtype, False)
 
 
 def _bf16(x):

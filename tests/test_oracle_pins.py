@@ -646,6 +646,53 @@ def test_per_query_norms_special_cases():
     assert np.max(np.abs(A1 - A0) / A0) > 1e-3
 
 
+def test_per_query_norms_closed_forms_of_rows_that_concentrate():
+    """Closed forms.  A row with all its weight on token t has o = v_t: it adds nothing to any A or C.  A row that
+    splits its weight evenly between t and t + 1 has o = (v_t + v_{t+1}) / 2: alpha (1 - 2 alpha) = 0, so it adds
+    nothing to A, and ||v_t + v_{t+1} - 2 o|| = 0, so nothing to C either.  A row with weights (a, 1 - a) on the two
+    adds a |1 - 2a| (1 - a) ||v_t - v_{t+1}|| to A_t, the same with a and 1 - a exchanged to A_{t+1}, and
+    a (1 - a) |1 - 2a| ||v_t - v_{t+1}|| to C_t.  Identical Values give zero norms whatever the weights."""
+    rng = np.random.default_rng(66)
+    n, d = 12, 6
+    V = rng.standard_normal((n, d))
+    big = 60.0                                       # logit gap: the other tokens' weights are below 1e-25
+    K = np.zeros((n, n))
+    np.fill_diagonal(K, 1.0)                         # token t answers to query e_t alone
+    scale = 1.0 / np.sqrt(n)
+
+    def row(weights):
+        """A query whose logits are ln(weight) on the named tokens and -big elsewhere."""
+        e = np.full(n, -big)
+        for t, w in weights.items():
+            e[t] = np.log(w)
+        return e / scale
+
+    t = 4
+    one_hot = row({t: 1.0})
+    halves = row({t: 0.5, t + 1: 0.5})
+    a = 0.8
+    uneven = row({t: a, t + 1: 1 - a})
+    A, C = O.per_query_norms(np.stack([one_hot, halves]), K, V)
+    assert np.max(A) < 1e-15 and np.max(C) < 1e-15     # (the halves' o carries fp64 rounding)
+    A, C = O.per_query_norms(uneven[None, :], K, V)
+    gap = np.linalg.norm(V[t] - V[t + 1])
+    want_A = np.zeros(n)
+    want_A[t] = a * abs(1 - 2 * a) * (1 - a) * gap
+    want_A[t + 1] = (1 - a) * abs(1 - 2 * (1 - a)) * a * gap
+    want_C = np.zeros(n - 1)
+    want_C[t] = a * (1 - a) * abs(1 - 2 * a) * gap
+    np.testing.assert_allclose(A, want_A, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(C, want_C, rtol=1e-12, atol=1e-15)
+    # the three rows together: the mean of their shares
+    A3, C3 = O.per_query_norms(np.stack([one_hot, halves, uneven]), K, V)
+    np.testing.assert_allclose(A3, want_A / 3, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(C3, want_C / 3, rtol=1e-12, atol=1e-15)
+    # identical Values
+    Q = rng.standard_normal((5, n))
+    A, C = O.per_query_norms(Q, K, np.tile(V[0], (n, 1)))
+    assert np.max(A) < 1e-15 and np.max(C) < 1e-15
+
+
 def test_per_query_norms_with_counts():
     """Streaming regime, every query row apart.  Each row by itself is the single-query case with slots of
     cardinality c: the blocks d s_t / d e_j of s_t = alpha_t (V_t / c_t - o) at logits e + ln c, by central
