@@ -180,7 +180,7 @@ class DeviceBatch:
         self.o_bar = torch.full((len(units) + 1, D), -7.0, dtype=torch.float32, device="cuda")
         self.mask = torch.full((p.rows_in + G,), 9, dtype=torch.uint8, device="cuda")
         self.slot = torch.full((p.rows_in + G,), -7, dtype=torch.int32, device="cuda")
-        self.ws = torch.empty(kvs.kvs_workspace_size(p) + 256, dtype=torch.uint8, device="cuda")
+        self.ws = torch.full((kvs.kvs_workspace_size(p) + 256,), 0xFF, dtype=torch.uint8, device="cuda")
         assert self.ws.data_ptr() % 256 == 0
 
     def stream(self) -> int:

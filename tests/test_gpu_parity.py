@@ -814,7 +814,7 @@ def test_step_headline_workload_in_the_launch_configuration_of_the_bench():
     main = torch.cuda.current_stream()
     streams = [main, torch.cuda.Stream()]
     streams[1].wait_stream(main)
-    wss = [torch.empty(kvs.kvs_workspace_size(p), dtype=torch.uint8, device="cuda") for _ in streams]
+    wss = [torch.full((kvs.kvs_workspace_size(p),), 0xFF, dtype=torch.uint8, device="cuda") for _ in streams]
     for c, st in enumerate(streams):
         u0, u1 = c * half, (c + 1) * half
         kvs.kvs_step(p, Q[u0:u1], K[u0 * n:u1 * n], V[u0 * n:u1 * n], K_out[u0 * B:u1 * B], V_out[u0 * B:u1 * B],
@@ -896,7 +896,7 @@ def check_whole_batch_in_one_call(w, layer, sampled_ids):
     counts = torch.empty(p.rows_out, dtype=torch.int32, device="cuda")
     mask = torch.empty(p.rows_in, dtype=torch.uint8, device="cuda")
     slot = torch.empty(p.rows_in, dtype=torch.int32, device="cuda")
-    ws = torch.empty(kvs.kvs_workspace_size(p), dtype=torch.uint8, device="cuda")
+    ws = torch.full((kvs.kvs_workspace_size(p),), 0xFF, dtype=torch.uint8, device="cuda")
     kvs.kvs_step(p, Q, K, V, K_out, V_out, counts, ws, slot_of_token_out=slot, edge_mask_out=mask,
                  stream=torch.cuda.current_stream().cuda_stream)
     torch_sync()
@@ -1028,7 +1028,7 @@ def test_step_at_the_maximum_length(dtype, D):
     counts = torch.empty(B, dtype=torch.int32, device="cuda")
     mask_d = torch.empty(n, dtype=torch.uint8, device="cuda")
     slot_d = torch.empty(n, dtype=torch.int32, device="cuda")
-    ws = torch.empty(kvs.kvs_workspace_size(p), dtype=torch.uint8, device="cuda")
+    ws = torch.full((kvs.kvs_workspace_size(p),), 0xFF, dtype=torch.uint8, device="cuda")
     kvs.kvs_step(p, Qd, Kd, Vd, K_out, V_out, counts, ws, slot_of_token_out=slot_d, edge_mask_out=mask_d,
                  stream=torch.cuda.current_stream().cuda_stream)
     torch_sync()
@@ -1104,7 +1104,7 @@ def check_decode(units, dtype, D, G, W, path):
     p = batch.problem
     R = G * W
     out = torch.full((len(units) + 1, R, D), -7.0, dtype=torch.float32, device="cuda")
-    ws = torch.empty(batch.kvs.kvs_decode_workspace_size(p), dtype=torch.uint8, device="cuda")
+    ws = torch.full((batch.kvs.kvs_decode_workspace_size(p),), 0xFF, dtype=torch.uint8, device="cuda")
     with switch_override("decode_path", {None: 0, "valu": 1, "mfma": 2}[path]):
         batch.kvs.kvs_decode_attention(p, batch.Q, batch.K, batch.V, batch.counts_in, out, ws, stream=batch.stream())
         torch_sync()
@@ -1138,7 +1138,7 @@ def test_decode_attention_over_the_output_of_a_step():
     from helpers import to_device
     Qd = to_device(qn.reshape(len(acc), G, w.head_dim), w.dtype)
     out = torch.empty((len(acc), G, w.head_dim), dtype=torch.float32, device="cuda")
-    ws = torch.empty(batch.kvs.kvs_decode_workspace_size(dp), dtype=torch.uint8, device="cuda")
+    ws = torch.full((batch.kvs.kvs_decode_workspace_size(dp),), 0xFF, dtype=torch.uint8, device="cuda")
     batch.kvs.kvs_decode_attention(dp, Qd, batch.K_out, batch.V_out, batch.counts, out, ws, stream=batch.stream())
     torch_sync()
     got = out.cpu().numpy()

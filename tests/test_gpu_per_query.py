@@ -51,7 +51,7 @@ def per_query_buffers(batch):
     G = batch.GUARD
     a_tok = torch.full((p.rows_in + G,), -7.0, dtype=torch.float32, device="cuda")
     c_edge = torch.full((p.rows_in + G,), -7.0, dtype=torch.float32, device="cuda")
-    ws = torch.empty(batch.kvs.kvs_per_query_workspace_size(p) + 256, dtype=torch.uint8, device="cuda")
+    ws = torch.full((batch.kvs.kvs_per_query_workspace_size(p) + 256,), 0xFF, dtype=torch.uint8, device="cuda")
     return a_tok, c_edge, ws
 
 
