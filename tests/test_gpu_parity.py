@@ -751,6 +751,27 @@ def test_step_random_shapes(seed):
     check_step(w, accepted, path, causal=causal)
 
 
+@pytest.mark.parametrize("dtype,D,G,W,n,B,causal", [
+    ("bf16", 128, 4, 32, 3000, 700, False), ("f32", 64, 2, 4, 1500, 300, False), ("bf16", 64, 4, 8, 5000, 1250, True)])
+@pytest.mark.parametrize("zeroed", ["Q", "K"])
+def test_step_with_uniform_attention(dtype, D, G, W, n, B, causal, zeroed):
+    """Queries or Keys that are all zero: every logit is 0, every token has the same mass (under the causal mask:
+    the same within the window's steps), so all edge scores tie and the selection is decided by the index alone.
+    No acceptance rule applies (the gap is zero by construction): both sides must break the ties alike."""
+    from helpers import AcceptedUnit
+    w = WORKLOADS["llama8b_8k"].scaled(dtype=dtype, head_dim=D, group=G, window=W, length=("fixed", n),
+                                       budget=("fixed", B))
+    u = generate_unit(w, 0, 0, 0, n=n)
+    if zeroed == "Q":
+        u.Q = np.zeros_like(u.Q)
+    else:
+        u.K = np.zeros_like(u.K)
+    ab, ob = O.score(u.Q, u.K, u.V, causal_window=W if causal else 0)
+    mask, slot = O.select(ab.astype(np.float32), u.budget, w.n_sink, w.n_recent, sigma_dtype=np.float32)
+    merged = O.merge_compact(u.K, u.V, ab, ob, mask, slot)
+    check_step(w, [AcceptedUnit(u, O.StepResult(ab, ob, mask, slot, merged), 0.0, 1.0)], causal=causal)
+
+
 def test_step_with_causal_window():
     """The whole step with the causal mask inside the window, bf16 (MFMA score) and fp32 (vector-ALU score)."""
     w = WORKLOADS["llama8b_8k"]
