@@ -772,6 +772,60 @@ def test_step_with_uniform_attention(dtype, D, G, W, n, B, causal, zeroed):
     check_step(w, [AcceptedUnit(u, O.StepResult(ab, ob, mask, slot, merged), 0.0, 1.0)], causal=causal)
 
 
+def test_streaming_loop_of_steps():
+    streaming_loop(check_step, per_query=False)
+
+
+def streaming_loop(check, per_query):
+    """The deployment loop of Sec. 3.1 / Sec. 5: a cache is merged down to the budget, a chunk of fresh tokens arrives,
+    and the cache of budget + chunk rows is merged again: six rounds for two heads (2560 -> 2048, five times 2048 +
+    512 -> 2048).  Every round's input is the GPU's own output of the round before, exactly as stored (merged Keys,
+    Value sums, cardinalities), followed by the fresh rows; the oracle takes one step from that same input and the
+    round is compared like any other step (partition bit for bit, cardinalities exact).  At the end every token that
+    ever arrived is accounted for."""
+    from helpers import AcceptedUnit, COND_MIN, GAP_MIN
+    from workloads.generator import UnitInputs
+    w = WORKLOADS["stream2560"]
+    plain = WORKLOADS["llama8b_8k"]                  # the recipe of the arriving tokens (same shape and dtype)
+    B, chunk, rounds, heads = 2048, 512, 6, 2
+    total = B + chunk * rounds
+    src = [generate_unit(plain, 0, 0, h, n=total) for h in range(heads)]
+    state = [(u.K[:B + chunk], u.V[:B + chunk], np.ones(B + chunk, dtype=np.int32)) for u in src]
+    for r in range(rounds):
+        accepted = []
+        for h, (K, V, c) in enumerate(state):
+            for attempt in range(200):
+                Q = generate_unit(plain, 1 + r, 0, h, attempt=attempt, n=64).Q          # a fresh window of queries
+                u = UnitInputs(layer=r, seq=0, head=h, attempt=attempt, n=len(K), budget=B, rho=0.0, Q=Q, K=K, V=V,
+                               counts=c)
+                ab, ob = O.score(Q, K, V, counts=c)
+                gap = O.boundary_gap(ab, B, w.n_sink, w.n_recent)
+                if gap < GAP_MIN:
+                    continue
+                mask, slot = O.select(ab, B, w.n_sink, w.n_recent)
+                norms = O.per_query_norms(Q, K, V, counts=c) if per_query else None
+                merged = O.merge_compact(K, V, ab, ob, mask, slot, counts_in=c, norms=norms)
+                if O.conditioning(merged) >= COND_MIN:
+                    break
+            else:
+                raise RuntimeError("no accepted attempt found")
+            accepted.append(AcceptedUnit(u, O.StepResult(ab, ob, mask, slot, merged), gap, 1.0))
+        batch = check(w, accepted)
+        p = batch.problem
+        Ko, Vo, cnt = from_device(batch.K_out), from_device(batch.V_out), batch.counts.cpu().numpy()
+        state = []
+        for h in range(heads):
+            r0 = p.out_rows[h]
+            assert cnt[r0:r0 + B].sum() == B + chunk * (r + 1)           # no token lost, none counted twice
+            if r + 1 == rounds:
+                continue
+            lo = B + chunk * (r + 1)
+            fresh = slice(lo, lo + chunk)
+            state.append((np.concatenate([Ko[r0:r0 + B], src[h].K[fresh]]),
+                          np.concatenate([Vo[r0:r0 + B], src[h].V[fresh]]),
+                          np.concatenate([cnt[r0:r0 + B], np.ones(chunk, dtype=np.int32)]).astype(np.int32)))
+
+
 def test_step_with_causal_window():
     """The whole step with the causal mask inside the window, bf16 (MFMA score) and fp32 (vector-ALU score)."""
     w = WORKLOADS["llama8b_8k"]

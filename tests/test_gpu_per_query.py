@@ -332,6 +332,12 @@ def test_step_per_query_streaming_regime():
     check_step_per_query(w, [accepted_unit_per_query(w, 0, 0, 0)])
 
 
+def test_streaming_loop_of_per_query_steps():
+    """The loop of test_streaming_loop_of_steps with the per-query aggregation in every round."""
+    from test_gpu_parity import streaming_loop
+    streaming_loop(check_step_per_query, per_query=True)
+
+
 def test_step_per_query_with_causal_window():
     w = WORKLOADS["llama8b_8k"]
     check_step_per_query(w, [accepted_unit_per_query(w, 0, 0, h, causal=True) for h in range(2)], causal=True)
