@@ -6,7 +6,7 @@
 One *step* is one pass of the whole hot path (score -> select -> merge_compact) over every layer of
 the workload, inputs resident in HBM.  A (layer, sequence, KV head) cache is one independent unit of
 the library, so the layers are simply more units of the same kvs_step call (--layers-per-call, all of
-them by default; the library launches its kernels over at most 64 units at a time).
+them by default; the library launches its kernels over groups of units: 64 of the headline's).
 Prints ONE JSON line: whole-job merged KV tokens/s, the roofline of the whole step (with the phases' and the
 dominant kernel's own figures as flat fields beside it, timed live with events on the launch stream) and the
 fp64 oracle's rate on the host cores of this machine.
@@ -30,6 +30,21 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 
 
+def launch_groups(lens):
+    """The units (cache lengths, in call order) that each launch of the library covers: a launch is closed at 2 M
+    tokens (64 units of 32768) or 1024 units.  Returns the groups' sizes."""
+    groups, count, tokens = [], 0, 0
+    for n in lens:
+        count += 1
+        tokens += n
+        if tokens >= 64 * 32768 or count == 1024:
+            groups.append(count)
+            count = tokens = 0
+    if count:
+        groups.append(count)
+    return groups
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -39,9 +54,10 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
     ap.add_argument("--layers-per-call", type=int, default=0,
                     help="layers handed to one kvs_step call (0 = all; 1 = one call per layer)")
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--streams", type=int, default=None,
                     help="deal the kvs_step calls of a step round-robin to this many streams (default 2: the layers go "
-                         "to two calls on two streams, whose kernels fill each other's idle resources)")
+                         "to two calls on two streams, whose kernels fill each other's idle resources; 1 when all units "
+                         "of the step fit ONE launch of the library, which then beats two half-size calls)")
     ap.add_argument("--no-per-layer-calls", action="store_true", help="skip the one-call-per-layer comparison loop")
     ap.add_argument("--io-dtype", default=None, choices=["bf16", "f32"],
                     help="run the workload's recipe with this I/O dtype instead of its own (fp32: the fp32 kernels at size)")
@@ -110,6 +126,8 @@ def main():
     D, R = w.head_dim, w.q_rows
     b = 4 if w.dtype == "f32" else 2
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    if args.streams is None:
+        args.streams = 1 if len(launch_groups(lens * layers)) == 1 else 2
     # launch shape: by default the layers are split evenly into one kvs_step call per stream
     lpc = args.layers_per_call or -(-layers // max(1, min(args.streams, layers)))
     batches = [list(range(l0, min(layers, l0 + lpc))) for l0 in range(0, layers, lpc)]
@@ -258,7 +276,7 @@ def main():
             kvs.kvs_select(pr, alpha, mask, slot, ws=ws, stream=stream)    # (with the workspace, as inside kvs_step)
             evs[i][2].record()
             kvs.kvs_merge_compact_counts(pr, Ks[i], Vs[i], Cs[i], alpha, obar, mask, slot, K_out[i], V_out[i], counts[i],
-                                         stream=stream)
+                                         ws=ws, stream=stream)
             evs[i][3].record()
         torch.cuda.synchronize()
         if rep == 0:
@@ -266,9 +284,11 @@ def main():
         for i in range(len(probs)):
             for j, p in enumerate(phases):
                 phase_ms[p] += evs[i][j].elapsed_time(evs[i][j + 1])
-    # One kernel launch of the library covers at most 64 units; the figures below are per such launch.
-    UNITS_PER_LAUNCH = 64
-    launches = reps * sum((pr.n_units + UNITS_PER_LAUNCH - 1) // UNITS_PER_LAUNCH for pr in probs)
+    # One kernel launch of the library covers one group of units (64 of the headline's; all 256 caches of the
+    # streaming workload); the figures below are per such launch.
+    groups = [g for bt in batches for g in launch_groups(lens * len(bt))]
+    UNITS_PER_LAUNCH = max(groups)
+    launches = reps * len(groups)
     layers_per_launch = layers * reps / launches
     phase_ms = {p: v / launches for p, v in phase_ms.items()}
     pb = {p: 0 for p in phases}                       # bytes of one layer's units

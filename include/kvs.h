@@ -55,9 +55,8 @@ typedef enum {
   KVS_ERR_BUDGET = 3,       /* budget < n_sink + 1 + n_recent for a unit that has to merge (len > budget),
                                or budget < 1 */
   KVS_ERR_WORKSPACE = 4,    /* workspace null, misaligned (256 B) or smaller than kvs_workspace_size(); only the
-                               calls that use one check it: kvs_merge_compact, kvs_merge_compact_counts and
-                               kvs_merge_compact_norms use none and ignore ws / ws_bytes (NULL and 0 are fine
-                               there); for kvs_select it is optional (see there)                        */
+                               calls that need one check it: for kvs_select and the kvs_merge_compact family it is
+                               optional (see there; NULL and 0 are fine)                                 */
   KVS_ERR_ALIAS = 5,        /* an output overlaps an input, another output or the workspace */
   KVS_ERR_DEVICE = 6        /* a HIP launch failed.  The library reads the calling thread's HIP error state after
                                each launch (which clears it) and drops an error left pending by the caller's own
@@ -119,7 +118,8 @@ kvs_status kvs_score(const kvs_problem* p, const void* Q, const void* K, const v
  *   slot_of_token DEVICE out [rows] i32: unit-local output slot of every token (non-decreasing)
  *   ws            optional.  With a workspace (256-byte aligned, at least kvs_workspace_size(p) bytes) a long unit's
  *                 selection may be spread over several workgroups that meet through it; with NULL, a misaligned or
- *                 a smaller one, every unit is selected by one workgroup.  The results are the same bit for bit. */
+ *                 a smaller one, every unit is selected by one workgroup, and a launch covers at most 64 units (with
+ *                 one: up to 1024 short units).  The results are the same bit for bit. */
 kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar,
                       uint8_t* edge_mask, int32_t* slot_of_token,
                       void* ws, size_t ws_bytes, void* hip_stream);
@@ -131,7 +131,10 @@ kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar,
  *   positive finite number), V_out[S] = sum V[t], counts_out[S] = |S|.  A slot of one token is a
  *   bit-exact copy.
  *   K_out, V_out DEVICE out [out rows, D] io_dtype;  counts_out DEVICE out [out rows] i32          */
-/*   edge_mask and slot_of_token are taken as kvs_select writes them: slot_of_token[t] = number of zero mask bytes
+/*   ws           optional (also for the _counts and _norms forms).  The kernel needs none; with a workspace (256-byte
+ *                aligned, at least kvs_workspace_size(p) bytes) a call with more than 64 short units puts up to 1024 of
+ *                them into one launch, whose unit descriptors then live there.  Same results either way.
+ *   edge_mask and slot_of_token are taken as kvs_select writes them: slot_of_token[t] = number of zero mask bytes
  *   before t.  The mask byte of a unit's last token is read as 0 whatever it holds; a slot index outside the
  *   unit's output rows is never written.  Nothing else about a mask from outside the library is checked.   */
 kvs_status kvs_merge_compact(const kvs_problem* p, const void* K, const void* V,

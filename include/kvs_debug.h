@@ -37,7 +37,10 @@ typedef enum {
                                                        item to the second kernel (1: it never waits)                   */
   KVS_DEBUG_FUSED_STAGGER = 9,/* KVS_FUSED_STAGGER=<n> n + 1: the four cohorts of workgroups of the one-pass score kernel start
                                                        n tenths of a microsecond apart                                 */
-  KVS_DEBUG_N_SWITCHES = 10
+  KVS_DEBUG_GROUP_UNITS = 10, /* KVS_GROUP_UNITS=<n>   most units of one launch (the library puts up to 1024 short units, or 2 M
+                                                       tokens, into one; groups of more than 64 keep their descriptors in
+                                                       the workspace)                                                   */
+  KVS_DEBUG_N_SWITCHES = 11
 } kvs_debug_switch;
 
 /* Sets a switch (a kvs_debug_switch, passed as an int) and returns its previous value; -1 (nothing changed) for an

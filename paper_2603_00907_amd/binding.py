@@ -30,7 +30,7 @@ EXPORTS = ["kvs_workspace_size", "kvs_score", "kvs_select", "kvs_merge_compact",
 STATIC_SCRATCH_BYTES = 16 << 20
 # testing switches of include/kvs_debug.h
 DEBUG_SWITCHES = {"score_path": 0, "score_wide": 1, "fuse_obar": 2, "decode_path": 3, "score_chunk": 4, "verbose": 5,
-                  "score_fused": 6, "select_split": 7, "fused_wait_us": 8, "fused_stagger": 9}
+                  "score_fused": 6, "select_split": 7, "fused_wait_us": 8, "fused_stagger": 9, "group_units": 10}
 
 
 KEY_RULES = {"hessian": 0, "diagonal": 1, "mean": 2}

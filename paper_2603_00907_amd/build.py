@@ -23,7 +23,7 @@ LIB = os.path.join(HERE, "libkvs.so")
 OBJ = os.path.join(HERE, "_build")
 
 SOURCES = ["kvs_api.hip", "kvs_score_valu.hip", "kvs_score_mfma.hip", "kvs_score_fused.hip", "kvs_select.hip", "kvs_merge.hip", "kvs_decode.hip",
-           "kvs_perquery.hip", "kvs_perquery_f32.hip"]
+           "kvs_perquery.hip", "kvs_perquery_f32.hip", "kvs_table.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

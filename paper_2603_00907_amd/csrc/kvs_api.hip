@@ -49,6 +49,8 @@ struct SwitchInit {
     g_switch[KVS_DEBUG_FUSED_WAIT_US] = t ? std::max(0, std::atoi(t)) + 1 : 0;
     const char* g = std::getenv("KVS_FUSED_STAGGER");
     g_switch[KVS_DEBUG_FUSED_STAGGER] = g ? std::max(0, std::atoi(g)) + 1 : 0;
+    const char* gu = std::getenv("KVS_GROUP_UNITS");
+    g_switch[KVS_DEBUG_GROUP_UNITS] = gu ? std::max(0, std::atoi(gu)) : 0;
   }
 } g_switch_init;
 }  // namespace
@@ -68,7 +70,19 @@ struct Plan {
   long long rows_in = 0, rows_out = 0;
   long long fused_items = 0;     // work items of the largest launch group when the one-pass score kernel applies
   std::vector<Unit> units;       // chunk_base / m_base filled per launch group
+  int group_cap = kInlineUnits;  // most units of a launch group
+  Unit* dev_table = nullptr;     // where a group of more than kInlineUnits units keeps its descriptors (workspace), or
+                                 // null: the call has no such memory and its groups stay within kInlineUnits
+  hipStream_t stream = nullptr;  // the call's stream (the descriptors are written on it)
 };
+
+// One past the last unit of the launch group that starts at unit `first`.
+int group_end(const Plan& plan, int first, int cap) {
+  long long tokens = 0;
+  int i = first;
+  while (i < plan.n_units && i - first < cap && tokens < kGroupTokens) tokens += plan.units[i++].len;
+  return i;
+}
 
 kvs_status make_plan(const kvs_problem* p, Plan* plan) {
   if (p == nullptr) return KVS_ERR_INVALID_ARG;
@@ -125,11 +139,14 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
     plan->rows_out = std::max(plan->rows_out, un.out_row + (long long)un.n_out);
   }
   // Score chunks (one workgroup each): long enough that a workgroup's prologue (Q block, statistics)
-  // is a small part of its life, short enough that one launch (at most kMaxUnitsPerLaunch units) still
+  // is a small part of its life, short enough that one launch (the first group of units) still
   // has a few workgroups for every slot of the chip; never more than kMaxChunks per unit.
+  // (the one-pass score kernel keeps per-unit counters for kInlineUnits units; a test may ask for smaller groups)
+  plan->group_cap = debug_switch(KVS_DEBUG_SCORE_FUSED) ? kInlineUnits : kMaxGroupUnits;
+  if (const int forced = debug_switch(KVS_DEBUG_GROUP_UNITS)) plan->group_cap = std::min(forced, kMaxGroupUnits);
   {
     long long total = 0;
-    for (int u = 0; u < std::min(p->n_units, kMaxUnitsPerLaunch); ++u) total += p->len[u];
+    for (int u = 0; u < group_end(*plan, 0, plan->group_cap); ++u) total += p->len[u];
     long long want = total / kScoreWorkgroups;
     if (const int forced = debug_switch(KVS_DEBUG_SCORE_CHUNK)) want = forced;   // tuning aid
     want = std::min<long long>(std::max<long long>(want, kMinChunkLen), kMaxChunkLen);
@@ -142,11 +159,11 @@ kvs_status make_plan(const kvs_problem* p, Plan* plan) {
   }
   // the one-pass score kernel (bf16, 65..128 query rows, every unit at least a tile long) keeps per-item tables
   if (plan->dtype == KVS_BF16 && plan->shape.R > 64 && plan->shape.R <= 128) {
-    for (int first = 0; first < p->n_units; first += kMaxUnitsPerLaunch) {
+    const int cap = std::min(plan->group_cap, kInlineUnits);
+    for (int first = 0, end; first < p->n_units; first = end) {
+      end = group_end(*plan, first, cap);
       long long items = 0;
-      for (int u = first; u < std::min(p->n_units, first + kMaxUnitsPerLaunch); ++u) {
-        items += fused_chunks(plan->units[u].len, plan->shape.D);
-      }
+      for (int u = first; u < end; ++u) items += fused_chunks(plan->units[u].len, plan->shape.D);
       plan->fused_items = std::max(plan->fused_items, items);
     }
   }
@@ -188,7 +205,8 @@ Workspace carve(const Plan& plan, void* base) {
     w.fsync = (unsigned int*)take(((size_t)kFusedSyncInts + plan.fused_items) * sizeof(unsigned int));
   }
   // exchange area of the selection by several workgroups per unit (one launch group at a time)
-  w.sel_shared = (unsigned int*)take((size_t)std::min(plan.n_units, kMaxUnitsPerLaunch) * kSelSharedInts * sizeof(unsigned int));
+  w.sel_shared = (unsigned int*)take((size_t)std::min(plan.n_units, kInlineUnits) * kSelSharedInts * sizeof(unsigned int));
+  w.unit_tab = (Unit*)take(plan.n_units > kInlineUnits ? (size_t)std::min(plan.n_units, kMaxGroupUnits) * sizeof(Unit) : 0);
   w.bytes = off;
   return w;
 }
@@ -214,10 +232,12 @@ PerQueryWs carve_per_query(const Plan& plan, void* base, Workspace* w) {
     off += align_up(bytes);
     return (void*)ptr;
   };
+  // (the chunks of the largest group; groups of a call that has to keep them smaller need less)
   long long max_chunks = 0;
-  for (int first = 0; first < plan.n_units; first += kMaxUnitsPerLaunch) {
+  for (int first = 0, end; first < plan.n_units; first = end) {
+    end = group_end(plan, first, plan.group_cap);
     long long c = 0;
-    for (int u = first; u < std::min(plan.n_units, first + kMaxUnitsPerLaunch); ++u) c += plan.units[u].n_chunks;
+    for (int u = first; u < end; ++u) c += plan.units[u].n_chunks;
     max_chunks = std::max(max_chunks, c);
   }
   const size_t rd = (size_t)plan.shape.R * plan.shape.D;
@@ -283,7 +303,17 @@ kvs_status check_ws(const Plan& plan, const void* ws, size_t ws_bytes, Workspace
   return KVS_OK;
 }
 
-// Calls f(table) for every group of at most kMaxUnitsPerLaunch units.
+// An entry point whose workspace is optional: with one that is usable, its groups may keep their descriptors there.
+// Returns the bytes of it that the call may write (0: none).
+size_t adopt_optional_ws(Plan& plan, void* ws, size_t ws_bytes) {
+  if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0) return 0;
+  const Workspace w = carve(plan, ws);
+  if (ws_bytes < w.bytes) return 0;
+  plan.dev_table = w.unit_tab;
+  return w.bytes;
+}
+
+// Calls f(table) for every launch group (see group_end).
 // Compute units of the current device (asked once per device).
 int compute_units() {
   static std::atomic<int> cached[64];
@@ -303,36 +333,51 @@ kvs_status for_each_group(const Plan& plan, F&& f, bool split_select = false) {
   // An error that the calling thread's earlier HIP calls left pending is not this call's: it is dropped here,
   // so that what the launchers read after their launches is theirs.
   (void)hipGetLastError();
-  for (int first = 0; first < plan.n_units; first += kMaxUnitsPerLaunch) {
+  const int split_mode = split_select ? debug_switch(KVS_DEBUG_SELECT_SPLIT) : 1;
+  const int n_cus = split_mode == 1 ? 0 : compute_units();
+  // A group of more than kInlineUnits units needs memory for its descriptors.  Where a test asks for every unit's
+  // selection to be spread over workgroups, the exchange area's kInlineUnits entries bound the group as well (left
+  // to itself the library spreads a selection only in launches of a few units).
+  int cap = plan.dev_table != nullptr ? plan.group_cap : std::min(plan.group_cap, kInlineUnits);
+  if (split_mode >= 2) cap = std::min(cap, kInlineUnits);
+  std::vector<Unit> units;
+  for (int first = 0, end; first < plan.n_units; first = end) {
+    end = group_end(plan, first, cap);
     UnitTable tab;
     std::memset(&tab, 0, sizeof(tab));
-    tab.n_units = std::min(kMaxUnitsPerLaunch, plan.n_units - first);
+    tab.n_units = end - first;
+    units.assign(plan.units.begin() + first, plan.units.begin() + end);
     int chunks = 0, mblocks = 0, ochunks = 0, fitems = 0, sparts = 0;
-    const int split_mode = split_select ? debug_switch(KVS_DEBUG_SELECT_SPLIT) : 1;
-    const int n_cus = split_mode == 1 ? 0 : compute_units();
-    for (int i = 0; i < tab.n_units; ++i) {
-      tab.u[i] = plan.units[first + i];
-      tab.u[i].s_base = sparts;
-      sparts += select_parts(tab.u[i], plan.shape, tab.n_units, n_cus, split_mode);
-      tab.u[i].chunk_base = chunks;
-      tab.u[i].m_base = mblocks;
-      tab.u[i].o_base = ochunks;
-      tab.u[i].f_base = fitems;
-      fitems += fused_chunks(tab.u[i].len, plan.shape.D);
-      ochunks += obar_chunks(tab.u[i].len);
-      chunks += tab.u[i].n_chunks;
-      mblocks += (tab.u[i].len + kMergeTokens - 1) / kMergeTokens;
+    long long rows = 0;
+    for (Unit& un : units) {
+      un.s_base = sparts;
+      sparts += select_parts(un, plan.shape, tab.n_units, n_cus, split_mode);
+      un.chunk_base = chunks;
+      un.m_base = mblocks;
+      un.o_base = ochunks;
+      un.f_base = fitems;
+      fitems += fused_chunks(un.len, plan.shape.D);
+      ochunks += obar_chunks(un.len);
+      chunks += un.n_chunks;
+      mblocks += (un.len + kMergeTokens - 1) / kMergeTokens;
+      rows += un.len;
     }
     tab.total_chunks = chunks;
     tab.total_mblocks = mblocks;
     tab.total_ochunks = ochunks;
     tab.total_fitems = fitems;
     tab.total_sparts = sparts;
-    long long rows = 0;
-    for (int i = 0; i < tab.n_units; ++i) rows += tab.u[i].len;
     Shape sh = plan.shape;
     sh.stream = 2 * rows * sh.D * (long long)plan.elt > kStreamBytes;
-    const hipError_t e = f(tab, sh);
+    hipError_t e = hipSuccess;
+    if (tab.n_units <= kInlineUnits) {
+      std::copy(units.begin(), units.end(), tab.u);
+    } else {
+      tab.host = units.data();
+      tab.ext = plan.dev_table;
+      e = launch_unit_table(units.data(), tab.n_units, plan.dev_table, plan.stream);
+    }
+    if (e == hipSuccess) e = f(tab, sh);
     if (e != hipSuccess) {
       if (debug_switch(KVS_DEBUG_VERBOSE)) {
         std::fprintf(stderr, "libkvs: launch failed in the group of units %d..%d: %s\n", first, first + tab.n_units - 1,
@@ -397,8 +442,8 @@ hipError_t launch_score(const UnitTable& tab, const Shape& sh, kvs_dtype dt, con
     // unit's selection is spread over several workgroups.)
     int longest = 0;
     for (int i = 0; i < tab.n_units; ++i) {
-      const int parts = (i + 1 < tab.n_units ? tab.u[i + 1].s_base : tab.total_sparts) - tab.u[i].s_base;
-      if (parts <= 1) longest = std::max(longest, tab.u[i].len);
+      const int parts = (i + 1 < tab.n_units ? tab.unit(i + 1).s_base : tab.total_sparts) - tab.unit(i).s_base;
+      if (parts <= 1) longest = std::max(longest, tab.unit(i).len);
     }
     bool want = sh.stream != 0 && longest <= kSelUnitKeys;
     if (fuse == 1) want = false;
@@ -449,6 +494,8 @@ kvs_status kvs_score_counts(const kvs_problem* p, const void* Q, const void* K, 
   if (counts_in) rs.push_back({counts_in, (size_t)plan.rows_in * 4, false});
   if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
+  plan.dev_table = w.unit_tab;
+  plan.stream = s;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     int o_layout = 0;
     hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, alpha_bar, w, s, V, &o_layout);
@@ -481,6 +528,8 @@ kvs_status kvs_select(const kvs_problem* p, const float* alpha_bar, uint8_t* edg
   }
   if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
+  if (with_ws) plan.dev_table = w.unit_tab;
+  plan.stream = s;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     if (tab.total_sparts != tab.n_units) {      // (the score kernels clear the area when they run before the selection)
       const hipError_t e = launch_select_clear(tab, w.sel_shared, s);
@@ -503,11 +552,10 @@ kvs_status kvs_merge_compact_counts(const kvs_problem* p, const void* K, const v
                                     const float* alpha_bar, const float* o_bar, const uint8_t* edge_mask,
                                     const int32_t* slot_of_token, void* K_out, void* V_out, int32_t* counts_out,
                                     void* ws, size_t ws_bytes, void* hip_stream) {
-  (void)ws;
-  (void)ws_bytes;
   Plan plan;
   kvs_status st = make_plan(p, &plan);
   if (st != KVS_OK) return st;
+  const size_t ws_used = adopt_optional_ws(plan, ws, ws_bytes);
   const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
   const size_t kvo = (size_t)plan.rows_out * plan.shape.D * plan.elt;
   std::vector<Range> rs = {{K, kv, false},
@@ -520,8 +568,10 @@ kvs_status kvs_merge_compact_counts(const kvs_problem* p, const void* K, const v
                            {V_out, kvo, true},
                            {counts_out, (size_t)plan.rows_out * 4, true}};
   if (counts_in) rs.push_back({counts_in, (size_t)plan.rows_in * 4, false});
+  if (ws_used) rs.push_back({ws, ws_used, true});
   if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
+  plan.stream = s;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     return launch_merge(tab, sh, plan.dtype, K, V, counts_in, alpha_bar, o_bar, nullptr, edge_mask, slot_of_token,
                         K_out, V_out, counts_out, s);
@@ -556,7 +606,7 @@ static kvs_status check_step_ranges(const Plan& plan, const void* Q, const void*
 
 // kvs_step_counts with the workspace given either by the caller (ws, ws_bytes) or, for kvs_step_static, by
 // `fixed_ws` (then ws_bytes is its capacity and the caller's argument checks have run before any device call).
-static kvs_status step_with_workspace(const Plan& plan, const void* Q, const void* K, const void* V,
+static kvs_status step_with_workspace(Plan& plan, const void* Q, const void* K, const void* V,
                                       const int32_t* counts_in, void* K_out, void* V_out, int32_t* counts_out,
                                       int32_t* slot_of_token_out, uint8_t* edge_mask_out, void* ws, size_t ws_bytes,
                                       void* hip_stream) {
@@ -571,6 +621,8 @@ static kvs_status step_with_workspace(const Plan& plan, const void* Q, const voi
   uint8_t* mask = edge_mask_out ? edge_mask_out : w.edge_mask;
   int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
   hipStream_t s = (hipStream_t)hip_stream;
+  plan.dev_table = w.unit_tab;
+  plan.stream = s;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     int o_layout = 0;
     hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, w.alpha_bar, w, s, V, &o_layout);
@@ -692,6 +744,8 @@ kvs_status kvs_sensitivity_counts(const kvs_problem* p, const void* Q, const voi
   if (counts_in) rs.push_back({counts_in, rows4, false});
   if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
+  plan.dev_table = w.unit_tab;
+  plan.stream = s;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, alpha_bar, w, s);
     if (e != hipSuccess) return e;
@@ -711,11 +765,10 @@ kvs_status kvs_merge_compact_norms_counts(const kvs_problem* p, const void* K, c
                                           const float* a_tok, const float* c_edge, const uint8_t* edge_mask,
                                           const int32_t* slot_of_token, void* K_out, void* V_out, int32_t* counts_out,
                                           void* ws, size_t ws_bytes, void* hip_stream) {
-  (void)ws;
-  (void)ws_bytes;
   Plan plan;
   kvs_status st = make_plan(p, &plan);
   if (st != KVS_OK) return st;
+  const size_t ws_used = adopt_optional_ws(plan, ws, ws_bytes);
   const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
   const size_t kvo = (size_t)plan.rows_out * plan.shape.D * plan.elt;
   std::vector<Range> rs = {{K, kv, false},
@@ -728,8 +781,10 @@ kvs_status kvs_merge_compact_norms_counts(const kvs_problem* p, const void* K, c
                            {V_out, kvo, true},
                            {counts_out, (size_t)plan.rows_out * 4, true}};
   if (counts_in) rs.push_back({counts_in, (size_t)plan.rows_in * 4, false});
+  if (ws_used) rs.push_back({ws, ws_used, true});
   if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
+  plan.stream = s;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     return launch_merge_norms(tab, sh, plan.dtype, K, V, counts_in, a_tok, c_edge, edge_mask, slot_of_token, K_out,
                               V_out, counts_out, s);
@@ -771,6 +826,8 @@ kvs_status kvs_step_per_query_counts(const kvs_problem* p, const void* Q, const 
   uint8_t* mask = edge_mask_out ? edge_mask_out : w.edge_mask;
   int32_t* slot = slot_of_token_out ? slot_of_token_out : w.slot;
   hipStream_t s = (hipStream_t)hip_stream;
+  plan.dev_table = w.unit_tab;
+  plan.stream = s;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     hipError_t e = launch_score(tab, sh, plan.dtype, Q, K, counts_in, w.alpha_bar, w, s);
     if (e != hipSuccess) return e;

@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kThreads) void decode_partial_kernel(
   __shared__ float sm_acc[GROUPS][kQB][D];
   __shared__ float2 sm_ml[GROUPS][kQB];
 
-  const Unit un = tab.u[blockIdx.y];
+  const Unit un = tab.unit(blockIdx.y);
   const int chunk = blockIdx.x;
   if (chunk >= dec_chunks(un.len)) return;               // the grid is as wide as the longest unit needs
   const int clen = dec_chunk_len(un.len);
@@ -182,7 +182,7 @@ template <int D>
 __global__ __launch_bounds__(D) void decode_reduce_kernel(const UnitTable tab, const Shape sh,
                                                           const float* __restrict__ part, float* __restrict__ out) {
   const int R = sh.R;
-  const Unit un = tab.u[blockIdx.x / R];
+  const Unit un = tab.unit(blockIdx.x / R);
   const int row = blockIdx.x % R;
   const int nc = dec_chunks(un.len);
   const int d = threadIdx.x;
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void decode_mfma_kernel(
   __shared__ __attribute__((aligned(16))) float sm_acc[kMfmaWaves][kTile][ACCW];
   __shared__ __attribute__((aligned(16))) float sm_cnt[kMfmaWaves][kTile];
 
-  const Unit un = tab.u[blockIdx.y];
+  const Unit un = tab.unit(blockIdx.y);
   const int chunk = blockIdx.x;
   if (chunk >= dec_chunks(un.len)) return;               // the grid is as wide as the longest unit needs
   const int clen = dec_chunk_len(un.len);
@@ -427,7 +427,7 @@ template <int D>
 hipError_t launch_mfma(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
                        const int32_t* counts, float* part, float* out, hipStream_t stream) {
   int widest = 1;
-  for (int i = 0; i < tab.n_units; ++i) widest = std::max(widest, dec_chunks(tab.u[i].len));
+  for (int i = 0; i < tab.n_units; ++i) widest = std::max(widest, dec_chunks(tab.unit(i).len));
   hipLaunchKernelGGL((decode_mfma_kernel<D>), dim3(widest, tab.n_units), dim3(kMfmaThreads), 0, stream, tab, sh,
                      (const uint16_t*)Q, (const uint16_t*)K, (const uint16_t*)V, counts, part);
   hipError_t e = hipGetLastError();
@@ -440,7 +440,7 @@ template <typename T, int D>
 hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const void* K, const void* V,
                     const int32_t* counts, float* part, float* out, hipStream_t stream) {
   int widest = 1;
-  for (int i = 0; i < tab.n_units; ++i) widest = std::max(widest, dec_chunks(tab.u[i].len));
+  for (int i = 0; i < tab.n_units; ++i) widest = std::max(widest, dec_chunks(tab.unit(i).len));
   hipLaunchKernelGGL((decode_partial_kernel<T, D>), dim3(widest, tab.n_units), dim3(kThreads), 0, stream, tab, sh,
                      (const T*)Q, (const T*)K, (const T*)V, counts, part);
   hipError_t e = hipGetLastError();
@@ -465,7 +465,7 @@ hipError_t launch_decode(const UnitTable& tab, const Shape& sh, kvs_dtype dt, co
   bool mfma = sh.R > kQB;
   if (force == 1) mfma = false;
   if (force == 2) mfma = true;
-  for (int i = 0; i < tab.n_units; ++i) mfma = mfma && tab.u[i].len >= kTile;   // its tiles hold 32 whole rows
+  for (int i = 0; i < tab.n_units; ++i) mfma = mfma && tab.unit(i).len >= kTile;   // its tiles hold 32 whole rows
   if (mfma) {
     return sh.D == 64 ? launch_mfma<64>(tab, sh, Q, K, V, counts, part, out, stream)
                       : launch_mfma<128>(tab, sh, Q, K, V, counts, part, out, stream);

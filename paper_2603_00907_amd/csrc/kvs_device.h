@@ -12,7 +12,13 @@ namespace kvs {
 // Current value of a testing switch (kvs_debug.h): one relaxed atomic load, no environment lookup.
 int debug_switch(kvs_debug_switch which);
 
-constexpr int kMaxUnitsPerLaunch = 64;   // unit descriptors travel by value in the kernel arguments
+// Units of one launch ("group").  Up to kInlineUnits unit descriptors travel by value in the kernel arguments; a
+// larger group (many short units: the streaming regime's caches of 2.5 K rows) has its descriptors written to the
+// workspace first, by small kernels that carry them in THEIR arguments, kInlineUnits at a time.  A group is closed
+// at kGroupTokens tokens (64 units of 32 K tokens: longer launches gain nothing) or kMaxGroupUnits units.
+constexpr int kInlineUnits = 64;
+constexpr int kMaxGroupUnits = 1024;
+constexpr long long kGroupTokens = 64ll * 32768;
 constexpr int kMaxChunks = 64;           // token chunks (= score workgroups) per unit
 constexpr int kMinChunkLen = 256;        // tokens
 constexpr int kMaxChunkLen = 2048;       // tokens
@@ -86,13 +92,27 @@ constexpr int kSelSharedInts = kSelCandPart + kSelCandMax;
 static_assert(kSelPartLow + kSelMaxParts <= kSelHist && kSelSharedInts % 4 == 0, "layout of the exchange area");
 
 struct UnitTable {
+  const Unit* ext;      // DEVICE: the descriptors of a group of more than kInlineUnits units, else null
+                        // (first, beside n_units: a kernel's first scalar load then brings both)
   int n_units;
   int total_chunks;
   int total_mblocks;
   int total_ochunks;
   int total_fitems;     // work items of the one-pass score kernel
   int total_sparts;     // select workgroups
-  Unit u[kMaxUnitsPerLaunch];
+  const Unit* host;     // HOST: the same descriptors for the launchers (meaningless on the device), else null
+  Unit u[kInlineUnits]; // the descriptors of a smaller group
+
+  // Descriptor i, on either side.  On the device the external table is read through the constant address space:
+  // the index is wavefront-uniform, so these are scalar loads like those of the kernel arguments.
+  __host__ __device__ __forceinline__ Unit unit(int i) const {
+#if defined(__HIP_DEVICE_COMPILE__)
+    if (ext != nullptr) return ((const __attribute__((address_space(4))) Unit*)ext)[i];
+    return u[i];
+#else
+    return host != nullptr ? host[i] : u[i];
+#endif
+  }
 };
 
 struct Shape {
@@ -129,15 +149,18 @@ struct Workspace {
   float* fstats;        // [work items][R]  log2 of the sum of 2^logit over the item's tokens, for every query row
   float* fo_part;       // [work items][D]  partial o_bar of every item
   unsigned int* fsync;  // kFusedSyncInts counters and flags, then one entry per work item (items given up on)
-  unsigned int* sel_shared;  // [kMaxUnitsPerLaunch][kSelSharedInts]  exchange area of the split selection
+  unsigned int* sel_shared;  // [kInlineUnits][kSelSharedInts]  exchange area of the split selection (only groups of
+                             // at most kInlineUnits units spread a unit's selection over workgroups)
+  Unit* unit_tab;            // [kMaxGroupUnits]  descriptors of a group of more than kInlineUnits units
   size_t bytes;
 };
 
 // Layout of Workspace::fsync (unsigned ints).
 constexpr int kFusedTicket = 0;                       // next work item
 constexpr int kFusedDeferred = 32;                    // number of items handed to the second kernel
-constexpr int kFusedDone = 64;                        // [kMaxUnitsPerLaunch] items of the unit whose statistics are out
-constexpr int kFusedSyncInts = 64 + kMaxUnitsPerLaunch;       // the list of deferred items starts here
+constexpr int kFusedDone = 64;                        // [kInlineUnits] items of the unit whose statistics are out
+constexpr int kFusedSyncInts = 64 + kInlineUnits;     // the list of deferred items starts here
+                                                      // (the one-pass kernel's groups have at most kInlineUnits units)
 // A normaliser c_row[unit][q] that the one-pass kernel has not produced yet holds this bit pattern (a NaN that no
 // arithmetic yields): the kernel's workgroups poll the words themselves, so no separate flag has to travel.
 constexpr unsigned int kFusedNotYet = 0xffffffffu;
@@ -222,7 +245,7 @@ __device__ __forceinline__ int find_unit_by(const UnitTable& tab, int x) {
   int lo = 0, hi = tab.n_units - 1;
   while (lo < hi) {
     const int mid = (lo + hi + 1) >> 1;
-    if (tab.u[mid].*BASE <= x) lo = mid;
+    if (tab.unit(mid).*BASE <= x) lo = mid;
     else hi = mid - 1;
   }
   return lo;
@@ -233,6 +256,9 @@ __device__ __forceinline__ int find_unit(const UnitTable& tab, int chunk) {
 }
 
 // Launchers (defined next to their kernels).  All enqueue on `stream` and return the launch status.
+// The descriptors of a group of more than kInlineUnits units (host memory) into the workspace, by kernels that
+// carry them in their arguments.
+hipError_t launch_unit_table(const Unit* units, int n_units, Unit* dst, hipStream_t stream);
 // Unit-wide softmax statistics from the chunks' partial ones (one small workgroup per unit).
 // (it also zeroes ws.sel_shared for the selection that follows, when there is one)
 hipError_t launch_score_finalize(const UnitTable& tab, const Shape& sh, const Workspace& ws, hipStream_t stream);

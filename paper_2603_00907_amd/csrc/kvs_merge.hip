@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kThreads) void merge_kernel(
   __shared__ float sm_obar[kThreads / D][D];
 
   const int ui = find_unit_by<&Unit::m_base>(tab, (int)blockIdx.x);
-  const Unit un = tab.u[ui];
+  const Unit un = tab.unit(ui);
   const int n = un.len;
   const int tid = threadIdx.x;
   const int group = tid / LPR, piece = tid % LPR;

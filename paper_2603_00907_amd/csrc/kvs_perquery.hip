@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kThreads, KVS_PQ_OUT_OCC) void pq_out_kernel(
   __shared__ uint4 sm_vt[2][DB][2][kWave];   // the V tile's blocks turned token-major: two operands per lane and block
 
   const int ui = find_unit(tab, blockIdx.x);
-  const Unit un = tab.u[ui];
+  const Unit un = tab.unit(ui);
   const int chunk = blockIdx.x - un.chunk_base;
   const int t0 = chunk * un.chunk_len;
   const int t1 = min(un.len, t0 + un.chunk_len);
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(D) void pq_out_reduce_kernel(const UnitTable tab, c
                                                           float* __restrict__ oo) {
   __shared__ float sm_ss[D / kWave];
   const int R = sh.R;
-  const Unit un = tab.u[blockIdx.x / R];
+  const Unit un = tab.unit(blockIdx.x / R);
   const int q = blockIdx.x % R;
   const int d = threadIdx.x;
   float s = 0.f, w = 0.f;
@@ -396,7 +396,7 @@ __global__ __launch_bounds__(kThreads, 2) void pq_norms_kernel(
   __shared__ float sm_lc[2][kTile + 1], sm_ic[2][kTile + 1];         // COUNTS: log2 c and 1 / c of the tile's rows
 
   const int ui = find_unit(tab, blockIdx.x);
-  const Unit un = tab.u[ui];
+  const Unit un = tab.unit(ui);
   const int chunk = blockIdx.x - un.chunk_base;
   const int t0 = chunk * un.chunk_len;
   const int t1 = min(un.len, t0 + un.chunk_len);
@@ -617,7 +617,7 @@ __global__ __launch_bounds__(kThreads) void pq_redo_kernel(
   __shared__ float sm_sum[2][kWaves];
   static_assert(kRedoSpan / kThreads <= 32, "one bit per token and thread");
 
-  const Unit un = tab.u[blockIdx.x];
+  const Unit un = tab.unit(blockIdx.x);
   const int t0 = blockIdx.y * kRedoSpan;
   const int t1 = min(un.len, t0 + kRedoSpan);
   if (t0 >= t1) return;                     // (the grid is sized for the launch's longest unit)
@@ -772,7 +772,7 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, const void* Q, const 
                      (const uint16_t*)K, (const uint16_t*)V, counts_in, c_row, o_hi, o_lo, oo, a_tok, c_edge);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   int longest = 1;
-  for (int u = 0; u < tab.n_units; ++u) longest = longest > tab.u[u].len ? longest : tab.u[u].len;
+  for (int u = 0; u < tab.n_units; ++u) longest = longest > tab.unit(u).len ? longest : tab.unit(u).len;
   const dim3 spans(tab.n_units, (longest + kRedoSpan - 1) / kRedoSpan);
   hipLaunchKernelGGL((pq_redo_kernel<D, COUNTS>), spans, block, 0, stream, tab, sh, (const uint16_t*)Q,
                      (const uint16_t*)K, (const uint16_t*)V, counts_in, c_row, o_hi, o_lo, a_tok, c_edge);

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(kThreads) void pq_out_f32_kernel(const UnitTable ta
   __shared__ float2 sm_p[kQB][kTile];            // (alpha / R, the same divided by the row's cardinality)
 
   const int ui = find_unit(tab, blockIdx.x);
-  const Unit un = tab.u[ui];
+  const Unit un = tab.unit(ui);
   const int chunk = blockIdx.x - un.chunk_base;
   const int t0 = chunk * un.chunk_len;
   const int t1 = min(un.len, t0 + un.chunk_len);
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(D) void pq_reduce_f32_kernel(const UnitTable tab, c
                                                           const float* __restrict__ o_part,
                                                           const float* __restrict__ p_part, float* __restrict__ o) {
   const int R = sh.R;
-  const Unit un = tab.u[blockIdx.x / R];
+  const Unit un = tab.unit(blockIdx.x / R);
   const int q = blockIdx.x % R;
   const int d = threadIdx.x;
   float s = 0.f, w = 0.f;
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void pq_norms_f32_kernel(const UnitTable 
   __shared__ float sm_lc[kTile + 1], sm_ic[kTile + 1];
 
   const int ui = find_unit(tab, blockIdx.x);
-  const Unit un = tab.u[ui];
+  const Unit un = tab.unit(ui);
   const int chunk = blockIdx.x - un.chunk_base;
   const int t0 = chunk * un.chunk_len;
   const int t1 = min(un.len, t0 + un.chunk_len);

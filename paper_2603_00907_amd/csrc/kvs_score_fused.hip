@@ -113,8 +113,8 @@ __device__ __forceinline__ float lse2(float a, float b) {
 // Before the one-pass kernel: counters to zero, the launch's normalisers to "not yet" (one block per unit).
 __global__ void score_fused_init_kernel(const UnitTable tab, const int R, float* c_row, unsigned int* fsync,
                                         unsigned int* sel_shared) {
-  const Unit un = tab.u[blockIdx.x];
-  if (sel_shared != nullptr) {                    // the exchange area of the selection that follows starts from zero
+  const Unit un = tab.unit(blockIdx.x);
+  if (sel_shared != nullptr && blockIdx.x < kInlineUnits) {   // the exchange area of the selection that follows starts from zero
     uint4* z = reinterpret_cast<uint4*>(sel_shared + (size_t)blockIdx.x * kSelSharedInts);
     for (int i = threadIdx.x; i < kSelSharedInts / 4; i += blockDim.x) z[i] = make_uint4(0u, 0u, 0u, 0u);
   }
@@ -225,7 +225,7 @@ __global__ __launch_bounds__(kThreads, 1) void score_fused_kernel(
     if (tid == 0) { pf_t = wall_clock64(); ++pf_items; }
 #endif
     const int ui = find_unit_by<&Unit::f_base>(tab, (int)item);
-    const Unit un = tab.u[ui];
+    const Unit un = tab.unit(ui);
     const int chunk = (int)item - un.f_base;
     const int n_chunks = fused_chunks(un.len, D);
     const int t0 = chunk * CH;
@@ -654,7 +654,7 @@ hipError_t launch_fused_d(const UnitTable& tab, const Shape& sh, const void* Q, 
 bool score_fused_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
   if (dt != KVS_BF16 || sh.R <= 64 || sh.R > kQRows) return false;
   for (int i = 0; i < tab.n_units; ++i) {
-    if (tab.u[i].len < kTile) return false;   // the tile loads assume 32 whole rows per unit
+    if (tab.unit(i).len < kTile) return false;   // the tile loads assume 32 whole rows per unit
   }
   return true;
 }

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_kernel(
   __shared__ float sm_alpha[kWaves][kTile];
 
   const int ui = find_unit(tab, blockIdx.x);
-  const Unit un = tab.u[ui];
+  const Unit un = tab.unit(ui);
   const int chunk = blockIdx.x - un.chunk_base;
   const int t0 = chunk * un.chunk_len;
   const int t1 = min(un.len, t0 + un.chunk_len);
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(QB == 2 ? 256 : 512, QB == 2 ? 2 : 1) void score_mf
   __shared__ __attribute__((aligned(16))) int sm_lim[QROWS];      // ... and the last row each attends to
 
   const int ui = find_unit(tab, blockIdx.x);
-  const Unit un = tab.u[ui];
+  const Unit un = tab.unit(ui);
   const int chunk = blockIdx.x - un.chunk_base;
   const int t0 = chunk * un.chunk_len;
   const int t1 = min(un.len, t0 + un.chunk_len);
@@ -862,7 +862,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_mfma_f32_kernel(
   __shared__ __attribute__((aligned(16))) int sm_lim[QROWS];
 
   const int ui = find_unit(tab, blockIdx.x);
-  const Unit un = tab.u[ui];
+  const Unit un = tab.unit(ui);
   const int chunk = blockIdx.x - un.chunk_base;
   const int t0 = chunk * un.chunk_len;
   const int t1 = min(un.len, t0 + un.chunk_len);
@@ -1078,7 +1078,7 @@ bool score_mfma_supported(const UnitTable& tab, const Shape& sh, kvs_dtype dt) {
   (void)dt;
   if (sh.R < 4) return false;
   for (int i = 0; i < tab.n_units; ++i) {
-    if (tab.u[i].len < kTile) return false;   // the tile loads assume 32 whole rows per unit
+    if (tab.unit(i).len < kTile) return false;   // the tile loads assume 32 whole rows per unit
   }
   return true;
 }

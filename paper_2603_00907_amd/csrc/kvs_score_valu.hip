@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kThreads) void score_valu_kernel(
   __shared__ float sm_c[KVS_MAX_Q_ROWS];
 
   const int ui = find_unit(tab, blockIdx.x);
-  const Unit un = tab.u[ui];
+  const Unit un = tab.unit(ui);
   const int chunk = blockIdx.x - un.chunk_base;
   const int t0 = chunk * un.chunk_len;
   const int t1 = min(un.len, t0 + un.chunk_len);
@@ -147,12 +147,14 @@ __global__ __launch_bounds__(kThreads) void score_finalize_kernel(const UnitTabl
                                                                   float* __restrict__ c_row,
                                                                   unsigned int* __restrict__ sel_shared) {
   constexpr int HALF = kMaxChunks / 2;
-  if (sel_shared != nullptr) {                    // the exchange area of the selection that follows starts from zero
+  // the exchange area of the selection that follows starts from zero (it has kInlineUnits entries: larger groups
+  // do not use it)
+  if (sel_shared != nullptr && blockIdx.x < kInlineUnits) {
     uint4* z = reinterpret_cast<uint4*>(sel_shared + (size_t)blockIdx.x * kSelSharedInts);
     for (int i = threadIdx.x; i < kSelSharedInts / 4; i += kThreads) z[i] = make_uint4(0u, 0u, 0u, 0u);
   }
   __shared__ float2 sm_pair[2][128];
-  const Unit un = tab.u[blockIdx.x];
+  const Unit un = tab.unit(blockIdx.x);
   const int R = sh.R;
   const size_t part_base = (size_t)un.index * kMaxChunks;
   const int tid = threadIdx.x;

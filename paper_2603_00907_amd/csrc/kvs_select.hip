@@ -1122,8 +1122,8 @@ __global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
   const int b = blockIdx.x;
   if (b < n_select) {
     const int ui = n_select == tab.n_units ? b : find_unit_by<&Unit::s_base>(tab, b);     // (one workgroup per unit: no search)
-    const Unit& un = tab.u[ui];
-    const int P = (ui + 1 < tab.n_units ? tab.u[ui + 1].s_base : tab.total_sparts) - un.s_base;
+    const Unit un = tab.unit(ui);
+    const int P = (ui + 1 < tab.n_units ? tab.unit(ui + 1).s_base : tab.total_sparts) - un.s_base;
     if (P <= 1) {
       select_unit(un, sh, alpha_bar, edge_mask, slot, sm);
     } else {
@@ -1138,18 +1138,18 @@ __global__ __launch_bounds__(kSelThreads) void select_obar_kernel(
       }
     }
   } else if (b < n_select + n_reduce) {
-    obar_reduce_unit(tab.u[b - n_select], sh, parts_in, o_bar_out);
+    obar_reduce_unit(tab.unit(b - n_select), sh, parts_in, o_bar_out);
   } else {
     const int c = b - n_select - n_reduce;
     const int ui = find_unit_by<&Unit::o_base>(tab, c);
-    if (sh.stream) obar_chunk<T, D, true>(tab.u[ui], c - tab.u[ui].o_base, V, counts_in, alpha_bar, o_part, sm_o);
-    else obar_chunk<T, D, false>(tab.u[ui], c - tab.u[ui].o_base, V, counts_in, alpha_bar, o_part, sm_o);
+    if (sh.stream) obar_chunk<T, D, true>(tab.unit(ui), c - tab.unit(ui).o_base, V, counts_in, alpha_bar, o_part, sm_o);
+    else obar_chunk<T, D, false>(tab.unit(ui), c - tab.unit(ui).o_base, V, counts_in, alpha_bar, o_part, sm_o);
   }
 }
 
 __global__ void obar_reduce_kernel(const UnitTable tab, const Shape sh, const float* __restrict__ parts,
                                    float* __restrict__ o_bar) {
-  obar_reduce_unit(tab.u[blockIdx.x], sh, parts, o_bar);
+  obar_reduce_unit(tab.unit(blockIdx.x), sh, parts, o_bar);
 }
 
 __global__ void select_clear_kernel(unsigned int* sel_shared) {
@@ -1173,8 +1173,8 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, bool with_select, con
   // does not; if its parts give up, its first part selects it from alpha_bar, pass by pass)
   bool small = true;
   for (int i = 0; with_select && i < tab.n_units; ++i) {
-    const Unit& un = tab.u[i];
-    const int parts = (i + 1 < tab.n_units ? tab.u[i + 1].s_base : tab.total_sparts) - un.s_base;
+    const Unit un = tab.unit(i);
+    const int parts = (i + 1 < tab.n_units ? tab.unit(i + 1).s_base : tab.total_sparts) - un.s_base;
     const int E = (un.len - 2 - sh.n_recent) - sh.n_sink + 1;
     if (parts == 1 && un.len > un.n_out && E + 6 > kLdsKeysSmall) small = false;
   }
@@ -1194,7 +1194,8 @@ hipError_t launch_t(const UnitTable& tab, const Shape& sh, bool with_select, con
 }  // namespace
 
 hipError_t launch_select_clear(const UnitTable& tab, unsigned int* sel_shared, hipStream_t stream) {
-  hipLaunchKernelGGL(select_clear_kernel, dim3(tab.n_units), dim3(256), 0, stream, sel_shared);
+  hipLaunchKernelGGL(select_clear_kernel, dim3(tab.n_units < kInlineUnits ? tab.n_units : kInlineUnits), dim3(256), 0, stream,
+                     sel_shared);
   return hipGetLastError();
 }
 

@@ -78,6 +78,9 @@ static void whole_calls(std::mt19937& rng, kvs_dtype dt, int group, int window, 
     EXPECT(kvs_select(&pr.p, alpha, mask, slot, ws, ws_bytes - 256, nullptr) == KVS_OK);    // too small: not used
     EXPECT(kvs_select(&pr.p, alpha, (uint8_t*)ws, slot, ws, ws_bytes, nullptr) == KVS_ERR_ALIAS);
     EXPECT(kvs_merge_compact(&pr.p, K, V, alpha, obar, mask, slot, Ko, Vo, cnt, nullptr, 0, nullptr) == KVS_OK);
+    EXPECT(kvs_merge_compact(&pr.p, K, V, alpha, obar, mask, slot, Ko, Vo, cnt, ws, ws_bytes, nullptr) == KVS_OK);   // optional
+    EXPECT(kvs_merge_compact(&pr.p, K, V, alpha, obar, mask, slot, Ko, Vo, cnt, ws, ws_bytes - 256, nullptr) == KVS_OK);
+    EXPECT(kvs_merge_compact(&pr.p, K, V, alpha, obar, (uint8_t*)ws, slot, Ko, Vo, cnt, ws, ws_bytes, nullptr) == KVS_ERR_ALIAS);
     EXPECT(kvs::stub_launches() >= before + 5 * ((nu + 63) / 64));
     EXPECT(kvs_step(&pr.p, Q, K, V, Ko, Vo, cnt, slot, mask, ws, ws_bytes - 1, nullptr) == KVS_ERR_WORKSPACE);
     EXPECT(kvs_step(&pr.p, Q, K, V, Ko, Ko, cnt, slot, mask, ws, ws_bytes, nullptr) == KVS_ERR_ALIAS);
@@ -90,6 +93,7 @@ static void whole_calls(std::mt19937& rng, kvs_dtype dt, int group, int window, 
       EXPECT(kvs_sensitivity(&pr.p, Q, K, V, alpha, a_tok, c_edge, pws, pq_bytes, nullptr) == KVS_OK);
       EXPECT(kvs_step_per_query(&pr.p, Q, K, V, Ko, Vo, cnt, nullptr, nullptr, pws, pq_bytes, nullptr) == KVS_OK);
       EXPECT(kvs_merge_compact_norms(&pr.p, K, V, a_tok, c_edge, mask, slot, Ko, Vo, cnt, nullptr, 0, nullptr) == KVS_OK);
+      EXPECT(kvs_merge_compact_norms(&pr.p, K, V, a_tok, c_edge, mask, slot, Ko, Vo, cnt, ws, ws_bytes, nullptr) == KVS_OK);
       EXPECT(kvs_sensitivity_counts(&pr.p, Q, K, V, cin, alpha, a_tok, c_edge, pws, pq_bytes, nullptr) == KVS_OK);
       EXPECT(kvs_step_per_query_counts(&pr.p, Q, K, V, cin, Ko, Vo, cnt, nullptr, nullptr, pws, pq_bytes, nullptr) == KVS_OK);
       EXPECT(kvs_merge_compact_norms_counts(&pr.p, K, V, cin, a_tok, c_edge, mask, slot, Ko, Vo, cnt, nullptr, 0, nullptr) == KVS_OK);
@@ -148,6 +152,11 @@ int main() {
   kvs_debug_set(KVS_DEBUG_SELECT_SPLIT, 1);     // never more than one
   whole_calls(rng, KVS_F32, 1, 8, 64);
   kvs_debug_set(KVS_DEBUG_SELECT_SPLIT, 0);
+  for (int cap : {7, 64, 100}) {                // launch groups held to a few units, to the inline descriptors, beyond them
+    kvs_debug_set(KVS_DEBUG_GROUP_UNITS, cap);
+    whole_calls(rng, KVS_BF16, 4, 32, 128);
+  }
+  kvs_debug_set(KVS_DEBUG_GROUP_UNITS, 0);
   EXPECT(kvs_debug_set(99, 1) == -1);
   std::printf(g_failed ? "host layer: %d checks failed\n" : "host layer: all checks passed (%d stub launches)\n",
               g_failed ? g_failed : kvs::stub_launches());

@@ -336,7 +336,15 @@ def test_merge_compact_ablation_rules(base, dtype, D, lens, budgets, rule):
     check_merge_compact(base, dtype, D, lens, budgets, rule)
 
 
-def check_merge_compact(base, dtype, D, lens, budgets, rule):
+@pytest.mark.parametrize("with_ws", [False, True])
+def test_merge_compact_more_units_than_the_kernel_arguments_hold(with_ws):
+    """150 units of 40 to 330 rows in one kvs_merge_compact call.  Its workspace is optional: without one the units
+    go out 64 per launch, with one in a single launch whose unit descriptors live in the workspace."""
+    lens = [40 + (37 * i) % 291 for i in range(150)]
+    check_merge_compact("llama8b_8k", "bf16", 128, lens, [max(36, n // 3) for n in lens], "hessian", with_ws=with_ws)
+
+
+def check_merge_compact(base, dtype, D, lens, budgets, rule, with_ws=False):
     import torch
     w, units = merge_case(base, dtype, D, lens, budgets)
     batch = DeviceBatch(units, group=w.group, window=w.window, head_dim=D, dtype=dtype, n_sink=w.n_sink,
@@ -360,12 +368,13 @@ def check_merge_compact(base, dtype, D, lens, budgets, rule):
         obar_all[i] = o32
     dev_args = (torch.from_numpy(alpha_all).cuda(), torch.from_numpy(obar_all).cuda(),
                 torch.from_numpy(mask_all).cuda(), torch.from_numpy(slot_all).cuda())
+    ws = batch.ws if with_ws else None
     if batch.counts_in is None:
         batch.kvs.kvs_merge_compact(p, batch.K, batch.V, *dev_args, batch.K_out, batch.V_out, batch.counts,
-                                    stream=batch.stream())
+                                    ws=ws, stream=batch.stream())
     else:
         batch.kvs.kvs_merge_compact_counts(p, batch.K, batch.V, batch.counts_in, *dev_args, batch.K_out,
-                                           batch.V_out, batch.counts, stream=batch.stream())
+                                           batch.V_out, batch.counts, ws=ws, stream=batch.stream())
     torch_sync()
     batch.check_guards()
     compare_outputs(batch, refs, dtype)
@@ -1011,11 +1020,29 @@ def test_step_stress_full_size_all_heads_in_one_call():
     check_whole_batch_in_one_call(WORKLOADS["stress128k"], 0, [(0, 0)])
 
 
-def test_step_more_units_than_one_launch_takes():
-    """70 short units of the headline shape (bf16, 128 query rows) in ONE call: the library splits them into
-    launch groups of 64; every unit is checked like any other."""
+@pytest.mark.parametrize("group_units", [0, 64, 100, 7])
+def test_step_more_units_than_the_kernel_arguments_hold(group_units):
+    """150 short units of the headline shape (bf16, 128 query rows) in ONE call.  The library makes one launch group
+    of them, whose unit descriptors go through the workspace (the kernel arguments hold 64); with the groups limited
+    to 64 units there are three groups with descriptors in the arguments, with 100 one of each kind, with 7 many
+    small ones.  Every unit is checked like any other, and all four ways give the same bits."""
+    import torch
     w = WORKLOADS["llama8b_32k"].scaled(length=("fixed", 1500), budget=("fixed", 400))
-    accepted = [accepted_unit(w, layer, 0, layer % w.n_kv_heads, n=1500 - 13 * (layer % 7)) for layer in range(70)]
+    accepted = [accepted_unit(w, layer, 0, layer % w.n_kv_heads, n=1500 - 13 * (layer % 7)) for layer in range(150)]
+    with switches(group_units=group_units):
+        batch = check_step(w, accepted)
+    if group_units:
+        ref = check_step(w, accepted)
+        assert torch.equal(batch.K_out.view(torch.int16), ref.K_out.view(torch.int16))
+        assert torch.equal(batch.V_out.view(torch.int16), ref.V_out.view(torch.int16))
+        assert torch.equal(batch.counts, ref.counts) and torch.equal(batch.slot, ref.slot)
+
+
+def test_step_more_units_than_one_launch_group_takes():
+    """1100 units of 40 to 167 rows (fp32, six query rows): more than the 1024 units a launch group may have, so two
+    groups, both with their descriptors in the workspace, the second written over the first."""
+    w = WORKLOADS["tiny"].scaled(group=2, window=3, length=("fixed", 167), budget=("fixed", 60), n_sink=4)
+    accepted = [accepted_unit(w, i, 0, 0, n=40 + i % 128) for i in range(1100)]
     check_step(w, accepted)
 
 
