@@ -31,13 +31,13 @@ HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E bandwidth
 
 
 def launch_groups(lens):
-    """The units (cache lengths, in call order) that each launch of the library covers: a launch is closed at 2 M
-    tokens (64 units of 32768) or 1024 units.  Returns the groups' sizes."""
+    """The units (cache lengths, in call order) that each launch of the library covers: 64 units, and more as long
+    as they have fewer than 2 M tokens (64 units of 32768), up to 1024 units.  Returns the groups' sizes."""
     groups, count, tokens = [], 0, 0
     for n in lens:
         count += 1
         tokens += n
-        if tokens >= 64 * 32768 or count == 1024:
+        if (count >= 64 and tokens >= 64 * 32768) or count == 1024:
             groups.append(count)
             count = tokens = 0
     if count:

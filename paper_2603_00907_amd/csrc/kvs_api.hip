@@ -80,7 +80,9 @@ struct Plan {
 int group_end(const Plan& plan, int first, int cap) {
   long long tokens = 0;
   int i = first;
-  while (i < plan.n_units && i - first < cap && tokens < kGroupTokens) tokens += plan.units[i++].len;
+  while (i < plan.n_units && i - first < cap && (i - first < kInlineUnits || tokens < kGroupTokens)) {
+    tokens += plan.units[i++].len;
+  }
   return i;
 }
 

@@ -14,8 +14,9 @@ int debug_switch(kvs_debug_switch which);
 
 // Units of one launch ("group").  Up to kInlineUnits unit descriptors travel by value in the kernel arguments; a
 // larger group (many short units: the streaming regime's caches of 2.5 K rows) has its descriptors written to the
-// workspace first, by small kernels that carry them in THEIR arguments, kInlineUnits at a time.  A group is closed
-// at kGroupTokens tokens (64 units of 32 K tokens: longer launches gain nothing) or kMaxGroupUnits units.
+// workspace first, by small kernels that carry them in THEIR arguments, kInlineUnits at a time.  A group takes
+// kInlineUnits units whatever their lengths, and more as long as it has fewer than kGroupTokens tokens (64 units of
+// 32 K tokens: longer launches gain nothing), up to kMaxGroupUnits units.
 constexpr int kInlineUnits = 64;
 constexpr int kMaxGroupUnits = 1024;
 constexpr long long kGroupTokens = 64ll * 32768;

@@ -24,7 +24,7 @@ static void check_table(const UnitTable& tab) {
   }
   long long tokens = 0;
   for (int i = 0; i + 1 < tab.n_units; ++i) tokens += tab.unit(i).len;
-  if (tokens >= kGroupTokens) __builtin_trap();     // the group was full before its last unit
+  if (tab.n_units > kInlineUnits && tokens >= kGroupTokens) __builtin_trap();   // the group was full before its last unit
   int chunks = 0, mblocks = 0, ochunks = 0;
   for (int i = 0; i < tab.n_units; ++i) {
     const Unit u = tab.unit(i);
