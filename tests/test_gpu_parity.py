@@ -657,13 +657,15 @@ def test_step_tiny_config_is_deterministic():
     assert torch.equal(b1.counts, b2.counts)
 
 
-def test_step_replayed_from_a_hip_graph_equals_the_eager_step():
+@pytest.mark.parametrize("n_units,n", [(3, 3000), (100, 600)])
+def test_step_replayed_from_a_hip_graph_equals_the_eager_step(n_units, n):
     """The library never allocates, memsets or synchronises, so a step can be captured as it is.  The graph is
     replayed three times, with the outputs scrubbed and other work on the device in between; every replay must
-    reproduce the eager result bit for bit."""
+    reproduce the eager result bit for bit.  With 100 units the launch group's unit descriptors go through the
+    workspace (which is scrubbed between the replays): the kernels that write them there are part of the graph."""
     import torch
-    w = WORKLOADS["llama8b_8k"].scaled(length=("fixed", 3000), budget=("fixed", 800))
-    acc = [accepted_unit(w, 0, 0, h) for h in range(3)]
+    w = WORKLOADS["llama8b_8k"].scaled(length=("fixed", n), budget=("fixed", n // 4 + 50))
+    acc = [accepted_unit(w, h // 8, 0, h % 8) for h in range(n_units)]
     eager = check_step(w, acc)
     batch = DeviceBatch([a.inputs for a in acc], group=w.group, window=w.window, head_dim=w.head_dim, dtype=w.dtype,
                         n_sink=w.n_sink)
