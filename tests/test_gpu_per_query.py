@@ -338,6 +338,13 @@ def test_streaming_loop_of_per_query_steps():
     streaming_loop(check_step_per_query, per_query=True)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_step_per_query_more_units_than_the_kernel_arguments_hold(dtype):
+    """100 short units in one call: one launch group, its unit descriptors in the workspace."""
+    w = WORKLOADS["llama8b_8k"].scaled(dtype=dtype, group=2, window=8, length=("fixed", 500), budget=("fixed", 150))
+    check_step_per_query(w, [accepted_unit_per_query(w, h // 8, 0, h % 8, n=500 - 3 * (h % 11)) for h in range(100)])
+
+
 def test_step_per_query_with_causal_window():
     w = WORKLOADS["llama8b_8k"]
     check_step_per_query(w, [accepted_unit_per_query(w, 0, 0, h, causal=True) for h in range(2)], causal=True)
