@@ -19,7 +19,10 @@ int debug_switch(kvs_debug_switch which);
 // 32 K tokens: longer launches gain nothing), up to kMaxGroupUnits units.
 constexpr int kInlineUnits = 64;
 constexpr int kMaxGroupUnits = 1024;
-constexpr long long kGroupTokens = 64ll * 32768;
+#ifndef KVS_GROUP_TOKENS
+#define KVS_GROUP_TOKENS (64ll * 32768)
+#endif
+constexpr long long kGroupTokens = KVS_GROUP_TOKENS;
 constexpr int kMaxChunks = 64;           // token chunks (= score workgroups) per unit
 constexpr int kMinChunkLen = 256;        // tokens
 constexpr int kMaxChunkLen = 2048;       // tokens
