@@ -305,6 +305,15 @@ kvs_status check_ws(const Plan& plan, const void* ws, size_t ws_bytes, Workspace
   return KVS_OK;
 }
 
+// The decode workspace: the chunks' partial results, then (calls of more than kInlineUnits units) the descriptors of
+// a launch group.
+size_t decode_partial_bytes(const Plan& plan) {
+  return align_up((size_t)plan.n_units * kMaxChunks * plan.shape.R * (plan.shape.D + 2) * sizeof(float));
+}
+size_t decode_table_bytes(const Plan& plan) {
+  return plan.n_units > kInlineUnits ? align_up((size_t)std::min(plan.n_units, kMaxGroupUnits) * sizeof(Unit)) : 0;
+}
+
 // An entry point whose workspace is optional: with one that is usable, its groups may keep their descriptors there.
 // Returns the bytes of it that the call may write (0: none).
 size_t adopt_optional_ws(Plan& plan, void* ws, size_t ws_bytes) {
@@ -849,7 +858,7 @@ kvs_status kvs_decode_workspace_size(const kvs_problem* p, size_t* bytes) {
   const kvs_status st = make_plan(p, &plan);
   if (st != KVS_OK) return st;
   if (plan.shape.R > KVS_MAX_DECODE_ROWS) return KVS_ERR_INVALID_ARG;
-  *bytes = align_up((size_t)plan.n_units * kMaxChunks * plan.shape.R * (plan.shape.D + 2) * sizeof(float));
+  *bytes = decode_partial_bytes(plan) + decode_table_bytes(plan);
   return KVS_OK;
 }
 
@@ -859,7 +868,7 @@ kvs_status kvs_decode_attention(const kvs_problem* p, const void* Q, const void*
   kvs_status st = make_plan(p, &plan);
   if (st != KVS_OK) return st;
   if (plan.shape.R > KVS_MAX_DECODE_ROWS) return KVS_ERR_INVALID_ARG;
-  const size_t need = align_up((size_t)plan.n_units * kMaxChunks * plan.shape.R * (plan.shape.D + 2) * sizeof(float));
+  const size_t need = decode_partial_bytes(plan) + decode_table_bytes(plan);
   if (ws == nullptr || ((uintptr_t)ws % kAlign) != 0 || ws_bytes < need) return KVS_ERR_WORKSPACE;
   const size_t kv = (size_t)plan.rows_in * plan.shape.D * plan.elt;
   const size_t qo = (size_t)plan.n_units * plan.shape.R * plan.shape.D;
@@ -868,6 +877,8 @@ kvs_status kvs_decode_attention(const kvs_problem* p, const void* Q, const void*
   if (counts) rs.push_back({counts, (size_t)plan.rows_in * 4, false});
   if ((st = check_ranges(rs)) != KVS_OK) return st;
   hipStream_t s = (hipStream_t)hip_stream;
+  if (decode_table_bytes(plan)) plan.dev_table = (Unit*)((char*)ws + decode_partial_bytes(plan));
+  plan.stream = s;
   return for_each_group(plan, [&](const UnitTable& tab, const Shape& sh) {
     return launch_decode(tab, sh, plan.dtype, Q, K, V, counts, (float*)ws, out, s);
   });

@@ -1189,6 +1189,16 @@ def test_decode_attention_matches_oracle(base, dtype, D, G, W, lens, path):
     check_decode(units, dtype, D, G, W, path)
 
 
+@pytest.mark.parametrize("dtype,G,path", [("f32", 2, None), ("bf16", 8, "mfma"), ("bf16", 4, "valu")])
+def test_decode_attention_more_units_than_the_kernel_arguments_hold(dtype, G, path):
+    """130 caches of 33 to 400 rows in one call: one launch group whose unit descriptors live in the decode workspace."""
+    lens = [33 + (53 * i) % 368 for i in range(130)]
+    w = variant("stream2560", dtype=dtype, head_dim=128, group=G, window=1, n_seq=len(lens), n_kv_heads=1)
+    w = w.scaled(fresh_tail=8, n_sink=2)
+    units = [generate_unit(w, 0, s, 0, n=n) for s, n in enumerate(lens)]
+    check_decode(units, dtype, 128, G, 1, path)
+
+
 @pytest.mark.parametrize("dtype,G,path", [("f32", 2, None), ("bf16", 8, "mfma"), ("bf16", 2, "valu")])
 def test_decode_attention_at_the_maximum_length(dtype, G, path):
     """A cache of KVS_MAX_LEN = 2^22 rows with head dim 128 (fp32: the longest rows there are), with cardinalities."""
