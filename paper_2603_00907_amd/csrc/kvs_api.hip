@@ -324,7 +324,6 @@ size_t adopt_optional_ws(Plan& plan, void* ws, size_t ws_bytes) {
   return w.bytes;
 }
 
-// Calls f(table) for every launch group (see group_end).
 // Compute units of the current device (asked once per device).
 int compute_units() {
   static std::atomic<int> cached[64];
@@ -338,6 +337,7 @@ int compute_units() {
   return n;
 }
 
+// Calls f(table, shape) for every launch group (see group_end).
 // split_select: the caller hands the launchers an exchange area, so a unit's selection may take several workgroups.
 template <typename F>
 kvs_status for_each_group(const Plan& plan, F&& f, bool split_select = false) {
