@@ -128,6 +128,7 @@ struct Shape {
   int stream;       // 1: the launch's K and V exceed the last-level cache, rows are read non-temporally
   int rule;         // kvs_key_rule of the merged Key
   int causal;       // 0, or the window W when query row q only sees the rows up to its own position n - W + q % W
+  int dec_chunk;    // decode attention: rows per workgroup, at least (chosen per launch, see launch_decode)
   int o_from_score; // where the partial sums of o_bar are: 0: o_part, one per chunk of the o_bar pass; 1: o_part, one
                     // per SCORE chunk (written by sweep 1); 2: fo_part, one per work item of the one-pass score kernel
 };
