@@ -58,6 +58,15 @@ def test_static_entry_matches_the_step_on_two_calls_in_a_row():
     check_against_oracle(b3, acc1, 1e-2)
 
 
+def test_static_entry_with_more_units_than_the_kernel_arguments_hold():
+    """90 short fp32 units in one call: one launch group, whose unit descriptors go through the library's array as
+    they go through a caller's workspace."""
+    w = WORKLOADS["tiny"].scaled(group=2, window=3, length=("fixed", 300), budget=("fixed", 90), n_sink=4)
+    acc = [accepted_unit(w, i, 0, 0, n=120 + 2 * i) for i in range(90)]
+    b = run_both([a.inputs for a in acc], w)
+    check_against_oracle(b, acc, 1e-5)
+
+
 def test_static_entry_refuses_a_problem_beyond_its_array():
     import paper_2603_00907_amd as kvs
     w = WORKLOADS["tiny"]
